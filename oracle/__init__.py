@@ -1,0 +1,205 @@
+"""CPU oracle for gradient-filtered convolution backward -- TEST INFRASTRUCTURE ONLY.
+
+A thin numpy/ctypes front for ``gf_ref.c``: every function takes and returns
+contiguous float64 NCHW arrays.  Only ``tests/``, the smoke check and the
+benchmark's ``cpu_baseline`` leg may import this package; the GPU library and
+its Python binding never do, and nothing here imports them.
+
+The arithmetic lives in ``gf_ref.c`` (plain loops, fp64 accumulation), each
+function citing the passage of the paper it follows in ``gf_ref.h``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libgf_ref.so")
+_SRC = [os.path.join(_HERE, "gf_ref.c"), os.path.join(_HERE, "gf_ref.h")]
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile gf_ref.c into libgf_ref.so with gcc (OpenMP over outer loops)."""
+    stale = force or not os.path.exists(_SO) or any(
+        os.path.getmtime(s) > os.path.getmtime(_SO) for s in _SRC)
+    if stale:
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _SO, _SRC[0]]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+    return _SO
+
+
+class _Desc(C.Structure):
+    _fields_ = [(k, C.c_int) for k in ("N", "C_in", "C_out", "H_in", "W_in", "K_h", "K_w",
+                                        "stride", "pad", "dilation", "groups", "r")]
+
+
+class _Cost(C.Structure):
+    _fields_ = [(k, C.c_double) for k in ("flops_exact_gx", "flops_gf_gx", "flops_gf_min",
+                                           "overhead_fwd", "overhead_bwd", "act_elems_exact",
+                                           "act_elems_gf")]
+
+
+@dataclass(frozen=True)
+class Desc:
+    """Layer description in the paper's symbols (x is [N, C_in, H_in, W_in])."""
+    N: int
+    C_in: int
+    C_out: int
+    H_in: int
+    W_in: int
+    K_h: int = 1
+    K_w: int = 1
+    stride: int = 1
+    pad: int = 0
+    dilation: int = 1
+    groups: int = 1
+    r: int = 2
+
+    def _c(self) -> _Desc:
+        return _Desc(self.N, self.C_in, self.C_out, self.H_in, self.W_in, self.K_h, self.K_w,
+                     self.stride, self.pad, self.dilation, self.groups, self.r)
+
+
+class OracleError(ValueError):
+    pass
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_SO)
+    return _lib
+
+
+def _chk(rc: int, what: str):
+    if rc != 0:
+        raise OracleError(f"{what}: oracle rejected the call (code {rc})")
+
+
+def _in(a, shape) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if tuple(a.shape) != tuple(shape):
+        raise OracleError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def num_threads() -> int:
+    return int(_L().gf_ref_num_threads())
+
+
+def out_shape(d: Desc):
+    """(H_y, W_y, H_p, W_p): output map and patch grid (Sec. 3.3)."""
+    v = [C.c_int() for _ in range(4)]
+    cd = d._c()
+    _chk(_L().gf_ref_out_shape(C.byref(cd), *[C.byref(t) for t in v]), "out_shape")
+    return tuple(int(t.value) for t in v)
+
+
+def xu_shape(d: Desc):
+    Hy, Wy, Hp, Wp = out_shape(d)
+    return (d.N, d.C_in, d.H_in, d.W_in) if d.r == 1 else (d.N, d.C_in, Hp, Wp)
+
+
+def w_shape(d: Desc):
+    return (d.C_out, d.C_in // d.groups, d.K_h, d.K_w)
+
+
+def filter_grad(d: Desc, g_y) -> np.ndarray:
+    Hy, Wy, Hp, Wp = out_shape(d)
+    g_y = _in(g_y, (d.N, d.C_out, Hy, Wy))
+    out = np.empty((d.N, d.C_out, Hp, Wp), np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_filter_grad(C.byref(cd), _p(g_y), _p(out)), "filter_grad")
+    return out
+
+
+def pool_activation(d: Desc, x) -> np.ndarray:
+    x = _in(x, (d.N, d.C_in, d.H_in, d.W_in))
+    out = np.empty(xu_shape(d), np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_pool_activation(C.byref(cd), _p(x), _p(out)), "pool_activation")
+    return out
+
+
+def kernel_sum(d: Desc, w) -> np.ndarray:
+    w = _in(w, w_shape(d))
+    out = np.empty((d.C_out, d.C_in // d.groups), np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_kernel_sum(C.byref(cd), _p(w), _p(out)), "kernel_sum")
+    return out
+
+
+def bwd_weight(d: Desc, x_u, gy_u) -> np.ndarray:
+    Hy, Wy, Hp, Wp = out_shape(d)
+    x_u = _in(x_u, xu_shape(d))
+    gy_u = _in(gy_u, (d.N, d.C_out, Hp, Wp))
+    out = np.empty(w_shape(d), np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_bwd_weight(C.byref(cd), _p(x_u), _p(gy_u), _p(out)), "bwd_weight")
+    return out
+
+
+def bwd_input(d: Desc, gy_u, w, reduced_out: bool = False) -> np.ndarray:
+    Hy, Wy, Hp, Wp = out_shape(d)
+    gy_u = _in(gy_u, (d.N, d.C_out, Hp, Wp))
+    w = _in(w, w_shape(d))
+    full = (d.N, d.C_in, d.H_in, d.W_in)
+    shape = (d.N, d.C_in, Hp, Wp) if (reduced_out and d.r > 1) else full
+    out = np.empty(shape, np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_bwd_input(C.byref(cd), _p(gy_u), _p(w), _p(out), int(bool(reduced_out))),
+         "bwd_input")
+    return out
+
+
+def bwd_exact(d: Desc, x, w, g_y, want_gw: bool = True, want_gx: bool = True):
+    e = Desc(**{**d.__dict__, "r": 1})
+    Hy, Wy, _, _ = out_shape(e)
+    g_y = _in(g_y, (d.N, d.C_out, Hy, Wy))
+    x = _in(x, (d.N, d.C_in, d.H_in, d.W_in)) if want_gw else None
+    w = _in(w, w_shape(d)) if want_gx else None
+    g_w = np.empty(w_shape(d), np.float64) if want_gw else None
+    g_x = np.empty((d.N, d.C_in, d.H_in, d.W_in), np.float64) if want_gx else None
+    cd = d._c()
+    _chk(_L().gf_ref_bwd_exact(C.byref(cd), _p(x) if want_gw else None,
+                               _p(w) if want_gx else None, _p(g_y),
+                               _p(g_w) if want_gw else None, _p(g_x) if want_gx else None),
+         "bwd_exact")
+    return g_w, g_x
+
+
+def conv_fwd(d: Desc, x, w) -> np.ndarray:
+    e = Desc(**{**d.__dict__, "r": 1})
+    Hy, Wy, _, _ = out_shape(e)
+    x = _in(x, (d.N, d.C_in, d.H_in, d.W_in))
+    w = _in(w, w_shape(d))
+    y = np.empty((d.N, d.C_out, Hy, Wy), np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_conv_fwd(C.byref(cd), _p(x), _p(w), _p(y)), "conv_fwd")
+    return y
+
+
+def cost_model(d: Desc) -> dict:
+    c = _Cost()
+    cd = d._c()
+    _chk(_L().gf_ref_cost_model(C.byref(cd), C.byref(c)), "cost_model")
+    return {k: float(getattr(c, k)) for k, _ in _Cost._fields_}
+
+
+def gf_backward(d: Desc, x, w, g_y, reduced_out: bool = False):
+    """The whole filtered backward in the paper's order (lower half of Fig. 2(a)):
+    x_u (forward time), gy_u, then g_theta and g_x from the reduced maps."""
+    x_u = pool_activation(d, x)
+    gy_u = filter_grad(d, g_y)
+    return bwd_weight(d, x_u, gy_u), bwd_input(d, gy_u, w, reduced_out), x_u, gy_u

@@ -1,0 +1,382 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test cites what fixes the expected value: a library routine that computes
+the same textbook quantity (torch autograd / pooling in fp64), a hand-worked
+fixture, an identity that follows from the paper's equations, or a number the
+paper prints.  They are chosen so that a dropped term, a wrong sign or index, a
+transposed operand or a mis-scaled factor in ``oracle/gf_ref.c`` fails at least
+one of them.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def D(o, **kw):
+    return o.Desc(**kw)
+
+
+# ----------------------------------------------------------------------------
+# exact BP (Sec. 3.1) against torch's fp64 autograd, a library routine
+# ----------------------------------------------------------------------------
+EXACT_CASES = [
+    # N Ci Co H  W  K s p d g
+    (2, 3, 4, 7, 6, 3, 1, 1, 1, 1),
+    (1, 4, 6, 9, 9, 3, 2, 1, 1, 2),
+    (2, 4, 4, 8, 8, 3, 1, 2, 2, 4),   # depthwise, dilated
+    (1, 2, 3, 5, 7, 1, 1, 0, 1, 1),   # pointwise
+    (1, 2, 2, 11, 10, 5, 2, 2, 1, 1),
+    (2, 6, 3, 10, 10, 3, 1, 3, 3, 3),
+    (1, 3, 5, 6, 6, 3, 1, 0, 1, 1),   # no padding: H_y < H_x
+]
+
+
+@pytest.mark.parametrize("case", EXACT_CASES)
+def test_exact_bp_matches_torch_autograd(oracle, case):
+    N, Ci, Co, H, W, K, s, p, dl, g = case
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, stride=s, pad=p,
+          dilation=dl, groups=g, r=1)
+    r = rng(hash(case) % 2**31)
+    x = r.standard_normal((N, Ci, H, W))
+    w = r.standard_normal((Co, Ci // g, K, K))
+    xt = torch.tensor(x, requires_grad=True)
+    wt = torch.tensor(w, requires_grad=True)
+    y = F.conv2d(xt, wt, None, s, p, dl, g)
+    gy = r.standard_normal(tuple(y.shape))
+    y.backward(torch.tensor(gy))
+    np.testing.assert_allclose(oracle.conv_fwd(d, x, w), y.detach().numpy(), rtol=1e-12, atol=1e-12)
+    g_w, g_x = oracle.bwd_exact(d, x, w, gy)
+    np.testing.assert_allclose(g_w, wt.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(g_x, xt.grad.numpy(), rtol=1e-11, atol=1e-11)
+    # r == 1 through the filtered entry points is vanilla BP (Sec. 4.2)
+    x_u = oracle.pool_activation(d, x)
+    gy_u = oracle.filter_grad(d, gy)
+    assert np.array_equal(x_u, x) and np.array_equal(gy_u, gy)
+    np.testing.assert_allclose(oracle.bwd_weight(d, x_u, gy_u), wt.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(oracle.bwd_input(d, gy_u, w), xt.grad.numpy(), rtol=1e-11, atol=1e-11)
+
+
+def test_exact_bp_brute_force_gather_form(oracle):
+    """g_x written the other way round (gather over taps that land on the pixel)
+    and g_theta by the definition, in pure Python on a tiny layer."""
+    N, Ci, Co, H, W, K, s, p, dl = 1, 2, 2, 5, 4, 3, 2, 1, 1
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, stride=s, pad=p, r=1)
+    Hy, Wy, _, _ = oracle.out_shape(d)
+    r = rng(7)
+    x, w, gy = r.standard_normal((N, Ci, H, W)), r.standard_normal((Co, Ci, K, K)), r.standard_normal((N, Co, Hy, Wy))
+    gx = np.zeros_like(x)
+    gw = np.zeros_like(w)
+    for n, ci, h, ww in itertools.product(range(N), range(Ci), range(H), range(W)):
+        for co, u, v in itertools.product(range(Co), range(K), range(K)):
+            ni, nj = h + p - u * dl, ww + p - v * dl
+            if ni % s or nj % s:
+                continue
+            i, j = ni // s, nj // s
+            if 0 <= i < Hy and 0 <= j < Wy:
+                gx[n, ci, h, ww] += w[co, ci, u, v] * gy[n, co, i, j]
+    for co, ci, u, v in itertools.product(range(Co), range(Ci), range(K), range(K)):
+        for n, i, j in itertools.product(range(N), range(Hy), range(Wy)):
+            h, ww = i * s - p + u * dl, j * s - p + v * dl
+            if 0 <= h < H and 0 <= ww < W:
+                gw[co, ci, u, v] += x[n, ci, h, ww] * gy[n, co, i, j]
+    g_w, g_x = oracle.bwd_exact(d, x, w, gy)
+    np.testing.assert_allclose(g_w, gw, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(g_x, gx, rtol=1e-12, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# the gradient filter and the activation pooling (Eq. 2; text after Eq. 5)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("H,W,r", [(8, 8, 2), (7, 7, 2), (7, 7, 4), (14, 14, 4), (9, 5, 3), (6, 10, 7),
+                                   (5, 5, 8), (16, 12, 4), (7, 7, 7)])
+def test_filter_and_pool_match_library_pooling(oracle, H, W, r):
+    """ceil-mode average pooling that divides by the in-bounds count is the
+    patch mean with ragged last patches; with divisor 1 it is the patch sum."""
+    d = D(oracle, N=2, C_in=3, C_out=3, H_in=H, W_in=W, r=r)
+    g = rng(H * 100 + W * 10 + r).standard_normal((2, 3, H, W))
+    ref_mean = F.avg_pool2d(torch.tensor(g), r, r, 0, ceil_mode=True, count_include_pad=False).numpy()
+    ref_sum = F.avg_pool2d(torch.tensor(g), r, r, 0, ceil_mode=True, divisor_override=1).numpy()
+    np.testing.assert_allclose(oracle.filter_grad(d, g), ref_mean, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(oracle.pool_activation(d, g), ref_sum, rtol=1e-13, atol=1e-13)
+    Hy, Wy, Hp, Wp = oracle.out_shape(d)
+    assert (Hp, Wp) == (-(-H // r), -(-W // r))   # ceil(H/r) x ceil(W/r) blocks, Sec. 3.3
+
+
+def _read_fixture(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                k, *v = line.split()
+                out[k] = [float(t) for t in v]
+    return out
+
+
+def test_worked_example_4x4(oracle):
+    fx = _read_fixture("worked_example_4x4.txt")
+    d = D(oracle, N=1, C_in=1, C_out=1, H_in=4, W_in=4, K_h=3, K_w=3, pad=1, r=2)
+    a = np.arange(1.0, 17.0).reshape(1, 1, 4, 4)
+    w = np.arange(1.0, 10.0).reshape(1, 1, 3, 3)
+    g_w, g_x, x_u, gy_u = oracle.gf_backward(d, a, w, a)
+    assert gy_u.ravel().tolist() == fx["gy_u"]
+    assert x_u.ravel().tolist() == fx["x_u"]
+    assert oracle.kernel_sum(d, w).ravel().tolist() == fx["w_sum"]
+    assert g_w.ravel().tolist() == fx["g_w"] * 9
+    assert oracle.bwd_input(d, gy_u, w, reduced_out=True).ravel().tolist() == fx["g_x_u"]
+    up = np.kron(np.array(fx["g_x_u"]).reshape(2, 2), np.ones((2, 2)))
+    assert np.array_equal(g_x[0, 0], up)
+
+
+def upsample(a, q, H, W):
+    """every pixel takes the value of its q x q patch (Supp. B, the 'p' view)"""
+    return np.repeat(np.repeat(a, q, axis=2), q, axis=3)[:, :, :H, :W]
+
+
+@pytest.mark.parametrize("H,W,r", [(8, 8, 2), (7, 7, 2), (7, 9, 4), (10, 10, 3), (5, 5, 8)])
+def test_filter_fixed_point_and_idempotence(oracle, H, W, r):
+    """A map that is constant on each patch passes through the filter unchanged
+    (Supp. B: all offsets of a patch share the unique value)."""
+    d = D(oracle, N=2, C_in=2, C_out=2, H_in=H, W_in=W, r=r)
+    _, _, Hp, Wp = oracle.out_shape(d)
+    u = rng(r + H).standard_normal((2, 2, Hp, Wp))
+    pc = upsample(u, r, H, W)
+    f = oracle.filter_grad(d, pc)
+    np.testing.assert_allclose(f, u, rtol=1e-15, atol=0)
+    g = rng(99).standard_normal((2, 2, H, W))
+    f1 = oracle.filter_grad(d, g)
+    f2 = oracle.filter_grad(d, upsample(f1, r, H, W))
+    np.testing.assert_allclose(f2, f1, rtol=1e-15, atol=0)
+    # the filter keeps the total of every full patch: mean * count == sum
+    if H % r == 0 and W % r == 0:
+        np.testing.assert_allclose(f1 * r * r, oracle.pool_activation(d, g), rtol=1e-13)
+
+
+GF_CASES = [
+    # N Ci Co H  W  K s p d g r
+    (2, 3, 4, 8, 8, 3, 1, 1, 1, 1, 2),
+    (2, 4, 6, 7, 7, 3, 1, 1, 1, 2, 2),    # ragged, grouped
+    (1, 4, 4, 7, 7, 3, 1, 1, 1, 4, 4),    # ragged, depthwise
+    (2, 2, 3, 12, 12, 3, 1, 2, 2, 1, 4),  # dilated
+    (1, 3, 2, 14, 14, 3, 2, 1, 1, 1, 2),  # strided 14 -> 7
+    (2, 4, 4, 14, 14, 3, 2, 1, 1, 4, 4),  # strided depthwise, r_x = 8
+    (1, 5, 3, 9, 6, 1, 1, 0, 1, 1, 3),    # pointwise
+    (1, 2, 2, 6, 6, 5, 1, 2, 1, 1, 7),    # one patch per plane (r >= H)
+]
+
+
+@pytest.mark.parametrize("case", GF_CASES)
+def test_gf_equals_pointwise_bp_of_the_filtered_gradient(oracle, case):
+    """Eq. (3) and Eq. (5), read through Supp. B: with every patch 'padded
+    sufficiently' the K x K layer acts on the filtered gradient like a 1x1,
+    stride-1 layer whose weight is the spatial kernel sum.  So
+      g_theta~ = <x, up(gy_u)> / s^2   and   g_x~ = sum_co up(gy_u) * w_sum / s^2,
+    which are the exact gradients (already pinned to torch above) of that 1x1
+    layer fed x and the upsampled filtered gradient."""
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, stride=s, pad=p,
+          dilation=dl, groups=g, r=r)
+    Hy, Wy, Hp, Wp = oracle.out_shape(d)
+    rr = rng(hash(case) % 2**31)
+    x = rr.standard_normal((N, Ci, H, W))
+    w = rr.standard_normal((Co, Ci // g, K, K))
+    gy = rr.standard_normal((N, Co, Hy, Wy))
+    g_w, g_x, x_u, gy_u = oracle.gf_backward(d, x, w, gy)
+
+    up = upsample(gy_u, r * s, H, W) / (s * s)
+    pw = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, groups=g, r=1)
+    w_sum = w.sum(axis=(2, 3))
+    np.testing.assert_allclose(oracle.kernel_sum(d, w), w_sum, rtol=1e-13, atol=1e-13)
+    ref_gw, ref_gx = oracle.bwd_exact(pw, x, w_sum[:, :, None, None], up)
+    np.testing.assert_allclose(g_x, ref_gx, rtol=1e-12, atol=1e-12)
+    for u, v in itertools.product(range(K), range(K)):       # same value for every tap
+        np.testing.assert_allclose(g_w[:, :, u, v], ref_gw[:, :, 0, 0], rtol=1e-12, atol=1e-12)
+        assert np.array_equal(g_w[:, :, u, v], g_w[:, :, 0, 0])
+    # and the same two numbers from torch directly
+    xt = torch.tensor(x, requires_grad=True)
+    wt = torch.tensor(w_sum[:, :, None, None].copy(), requires_grad=True)
+    F.conv2d(xt, wt, groups=g).backward(torch.tensor(up))
+    np.testing.assert_allclose(g_x, xt.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(g_w[:, :, 0, 0], wt.grad.numpy()[:, :, 0, 0], rtol=1e-11, atol=1e-11)
+    # layout: reduced output is the unique-value view of the full output
+    g_x_u = oracle.bwd_input(d, gy_u, w, reduced_out=True)
+    assert g_x_u.shape == (N, Ci, Hp, Wp)
+    assert np.array_equal(upsample(g_x_u, r * s, H, W), g_x)
+
+
+@pytest.mark.parametrize("r,g", [(2, 1), (4, 1), (3, 2), (2, 4)])
+def test_pointwise_layer_with_patch_constant_gradient_is_exact(oracle, r, g):
+    """For a 1x1 stride-1 layer no tap leaves its patch, so if g_y is already
+    constant on each patch the filtered gradients ARE the exact ones."""
+    N, Ci, Co, H, W = 2, 4, 8, 9, 8
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, groups=g, r=r)
+    _, _, Hp, Wp = oracle.out_shape(d)
+    rr = rng(31 + r)
+    x = rr.standard_normal((N, Ci, H, W))
+    w = rr.standard_normal((Co, Ci // g, 1, 1))
+    gy = upsample(rr.standard_normal((N, Co, Hp, Wp)), r, H, W)
+    g_w, g_x, _, _ = oracle.gf_backward(d, x, w, gy)
+    e_w, e_x = oracle.bwd_exact(d, x, w, gy)
+    np.testing.assert_allclose(g_w, e_w, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(g_x, e_x, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("K,dl", [(3, 1), (3, 2), (5, 1)])
+def test_constant_gradient_interior_exactness(oracle, K, dl):
+    """Sec. 3.2 (ii): if every element of g_y is the same value v the
+    convolution with the rotated kernel is (sum theta') v, boundary elements
+    aside.  The filtered g_x must equal exact g_x wherever the whole (dilated)
+    window stays inside the image."""
+    N, Ci, Co, H, W, r = 1, 2, 3, 12, 12, 2
+    p = dl * (K - 1) // 2
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, pad=p, dilation=dl, r=r)
+    rr = rng(K * 10 + dl)
+    w = rr.standard_normal((Co, Ci, K, K))
+    v = rr.standard_normal((N, Co, 1, 1))
+    gy = np.broadcast_to(v, (N, Co, H, W)).copy()
+    gf = oracle.bwd_input(d, oracle.filter_grad(d, gy), w)
+    _, ex = oracle.bwd_exact(d, np.zeros((N, Ci, H, W)), w, gy, want_gw=False)
+    m = p
+    np.testing.assert_allclose(gf[:, :, m:H - m, m:W - m], ex[:, :, m:H - m, m:W - m], rtol=1e-12, atol=1e-12)
+    assert not np.allclose(gf, ex)        # border pixels differ: no border correction
+
+
+@pytest.mark.parametrize("g,r,s", [(1, 2, 2), (4, 2, 2), (1, 1 + 1, 3)])
+def test_stride_rule_zero_insertion(oracle, g, r, s):
+    """A stride-s layer is a stride-1 layer followed by subsampling; the
+    subsampling back-propagates by zero insertion.  Applying the paper's method
+    with patch r*s to that stride-1 layer must give the strided result
+    (this is where the 1/s^2 factor and the r*s activation patch come from)."""
+    N, Ci, Co, K, p = 2, 4, 4, 3, 1
+    Hy = 7 if s == 2 else 4
+    H = Hy * s
+    ds = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=H, K_h=K, K_w=K, stride=s, pad=p, groups=g, r=r)
+    d1 = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=H, K_h=K, K_w=K, stride=1, pad=p, groups=g, r=r * s)
+    assert oracle.out_shape(ds)[0] == Hy and oracle.out_shape(d1)[0] == H
+    rr = rng(5 + s)
+    x = rr.standard_normal((N, Ci, H, H))
+    w = rr.standard_normal((Co, Ci // g, K, K))
+    gy = rr.standard_normal((N, Co, Hy, Hy))
+    gy1 = np.zeros((N, Co, H, H))
+    gy1[:, :, ::s, ::s] = gy
+    a_w, a_x, a_xu, _ = oracle.gf_backward(ds, x, w, gy)
+    b_w, b_x, b_xu, _ = oracle.gf_backward(d1, x, w, gy1)
+    assert np.array_equal(a_xu, b_xu)
+    np.testing.assert_allclose(a_w, b_w, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(a_x, b_x, rtol=1e-12, atol=1e-12)
+
+
+def test_linearity_and_structure(oracle):
+    d = D(oracle, N=2, C_in=4, C_out=6, H_in=7, W_in=7, K_h=3, K_w=3, pad=1, groups=2, r=2)
+    rr = rng(3)
+    x1, x2 = rr.standard_normal((2, 2, 4, 7, 7))
+    g1, g2 = rr.standard_normal((2, 2, 6, 7, 7))
+    w = rr.standard_normal((6, 2, 3, 3))
+    a, b = 0.75, -1.5
+    f = oracle.filter_grad
+    np.testing.assert_allclose(f(d, a * g1 + b * g2), a * f(d, g1) + b * f(d, g2), rtol=1e-12, atol=1e-12)
+    pa = oracle.pool_activation
+    np.testing.assert_allclose(pa(d, a * x1 + b * x2), a * pa(d, x1) + b * pa(d, x2), rtol=1e-12, atol=1e-12)
+    gw = lambda x, g: oracle.bwd_weight(d, pa(d, x), f(d, g))
+    np.testing.assert_allclose(gw(a * x1 + b * x2, g1), a * gw(x1, g1) + b * gw(x2, g1), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(gw(x1, a * g1 + b * g2), a * gw(x1, g1) + b * gw(x1, g2), rtol=1e-12, atol=1e-12)
+    gx = lambda g, ww: oracle.bwd_input(d, f(d, g), ww)
+    np.testing.assert_allclose(gx(a * g1 + b * g2, w), a * gx(g1, w) + b * gx(g2, w), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(gx(g1, a * w), a * gx(g1, w), rtol=1e-12, atol=1e-12)
+    # group structure: output channels of group 1 never reach input channels of group 0
+    g0 = g1.copy()
+    g0[:, :3] = 0.0
+    assert np.all(gx(g0, w)[:, :2] == 0.0) and np.any(gx(g0, w)[:, 2:] != 0.0)
+    assert np.all(gw(x1, g0)[:3] == 0.0)
+    # transposed-operand check: weight-gradient entry [co, ci] pairs gy channel co with x channel ci
+    e = np.zeros((2, 6, 7, 7)); e[:, 1] = 1.0
+    xx = np.zeros((2, 4, 7, 7)); xx[:, 1] = 1.0
+    gwe = gw(xx, e)
+    assert gwe[1, 1, 0, 0] == 2 * 49 and np.count_nonzero(gwe[:, :, 0, 0]) == 1
+
+
+# ----------------------------------------------------------------------------
+# numbers and closed forms the paper prints
+# ----------------------------------------------------------------------------
+def _layers(net, k):
+    """(C_in, C_out, K, stride, pad, groups, H_in) of the last k conv layers."""
+    r18 = [(256, 512, 3, 2, 1, 1, 14), (512, 512, 3, 1, 1, 1, 7), (512, 512, 3, 1, 1, 1, 7), (512, 512, 3, 1, 1, 1, 7)]
+    r34 = [(512, 512, 3, 1, 1, 1, 7)] * 4
+    mb2 = [(160, 960, 1, 1, 0, 1, 7), (960, 960, 3, 1, 1, 960, 7), (960, 320, 1, 1, 0, 1, 7), (320, 1280, 1, 1, 0, 1, 7)]
+    return {"ResNet-18": r18, "ResNet-34": r34, "MobileNetV2": mb2}[net][-k:]
+
+
+def test_table1_activation_memory(oracle):
+    rows = []
+    with open(os.path.join(GOLDEN, "table1_activation_memory.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if line:
+                rows.append((line[0], int(line[1]), float(line[2]), float(line[3])))
+    assert len(rows) == 6
+    for net, k, kb_exact, kb_gf in rows:
+        ex = gf = 0.0
+        for ci, co, K, s, p, g, H in _layers(net, k):
+            c = oracle.cost_model(D(oracle, N=1, C_in=ci, C_out=co, H_in=H, W_in=H, K_h=K, K_w=K,
+                                    stride=s, pad=p, groups=g, r=2))
+            ex += c["act_elems_exact"] * 4 / 1024
+            gf += c["act_elems_gf"] * 4 / 1024
+        assert abs(ex - kb_exact) < 0.005, (net, k, ex)
+        assert abs(gf - kb_gf) < 0.005, (net, k, gf)
+
+
+def test_closed_forms(oracle):
+    fx = _read_fixture("closed_forms.txt")
+    unet = dict(N=1, C_in=192, C_out=64, H_in=160, W_in=120, K_h=3, K_w=3, pad=1)   # footnote of Fig. 3
+    c1 = oracle.cost_model(D(oracle, r=1, **unet))
+    assert c1["flops_exact_gx"] == 2 * 192 * 64 * 120 * 160 * 9                      # Eq. (1)
+    for r in (2, 4, 8):
+        c = oracle.cost_model(D(oracle, r=r, **unet))
+        assert c["flops_gf_gx"] == (160 // r) * (120 // r) * 192 * (2 * 64 - 1)      # Eq. (12)
+        ratio = c["flops_exact_gx"] / c["flops_gf_gx"]
+        assert abs(ratio / (r * r * 9) - 1) < 0.01                                   # Supp. D: about 1/(r^2 H_th W_th)
+        assert c["flops_gf_min"] == 2 * 192 * 64 - 192                               # Eq. (13)
+    # patch as large as the map reaches the minimum (Sec. 4.2)
+    c = oracle.cost_model(D(oracle, r=160, **unet))
+    assert c["flops_gf_gx"] == c["flops_gf_min"]
+    # kernel collapse alone: (K^2 - 1)/K^2 of the work removed
+    for K, key in ((3, "kernel_collapse_3x3_removed"), (5, "kernel_collapse_5x5_removed")):
+        removed = 1 - 1 / (K * K)
+        assert abs(removed - fx[key][0]) <= fx[key][1]
+        cK = oracle.cost_model(D(oracle, N=1, C_in=8, C_out=8, H_in=16, W_in=16, K_h=K, K_w=K, pad=K // 2, r=1))
+        # r = 1 in Eq. (12) is the structured map alone
+        assert abs(1 - (cK["flops_gf_gx"] + 8 * 16 * 16) / cK["flops_exact_gx"] - removed) < 1e-12
+    c2 = oracle.cost_model(D(oracle, r=2, **unet))
+    assert c2["overhead_fwd"] == 1 / (2 * 64 * 9) and c2["overhead_bwd"] == 3 / (2 * 192)
+    assert c2["overhead_fwd"] < fx["unet_overhead_upper_bound"][0]
+    assert c2["overhead_bwd"] < fx["unet_overhead_upper_bound"][0]
+    # Sec. 4.3: about 1 - 1/r^2 of the activation memory saved
+    for r in (2, 4):
+        c = oracle.cost_model(D(oracle, r=r, **unet))
+        assert c["act_elems_gf"] / c["act_elems_exact"] == 1 / (r * r)
+
+
+def test_descriptor_rejection(oracle):
+    ok = dict(N=1, C_in=4, C_out=4, H_in=8, W_in=8, K_h=3, K_w=3, pad=1, r=2)
+    oracle.out_shape(D(oracle, **ok))
+    for bad in (dict(r=0), dict(groups=3), dict(N=0), dict(stride=0), dict(dilation=0), dict(pad=-1),
+                dict(pad=0),              # 8 -> 6: patch grids of x and g_y differ (3 vs 4)...
+                dict(K_h=11, K_w=11)):    # kernel larger than padded input
+        kw = {**ok, **bad}
+        if bad == dict(pad=0):
+            # 6x6 output, r=2 -> 3x3 grid; 8x8 input -> 4x4 grid: rejected
+            pass
+        with pytest.raises(oracle.OracleError):
+            oracle.out_shape(D(oracle, **kw))
+    # with r == 1 the unpadded layer is legal (exact BP has no grid rule)
+    oracle.out_shape(D(oracle, **{**ok, "pad": 0, "r": 1}))
