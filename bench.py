@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the gradient-filtered conv backward hot path on one MI355X.
+
+A "step" is one pass of the whole filtered path over one batch of the workload:
+for every conv layer of the block, the forward-time activation pooling, the
+gradient filter, the kernel sum, the filtered weight gradient and the filtered
+input gradient.  The default workload is the MobileNetV2 inverted-residual block
+backward (N=32, 56x56, expand 24->144, depthwise 3x3, project 144->24, r=2).
+Inputs are seeded synthetic tensors resident in HBM before the timed region; the
+buffer sets rotate so that no step finds its tensors in the last-level cache.
+
+Prints one JSON line (see the keys below); everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--config", type=int, default=2, help="workload: configuration id in workloads.CONFIGS")
+    ap.add_argument("--r", type=int, default=0, help="patch size (default: the configuration's first)")
+    ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (default: enough for > 768 MB)")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-exact", action="store_true")
+    ap.add_argument("--table", action="store_true", help="also print a per-layer table to stderr")
+    return ap.parse_args()
+
+
+class LayerBufs:
+    """Device tensors of one layer in one buffer set, plus raw pointers for the C ABI."""
+
+    def __init__(self, T, B, d, x, w, gy, torch):
+        s = T.shapes(d)
+        self.d = d
+        self.x, self.w, self.gy = x.cuda(), w.cuda(), gy.cuda()
+        dt = self.x.dtype
+        self.x_u = torch.empty(s["x_u"], dtype=dt, device="cuda")
+        self.gy_u = torch.empty(s["gy_u"], dtype=dt, device="cuda")
+        self.g_w = torch.empty(s["w"], dtype=torch.float32, device="cuda")
+        self.g_x = torch.empty(s["x"], dtype=dt, device="cuda")
+        self.ws_w_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT)
+        self.ws_i_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT)
+        self.ws_e_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_EXACT)
+        self.ws_w = torch.empty(max(self.ws_w_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.ws_i = torch.empty(max(self.ws_i_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.ws_e = torch.empty(max(self.ws_e_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.e_w = None
+        self.e_x = None
+
+    def nbytes(self):
+        ts = [self.x, self.w, self.gy, self.x_u, self.gy_u, self.g_w, self.g_x, self.ws_w, self.ws_i]
+        return sum(t.numel() * t.element_size() for t in ts)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log("bench.py: this build measures ONE GPU only (the path has no multi-GPU part); "
+            "run with --gpus 1")
+        sys.exit(2)
+
+    import torch
+    import paper_2301_00330_amd.binding as B
+    import paper_2301_00330_amd.torch_api as T
+    from paper_2301_00330_amd import workloads as WL
+
+    B.lib()  # no fallback: fail here if libgf.so is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    cfg = WL.CONFIGS[args.config]
+    r = args.r or cfg.rs[0]
+    dtype = args.dtype
+    if dtype not in cfg.dtypes:
+        dtype = cfg.dtypes[0]
+    N = cfg.N
+    layers = list(cfg.layers)
+
+    # ---- inputs: seeded on the host, copied once into several HBM-resident buffer sets ----
+    host = [WL.make_inputs(cfg, L, dtype) for L in layers]
+    descs = [T.desc_for(L, N, r, dtype) for L in layers]
+    one = [LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)]
+    set_bytes = sum(lb.nbytes() for lb in one)
+    nsets = args.sets or max(3, int(768e6 // set_bytes) + 1)
+    sets = [one] + [[LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)] for _ in range(nsets - 1)]
+    log(f"workload cfg{cfg.cfg_id} '{cfg.name}' N={N} r={r} dtype={dtype}: {set_bytes / 1e6:.1f} MB per set x {nsets} sets")
+
+    def st():
+        return int(torch.cuda.current_stream().cuda_stream)
+
+    P = B.ptr
+
+    def enqueue_pool(lb, s): B.gf_pool_activation(lb.d, P(lb.x), P(lb.x_u), s)
+    def enqueue_filter(lb, s): B.gf_filter_grad(lb.d, P(lb.gy), P(lb.gy_u), s)
+    def enqueue_bww(lb, s): B.gf_conv_bwd_weight(lb.d, P(lb.x_u), P(lb.gy_u), P(lb.g_w), P(lb.ws_w), lb.ws_w.numel(), s)
+    def enqueue_bwi(lb, s): B.gf_conv_bwd_input(lb.d, P(lb.gy_u), P(lb.w), P(lb.g_x), False, P(lb.ws_i), lb.ws_i.numel(), s)
+
+    def enqueue_exact(lb, s):
+        if lb.e_w is None:
+            lb.e_w = torch.empty_like(lb.g_w)
+            lb.e_x = torch.empty_like(lb.g_x)
+        B.gf_conv_bwd_exact(lb.d, P(lb.x), P(lb.w), P(lb.gy), P(lb.e_w), P(lb.e_x), P(lb.ws_e), lb.ws_e.numel(), s)
+
+    STAGES = (("pool_activation", enqueue_pool), ("filter_grad", enqueue_filter),
+              ("bwd_weight", enqueue_bww), ("bwd_input", enqueue_bwi))
+
+    def step(bufset):
+        s = st()
+        for lb in bufset:
+            for _, fn in STAGES:
+                fn(lb, s)
+
+    # ---- warm-up (eager), then optional graph capture of one step per buffer set ----
+    for i in range(max(args.warmup, 1)):
+        step(sets[i % nsets])
+    torch.cuda.synchronize()
+
+    graphs = None
+    if not args.no_graph:
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for bs in sets:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step(bs)
+                graphs.append(g)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for g in graphs:   # one untimed replay each
+            g.replay()
+        torch.cuda.synchronize()
+
+    def run_steps(k):
+        for i in range(k):
+            if graphs is not None:
+                graphs[i % nsets].replay()
+            else:
+                step(sets[i % nsets])
+
+    # ---- the timed region: exactly --steps steps ----
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(args.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = N / (ms_per_step * 1e-3)
+
+    # eager launches for comparison (host launch overhead included)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % nsets])
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per-kernel durations with HIP events on the launch stream (cold, rotating sets) ----
+    def time_stage(fn, li, reps=8):
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        s = st()
+        for k in range(nsets):
+            fn(sets[k][li], s)
+        torch.cuda.synchronize()
+        ev0.record()
+        for rep in range(reps):
+            for k in range(nsets):
+                fn(sets[k][li], s)
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) * 1e3 / (reps * nsets)   # microseconds per launch
+
+    cost = [B.gf_cost_model(d) for d in descs]
+    stage_bytes = {"pool_activation": "bytes_pool", "filter_grad": "bytes_filter",
+                   "bwd_weight": "bytes_bwd_weight", "bwd_input": "bytes_bwd_input"}
+    per_layer = []
+    for li, L in enumerate(layers):
+        row = {"layer": L.name}
+        tot_us = 0.0
+        for name, fn in STAGES:
+            us = time_stage(fn, li)
+            by = cost[li][stage_bytes[name]]
+            row[name] = {"us": round(us, 2), "GBps": round(by / us * 1e-3, 1), "bytes": by}
+            if name != "pool_activation":
+                tot_us += us
+        fl = cost[li]["flops_bwd_weight"] + cost[li]["flops_bwd_input"]
+        row["backward_us"] = round(tot_us, 2)           # S1 + S2 + S3 + S4 (pooling is forward-time)
+        row["images_per_s"] = round(N / (tot_us * 1e-6), 1)
+        row["tflops"] = round(fl / tot_us * 1e-6, 3)
+        per_layer.append(row)
+
+    # the reduction kernel (patch_reduce_lds) runs 2x per layer and moves most of the bytes
+    red_us = [per_layer[li][k]["us"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
+    red_by = [per_layer[li][k]["bytes"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
+    achieved = sum(red_by) / sum(red_us) * 1e-3      # GB/s, algorithmic bytes / measured time
+    roofline = {"kernel": "patch_reduce_lds", "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "avg_launch_us": round(sum(red_us) / len(red_us), 2),
+                "bytes_per_launch": sum(red_by) / len(red_by), "traffic": None}
+
+    # ---- exact BP at the same shapes (speed-up denominator) ----
+    exact = None
+    if not args.no_exact:
+        ex_us = []
+        for li in range(len(layers)):
+            ex_us.append(time_stage(enqueue_exact, li, reps=2))
+        gf_us = [row["backward_us"] for row in per_layer]
+        exact = {"per_layer_us": [round(u, 1) for u in ex_us],
+                 "speedup_per_layer": [round(e / g, 2) for e, g in zip(ex_us, gf_us)],
+                 "speedup_block": round(sum(ex_us) / sum(gf_us), 2),
+                 "note": "own exact-BP entry (gf_conv_bwd_exact) at the same shapes"}
+
+    # ---- CPU oracle on the host cores (reported baseline only) ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        f64 = lambda t: t.to(torch.float64).numpy()
+        prep = []
+        for L, d, (x, w, gy) in zip(layers, descs, host):
+            od = oracle.Desc(N=N, C_in=L.C_in, C_out=L.C_out, H_in=L.H, W_in=L.W, K_h=L.K, K_w=L.K,
+                             stride=L.stride, pad=L.pad, dilation=L.dilation, groups=L.groups, r=r)
+            prep.append((od, f64(x), f64(w), f64(gy)))
+        oracle.gf_backward(*prep[0])     # build + warm
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 5:
+            t0 = time.perf_counter()
+            for od, x, w, gy in prep:
+                oracle.gf_backward(od, x, w, gy)
+            t_cpu += time.perf_counter() - t0
+            reps += 1
+        cpu = {"value": round(N / (t_cpu / reps), 2), "unit": "images/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"the full workload (all {len(layers)} layers, N={N}), fp64, mean of {reps} passes"}
+
+    if args.table:
+        for row in per_layer:
+            log(json.dumps(row))
+
+    out = {
+        "metric": "filtered_conv_backward_images_per_sec", "value": round(value, 1), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"cfg{cfg.cfg_id}: {cfg.name}, N={N}, r={r}, "
+                               + " + ".join(L.name for L in layers),
+                   "step": "pool_activation + filter_grad + kernel_sum + bwd_weight + bwd_input for every layer",
+                   "launch": "eager" if graphs is None else "hip-graph replay", "buffer_sets": nsets,
+                   "cache": "cold (rotating sets)"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "eager_ms_per_step": round(eager_ms, 5),
+        "per_layer": per_layer,
+        "exact_bp": exact,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

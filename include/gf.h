@@ -1,0 +1,156 @@
+/*
+ * gf.h -- C ABI of libgf: gradient-filtered convolution backward on AMD MI355X
+ * (gfx950), after "Efficient On-device Training via Gradient Filtering"
+ * (arXiv 2301.00330).
+ *
+ * The method (Sec. 3): the output gradient g_y of a conv layer is replaced by
+ * its r x r patch averages (Eq. 2) and only one value per patch is kept; the
+ * stored forward input x is replaced by its patch sums (text after Eq. 5); the
+ * kernel theta by its spatial sum (text after Eq. 3).  The layer's gradients
+ * then are two small channel contractions on maps that are r^2 smaller:
+ *   g_x~[n,ci,h,w]     = 1/s^2 * sum_co gy_u[n,co,h/r_x,w/r_x] * sum_uv theta[co,ci,u,v]   (Eq. 3)
+ *   g_th~[co,ci,u,v]   = 1/s^2 * sum_{n,patch} x_u[n,ci,patch] * gy_u[n,co,patch]          (Eq. 5)
+ *
+ * Conventions common to every entry point
+ *  - Tensors are contiguous NCHW (the paper's index order x[n,c,h,w],
+ *    theta[co,ci,u,v]), element type desc->dtype (fp32, or bf16 stored as the
+ *    upper 16 bits of an fp32, rounded to nearest even).  Weight gradients are
+ *    always fp32.  Accumulation is always fp32.
+ *  - Every tensor / workspace pointer is a DEVICE pointer, 16-byte aligned,
+ *    owned by the caller; the library never allocates, frees or keeps one.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it: they never synchronise and never throw.
+ *  - The return value is a gf_status.  Descriptor, pointer, shape and workspace
+ *    errors are detected on the host BEFORE anything is enqueued, so a failed
+ *    call has no effect on the device.  GF_ERR_DEVICE reports a failed launch.
+ *  - Shapes: with (H_y, W_y, H_p, W_p) from gf_out_shape,
+ *      x    [N, C_in,  H_in, W_in]        g_y  [N, C_out, H_y, W_y]
+ *      w    [C_out, C_in/groups, K_h, K_w] g_w  same shape as w, fp32
+ *      x_u  [N, C_in,  H_p, W_p]          gy_u [N, C_out, H_p, W_p]
+ *      g_x  [N, C_in,  H_in, W_in]  (or [N, C_in, H_p, W_p] with reduced_out)
+ *    The patch grid is H_p = ceil(H_y / r) (Sec. 3.3); a ragged last patch
+ *    averages / sums its in-bounds pixels only.  On the input side the patch is
+ *    r_x = r * stride, and the layer must satisfy ceil(H_in / r_x) == H_p
+ *    (true for every "same"-padded layer), else GF_ERR_SHAPE.
+ *  - r == 1 means vanilla back-propagation (Sec. 4.2): x_u and gy_u are then
+ *    the full maps x and g_y (x_u is [N, C_in, H_in, W_in]), the two reduction
+ *    entries are plain copies, and gf_conv_bwd_weight / gf_conv_bwd_input
+ *    evaluate the exact K_h x K_w contractions of Sec. 3.1.
+ *  - Dilation only affects H_y and the exact entry: the filtered formulas read
+ *    the tap's own padded patch wherever it lands (Supp. B "Boundary Elements").
+ *  - Results are deterministic: no floating-point atomics, so two calls on the
+ *    same inputs give bit-identical outputs.
+ */
+#ifndef GF_H
+#define GF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gf_status {
+  GF_OK = 0,
+  GF_ERR_NULL = 1,        /* a required pointer is NULL                              */
+  GF_ERR_BAD_DESC = 2,    /* non-positive size, r < 1, groups not dividing channels,
+                             unknown dtype, wrong struct_size                        */
+  GF_ERR_SHAPE = 3,       /* kernel larger than the padded input, or the patch grids
+                             of x and g_y differ                                     */
+  GF_ERR_UNSUPPORTED = 4, /* legal but not implemented (e.g. a misaligned pointer,
+                             more than 2^31-1 elements in one tensor)                */
+  GF_ERR_WORKSPACE = 5,   /* ws is NULL or smaller than gf_workspace_bytes says      */
+  GF_ERR_DEVICE = 6       /* the HIP runtime refused a launch                        */
+} gf_status;
+
+typedef enum gf_dtype { GF_F32 = 0, GF_BF16 = 1 } gf_dtype;
+
+typedef enum gf_op {
+  GF_OP_BWD_WEIGHT = 0,
+  GF_OP_BWD_INPUT = 1,
+  GF_OP_BWD_EXACT = 2
+} gf_op;
+
+/* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
+ * Sec. 3); set struct_size = sizeof(gf_conv_desc). */
+typedef struct gf_conv_desc {
+  uint32_t struct_size;
+  int32_t N, C_in, C_out, H_in, W_in; /* x: [N, C_in, H_in, W_in]                   */
+  int32_t K_h, K_w, stride, pad, dilation, groups;
+  int32_t r;                          /* patch size on g_y; 1 = vanilla BP          */
+  int32_t dtype;                      /* gf_dtype of x, w, g_y, g_x, x_u, gy_u      */
+} gf_conv_desc;
+
+/* Closed forms of the paper for one layer (host only). FLOPs and stored
+ * activation counts are per image; the byte counts are this library's
+ * algorithmic HBM traffic for the whole batch (each tensor read or written
+ * once by the step that owns it). */
+typedef struct gf_cost {
+  double flops_exact_gx;  /* Eq. (1)                                                */
+  double flops_gf_gx;     /* Eq. (12), leading term                                 */
+  double flops_gf_min;    /* Eq. (13), leading term                                 */
+  double overhead_fwd;    /* Sec. 4.2 "Overhead": 1 / (2 C_o W_th H_th)             */
+  double overhead_bwd;    /* Sec. 4.2 "Overhead": (r^2 - 1) / (2 C_x)               */
+  double act_elems_exact; /* Sec. 4.3: stored values of x per image                 */
+  double act_elems_gf;    /* Sec. 4.3: stored values of x_u per image               */
+  double bytes_pool;      /* gf_pool_activation: read x, write x_u                  */
+  double bytes_filter;    /* gf_filter_grad: read g_y, write gy_u                   */
+  double bytes_bwd_weight;/* read x_u and gy_u, write g_w                           */
+  double bytes_bwd_input; /* read gy_u and w, write g_x (full resolution)           */
+  double bytes_exact;     /* read x, w, g_y; write g_w and g_x                      */
+  double flops_bwd_weight;/* 2 N P C_out C_in/groups                                */
+  double flops_bwd_input; /* 2 N P C_out C_in/groups                                */
+  double flops_exact;     /* 4 N C_out (C_in/groups) K_h K_w H_y W_y                */
+} gf_cost;
+
+/* Output map and patch grid of the layer (Sec. 3.3).  Any out pointer may be
+ * NULL.  Host only. */
+gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int32_t* H_p,
+                       int32_t* W_p);
+
+/* Scratch bytes `op` needs for this layer (may be 0).  Host only. */
+gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes);
+
+/* Forward-time pooling of the activation (text after Eq. 5; Fig. 2(a) lower
+ * half): x_u = sum of x over each r_x x r_x patch.  x_u is what a training
+ * loop keeps for the backward pass instead of x (Sec. 4.3). */
+gf_status gf_pool_activation(const gf_conv_desc* desc, const void* x, void* x_u, void* stream);
+
+/* The gradient filter (Eq. 2): gy_u = mean of g_y over each r x r patch, one
+ * value per patch (the matrix of unique values, Sec. 3.3). */
+gf_status gf_filter_grad(const gf_conv_desc* desc, const void* g_y, void* gy_u, void* stream);
+
+/* Filtered weight gradient (Eq. 5): the Frobenius inner product of x_u and gy_u
+ * over (n, patch) for every (c_o, c_i) pair of a group, scaled by 1/stride^2 and
+ * written to all K_h*K_w taps (they are bit-identical).  g_w is fp32. */
+gf_status gf_conv_bwd_weight(const gf_conv_desc* desc, const void* x_u, const void* gy_u,
+                             float* g_w, void* ws, size_t ws_bytes, void* stream);
+
+/* Filtered input gradient (Eq. 3): sum over the group's c_o of gy_u times the
+ * spatial sum of the kernel, scaled by 1/stride^2; every pixel of an input-side
+ * patch receives its patch's value (bit-identical), or, with reduced_out != 0,
+ * only the one value per patch is written ([N, C_in, H_p, W_p]). */
+gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const void* w, void* g_x,
+                            int reduced_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Vanilla back-propagation of the layer (Sec. 3.1): g_w = g_y (F) x and
+ * g_x = g_y (*) rot180(w), zero padding, with stride, dilation and groups.
+ * The reference the filtered path approximates and the speed-up denominator.
+ * g_w or g_x may be NULL to skip that gradient (x resp. w may then be NULL). */
+gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void* w,
+                            const void* g_y, float* g_w, void* g_x, void* ws, size_t ws_bytes,
+                            void* stream);
+
+/* Closed forms of Sec. 3.2, 4.2, 4.3 plus the byte / FLOP model.  Host only. */
+gf_status gf_cost_model(const gf_conv_desc* desc, gf_cost* out);
+
+const char* gf_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int gf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GF_H */

@@ -301,7 +301,7 @@ int gf_ref_cost_model(const gf_ref_desc* d, gf_ref_cost* out) {
   if (rc) return rc;
   if (!out) return REF_NULL;
   double Cx = d->C_in, Cy = d->C_out, KK = (double)d->K_h * d->K_w;
-  int rx = d->r * d->stride;
+  int rx = d->r == 1 ? 1 : d->r * d->stride; /* r == 1 is vanilla BP: x itself is stored */
   out->flops_exact_gx = 2.0 * Cx * Cy * (double)Wy * Hy * KK;
   out->flops_gf_gx = (double)Hp * Wp * Cx * (2.0 * Cy - 1.0);
   out->flops_gf_min = 2.0 * Cx * Cy - Cx;

@@ -1,0 +1,229 @@
+// C ABI of libgf: validation, workspace planning and dispatch.  Every check
+// happens on the host before anything is enqueued.
+#include <string.h>
+
+#include "gf_internal.h"
+
+namespace gf {
+
+gf_status make_geom(const gf_conv_desc* d, Geom* o) {
+  if (!d) return GF_ERR_NULL;
+  if (d->struct_size != sizeof(gf_conv_desc)) return GF_ERR_BAD_DESC;
+  if (d->N < 1 || d->C_in < 1 || d->C_out < 1 || d->H_in < 1 || d->W_in < 1) return GF_ERR_BAD_DESC;
+  if (d->K_h < 1 || d->K_w < 1 || d->stride < 1 || d->pad < 0 || d->dilation < 1)
+    return GF_ERR_BAD_DESC;
+  if (d->groups < 1 || d->C_in % d->groups || d->C_out % d->groups) return GF_ERR_BAD_DESC;
+  if (d->r < 1) return GF_ERR_BAD_DESC;
+  if (d->dtype != GF_F32 && d->dtype != GF_BF16) return GF_ERR_BAD_DESC;
+  Geom g;
+  g.N = d->N; g.Ci = d->C_in; g.Co = d->C_out; g.H = d->H_in; g.W = d->W_in;
+  g.Kh = d->K_h; g.Kw = d->K_w; g.s = d->stride; g.p = d->pad; g.dl = d->dilation;
+  g.g = d->groups; g.r = d->r;
+  const long eh = (long)g.H + 2L * g.p - (long)g.dl * (g.Kh - 1) - 1;
+  const long ew = (long)g.W + 2L * g.p - (long)g.dl * (g.Kw - 1) - 1;
+  if (eh < 0 || ew < 0) return GF_ERR_SHAPE;
+  g.Hy = (int)(eh / g.s) + 1;
+  g.Wy = (int)(ew / g.s) + 1;
+  g.Hp = cdiv(g.Hy, g.r);
+  g.Wp = cdiv(g.Wy, g.r);
+  g.rx = g.r == 1 ? 1 : g.r * g.s;
+  if (g.r > 1 && (cdiv(g.H, g.rx) != g.Hp || cdiv(g.W, g.rx) != g.Wp)) return GF_ERR_SHAPE;
+  g.Cg = g.Ci / g.g;
+  g.Og = g.Co / g.g;
+  g.KK = g.Kh * g.Kw;
+  g.P = g.Hp * g.Wp;
+  g.dtype = d->dtype;
+  g.b = d->dtype == GF_BF16 ? 2 : 4;
+  // 32-bit element indexing inside the kernels
+  const long lim = 2147483647L;
+  if ((long)g.N * g.Ci * g.H * g.W > lim || (long)g.N * g.Co * g.Hy * g.Wy > lim ||
+      (long)g.Co * g.Cg * g.KK > lim)
+    return GF_ERR_UNSUPPORTED;
+  // grid dimensions y (group x channel tile) and z (image) are limited to 65535
+  if (g.N > 65535 || (long)g.g * cdiv(g.Cg > g.Og ? g.Cg : g.Og, 16) > 65535) return GF_ERR_UNSUPPORTED;
+  *o = g;
+  return GF_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static gf_status dev(hipError_t e) { return e == hipSuccess ? GF_OK : GF_ERR_DEVICE; }
+
+static size_t ws_need(const Geom& g, int op, bool reduced_out) {
+  switch (op) {
+    case GF_OP_BWD_WEIGHT:
+      return g.r == 1 ? ws_exact(g, true, false) : ws_bwd_weight(g);
+    case GF_OP_BWD_INPUT:
+      return g.r == 1 ? ws_exact(g, false, true) : ws_bwd_input(g, reduced_out);
+    default:
+      return ws_exact(g, true, true);
+  }
+}
+
+static gf_status check_ws(size_t need, const void* ws, size_t ws_bytes) {
+  if (need == 0) return GF_OK;
+  if (!ws || ws_bytes < need) return GF_ERR_WORKSPACE;
+  if (!aligned16(ws)) return GF_ERR_UNSUPPORTED;
+  return GF_OK;
+}
+
+}  // namespace gf
+
+using namespace gf;
+
+extern "C" {
+
+int gf_version(void) { return 100; }
+
+const char* gf_status_string(int s) {
+  switch (s) {
+    case GF_OK: return "GF_OK";
+    case GF_ERR_NULL: return "GF_ERR_NULL: a required pointer is NULL";
+    case GF_ERR_BAD_DESC: return "GF_ERR_BAD_DESC: invalid layer descriptor";
+    case GF_ERR_SHAPE: return "GF_ERR_SHAPE: kernel exceeds padded input or patch grids of x and g_y differ";
+    case GF_ERR_UNSUPPORTED: return "GF_ERR_UNSUPPORTED: misaligned pointer or tensor too large";
+    case GF_ERR_WORKSPACE: return "GF_ERR_WORKSPACE: workspace missing or too small";
+    case GF_ERR_DEVICE: return "GF_ERR_DEVICE: HIP launch failed";
+    default: return "GF_ERR_?: unknown status";
+  }
+}
+
+gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int32_t* H_p,
+                       int32_t* W_p) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (H_y) *H_y = g.Hy;
+  if (W_y) *W_y = g.Wy;
+  if (H_p) *H_p = g.Hp;
+  if (W_p) *W_p = g.Wp;
+  return GF_OK;
+}
+
+gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
+  if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT)
+    return GF_ERR_BAD_DESC;
+  if (!desc) return GF_ERR_NULL;
+  gf_conv_desc d1;
+  if (desc->struct_size != sizeof(gf_conv_desc)) return GF_ERR_BAD_DESC;
+  memcpy(&d1, desc, sizeof(d1));
+  if (d1.r < 1) return GF_ERR_BAD_DESC;
+  if (op == GF_OP_BWD_EXACT) d1.r = 1;  // the exact entry ignores the patch size
+  Geom g;
+  gf_status rc = make_geom(&d1, &g);
+  if (rc) return rc;
+  if (!bytes) return GF_ERR_NULL;
+  // the full-resolution form of the input gradient needs at least as much as the reduced one
+  *bytes = ws_need(g, op, false);
+  return GF_OK;
+}
+
+gf_status gf_pool_activation(const gf_conv_desc* desc, const void* x, void* x_u, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!x || !x_u) return GF_ERR_NULL;
+  if (!aligned16(x) || !aligned16(x_u)) return GF_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long planes = (long)g.N * g.Ci;
+  if (g.r == 1)
+    return dev(hipMemcpyAsync(x_u, x, (size_t)planes * g.H * g.W * g.b, hipMemcpyDeviceToDevice, st));
+  return dev(launch_patch_reduce(x, x_u, planes, g.H, g.W, g.rx, false, g.dtype, st));
+}
+
+gf_status gf_filter_grad(const gf_conv_desc* desc, const void* g_y, void* gy_u, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!g_y || !gy_u) return GF_ERR_NULL;
+  if (!aligned16(g_y) || !aligned16(gy_u)) return GF_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long planes = (long)g.N * g.Co;
+  if (g.r == 1)
+    return dev(hipMemcpyAsync(gy_u, g_y, (size_t)planes * g.Hy * g.Wy * g.b, hipMemcpyDeviceToDevice, st));
+  return dev(launch_patch_reduce(g_y, gy_u, planes, g.Hy, g.Wy, g.r, true, g.dtype, st));
+}
+
+gf_status gf_conv_bwd_weight(const gf_conv_desc* desc, const void* x_u, const void* gy_u,
+                             float* g_w, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!x_u || !gy_u || !g_w) return GF_ERR_NULL;
+  if (!aligned16(x_u) || !aligned16(gy_u) || !aligned16(g_w)) return GF_ERR_UNSUPPORTED;
+  rc = check_ws(ws_need(g, GF_OP_BWD_WEIGHT, false), ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (g.r == 1) return dev(launch_exact_wgrad(g, x_u, gy_u, g_w, ws, st));
+  return dev(launch_gf_bwd_weight(g, x_u, gy_u, g_w, ws, st));
+}
+
+gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const void* w, void* g_x,
+                            int reduced_out, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!gy_u || !w || !g_x) return GF_ERR_NULL;
+  if (!aligned16(gy_u) || !aligned16(w) || !aligned16(g_x)) return GF_ERR_UNSUPPORTED;
+  rc = check_ws(ws_need(g, GF_OP_BWD_INPUT, reduced_out != 0), ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (g.r == 1) return dev(launch_exact_dgrad(g, w, gy_u, g_x, ws, st));
+  return dev(launch_gf_bwd_input(g, gy_u, w, g_x, reduced_out != 0, ws, st));
+}
+
+gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void* w,
+                            const void* g_y, float* g_w, void* g_x, void* ws, size_t ws_bytes,
+                            void* stream) {
+  if (!desc) return GF_ERR_NULL;
+  gf_conv_desc d1;
+  if (desc->struct_size != sizeof(gf_conv_desc)) return GF_ERR_BAD_DESC;
+  memcpy(&d1, desc, sizeof(d1));
+  if (d1.r < 1) return GF_ERR_BAD_DESC;
+  d1.r = 1;  // the exact entry ignores the patch size
+  Geom g;
+  gf_status rc = make_geom(&d1, &g);
+  if (rc) return rc;
+  if (!g_y || (!g_w && !g_x)) return GF_ERR_NULL;
+  if ((g_w && !x) || (g_x && !w)) return GF_ERR_NULL;
+  if (!aligned16(g_y) || !aligned16(x) || !aligned16(w) || !aligned16(g_w) || !aligned16(g_x))
+    return GF_ERR_UNSUPPORTED;
+  rc = check_ws(ws_exact(g, g_w != nullptr, g_x != nullptr), ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (g_w) {
+    rc = dev(launch_exact_wgrad(g, x, g_y, g_w, ws, st));
+    if (rc) return rc;
+  }
+  if (g_x) rc = dev(launch_exact_dgrad(g, w, g_y, g_x, ws, st));
+  return rc;
+}
+
+gf_status gf_cost_model(const gf_conv_desc* desc, gf_cost* out) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!out) return GF_ERR_NULL;
+  const double Cx = g.Ci, Cy = g.Co, KK = g.KK, b = g.b;
+  const double HWx = (double)g.H * g.W, HWy = (double)g.Hy * g.Wy, P = g.P, N = g.N;
+  const double wel = Cy * g.Cg * KK;
+  out->flops_exact_gx = 2.0 * Cx * Cy * HWy * KK;
+  out->flops_gf_gx = P * Cx * (2.0 * Cy - 1.0);
+  out->flops_gf_min = 2.0 * Cx * Cy - Cx;
+  out->overhead_fwd = 1.0 / (2.0 * Cy * KK);
+  out->overhead_bwd = ((double)g.r * g.r - 1.0) / (2.0 * Cx);
+  out->act_elems_exact = Cx * HWx;
+  const double Px = g.r == 1 ? HWx : P;  // x_u keeps x's resolution for r == 1
+  out->act_elems_gf = Cx * Px;
+  out->bytes_pool = b * N * Cx * (HWx + Px);
+  out->bytes_filter = b * N * Cy * (HWy + P);
+  out->bytes_bwd_weight = b * N * (Cx * Px + Cy * P) + 4.0 * wel;
+  out->bytes_bwd_input = b * N * Cy * P + b * wel + b * N * Cx * HWx;
+  out->bytes_exact = b * N * (Cx * HWx + Cy * HWy) + b * wel + 4.0 * wel + b * N * Cx * HWx;
+  out->flops_bwd_weight = 2.0 * N * P * Cy * g.Cg;
+  out->flops_bwd_input = 2.0 * N * P * Cy * g.Cg;
+  out->flops_exact = 4.0 * N * Cy * g.Cg * KK * HWy;
+  return GF_OK;
+}
+
+}  // extern "C"

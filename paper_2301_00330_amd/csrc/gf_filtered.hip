@@ -1,0 +1,418 @@
+// Filtered backward from the reduced maps: kernel spatial sum (text after
+// Eq. 3), weight gradient (Eq. 5) and input gradient (Eq. 3).
+//
+// This file holds the shape-generic kernels (any groups, any P, fp32 FMA with
+// LDS tiling) and the depthwise kernels.  Reductions over the batch are done in
+// two deterministic stages (partials in the workspace, then a fixed-order sum),
+// never with floating-point atomics.
+#include "gf_internal.h"
+
+namespace gf {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// ---------------------------------------------------------------------------
+// S2: wsum[pair] = sum_t w[pair, t]
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(kThreads) void kernel_sum_k(const T* w, float* wsum, int pairs, int KK) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= pairs) return;
+  const T* p = w + (long)e * KK;
+  float acc = 0.f;
+  for (int t = 0; t < KK; ++t) acc += to_f32(p[t]);
+  wsum[e] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// finalize a two-stage reduction: g_w[pair, all taps] = scale * sum_z part[z, pair]
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void finalize_gw_k(const float* part, float* g_w, int pairs,
+                                                         int nz, int KK, float scale) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= pairs) return;
+  float acc = 0.f;
+  for (int z = 0; z < nz; ++z) acc += part[(long)z * pairs + e];
+  acc *= scale;
+  for (int t = 0; t < KK; ++t) g_w[(long)e * KK + t] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// S3 depthwise, stage 1: part[plane] = <x_u[plane, :], gy_u[plane, :]>,
+// L lanes per plane (L a power of two <= 64), xor-shuffle reduction.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(kThreads) void dw_dot_k(const T* xu, const T* gyu, float* part,
+                                                    int planes, int P, int L) {
+  const int gid = blockIdx.x * kThreads + threadIdx.x;
+  const int plane = gid / L;
+  const int lane = gid - plane * L;
+  float acc = 0.f;
+  if (plane < planes) {
+    const T* a = xu + (long)plane * P;
+    const T* b = gyu + (long)plane * P;
+    for (int p = lane; p < P; p += L) acc += to_f32(a[p]) * to_f32(b[p]);
+  }
+  for (int m = L >> 1; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (plane < planes && lane == 0) part[plane] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// S3 generic: part[z, co, cl] = sum_{n in slab z} sum_p gy_u[n,co,p] * x_u[n,ci,p]
+// 64 x 64 output tile per block, 4 x 4 per lane, K chunks of 16 patches.
+// ---------------------------------------------------------------------------
+struct WgradArgs {
+  const void* xu;
+  const void* gyu;
+  float* part;
+  int N, Ci, Co, Cg, Og, P;
+  int tiles_co;  // per group
+  int n_per_z;
+};
+
+template <class T>
+__global__ __launch_bounds__(kThreads) void gf_wgrad_tile_k(WgradArgs a) {
+  __shared__ float As[16][65];  // [k][co]
+  __shared__ float Bs[16][65];  // [k][cl]
+  const T* xu = static_cast<const T*>(a.xu);
+  const T* gyu = static_cast<const T*>(a.gyu);
+  const int tid = threadIdx.x;
+  const int grp = blockIdx.y / a.tiles_co;
+  const int ol0 = (blockIdx.y - grp * a.tiles_co) * 64;  // first c_o of the tile, local to the group
+  const int cl0 = blockIdx.x * 64;
+  const int n0 = blockIdx.z * a.n_per_z;
+  const int n1 = min(n0 + a.n_per_z, a.N);
+  const int ty = tid >> 4, tx = tid & 15;
+  float acc[4][4] = {};
+  for (int n = n0; n < n1; ++n) {
+    const T* ga = gyu + ((long)n * a.Co + grp * a.Og) * a.P;
+    const T* gb = xu + ((long)n * a.Ci + grp * a.Cg) * a.P;
+    for (int p0 = 0; p0 < a.P; p0 += 16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = tid + i * kThreads;
+        const int row = e >> 4, k = e & 15;
+        const bool kin = p0 + k < a.P;
+        As[k][row] = (kin && ol0 + row < a.Og) ? to_f32(ga[(long)(ol0 + row) * a.P + p0 + k]) : 0.f;
+        Bs[k][row] = (kin && cl0 + row < a.Cg) ? to_f32(gb[(long)(cl0 + row) * a.P + p0 + k]) : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        float av[4], bv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) av[i] = As[k][ty * 4 + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bv[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] += av[i] * bv[j];
+      }
+      __syncthreads();
+    }
+  }
+  float* dst = a.part + (long)blockIdx.z * a.Co * a.Cg;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ol = ol0 + ty * 4 + i;
+    if (ol >= a.Og) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int cl = cl0 + tx * 4 + j;
+      if (cl < a.Cg) dst[(long)(grp * a.Og + ol) * a.Cg + cl] = acc[i][j];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// S4 generic, reduced map: dst[n, ci, p] = scale * sum_ol wsum[co, cl] * gy_u[n, co, p]
+// 64 (ci) x 64 (p) tile per block, K chunks of 16 output channels.
+// ---------------------------------------------------------------------------
+struct DgradArgs {
+  const void* gyu;
+  const float* wsum;
+  void* dst;
+  int N, Ci, Co, Cg, Og, P;
+  int tiles_ci;  // per group
+  float scale;
+};
+
+template <class T, class D>
+__global__ __launch_bounds__(kThreads) void gf_dgrad_tile_k(DgradArgs a) {
+  __shared__ float As[16][65];  // [k = ol][cl]
+  __shared__ float Bs[16][65];  // [k = ol][p]
+  const T* gyu = static_cast<const T*>(a.gyu);
+  D* dst = static_cast<D*>(a.dst);
+  const int tid = threadIdx.x;
+  const int n = blockIdx.z;
+  const int grp = blockIdx.y / a.tiles_ci;
+  const int cl0 = (blockIdx.y - grp * a.tiles_ci) * 64;
+  const int p0 = blockIdx.x * 64;
+  const int ty = tid >> 4, tx = tid & 15;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < a.Og; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + i * kThreads;
+      const int k = e >> 6, col = e & 63;
+      const bool kin = k0 + k < a.Og;
+      const int co = grp * a.Og + k0 + k;
+      As[k][col] = (kin && cl0 + col < a.Cg) ? a.wsum[(long)co * a.Cg + cl0 + col] : 0.f;
+      Bs[k][col] = (kin && p0 + col < a.P) ? to_f32(gyu[((long)n * a.Co + co) * a.P + p0 + col]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) av[i] = As[k][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bv[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += av[i] * bv[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int cl = cl0 + ty * 4 + i;
+    if (cl >= a.Cg) continue;
+    const int ci = grp * a.Cg + cl;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = p0 + tx * 4 + j;
+      if (p < a.P) dst[((long)n * a.Ci + ci) * a.P + p] = from_f32<D>(acc[i][j] * a.scale);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Expansion to full resolution: out[plane, h, w] = f(src[plane, h/rx, w/rx]),
+// f(v) = v * chscale[plane % C] * scalar (chscale may be null).  Each lane
+// produces one 16-byte run of consecutive output elements; the run may cross
+// rows and planes, so indices are advanced element by element.
+// ---------------------------------------------------------------------------
+struct ExpandArgs {
+  const void* src;
+  void* out;
+  const float* chscale;
+  float scalar;
+  int C, H, W, rx, Hp, Wp;
+  int total;  // planes * H * W
+};
+
+template <class T, class S>
+__global__ __launch_bounds__(kThreads) void expand_k(ExpandArgs a) {
+  constexpr int V = 16 / (int)sizeof(T);
+  const S* src = static_cast<const S*>(a.src);
+  T* out = static_cast<T*>(a.out);
+  const int e0 = (blockIdx.x * kThreads + threadIdx.x) * V;
+  if (e0 >= a.total) return;
+  const int HW = a.H * a.W;
+  int plane = e0 / HW;
+  int rem = e0 - plane * HW;
+  int h = rem / a.W;
+  int w = rem - h * a.W;
+  int hp = h / a.rx, hr = h - hp * a.rx;
+  int wp = w / a.rx, wr = w - wp * a.rx;
+  float sc = a.scalar * (a.chscale ? a.chscale[plane % a.C] : 1.f);
+  const int P = a.Hp * a.Wp;
+  T vals[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    float v = 0.f;
+    if (e0 + k < a.total) v = to_f32(src[(long)plane * P + hp * a.Wp + wp]) * sc;
+    vals[k] = from_f32<T>(v);
+    // advance one output element
+    ++w;
+    if (++wr == a.rx) { wr = 0; ++wp; }
+    if (w == a.W) {
+      w = 0; wp = 0; wr = 0;
+      ++h;
+      if (++hr == a.rx) { hr = 0; ++hp; }
+      if (h == a.H) {
+        h = 0; hp = 0; hr = 0;
+        ++plane;
+        sc = a.scalar * (a.chscale ? a.chscale[plane % a.C] : 1.f);
+      }
+    }
+  }
+  if (e0 + V <= a.total) {
+    *reinterpret_cast<uint4*>(out + e0) = *reinterpret_cast<const uint4*>(vals);
+  } else {
+    for (int k = 0; e0 + k < a.total; ++k) out[e0 + k] = vals[k];
+  }
+}
+
+template <class T, class S>
+hipError_t launch_expand(const S* src, T* out, const float* chscale, float scalar, long planes,
+                         int C, int H, int W, int rx, int Hp, int Wp, hipStream_t st) {
+  ExpandArgs a;
+  a.src = src;
+  a.out = out;
+  a.chscale = chscale;
+  a.scalar = scalar;
+  a.C = C;
+  a.H = H;
+  a.W = W;
+  a.rx = rx;
+  a.Hp = Hp;
+  a.Wp = Wp;
+  a.total = (int)(planes * H * W);
+  constexpr int V = 16 / (int)sizeof(T);
+  const int blocks = cdiv(cdiv(a.total, V), kThreads);
+  hipLaunchKernelGGL((expand_k<T, S>), dim3(blocks), dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+int dw_lanes(int P) {
+  int L = 1;
+  while (L < P && L < 64) L <<= 1;
+  return L;
+}
+
+bool is_depthwise(const Geom& g) { return g.Cg == 1 && g.Og == 1; }
+
+int wgrad_splits(const Geom& g) {
+  // enough blocks to cover the chip: tiles * splits >= ~512, at most one image per split
+  const int tiles = g.g * cdiv(g.Og, 64) * cdiv(g.Cg, 64);
+  int z = cdiv(512, tiles);
+  if (z > g.N) z = g.N;
+  if (z < 1) z = 1;
+  const int n_per_z = cdiv(g.N, z);
+  return cdiv(g.N, n_per_z);
+}
+
+}  // namespace
+
+hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int dtype,
+                             hipStream_t st) {
+  const int blocks = cdiv(pairs, kThreads);
+  if (dtype == GF_BF16)
+    hipLaunchKernelGGL(kernel_sum_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
+                       static_cast<const bf16_t*>(w), wsum, (int)pairs, KK);
+  else
+    hipLaunchKernelGGL(kernel_sum_k<float>, dim3(blocks), dim3(kThreads), 0, st,
+                       static_cast<const float*>(w), wsum, (int)pairs, KK);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// S3
+// ---------------------------------------------------------------------------
+size_t ws_bwd_weight(const Geom& g) {
+  if (is_depthwise(g)) return (size_t)g.N * g.Ci * sizeof(float);
+  return (size_t)wgrad_splits(g) * g.Co * g.Cg * sizeof(float);
+}
+
+hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u, float* g_w,
+                                void* ws, hipStream_t st) {
+  float* part = static_cast<float*>(ws);
+  const float scale = 1.f / ((float)g.s * (float)g.s);
+  const int pairs = g.Co * g.Cg;
+  int nz;
+  if (is_depthwise(g)) {
+    const int planes = g.N * g.Ci;
+    const int L = dw_lanes(g.P);
+    const int blocks = cdiv((long)planes * L, kThreads);
+    if (g.dtype == GF_BF16)
+      hipLaunchKernelGGL(dw_dot_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
+                         static_cast<const bf16_t*>(x_u), static_cast<const bf16_t*>(gy_u), part,
+                         planes, g.P, L);
+    else
+      hipLaunchKernelGGL(dw_dot_k<float>, dim3(blocks), dim3(kThreads), 0, st,
+                         static_cast<const float*>(x_u), static_cast<const float*>(gy_u), part,
+                         planes, g.P, L);
+    nz = g.N;
+  } else {
+    WgradArgs a;
+    a.xu = x_u;
+    a.gyu = gy_u;
+    a.part = part;
+    a.N = g.N;
+    a.Ci = g.Ci;
+    a.Co = g.Co;
+    a.Cg = g.Cg;
+    a.Og = g.Og;
+    a.P = g.P;
+    a.tiles_co = cdiv(g.Og, 64);
+    nz = wgrad_splits(g);
+    a.n_per_z = cdiv(g.N, nz);
+    dim3 grid(cdiv(g.Cg, 64), g.g * a.tiles_co, nz);
+    if (g.dtype == GF_BF16)
+      hipLaunchKernelGGL(gf_wgrad_tile_k<bf16_t>, grid, dim3(kThreads), 0, st, a);
+    else
+      hipLaunchKernelGGL(gf_wgrad_tile_k<float>, grid, dim3(kThreads), 0, st, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(finalize_gw_k, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, part, g_w,
+                     pairs, nz, g.KK, scale);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// S2 + S4
+// ---------------------------------------------------------------------------
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t ws_bwd_input(const Geom& g, bool reduced_out) {
+  size_t wsum = align256((size_t)g.Co * g.Cg * sizeof(float));
+  if (is_depthwise(g) || reduced_out) return wsum;
+  return wsum + (size_t)g.N * g.Ci * g.P * sizeof(float);
+}
+
+template <class T>
+static hipError_t bwd_input_t(const Geom& g, const T* gy_u, const T* w, T* g_x, bool reduced_out,
+                              void* ws, hipStream_t st) {
+  float* wsum = static_cast<float*>(ws);
+  hipError_t e = launch_kernel_sum(w, wsum, (long)g.Co * g.Cg, g.KK, g.dtype, st);
+  if (e != hipSuccess) return e;
+  const float scale = 1.f / ((float)g.s * (float)g.s);
+  const long planes = (long)g.N * g.Ci;
+  if (is_depthwise(g)) {
+    if (reduced_out)
+      return launch_expand<T, T>(gy_u, g_x, wsum, scale, planes, g.Ci, g.Hp, g.Wp, 1, g.Hp, g.Wp, st);
+    return launch_expand<T, T>(gy_u, g_x, wsum, scale, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
+  }
+  DgradArgs a;
+  a.gyu = gy_u;
+  a.wsum = wsum;
+  a.N = g.N;
+  a.Ci = g.Ci;
+  a.Co = g.Co;
+  a.Cg = g.Cg;
+  a.Og = g.Og;
+  a.P = g.P;
+  a.tiles_ci = cdiv(g.Cg, 64);
+  a.scale = scale;
+  dim3 grid(cdiv(g.P, 64), g.g * a.tiles_ci, g.N);
+  if (reduced_out) {
+    a.dst = g_x;
+    hipLaunchKernelGGL((gf_dgrad_tile_k<T, T>), grid, dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+  }
+  float* red = reinterpret_cast<float*>(static_cast<char*>(ws) +
+                                        align256((size_t)g.Co * g.Cg * sizeof(float)));
+  a.dst = red;
+  hipLaunchKernelGGL((gf_dgrad_tile_k<T, float>), grid, dim3(kThreads), 0, st, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_expand<T, float>(red, g_x, nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
+}
+
+hipError_t launch_gf_bwd_input(const Geom& g, const void* gy_u, const void* w, void* g_x,
+                               bool reduced_out, void* ws, hipStream_t st) {
+  if (g.dtype == GF_BF16)
+    return bwd_input_t<bf16_t>(g, static_cast<const bf16_t*>(gy_u), static_cast<const bf16_t*>(w),
+                               static_cast<bf16_t*>(g_x), reduced_out, ws, st);
+  return bwd_input_t<float>(g, static_cast<const float*>(gy_u), static_cast<const float*>(w),
+                            static_cast<float*>(g_x), reduced_out, ws, st);
+}
+
+}  // namespace gf

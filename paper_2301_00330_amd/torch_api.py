@@ -1,0 +1,128 @@
+"""Tensor-level convenience layer over ``binding``: allocates outputs and the
+workspace with torch on the tensor's device and enqueues on torch's current
+stream.  Plumbing only -- every arithmetic step runs inside libgf.so."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+from .workloads import Layer
+
+
+def desc_for(layer: Layer, N: int, r: int, dtype: str) -> B.ConvDesc:
+    return B.ConvDesc(N=N, C_in=layer.C_in, C_out=layer.C_out, H_in=layer.H, W_in=layer.W,
+                      K_h=layer.K, K_w=layer.K, stride=layer.stride, pad=layer.pad,
+                      dilation=layer.dilation, groups=layer.groups, r=r,
+                      dtype=B.GF_BF16 if dtype == "bf16" else B.GF_F32)
+
+
+def _tdtype(d: B.ConvDesc):
+    return torch.bfloat16 if d.dtype == B.GF_BF16 else torch.float32
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(t: torch.Tensor, d: B.ConvDesc, shape, what: str, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous device tensor")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{what}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if t.dtype != (dtype or _tdtype(d)):
+        raise ValueError(f"{what}: expected dtype {dtype or _tdtype(d)}, got {t.dtype}")
+
+
+def shapes(d: B.ConvDesc) -> dict:
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    cg = d.C_in // d.groups
+    return {
+        "x": (d.N, d.C_in, d.H_in, d.W_in), "g_y": (d.N, d.C_out, Hy, Wy),
+        "w": (d.C_out, cg, d.K_h, d.K_w),
+        "x_u": (d.N, d.C_in, d.H_in, d.W_in) if d.r == 1 else (d.N, d.C_in, Hp, Wp),
+        "gy_u": (d.N, d.C_out, Hp, Wp),
+        "g_x_u": (d.N, d.C_in, d.H_in, d.W_in) if d.r == 1 else (d.N, d.C_in, Hp, Wp),
+    }
+
+
+class Workspace:
+    """A reusable device scratch buffer (grown on demand, never inside a call to libgf)."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.buf = None
+
+    def get(self, nbytes: int):
+        if nbytes == 0:
+            return 0, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        return int(self.buf.data_ptr()), int(self.buf.numel())
+
+
+_default_ws = {}
+
+
+def _ws(t: torch.Tensor, ws: Workspace | None) -> Workspace:
+    if ws is not None:
+        return ws
+    key = str(t.device)
+    if key not in _default_ws:
+        _default_ws[key] = Workspace(t.device)
+    return _default_ws[key]
+
+
+def pool_activation(d: B.ConvDesc, x: torch.Tensor, out: torch.Tensor | None = None):
+    s = shapes(d)
+    _check(x, d, s["x"], "x")
+    out = torch.empty(s["x_u"], dtype=x.dtype, device=x.device) if out is None else out
+    B.gf_pool_activation(d, B.ptr(x), B.ptr(out), _stream())
+    return out
+
+
+def filter_grad(d: B.ConvDesc, g_y: torch.Tensor, out: torch.Tensor | None = None):
+    s = shapes(d)
+    _check(g_y, d, s["g_y"], "g_y")
+    out = torch.empty(s["gy_u"], dtype=g_y.dtype, device=g_y.device) if out is None else out
+    B.gf_filter_grad(d, B.ptr(g_y), B.ptr(out), _stream())
+    return out
+
+
+def conv_bwd_weight(d: B.ConvDesc, x_u: torch.Tensor, gy_u: torch.Tensor,
+                    out: torch.Tensor | None = None, ws: Workspace | None = None):
+    s = shapes(d)
+    _check(x_u, d, s["x_u"], "x_u")
+    _check(gy_u, d, s["gy_u"], "gy_u")
+    out = torch.empty(s["w"], dtype=torch.float32, device=x_u.device) if out is None else out
+    p, n = _ws(x_u, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT))
+    B.gf_conv_bwd_weight(d, B.ptr(x_u), B.ptr(gy_u), B.ptr(out), p, n, _stream())
+    return out
+
+
+def conv_bwd_input(d: B.ConvDesc, gy_u: torch.Tensor, w: torch.Tensor, reduced_out: bool = False,
+                   out: torch.Tensor | None = None, ws: Workspace | None = None):
+    s = shapes(d)
+    _check(gy_u, d, s["gy_u"], "gy_u")
+    _check(w, d, s["w"], "w")
+    shape = s["g_x_u"] if reduced_out else s["x"]
+    out = torch.empty(shape, dtype=gy_u.dtype, device=gy_u.device) if out is None else out
+    p, n = _ws(gy_u, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT))
+    B.gf_conv_bwd_input(d, B.ptr(gy_u), B.ptr(w), B.ptr(out), reduced_out, p, n, _stream())
+    return out
+
+
+def conv_bwd_exact(d: B.ConvDesc, x, w, g_y, want_gw: bool = True, want_gx: bool = True,
+                   ws: Workspace | None = None):
+    s = shapes(d.with_(r=1))
+    _check(g_y, d, s["g_y"], "g_y")
+    g_w = g_x = None
+    if want_gw:
+        _check(x, d, s["x"], "x")
+        g_w = torch.empty(s["w"], dtype=torch.float32, device=g_y.device)
+    if want_gx:
+        _check(w, d, s["w"], "w")
+        g_x = torch.empty(s["x"], dtype=g_y.dtype, device=g_y.device)
+    p, n = _ws(g_y, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_EXACT))
+    B.gf_conv_bwd_exact(d, B.ptr(x) if want_gw else 0, B.ptr(w) if want_gx else 0, B.ptr(g_y),
+                        B.ptr(g_w), B.ptr(g_x), p, n, _stream())
+    return g_w, g_x

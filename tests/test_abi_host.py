@@ -1,0 +1,108 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/gf.h declares, and rejects bad calls before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2301_00330_amd.binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2301_00330_amd.build import build
+        build()
+    return B.lib()
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "gf.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(gf_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.gf_version() >= 100
+
+
+OK = dict(N=2, C_in=4, C_out=8, H_in=8, W_in=8, K_h=3, K_w=3, pad=1, r=2)
+FAKE = 0x1000  # non-null, 16-byte aligned; never dereferenced because validation fails first
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(r=0), B.GF_ERR_BAD_DESC), (dict(groups=3), B.GF_ERR_BAD_DESC), (dict(N=0), B.GF_ERR_BAD_DESC),
+    (dict(stride=0), B.GF_ERR_BAD_DESC), (dict(dilation=0), B.GF_ERR_BAD_DESC), (dict(pad=-1), B.GF_ERR_BAD_DESC),
+    (dict(dtype=7), B.GF_ERR_BAD_DESC), (dict(pad=0), B.GF_ERR_SHAPE), (dict(K_h=19, K_w=19), B.GF_ERR_SHAPE),
+    (dict(N=1 << 20, C_in=1 << 10, H_in=64, W_in=64), B.GF_ERR_UNSUPPORTED),
+])
+def test_descriptor_errors(lib, bad, status):
+    d = B.ConvDesc(**{**OK, **bad})
+    for call in (lambda: B.gf_out_shape(d),
+                 lambda: B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT),
+                 lambda: B.gf_filter_grad(d, FAKE, FAKE),
+                 lambda: B.gf_pool_activation(d, FAKE, FAKE),
+                 lambda: B.gf_conv_bwd_weight(d, FAKE, FAKE, FAKE, FAKE, 1 << 30),
+                 lambda: B.gf_conv_bwd_input(d, FAKE, FAKE, FAKE, False, FAKE, 1 << 30),
+                 lambda: B.gf_cost_model(d)):
+        with pytest.raises(B.GfError) as ei:
+            call()
+        assert ei.value.status == status
+
+
+def test_exact_entry_ignores_patch_grid_rule(lib):
+    # an unpadded 3x3 layer is illegal for r = 2 (grids differ) but fine for the exact entry
+    d = B.ConvDesc(**{**OK, "pad": 0})
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_exact(d, FAKE, FAKE, 0, FAKE, FAKE, 0, 0)
+    assert ei.value.status == B.GF_ERR_NULL        # g_y is NULL: shape accepted, pointer rejected
+
+
+def test_pointer_and_workspace_errors(lib):
+    d = B.ConvDesc(**OK)
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad(d, 0, FAKE)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation(d, FAKE, 0)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad(d, FAKE + 4, FAKE)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    need = B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT)
+    assert need > 0
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_weight(d, FAKE, FAKE, FAKE, FAKE, need - 1)
+    assert ei.value.status == B.GF_ERR_WORKSPACE
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_input(d, FAKE, FAKE, FAKE, False, 0, 0)
+    assert ei.value.status == B.GF_ERR_WORKSPACE
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_exact(d, 0, 0, FAKE, 0, 0, 0, 0)
+    assert ei.value.status == B.GF_ERR_NULL
+    # wrong struct_size
+    cd = d.c()
+    cd.struct_size = 8
+    assert lib.gf_out_shape(C.byref(cd), None, None, None, None) == B.GF_ERR_BAD_DESC
+    assert lib.gf_out_shape(None, None, None, None, None) == B.GF_ERR_NULL
+    assert "GF_ERR_SHAPE" in B.status_string(B.GF_ERR_SHAPE)
+
+
+def test_shapes_and_cost_model_against_oracle(lib, oracle):
+    """The library's host-side shape rule and closed forms agree with the oracle's
+    (two independent implementations of Sec. 3.2 / 3.3 / 4.2 / 4.3)."""
+    cases = [dict(N=32, C_in=24, C_out=144, H_in=56, W_in=56, r=2),
+             dict(N=64, C_in=256, C_out=512, H_in=14, W_in=14, K_h=3, K_w=3, stride=2, pad=1, r=2),
+             dict(N=64, C_in=512, C_out=512, H_in=7, W_in=7, K_h=3, K_w=3, pad=1, r=4),
+             dict(N=8, C_in=256, C_out=256, H_in=64, W_in=64, K_h=3, K_w=3, pad=36, dilation=36, r=8),
+             dict(N=1, C_in=192, C_out=64, H_in=160, W_in=120, K_h=3, K_w=3, pad=1, r=1),
+             dict(N=2, C_in=8, C_out=8, H_in=14, W_in=14, K_h=3, K_w=3, stride=2, pad=1, groups=8, r=1)]
+    for kw in cases:
+        d, o = B.ConvDesc(**kw), oracle.Desc(**kw)
+        assert B.gf_out_shape(d) == oracle.out_shape(o)
+        c, oc = B.gf_cost_model(d), oracle.cost_model(o)
+        for k, v in oc.items():
+            assert c[k] == pytest.approx(v, rel=1e-12), k

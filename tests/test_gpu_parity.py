@@ -1,0 +1,340 @@
+"""GPU parity: every entry point of libgf, called through the C ABI, against the
+CPU oracle on the same seeded inputs.
+
+Tolerances (per output tensor, max|gpu - ref| / max|ref|): 1e-5 for fp32 and
+2e-2 for bf16 storage with fp32 accumulation; the oracle accumulates in fp64 and
+consumes the same (already rounded) inputs.  Layout / index tests use
+integer-coded inputs whose sums are exact, and must agree bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2301_00330_amd.binding as B
+import paper_2301_00330_amd.torch_api as T
+from paper_2301_00330_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.lib()  # fail loudly if libgf.so was not built
+
+
+def to64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def rel_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
+    g = to64(gpu)
+    assert g.shape == ref.shape, (g.shape, ref.shape)
+    den = np.abs(ref).max()
+    return float(np.abs(g - ref).max() / (den if den > 0 else 1.0))
+
+
+def rounded(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """oracle result -> the storage dtype (one round-to-nearest-even), as a CPU tensor"""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(WL.torch_dtype(dtype))
+
+
+def odesc(oracle, d: B.ConvDesc):
+    return oracle.Desc(N=d.N, C_in=d.C_in, C_out=d.C_out, H_in=d.H_in, W_in=d.W_in, K_h=d.K_h,
+                       K_w=d.K_w, stride=d.stride, pad=d.pad, dilation=d.dilation, groups=d.groups, r=d.r)
+
+
+def mk(N, Ci, Co, H, W, K=1, s=1, p=0, dl=1, g=1, r=2, dtype="f32"):
+    return B.ConvDesc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, stride=s, pad=p,
+                      dilation=dl, groups=g, r=r, dtype=B.GF_BF16 if dtype == "bf16" else B.GF_F32)
+
+
+def randn(shape, seed, dtype, scale=1.0, relu=False):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    t = torch.randn(shape, generator=g, dtype=torch.float32) * scale
+    if relu:
+        t = t.abs()
+    return t.to(WL.torch_dtype(dtype))
+
+
+# ---------------------------------------------------------------------------
+# S0 / S1: patch sum and patch mean
+# ---------------------------------------------------------------------------
+REDUCE_CASES = [
+    # N  C   H   W   r  s
+    (2, 3, 8, 8, 2, 1), (3, 5, 7, 7, 2, 1), (3, 5, 7, 7, 4, 1), (2, 4, 14, 14, 2, 2), (2, 4, 14, 14, 4, 2),
+    (1, 2, 56, 56, 2, 1), (2, 3, 64, 64, 8, 1), (1, 3, 9, 5, 3, 1), (2, 2, 7, 7, 7, 1), (1, 2, 5, 6, 8, 1),
+    (4, 37, 7, 7, 2, 1), (1, 1, 1, 1, 2, 1), (2, 3, 30, 40, 4, 1), (1, 2, 160, 120, 2, 1), (1, 1, 33, 4100, 4, 1),
+    (1, 1, 12, 9000, 8, 1),     # one strip larger than the LDS staging budget
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", REDUCE_CASES)
+def test_pool_and_filter(oracle, case, dtype):
+    N, C, H, W, r, s = case
+    # a "same"-padded 3x3 layer with that stride: H_y = ceil(H / s)
+    d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = randn((N, C, H, W), 11, dtype)
+    gy = randn((N, C, Hy, Wy), 12, dtype)
+    od = odesc(oracle, d)
+    x_u = T.pool_activation(d, x.cuda())
+    gy_u = T.filter_grad(d, gy.cuda())
+    torch.cuda.synchronize()
+    assert tuple(x_u.shape) == (N, C, Hp, Wp) and tuple(gy_u.shape) == (N, C, Hp, Wp)
+    assert rel_err(x_u, oracle.pool_activation(od, to64(x))) <= TOL[dtype]
+    assert rel_err(gy_u, oracle.filter_grad(od, to64(gy))) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H,W,r,s", [(8, 8, 2, 1), (16, 16, 4, 1), (56, 56, 2, 1), (64, 64, 8, 1), (16, 16, 2, 2),
+                                     (7, 7, 2, 1), (14, 14, 4, 1)])
+def test_patch_layout_bit_exact(oracle, H, W, r, s, dtype):
+    """Integer-coded maps: all sums are exact, so patch positions, the ragged-edge
+    rule and the row-major [N, C, H_p, W_p] layout must match bit for bit.  (Ragged
+    patches here hold 1, 2, 4, 8 or 16 pixels and g_y is a multiple of r*r, so the
+    means are exact too.)"""
+    N, C = 3, 5
+    d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = WL.integer_coded((N, C, H, W), 5, dtype=dtype)
+    gy = WL.integer_coded((N, C, Hy, Wy), 6, dtype=dtype) * (r * r)
+    od = odesc(oracle, d)
+    x_u = T.pool_activation(d, x.cuda())
+    gy_u = T.filter_grad(d, gy.cuda())
+    ref_x = oracle.pool_activation(od, to64(x))
+    ref_g = oracle.filter_grad(od, to64(gy))
+    assert np.array_equal(to64(x_u), ref_x)
+    assert np.array_equal(to64(gy_u), ref_g)
+
+
+def test_r1_reductions_are_copies():
+    d = mk(2, 3, 4, 14, 14, K=3, s=2, p=1, r=1, dtype="bf16")
+    x = randn((2, 3, 14, 14), 1, "bf16").cuda()
+    gy = randn((2, 4, 7, 7), 2, "bf16").cuda()
+    assert torch.equal(T.pool_activation(d, x), x)
+    assert torch.equal(T.filter_grad(d, gy), gy)
+
+
+# ---------------------------------------------------------------------------
+# S3 / S4 from given reduced maps
+# ---------------------------------------------------------------------------
+GF_CASES = [
+    # N  Ci  Co  H   W  K  s  p  dl g   r
+    (1, 16, 16, 16, 16, 3, 1, 1, 1, 1, 2),        # config 1
+    (3, 24, 40, 12, 12, 1, 1, 0, 1, 1, 2),        # pointwise, channels not multiples of the tile
+    (2, 70, 130, 7, 7, 3, 1, 1, 1, 1, 2),         # ragged 7x7, P = 16, several tiles with tails
+    (5, 64, 96, 7, 7, 3, 1, 1, 1, 1, 4),          # P = 4
+    (2, 32, 64, 14, 14, 3, 1, 1, 1, 1, 2),        # P = 49 (odd)
+    (2, 32, 48, 14, 14, 3, 2, 1, 1, 1, 2),        # strided 14 -> 7, r_x = 4
+    (2, 16, 16, 24, 24, 3, 1, 6, 6, 1, 4),        # dilated
+    (3, 12, 18, 10, 10, 3, 1, 1, 1, 3, 2),        # grouped
+    (4, 48, 48, 12, 12, 3, 1, 1, 1, 48, 2),       # depthwise
+    (3, 40, 40, 7, 7, 3, 1, 1, 1, 40, 2),         # depthwise, ragged
+    (3, 24, 24, 14, 14, 3, 2, 1, 1, 24, 2),       # depthwise, strided
+    (2, 8, 8, 9, 9, 3, 1, 1, 1, 1, 3),            # r = 3
+    (2, 8, 12, 7, 7, 3, 1, 1, 1, 1, 7),           # one patch per plane
+    (2, 6, 6, 5, 5, 5, 1, 2, 1, 1, 8),            # r > H
+    (1, 1, 1, 4, 4, 3, 1, 1, 1, 1, 2),            # the worked 4x4 example's shape
+    (9, 200, 72, 8, 8, 1, 1, 0, 1, 1, 2),         # batch split across several slabs
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", GF_CASES)
+def test_filtered_backward_steps(oracle, case, dtype):
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, r, dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 21, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 22, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    gy = randn((N, Co, Hy, Wy), 23, dtype, scale=1e-2)
+    # reduced maps from the ORACLE, rounded once to the storage dtype, feed both sides
+    x_u = rounded(oracle.pool_activation(od, to64(x)), dtype)
+    gy_u = rounded(oracle.filter_grad(od, to64(gy)), dtype)
+    ref_gw = oracle.bwd_weight(od, to64(x_u), to64(gy_u))
+    ref_gx = oracle.bwd_input(od, to64(gy_u), to64(w))
+    ref_gxu = oracle.bwd_input(od, to64(gy_u), to64(w), reduced_out=True)
+
+    g_w = T.conv_bwd_weight(d, x_u.cuda(), gy_u.cuda())
+    g_x = T.conv_bwd_input(d, gy_u.cuda(), w.cuda())
+    g_xu = T.conv_bwd_input(d, gy_u.cuda(), w.cuda(), reduced_out=True)
+    torch.cuda.synchronize()
+    assert g_w.dtype == torch.float32
+    assert rel_err(g_w, ref_gw) <= TOL[dtype]
+    assert rel_err(g_x, ref_gx) <= TOL[dtype]
+    assert rel_err(g_xu, ref_gxu) <= TOL[dtype]
+    # structure with exactly one right answer: taps identical, patches constant, reduced == unique view
+    gw = g_w.cpu()
+    assert torch.equal(gw, gw[:, :, :1, :1].expand_as(gw))
+    rx = r * s
+    up = g_xu.repeat_interleave(rx, 2).repeat_interleave(rx, 3)[:, :, :H, :W]
+    assert torch.equal(up, g_x)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("g,s", [(1, 1), (16, 1), (1, 2), (4, 1)])
+def test_filtered_backward_bit_exact_on_integers(oracle, g, s, dtype):
+    """Channel pairing, group ranges and the patch -> pixel map with integer-coded
+    reduced maps and weights (power-of-two scale 1/s^2): every partial sum is an
+    integer below 2^24, so any summation order gives the same bits."""
+    N, Ci, Co, H, K, r = 4, 16, 16 if g != 4 else 32, 8 * s, 3, 2
+    d = mk(N, Ci, Co, H, H, K, s, 1, 1, g, r, dtype)
+    od = odesc(oracle, d)
+    _, _, Hp, Wp = B.gf_out_shape(d)
+    x_u = WL.integer_coded((N, Ci, Hp, Wp), 31, dtype=dtype)
+    gy_u = WL.integer_coded((N, Co, Hp, Wp), 32, dtype=dtype)
+    w = WL.integer_coded((Co, Ci // g, K, K), 33, lo=-2, hi=2, dtype=dtype)
+    g_w = T.conv_bwd_weight(d, x_u.cuda(), gy_u.cuda())
+    g_x = T.conv_bwd_input(d, gy_u.cuda(), w.cuda())
+    assert np.array_equal(to64(g_w), oracle.bwd_weight(od, to64(x_u), to64(gy_u)))
+    ref_gx = oracle.bwd_input(od, to64(gy_u), to64(w))
+    # fp32 holds these integers exactly; bf16 storage rounds the exact value once
+    assert np.array_equal(to64(g_x), to64(rounded(ref_gx, dtype)))
+
+
+# ---------------------------------------------------------------------------
+# S5 exact BP, and r == 1 through the filtered entries
+# ---------------------------------------------------------------------------
+EXACT_CASES = [
+    (2, 6, 8, 9, 9, 3, 1, 1, 1, 1), (2, 8, 8, 14, 14, 3, 2, 1, 1, 1), (1, 8, 8, 12, 12, 3, 1, 4, 4, 1),
+    (2, 12, 12, 10, 10, 3, 1, 1, 1, 12), (2, 8, 12, 14, 14, 3, 2, 1, 1, 4), (3, 10, 7, 6, 8, 1, 1, 0, 1, 1),
+    (1, 4, 4, 11, 11, 5, 1, 2, 1, 1), (1, 5, 6, 8, 8, 3, 1, 0, 1, 1), (1, 16, 16, 16, 16, 3, 1, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", EXACT_CASES)
+def test_exact_backward(oracle, case, dtype):
+    N, Ci, Co, H, W, K, s, p, dl, g = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, 1, dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, _, _ = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 41, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 42, dtype, scale=0.3)
+    gy = randn((N, Co, Hy, Wy), 43, dtype)
+    ref_gw, ref_gx = oracle.bwd_exact(od, to64(x), to64(w), to64(gy))
+    g_w, g_x = T.conv_bwd_exact(d.with_(r=3), x.cuda(), w.cuda(), gy.cuda())   # the exact entry ignores r
+    assert rel_err(g_w, ref_gw) <= TOL[dtype]
+    assert rel_err(g_x, ref_gx) <= TOL[dtype]
+    # r == 1 through the filtered entry points is vanilla BP (Sec. 4.2)
+    xu = T.pool_activation(d, x.cuda())
+    gyu = T.filter_grad(d, gy.cuda())
+    assert rel_err(T.conv_bwd_weight(d, xu, gyu), ref_gw) <= TOL[dtype]
+    assert rel_err(T.conv_bwd_input(d, gyu, w.cuda()), ref_gx) <= TOL[dtype]
+    only_w, none_x = T.conv_bwd_exact(d, x.cuda(), None, gy.cuda(), want_gx=False)
+    assert none_x is None and torch.equal(only_w, g_w)
+
+
+# ---------------------------------------------------------------------------
+# whole filtered backward on the benchmark configurations
+# ---------------------------------------------------------------------------
+def run_layer(d, x, w, gy):
+    xg, wg, gyg = x.cuda(), w.cuda(), gy.cuda()
+    x_u = T.pool_activation(d, xg)
+    gy_u = T.filter_grad(d, gyg)
+    g_w = T.conv_bwd_weight(d, x_u, gy_u)
+    g_x = T.conv_bwd_input(d, gy_u, wg)
+    torch.cuda.synchronize()
+    return x_u, gy_u, g_w, g_x
+
+
+def check_layer_full(oracle, cfg, layer, dtype, r, N=None):
+    """End to end on one layer: the GPU chains its own (rounded) reduced maps, the
+    oracle runs the whole path in fp64 from the same inputs."""
+    N = cfg.N if N is None else N
+    d = T.desc_for(layer, N, r, dtype)
+    od = odesc(oracle, d)
+    x, w, gy = WL.make_inputs(cfg, layer, dtype, N=N)
+    x_u, gy_u, g_w, g_x = run_layer(d, x, w, gy)
+    ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    tol = TOL[dtype]
+    assert rel_err(x_u, ref_xu) <= tol, "x_u"
+    assert rel_err(gy_u, ref_gyu) <= tol, "gy_u"
+    assert rel_err(g_w, ref_gw) <= tol, "g_w"
+    assert rel_err(g_x, ref_gx) <= tol, "g_x"
+
+
+def test_config1_with_exact(oracle):
+    cfg = WL.CONFIGS[1]
+    layer = cfg.layers[0]
+    check_layer_full(oracle, cfg, layer, "f32", 2)
+    d = T.desc_for(layer, 1, 2, "f32")
+    x, w, gy = WL.make_inputs(cfg, layer, "f32")
+    g_w, g_x = T.conv_bwd_exact(d, x.cuda(), w.cuda(), gy.cuda())
+    ref_gw, ref_gx = oracle.bwd_exact(odesc(oracle, d), to64(x), to64(w), to64(gy))
+    assert rel_err(g_w, ref_gw) <= 1e-5 and rel_err(g_x, ref_gx) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("li", [0, 1, 2])
+def test_config2_full_size(oracle, li, dtype):
+    cfg = WL.CONFIGS[2]
+    check_layer_full(oracle, cfg, cfg.layers[li], dtype, 2)
+
+
+@pytest.mark.parametrize("r", [2, 4])
+@pytest.mark.parametrize("li", [0, 1, 2])
+def test_config3_full_size(oracle, li, r):
+    cfg = WL.CONFIGS[3]
+    check_layer_full(oracle, cfg, cfg.layers[li], "bf16", r)
+
+
+@pytest.mark.parametrize("r", [2, 4, 8])
+@pytest.mark.parametrize("li", [0, 1, 3])
+def test_config4_sub_batch(oracle, li, r):
+    """Full layer shapes with a sub-batch of 2 images so the fp64 oracle stays within seconds."""
+    cfg = WL.CONFIGS[4]
+    check_layer_full(oracle, cfg, cfg.layers[li], "bf16", r, N=2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("li", [0, 2, 4, 6, 7, 9])
+def test_config5_sub_batch(oracle, li, dtype):
+    cfg = WL.CONFIGS[5]
+    check_layer_full(oracle, cfg, cfg.layers[li], dtype, 2, N=16)
+
+
+def test_config4_full_size_sampled(oracle):
+    """Config 4's largest layer at its full batch, in the launch configuration the
+    benchmark uses; the oracle evaluates sampled outputs one by one: a weight
+    gradient entry is a dot product over (n, patch) of two channel slices, and an
+    input-gradient pixel is a dot product over c_o."""
+    cfg = WL.CONFIGS[4]
+    layer, r, dtype = cfg.layers[0], 2, "bf16"
+    d = T.desc_for(layer, cfg.N, r, dtype)
+    x, w, gy = WL.make_inputs(cfg, layer, dtype)
+    x_u, gy_u, g_w, g_x = run_layer(d, x, w, gy)
+    rs = np.random.default_rng(4)
+    gw_c, gx_c = g_w.cpu(), g_x.cpu()
+    gw_max = float(gw_c.abs().max())
+    gx_max = float(gx_c.abs().float().max())
+    cos = rs.choice(layer.C_out, 6, replace=False)
+    cis = rs.choice(layer.C_in, 6, replace=False)
+    for co, ci in zip(cos, cis):
+        # slice one (c_o, c_i) pair: a 1 -> 1 channel layer seen by the oracle
+        sd = oracle.Desc(N=cfg.N, C_in=1, C_out=1, H_in=layer.H, W_in=layer.W, r=r)
+        xs, gs, ws = to64(x[:, ci:ci + 1]), to64(gy[:, co:co + 1]), to64(w[co:co + 1, ci:ci + 1])
+        ref_gw, _, _, _ = oracle.gf_backward(sd, xs, ws, gs)
+        assert abs(float(gw_c[co, ci, 0, 0]) - ref_gw[0, 0, 0, 0]) <= TOL[dtype] * gw_max
+    # input gradient of one image, a slice of input channels (needs every c_o)
+    n, c0 = 5, 1000
+    sd = oracle.Desc(N=1, C_in=8, C_out=layer.C_out, H_in=layer.H, W_in=layer.W, r=r)
+    ref = oracle.bwd_input(sd, oracle.filter_grad(sd, to64(gy[n:n + 1])), to64(w[:, c0:c0 + 8]))
+    assert np.abs(to64(gx_c[n:n + 1, c0:c0 + 8]) - ref).max() <= TOL[dtype] * gx_max
+
+
+def test_repeat_runs_are_bit_identical():
+    """No floating-point atomics anywhere: two runs must agree bit for bit."""
+    cfg = WL.CONFIGS[2]
+    for layer in cfg.layers:
+        d = T.desc_for(layer, 8, 2, "bf16")
+        x, w, gy = WL.make_inputs(cfg, layer, "bf16", N=8)
+        a = run_layer(d, x, w, gy)
+        b = run_layer(d, x, w, gy)
+        for u, v in zip(a, b):
+            assert torch.equal(u, v)
