@@ -178,19 +178,33 @@ def main():
 
     # ---- per-kernel durations with HIP events on the launch stream (cold, rotating sets) ----
     def time_stage(fn, li, reps=8):
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        s = st()
-        for k in range(nsets):
-            fn(sets[k][li], s)
-        torch.cuda.synchronize()
-        ev0.record()
-        for rep in range(reps):
+        """Average GPU time of one launch of stage `fn` on layer `li`, cold: a HIP graph holding
+        one launch per buffer set (twice over) is replayed `reps` times between two events on
+        the launch stream, so neither host launch latency nor cache reuse enters the figure."""
+        per_graph = 2 * nsets
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            s = int(side.cuda_stream)
             for k in range(nsets):
                 fn(sets[k][li], s)
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                s = int(torch.cuda.current_stream().cuda_stream)
+                for k in range(per_graph):
+                    fn(sets[k % nsets][li], s)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for rep in range(reps):
+            g.replay()
         ev1.record()
         torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) * 1e3 / (reps * nsets)   # microseconds per launch
+        return ev0.elapsed_time(ev1) * 1e3 / (reps * per_graph)   # microseconds per launch
 
     cost = [B.gf_cost_model(d) for d in descs]
     stage_bytes = {"pool_activation": "bytes_pool", "filter_grad": "bytes_filter",
@@ -225,7 +239,7 @@ def main():
     if not args.no_exact:
         ex_us = []
         for li in range(len(layers)):
-            ex_us.append(time_stage(enqueue_exact, li, reps=2))
+            ex_us.append(time_stage(enqueue_exact, li, reps=1))
         gf_us = [row["backward_us"] for row in per_layer]
         exact = {"per_layer_us": [round(u, 1) for u in ex_us],
                  "speedup_per_layer": [round(e / g, 2) for e, g in zip(ex_us, gf_us)],

@@ -34,7 +34,15 @@ __global__ __launch_bounds__(kThreads) void finalize_gw_k(const float* part, flo
   const int e = blockIdx.x * kThreads + threadIdx.x;
   if (e >= pairs) return;
   float acc = 0.f;
-  for (int z = 0; z < nz; ++z) acc += part[(long)z * pairs + e];
+  int z = 0;
+  for (; z + 8 <= nz; z += 8) {  // eight independent loads in flight, summed in index order
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = part[(long)(z + k) * pairs + e];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += v[k];
+  }
+  for (; z < nz; ++z) acc += part[(long)z * pairs + e];
   acc *= scale;
   for (int t = 0; t < KK; ++t) g_w[(long)e * KK + t] = acc;
 }
@@ -54,6 +62,39 @@ __global__ __launch_bounds__(kThreads) void dw_dot_k(const T* xu, const T* gyu, 
     const T* a = xu + (long)plane * P;
     const T* b = gyu + (long)plane * P;
     for (int p = lane; p < P; p += L) acc += to_f32(a[p]) * to_f32(b[p]);
+  }
+  for (int m = L >> 1; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (plane < planes && lane == 0) part[plane] = acc;
+}
+
+// Same with 16-byte loads (P a multiple of the vector length): L lanes per plane,
+// each lane takes vectors lane, lane + L, ... of both operands.
+template <class T>
+__global__ __launch_bounds__(kThreads) void dw_dot_vec_k(const T* xu, const T* gyu, float* part,
+                                                        int planes, int nvec, int L) {
+  constexpr int VE = Vec16<T>::N;
+  const int gid = blockIdx.x * kThreads + threadIdx.x;
+  const int plane = gid / L;
+  const int lane = gid - plane * L;
+  float acc = 0.f;
+  if (plane < planes) {
+    const uint4* a = reinterpret_cast<const uint4*>(xu + (long)plane * nvec * VE);
+    const uint4* b = reinterpret_cast<const uint4*>(gyu + (long)plane * nvec * VE);
+    for (int v = lane; v < nvec; v += 2 * L) {
+      const bool two = v + L < nvec;
+      const uint4 a0 = a[v], b0 = b[v];
+      const uint4 a1 = two ? a[v + L] : make_uint4(0, 0, 0, 0);
+      const uint4 b1 = two ? b[v + L] : make_uint4(0, 0, 0, 0);
+      float fa[VE], fb[VE];
+      Vec16<T>::unpack(a0, fa);
+      Vec16<T>::unpack(b0, fb);
+#pragma unroll
+      for (int e = 0; e < VE; ++e) acc += fa[e] * fb[e];
+      Vec16<T>::unpack(a1, fa);
+      Vec16<T>::unpack(b1, fb);
+#pragma unroll
+      for (int e = 0; e < VE; ++e) acc += fa[e] * fb[e];
+    }
   }
   for (int m = L >> 1; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
   if (plane < planes && lane == 0) part[plane] = acc;
@@ -249,9 +290,96 @@ __global__ __launch_bounds__(kThreads) void expand_k(ExpandArgs a) {
   }
 }
 
+// Fast path: rows are 16-byte multiples, r_x is a power of two that divides W.
+// One lane per (patch row, 16-byte column vector): it reads the few source values
+// the vector needs once, builds the vector, and stores it to the r_x output rows.
+// With `wdw` set the per-channel scale is the depthwise kernel sum, formed here
+// (text after Eq. 3) instead of in a launch of its own.
+struct ExpandRowsArgs {
+  const void* src;
+  void* out;
+  const float* chscale;  // per channel, or null
+  const void* wdw;       // depthwise weights [C, KK], or null
+  int KK;
+  float scalar;
+  int C, H, W, Hp, Wp;
+  int vpr;               // 16-byte vectors per output row
+  int total_items;       // planes * Hp * vpr
+  FastDiv d_vpr, d_hp, d_c;
+};
+
+template <class T, class S, int RX>
+__global__ __launch_bounds__(kThreads) void expand_rows_k(ExpandRowsArgs a) {
+  constexpr int VE = Vec16<T>::N;
+  constexpr int NS = VE >= RX ? VE / RX : 1;  // source values per output vector
+  const int t = blockIdx.x * kThreads + threadIdx.x;
+  if (t >= a.total_items) return;
+  const S* src = static_cast<const S*>(a.src);
+  T* out = static_cast<T*>(a.out);
+  const int s = (int)a.d_vpr.div((uint32_t)t);   // strip = plane * Hp + hp
+  const int v = t - s * a.vpr;
+  const int pl = (int)a.d_hp.div((uint32_t)s);
+  const int hp = s - pl * a.Hp;
+  float sc = a.scalar;
+  if (a.chscale || a.wdw) {
+    const int c = pl - (int)a.d_c.div((uint32_t)pl) * a.C;
+    if (a.wdw) {
+      const T* w = static_cast<const T*>(a.wdw) + (long)c * a.KK;
+      float ws = 0.f;
+      for (int k = 0; k < a.KK; ++k) ws += to_f32(w[k]);
+      sc *= ws;
+    } else {
+      sc *= a.chscale[c];
+    }
+  }
+  const int wp0 = VE >= RX ? v * NS : (v * VE) / RX;
+  const S* sp = src + (long)s * a.Wp + wp0;
+  float f[VE];
+#pragma unroll
+  for (int k = 0; k < NS; ++k) {
+    const float val = to_f32(sp[k]) * sc;
+#pragma unroll
+    for (int j = 0; j < VE / NS; ++j) f[k * (VE / NS) + j] = val;
+  }
+  // round once, then replicate the rounded bits
+  const uint4 vec = Vec16<T>::pack(f);
+  const int rows = min(RX, a.H - hp * RX);
+  T* dst = out + ((long)pl * a.H + (long)hp * RX) * a.W + v * VE;
+  for (int i = 0; i < rows; ++i) *reinterpret_cast<uint4*>(dst + (long)i * a.W) = vec;
+}
+
+template <class T, class S, int RX>
+hipError_t launch_expand_rows(ExpandRowsArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((expand_rows_k<T, S, RX>), dim3(cdiv(a.total_items, kThreads)), dim3(kThreads),
+                     0, st, a);
+  return hipGetLastError();
+}
+
 template <class T, class S>
 hipError_t launch_expand(const S* src, T* out, const float* chscale, float scalar, long planes,
-                         int C, int H, int W, int rx, int Hp, int Wp, hipStream_t st) {
+                         int C, int H, int W, int rx, int Hp, int Wp, hipStream_t st,
+                         const void* wdw = nullptr, int KK = 0, float* wsum_scratch = nullptr) {
+  constexpr int VEC = 16 / (int)sizeof(T);
+  const bool pow2 = rx == 2 || rx == 4 || rx == 8 || rx == 16;
+  if (pow2 && W % VEC == 0 && W % rx == 0 && planes * Hp * (W / VEC) < 2147483647L) {
+    ExpandRowsArgs e;
+    e.src = src; e.out = out; e.chscale = wdw ? nullptr : chscale; e.wdw = wdw; e.KK = KK;
+    e.scalar = scalar; e.C = C; e.H = H; e.W = W; e.Hp = Hp; e.Wp = Wp;
+    e.vpr = W / VEC;
+    e.total_items = (int)(planes * Hp * e.vpr);
+    e.d_vpr = FastDiv((uint32_t)e.vpr);
+    e.d_hp = FastDiv((uint32_t)Hp);
+    e.d_c = FastDiv((uint32_t)C);
+    if (rx == 2) return launch_expand_rows<T, S, 2>(e, st);
+    if (rx == 4) return launch_expand_rows<T, S, 4>(e, st);
+    if (rx == 8) return launch_expand_rows<T, S, 8>(e, st);
+    return launch_expand_rows<T, S, 16>(e, st);
+  }
+  if (wdw) {  // generic path wants the per-channel sums in memory
+    hipError_t err = launch_kernel_sum(wdw, wsum_scratch, C, KK, sizeof(T) == 2 ? GF_BF16 : GF_F32, st);
+    if (err != hipSuccess) return err;
+    chscale = wsum_scratch;
+  }
   ExpandArgs a;
   a.src = src;
   a.out = out;
@@ -318,6 +446,20 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
   int nz;
   if (is_depthwise(g)) {
     const int planes = g.N * g.Ci;
+    const int VE = 16 / g.b;
+    if (g.P % VE == 0) {
+      const int nvec = g.P / VE;
+      const int L = dw_lanes(cdiv(nvec, 2));
+      const int blocks = cdiv((long)planes * L, kThreads);
+      if (g.dtype == GF_BF16)
+        hipLaunchKernelGGL(dw_dot_vec_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
+                           static_cast<const bf16_t*>(x_u), static_cast<const bf16_t*>(gy_u), part,
+                           planes, nvec, L);
+      else
+        hipLaunchKernelGGL(dw_dot_vec_k<float>, dim3(blocks), dim3(kThreads), 0, st,
+                           static_cast<const float*>(x_u), static_cast<const float*>(gy_u), part,
+                           planes, nvec, L);
+    } else {
     const int L = dw_lanes(g.P);
     const int blocks = cdiv((long)planes * L, kThreads);
     if (g.dtype == GF_BF16)
@@ -328,6 +470,7 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
       hipLaunchKernelGGL(dw_dot_k<float>, dim3(blocks), dim3(kThreads), 0, st,
                          static_cast<const float*>(x_u), static_cast<const float*>(gy_u), part,
                          planes, g.P, L);
+    }
     nz = g.N;
   } else {
     WgradArgs a;
@@ -371,15 +514,18 @@ template <class T>
 static hipError_t bwd_input_t(const Geom& g, const T* gy_u, const T* w, T* g_x, bool reduced_out,
                               void* ws, hipStream_t st) {
   float* wsum = static_cast<float*>(ws);
-  hipError_t e = launch_kernel_sum(w, wsum, (long)g.Co * g.Cg, g.KK, g.dtype, st);
-  if (e != hipSuccess) return e;
   const float scale = 1.f / ((float)g.s * (float)g.s);
   const long planes = (long)g.N * g.Ci;
+  hipError_t e;
   if (is_depthwise(g)) {
     if (reduced_out)
-      return launch_expand<T, T>(gy_u, g_x, wsum, scale, planes, g.Ci, g.Hp, g.Wp, 1, g.Hp, g.Wp, st);
-    return launch_expand<T, T>(gy_u, g_x, wsum, scale, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
+      return launch_expand<T, T>(gy_u, g_x, nullptr, scale, planes, g.Ci, g.Hp, g.Wp, 1, g.Hp, g.Wp, st,
+                                 w, g.KK, wsum);
+    return launch_expand<T, T>(gy_u, g_x, nullptr, scale, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st,
+                               w, g.KK, wsum);
   }
+  e = launch_kernel_sum(w, wsum, (long)g.Co * g.Cg, g.KK, g.dtype, st);
+  if (e != hipSuccess) return e;
   DgradArgs a;
   a.gyu = gy_u;
   a.wsum = wsum;

@@ -29,8 +29,53 @@ template <class T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
 
+// 16-byte vectors of the storage type, unpacked to / packed from fp32
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
+  const bf16_t a = (bf16_t)lo, b = (bf16_t)hi;
+  return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+}
+
+template <class T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                      __float_as_uint(f[3]));
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    f[0] = bf_lo(v.x); f[1] = bf_hi(v.x); f[2] = bf_lo(v.y); f[3] = bf_hi(v.y);
+    f[4] = bf_lo(v.z); f[5] = bf_hi(v.z); f[6] = bf_lo(v.w); f[7] = bf_hi(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return make_uint4(bf_pack(f[0], f[1]), bf_pack(f[2], f[3]), bf_pack(f[4], f[5]),
+                      bf_pack(f[6], f[7]));
+  }
+};
+
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 static inline int imin_host(int a, int b) { return a < b ? a : b; }
+
+// Division of a 31-bit unsigned number by a run-time constant as multiply-high,
+// add and shift (round-up method: m = floor(2^32 (2^s - d) / d) + 1, s = ceil(log2 d)).
+struct FastDiv {
+  uint32_t m, s, d;
+  FastDiv() : m(1), s(0), d(1) {}
+  explicit FastDiv(uint32_t dd) : d(dd) {
+    s = 0;
+    while ((1ull << s) < dd) ++s;
+    m = (uint32_t)((((1ull << 32) * ((1ull << s) - dd)) / dd) + 1);
+  }
+  __device__ __forceinline__ uint32_t div(uint32_t n) const { return (__umulhi(n, m) + n) >> s; }
+};
 
 // ---- launchers; each returns the hipError_t of its launches ----------------
 

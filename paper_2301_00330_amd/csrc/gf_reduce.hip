@@ -1,9 +1,16 @@
 // Patch reduction: the gradient filter (Eq. 2, patch mean of g_y) and the
 // activation pooling (text after Eq. 5, patch sum of x).  Both are one streaming
-// read of an NCHW tensor, so the kernel is built around coalesced 16-byte loads
-// of a flat run of whole patch-row strips into LDS, from which each lane sums
-// one patch.  NCHW planes are treated as one flat stream: a block's input range
-// is contiguous in memory whatever H, W and q are (7x7 planes included).
+// read of an NCHW tensor, so everything here is about coalesced 16-byte loads.
+//
+//  * patch_reduce_rows  -- maps whose rows are 16-byte multiples and whose width
+//    is a multiple of the patch: every lane loads one 16-byte vector from each of
+//    the q rows of a patch-row strip, adds them vertically in registers and then
+//    horizontally inside the vector; no LDS, no barrier, U independent strips per
+//    lane in flight.
+//  * patch_reduce_lds   -- every other shape (7x7, 14x14, ragged widths, odd q):
+//    NCHW planes are treated as one flat stream; a block loads a contiguous run of
+//    whole strips into LDS with 16-byte loads and each lane then sums one patch.
+//  * patch_reduce_direct -- strips too large for LDS.
 #include "gf_internal.h"
 
 namespace gf {
@@ -20,25 +27,101 @@ struct ReduceArgs {
   int H, W, q, Hp, Wp;
   int total_in;      // planes * H * W
   int total_strips;  // planes * Hp
-  int spb;           // strips per block
+  int spb;           // strips per block (LDS kernel)
   int mean;
+  int ipr;           // items per row (rows kernel)
+  int total_items;   // total_strips * ipr
+  FastDiv d_hp, d_wp, d_ipr;
 };
 
-// element offset of strip s = (plane, hp): rows hp*q .. of that plane
-__device__ __forceinline__ int strip_offset(const ReduceArgs& a, int s) {
-  int pl = s / a.Hp;
-  int hp = s - pl * a.Hp;
-  return pl * a.H * a.W + hp * a.q * a.W;
+// ---------------------------------------------------------------------------
+// rows kernel: requires W % max(VE, Q) == 0 and (W * sizeof(T)) % 16 == 0
+// ---------------------------------------------------------------------------
+template <class T, int Q, int U>
+__global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
+  constexpr int VE = Vec16<T>::N;            // elements per 16-byte vector
+  constexpr int IW = VE > Q ? VE : Q;        // elements of one row an item covers
+  constexpr int VW = IW / VE;                // vectors per row per item
+  constexpr int NOUT = IW / Q;               // patches per item
+  const T* in = static_cast<const T*>(a.in);
+  T* out = static_cast<T*>(a.out);
+  uint4 v[U][Q][VW];
+  int strip[U], col[U], rows[U];
+  const int t0 = blockIdx.x * (kThreads * U) + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int t = t0 + u * kThreads;
+    strip[u] = -1;
+    if (t < a.total_items) {
+      const int s = (int)a.d_ipr.div((uint32_t)t);
+      const int c = t - s * a.ipr;
+      const int pl = (int)a.d_hp.div((uint32_t)s);
+      const int hp = s - pl * a.Hp;
+      strip[u] = s;
+      col[u] = c;
+      rows[u] = min(Q, a.H - hp * Q);
+      const T* p = in + ((long)pl * a.H + (long)hp * Q) * a.W + c * IW;
+#pragma unroll
+      for (int i = 0; i < Q; ++i)
+#pragma unroll
+        for (int k = 0; k < VW; ++k)
+          v[u][i][k] = (i < rows[u]) ? *reinterpret_cast<const uint4*>(p + (long)i * a.W + k * VE)
+                                     : make_uint4(0, 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (strip[u] < 0) continue;
+    float colsum[IW];
+#pragma unroll
+    for (int e = 0; e < IW; ++e) colsum[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < Q; ++i)
+#pragma unroll
+      for (int k = 0; k < VW; ++k) {
+        float f[VE];
+        Vec16<T>::unpack(v[u][i][k], f);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) colsum[k * VE + e] += f[e];
+      }
+    const float den = a.mean ? (float)(rows[u] * Q) : 1.f;
+    T res[NOUT];
+#pragma unroll
+    for (int o = 0; o < NOUT; ++o) {
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < Q; ++j) acc += colsum[o * Q + j];
+      res[o] = from_f32<T>(acc / den);
+    }
+    T* dst = out + (long)strip[u] * a.Wp + col[u] * NOUT;
+    if constexpr (NOUT * sizeof(T) == 8) {
+      *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(res);
+    } else if constexpr (NOUT * sizeof(T) == 4) {
+      *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(res);
+    } else {
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) dst[o] = res[o];
+    }
+  }
 }
 
+// ---------------------------------------------------------------------------
+// LDS kernel: any shape whose strip fits the staging buffer
+// ---------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int s0 = blockIdx.x * a.spb;
   const int s1 = min(s0 + a.spb, a.total_strips);
-  const int e0 = strip_offset(a, s0);
-  const int e1 = (s1 == a.total_strips) ? a.total_in : strip_offset(a, s1);
+  const int pl0 = (int)a.d_hp.div((uint32_t)s0);
+  const int hp0 = s0 - pl0 * a.Hp;
+  const int e0 = pl0 * a.H * a.W + hp0 * a.q * a.W;
+  int e1 = a.total_in;
+  if (s1 != a.total_strips) {
+    const int pl1 = (int)a.d_hp.div((uint32_t)s1);
+    e1 = pl1 * a.H * a.W + (s1 - pl1 * a.Hp) * a.q * a.W;
+  }
   const long byte0 = (long)e0 * (long)sizeof(T);
   const long byte1 = (long)e1 * (long)sizeof(T);
   const long a0 = byte0 & ~15L;  // the tensor base is 16-byte aligned
@@ -66,15 +149,16 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
   const T* lds = reinterpret_cast<const T*>(smem + (int)(byte0 - a0));  // lds[e - e0]
   T* out = static_cast<T*>(a.out);
   const int nout = (s1 - s0) * a.Wp;
+  const int HW = a.H * a.W;
   for (int lo = tid; lo < nout; lo += kThreads) {
-    const int ls = lo / a.Wp;
+    const int ls = (int)a.d_wp.div((uint32_t)lo);
     const int wp = lo - ls * a.Wp;
-    const int strip = s0 + ls;
-    const int pl = strip / a.Hp;
-    const int hp = strip - pl * a.Hp;
+    const int hq = hp0 + ls;                        // patch row counted from plane pl0
+    const int dpl = (int)a.d_hp.div((uint32_t)hq);  // planes past pl0
+    const int hp = hq - dpl * a.Hp;
     const int ch = min(a.q, a.H - hp * a.q);
     const int cw = min(a.q, a.W - wp * a.q);
-    const int base = pl * a.H * a.W + hp * a.q * a.W + wp * a.q - e0;
+    const int base = (pl0 + dpl) * HW + hp * a.q * a.W + wp * a.q - e0;
     float acc = 0.f;
     for (int i = 0; i < ch; ++i)
       for (int j = 0; j < cw; ++j) acc += to_f32(lds[base + i * a.W + j]);
@@ -105,11 +189,61 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
   }
 }
 
+template <class T, int Q>
+hipError_t launch_rows(ReduceArgs& a, hipStream_t st) {
+  constexpr int VE = Vec16<T>::N;
+  constexpr int IW = VE > Q ? VE : Q;
+  constexpr int U = (Q >= 8) ? 1 : 2;  // vectors in flight per lane: U * Q * VW
+  a.ipr = a.W / IW;
+  a.total_items = a.total_strips * a.ipr;
+  a.d_ipr = FastDiv((uint32_t)a.ipr);
+  const int blocks = cdiv(a.total_items, kThreads * U);
+  hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks), dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+template <class T>
+bool rows_ok(int W, int q) {
+  constexpr int VE = Vec16<T>::N;
+  if (q != 2 && q != 4 && q != 8) return false;
+  const int IW = VE > q ? VE : q;
+  return W % IW == 0 && (W * (int)sizeof(T)) % 16 == 0;
+}
+
+template <class T>
+hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
+  if (rows_ok<T>(a.W, a.q) && (long)a.total_strips * (a.W / 4) < 2147483647L) {
+    if (a.q == 2) return launch_rows<T, 2>(a, st);
+    if (a.q == 4) return launch_rows<T, 4>(a, st);
+    return launch_rows<T, 8>(a, st);
+  }
+  const long strip_bytes = (long)imin_host(a.q, a.H) * a.W * (long)sizeof(T);
+  if (strip_bytes + 32 > kLdsMax) {
+    a.spb = 1;
+    const long nout = (long)a.total_strips * a.Wp;
+    int blocks = (int)((nout + kThreads - 1) / kThreads);
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks), dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+  }
+  int spb = (int)((kLdsBudget - 32) / strip_bytes);
+  if (spb < 1) spb = 1;
+  // keep ~8 blocks per CU in flight when the tensor is large enough
+  const int want_blocks = 2048;
+  if (a.total_strips / spb < want_blocks) spb = a.total_strips / want_blocks;
+  if (spb < 1) spb = 1;
+  a.spb = spb;
+  const size_t lds = (size_t)spb * strip_bytes + 32;
+  const int blocks = (a.total_strips + spb - 1) / spb;
+  hipLaunchKernelGGL(patch_reduce_lds<T>, dim3(blocks), dim3(kThreads), lds, st, a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
                                bool mean, int dtype, hipStream_t st) {
-  ReduceArgs a;
+  ReduceArgs a = {};
   a.in = in;
   a.out = out;
   a.H = H;
@@ -120,33 +254,10 @@ hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, in
   a.total_in = (int)(planes * H * W);
   a.total_strips = (int)(planes * a.Hp);
   a.mean = mean ? 1 : 0;
-  const int b = dtype == GF_BF16 ? 2 : 4;
-  const long strip_bytes = (long)imin_host(q, H) * W * b;
-  if (strip_bytes + 32 > kLdsMax) {
-    a.spb = 1;
-    const long nout = (long)a.total_strips * a.Wp;
-    int blocks = (int)((nout + kThreads - 1) / kThreads);
-    if (blocks > 65536) blocks = 65536;
-    if (dtype == GF_BF16)
-      hipLaunchKernelGGL(patch_reduce_direct<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, a);
-    else
-      hipLaunchKernelGGL(patch_reduce_direct<float>, dim3(blocks), dim3(kThreads), 0, st, a);
-    return hipGetLastError();
-  }
-  int spb = (int)((kLdsBudget - 32) / strip_bytes);
-  if (spb < 1) spb = 1;
-  // keep at least ~8 blocks per CU in flight when the tensor is large enough
-  const int want_blocks = 2048;
-  if (a.total_strips / spb < want_blocks) spb = a.total_strips / want_blocks;
-  if (spb < 1) spb = 1;
-  a.spb = spb;
-  const size_t lds = (size_t)spb * strip_bytes + 32;
-  const int blocks = (a.total_strips + spb - 1) / spb;
-  if (dtype == GF_BF16)
-    hipLaunchKernelGGL(patch_reduce_lds<bf16_t>, dim3(blocks), dim3(kThreads), lds, st, a);
-  else
-    hipLaunchKernelGGL(patch_reduce_lds<float>, dim3(blocks), dim3(kThreads), lds, st, a);
-  return hipGetLastError();
+  a.d_hp = FastDiv((uint32_t)a.Hp);
+  a.d_wp = FastDiv((uint32_t)a.Wp);
+  if (dtype == GF_BF16) return launch_t<bf16_t>(a, st);
+  return launch_t<float>(a, st);
 }
 
 }  // namespace gf
