@@ -435,6 +435,7 @@ hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int
 // ---------------------------------------------------------------------------
 size_t ws_bwd_weight(const Geom& g) {
   if (is_depthwise(g)) return (size_t)g.N * g.Ci * sizeof(float);
+  if (g.g == 1) return (size_t)mfma_wgrad_splits(g, nullptr) * g.Co * g.Ci * sizeof(float);
   return (size_t)wgrad_splits(g) * g.Co * g.Cg * sizeof(float);
 }
 
@@ -472,6 +473,9 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
                          planes, g.P, L);
     }
     nz = g.N;
+  } else if (g.g == 1) {
+    hipError_t e = launch_mfma_wgrad(g, x_u, gy_u, part, &nz, st);
+    if (e != hipSuccess) return e;
   } else {
     WgradArgs a;
     a.xu = x_u;
@@ -507,6 +511,7 @@ static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 size_t ws_bwd_input(const Geom& g, bool reduced_out) {
   size_t wsum = align256((size_t)g.Co * g.Cg * sizeof(float));
   if (is_depthwise(g) || reduced_out) return wsum;
+  if (g.g == 1) return wsum + (size_t)g.N * g.Ci * g.P * g.b;
   return wsum + (size_t)g.N * g.Ci * g.P * sizeof(float);
 }
 
@@ -523,6 +528,13 @@ static hipError_t bwd_input_t(const Geom& g, const T* gy_u, const T* w, T* g_x, 
                                  w, g.KK, wsum);
     return launch_expand<T, T>(gy_u, g_x, nullptr, scale, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st,
                                w, g.KK, wsum);
+  }
+  if (g.g == 1) {  // dense: MFMA GEMM to the reduced map (storage type), then replicate
+    if (reduced_out) return launch_mfma_dgrad(g, gy_u, w, ws, g_x, st);
+    T* redt = reinterpret_cast<T*>(static_cast<char*>(ws) + align256((size_t)g.Co * g.Cg * sizeof(float)));
+    e = launch_mfma_dgrad(g, gy_u, w, ws, redt, st);
+    if (e != hipSuccess) return e;
+    return launch_expand<T, T>(redt, g_x, nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
   }
   e = launch_kernel_sum(w, wsum, (long)g.Co * g.Cg, g.KK, g.dtype, st);
   if (e != hipSuccess) return e;

@@ -97,6 +97,16 @@ size_t ws_bwd_input(const Geom& g, bool reduced_out);
 hipError_t launch_gf_bwd_input(const Geom& g, const void* gy_u, const void* w, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st);
 
+// MFMA kernels for groups == 1 (gf_mfma.hip).  The weight gradient writes nz K-slab
+// partials [nz, Co, Ci] to `part`; the input gradient writes the reduced map
+// [N, Ci, P] in the storage type to `dst`, using wsum_t ([Co, Ci], storage type)
+// for the rounded kernel sum when the kernel is larger than 1x1.
+int mfma_wgrad_splits(const Geom& g, int* chunks_per_z);
+hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, float* part,
+                             int* nz_out, hipStream_t st);
+hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
+                             hipStream_t st);
+
 // S5: exact K x K backward.
 size_t ws_exact(const Geom& g, bool want_gw, bool want_gx);
 hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, float* g_w, void* ws,

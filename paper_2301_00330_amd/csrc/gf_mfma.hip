@@ -1,0 +1,511 @@
+// Dense-channel (groups == 1) contractions of the filtered backward on the MFMA
+// matrix cores of gfx950:
+//
+//   weight gradient (Eq. 5):  g_th~[co, ci] = sum_j gy_u[co, j] * x_u[ci, j],   j = (n, patch)
+//   input gradient  (Eq. 3):  g_x~u[ci, j]  = sum_co wsum[co, ci] * gy_u[co, j]
+//
+// Both are skinny, bandwidth-bound GEMMs, so the kernels are built around
+// 128-byte coalesced row segments staged through LDS and register-prefetched one
+// K chunk ahead; the tile shapes are picked on the host for 64-wide wavefronts
+// (16x16 MFMA tiles, TM x TN of them per wave, WM x WN waves per 256-lane block).
+//
+// bf16 uses v_mfma_f32_16x16x32_bf16 (8 k-values per lane), fp32 uses
+// v_mfma_f32_16x16x4_f32 (1 k-value per lane).  In the weight gradient both
+// operands are K-contiguous in memory and go to LDS as they are.  In the input
+// gradient both are K-strided; fp32 still needs no reshuffle (one value per lane)
+// while bf16 rows are interleaved in k-pairs on the way into LDS so that a lane
+// picks up its 8 k-values with four 32-bit reads.
+#include "gf_internal.h"
+
+namespace gf {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kRowBytes = 128 + 16;  // one staged row: 128 data bytes + 16 pad (K-major tiles)
+
+template <class T> struct Mma;
+template <> struct Mma<bf16_t> {
+  static constexpr int KSTEP = 32;  // k per MFMA
+  static constexpr int BK = 64;     // k per staged chunk (128 bytes)
+  static constexpr int VE = 8;
+};
+template <> struct Mma<float> {
+  static constexpr int KSTEP = 4;
+  static constexpr int BK = 32;
+  static constexpr int VE = 4;
+};
+
+__device__ __forceinline__ f32x4 mma16(const uint4& a, const uint4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mma16(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+template <class T> __device__ __forceinline__ uint32_t bits_of(T v);
+template <> __device__ __forceinline__ uint32_t bits_of<float>(float v) { return __float_as_uint(v); }
+template <> __device__ __forceinline__ uint32_t bits_of<bf16_t>(bf16_t v) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, v);
+}
+
+// 16 bytes (VE elements) of row `base` starting at flat column j = (n, p), where a
+// row of image n starts at base + n * img_stride.  Zero beyond jtot.
+template <class T, bool VEC>
+__device__ __forceinline__ uint4 load_cols(const T* base, long img_stride, int j, int jtot, int P,
+                                           const FastDiv& d_p) {
+  constexpr int VE = Mma<T>::VE;
+  if (VEC) {
+    if (j >= jtot) return make_uint4(0, 0, 0, 0);
+    const int n = (int)d_p.div((uint32_t)j);
+    const int p = j - n * P;
+    return *reinterpret_cast<const uint4*>(base + (long)n * img_stride + p);
+  }
+  uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int e = 0; e < VE; ++e) {
+    const int jj = j + e;
+    if (jj < jtot) {
+      const int n = (int)d_p.div((uint32_t)jj);
+      const int p = jj - n * P;
+      const uint32_t b = bits_of<T>(base[(long)n * img_stride + p]);
+      if (sizeof(T) == 4) w[e & 3] = b; else w[e >> 1] |= b << ((e & 1) * 16);
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// ---------------------------------------------------------------------------
+// weight gradient: part[z, co, ci] = sum over the K chunks of slab z
+// ---------------------------------------------------------------------------
+struct WgradMfmaArgs {
+  const void* gyu;
+  const void* xu;
+  float* part;
+  int Ci, Co, P, Ktot;
+  int nchunks, chunks_per_z;
+  FastDiv d_p;
+};
+
+template <class T, int TM, int TN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
+  constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
+  constexpr int BK = Mma<T>::BK, VE = Mma<T>::VE, KSTEP = Mma<T>::KSTEP;
+  constexpr int LA = BM / 32, LB = BN / 32;  // 16-byte loads per lane and chunk
+  static_assert(WM * WN == 4 && BM % 32 == 0 && BN % 32 == 0, "tile shape");
+  __shared__ __attribute__((aligned(16))) unsigned char As[BM * kRowBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * kRowBytes];
+  const T* gyu = static_cast<const T*>(a.gyu);
+  const T* xu = static_cast<const T*>(a.xu);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int kc0 = blockIdx.z * a.chunks_per_z;
+  const int kc1 = min(kc0 + a.chunks_per_z, a.nchunks);
+
+  uint4 ra[LA], rb[LB];
+  auto fetch = [&](int kc) {
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
+      const int co = m0 + row;
+      ra[i] = co < a.Co ? load_cols<T, VEC>(gyu + (long)co * a.P, (long)a.Co * a.P, kc * BK + vi * VE,
+                                            a.Ktot, a.P, a.d_p)
+                        : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
+      const int ci = n0 + row;
+      rb[i] = ci < a.Ci ? load_cols<T, VEC>(xu + (long)ci * a.P, (long)a.Ci * a.P, kc * BK + vi * VE,
+                                            a.Ktot, a.P, a.d_p)
+                        : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int s = tid + i * kThreads;
+      *reinterpret_cast<uint4*>(As + (s >> 3) * kRowBytes + (s & 7) * 16) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int s = tid + i * kThreads;
+      *reinterpret_cast<uint4*>(Bs + (s >> 3) * kRowBytes + (s & 7) * 16) = rb[i];
+    }
+  };
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (kc0 < kc1) fetch(kc0);
+  for (int kc = kc0; kc < kc1; ++kc) {
+    stage();
+    __syncthreads();
+    if (kc + 1 < kc1) fetch(kc + 1);
+    const int r = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int ks = 0; ks < BK / KSTEP; ++ks) {
+      if constexpr (sizeof(T) == 2) {
+        uint4 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * TM + i) * 16 + r) * kRowBytes + ks * 64 + kg * 16);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          fb[j] = *reinterpret_cast<const uint4*>(Bs + ((wn * TN + j) * 16 + r) * kRowBytes + ks * 64 + kg * 16);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mma16(fa[i], fb[j], acc[i][j]);
+      } else {
+        float fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          fa[i] = *reinterpret_cast<const float*>(As + ((wm * TM + i) * 16 + r) * kRowBytes + (ks * 4 + kg) * 4);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          fb[j] = *reinterpret_cast<const float*>(Bs + ((wn * TN + j) * 16 + r) * kRowBytes + (ks * 4 + kg) * 4);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mma16(fa[i], fb[j], acc[i][j]);
+      }
+    }
+    __syncthreads();
+  }
+  // D[i = 4 * (lane / 16) + v][j = lane % 16] of every 16 x 16 tile
+  float* dst = a.part + (long)blockIdx.z * a.Co * a.Ci;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int ci = n0 + (wn * TN + j) * 16 + (lane & 15);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int co = m0 + (wm * TM + i) * 16 + 4 * (lane >> 4) + v;
+        if (co < a.Co && ci < a.Ci) dst[(long)co * a.Ci + ci] = acc[i][j][v];
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// input gradient, reduced map: dst[n, ci, p] = scale * sum_co wt[co, ci] * gy_u[n, co, p]
+// ---------------------------------------------------------------------------
+struct DgradMfmaArgs {
+  const void* gyu;
+  const void* wt;   // [Co][Ci] in the storage type: the 1x1 kernel itself or the rounded kernel sum
+  void* dst;        // [N, Ci, P] in the storage type
+  int Ci, Co, P, Jtot;
+  float scale;
+  FastDiv d_p;
+};
+
+// rows k (c_o) x columns mn, LDS tile of 32 word-rows: fp32 one k per row, bf16 a k-pair per row
+template <class T, int BMN, bool VEC, class RowPtr>
+__device__ __forceinline__ void dgrad_fetch(uint4* rg, int tid, int k0, int Ktot, RowPtr&& load_row) {
+  constexpr int VE = Mma<T>::VE;
+  constexpr int VPR = BMN / VE;                      // vectors per k row
+  constexpr int ROWS_PER_SLOT = sizeof(T) == 2 ? 2 : 1;
+  constexpr int SLOTS = 32 * VPR;                    // 32 word-rows
+  constexpr int PER = (SLOTS + kThreads - 1) / kThreads;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int s = tid + i * kThreads;
+    if (SLOTS % kThreads != 0 && s >= SLOTS) break;
+    const int wr = s / VPR, vi = s - wr * VPR;
+#pragma unroll
+    for (int q = 0; q < ROWS_PER_SLOT; ++q) {
+      const int k = k0 + wr * ROWS_PER_SLOT + q;
+      rg[i * ROWS_PER_SLOT + q] = k < Ktot ? load_row(k, vi * VE) : make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+template <class T, int BMN, int STRIDE>
+__device__ __forceinline__ void dgrad_stage(uint32_t* tile, const uint4* rg, int tid) {
+  constexpr int VE = Mma<T>::VE;
+  constexpr int VPR = BMN / VE;
+  constexpr int SLOTS = 32 * VPR;
+  constexpr int PER = (SLOTS + kThreads - 1) / kThreads;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int s = tid + i * kThreads;
+    if (SLOTS % kThreads != 0 && s >= SLOTS) break;
+    const int wr = s / VPR, vi = s - wr * VPR;
+    uint32_t* d = tile + wr * STRIDE + vi * VE;
+    if constexpr (sizeof(T) == 4) {
+      *reinterpret_cast<uint4*>(d) = rg[i];
+    } else {
+      const uint4 lo = rg[2 * i], hi = rg[2 * i + 1];  // rows k and k + 1, eight columns each
+      uint4 o0, o1;                                    // word c = (row k col c) | (row k+1 col c) << 16
+      o0.x = (lo.x & 0xffffu) | (hi.x << 16); o0.y = (lo.x >> 16) | (hi.x & 0xffff0000u);
+      o0.z = (lo.y & 0xffffu) | (hi.y << 16); o0.w = (lo.y >> 16) | (hi.y & 0xffff0000u);
+      o1.x = (lo.z & 0xffffu) | (hi.z << 16); o1.y = (lo.z >> 16) | (hi.z & 0xffff0000u);
+      o1.z = (lo.w & 0xffffu) | (hi.w << 16); o1.w = (lo.w >> 16) | (hi.w & 0xffff0000u);
+      *reinterpret_cast<uint4*>(d) = o0;
+      *reinterpret_cast<uint4*>(d + 4) = o1;
+    }
+  }
+}
+
+template <class T, int TM, int TN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
+  constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
+  constexpr int BK = Mma<T>::BK, VE = Mma<T>::VE;
+  constexpr int SA = BM + 4, SB = BN + 4;  // word strides of the two tiles (multiples of 4)
+  constexpr int RPS = sizeof(T) == 2 ? 2 : 1;
+  constexpr int PA = (32 * BM / VE + kThreads - 1) / kThreads * RPS;
+  constexpr int PB = (32 * BN / VE + kThreads - 1) / kThreads * RPS;
+  constexpr int SC = BN + 16 / (int)sizeof(T);  // element stride of the output staging tile
+  constexpr int kTileWords = 32 * (SA + SB);
+  constexpr int kOutWords = (BM * SC * (int)sizeof(T) + 3) / 4;
+  __shared__ __attribute__((aligned(16))) uint32_t smem[kTileWords > kOutWords ? kTileWords : kOutWords];
+  uint32_t* As = smem;
+  uint32_t* Bs = smem + 32 * SA;
+  const T* gyu = static_cast<const T*>(a.gyu);
+  const T* wt = static_cast<const T*>(a.wt);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int m0 = blockIdx.y * BM;  // first c_i
+  const int j0 = blockIdx.x * BN;  // first flat column (n, p)
+
+  auto load_a = [&](int k, int col) -> uint4 {  // wt[k][m0 + col ..]
+    const int ci = m0 + col;
+    if (VEC) {
+      if (ci >= a.Ci) return make_uint4(0, 0, 0, 0);
+      return *reinterpret_cast<const uint4*>(wt + (long)k * a.Ci + ci);
+    }
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < VE; ++e)
+      if (ci + e < a.Ci) {
+        const uint32_t b = bits_of<T>(wt[(long)k * a.Ci + ci + e]);
+        if (sizeof(T) == 4) w[e & 3] = b; else w[e >> 1] |= b << ((e & 1) * 16);
+      }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  };
+  auto load_b = [&](int k, int col) -> uint4 {  // gy_u[n, k, p] for flat column j0 + col
+    return load_cols<T, VEC>(gyu + (long)k * a.P, (long)a.Co * a.P, j0 + col, a.Jtot, a.P, a.d_p);
+  };
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 ra[PA], rb[PB];
+  dgrad_fetch<T, BM, VEC>(ra, tid, 0, a.Co, load_a);
+  dgrad_fetch<T, BN, VEC>(rb, tid, 0, a.Co, load_b);
+  const int r = lane & 15, kg = lane >> 4;
+  for (int k0 = 0; k0 < a.Co; k0 += BK) {
+    dgrad_stage<T, BM, SA>(As, ra, tid);
+    dgrad_stage<T, BN, SB>(Bs, rb, tid);
+    __syncthreads();
+    if (k0 + BK < a.Co) {
+      dgrad_fetch<T, BM, VEC>(ra, tid, k0 + BK, a.Co, load_a);
+      dgrad_fetch<T, BN, VEC>(rb, tid, k0 + BK, a.Co, load_b);
+    }
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {  // 32 k = 16 pair rows per MFMA
+        uint4 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const uint32_t* p = As + (ks * 16 + kg * 4) * SA + (wm * TM + i) * 16 + r;
+          fa[i] = make_uint4(p[0], p[SA], p[2 * SA], p[3 * SA]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const uint32_t* p = Bs + (ks * 16 + kg * 4) * SB + (wn * TN + j) * 16 + r;
+          fb[j] = make_uint4(p[0], p[SB], p[2 * SB], p[3 * SB]);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mma16(fa[i], fb[j], acc[i][j]);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {  // 4 k per MFMA
+        float fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = __uint_as_float(As[(ks * 4 + kg) * SA + (wm * TM + i) * 16 + r]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = __uint_as_float(Bs[(ks * 4 + kg) * SB + (wn * TN + j) * 16 + r]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mma16(fa[i], fb[j], acc[i][j]);
+      }
+    }
+    __syncthreads();
+  }
+  // stage the output tile in LDS (rounded once), then store 16-byte runs along j
+  T* Cs = reinterpret_cast<T*>(smem);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = (wm * TM + i) * 16 + 4 * (lane >> 4) + v;
+        const int col = (wn * TN + j) * 16 + (lane & 15);
+        Cs[row * SC + col] = from_f32<T>(acc[i][j][v] * a.scale);
+      }
+  __syncthreads();
+  T* dst = static_cast<T*>(a.dst);
+  constexpr int VPR = BN / VE;
+  for (int s = tid; s < BM * VPR; s += kThreads) {
+    const int row = s / VPR, vi = s - row * VPR;
+    const int ci = m0 + row, j = j0 + vi * VE;
+    if (ci >= a.Ci || j >= a.Jtot) continue;
+    if (VEC) {
+      const int n = (int)a.d_p.div((uint32_t)j);
+      const int p = j - n * a.P;
+      *reinterpret_cast<uint4*>(dst + ((long)n * a.Ci + ci) * a.P + p) =
+          *reinterpret_cast<const uint4*>(Cs + row * SC + vi * VE);
+    } else {
+      for (int e = 0; e < VE && j + e < a.Jtot; ++e) {
+        const int n = (int)a.d_p.div((uint32_t)(j + e));
+        const int p = j + e - n * a.P;
+        dst[((long)n * a.Ci + ci) * a.P + p] = Cs[row * SC + vi * VE + e];
+      }
+    }
+  }
+}
+
+// kernel sum rounded to the storage type, [Co][Ci] (text after Eq. 3)
+template <class T>
+__global__ __launch_bounds__(kThreads) void kernel_sum_t_k(const T* w, T* wsum, int pairs, int KK) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= pairs) return;
+  const T* p = w + (long)e * KK;
+  float acc = 0.f;
+  for (int t = 0; t < KK; ++t) acc += to_f32(p[t]);
+  wsum[e] = from_f32<T>(acc);
+}
+
+template <class T, int TM, int TN, int WM, int WN>
+hipError_t wgrad_launch(WgradMfmaArgs& a, int nz, bool vec, hipStream_t st) {
+  constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
+  dim3 grid(cdiv(a.Ci, BN), cdiv(a.Co, BM), nz);
+  if (vec)
+    hipLaunchKernelGGL((wgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((wgrad_mfma_k<T, TM, TN, WM, WN, false>), grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+template <class T, int TM, int TN, int WM, int WN>
+hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
+  constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
+  dim3 grid(cdiv(a.Jtot, BN), cdiv(a.Ci, BM), 1);
+  if (vec)
+    hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, false>), grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+// tile shape of the weight-gradient GEMM: 0 = 64x64, 1 = 128 (co) x 32 (ci), 2 = 32 x 128
+int wgrad_shape(const Geom& g) {
+  if (g.Ci <= 32 && g.Co > 64) return 1;
+  if (g.Co <= 32 && g.Ci > 64) return 2;
+  return 0;
+}
+
+void wgrad_tile(int shape, int* bm, int* bn) {
+  *bm = shape == 1 ? 128 : shape == 2 ? 32 : 64;
+  *bn = shape == 1 ? 32 : shape == 2 ? 128 : 64;
+}
+
+}  // namespace
+
+// K slabs of the weight-gradient GEMM: enough blocks to cover the chip, at least
+// four staged chunks per block.
+int mfma_wgrad_splits(const Geom& g, int* chunks_per_z) {
+  const int BK = g.dtype == GF_BF16 ? 64 : 32;
+  const int nchunks = cdiv((long)g.N * g.P, BK);
+  int bm, bn;
+  wgrad_tile(wgrad_shape(g), &bm, &bn);
+  const int tiles = cdiv(g.Co, bm) * cdiv(g.Ci, bn);
+  int nz = cdiv(1024, tiles);
+  if (nz > cdiv(nchunks, 4)) nz = cdiv(nchunks, 4);
+  if (nz < 1) nz = 1;
+  const int cpz = cdiv(nchunks, nz);
+  if (chunks_per_z) *chunks_per_z = cpz;
+  return cdiv(nchunks, cpz);
+}
+
+template <class T>
+static hipError_t wgrad_t(const Geom& g, const void* x_u, const void* gy_u, float* part, int* nz_out,
+                          hipStream_t st) {
+  WgradMfmaArgs a;
+  a.gyu = gy_u;
+  a.xu = x_u;
+  a.part = part;
+  a.Ci = g.Ci;
+  a.Co = g.Co;
+  a.P = g.P;
+  a.Ktot = g.N * g.P;
+  a.nchunks = cdiv(a.Ktot, Mma<T>::BK);
+  const int nz = mfma_wgrad_splits(g, &a.chunks_per_z);
+  a.d_p = FastDiv((uint32_t)g.P);
+  *nz_out = nz;
+  const bool vec = g.P % Mma<T>::VE == 0;
+  switch (wgrad_shape(g)) {
+    case 1: return wgrad_launch<T, 2, 2, 4, 1>(a, nz, vec, st);
+    case 2: return wgrad_launch<T, 2, 2, 1, 4>(a, nz, vec, st);
+    default: return wgrad_launch<T, 2, 2, 2, 2>(a, nz, vec, st);
+  }
+}
+
+hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, float* part,
+                             int* nz_out, hipStream_t st) {
+  if (g.dtype == GF_BF16) return wgrad_t<bf16_t>(g, x_u, gy_u, part, nz_out, st);
+  return wgrad_t<float>(g, x_u, gy_u, part, nz_out, st);
+}
+
+template <class T>
+static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
+                          hipStream_t st) {
+  const T* wt = static_cast<const T*>(w);
+  if (g.KK > 1) {  // S2: the kernel's spatial sum, rounded to the storage type
+    const int pairs = g.Co * g.Ci;
+    hipLaunchKernelGGL(kernel_sum_t_k<T>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st,
+                       static_cast<const T*>(w), static_cast<T*>(wsum_t), pairs, g.KK);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    wt = static_cast<const T*>(wsum_t);
+  }
+  DgradMfmaArgs a;
+  a.gyu = gy_u;
+  a.wt = wt;
+  a.dst = dst;
+  a.Ci = g.Ci;
+  a.Co = g.Co;
+  a.P = g.P;
+  a.Jtot = g.N * g.P;
+  a.scale = 1.f / ((float)g.s * (float)g.s);
+  a.d_p = FastDiv((uint32_t)g.P);
+  const bool vec = g.P % Mma<T>::VE == 0 && g.Ci % Mma<T>::VE == 0;
+  if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);
+  return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
+}
+
+hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
+                             hipStream_t st) {
+  if (g.dtype == GF_BF16) return dgrad_t<bf16_t>(g, gy_u, w, wsum_t, dst, st);
+  return dgrad_t<float>(g, gy_u, w, wsum_t, dst, st);
+}
+
+}  // namespace gf
