@@ -225,11 +225,11 @@ def main():
         row["tflops"] = round(fl / tot_us * 1e-6, 3)
         per_layer.append(row)
 
-    # the reduction kernel (patch_reduce_lds) runs 2x per layer and moves most of the bytes
+    # the reduction kernel (patch_reduce_rows) runs 2x per layer and moves most of the bytes
     red_us = [per_layer[li][k]["us"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
     red_by = [per_layer[li][k]["bytes"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
     achieved = sum(red_by) / sum(red_us) * 1e-3      # GB/s, algorithmic bytes / measured time
-    roofline = {"kernel": "patch_reduce_lds", "bound": "hbm", "achieved": round(achieved, 1),
+    roofline = {"kernel": "patch_reduce_rows", "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "avg_launch_us": round(sum(red_us) / len(red_us), 2),
                 "bytes_per_launch": sum(red_by) / len(red_by), "traffic": None}

@@ -29,22 +29,45 @@ __global__ __launch_bounds__(kThreads) void kernel_sum_k(const T* w, float* wsum
 // ---------------------------------------------------------------------------
 // finalize a two-stage reduction: g_w[pair, all taps] = scale * sum_z part[z, pair]
 // ---------------------------------------------------------------------------
+// 16 outputs per block, G lanes per output: lane zg sums slabs zg, zg + G, ... (all
+// loads in flight together), then one lane adds the G sums in index order.
+template <int G>
 __global__ __launch_bounds__(kThreads) void finalize_gw_k(const float* part, float* g_w, int pairs,
                                                          int nz, int KK, float scale) {
-  const int e = blockIdx.x * kThreads + threadIdx.x;
-  if (e >= pairs) return;
+  constexpr int OUT = kThreads / G;
+  __shared__ float red[G][OUT + 1];
+  const int o = threadIdx.x % OUT, zg = threadIdx.x / OUT;
+  const int e = blockIdx.x * OUT + o;
   float acc = 0.f;
-  int z = 0;
-  for (; z + 8 <= nz; z += 8) {  // eight independent loads in flight, summed in index order
-    float v[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = part[(long)(z + k) * pairs + e];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc += v[k];
+  if (e < pairs) {
+    int z = zg;
+    for (; z + 3 * G < nz; z += 4 * G) {
+      const float v0 = part[(long)z * pairs + e], v1 = part[(long)(z + G) * pairs + e];
+      const float v2 = part[(long)(z + 2 * G) * pairs + e], v3 = part[(long)(z + 3 * G) * pairs + e];
+      acc += v0; acc += v1; acc += v2; acc += v3;
+    }
+    for (; z < nz; z += G) acc += part[(long)z * pairs + e];
   }
-  for (; z < nz; ++z) acc += part[(long)z * pairs + e];
-  acc *= scale;
-  for (int t = 0; t < KK; ++t) g_w[(long)e * KK + t] = acc;
+  red[zg][o] = acc;
+  __syncthreads();
+  if (zg == 0 && e < pairs) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < G; ++k) s += red[k][o];
+    s *= scale;
+    for (int t = 0; t < KK; ++t) g_w[(long)e * KK + t] = s;
+  }
+}
+
+hipError_t launch_finalize(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
+                           hipStream_t st) {
+  if (nz >= 32)
+    hipLaunchKernelGGL(finalize_gw_k<16>, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
+  else if (nz >= 8)
+    hipLaunchKernelGGL(finalize_gw_k<4>, dim3(cdiv(pairs, kThreads / 4)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
+  else
+    hipLaunchKernelGGL(finalize_gw_k<1>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -498,9 +521,7 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(finalize_gw_k, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, part, g_w,
-                     pairs, nz, g.KK, scale);
-  return hipGetLastError();
+  return launch_finalize(part, g_w, pairs, nz, g.KK, scale, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -530,9 +551,10 @@ static hipError_t bwd_input_t(const Geom& g, const T* gy_u, const T* w, T* g_x, 
                                w, g.KK, wsum);
   }
   if (g.g == 1) {  // dense: MFMA GEMM to the reduced map (storage type), then replicate
-    if (reduced_out) return launch_mfma_dgrad(g, gy_u, w, ws, g_x, st);
+    if (reduced_out) return launch_mfma_dgrad(g, gy_u, w, ws, g_x, nullptr, st);
+    if (mfma_dgrad_writes_full(g)) return launch_mfma_dgrad(g, gy_u, w, ws, nullptr, g_x, st);
     T* redt = reinterpret_cast<T*>(static_cast<char*>(ws) + align256((size_t)g.Co * g.Cg * sizeof(float)));
-    e = launch_mfma_dgrad(g, gy_u, w, ws, redt, st);
+    e = launch_mfma_dgrad(g, gy_u, w, ws, redt, nullptr, st);
     if (e != hipSuccess) return e;
     return launch_expand<T, T>(redt, g_x, nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
   }

@@ -105,7 +105,9 @@ int mfma_wgrad_splits(const Geom& g, int* chunks_per_z);
 hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, float* part,
                              int* nz_out, hipStream_t st);
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
-                             hipStream_t st);
+                             void* full, hipStream_t st);
+// true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
+bool mfma_dgrad_writes_full(const Geom& g);
 
 // S5: exact K x K backward.
 size_t ws_exact(const Geom& g, bool want_gw, bool want_gx);

@@ -206,6 +206,10 @@ struct DgradMfmaArgs {
   int Ci, Co, P, Jtot;
   float scale;
   FastDiv d_p;
+  // full-resolution store (Eq. 3 broadcast): every patch value goes to its rx x rx pixels
+  void* full;       // [N, Ci, H, W], or null to write the reduced map to dst
+  int H, W, Wp, rx;
+  FastDiv d_wp;
 };
 
 // rows k (c_o) x columns mn, LDS tile of 32 word-rows: fp32 one k per row, bf16 a k-pair per row
@@ -362,6 +366,41 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
         Cs[row * SC + col] = from_f32<T>(acc[i][j][v] * a.scale);
       }
   __syncthreads();
+  if (a.full) {
+    // one 16-byte run of output pixels per step: row ci, sub-row i of the patch, pixel run q0..
+    // (host guarantees rx | VE or VE | rx, W == Wp * rx, W % VE == 0, Wp * rx % VE == 0)
+    T* out = static_cast<T*>(a.full);
+    const int rx = a.rx;
+    const int vprow = BN * rx / VE;          // vectors per (row, sub-row)
+    const int per_row = rx * vprow;
+    for (int s = tid; s < BM * per_row; s += kThreads) {
+      const int row = s / per_row;
+      const int t = s - row * per_row;
+      const int i = t / vprow, ov = t - i * vprow;
+      const int q0 = ov * VE;                // first output pixel of the run, tile-relative
+      const int col = q0 / rx;               // first patch column of the run
+      const int ci = m0 + row, j = j0 + col;
+      if (ci >= a.Ci || j >= a.Jtot) continue;
+      const int n = (int)a.d_p.div((uint32_t)j);
+      const int p = j - n * a.P;
+      const int hp = (int)a.d_wp.div((uint32_t)p);
+      const int wp = p - hp * a.Wp;
+      const int h = hp * rx + i;
+      if (h >= a.H) continue;
+      T vals[VE];
+      const T* src = Cs + row * SC + col;
+      if (rx >= VE) {
+#pragma unroll
+        for (int e = 0; e < VE; ++e) vals[e] = src[0];
+      } else {
+#pragma unroll
+        for (int e = 0; e < VE; ++e) vals[e] = src[e / rx];
+      }
+      T* d = out + (((long)n * a.Ci + ci) * a.H + h) * a.W + wp * rx + (q0 - col * rx);
+      *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);
+    }
+    return;
+  }
   T* dst = static_cast<T*>(a.dst);
   constexpr int VPR = BN / VE;
   for (int s = tid; s < BM * VPR; s += kThreads) {
@@ -476,8 +515,23 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
 }
 
 template <class T>
+static bool dgrad_full_ok(const Geom& g) {
+  constexpr int VE = Mma<T>::VE;
+  const int rx = g.rx;
+  if (rx != 2 && rx != 4 && rx != 8) return false;
+  if (g.P % VE != 0 || g.Ci % VE != 0) return false;   // vector loads of the operands
+  if (g.W != g.Wp * rx || g.W % VE != 0) return false;  // no ragged patch columns, aligned rows
+  if (rx < VE && g.Wp % (VE / rx) != 0) return false;   // a pixel run never leaves its patch row
+  return true;
+}
+
+bool mfma_dgrad_writes_full(const Geom& g) {
+  return g.dtype == GF_BF16 ? dgrad_full_ok<bf16_t>(g) : dgrad_full_ok<float>(g);
+}
+
+template <class T>
 static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
-                          hipStream_t st) {
+                          void* full, hipStream_t st) {
   const T* wt = static_cast<const T*>(w);
   if (g.KK > 1) {  // S2: the kernel's spatial sum, rounded to the storage type
     const int pairs = g.Co * g.Ci;
@@ -497,15 +551,21 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   a.Jtot = g.N * g.P;
   a.scale = 1.f / ((float)g.s * (float)g.s);
   a.d_p = FastDiv((uint32_t)g.P);
+  a.full = full;
+  a.H = g.H;
+  a.W = g.W;
+  a.Wp = g.Wp;
+  a.rx = g.rx;
+  a.d_wp = FastDiv((uint32_t)g.Wp);
   const bool vec = g.P % Mma<T>::VE == 0 && g.Ci % Mma<T>::VE == 0;
   if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);
   return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
 }
 
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
-                             hipStream_t st) {
-  if (g.dtype == GF_BF16) return dgrad_t<bf16_t>(g, gy_u, w, wsum_t, dst, st);
-  return dgrad_t<float>(g, gy_u, w, wsum_t, dst, st);
+                             void* full, hipStream_t st) {
+  if (g.dtype == GF_BF16) return dgrad_t<bf16_t>(g, gy_u, w, wsum_t, dst, full, st);
+  return dgrad_t<float>(g, gy_u, w, wsum_t, dst, full, st);
 }
 
 }  // namespace gf

@@ -140,6 +140,10 @@ GF_CASES = [
     (2, 6, 6, 5, 5, 5, 1, 2, 1, 1, 8),            # r > H
     (1, 1, 1, 4, 4, 3, 1, 1, 1, 1, 2),            # the worked 4x4 example's shape
     (9, 200, 72, 8, 8, 1, 1, 0, 1, 1, 2),         # batch split across several slabs
+    (2, 32, 24, 32, 32, 1, 1, 0, 1, 1, 8),        # r_x = 8: one patch spans whole 16-byte runs
+    (2, 16, 32, 16, 16, 3, 2, 1, 1, 1, 2),        # strided with aligned rows, r_x = 4
+    (2, 40, 24, 24, 16, 3, 1, 1, 1, 1, 4),        # H ragged (24 = 6 x 4), W aligned
+    (1, 136, 264, 16, 16, 1, 1, 0, 1, 1, 2),      # several channel tiles in both directions
 ]
 
 
