@@ -59,11 +59,12 @@ template <class T, bool VEC>
 __device__ __forceinline__ uint4 load_cols(const T* base, long img_stride, int j, int jtot, int P,
                                            const FastDiv& d_p) {
   constexpr int VE = Mma<T>::VE;
-  if (VEC) {
-    if (j >= jtot) return make_uint4(0, 0, 0, 0);
-    const int n = (int)d_p.div((uint32_t)j);
-    const int p = j - n * P;
-    return *reinterpret_cast<const uint4*>(base + (long)n * img_stride + p);
+  if (VEC) {  // unconditional load of a clamped column (keeps a lane's loads in flight together)
+    const int jc = min(j, jtot - VE);
+    const int n = (int)d_p.div((uint32_t)jc);
+    const int p = jc - n * P;
+    const uint4 v = *reinterpret_cast<const uint4*>(base + (long)n * img_stride + p);
+    return j < jtot ? v : make_uint4(0, 0, 0, 0);
   }
   uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -113,17 +114,17 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
     for (int i = 0; i < LA; ++i) {
       const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
       const int co = m0 + row;
-      ra[i] = co < a.Co ? load_cols<T, VEC>(gyu + (long)co * a.P, (long)a.Co * a.P, kc * BK + vi * VE,
-                                            a.Ktot, a.P, a.d_p)
-                        : make_uint4(0, 0, 0, 0);
+      const uint4 v = load_cols<T, VEC>(gyu + (long)min(co, a.Co - 1) * a.P, (long)a.Co * a.P,
+                                        kc * BK + vi * VE, a.Ktot, a.P, a.d_p);
+      ra[i] = co < a.Co ? v : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
       const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
       const int ci = n0 + row;
-      rb[i] = ci < a.Ci ? load_cols<T, VEC>(xu + (long)ci * a.P, (long)a.Ci * a.P, kc * BK + vi * VE,
-                                            a.Ktot, a.P, a.d_p)
-                        : make_uint4(0, 0, 0, 0);
+      const uint4 v = load_cols<T, VEC>(xu + (long)min(ci, a.Ci - 1) * a.P, (long)a.Ci * a.P,
+                                        kc * BK + vi * VE, a.Ktot, a.P, a.d_p);
+      rb[i] = ci < a.Ci ? v : make_uint4(0, 0, 0, 0);
     }
   };
   auto stage = [&]() {
@@ -228,7 +229,8 @@ __device__ __forceinline__ void dgrad_fetch(uint4* rg, int tid, int k0, int Ktot
 #pragma unroll
     for (int q = 0; q < ROWS_PER_SLOT; ++q) {
       const int k = k0 + wr * ROWS_PER_SLOT + q;
-      rg[i * ROWS_PER_SLOT + q] = k < Ktot ? load_row(k, vi * VE) : make_uint4(0, 0, 0, 0);
+      const uint4 v = load_row(min(k, Ktot - 1), vi * VE);
+      rg[i * ROWS_PER_SLOT + q] = k < Ktot ? v : make_uint4(0, 0, 0, 0);
     }
   }
 }
@@ -284,8 +286,8 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
   auto load_a = [&](int k, int col) -> uint4 {  // wt[k][m0 + col ..]
     const int ci = m0 + col;
     if (VEC) {
-      if (ci >= a.Ci) return make_uint4(0, 0, 0, 0);
-      return *reinterpret_cast<const uint4*>(wt + (long)k * a.Ci + ci);
+      const uint4 v = *reinterpret_cast<const uint4*>(wt + (long)k * a.Ci + min(ci, a.Ci - VE));
+      return ci < a.Ci ? v : make_uint4(0, 0, 0, 0);
     }
     uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll

@@ -48,25 +48,26 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
   uint4 v[U][Q][VW];
   int strip[U], col[U], rows[U];
   const int t0 = blockIdx.x * (kThreads * U) + threadIdx.x;
+  // all loads are issued unconditionally (indices clamped into the tensor) so that the
+  // U * Q * VW vectors of a lane are in flight together; invalid ones are dropped below
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int t = t0 + u * kThreads;
-    strip[u] = -1;
-    if (t < a.total_items) {
-      const int s = (int)a.d_ipr.div((uint32_t)t);
-      const int c = t - s * a.ipr;
-      const int pl = (int)a.d_hp.div((uint32_t)s);
-      const int hp = s - pl * a.Hp;
-      strip[u] = s;
-      col[u] = c;
-      rows[u] = min(Q, a.H - hp * Q);
-      const T* p = in + ((long)pl * a.H + (long)hp * Q) * a.W + c * IW;
+    const int tc = min(t, a.total_items - 1);
+    const int s = (int)a.d_ipr.div((uint32_t)tc);
+    const int c = tc - s * a.ipr;
+    const int pl = (int)a.d_hp.div((uint32_t)s);
+    const int hp = s - pl * a.Hp;
+    strip[u] = t < a.total_items ? s : -1;
+    col[u] = c;
+    rows[u] = min(Q, a.H - hp * Q);
+    const T* p = in + ((long)pl * a.H + (long)hp * Q) * a.W + c * IW;
 #pragma unroll
-      for (int i = 0; i < Q; ++i)
+    for (int i = 0; i < Q; ++i) {
+      const int ri = min(i, rows[u] - 1);
 #pragma unroll
-        for (int k = 0; k < VW; ++k)
-          v[u][i][k] = (i < rows[u]) ? *reinterpret_cast<const uint4*>(p + (long)i * a.W + k * VE)
-                                     : make_uint4(0, 0, 0, 0);
+      for (int k = 0; k < VW; ++k)
+        v[u][i][k] = *reinterpret_cast<const uint4*>(p + (long)ri * a.W + k * VE);
     }
   }
 #pragma unroll
@@ -81,8 +82,9 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
       for (int k = 0; k < VW; ++k) {
         float f[VE];
         Vec16<T>::unpack(v[u][i][k], f);
+        const bool keep = i < rows[u];  // rows past the ragged edge were clamped
 #pragma unroll
-        for (int e = 0; e < VE; ++e) colsum[k * VE + e] += f[e];
+        for (int e = 0; e < VE; ++e) colsum[k * VE + e] += keep ? f[e] : 0.f;
       }
     const float den = a.mean ? (float)(rows[u] * Q) : 1.f;
     T res[NOUT];
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
 // ---------------------------------------------------------------------------
 // LDS kernel: any shape whose strip fits the staging buffer
 // ---------------------------------------------------------------------------
-template <class T>
+template <class T, int QT>  // QT: compile-time patch size, 0 = run-time
 __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
@@ -130,13 +132,16 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
   const uint4* src = reinterpret_cast<const uint4*>(static_cast<const unsigned char*>(a.in) + a0);
   uint4* dst = reinterpret_cast<uint4*>(smem);
   for (int v = tid; v < nvec; v += 4 * kThreads) {
+    // four loads in flight per lane, no branches: past-the-end indices are clamped to the
+    // last vector, which is then simply written again with the same bytes
     uint4 rg[4];
+    int idx[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (v + k * kThreads < nvec) rg[k] = src[v + k * kThreads];
+    for (int k = 0; k < 4; ++k) idx[k] = min(v + k * kThreads, nvec - 1);
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (v + k * kThreads < nvec) dst[v + k * kThreads] = rg[k];
+    for (int k = 0; k < 4; ++k) rg[k] = src[idx[k]];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) dst[idx[k]] = rg[k];
   }
   {  // fewer than 16 trailing bytes: the range ends where the tensor ends
     const int tail0 = nvec << 4;
@@ -159,9 +164,18 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
     const int ch = min(a.q, a.H - hp * a.q);
     const int cw = min(a.q, a.W - wp * a.q);
     const int base = (pl0 + dpl) * HW + hp * a.q * a.W + wp * a.q - e0;
+    const int q = QT ? QT : a.q;
     float acc = 0.f;
-    for (int i = 0; i < ch; ++i)
-      for (int j = 0; j < cw; ++j) acc += to_f32(lds[base + i * a.W + j]);
+    // uniform q x q loop (no divergent branches): out-of-patch positions read the patch's
+    // first element and are not added
+#pragma unroll
+    for (int i = 0; i < q; ++i)
+#pragma unroll
+      for (int j = 0; j < q; ++j) {
+        const bool ok = i < ch && j < cw;
+        const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
+        acc += ok ? val : 0.f;
+      }
     if (a.mean) acc = acc / (float)(ch * cw);
     out[s0 * a.Wp + lo] = from_f32<T>(acc);
   }
@@ -235,7 +249,14 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
   a.spb = spb;
   const size_t lds = (size_t)spb * strip_bytes + 32;
   const int blocks = (a.total_strips + spb - 1) / spb;
-  hipLaunchKernelGGL(patch_reduce_lds<T>, dim3(blocks), dim3(kThreads), lds, st, a);
+  if (a.q == 2)
+    hipLaunchKernelGGL((patch_reduce_lds<T, 2>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else if (a.q == 4)
+    hipLaunchKernelGGL((patch_reduce_lds<T, 4>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else if (a.q == 8)
+    hipLaunchKernelGGL((patch_reduce_lds<T, 8>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else
+    hipLaunchKernelGGL((patch_reduce_lds<T, 0>), dim3(blocks), dim3(kThreads), lds, st, a);
   return hipGetLastError();
 }
 
