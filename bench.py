@@ -65,11 +65,13 @@ class LayerBufs:
         self.ws_w = torch.empty(max(self.ws_w_bytes, 256), dtype=torch.uint8, device="cuda")
         self.ws_i = torch.empty(max(self.ws_i_bytes, 256), dtype=torch.uint8, device="cuda")
         self.ws_e = torch.empty(max(self.ws_e_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.ws_f_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED)
+        self.ws_f = torch.empty(max(self.ws_f_bytes, 256), dtype=torch.uint8, device="cuda")
         self.e_w = None
         self.e_x = None
 
     def nbytes(self):
-        ts = [self.x, self.w, self.gy, self.x_u, self.gy_u, self.g_w, self.g_x, self.ws_w, self.ws_i]
+        ts = [self.x, self.w, self.gy, self.x_u, self.gy_u, self.g_w, self.g_x, self.ws_w, self.ws_i, self.ws_f]
         return sum(t.numel() * t.element_size() for t in ts)
 
 
@@ -115,6 +117,9 @@ def main():
     def enqueue_bww(lb, s): B.gf_conv_bwd_weight(lb.d, P(lb.x_u), P(lb.gy_u), P(lb.g_w), P(lb.ws_w), lb.ws_w.numel(), s)
     def enqueue_bwi(lb, s): B.gf_conv_bwd_input(lb.d, P(lb.gy_u), P(lb.w), P(lb.g_x), False, P(lb.ws_i), lb.ws_i.numel(), s)
 
+    def enqueue_fused(lb, s):   # filter + weight gradient + input gradient in one call
+        B.gf_conv_bwd_filtered(lb.d, P(lb.gy), P(lb.x_u), P(lb.w), 0, P(lb.g_w), P(lb.g_x), P(lb.ws_f), lb.ws_f.numel(), s)
+
     def enqueue_exact(lb, s):
         if lb.e_w is None:
             lb.e_w = torch.empty_like(lb.g_w)
@@ -127,8 +132,8 @@ def main():
     def step(bufset):
         s = st()
         for lb in bufset:
-            for _, fn in STAGES:
-                fn(lb, s)
+            enqueue_pool(lb, s)      # forward-time S0
+            enqueue_fused(lb, s)     # S1 + S2 + S3 + S4
 
     # ---- warm-up (eager), then optional graph capture of one step per buffer set ----
     for i in range(max(args.warmup, 1)):
@@ -220,7 +225,11 @@ def main():
             if name != "pool_activation":
                 tot_us += us
         fl = cost[li]["flops_bwd_weight"] + cost[li]["flops_bwd_input"]
-        row["backward_us"] = round(tot_us, 2)           # S1 + S2 + S3 + S4 (pooling is forward-time)
+        row["separate_calls_us"] = round(tot_us, 2)     # gf_filter_grad + gf_conv_bwd_weight + gf_conv_bwd_input
+        tot_us = time_stage(enqueue_fused, li)
+        row["backward_us"] = round(tot_us, 2)           # S1 + S2 + S3 + S4 in one call (pooling is forward-time)
+        by = cost[li]["bytes_filter"] + cost[li]["bytes_bwd_weight"] + cost[li]["bytes_bwd_input"]
+        row["backward_GBps"] = round(by / tot_us * 1e-3, 1)
         row["images_per_s"] = round(N / (tot_us * 1e-6), 1)
         row["tflops"] = round(fl / tot_us * 1e-6, 3)
         per_layer.append(row)
@@ -297,7 +306,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"cfg{cfg.cfg_id}: {cfg.name}, N={N}, r={r}, "
                                + " + ".join(L.name for L in layers),
-                   "step": "pool_activation + filter_grad + kernel_sum + bwd_weight + bwd_input for every layer",
+                   "step": "gf_pool_activation + gf_conv_bwd_filtered (filter, kernel sum, weight and input gradient) for every layer",
                    "launch": "eager" if graphs is None else "hip-graph replay", "buffer_sets": nsets,
                    "cache": "cold (rotating sets)"},
         "roofline": roofline,

@@ -69,7 +69,8 @@ typedef enum gf_dtype { GF_F32 = 0, GF_BF16 = 1 } gf_dtype;
 typedef enum gf_op {
   GF_OP_BWD_WEIGHT = 0,
   GF_OP_BWD_INPUT = 1,
-  GF_OP_BWD_EXACT = 2
+  GF_OP_BWD_EXACT = 2,
+  GF_OP_BWD_FILTERED = 3
 } gf_op;
 
 /* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
@@ -133,6 +134,18 @@ gf_status gf_conv_bwd_weight(const gf_conv_desc* desc, const void* x_u, const vo
  * only the one value per patch is written ([N, C_in, H_p, W_p]). */
 gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const void* w, void* g_x,
                             int reduced_out, void* ws, size_t ws_bytes, void* stream);
+
+/* The whole backward of one layer under gradient filtering in one call (lower half
+ * of Fig. 2(a)): the gradient filter on g_y (Eq. 2), then the weight gradient
+ * (Eq. 5) from the stored x_u and the input gradient (Eq. 3) from w.  Same results
+ * as gf_filter_grad + gf_conv_bwd_weight + gf_conv_bwd_input: g_x and gy_u bit for
+ * bit, g_w up to the order of the fp32 partial sums.  Where the layer shape allows
+ * (depthwise, stride 1) it is a single pass over g_y.  gy_u may be NULL if the
+ * caller does not want the filtered gradient itself.  With r == 1, x_u is x and
+ * the call is vanilla back-propagation. */
+gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const void* x_u,
+                               const void* w, void* gy_u, float* g_w, void* g_x, void* ws,
+                               size_t ws_bytes, void* stream);
 
 /* Vanilla back-propagation of the layer (Sec. 3.1): g_w = g_y (F) x and
  * g_x = g_y (*) rot180(w), zero padding, with stride, dilation and groups.

@@ -49,8 +49,32 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 static gf_status dev(hipError_t e) { return e == hipSuccess ? GF_OK : GF_ERR_DEVICE; }
 
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// layout of the fused call's workspace: [gy_u when the caller passes none][weight ws][input ws]
+static size_t ws_filtered(const Geom& g, bool own_gyu, size_t* off_w, size_t* off_i) {
+  if (g.r == 1) {
+    if (off_w) *off_w = 0;
+    if (off_i) *off_i = 0;
+    return ws_exact(g, true, true);
+  }
+  int nz = 0;
+  if (dw_fused_ok(g, &nz)) {
+    if (off_w) *off_w = 0;
+    if (off_i) *off_i = 0;
+    return (size_t)nz * g.Ci * sizeof(float);
+  }
+  size_t o = own_gyu ? align256((size_t)g.N * g.Co * g.P * g.b) : 0;
+  if (off_w) *off_w = o;
+  o += align256(ws_bwd_weight(g));
+  if (off_i) *off_i = o;
+  return o + ws_bwd_input(g, false);
+}
+
 static size_t ws_need(const Geom& g, int op, bool reduced_out) {
   switch (op) {
+    case GF_OP_BWD_FILTERED:
+      return ws_filtered(g, true, nullptr, nullptr);
     case GF_OP_BWD_WEIGHT:
       return g.r == 1 ? ws_exact(g, true, false) : ws_bwd_weight(g);
     case GF_OP_BWD_INPUT:
@@ -101,7 +125,8 @@ gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int
 }
 
 gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
-  if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT)
+  if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT &&
+      op != GF_OP_BWD_FILTERED)
     return GF_ERR_BAD_DESC;
   if (!desc) return GF_ERR_NULL;
   gf_conv_desc d1;
@@ -170,6 +195,47 @@ gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const vo
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (g.r == 1) return dev(launch_exact_dgrad(g, w, gy_u, g_x, ws, st));
   return dev(launch_gf_bwd_input(g, gy_u, w, g_x, reduced_out != 0, ws, st));
+}
+
+gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const void* x_u,
+                               const void* w, void* gy_u, float* g_w, void* g_x, void* ws,
+                               size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!g_y || !x_u || !w || !g_w || !g_x) return GF_ERR_NULL;
+  if (!aligned16(g_y) || !aligned16(x_u) || !aligned16(w) || !aligned16(gy_u) || !aligned16(g_w) ||
+      !aligned16(g_x))
+    return GF_ERR_UNSUPPORTED;
+  size_t off_w = 0, off_i = 0;
+  const size_t need = ws_filtered(g, gy_u == nullptr, &off_w, &off_i);
+  rc = check_ws(need, ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* wsb = static_cast<char*>(ws);
+  if (g.r == 1) {  // vanilla BP: x_u is x, the filtered gradient is g_y itself
+    if (gy_u) {
+      rc = dev(hipMemcpyAsync(gy_u, g_y, (size_t)g.N * g.Co * g.Hy * g.Wy * g.b,
+                              hipMemcpyDeviceToDevice, st));
+      if (rc) return rc;
+    }
+    rc = dev(launch_exact_wgrad(g, x_u, g_y, g_w, ws, st));
+    if (rc) return rc;
+    return dev(launch_exact_dgrad(g, w, g_y, g_x, ws, st));
+  }
+  int nz = 0;
+  if (dw_fused_ok(g, &nz)) {
+    float* part = static_cast<float*>(ws);
+    rc = dev(launch_dw_fused(g, g_y, x_u, w, gy_u, g_x, part, st));
+    if (rc) return rc;
+    return dev(launch_finalize(part, g_w, g.Ci, nz, g.KK, 1.f / ((float)g.s * (float)g.s), st));
+  }
+  void* gyu = gy_u ? gy_u : static_cast<void*>(wsb);
+  rc = dev(launch_patch_reduce(g_y, gyu, (long)g.N * g.Co, g.Hy, g.Wy, g.r, true, g.dtype, st));
+  if (rc) return rc;
+  rc = dev(launch_gf_bwd_weight(g, x_u, gyu, g_w, wsb + off_w, st));
+  if (rc) return rc;
+  return dev(launch_gf_bwd_input(g, gyu, w, g_x, false, wsb + off_i, st));
 }
 
 gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void* w,

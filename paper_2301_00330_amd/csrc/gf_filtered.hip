@@ -20,10 +20,7 @@ template <class T>
 __global__ __launch_bounds__(kThreads) void kernel_sum_k(const T* w, float* wsum, int pairs, int KK) {
   const int e = blockIdx.x * kThreads + threadIdx.x;
   if (e >= pairs) return;
-  const T* p = w + (long)e * KK;
-  float acc = 0.f;
-  for (int t = 0; t < KK; ++t) acc += to_f32(p[t]);
-  wsum[e] = acc;
+  wsum[e] = kernel_sum_of(w, e, KK);
 }
 
 // ---------------------------------------------------------------------------
@@ -59,8 +56,8 @@ __global__ __launch_bounds__(kThreads) void finalize_gw_k(const float* part, flo
   }
 }
 
-hipError_t launch_finalize(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
-                           hipStream_t st) {
+hipError_t launch_finalize_impl(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
+                                hipStream_t st) {
   if (nz >= 32)
     hipLaunchKernelGGL(finalize_gw_k<16>, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
   else if (nz >= 8)
@@ -347,10 +344,7 @@ __global__ __launch_bounds__(kThreads) void expand_rows_k(ExpandRowsArgs a) {
   if (a.chscale || a.wdw) {
     const int c = pl - (int)a.d_c.div((uint32_t)pl) * a.C;
     if (a.wdw) {
-      const T* w = static_cast<const T*>(a.wdw) + (long)c * a.KK;
-      float ws = 0.f;
-      for (int k = 0; k < a.KK; ++k) ws += to_f32(w[k]);
-      sc *= ws;
+      sc *= kernel_sum_of(static_cast<const T*>(a.wdw), c, a.KK);
     } else {
       sc *= a.chscale[c];
     }
@@ -441,6 +435,11 @@ int wgrad_splits(const Geom& g) {
 
 }  // namespace
 
+hipError_t launch_finalize(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
+                           hipStream_t st) {
+  return launch_finalize_impl(part, g_w, pairs, nz, KK, scale, st);
+}
+
 hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int dtype,
                              hipStream_t st) {
   const int blocks = cdiv(pairs, kThreads);
@@ -521,7 +520,7 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_finalize(part, g_w, pairs, nz, g.KK, scale, st);
+  return launch_finalize_impl(part, g_w, pairs, nz, g.KK, scale, st);
 }
 
 // ---------------------------------------------------------------------------

@@ -1,0 +1,349 @@
+// One launch for the whole filtered backward of a depthwise layer (stride 1):
+// gradient filter (Eq. 2), weight gradient (Eq. 5) and input gradient (Eq. 3).
+// g_y is read once; the patch means are rounded to the storage type exactly as the
+// stand-alone filter stores them, multiplied with x_u for the weight-gradient
+// partial, scaled by the kernel sum (text after Eq. 3, formed in the kernel) and
+// written back over the same pixel positions as g_x.  Two variants mirror the two
+// patch-reduction kernels: register rows for 16-byte-aligned maps, LDS-staged
+// flat planes for small or ragged maps.
+#include "gf_internal.h"
+
+namespace gf {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kLdsBudget = 40 * 1024;
+
+struct DwFusedArgs {
+  const void* gy;
+  const void* xu;
+  const void* w;
+  void* gyu;    // nullable
+  void* gx;
+  float* part;  // [N * cpp, C] partial dot products
+  int C, H, W, Hp, Wp, P, KK, q;
+  int planes;
+  float scale;
+  // rows variant
+  int ipr, ipp, cpp;  // items per row / per plane, chunks per plane
+  FastDiv d_ipr, d_cpp, d_c;
+  // LDS variant
+  int ppb;            // planes per block
+  FastDiv d_wp, d_p;
+};
+
+// fixed-order block sum of one float per lane; result valid in lane 0 of the block
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float s = 0.f;
+  if (threadIdx.x == 0)
+    for (int k = 0; k < kThreads / 64; ++k) s += red[k];
+  __syncthreads();
+  return s;
+}
+
+// ---------------------------------------------------------------------------
+// rows variant: W % max(VE, Q) == 0, rows 16-byte multiples, stride 1
+// block = (U consecutive planes, one chunk of 256 items); lane u-th item belongs to plane u
+// ---------------------------------------------------------------------------
+template <class T, int Q, int U>
+__global__ __launch_bounds__(kThreads) void dw_fused_rows_k(DwFusedArgs a) {
+  constexpr int VE = Vec16<T>::N;
+  constexpr int IW = VE > Q ? VE : Q;
+  constexpr int VW = IW / VE;
+  constexpr int NOUT = IW / Q;
+  __shared__ float red[kThreads / 64];
+  const T* gy = static_cast<const T*>(a.gy);
+  const T* xu = static_cast<const T*>(a.xu);
+  const T* w = static_cast<const T*>(a.w);
+  T* gx = static_cast<T*>(a.gx);
+  T* gyu = static_cast<T*>(a.gyu);
+  const int pg = (int)a.d_cpp.div(blockIdx.x);
+  const int chunk = blockIdx.x - pg * a.cpp;
+  const int item = chunk * kThreads + threadIdx.x;
+  const bool item_ok = item < a.ipp;
+  const int itc = min(item, a.ipp - 1);
+  const int hp = (int)a.d_ipr.div((uint32_t)itc);
+  const int col = itc - hp * a.ipr;
+  const int rows = min(Q, a.H - hp * Q);
+
+  uint4 v[U][Q][VW];
+  T xv[U][NOUT];
+  float sc[U];
+  int plane[U];
+  // kernel sums first: their loads retire before the wide ones issued after them
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    plane[u] = pg * U + u;
+    const int pc = min(plane[u], a.planes - 1);
+    const int c = pc - (int)a.d_c.div((uint32_t)pc) * a.C;
+    sc[u] = kernel_sum_of(w, c, a.KK) * a.scale;
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int pc = min(plane[u], a.planes - 1);
+    const T* p = gy + ((long)pc * a.H + (long)hp * Q) * a.W + col * IW;
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      const int ri = min(i, rows - 1);
+#pragma unroll
+      for (int k = 0; k < VW; ++k)
+        v[u][i][k] = *reinterpret_cast<const uint4*>(p + (long)ri * a.W + k * VE);
+    }
+    const T* xp = xu + (long)pc * a.P + hp * a.Wp + col * NOUT;
+#pragma unroll
+    for (int o = 0; o < NOUT; ++o) xv[u][o] = xp[o];
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const bool ok = item_ok && plane[u] < a.planes;
+    float colsum[IW];
+#pragma unroll
+    for (int e = 0; e < IW; ++e) colsum[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < Q; ++i)
+#pragma unroll
+      for (int k = 0; k < VW; ++k) {
+        float f[VE];
+        Vec16<T>::unpack(v[u][i][k], f);
+        const bool keep = i < rows;
+#pragma unroll
+        for (int e = 0; e < VE; ++e) colsum[k * VE + e] += keep ? f[e] : 0.f;
+      }
+    const float den = (float)(rows * Q);
+    float dot = 0.f;
+    float outv[IW];
+    T means[NOUT];
+#pragma unroll
+    for (int o = 0; o < NOUT; ++o) {
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < Q; ++j) acc += colsum[o * Q + j];
+      means[o] = from_f32<T>(acc / den);           // the value the filter stores
+      const float m = to_f32(means[o]);
+      dot += m * to_f32(xv[u][o]);
+      const float g = to_f32(from_f32<T>(m * sc[u]));  // rounded once, then replicated
+#pragma unroll
+      for (int j = 0; j < Q; ++j) outv[o * Q + j] = g;
+    }
+    if (!ok) dot = 0.f;
+    if (ok) {
+      if (gyu) {
+        T* dst = gyu + (long)plane[u] * a.P + hp * a.Wp + col * NOUT;
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o) dst[o] = means[o];
+      }
+      T* dst = gx + ((long)plane[u] * a.H + (long)hp * Q) * a.W + col * IW;
+#pragma unroll
+      for (int k = 0; k < VW; ++k) {
+        const uint4 vec = Vec16<T>::pack(outv + k * VE);
+        for (int i = 0; i < rows; ++i) *reinterpret_cast<uint4*>(dst + (long)i * a.W + k * VE) = vec;
+      }
+    }
+    const float s = block_sum(dot, red);
+    if (threadIdx.x == 0 && plane[u] < a.planes) {
+      const int n = (int)a.d_c.div((uint32_t)plane[u]);
+      const int c = plane[u] - n * a.C;
+      a.part[((long)n * a.cpp + chunk) * a.C + c] = s;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// LDS variant: any map whose planes fit the staging buffer, stride 1.
+// A block owns ppb whole planes: the flat run of g_y is loaded into LDS, every lane
+// reduces one patch and overwrites that patch in LDS with the input-gradient value,
+// the run is then stored to g_x with the same coalesced vectors.
+// ---------------------------------------------------------------------------
+template <class T, int QT>
+__global__ __launch_bounds__(kThreads) void dw_fused_lds_k(DwFusedArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int HW = a.H * a.W;
+  const int pl0 = blockIdx.x * a.ppb;
+  const int np = min(a.ppb, a.planes - pl0);
+  const long byte0 = (long)pl0 * HW * (long)sizeof(T);
+  const long byte1 = byte0 + (long)np * HW * (long)sizeof(T);
+  const long a0 = byte0 & ~15L;
+  const int span = (int)(byte1 - a0);
+  const int nvec = span >> 4;
+  const int shift = (int)(byte0 - a0);
+  // layout: [run bytes, 16-aligned][prods: ppb * P floats][sc: ppb floats]
+  const int run_bytes = ((a.ppb * HW * (int)sizeof(T) + 32) + 15) & ~15;
+  float* prods = reinterpret_cast<float*>(smem + run_bytes);
+  float* scs = prods + a.ppb * a.P;
+  const uint4* src = reinterpret_cast<const uint4*>(static_cast<const unsigned char*>(a.gy) + a0);
+  uint4* lds4 = reinterpret_cast<uint4*>(smem);
+  for (int v = tid; v < nvec; v += 4 * kThreads) {
+    uint4 rg[4];
+    int idx[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) idx[k] = min(v + k * kThreads, nvec - 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) rg[k] = src[idx[k]];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) lds4[idx[k]] = rg[k];
+  }
+  {
+    const int tail0 = nvec << 4;
+    const int ntail = (span - tail0) / (int)sizeof(T);
+    if (tid < ntail)
+      reinterpret_cast<T*>(smem + tail0)[tid] =
+          reinterpret_cast<const T*>(reinterpret_cast<const unsigned char*>(src) + tail0)[tid];
+  }
+  if (tid < np) {
+    const int pl = pl0 + tid;
+    const int c = pl - (int)a.d_c.div((uint32_t)pl) * a.C;
+    scs[tid] = kernel_sum_of(static_cast<const T*>(a.w), c, a.KK) * a.scale;
+  }
+  __syncthreads();
+  T* lds = reinterpret_cast<T*>(smem + shift);  // lds[e], e relative to the first plane
+  const T* xu = static_cast<const T*>(a.xu) + (long)pl0 * a.P;
+  T* gyu = a.gyu ? static_cast<T*>(a.gyu) + (long)pl0 * a.P : nullptr;
+  const int nout = np * a.P;
+  const int q = QT ? QT : a.q;
+  for (int lo = tid; lo < nout; lo += kThreads) {
+    const int lp = (int)a.d_p.div((uint32_t)lo);  // local plane
+    const int pp = lo - lp * a.P;
+    const int hp = (int)a.d_wp.div((uint32_t)pp);
+    const int wp = pp - hp * a.Wp;
+    const int ch = min(q, a.H - hp * q);
+    const int cw = min(q, a.W - wp * q);
+    const int base = lp * HW + hp * q * a.W + wp * q;
+    const float xval = to_f32(xu[lo]);
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < q; ++i)
+#pragma unroll
+      for (int j = 0; j < q; ++j) {
+        const bool ok = i < ch && j < cw;
+        const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
+        acc += ok ? val : 0.f;
+      }
+    const T mean = from_f32<T>(acc / (float)(ch * cw));
+    const float m = to_f32(mean);
+    if (gyu) gyu[lo] = mean;
+    prods[lo] = m * xval;
+    const T g = from_f32<T>(m * scs[lp]);
+#pragma unroll
+    for (int i = 0; i < q; ++i)
+#pragma unroll
+      for (int j = 0; j < q; ++j)
+        if (i < ch && j < cw) lds[base + i * a.W + j] = g;
+  }
+  __syncthreads();
+  // store the run: whole vectors strictly inside [byte0, byte1), head and tail by element
+  T* out = static_cast<T*>(a.gx);
+  unsigned char* dstb = static_cast<unsigned char*>(a.gx) + a0;
+  const int v0 = shift ? 1 : 0;  // the first vector is shared with the previous block's planes
+  for (int v = tid + v0; v < nvec; v += kThreads)
+    *reinterpret_cast<uint4*>(dstb + ((long)v << 4)) = lds4[v];
+  if (shift) {
+    const int nhead = (16 - shift) / (int)sizeof(T);  // elements of this block in vector 0
+    if (tid < nhead && tid < np * HW) out[(long)pl0 * HW + tid] = lds[tid];
+  }
+  {
+    const int tail0 = nvec << 4;
+    const int ntail = (span - tail0) / (int)sizeof(T);
+    const int efirst = (tail0 - shift) / (int)sizeof(T);
+    if (tid < ntail && efirst + tid >= 0) out[(long)pl0 * HW + efirst + tid] = lds[efirst + tid];
+  }
+  // per-plane dot product in fixed order
+  if (tid < np) {
+    float s = 0.f;
+    const float* pr = prods + tid * a.P;
+    for (int k = 0; k < a.P; ++k) s += pr[k];
+    a.part[pl0 + tid] = s;
+  }
+}
+
+template <class T>
+bool rows_variant_ok(const Geom& g) {
+  constexpr int VE = Vec16<T>::N;
+  const int q = g.r;
+  if (q != 2 && q != 4 && q != 8) return false;
+  const int IW = VE > q ? VE : q;
+  return g.W % IW == 0 && (g.W * (int)sizeof(T)) % 16 == 0;
+}
+
+template <class T>
+int lds_planes_per_block(const Geom& g) {
+  const long per_plane = (long)g.H * g.W * sizeof(T) + (long)g.P * 4 + 4;
+  long ppb = (kLdsBudget - 64) / per_plane;
+  const long planes = (long)g.N * g.Ci;
+  if (ppb > planes / 1024) ppb = planes / 1024;  // keep ~4 blocks per CU when the tensor allows
+  if (ppb > kThreads) ppb = kThreads;
+  const long fit = (64 * 1024 - 64) / per_plane;
+  if (ppb < 1) ppb = fit >= 1 ? 1 : 0;
+  return (int)ppb;
+}
+
+}  // namespace
+
+// shapes the fused depthwise launch handles; *nz = number of partial slabs per channel
+bool dw_fused_ok(const Geom& g, int* nz) {
+  if (!(g.Cg == 1 && g.Og == 1) || g.s != 1 || g.r < 2) return false;
+  if (g.Hy != g.H || g.Wy != g.W) return false;
+  const bool rows = g.dtype == GF_BF16 ? rows_variant_ok<bf16_t>(g) : rows_variant_ok<float>(g);
+  if (rows) {
+    const int VE = 16 / g.b;
+    const int IW = VE > g.r ? VE : g.r;
+    const int ipp = g.Hp * (g.W / IW);
+    if (nz) *nz = g.N * cdiv(ipp, kThreads);
+    return true;
+  }
+  const int ppb = g.dtype == GF_BF16 ? lds_planes_per_block<bf16_t>(g) : lds_planes_per_block<float>(g);
+  if (ppb < 1) return false;
+  if (nz) *nz = g.N;
+  return true;
+}
+
+template <class T>
+static hipError_t dw_fused_t(const Geom& g, const void* g_y, const void* x_u, const void* w, void* gy_u,
+                             void* g_x, float* part, hipStream_t st) {
+  DwFusedArgs a = {};
+  a.gy = g_y; a.xu = x_u; a.w = w; a.gyu = gy_u; a.gx = g_x; a.part = part;
+  a.C = g.Ci; a.H = g.H; a.W = g.W; a.Hp = g.Hp; a.Wp = g.Wp; a.P = g.P; a.KK = g.KK; a.q = g.r;
+  a.planes = g.N * g.Ci;
+  a.scale = 1.f;  // stride 1
+  a.d_c = FastDiv((uint32_t)g.Ci);
+  if (rows_variant_ok<T>(g)) {
+    constexpr int VE = Vec16<T>::N;
+    const int IW = VE > g.r ? VE : g.r;
+    a.ipr = g.W / IW;
+    a.ipp = g.Hp * a.ipr;
+    a.cpp = cdiv(a.ipp, kThreads);
+    a.d_ipr = FastDiv((uint32_t)a.ipr);
+    a.d_cpp = FastDiv((uint32_t)a.cpp);
+    if (g.r == 8) {
+      hipLaunchKernelGGL((dw_fused_rows_k<T, 8, 1>), dim3(a.planes * a.cpp), dim3(kThreads), 0, st, a);
+    } else {
+      const int blocks = cdiv(a.planes, 2) * a.cpp;
+      if (g.r == 2) hipLaunchKernelGGL((dw_fused_rows_k<T, 2, 2>), dim3(blocks), dim3(kThreads), 0, st, a);
+      else hipLaunchKernelGGL((dw_fused_rows_k<T, 4, 2>), dim3(blocks), dim3(kThreads), 0, st, a);
+    }
+    return hipGetLastError();
+  }
+  a.ppb = lds_planes_per_block<T>(g);
+  a.d_wp = FastDiv((uint32_t)g.Wp);
+  a.d_p = FastDiv((uint32_t)g.P);
+  const int run_bytes = ((a.ppb * g.H * g.W * (int)sizeof(T) + 32) + 15) & ~15;
+  const size_t lds = (size_t)run_bytes + (size_t)a.ppb * g.P * 4 + (size_t)a.ppb * 4;
+  const int blocks = cdiv(a.planes, a.ppb);
+  if (g.r == 2) hipLaunchKernelGGL((dw_fused_lds_k<T, 2>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else if (g.r == 4) hipLaunchKernelGGL((dw_fused_lds_k<T, 4>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else hipLaunchKernelGGL((dw_fused_lds_k<T, 0>), dim3(blocks), dim3(kThreads), lds, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_fused(const Geom& g, const void* g_y, const void* x_u, const void* w, void* gy_u,
+                           void* g_x, float* part, hipStream_t st) {
+  if (g.dtype == GF_BF16) return dw_fused_t<bf16_t>(g, g_y, x_u, w, gy_u, g_x, part, st);
+  return dw_fused_t<float>(g, g_y, x_u, w, gy_u, g_x, part, st);
+}
+
+}  // namespace gf

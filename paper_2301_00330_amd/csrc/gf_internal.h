@@ -61,6 +61,22 @@ template <> struct Vec16<bf16_t> {
   }
 };
 
+// Spatial sum of one kernel (text after Eq. 3), taps added in index order.  Taps are
+// fetched eight at a time with clamped indices so the loads are in flight together.
+template <class T>
+__device__ __forceinline__ float kernel_sum_of(const T* w, long pair, int KK) {
+  const T* p = w + pair * KK;
+  float s = 0.f;
+  for (int t0 = 0; t0 < KK; t0 += 8) {
+    T v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = p[min(t0 + k, KK - 1)];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += (t0 + k < KK) ? to_f32(v[k]) : 0.f;
+  }
+  return s;
+}
+
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 static inline int imin_host(int a, int b) { return a < b ? a : b; }
 
@@ -108,6 +124,14 @@ hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, voi
                              void* full, hipStream_t st);
 // true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
 bool mfma_dgrad_writes_full(const Geom& g);
+
+// One-pass filtered backward of a depthwise stride-1 layer (gf_fused.hip): filter, weight
+// gradient partials ([nz, C] in `part`, to be finalized) and input gradient.
+bool dw_fused_ok(const Geom& g, int* nz);
+hipError_t launch_dw_fused(const Geom& g, const void* g_y, const void* x_u, const void* w, void* gy_u,
+                           void* g_x, float* part, hipStream_t st);
+hipError_t launch_finalize(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
+                           hipStream_t st);
 
 // S5: exact K x K backward.
 size_t ws_exact(const Geom& g, bool want_gw, bool want_gx);

@@ -429,10 +429,7 @@ template <class T>
 __global__ __launch_bounds__(kThreads) void kernel_sum_t_k(const T* w, T* wsum, int pairs, int KK) {
   const int e = blockIdx.x * kThreads + threadIdx.x;
   if (e >= pairs) return;
-  const T* p = w + (long)e * KK;
-  float acc = 0.f;
-  for (int t = 0; t < KK; ++t) acc += to_f32(p[t]);
-  wsum[e] = from_f32<T>(acc);
+  wsum[e] = from_f32<T>(kernel_sum_of(w, e, KK));
 }
 
 template <class T, int TM, int TN, int WM, int WN>
@@ -471,8 +468,9 @@ void wgrad_tile(int shape, int* bm, int* bn) {
 
 }  // namespace
 
-// K slabs of the weight-gradient GEMM: enough blocks to cover the chip, at least
-// four staged chunks per block.
+// K slabs of the weight-gradient GEMM: enough for ~1024 blocks, but at least four staged
+// chunks per block so that the partial slabs stay small next to the operands (measured:
+// one chunk per block is slower on the 144 x 24 x 25088 and 512 x 512 x 1024 problems).
 int mfma_wgrad_splits(const Geom& g, int* chunks_per_z) {
   const int BK = g.dtype == GF_BF16 ? 64 : 32;
   const int nchunks = cdiv((long)g.N * g.P, BK);

@@ -111,6 +111,22 @@ def conv_bwd_input(d: B.ConvDesc, gy_u: torch.Tensor, w: torch.Tensor, reduced_o
     return out
 
 
+def conv_bwd_filtered(d: B.ConvDesc, g_y: torch.Tensor, x_u: torch.Tensor, w: torch.Tensor,
+                      want_gyu: bool = True, ws: Workspace | None = None):
+    """(g_w, g_x, gy_u or None) from one call of gf_conv_bwd_filtered."""
+    s = shapes(d)
+    _check(g_y, d, s["g_y"], "g_y")
+    _check(x_u, d, s["x_u"], "x_u")
+    _check(w, d, s["w"], "w")
+    g_w = torch.empty(s["w"], dtype=torch.float32, device=g_y.device)
+    g_x = torch.empty(s["x"], dtype=g_y.dtype, device=g_y.device)
+    gy_u = torch.empty(s["gy_u"], dtype=g_y.dtype, device=g_y.device) if want_gyu else None
+    p, n = _ws(g_y, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED))
+    B.gf_conv_bwd_filtered(d, B.ptr(g_y), B.ptr(x_u), B.ptr(w), B.ptr(gy_u), B.ptr(g_w), B.ptr(g_x),
+                           p, n, _stream())
+    return g_w, g_x, gy_u
+
+
 def conv_bwd_exact(d: B.ConvDesc, x, w, g_y, want_gw: bool = True, want_gx: bool = True,
                    ws: Workspace | None = None):
     s = shapes(d.with_(r=1))

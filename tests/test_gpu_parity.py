@@ -180,6 +180,65 @@ def test_filtered_backward_steps(oracle, case, dtype):
     assert torch.equal(up, g_x)
 
 
+FUSED_EXTRA = [
+    (4, 48, 48, 56, 56, 3, 1, 1, 1, 48, 2),       # depthwise, aligned rows (register variant), 2 planes per block
+    (3, 7, 7, 64, 64, 3, 1, 1, 1, 7, 4),          # odd plane count, r = 4
+    (2, 6, 6, 32, 32, 3, 1, 1, 1, 6, 8),          # r = 8
+    (2, 5, 5, 40, 120, 3, 1, 1, 1, 5, 2),         # more than one 256-item chunk per plane
+    (5, 24, 24, 14, 14, 3, 1, 1, 1, 24, 2),       # depthwise 14x14 (LDS variant)
+    (6, 33, 33, 7, 7, 3, 1, 1, 1, 33, 2),         # ragged 7x7, odd plane count: unaligned block runs
+    (3, 10, 10, 7, 7, 3, 1, 1, 1, 10, 4),         # ragged, r = 4
+    (2, 9, 9, 9, 9, 3, 1, 1, 1, 9, 3),            # r = 3 (run-time patch size)
+    (1, 3, 3, 5, 5, 5, 1, 2, 1, 3, 8),            # one patch per plane, tiny tensor
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("want_gyu", [True, False])
+@pytest.mark.parametrize("case", GF_CASES + FUSED_EXTRA)
+def test_fused_entry_matches_separate_calls(oracle, case, dtype, want_gyu):
+    """gf_conv_bwd_filtered against the oracle, and against the three separate entry
+    points: g_x and gy_u bit for bit, g_w within the fp32 summation tolerance."""
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, r, dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 51, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 52, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    gy = randn((N, Co, Hy, Wy), 53, dtype, scale=1e-2)
+    x_u = rounded(oracle.pool_activation(od, to64(x)), dtype).cuda()
+    gyg, wg = gy.cuda(), w.cuda()
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gyg, x_u, wg, want_gyu=want_gyu)
+    s_gyu = T.filter_grad(d, gyg)
+    s_gw = T.conv_bwd_weight(d, x_u, s_gyu)
+    s_gx = T.conv_bwd_input(d, s_gyu, wg)
+    torch.cuda.synchronize()
+    assert torch.equal(g_x, s_gx)
+    if want_gyu:
+        assert torch.equal(gy_u, s_gyu)
+    else:
+        assert gy_u is None
+    gw_tol = 1e-5 if dtype == "f32" else 1e-5   # same rounded operands, only the fp32 summation order differs
+    assert float((g_w - s_gw).abs().max()) <= gw_tol * float(s_gw.abs().max() + 1e-30)
+    # and against the oracle, end to end from the same inputs
+    ref_gyu = oracle.filter_grad(od, to64(gy))
+    ref_gw = oracle.bwd_weight(od, to64(x_u), to64(s_gyu))
+    ref_gx = oracle.bwd_input(od, to64(s_gyu), to64(w))
+    assert rel_err(s_gyu, ref_gyu) <= TOL[dtype]
+    assert rel_err(g_w, ref_gw) <= TOL[dtype]
+    assert rel_err(g_x, ref_gx) <= TOL[dtype]
+
+
+def test_fused_entry_r1_is_vanilla_bp(oracle):
+    d = mk(2, 6, 8, 9, 9, 3, 1, 1, 1, 1, 1, "f32")
+    od = odesc(oracle, d)
+    x, w, gy = randn((2, 6, 9, 9), 1, "f32"), randn((8, 6, 3, 3), 2, "f32"), randn((2, 8, 9, 9), 3, "f32")
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x.cuda(), w.cuda())
+    ref_gw, ref_gx = oracle.bwd_exact(od, to64(x), to64(w), to64(gy))
+    assert torch.equal(gy_u.cpu(), gy)
+    assert rel_err(g_w, ref_gw) <= 1e-5 and rel_err(g_x, ref_gx) <= 1e-5
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("g,s", [(1, 1), (16, 1), (1, 2), (4, 1)])
 def test_filtered_backward_bit_exact_on_integers(oracle, g, s, dtype):
