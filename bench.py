@@ -36,7 +36,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="f32",
+                    help="storage dtype of the headline number (fp32 is the paper's precision); the other\n"
+                         "dtype of the configuration is measured too and reported under 'other_dtype'")
+    ap.add_argument("--single-dtype", action="store_true", help="skip the second dtype")
     ap.add_argument("--config", type=int, default=2, help="workload: configuration id in workloads.CONFIGS")
     ap.add_argument("--r", type=int, default=0, help="patch size (default: the configuration's first)")
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (default: enough for > 768 MB)")
@@ -81,7 +84,16 @@ def main():
         log("bench.py: this build measures ONE GPU only (the path has no multi-GPU part); "
             "run with --gpus 1")
         sys.exit(2)
+    out = measure(args, args.dtype, full=True)
+    from paper_2301_00330_amd import workloads as WL
+    others = [d for d in WL.CONFIGS[args.config].dtypes if d != out["dtype"]]
+    if others and not args.single_dtype:
+        o = measure(args, others[0], full=False)
+        out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer")}
+    print(json.dumps(out), flush=True)
 
+
+def measure(args, dtype, full):
     import torch
     import paper_2301_00330_amd.binding as B
     import paper_2301_00330_amd.torch_api as T
@@ -92,7 +104,6 @@ def main():
     torch.cuda.set_device(0)
     cfg = WL.CONFIGS[args.config]
     r = args.r or cfg.rs[0]
-    dtype = args.dtype
     if dtype not in cfg.dtypes:
         dtype = cfg.dtypes[0]
     N = cfg.N
@@ -245,7 +256,7 @@ def main():
 
     # ---- exact BP at the same shapes (speed-up denominator) ----
     exact = None
-    if not args.no_exact:
+    if full and not args.no_exact:
         import torch.nn.functional as F
         ex_us, mi_us = [], []
         for li, L in enumerate(layers):
@@ -277,7 +288,7 @@ def main():
 
     # ---- CPU oracle on the host cores (reported baseline only) ----
     cpu = None
-    if not args.no_cpu_baseline:
+    if full and not args.no_cpu_baseline:
         import oracle
         f64 = lambda t: t.to(torch.float64).numpy()
         prep = []
@@ -315,7 +326,9 @@ def main():
         "per_layer": per_layer,
         "exact_bp": exact,
     }
-    print(json.dumps(out), flush=True)
+    del sets, one, graphs
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

@@ -133,6 +133,7 @@ hipError_t launch_dw_fused(const Geom& g, const void* g_y, const void* x_u, cons
 hipError_t launch_finalize(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
                            hipStream_t st);
 
+
 // S5: exact K x K backward.
 size_t ws_exact(const Geom& g, bool want_gw, bool want_gx);
 hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, float* g_w, void* ws,

@@ -211,7 +211,12 @@ struct DgradMfmaArgs {
   void* full;       // [N, Ci, H, W], or null to write the reduced map to dst
   int H, W, Wp, rx;
   FastDiv d_wp;
+  // plane mode (small or unaligned maps): a tile's columns are `ipt` whole images, so the
+  // full-resolution output of a tile row range is one contiguous run of planes per image
+  int planes_mode, ipt, cols_per_tile, rows_per_pass;
 };
+
+constexpr int kPlaneStageBytes = 16 * 1024;
 
 // rows k (c_o) x columns mn, LDS tile of 32 word-rows: fp32 one k per row, bf16 a k-pair per row
 template <class T, int BMN, bool VEC, class RowPtr>
@@ -274,6 +279,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
   constexpr int kTileWords = 32 * (SA + SB);
   constexpr int kOutWords = (BM * SC * (int)sizeof(T) + 3) / 4;
   __shared__ __attribute__((aligned(16))) uint32_t smem[kTileWords > kOutWords ? kTileWords : kOutWords];
+  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
   uint32_t* As = smem;
   uint32_t* Bs = smem + 32 * SA;
   const T* gyu = static_cast<const T*>(a.gyu);
@@ -281,7 +287,8 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int m0 = blockIdx.y * BM;  // first c_i
-  const int j0 = blockIdx.x * BN;  // first flat column (n, p)
+  const int j0 = blockIdx.x * a.cols_per_tile;  // first flat column (n, p)
+  const int jend = min(a.Jtot, j0 + a.cols_per_tile);
 
   auto load_a = [&](int k, int col) -> uint4 {  // wt[k][m0 + col ..]
     const int ci = m0 + col;
@@ -299,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
     return make_uint4(w[0], w[1], w[2], w[3]);
   };
   auto load_b = [&](int k, int col) -> uint4 {  // gy_u[n, k, p] for flat column j0 + col
-    return load_cols<T, VEC>(gyu + (long)k * a.P, (long)a.Co * a.P, j0 + col, a.Jtot, a.P, a.d_p);
+    return load_cols<T, VEC>(gyu + (long)k * a.P, (long)a.Co * a.P, j0 + col, jend, a.P, a.d_p);
   };
 
   f32x4 acc[TM][TN];
@@ -368,6 +375,54 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
         Cs[row * SC + col] = from_f32<T>(acc[i][j][v] * a.scale);
       }
   __syncthreads();
+  if (a.planes_mode) {
+    // Every image of the tile, `rows_per_pass` channel rows at a time: replicate the patch
+    // values into an LDS image of the output run (rows are consecutive planes, so the run is
+    // contiguous in memory), then store it with 16-byte vectors; the partial vectors at both
+    // ends, which neighbouring tiles share, go out element by element.
+    T* out = static_cast<T*>(a.full);
+    const int HW = a.H * a.W, rx = a.rx;
+    const int n0 = blockIdx.x * a.ipt;
+    const int nimg = (jend - j0) / a.P;
+    const int rows_valid = min(BM, a.Ci - m0);
+    for (int il = 0; il < nimg; ++il)
+      for (int r0 = 0; r0 < rows_valid; r0 += a.rows_per_pass) {
+        const int nr = min(a.rows_per_pass, rows_valid - r0);
+        const long e0 = (((long)(n0 + il) * a.Ci + m0 + r0)) * HW;   // first element of the run
+        const long byte0 = e0 * (long)sizeof(T);
+        const long a0 = byte0 & ~15L;
+        const int shift = (int)(byte0 - a0);
+        const int span = shift + nr * HW * (int)sizeof(T);
+        T* img = reinterpret_cast<T*>(Es + shift);
+        for (int it = tid; it < nr * a.P; it += kThreads) {
+          const int rl = (int)a.d_p.div((uint32_t)it);
+          const int pp = it - rl * a.P;
+          const int hp = (int)a.d_wp.div((uint32_t)pp);
+          const int wp = pp - hp * a.Wp;
+          const T val = Cs[(r0 + rl) * SC + il * a.P + pp];
+          const int h1 = min(a.H, (hp + 1) * rx), w1 = min(a.W, (wp + 1) * rx);
+          for (int h = hp * rx; h < h1; ++h)
+            for (int ww = wp * rx; ww < w1; ++ww) img[rl * HW + h * a.W + ww] = val;
+        }
+        __syncthreads();
+        const int nvec = span >> 4;
+        unsigned char* dstb = reinterpret_cast<unsigned char*>(out) + a0;
+        for (int v = tid + (shift ? 1 : 0); v < nvec; v += kThreads)
+          *reinterpret_cast<uint4*>(dstb + ((long)v << 4)) = *reinterpret_cast<const uint4*>(Es + (v << 4));
+        if (shift) {
+          const int nhead = min((16 - shift) / (int)sizeof(T), nr * HW);
+          if (tid < nhead) out[e0 + tid] = img[tid];
+        }
+        {
+          const int tail0 = nvec << 4;
+          const int ntail = (span - tail0) / (int)sizeof(T);
+          const int efirst = (tail0 - shift) / (int)sizeof(T);
+          if (tid < ntail && efirst + tid >= 0) out[e0 + efirst + tid] = img[efirst + tid];
+        }
+        __syncthreads();
+      }
+    return;
+  }
   if (a.full) {
     // one 16-byte run of output pixels per step: row ci, sub-row i of the patch, pixel run q0..
     // (host guarantees rx | VE or VE | rx, W == Wp * rx, W % VE == 0, Wp * rx % VE == 0)
@@ -446,7 +501,8 @@ hipError_t wgrad_launch(WgradMfmaArgs& a, int nz, bool vec, hipStream_t st) {
 template <class T, int TM, int TN, int WM, int WN>
 hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
-  dim3 grid(cdiv(a.Jtot, BN), cdiv(a.Ci, BM), 1);
+  if (!a.planes_mode) a.cols_per_tile = BN;
+  dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, BM), 1);
   if (vec)
     hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
   else
@@ -525,8 +581,14 @@ static bool dgrad_full_ok(const Geom& g) {
   return true;
 }
 
+// plane mode: whole images fit the 64-column tile and one plane fits the staging buffer
+static bool dgrad_planes_ok(const Geom& g) {
+  return g.P <= 64 && (long)g.H * g.W * g.b + 32 <= kPlaneStageBytes;
+}
+
 bool mfma_dgrad_writes_full(const Geom& g) {
-  return g.dtype == GF_BF16 ? dgrad_full_ok<bf16_t>(g) : dgrad_full_ok<float>(g);
+  const bool runs = g.dtype == GF_BF16 ? dgrad_full_ok<bf16_t>(g) : dgrad_full_ok<float>(g);
+  return runs || dgrad_planes_ok(g);
 }
 
 template <class T>
@@ -557,7 +619,18 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   a.Wp = g.Wp;
   a.rx = g.rx;
   a.d_wp = FastDiv((uint32_t)g.Wp);
+  a.planes_mode = 0;
+  a.ipt = 0;
+  a.cols_per_tile = 0;
+  a.rows_per_pass = 0;
   const bool vec = g.P % Mma<T>::VE == 0 && g.Ci % Mma<T>::VE == 0;
+  if (full && !dgrad_full_ok<T>(g)) {  // small / unaligned maps: whole images per 64-column tile
+    a.planes_mode = 1;
+    a.ipt = 64 / g.P;
+    a.cols_per_tile = a.ipt * g.P;
+    a.rows_per_pass = (kPlaneStageBytes - 32) / (g.H * g.W * (int)sizeof(T));
+    return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
+  }
   if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);
   return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
 }

@@ -190,6 +190,12 @@ FUSED_EXTRA = [
     (3, 10, 10, 7, 7, 3, 1, 1, 1, 10, 4),         # ragged, r = 4
     (2, 9, 9, 9, 9, 3, 1, 1, 1, 9, 3),            # r = 3 (run-time patch size)
     (1, 3, 3, 5, 5, 5, 1, 2, 1, 3, 8),            # one patch per plane, tiny tensor
+    (3, 24, 144, 56, 56, 1, 1, 0, 1, 1, 2),       # MobileNetV2 expand shape
+    (3, 144, 24, 56, 56, 1, 1, 0, 1, 1, 2),       # MobileNetV2 project shape
+    (2, 40, 56, 32, 32, 3, 1, 1, 1, 1, 4),        # 3x3, r = 4, channels not multiples of 16
+    (5, 16, 16, 16, 16, 3, 1, 1, 1, 1, 2),        # several units per block, W_p = 8
+    (2, 20, 36, 64, 64, 1, 1, 0, 1, 1, 8),        # r = 8
+    (1, 64, 64, 22, 24, 3, 1, 1, 1, 1, 2),        # ragged H (22 = 11 x 2), W_p = 12
 ]
 
 
