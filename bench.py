@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="end with five plain 256 MiB device copies (a kernel of known traffic, used to\n"
+                         "scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--table", action="store_true", help="also print a per-layer table to stderr")
     return ap.parse_args()
 
@@ -249,10 +252,16 @@ def measure(args, dtype, full):
     red_us = [per_layer[li][k]["us"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
     red_by = [per_layer[li][k]["bytes"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
     achieved = sum(red_by) / sum(red_us) * 1e-3      # GB/s, algorithmic bytes / measured time
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_patch_reduce_rows_cfg{cfg.cfg_id}_{dtype}.txt")
+    if os.path.exists(tpath):   # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch="):
+                traffic = float(line.split("=")[1])
     roofline = {"kernel": "patch_reduce_rows", "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "avg_launch_us": round(sum(red_us) / len(red_us), 2),
-                "bytes_per_launch": sum(red_by) / len(red_by), "traffic": None}
+                "bytes_per_launch": sum(red_by) / len(red_by), "traffic": traffic}
 
     # ---- exact BP at the same shapes (speed-up denominator) ----
     exact = None
@@ -328,6 +337,13 @@ def measure(args, dtype, full):
     }
     del sets, one, graphs
     torch.cuda.empty_cache()
+    if full and args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     return out
 
 
