@@ -219,17 +219,17 @@ struct DgradMfmaArgs {
 constexpr int kPlaneStageBytes = 16 * 1024;
 
 // rows k (c_o) x columns mn, LDS tile of 32 word-rows: fp32 one k per row, bf16 a k-pair per row
-template <class T, int BMN, bool VEC, class RowPtr>
+template <class T, int BMN, bool VEC, int NT = kThreads, class RowPtr>
 __device__ __forceinline__ void dgrad_fetch(uint4* rg, int tid, int k0, int Ktot, RowPtr&& load_row) {
   constexpr int VE = Mma<T>::VE;
   constexpr int VPR = BMN / VE;                      // vectors per k row
   constexpr int ROWS_PER_SLOT = sizeof(T) == 2 ? 2 : 1;
   constexpr int SLOTS = 32 * VPR;                    // 32 word-rows
-  constexpr int PER = (SLOTS + kThreads - 1) / kThreads;
+  constexpr int PER = (SLOTS + NT - 1) / NT;
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
-    const int s = tid + i * kThreads;
-    if (SLOTS % kThreads != 0 && s >= SLOTS) break;
+    const int s = tid + i * NT;
+    if (SLOTS % NT != 0 && s >= SLOTS) break;
     const int wr = s / VPR, vi = s - wr * VPR;
 #pragma unroll
     for (int q = 0; q < ROWS_PER_SLOT; ++q) {
@@ -240,16 +240,16 @@ __device__ __forceinline__ void dgrad_fetch(uint4* rg, int tid, int k0, int Ktot
   }
 }
 
-template <class T, int BMN, int STRIDE>
+template <class T, int BMN, int STRIDE, int NT = kThreads>
 __device__ __forceinline__ void dgrad_stage(uint32_t* tile, const uint4* rg, int tid) {
   constexpr int VE = Mma<T>::VE;
   constexpr int VPR = BMN / VE;
   constexpr int SLOTS = 32 * VPR;
-  constexpr int PER = (SLOTS + kThreads - 1) / kThreads;
+  constexpr int PER = (SLOTS + NT - 1) / NT;
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
-    const int s = tid + i * kThreads;
-    if (SLOTS % kThreads != 0 && s >= SLOTS) break;
+    const int s = tid + i * NT;
+    if (SLOTS % NT != 0 && s >= SLOTS) break;
     const int wr = s / VPR, vi = s - wr * VPR;
     uint32_t* d = tile + wr * STRIDE + vi * VE;
     if constexpr (sizeof(T) == 4) {
@@ -375,6 +375,16 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
         Cs[row * SC + col] = from_f32<T>(acc[i][j][v] * a.scale);
       }
   __syncthreads();
+  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, m0, j0, jend, tid);
+}
+
+// Store the finished tile Cs[BM][SC] (already rounded to the storage type): as the reduced map,
+// as 16-byte pixel runs at full resolution, or plane by plane through the LDS image Es.
+template <class T, int BM, int BN, bool VEC>
+__device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* Cs, unsigned char* Es,
+                                               int m0, int j0, int jend, int tid) {
+  constexpr int VE = Mma<T>::VE;
+  constexpr int SC = BN + 16 / (int)sizeof(T);
   if (a.planes_mode) {
     // Every image of the tile, `rows_per_pass` channel rows at a time: replicate the patch
     // values into an LDS image of the output run (rows are consecutive planes, so the run is
@@ -479,6 +489,140 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Same contraction for layers whose GEMM has few output tiles but a long K = C_y (small maps,
+// many channels): a 32 x BN tile per block, and the four waves split K among themselves.
+// Each wave stages its own chunks in a private LDS tile (no block barrier inside the K loop),
+// the four accumulators are added in fixed order through LDS at the end.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <class T, int BN, bool VEC>
+__global__ __launch_bounds__(kThreads) void dgrad_ksplit_k(DgradMfmaArgs a) {
+  constexpr int BM = 32, TM = 2, TN = BN / 16;
+  constexpr int BK = Mma<T>::BK, VE = Mma<T>::VE;
+  constexpr int SA = BM + 4, SB = BN + 4;
+  constexpr int RPS = sizeof(T) == 2 ? 2 : 1;
+  constexpr int PA = (32 * BM / VE + 63) / 64 * RPS;
+  constexpr int PB = (32 * BN / VE + 63) / 64 * RPS;
+  constexpr int SC = BN + 16 / (int)sizeof(T);
+  constexpr int kWaveWords = 32 * (SA + SB);
+  constexpr int kSumWords = 4 * BM * BN;                       // the four fp32 accumulator tiles
+  constexpr int kOutWords = (BM * SC * (int)sizeof(T) + 3) / 4;
+  static_assert(kSumWords + kOutWords <= 4 * kWaveWords, "reduction buffers fit the staging tiles");
+  __shared__ __attribute__((aligned(16))) uint32_t smem[4 * kWaveWords];
+  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
+  const T* gyu = static_cast<const T*>(a.gyu);
+  const T* wt = static_cast<const T*>(a.wt);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t* As = smem + wave * kWaveWords;
+  uint32_t* Bs = As + 32 * SA;
+  const int m0 = blockIdx.y * BM;
+  const int j0 = blockIdx.x * a.cols_per_tile;
+  const int jend = min(a.Jtot, j0 + a.cols_per_tile);
+
+  auto load_a = [&](int k, int col) -> uint4 {
+    const int ci = m0 + col;
+    if (VEC) {
+      const uint4 v = *reinterpret_cast<const uint4*>(wt + (long)k * a.Ci + min(ci, a.Ci - VE));
+      return ci < a.Ci ? v : make_uint4(0, 0, 0, 0);
+    }
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < VE; ++e)
+      if (ci + e < a.Ci) {
+        const uint32_t b = bits_of<T>(wt[(long)k * a.Ci + ci + e]);
+        if (sizeof(T) == 4) w[e & 3] = b; else w[e >> 1] |= b << ((e & 1) * 16);
+      }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  };
+  auto load_b = [&](int k, int col) -> uint4 {
+    return load_cols<T, VEC>(gyu + (long)k * a.P, (long)a.Co * a.P, j0 + col, jend, a.P, a.d_p);
+  };
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // this wave's K range, whole chunks
+  const int nch = (a.Co + BK - 1) / BK;
+  const int cpw = (nch + 3) / 4;
+  const int kbeg = min(a.Co, wave * cpw * BK);
+  const int kend = min(a.Co, kbeg + cpw * BK);
+  uint4 ra[PA], rb[PB];
+  if (kbeg < kend) {
+    dgrad_fetch<T, BM, VEC, 64>(ra, lane, kbeg, kend, load_a);
+    dgrad_fetch<T, BN, VEC, 64>(rb, lane, kbeg, kend, load_b);
+  }
+  const int r = lane & 15, kg = lane >> 4;
+  for (int k0 = kbeg; k0 < kend; k0 += BK) {
+    dgrad_stage<T, BM, SA, 64>(As, ra, lane);
+    dgrad_stage<T, BN, SB, 64>(Bs, rb, lane);
+    wave_sync();
+    if (k0 + BK < kend) {
+      dgrad_fetch<T, BM, VEC, 64>(ra, lane, k0 + BK, kend, load_a);
+      dgrad_fetch<T, BN, VEC, 64>(rb, lane, k0 + BK, kend, load_b);
+    }
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        uint4 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const uint32_t* p = As + (ks * 16 + kg * 4) * SA + i * 16 + r;
+          fa[i] = make_uint4(p[0], p[SA], p[2 * SA], p[3 * SA]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const uint32_t* p = Bs + (ks * 16 + kg * 4) * SB + j * 16 + r;
+          fb[j] = make_uint4(p[0], p[SB], p[2 * SB], p[3 * SB]);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mma16(fa[i], fb[j], acc[i][j]);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        float fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = __uint_as_float(As[(ks * 4 + kg) * SA + i * 16 + r]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = __uint_as_float(Bs[(ks * 4 + kg) * SB + j * 16 + r]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mma16(fa[i], fb[j], acc[i][j]);
+      }
+    }
+    wave_sync();
+  }
+  __syncthreads();  // every wave is done with its staging tile: reuse the memory
+  float* Rs = reinterpret_cast<float*>(smem);               // [4][BM][BN]
+  T* Cs = reinterpret_cast<T*>(smem + kSumWords);           // [BM][SC]
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        Rs[(wave * BM + i * 16 + 4 * kg + v) * BN + j * 16 + r] = acc[i][j][v];
+  __syncthreads();
+  for (int e = tid; e < BM * BN; e += kThreads) {
+    const float s = ((Rs[e] + Rs[BM * BN + e]) + Rs[2 * BM * BN + e]) + Rs[3 * BM * BN + e];
+    Cs[(e / BN) * SC + (e % BN)] = from_f32<T>(s * a.scale);
+  }
+  __syncthreads();
+  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, m0, j0, jend, tid);
+}
+
 // kernel sum rounded to the storage type, [Co][Ci] (text after Eq. 3)
 template <class T>
 __global__ __launch_bounds__(kThreads) void kernel_sum_t_k(const T* w, T* wsum, int pairs, int KK) {
@@ -570,6 +714,17 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
   return wgrad_t<float>(g, x_u, gy_u, part, nz_out, st);
 }
 
+template <class T, int BN>
+hipError_t dgrad_ksplit_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
+  if (!a.planes_mode) a.cols_per_tile = BN;
+  dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, 32), 1);
+  if (vec)
+    hipLaunchKernelGGL((dgrad_ksplit_k<T, BN, true>), grid, dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((dgrad_ksplit_k<T, BN, false>), grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
 template <class T>
 static bool dgrad_full_ok(const Geom& g) {
   constexpr int VE = Mma<T>::VE;
@@ -624,13 +779,21 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   a.cols_per_tile = 0;
   a.rows_per_pass = 0;
   const bool vec = g.P % Mma<T>::VE == 0 && g.Ci % Mma<T>::VE == 0;
-  if (full && !dgrad_full_ok<T>(g)) {  // small / unaligned maps: whole images per 64-column tile
+  const bool planes = full && !dgrad_full_ok<T>(g);
+  // few 64 x 64 tiles and a long K: let the four waves of a block split K instead
+  // (measured: pays from K = 512 up; at K = 320 .. 576 with many tiles it is slower)
+  const long tiles64 = (long)cdiv(a.Jtot, planes ? (64 / g.P) * g.P : 64) * cdiv(g.Ci, 64);
+  const bool ksplit = vec && g.Co >= 512 && tiles64 < 512;
+  if (planes) {  // small / unaligned maps: whole images per column tile
+    const int bn = (ksplit && g.P <= 32) ? 32 : 64;
     a.planes_mode = 1;
-    a.ipt = 64 / g.P;
+    a.ipt = bn / g.P;
     a.cols_per_tile = a.ipt * g.P;
     a.rows_per_pass = (kPlaneStageBytes - 32) / (g.H * g.W * (int)sizeof(T));
+    if (ksplit) return bn == 32 ? dgrad_ksplit_launch<T, 32>(a, vec, st) : dgrad_ksplit_launch<T, 64>(a, vec, st);
     return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
   }
+  if (ksplit) return dgrad_ksplit_launch<T, 64>(a, vec, st);
   if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);
   return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
 }

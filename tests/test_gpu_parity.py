@@ -144,6 +144,10 @@ GF_CASES = [
     (2, 16, 32, 16, 16, 3, 2, 1, 1, 1, 2),        # strided with aligned rows, r_x = 4
     (2, 40, 24, 24, 16, 3, 1, 1, 1, 1, 4),        # H ragged (24 = 6 x 4), W aligned
     (1, 136, 264, 16, 16, 1, 1, 0, 1, 1, 2),      # several channel tiles in both directions
+    (6, 72, 320, 7, 7, 1, 1, 0, 1, 1, 2),         # long K = C_out, few tiles: waves split K (P = 16)
+    (3, 40, 600, 14, 14, 1, 1, 0, 1, 1, 2),       # same with P = 49 and uneven K split
+    (2, 48, 256, 7, 7, 3, 1, 1, 1, 1, 4),         # P = 4
+    (2, 64, 288, 16, 16, 1, 1, 0, 1, 1, 2),       # K split with aligned rows (pixel-run store)
 ]
 
 
