@@ -90,7 +90,95 @@ struct WgradMfmaArgs {
   int Ci, Co, P, Ktot;
   int nchunks, chunks_per_z;
   FastDiv d_p;
+  // flat mode (P not a multiple of the vector length, P <= BK): a K chunk is G whole images,
+  // the tile rows of one image are one contiguous, 16-byte aligned block that is loaded with
+  // vectors and scattered to the [row][k] tile element by element
+  int flat, G, N;
 };
+
+template <class T>
+__device__ __forceinline__ uint32_t elem_bits(const uint4& v, int e) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if (sizeof(T) == 4) return w[e & 3];
+  return (w[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+}
+
+// vectors of the image blocks [rows r0 .. r0+ROWS) x P of images kc*G .. kc*G+G-1
+template <class T, int ROWS, int NREG = ROWS / 32>
+__device__ __forceinline__ void flat_fetch(uint4* rg, const T* base, int C, int r0, int kc, int P,
+                                           int G, int N, int tid) {
+  constexpr int VE = Mma<T>::VE;
+  const int vpi = ROWS * P / VE;
+  const int valid_vec = (min(ROWS, C - r0) * P + VE - 1) / VE;
+#pragma unroll
+  for (int i = 0; i < NREG; ++i) {
+    const int s = tid + i * kThreads;
+    const int g = s / vpi, vidx = s - g * vpi;
+    const int n = kc * G + g;
+    const bool ok = g < G && n < N && vidx < valid_vec;
+    const uint4 v = *reinterpret_cast<const uint4*>(base + ((long)min(n, N - 1) * C + r0) * P +
+                                                    (long)min(vidx, valid_vec - 1) * VE);
+    rg[i] = ok ? v : make_uint4(0, 0, 0, 0);
+  }
+}
+
+// scatter them into the K-major tile: element (row, p) of image g goes to k = g * P + p
+template <class T, int ROWS>
+__device__ __forceinline__ void flat_stage_kmajor(unsigned char* tile, const uint4* rg, int C, int r0,
+                                                  int P, int G, const FastDiv& d_p, int tid) {
+  constexpr int VE = Mma<T>::VE;
+  const int vpi = ROWS * P / VE;
+  const int valid = min(ROWS, C - r0) * P;
+#pragma unroll
+  for (int i = 0; i < ROWS / 32; ++i) {
+    const int s = tid + i * kThreads;
+    const int g = s / vpi, vidx = s - g * vpi;
+    if (g >= G) continue;
+    int f = vidx * VE;
+    int row = (int)d_p.div((uint32_t)f);
+    int p = f - row * P;
+#pragma unroll
+    for (int e = 0; e < VE; ++e) {
+      if (f < valid) {
+        unsigned char* d = tile + row * kRowBytes + (g * P + p) * (int)sizeof(T);
+        if (sizeof(T) == 4) *reinterpret_cast<uint32_t*>(d) = elem_bits<T>(rg[i], e);
+        else *reinterpret_cast<uint16_t*>(d) = (uint16_t)elem_bits<T>(rg[i], e);
+      }
+      ++f;
+      if (++p == P) { p = 0; ++row; }
+    }
+  }
+}
+
+// scatter image blocks [ROWS k-rows x P] into the K-strided tile of the input-gradient GEMM:
+// element (k, p) of image g goes to column g * P + p; fp32 one k per word row, bf16 a k-pair
+// per word row.  Every position of the block is written (zeros past the valid rows), because
+// the previous chunk may have left data there.
+template <class T, int ROWS, int NREG, int STRIDE>
+__device__ __forceinline__ void flat_stage_kstrided(uint32_t* tile, const uint4* rg, int C, int r0,
+                                                    int P, int G, const FastDiv& d_p, int tid) {
+  constexpr int VE = Mma<T>::VE;
+  const int vpi = ROWS * P / VE;
+  const int valid = min(ROWS, C - r0) * P;
+#pragma unroll
+  for (int i = 0; i < NREG; ++i) {
+    const int s = tid + i * kThreads;
+    const int g = s / vpi, vidx = s - g * vpi;
+    if (g >= G) continue;
+    int f = vidx * VE;
+    int k = (int)d_p.div((uint32_t)f);
+    int p = f - k * P;
+#pragma unroll
+    for (int e = 0; e < VE; ++e) {
+      const uint32_t b = f < valid ? elem_bits<T>(rg[i], e) : 0u;
+      const int col = g * P + p;
+      if (sizeof(T) == 4) tile[k * STRIDE + col] = b;
+      else reinterpret_cast<uint16_t*>(tile)[((k >> 1) * STRIDE + col) * 2 + (k & 1)] = (uint16_t)b;
+      ++f;
+      if (++p == P) { p = 0; ++k; }
+    }
+  }
+}
 
 template <class T, int TM, int TN, int WM, int WN, bool VEC>
 __global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
@@ -109,7 +197,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
   const int kc1 = min(kc0 + a.chunks_per_z, a.nchunks);
 
   uint4 ra[LA], rb[LB];
+  const bool flat = !VEC && a.flat;
+  if (flat) {  // pad columns and rows past the channel count are never written: clear them once
+    for (int i = tid; i < BM * kRowBytes / 4; i += kThreads) reinterpret_cast<uint32_t*>(As)[i] = 0u;
+    for (int i = tid; i < BN * kRowBytes / 4; i += kThreads) reinterpret_cast<uint32_t*>(Bs)[i] = 0u;
+    __syncthreads();
+  }
   auto fetch = [&](int kc) {
+    if (flat) {
+      flat_fetch<T, BM>(ra, gyu, a.Co, m0, kc, a.P, a.G, a.N, tid);
+      flat_fetch<T, BN>(rb, xu, a.Ci, n0, kc, a.P, a.G, a.N, tid);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
       const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
@@ -128,6 +227,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
     }
   };
   auto stage = [&]() {
+    if (flat) {
+      flat_stage_kmajor<T, BM>(As, ra, a.Co, m0, a.P, a.G, a.d_p, tid);
+      flat_stage_kmajor<T, BN>(Bs, rb, a.Ci, n0, a.P, a.G, a.d_p, tid);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
       const int s = tid + i * kThreads;
@@ -214,6 +318,10 @@ struct DgradMfmaArgs {
   // plane mode (small or unaligned maps): a tile's columns are `ipt` whole images, so the
   // full-resolution output of a tile row range is one contiguous run of planes per image
   int planes_mode, ipt, cols_per_tile, rows_per_pass;
+  // operand loading when P is not a multiple of the vector length: veca = the kernel matrix can
+  // still be read with vectors; flatb = gy_u is read as whole-image blocks (column tiles are
+  // `ipt` whole images) and scattered into the tile
+  int veca, flatb, N;
 };
 
 constexpr int kPlaneStageBytes = 16 * 1024;
@@ -292,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
 
   auto load_a = [&](int k, int col) -> uint4 {  // wt[k][m0 + col ..]
     const int ci = m0 + col;
-    if (VEC) {
+    if (VEC || a.veca) {
       const uint4 v = *reinterpret_cast<const uint4*>(wt + (long)k * a.Ci + min(ci, a.Ci - VE));
       return ci < a.Ci ? v : make_uint4(0, 0, 0, 0);
     }
@@ -316,16 +424,26 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   uint4 ra[PA], rb[PB];
+  const bool flatb = !VEC && a.flatb;
+  if (flatb) {  // columns past the tile's images are never written: clear the tile once
+    for (int i = tid; i < 32 * SB; i += kThreads) Bs[i] = 0u;
+    __syncthreads();
+  }
+  auto fetch_b = [&](int k0) {
+    if (flatb) flat_fetch<T, BK, PB>(rb, gyu, a.Co, k0, blockIdx.x, a.P, a.ipt, a.N, tid);
+    else dgrad_fetch<T, BN, VEC>(rb, tid, k0, a.Co, load_b);
+  };
   dgrad_fetch<T, BM, VEC>(ra, tid, 0, a.Co, load_a);
-  dgrad_fetch<T, BN, VEC>(rb, tid, 0, a.Co, load_b);
+  fetch_b(0);
   const int r = lane & 15, kg = lane >> 4;
   for (int k0 = 0; k0 < a.Co; k0 += BK) {
     dgrad_stage<T, BM, SA>(As, ra, tid);
-    dgrad_stage<T, BN, SB>(Bs, rb, tid);
+    if (flatb) flat_stage_kstrided<T, BK, PB, SB>(Bs, rb, a.Co, k0, a.P, a.ipt, a.d_p, tid);
+    else dgrad_stage<T, BN, SB>(Bs, rb, tid);
     __syncthreads();
     if (k0 + BK < a.Co) {
       dgrad_fetch<T, BM, VEC>(ra, tid, k0 + BK, a.Co, load_a);
-      dgrad_fetch<T, BN, VEC>(rb, tid, k0 + BK, a.Co, load_b);
+      fetch_b(k0 + BK);
     }
     if constexpr (sizeof(T) == 2) {
 #pragma unroll
@@ -447,7 +565,7 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
       const int q0 = ov * VE;                // first output pixel of the run, tile-relative
       const int col = q0 / rx;               // first patch column of the run
       const int ci = m0 + row, j = j0 + col;
-      if (ci >= a.Ci || j >= a.Jtot) continue;
+      if (ci >= a.Ci || j >= jend) continue;
       const int n = (int)a.d_p.div((uint32_t)j);
       const int p = j - n * a.P;
       const int hp = (int)a.d_wp.div((uint32_t)p);
@@ -473,14 +591,14 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
   for (int s = tid; s < BM * VPR; s += kThreads) {
     const int row = s / VPR, vi = s - row * VPR;
     const int ci = m0 + row, j = j0 + vi * VE;
-    if (ci >= a.Ci || j >= a.Jtot) continue;
+    if (ci >= a.Ci || j >= jend) continue;
     if (VEC) {
       const int n = (int)a.d_p.div((uint32_t)j);
       const int p = j - n * a.P;
       *reinterpret_cast<uint4*>(dst + ((long)n * a.Ci + ci) * a.P + p) =
           *reinterpret_cast<const uint4*>(Cs + row * SC + vi * VE);
     } else {
-      for (int e = 0; e < VE && j + e < a.Jtot; ++e) {
+      for (int e = 0; e < VE && j + e < jend; ++e) {
         const int n = (int)a.d_p.div((uint32_t)(j + e));
         const int p = j + e - n * a.P;
         dst[((long)n * a.Ci + ci) * a.P + p] = Cs[row * SC + vi * VE + e];
@@ -645,7 +763,7 @@ hipError_t wgrad_launch(WgradMfmaArgs& a, int nz, bool vec, hipStream_t st) {
 template <class T, int TM, int TN, int WM, int WN>
 hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
-  if (!a.planes_mode) a.cols_per_tile = BN;
+  if (!a.planes_mode && !a.flatb) a.cols_per_tile = BN;
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, BM), 1);
   if (vec)
     hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
@@ -668,12 +786,26 @@ void wgrad_tile(int shape, int* bm, int* bn) {
 
 }  // namespace
 
+// flat mode of the weight-gradient GEMM (see WgradMfmaArgs): G images per K chunk
+bool wgrad_flat(const Geom& g, int* G) {
+  const int VE = 16 / g.b, BK = g.dtype == GF_BF16 ? 64 : 32;
+  if (g.P % VE == 0 || g.P > BK) return false;
+  if (((long)g.Co * g.P * g.b) % 16 != 0 || ((long)g.Ci * g.P * g.b) % 16 != 0) return false;
+  if (G) *G = BK / g.P;
+  return true;
+}
+
+int wgrad_chunks(const Geom& g) {
+  int G = 1;
+  if (wgrad_flat(g, &G)) return cdiv(g.N, G);
+  return cdiv((long)g.N * g.P, g.dtype == GF_BF16 ? 64 : 32);
+}
+
 // K slabs of the weight-gradient GEMM: enough for ~1024 blocks, but at least four staged
 // chunks per block so that the partial slabs stay small next to the operands (measured:
 // one chunk per block is slower on the 144 x 24 x 25088 and 512 x 512 x 1024 problems).
 int mfma_wgrad_splits(const Geom& g, int* chunks_per_z) {
-  const int BK = g.dtype == GF_BF16 ? 64 : 32;
-  const int nchunks = cdiv((long)g.N * g.P, BK);
+  const int nchunks = wgrad_chunks(g);
   int bm, bn;
   wgrad_tile(wgrad_shape(g), &bm, &bn);
   const int tiles = cdiv(g.Co, bm) * cdiv(g.Ci, bn);
@@ -696,7 +828,10 @@ static hipError_t wgrad_t(const Geom& g, const void* x_u, const void* gy_u, floa
   a.Co = g.Co;
   a.P = g.P;
   a.Ktot = g.N * g.P;
-  a.nchunks = cdiv(a.Ktot, Mma<T>::BK);
+  a.nchunks = wgrad_chunks(g);
+  a.N = g.N;
+  a.G = 1;
+  a.flat = wgrad_flat(g, &a.G) ? 1 : 0;
   const int nz = mfma_wgrad_splits(g, &a.chunks_per_z);
   a.d_p = FastDiv((uint32_t)g.P);
   *nz_out = nz;
@@ -778,7 +913,12 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   a.ipt = 0;
   a.cols_per_tile = 0;
   a.rows_per_pass = 0;
+  a.N = g.N;
+  a.veca = g.Ci % Mma<T>::VE == 0;
+  a.flatb = 0;
   const bool vec = g.P % Mma<T>::VE == 0 && g.Ci % Mma<T>::VE == 0;
+  // P not a multiple of the vector length: whole-image column tiles, gy_u read as image blocks
+  const bool flatb = g.P % Mma<T>::VE != 0 && g.P <= 64 && ((long)g.Co * g.P * sizeof(T)) % 16 == 0;
   const bool planes = full && !dgrad_full_ok<T>(g);
   // few 64 x 64 tiles and a long K: let the four waves of a block split K instead
   // (measured: pays from K = 512 up; at K = 320 .. 576 with many tiles it is slower)
@@ -791,7 +931,15 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
     a.cols_per_tile = a.ipt * g.P;
     a.rows_per_pass = (kPlaneStageBytes - 32) / (g.H * g.W * (int)sizeof(T));
     if (ksplit) return bn == 32 ? dgrad_ksplit_launch<T, 32>(a, vec, st) : dgrad_ksplit_launch<T, 64>(a, vec, st);
+    a.flatb = flatb ? 1 : 0;
     return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
+  }
+  if (flatb) {  // reduced map out, whole-image column tiles
+    a.flatb = 1;
+    a.planes_mode = 0;
+    a.ipt = 64 / g.P;
+    a.cols_per_tile = a.ipt * g.P;
+    return dgrad_launch<T, 2, 2, 2, 2>(a, false, st);
   }
   if (ksplit) return dgrad_ksplit_launch<T, 64>(a, vec, st);
   if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);

@@ -144,10 +144,12 @@ GF_CASES = [
     (2, 16, 32, 16, 16, 3, 2, 1, 1, 1, 2),        # strided with aligned rows, r_x = 4
     (2, 40, 24, 24, 16, 3, 1, 1, 1, 1, 4),        # H ragged (24 = 6 x 4), W aligned
     (1, 136, 264, 16, 16, 1, 1, 0, 1, 1, 2),      # several channel tiles in both directions
-    (6, 72, 320, 7, 7, 1, 1, 0, 1, 1, 2),         # long K = C_out, few tiles: waves split K (P = 16)
+    (6, 72, 640, 7, 7, 1, 1, 0, 1, 1, 2),         # long K = C_out, few tiles: waves split K (P = 16)
     (3, 40, 600, 14, 14, 1, 1, 0, 1, 1, 2),       # same with P = 49 and uneven K split
-    (2, 48, 256, 7, 7, 3, 1, 1, 1, 1, 4),         # P = 4
-    (2, 64, 288, 16, 16, 1, 1, 0, 1, 1, 2),       # K split with aligned rows (pixel-run store)
+    (2, 48, 512, 7, 7, 3, 1, 1, 1, 1, 4),         # P = 4: image blocks, 16 (bf16) / 8 (fp32) images per K chunk
+    (2, 64, 544, 16, 16, 1, 1, 0, 1, 1, 2),       # K split with aligned rows (pixel-run store)
+    (19, 24, 40, 7, 7, 3, 1, 1, 1, 1, 4),         # P = 4, batch not a multiple of the images per chunk
+    (3, 72, 200, 6, 6, 1, 1, 0, 1, 1, 2),         # P = 9: seven images per chunk, blocks 16-byte aligned
 ]
 
 
