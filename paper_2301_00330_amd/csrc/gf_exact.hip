@@ -88,6 +88,151 @@ __global__ __launch_bounds__(kThreads) void exact_wgrad_k(ExactArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Dense layers: the K x K contractions as GEMMs on the MFMA kernels of the filtered path.
+// The shifted operand is written out once per tap ("column" tensor in the workspace):
+//   weight gradient: xcol[n, ci*KK + t, (i,j)] = x[n, ci, i s - p + u d, j s - p + v d]
+//                    g_theta[co, ci, t] = sum_{n,(i,j)} g_y[n, co, (i,j)] * xcol[n, ci*KK + t, (i,j)]
+//   input gradient:  gcol[n, co*KK + t, (h,w)] = g_y[n, co, (h + p - u d)/s, (w + p - v d)/s]
+//                    g_x[n, ci, (h,w)] = sum_{co,t} theta[co, ci, t] * gcol[n, co*KK + t, (h,w)]
+// (zero where the source index is out of range or not divisible by the stride).
+// ---------------------------------------------------------------------------
+struct ColArgs {
+  const void* src;
+  void* dst;
+  int C, Hs, Ws;      // source tensor [N, C, Hs, Ws]
+  int Ho, Wo;         // positions of the column tensor
+  int Kh, Kw, s, p, dl;
+  int gather_input;   // 1: x -> xcol (forward index map), 0: g_y -> gcol (transposed map)
+  long total;         // N * C * KK * Ho * Wo
+};
+
+template <class T>
+__global__ __launch_bounds__(kThreads) void im2col_k(ColArgs a) {
+  constexpr int VE = 16 / (int)sizeof(T);
+  const T* src = static_cast<const T*>(a.src);
+  T* dst = static_cast<T*>(a.dst);
+  const uint32_t HWo = (uint32_t)(a.Ho * a.Wo), KK = (uint32_t)(a.Kh * a.Kw);
+  const uint32_t total = (uint32_t)a.total;   // < 2^31 (checked on the host)
+  for (uint32_t e0 = (blockIdx.x * kThreads + threadIdx.x) * VE; e0 < total;
+       e0 += gridDim.x * kThreads * VE) {
+    // decode the first element; the following ones advance the position incrementally
+    uint32_t o = e0 % HWo;
+    uint32_t row = e0 / HWo;                  // (n * C + c) * KK + t
+    uint32_t t = row % KK;
+    uint32_t plane = row / KK;                // n * C + c
+    int u = (int)(t / a.Kw), vv = (int)(t - (t / a.Kw) * a.Kw);
+    int oh = (int)(o / a.Wo), ow = (int)(o - (o / a.Wo) * a.Wo);
+    T vals[VE];
+#pragma unroll
+    for (int k = 0; k < VE; ++k) {
+      float v = 0.f;
+      if (e0 + k < total) {
+        int sh, sw;
+        bool ok = true;
+        if (a.gather_input) {
+          sh = oh * a.s - a.p + u * a.dl;
+          sw = ow * a.s - a.p + vv * a.dl;
+        } else {
+          const int nh = oh + a.p - u * a.dl, nw = ow + a.p - vv * a.dl;
+          ok = nh >= 0 && nw >= 0 && nh % a.s == 0 && nw % a.s == 0;
+          sh = nh / a.s;
+          sw = nw / a.s;
+        }
+        if (ok && sh >= 0 && sh < a.Hs && sw >= 0 && sw < a.Ws)
+          v = to_f32(src[((long)plane * a.Hs + sh) * a.Ws + sw]);
+      }
+      vals[k] = from_f32<T>(v);
+      if (++ow == a.Wo) {
+        ow = 0;
+        if (++oh == a.Ho) {
+          oh = 0;
+          if (++vv == a.Kw) {
+            vv = 0;
+            if (++u == a.Kh) { u = 0; ++plane; }
+          }
+        }
+      }
+    }
+    if (e0 + VE <= total) {
+      *reinterpret_cast<uint4*>(dst + e0) = *reinterpret_cast<const uint4*>(vals);
+    } else {
+      for (int k = 0; e0 + k < total; ++k) dst[e0 + k] = vals[k];
+    }
+  }
+}
+
+// wt[(co*KK + t), ci] = w[co, ci, t]
+template <class T>
+__global__ __launch_bounds__(kThreads) void permute_w_k(const T* w, T* wt, int Co, int Ci, int KK) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= Co * Ci * KK) return;
+  const int ci = e % Ci;
+  const int row = e / Ci;
+  const int t = row % KK, co = row / KK;
+  wt[e] = w[((long)co * Ci + ci) * KK + t];
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// dense layers whose column tensors stay below 2^31 elements go through the GEMM path
+bool gemm_path(const Geom& g) {
+  if (g.g != 1) return false;
+  const long lim = 2147483647L;
+  return (long)g.N * g.Ci * g.KK * g.Hy * g.Wy < lim && (long)g.N * g.Co * g.KK * g.H * g.W < lim &&
+         (long)g.Co * g.KK <= 65535L * 16 && (long)g.Ci * g.KK <= 65535L * 16;
+}
+
+bool pointwise_plain(const Geom& g) { return g.KK == 1 && g.s == 1 && g.p == 0; }
+
+Geom wgrad_geom(const Geom& g) {  // Ci*KK "input channels", one "patch" per output pixel
+  Geom q = g;
+  q.Ci = g.Ci * g.KK; q.Cg = q.Ci; q.KK = 1; q.Kh = q.Kw = 1;
+  q.P = g.Hy * g.Wy; q.Hp = g.Hy; q.Wp = g.Wy; q.r = 2; q.s = 1;
+  return q;
+}
+
+Geom dgrad_geom(const Geom& g) {  // Co*KK "output channels", one "patch" per input pixel
+  Geom q = g;
+  q.Co = g.Co * g.KK; q.Og = q.Co; q.KK = 1; q.Kh = q.Kw = 1;
+  q.P = g.H * g.W; q.Hp = g.H; q.Wp = g.W; q.r = 2; q.s = 1; q.rx = 1;
+  return q;
+}
+
+size_t col_bytes(const Geom& g, bool want_gw, bool want_gx) {
+  if (pointwise_plain(g)) return 0;
+  size_t a = want_gw ? (size_t)g.N * g.Ci * g.KK * g.Hy * g.Wy * g.b : 0;
+  size_t c = want_gx ? (size_t)g.N * g.Co * g.KK * g.H * g.W * g.b : 0;
+  return align256(a > c ? a : c);
+}
+
+size_t aux_bytes(const Geom& g, bool want_gw, bool want_gx) {
+  size_t a = 0, c = 0;
+  if (want_gw) {
+    const Geom q = wgrad_geom(g);
+    a = (size_t)mfma_wgrad_splits(q, nullptr) * q.Co * q.Ci * sizeof(float);
+  }
+  if (want_gx) c = pointwise_plain(g) ? 0 : (size_t)g.Co * g.KK * g.Ci * g.b;
+  return align256(a > c ? a : c);
+}
+
+template <class T>
+hipError_t launch_col(const Geom& g, const void* src, void* dst, bool gather_input, hipStream_t st) {
+  ColArgs a;
+  a.src = src; a.dst = dst;
+  a.Kh = g.Kh; a.Kw = g.Kw; a.s = g.s; a.p = g.p; a.dl = g.dl;
+  a.gather_input = gather_input ? 1 : 0;
+  if (gather_input) { a.C = g.Ci; a.Hs = g.H; a.Ws = g.W; a.Ho = g.Hy; a.Wo = g.Wy; }
+  else { a.C = g.Co; a.Hs = g.Hy; a.Ws = g.Wy; a.Ho = g.H; a.Wo = g.W; }
+  a.total = (long)g.N * a.C * g.KK * a.Ho * a.Wo;
+  constexpr int VE = 16 / (int)sizeof(T);
+  long blocks = (a.total / VE + kThreads - 1) / kThreads;
+  if (blocks > (1 << 20)) blocks = 1 << 20;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(im2col_k<T>, dim3((int)blocks), dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
 ExactArgs make_args(const Geom& g) {
   ExactArgs a = {};
   a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.H = g.H; a.W = g.W; a.Kh = g.Kh; a.Kw = g.Kw;
@@ -97,10 +242,33 @@ ExactArgs make_args(const Geom& g) {
 
 }  // namespace
 
-size_t ws_exact(const Geom&, bool, bool) { return 0; }
+size_t ws_exact(const Geom& g, bool want_gw, bool want_gx) {
+  if (!gemm_path(g)) return 0;
+  return col_bytes(g, want_gw, want_gx) + aux_bytes(g, want_gw, want_gx);
+}
 
-hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, float* g_w, void*,
+hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, float* g_w, void* ws,
                               hipStream_t st) {
+  if (gemm_path(g)) {
+    const void* xcol = x;
+    char* wsb = static_cast<char*>(ws);
+    // the workspace may have been sized for both gradients: the aux region follows the larger
+    // column tensor; the partial slabs are placed right behind this call's own column tensor
+    size_t off = 0;
+    if (!pointwise_plain(g)) {
+      hipError_t e = g.dtype == GF_BF16 ? launch_col<bf16_t>(g, x, ws, true, st)
+                                        : launch_col<float>(g, x, ws, true, st);
+      if (e != hipSuccess) return e;
+      xcol = ws;
+      off = align256((size_t)g.N * g.Ci * g.KK * g.Hy * g.Wy * g.b);
+    }
+    const Geom q = wgrad_geom(g);
+    float* part = reinterpret_cast<float*>(wsb + off);
+    int nz = 0;
+    hipError_t e = launch_mfma_wgrad(q, xcol, g_y, part, &nz, st);
+    if (e != hipSuccess) return e;
+    return launch_finalize(part, g_w, q.Co * q.Ci, nz, 1, 1.f, st);
+  }
   ExactArgs a = make_args(g);
   a.x = x;
   a.gy = g_y;
@@ -113,8 +281,27 @@ hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, flo
   return hipGetLastError();
 }
 
-hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, void* g_x, void*,
+hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, void* g_x, void* ws,
                               hipStream_t st) {
+  if (gemm_path(g)) {
+    const Geom q = dgrad_geom(g);
+    if (pointwise_plain(g)) return launch_mfma_dgrad(q, g_y, w, nullptr, g_x, nullptr, st);
+    char* wsb = static_cast<char*>(ws);
+    hipError_t e = g.dtype == GF_BF16 ? launch_col<bf16_t>(g, g_y, ws, false, st)
+                                      : launch_col<float>(g, g_y, ws, false, st);
+    if (e != hipSuccess) return e;
+    void* wt = wsb + align256((size_t)g.N * g.Co * g.KK * g.H * g.W * g.b);
+    const int tot = g.Co * g.Ci * g.KK;
+    if (g.dtype == GF_BF16)
+      hipLaunchKernelGGL(permute_w_k<bf16_t>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
+                         static_cast<const bf16_t*>(w), static_cast<bf16_t*>(wt), g.Co, g.Ci, g.KK);
+    else
+      hipLaunchKernelGGL(permute_w_k<float>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
+                         static_cast<const float*>(w), static_cast<float*>(wt), g.Co, g.Ci, g.KK);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_mfma_dgrad(q, ws, wt, nullptr, g_x, nullptr, st);
+  }
   ExactArgs a = make_args(g);
   a.w = w;
   a.gy = g_y;

@@ -279,6 +279,9 @@ EXACT_CASES = [
     (2, 6, 8, 9, 9, 3, 1, 1, 1, 1), (2, 8, 8, 14, 14, 3, 2, 1, 1, 1), (1, 8, 8, 12, 12, 3, 1, 4, 4, 1),
     (2, 12, 12, 10, 10, 3, 1, 1, 1, 12), (2, 8, 12, 14, 14, 3, 2, 1, 1, 4), (3, 10, 7, 6, 8, 1, 1, 0, 1, 1),
     (1, 4, 4, 11, 11, 5, 1, 2, 1, 1), (1, 5, 6, 8, 8, 3, 1, 0, 1, 1), (1, 16, 16, 16, 16, 3, 1, 1, 1, 1),
+    (3, 72, 136, 14, 14, 3, 1, 1, 1, 1), (2, 64, 96, 7, 7, 3, 1, 1, 1, 1), (2, 40, 80, 14, 14, 3, 2, 1, 1, 1),
+    (2, 32, 48, 24, 24, 3, 1, 6, 6, 1), (4, 130, 70, 8, 8, 1, 1, 0, 1, 1), (2, 256, 288, 16, 16, 3, 1, 1, 1, 1),
+    (1, 24, 24, 56, 56, 1, 1, 0, 1, 1), (2, 16, 24, 9, 7, 3, 2, 1, 1, 1),
 ]
 
 
