@@ -552,16 +552,16 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
     return;
   }
   if (a.full) {
-    // one 16-byte run of output pixels per step: row ci, sub-row i of the patch, pixel run q0..
+    // one item = (row ci, one 16-byte run of output pixels): the few patch values the run needs
+    // are read from LDS once and the same vector is stored to the rx pixel rows of the patch row
     // (host guarantees rx | VE or VE | rx, W == Wp * rx, W % VE == 0, Wp * rx % VE == 0)
     T* out = static_cast<T*>(a.full);
     const int rx = a.rx;
-    const int vprow = BN * rx / VE;          // vectors per (row, sub-row)
-    const int per_row = rx * vprow;
-    for (int s = tid; s < BM * per_row; s += kThreads) {
-      const int row = s / per_row;
-      const int t = s - row * per_row;
-      const int i = t / vprow, ov = t - i * vprow;
+    const int vprow = BN * rx / VE;          // vectors per tile row
+    const int vshift = 31 - __builtin_clz(vprow);  // BN, rx, VE are powers of two
+    for (int s = tid; s < BM * vprow; s += kThreads) {
+      const int row = s >> vshift;
+      const int ov = s & (vprow - 1);
       const int q0 = ov * VE;                // first output pixel of the run, tile-relative
       const int col = q0 / rx;               // first patch column of the run
       const int ci = m0 + row, j = j0 + col;
@@ -570,8 +570,6 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
       const int p = j - n * a.P;
       const int hp = (int)a.d_wp.div((uint32_t)p);
       const int wp = p - hp * a.Wp;
-      const int h = hp * rx + i;
-      if (h >= a.H) continue;
       T vals[VE];
       const T* src = Cs + row * SC + col;
       if (rx >= VE) {
@@ -581,8 +579,11 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
 #pragma unroll
         for (int e = 0; e < VE; ++e) vals[e] = src[e / rx];
       }
-      T* d = out + (((long)n * a.Ci + ci) * a.H + h) * a.W + wp * rx + (q0 - col * rx);
-      *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(vals);
+      const uint4 vec = *reinterpret_cast<const uint4*>(vals);
+      const int h0 = hp * rx;
+      const int nrows = min(rx, a.H - h0);
+      T* d = out + (((long)n * a.Ci + ci) * a.H + h0) * a.W + wp * rx + (q0 - col * rx);
+      for (int i = 0; i < nrows; ++i) *reinterpret_cast<uint4*>(d + (long)i * a.W) = vec;
     }
     return;
   }
