@@ -884,6 +884,15 @@ bool mfma_dgrad_writes_full(const Geom& g) {
   return runs || dgrad_planes_ok(g);
 }
 
+// images per column tile when tiles are whole images: as many as fit, but few enough to
+// leave ~512 blocks for the chip (small maps with a small batch would otherwise run on a
+// handful of CUs)
+static int images_per_tile(const Geom& g, int bn, int bm) {
+  int ipt = bn / g.P;
+  while (ipt > 1 && (long)cdiv(g.N, ipt) * cdiv(g.Ci, bm) < 512) --ipt;
+  return ipt;
+}
+
 template <class T>
 static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
                           void* full, hipStream_t st) {
@@ -930,7 +939,7 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   if (planes) {  // small / unaligned maps: whole images per column tile
     const int bn = (ksplit && g.P <= 32) ? 32 : 64;
     a.planes_mode = 1;
-    a.ipt = bn / g.P;
+    a.ipt = images_per_tile(g, bn, ksplit ? 32 : 64);
     a.cols_per_tile = a.ipt * g.P;
     a.rows_per_pass = (kPlaneStageBytes - 32) / (g.H * g.W * (int)sizeof(T));
     if (ksplit) return bn == 32 ? dgrad_ksplit_launch<T, 32>(a, vec, st) : dgrad_ksplit_launch<T, 64>(a, vec, st);
@@ -940,7 +949,7 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   if (flatb) {  // reduced map out, whole-image column tiles
     a.flatb = 1;
     a.planes_mode = 0;
-    a.ipt = 64 / g.P;
+    a.ipt = images_per_tile(g, 64, 64);
     a.cols_per_tile = a.ipt * g.P;
     return dgrad_launch<T, 2, 2, 2, 2>(a, false, st);
   }

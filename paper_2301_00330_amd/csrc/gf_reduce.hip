@@ -207,7 +207,7 @@ template <class T, int Q>
 hipError_t launch_rows(ReduceArgs& a, hipStream_t st) {
   constexpr int VE = Vec16<T>::N;
   constexpr int IW = VE > Q ? VE : Q;
-  constexpr int U = (Q >= 8) ? 1 : 2;  // vectors in flight per lane: U * Q * VW
+  constexpr int U = (Q >= 8) ? 1 : 2;  // vectors in flight per lane: U * Q * VW (U = 4 measured slower)
   a.ipr = a.W / IW;
   a.total_items = a.total_strips * a.ipr;
   a.d_ipr = FastDiv((uint32_t)a.ipr);
