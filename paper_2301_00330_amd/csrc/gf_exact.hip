@@ -162,6 +162,48 @@ __global__ __launch_bounds__(kThreads) void im2col_k(ColArgs a) {
   }
 }
 
+// Stride-1 layers with W_o a multiple of the vector length: a 16-byte vector of the column tensor
+// is 8 (4) consecutive pixels of one source row, shifted by the tap offset and clipped at the row
+// ends.  One index decode per vector, FastDiv instead of divisions.
+struct ColRowsArgs {
+  const void* src;
+  void* dst;
+  int Hs, Ws, Ho, Wo, Kw;
+  int dh0, dw0, dstep;   // source row = oh + dh0 + u * dstep, source col = ow + dw0 + v * dstep
+  int vpr;               // vectors per column-tensor row of Wo pixels
+  uint32_t total_vec;
+  FastDiv d_vpr, d_ho, d_kk, d_kw;
+};
+
+template <class T>
+__global__ __launch_bounds__(kThreads) void im2col_rows_k(ColRowsArgs a) {
+  constexpr int VE = 16 / (int)sizeof(T);
+  const T* src = static_cast<const T*>(a.src);
+  T* dst = static_cast<T*>(a.dst);
+  for (uint32_t vi = blockIdx.x * kThreads + threadIdx.x; vi < a.total_vec; vi += gridDim.x * kThreads) {
+    const uint32_t rowid = a.d_vpr.div(vi);            // ((plane * KK + t) * Ho + oh)
+    const int ow0 = (int)(vi - rowid * a.vpr) * VE;
+    const uint32_t pt = a.d_ho.div(rowid);             // plane * KK + t
+    const int oh = (int)(rowid - pt * a.Ho);
+    const uint32_t plane = a.d_kk.div(pt);
+    const int t = (int)(pt - plane * a.d_kk.d);
+    const int u = (int)a.d_kw.div((uint32_t)t), v = t - u * a.Kw;
+    const int sh = oh + a.dh0 + u * a.dstep;
+    const int sw0 = ow0 + a.dw0 + v * a.dstep;
+    const bool row_ok = sh >= 0 && sh < a.Hs;
+    const T* p = src + ((long)plane * a.Hs + (row_ok ? sh : 0)) * a.Ws;
+    T vals[VE];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) {
+      const int sw = sw0 + e;
+      const bool ok = row_ok && sw >= 0 && sw < a.Ws;
+      const T val = p[ok ? sw : 0];
+      vals[e] = ok ? val : from_f32<T>(0.f);
+    }
+    *reinterpret_cast<uint4*>(dst + (long)vi * VE) = *reinterpret_cast<const uint4*>(vals);
+  }
+}
+
 // wt[(co*KK + t), ci] = w[co, ci, t]
 template <class T>
 __global__ __launch_bounds__(kThreads) void permute_w_k(const T* w, T* wt, int Co, int Ci, int KK) {
@@ -226,6 +268,24 @@ hipError_t launch_col(const Geom& g, const void* src, void* dst, bool gather_inp
   else { a.C = g.Co; a.Hs = g.Hy; a.Ws = g.Wy; a.Ho = g.H; a.Wo = g.W; }
   a.total = (long)g.N * a.C * g.KK * a.Ho * a.Wo;
   constexpr int VE = 16 / (int)sizeof(T);
+  if (g.s == 1 && a.Wo % VE == 0) {
+    ColRowsArgs r;
+    r.src = src; r.dst = dst; r.Hs = a.Hs; r.Ws = a.Ws; r.Ho = a.Ho; r.Wo = a.Wo; r.Kw = g.Kw;
+    // forward map: source = o - p + tap * d;  transposed map: source = o + p - tap * d
+    r.dh0 = gather_input ? -g.p : g.p;
+    r.dw0 = r.dh0;
+    r.dstep = gather_input ? g.dl : -g.dl;
+    r.vpr = a.Wo / VE;
+    r.total_vec = (uint32_t)(a.total / VE);
+    r.d_vpr = FastDiv((uint32_t)r.vpr);
+    r.d_ho = FastDiv((uint32_t)a.Ho);
+    r.d_kk = FastDiv((uint32_t)g.KK);
+    r.d_kw = FastDiv((uint32_t)g.Kw);
+    long nb = ((long)r.total_vec + kThreads - 1) / kThreads;
+    if (nb > (1 << 20)) nb = 1 << 20;
+    hipLaunchKernelGGL(im2col_rows_k<T>, dim3((int)nb), dim3(kThreads), 0, st, r);
+    return hipGetLastError();
+  }
   long blocks = (a.total / VE + kThreads - 1) / kThreads;
   if (blocks > (1 << 20)) blocks = 1 << 20;
   if (blocks < 1) blocks = 1;

@@ -773,17 +773,23 @@ hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   return hipGetLastError();
 }
 
-// tile shape of the weight-gradient GEMM: 0 = 64x64, 1 = 128 (co) x 32 (ci), 2 = 32 x 128
-// (a 128 x 128 tile with 4 x 4 MFMA tiles per wave was measured slower than 64 x 64 on the
-// 256 x 2048 x 8192 problem: 55 us against 33 us)
+// tile shape of the weight-gradient GEMM: 0 = 64x64, 1 = 128 (co) x 32 (ci), 2 = 32 x 128,
+// 4 = 256 x 64.  The last one is for a second operand too large for the caches (the column
+// tensors of exact BP): every row tile re-reads it from HBM, so all 256 rows go into one tile.
+// (A 128 x 128 tile with 4 x 4 MFMA tiles per wave was measured no faster than 64 x 64.)
+constexpr long kHugeOperandBytes = 96L << 20;
+
 int wgrad_shape(const Geom& g) {
   if (g.Ci <= 32 && g.Co > 64) return 1;
   if (g.Co <= 32 && g.Ci > 64) return 2;
+  if (g.Co >= 256 && g.Ci >= 256 && g.P % (16 / g.b) == 0 &&
+      (long)g.N * g.P * g.Ci * g.b >= kHugeOperandBytes)
+    return 4;
   return 0;
 }
 
 void wgrad_tile(int shape, int* bm, int* bn) {
-  *bm = shape == 1 ? 128 : shape == 2 ? 32 : 64;
+  *bm = shape == 1 ? 128 : shape == 2 ? 32 : shape == 4 ? 256 : 64;
   *bn = shape == 1 ? 32 : shape == 2 ? 128 : 64;
 }
 
@@ -842,6 +848,7 @@ static hipError_t wgrad_t(const Geom& g, const void* x_u, const void* gy_u, floa
   switch (wgrad_shape(g)) {
     case 1: return wgrad_launch<T, 2, 2, 4, 1>(a, nz, vec, st);
     case 2: return wgrad_launch<T, 2, 2, 1, 4>(a, nz, vec, st);
+    case 4: return wgrad_launch<T, 4, 4, 4, 1>(a, nz, vec, st);
     default: return wgrad_launch<T, 2, 2, 2, 2>(a, nz, vec, st);
   }
 }
@@ -955,6 +962,8 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   }
   if (ksplit) return dgrad_ksplit_launch<T, 64>(a, vec, st);
   if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);
+  if (vec && g.Ci >= 256 && !full && (long)g.N * g.P * g.Co * g.b >= kHugeOperandBytes)
+    return dgrad_launch<T, 4, 4, 4, 1>(a, vec, st);  // huge gy_u (column tensor): read it once
   return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
 }
 
