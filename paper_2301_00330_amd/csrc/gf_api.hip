@@ -233,6 +233,13 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
   void* gyu = gy_u ? gy_u : static_cast<void*>(wsb);
   rc = dev(launch_patch_reduce(g_y, gyu, (long)g.N * g.Co, g.Hy, g.Wy, g.r, true, g.dtype, st));
   if (rc) return rc;
+  if (mfma_s3s4_ok(g)) {  // dense, aligned: weight and input gradient share one launch
+    float* part = reinterpret_cast<float*>(wsb + off_w);
+    int nzs = 0;
+    rc = dev(launch_mfma_s3s4(g, x_u, gyu, w, wsb + off_i, part, &nzs, g_x, st));
+    if (rc) return rc;
+    return dev(launch_finalize(part, g_w, g.Co * g.Ci, nzs, g.KK, 1.f / ((float)g.s * (float)g.s), st));
+  }
   rc = dev(launch_gf_bwd_weight(g, x_u, gyu, g_w, wsb + off_w, st));
   if (rc) return rc;
   return dev(launch_gf_bwd_input(g, gyu, w, g_x, false, wsb + off_i, st));

@@ -122,6 +122,10 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
                              int* nz_out, hipStream_t st);
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
                              void* full, hipStream_t st);
+// both gradients of a dense layer in one launch (then launch_finalize on `part`, nz slabs)
+bool mfma_s3s4_ok(const Geom& g);
+hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
+                            void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st);
 // true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
 bool mfma_dgrad_writes_full(const Geom& g);
 

@@ -180,20 +180,20 @@ __device__ __forceinline__ void flat_stage_kstrided(uint32_t* tile, const uint4*
   }
 }
 
+// block (bx, by, bz) = (c_i tile, c_o tile, K slab); As / Bs: LDS tiles of BM resp. BN staged rows
 template <class T, int TM, int TN, int WM, int WN, bool VEC>
-__global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
+__device__ __forceinline__ void wgrad_body(const WgradMfmaArgs& a, int bx, int by, int bz,
+                                           unsigned char* As, unsigned char* Bs) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
   constexpr int BK = Mma<T>::BK, VE = Mma<T>::VE, KSTEP = Mma<T>::KSTEP;
   constexpr int LA = BM / 32, LB = BN / 32;  // 16-byte loads per lane and chunk
   static_assert(WM * WN == 4 && BM % 32 == 0 && BN % 32 == 0, "tile shape");
-  __shared__ __attribute__((aligned(16))) unsigned char As[BM * kRowBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * kRowBytes];
   const T* gyu = static_cast<const T*>(a.gyu);
   const T* xu = static_cast<const T*>(a.xu);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int kc0 = blockIdx.z * a.chunks_per_z;
+  const int m0 = by * BM, n0 = bx * BN;
+  const int kc0 = bz * a.chunks_per_z;
   const int kc1 = min(kc0 + a.chunks_per_z, a.nchunks);
 
   uint4 ra[LA], rb[LB];
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
     __syncthreads();
   }
   // D[i = 4 * (lane / 16) + v][j = lane % 16] of every 16 x 16 tile
-  float* dst = a.part + (long)blockIdx.z * a.Co * a.Ci;
+  float* dst = a.part + (long)bz * a.Co * a.Ci;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -299,6 +299,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
         if (co < a.Co && ci < a.Ci) dst[(long)co * a.Ci + ci] = acc[i][j][v];
       }
     }
+}
+
+template <class T, int TM, int TN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(kThreads) void wgrad_mfma_k(WgradMfmaArgs a) {
+  constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
+  __shared__ __attribute__((aligned(16))) unsigned char As[BM * kRowBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * kRowBytes];
+  wgrad_body<T, TM, TN, WM, WN, VEC>(a, blockIdx.x, blockIdx.y, blockIdx.z, As, Bs);
 }
 
 // ---------------------------------------------------------------------------
@@ -375,8 +383,20 @@ __device__ __forceinline__ void dgrad_stage(uint32_t* tile, const uint4* rg, int
   }
 }
 
+// LDS words the input-gradient block needs for its operand tiles / output tile
+template <class T, int BM, int BN>
+constexpr int dgrad_smem_words() {
+  constexpr int SC = BN + 16 / (int)sizeof(T);
+  constexpr int tile = 32 * (BM + 4 + BN + 4);
+  constexpr int out = (BM * SC * (int)sizeof(T) + 3) / 4;
+  return tile > out ? tile : out;
+}
+
+// block (bx, by) = (column tile, c_i tile); smem: dgrad_smem_words() words; Es: plane staging
+// buffer (only touched in plane mode)
 template <class T, int TM, int TN, int WM, int WN, bool VEC>
-__global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
+__device__ __forceinline__ void dgrad_body(const DgradMfmaArgs& a, int bx, int by, uint32_t* smem,
+                                           unsigned char* Es) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
   constexpr int BK = Mma<T>::BK, VE = Mma<T>::VE;
   constexpr int SA = BM + 4, SB = BN + 4;  // word strides of the two tiles (multiples of 4)
@@ -384,18 +404,14 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
   constexpr int PA = (32 * BM / VE + kThreads - 1) / kThreads * RPS;
   constexpr int PB = (32 * BN / VE + kThreads - 1) / kThreads * RPS;
   constexpr int SC = BN + 16 / (int)sizeof(T);  // element stride of the output staging tile
-  constexpr int kTileWords = 32 * (SA + SB);
-  constexpr int kOutWords = (BM * SC * (int)sizeof(T) + 3) / 4;
-  __shared__ __attribute__((aligned(16))) uint32_t smem[kTileWords > kOutWords ? kTileWords : kOutWords];
-  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
   uint32_t* As = smem;
   uint32_t* Bs = smem + 32 * SA;
   const T* gyu = static_cast<const T*>(a.gyu);
   const T* wt = static_cast<const T*>(a.wt);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int m0 = blockIdx.y * BM;  // first c_i
-  const int j0 = blockIdx.x * a.cols_per_tile;  // first flat column (n, p)
+  const int m0 = by * BM;  // first c_i
+  const int j0 = bx * a.cols_per_tile;  // first flat column (n, p)
   const int jend = min(a.Jtot, j0 + a.cols_per_tile);
 
   auto load_a = [&](int k, int col) -> uint4 {  // wt[k][m0 + col ..]
@@ -430,7 +446,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
     __syncthreads();
   }
   auto fetch_b = [&](int k0) {
-    if (flatb) flat_fetch<T, BK, PB>(rb, gyu, a.Co, k0, blockIdx.x, a.P, a.ipt, a.N, tid);
+    if (flatb) flat_fetch<T, BK, PB>(rb, gyu, a.Co, k0, bx, a.P, a.ipt, a.N, tid);
     else dgrad_fetch<T, BN, VEC>(rb, tid, k0, a.Co, load_b);
   };
   dgrad_fetch<T, BM, VEC>(ra, tid, 0, a.Co, load_a);
@@ -493,14 +509,22 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
         Cs[row * SC + col] = from_f32<T>(acc[i][j][v] * a.scale);
       }
   __syncthreads();
-  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, m0, j0, jend, tid);
+  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, bx, m0, j0, jend, tid);
+}
+
+template <class T, int TM, int TN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(kThreads) void dgrad_mfma_k(DgradMfmaArgs a) {
+  constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
+  __shared__ __attribute__((aligned(16))) uint32_t smem[dgrad_smem_words<T, BM, BN>()];
+  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
+  dgrad_body<T, TM, TN, WM, WN, VEC>(a, blockIdx.x, blockIdx.y, smem, Es);
 }
 
 // Store the finished tile Cs[BM][SC] (already rounded to the storage type): as the reduced map,
 // as 16-byte pixel runs at full resolution, or plane by plane through the LDS image Es.
 template <class T, int BM, int BN, bool VEC>
 __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* Cs, unsigned char* Es,
-                                               int m0, int j0, int jend, int tid) {
+                                               int bx, int m0, int j0, int jend, int tid) {
   constexpr int VE = Mma<T>::VE;
   constexpr int SC = BN + 16 / (int)sizeof(T);
   if (a.planes_mode) {
@@ -510,7 +534,7 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
     // ends, which neighbouring tiles share, go out element by element.
     T* out = static_cast<T*>(a.full);
     const int HW = a.H * a.W, rx = a.rx;
-    const int n0 = blockIdx.x * a.ipt;
+    const int n0 = bx * a.ipt;
     const int nimg = (jend - j0) / a.P;
     const int rows_valid = min(BM, a.Ci - m0);
     for (int il = 0; il < nimg; ++il)
@@ -739,7 +763,37 @@ __global__ __launch_bounds__(kThreads) void dgrad_ksplit_k(DgradMfmaArgs a) {
     Cs[(e / BN) * SC + (e % BN)] = from_f32<T>(s * a.scale);
   }
   __syncthreads();
-  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, m0, j0, jend, tid);
+  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, blockIdx.x, m0, j0, jend, tid);
+}
+
+// ---------------------------------------------------------------------------
+// Weight and input gradient of one layer in ONE launch: both only depend on gy_u, so the
+// first `nw` blocks of the grid run weight-gradient tiles and the rest input-gradient tiles.
+// The short, latency-bound K loops of the former overlap with the store-bound epilogues of
+// the latter, and one launch ramp is saved.
+// ---------------------------------------------------------------------------
+struct S3S4Grid {
+  int nw, wgx, wgy, dgx;
+};
+
+template <class T, int WTM, int WTN, int WWM, int WWN, int DTM, int DTN, int DWM, int DWN>
+__global__ __launch_bounds__(kThreads) void s3s4_mfma_k(WgradMfmaArgs wa, DgradMfmaArgs da, S3S4Grid g) {
+  constexpr int WBM = WWM * WTM * 16, WBN = WWN * WTN * 16;
+  constexpr int DBM = DWM * DTM * 16, DBN = DWN * DTN * 16;
+  constexpr int kWBytes = (WBM + WBN) * kRowBytes;
+  constexpr int kDBytes = dgrad_smem_words<T, DBM, DBN>() * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kWBytes > kDBytes ? kWBytes : kDBytes];
+  const int b = blockIdx.x;
+  if (b < g.nw) {
+    const int bx = b % g.wgx;
+    const int t = b / g.wgx;
+    wgrad_body<T, WTM, WTN, WWM, WWN, true>(wa, bx, t % g.wgy, t / g.wgy, smem, smem + WBM * kRowBytes);
+  } else {
+    const int q = b - g.nw;
+    // pixel-run epilogue only: the plane staging buffer is never touched
+    dgrad_body<T, DTM, DTN, DWM, DWN, true>(da, q % g.dgx, q / g.dgx, reinterpret_cast<uint32_t*>(smem),
+                                            nullptr);
+  }
 }
 
 // kernel sum rounded to the storage type, [Co][Ci] (text after Eq. 3)
@@ -900,18 +954,32 @@ static int images_per_tile(const Geom& g, int bn, int bm) {
   return ipt;
 }
 
+// S2 when the kernel is larger than 1x1: its spatial sum, rounded to the storage type
+template <class T>
+static hipError_t kernel_sum_if_needed(const Geom& g, const void* w, void* wsum_t, const T** wt,
+                                       hipStream_t st) {
+  *wt = static_cast<const T*>(w);
+  if (g.KK == 1) return hipSuccess;
+  const int pairs = g.Co * g.Ci;
+  hipLaunchKernelGGL(kernel_sum_t_k<T>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st,
+                     static_cast<const T*>(w), static_cast<T*>(wsum_t), pairs, g.KK);
+  *wt = static_cast<const T*>(wsum_t);
+  return hipGetLastError();
+}
+
+template <class T>
+static bool dgrad_wants_ksplit(const Geom& g, bool planes) {
+  const bool vec = g.P % Mma<T>::VE == 0 && g.Ci % Mma<T>::VE == 0;
+  const long tiles64 = (long)cdiv((long)g.N * g.P, planes ? (64 / g.P) * g.P : 64) * cdiv(g.Ci, 64);
+  return vec && g.Co >= 512 && tiles64 < 512;
+}
+
 template <class T>
 static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
                           void* full, hipStream_t st) {
-  const T* wt = static_cast<const T*>(w);
-  if (g.KK > 1) {  // S2: the kernel's spatial sum, rounded to the storage type
-    const int pairs = g.Co * g.Ci;
-    hipLaunchKernelGGL(kernel_sum_t_k<T>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st,
-                       static_cast<const T*>(w), static_cast<T*>(wsum_t), pairs, g.KK);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    wt = static_cast<const T*>(wsum_t);
-  }
+  const T* wt = nullptr;
+  hipError_t e0 = kernel_sum_if_needed<T>(g, w, wsum_t, &wt, st);
+  if (e0 != hipSuccess) return e0;
   DgradMfmaArgs a;
   a.gyu = gy_u;
   a.wt = wt;
@@ -941,8 +1009,7 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   const bool planes = full && !dgrad_full_ok<T>(g);
   // few 64 x 64 tiles and a long K: let the four waves of a block split K instead
   // (measured: pays from K = 512 up; at K = 320 .. 576 with many tiles it is slower)
-  const long tiles64 = (long)cdiv(a.Jtot, planes ? (64 / g.P) * g.P : 64) * cdiv(g.Ci, 64);
-  const bool ksplit = vec && g.Co >= 512 && tiles64 < 512;
+  const bool ksplit = dgrad_wants_ksplit<T>(g, planes);
   if (planes) {  // small / unaligned maps: whole images per column tile
     const int bn = (ksplit && g.P <= 32) ? 32 : 64;
     a.planes_mode = 1;
@@ -965,6 +1032,71 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   if (vec && g.Ci >= 256 && !full && (long)g.N * g.P * g.Co * g.b >= kHugeOperandBytes)
     return dgrad_launch<T, 4, 4, 4, 1>(a, vec, st);  // huge gy_u (column tensor): read it once
   return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
+}
+
+// both gradients in one launch; shapes: vector loads for every operand, pixel-run epilogue
+template <class T>
+static bool s3s4_ok(const Geom& g) {
+  constexpr int VE = Mma<T>::VE;
+  if (g.g != 1 || g.P % VE != 0 || g.Ci % VE != 0) return false;
+  if (!dgrad_full_ok<T>(g) || dgrad_wants_ksplit<T>(g, false)) return false;
+  if (wgrad_shape(g) == 4) return false;
+  return true;
+}
+
+bool mfma_s3s4_ok(const Geom& g) { return g.dtype == GF_BF16 ? s3s4_ok<bf16_t>(g) : s3s4_ok<float>(g); }
+
+template <class T, int WTM, int WTN, int WWM, int WWN>
+static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& da, int nz, hipStream_t st) {
+  constexpr int WBM = WWM * WTM * 16, WBN = WWN * WTN * 16;
+  S3S4Grid gr;
+  gr.wgx = cdiv(g.Ci, WBN);
+  gr.wgy = cdiv(g.Co, WBM);
+  gr.nw = gr.wgx * gr.wgy * nz;
+  da.cols_per_tile = g.Ci <= 32 ? 128 : 64;
+  gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
+  const int nd = gr.dgx * cdiv(g.Ci, g.Ci <= 32 ? 32 : 64);
+  if (g.Ci <= 32)
+    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
+  else
+    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
+  return hipGetLastError();
+}
+
+template <class T>
+static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const void* w, void* wsum_t,
+                         float* part, int* nz_out, void* g_x, hipStream_t st) {
+  const T* wt = nullptr;
+  hipError_t e = kernel_sum_if_needed<T>(g, w, wsum_t, &wt, st);
+  if (e != hipSuccess) return e;
+  WgradMfmaArgs wa;
+  wa.gyu = gy_u; wa.xu = x_u; wa.part = part;
+  wa.Ci = g.Ci; wa.Co = g.Co; wa.P = g.P; wa.Ktot = g.N * g.P;
+  wa.nchunks = wgrad_chunks(g);
+  wa.N = g.N; wa.G = 1; wa.flat = 0;
+  const int nz = mfma_wgrad_splits(g, &wa.chunks_per_z);
+  wa.d_p = FastDiv((uint32_t)g.P);
+  *nz_out = nz;
+  DgradMfmaArgs da;
+  da.gyu = gy_u; da.wt = wt; da.dst = nullptr;
+  da.Ci = g.Ci; da.Co = g.Co; da.P = g.P; da.Jtot = g.N * g.P;
+  da.scale = 1.f / ((float)g.s * (float)g.s);
+  da.d_p = FastDiv((uint32_t)g.P);
+  da.full = g_x; da.H = g.H; da.W = g.W; da.Wp = g.Wp; da.rx = g.rx;
+  da.d_wp = FastDiv((uint32_t)g.Wp);
+  da.planes_mode = 0; da.ipt = 0; da.cols_per_tile = 0; da.rows_per_pass = 0;
+  da.N = g.N; da.veca = 1; da.flatb = 0;
+  switch (wgrad_shape(g)) {
+    case 1: return s3s4_launch<T, 2, 2, 4, 1>(g, wa, da, nz, st);
+    case 2: return s3s4_launch<T, 2, 2, 1, 4>(g, wa, da, nz, st);
+    default: return s3s4_launch<T, 2, 2, 2, 2>(g, wa, da, nz, st);
+  }
+}
+
+hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
+                            void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st) {
+  if (g.dtype == GF_BF16) return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st);
+  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st);
 }
 
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
