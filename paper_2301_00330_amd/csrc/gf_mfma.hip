@@ -776,23 +776,25 @@ struct S3S4Grid {
   int nw, wgx, wgy, dgx;
 };
 
-template <class T, int WTM, int WTN, int WWM, int WWN, int DTM, int DTN, int DWM, int DWN>
+// VEC: vector loads of every operand (else the image-block loaders); PLANES: the input
+// gradient stores whole planes through the LDS staging buffer (small / unaligned maps)
+template <class T, int WTM, int WTN, int WWM, int WWN, int DTM, int DTN, int DWM, int DWN, bool VEC,
+          bool PLANES>
 __global__ __launch_bounds__(kThreads) void s3s4_mfma_k(WgradMfmaArgs wa, DgradMfmaArgs da, S3S4Grid g) {
   constexpr int WBM = WWM * WTM * 16, WBN = WWN * WTN * 16;
   constexpr int DBM = DWM * DTM * 16, DBN = DWN * DTN * 16;
   constexpr int kWBytes = (WBM + WBN) * kRowBytes;
   constexpr int kDBytes = dgrad_smem_words<T, DBM, DBN>() * 4;
   __shared__ __attribute__((aligned(16))) unsigned char smem[kWBytes > kDBytes ? kWBytes : kDBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Es[PLANES ? kPlaneStageBytes : 16];
   const int b = blockIdx.x;
   if (b < g.nw) {
     const int bx = b % g.wgx;
     const int t = b / g.wgx;
-    wgrad_body<T, WTM, WTN, WWM, WWN, true>(wa, bx, t % g.wgy, t / g.wgy, smem, smem + WBM * kRowBytes);
+    wgrad_body<T, WTM, WTN, WWM, WWN, VEC>(wa, bx, t % g.wgy, t / g.wgy, smem, smem + WBM * kRowBytes);
   } else {
     const int q = b - g.nw;
-    // pixel-run epilogue only: the plane staging buffer is never touched
-    dgrad_body<T, DTM, DTN, DWM, DWN, true>(da, q % g.dgx, q / g.dgx, reinterpret_cast<uint32_t*>(smem),
-                                            nullptr);
+    dgrad_body<T, DTM, DTN, DWM, DWN, VEC>(da, q % g.dgx, q / g.dgx, reinterpret_cast<uint32_t*>(smem), Es);
   }
 }
 
@@ -1034,13 +1036,20 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   return dgrad_launch<T, 2, 2, 2, 2>(a, vec, st);
 }
 
-// both gradients in one launch; shapes: vector loads for every operand, pixel-run epilogue
+// both gradients in one launch: every shape the 64 x 64 (or 32 x 128) input-gradient block handles
+// without splitting K among its waves
 template <class T>
 static bool s3s4_ok(const Geom& g) {
   constexpr int VE = Mma<T>::VE;
-  if (g.g != 1 || g.P % VE != 0 || g.Ci % VE != 0) return false;
-  if (!dgrad_full_ok<T>(g) || dgrad_wants_ksplit<T>(g, false)) return false;
+  if (g.g != 1 || g.Ci % VE != 0) return false;
   if (wgrad_shape(g) == 4) return false;
+  const bool runs = dgrad_full_ok<T>(g);
+  if (!runs && !dgrad_planes_ok(g)) return false;
+  if (dgrad_wants_ksplit<T>(g, !runs)) return false;
+  if (g.P % VE != 0) {  // image-block loaders on both sides
+    if (runs || !wgrad_flat(g, nullptr)) return false;
+    if (g.P > 64 || ((long)g.Co * g.P * sizeof(T)) % 16 != 0) return false;
+  }
   return true;
 }
 
@@ -1053,13 +1062,23 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
   gr.wgx = cdiv(g.Ci, WBN);
   gr.wgy = cdiv(g.Co, WBM);
   gr.nw = gr.wgx * gr.wgy * nz;
+  const bool vec = g.P % Mma<T>::VE == 0;
+  if (da.planes_mode) {
+    gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
+    const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 64);
+    if (vec)
+      hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+    else
+      hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+    return hipGetLastError();
+  }
   da.cols_per_tile = g.Ci <= 32 ? 128 : 64;
   gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
   const int nd = gr.dgx * cdiv(g.Ci, g.Ci <= 32 ? 32 : 64);
   if (g.Ci <= 32)
-    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
+    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, true, false>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
   else
-    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
+    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, false>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
   return hipGetLastError();
 }
 
@@ -1073,7 +1092,8 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
   wa.gyu = gy_u; wa.xu = x_u; wa.part = part;
   wa.Ci = g.Ci; wa.Co = g.Co; wa.P = g.P; wa.Ktot = g.N * g.P;
   wa.nchunks = wgrad_chunks(g);
-  wa.N = g.N; wa.G = 1; wa.flat = 0;
+  wa.N = g.N; wa.G = 1;
+  wa.flat = wgrad_flat(g, &wa.G) ? 1 : 0;
   const int nz = mfma_wgrad_splits(g, &wa.chunks_per_z);
   wa.d_p = FastDiv((uint32_t)g.P);
   *nz_out = nz;
@@ -1086,6 +1106,13 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
   da.d_wp = FastDiv((uint32_t)g.Wp);
   da.planes_mode = 0; da.ipt = 0; da.cols_per_tile = 0; da.rows_per_pass = 0;
   da.N = g.N; da.veca = 1; da.flatb = 0;
+  if (!dgrad_full_ok<T>(g)) {  // plane mode, as in dgrad_t
+    da.planes_mode = 1;
+    da.ipt = images_per_tile(g, 64, 64);
+    da.cols_per_tile = da.ipt * g.P;
+    da.rows_per_pass = (kPlaneStageBytes - 32) / (g.H * g.W * (int)sizeof(T));
+    da.flatb = g.P % Mma<T>::VE != 0 ? 1 : 0;
+  }
   switch (wgrad_shape(g)) {
     case 1: return s3s4_launch<T, 2, 2, 4, 1>(g, wa, da, nz, st);
     case 2: return s3s4_launch<T, 2, 2, 1, 4>(g, wa, da, nz, st);
