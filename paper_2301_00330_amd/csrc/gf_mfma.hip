@@ -644,8 +644,13 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+template <int BN>
+constexpr int ksplit_smem_words() { return 4 * 32 * (32 + 4 + BN + 4); }
+
+// block (bx, by) = (column tile, 32-row c_i tile); smem: ksplit_smem_words<BN>() words
 template <class T, int BN, bool VEC>
-__global__ __launch_bounds__(kThreads) void dgrad_ksplit_k(DgradMfmaArgs a) {
+__device__ __forceinline__ void dgrad_ksplit_body(const DgradMfmaArgs& a, int bx, int by, uint32_t* smem,
+                                                  unsigned char* Es) {
   constexpr int BM = 32, TM = 2, TN = BN / 16;
   constexpr int BK = Mma<T>::BK, VE = Mma<T>::VE;
   constexpr int SA = BM + 4, SB = BN + 4;
@@ -657,15 +662,14 @@ __global__ __launch_bounds__(kThreads) void dgrad_ksplit_k(DgradMfmaArgs a) {
   constexpr int kSumWords = 4 * BM * BN;                       // the four fp32 accumulator tiles
   constexpr int kOutWords = (BM * SC * (int)sizeof(T) + 3) / 4;
   static_assert(kSumWords + kOutWords <= 4 * kWaveWords, "reduction buffers fit the staging tiles");
-  __shared__ __attribute__((aligned(16))) uint32_t smem[4 * kWaveWords];
-  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
+  static_assert(4 * kWaveWords == ksplit_smem_words<BN>(), "smem size");
   const T* gyu = static_cast<const T*>(a.gyu);
   const T* wt = static_cast<const T*>(a.wt);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint32_t* As = smem + wave * kWaveWords;
   uint32_t* Bs = As + 32 * SA;
-  const int m0 = blockIdx.y * BM;
-  const int j0 = blockIdx.x * a.cols_per_tile;
+  const int m0 = by * BM;
+  const int j0 = bx * a.cols_per_tile;
   const int jend = min(a.Jtot, j0 + a.cols_per_tile);
 
   auto load_a = [&](int k, int col) -> uint4 {
@@ -763,7 +767,14 @@ __global__ __launch_bounds__(kThreads) void dgrad_ksplit_k(DgradMfmaArgs a) {
     Cs[(e / BN) * SC + (e % BN)] = from_f32<T>(s * a.scale);
   }
   __syncthreads();
-  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, blockIdx.x, m0, j0, jend, tid);
+  dgrad_epilogue<T, BM, BN, VEC>(a, Cs, Es, bx, m0, j0, jend, tid);
+}
+
+template <class T, int BN, bool VEC>
+__global__ __launch_bounds__(kThreads) void dgrad_ksplit_k(DgradMfmaArgs a) {
+  __shared__ __attribute__((aligned(16))) uint32_t smem[ksplit_smem_words<BN>()];
+  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
+  dgrad_ksplit_body<T, BN, VEC>(a, blockIdx.x, blockIdx.y, smem, Es);
 }
 
 // ---------------------------------------------------------------------------
@@ -795,6 +806,25 @@ __global__ __launch_bounds__(kThreads) void s3s4_mfma_k(WgradMfmaArgs wa, DgradM
   } else {
     const int q = b - g.nw;
     dgrad_body<T, DTM, DTN, DWM, DWN, VEC>(da, q % g.dgx, q / g.dgx, reinterpret_cast<uint32_t*>(smem), Es);
+  }
+}
+
+// the same with the K-split input-gradient block
+template <class T, int WTM, int WTN, int WWM, int WWN, int BN>
+__global__ __launch_bounds__(kThreads) void s3s4_ksplit_k(WgradMfmaArgs wa, DgradMfmaArgs da, S3S4Grid g) {
+  constexpr int WBM = WWM * WTM * 16, WBN = WWN * WTN * 16;
+  constexpr int kWBytes = (WBM + WBN) * kRowBytes;
+  constexpr int kDBytes = ksplit_smem_words<BN>() * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kWBytes > kDBytes ? kWBytes : kDBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Es[kPlaneStageBytes];
+  const int b = blockIdx.x;
+  if (b < g.nw) {
+    const int bx = b % g.wgx;
+    const int t = b / g.wgx;
+    wgrad_body<T, WTM, WTN, WWM, WWN, true>(wa, bx, t % g.wgy, t / g.wgy, smem, smem + WBM * kRowBytes);
+  } else {
+    const int q = b - g.nw;
+    dgrad_ksplit_body<T, BN, true>(da, q % g.dgx, q / g.dgx, reinterpret_cast<uint32_t*>(smem), Es);
   }
 }
 
@@ -1045,7 +1075,6 @@ static bool s3s4_ok(const Geom& g) {
   if (wgrad_shape(g) == 4) return false;
   const bool runs = dgrad_full_ok<T>(g);
   if (!runs && !dgrad_planes_ok(g)) return false;
-  if (dgrad_wants_ksplit<T>(g, !runs)) return false;
   if (g.P % VE != 0) {  // image-block loaders on both sides
     if (runs || !wgrad_flat(g, nullptr)) return false;
     if (g.P > 64 || ((long)g.Co * g.P * sizeof(T)) % 16 != 0) return false;
@@ -1063,6 +1092,22 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
   gr.wgy = cdiv(g.Co, WBM);
   gr.nw = gr.wgx * gr.wgy * nz;
   const bool vec = g.P % Mma<T>::VE == 0;
+  if (dgrad_wants_ksplit<T>(g, da.planes_mode != 0)) {  // K-split block, 32 rows of c_i
+    const int bn = (da.planes_mode && g.P <= 32) ? 32 : 64;
+    if (da.planes_mode) {
+      da.ipt = images_per_tile(g, bn, 32);
+      da.cols_per_tile = da.ipt * g.P;
+    } else {
+      da.cols_per_tile = bn;
+    }
+    gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
+    const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 32);
+    if (bn == 32)
+      hipLaunchKernelGGL((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 32>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+    else
+      hipLaunchKernelGGL((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 64>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+    return hipGetLastError();
+  }
   if (da.planes_mode) {
     gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
     const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 64);
