@@ -264,6 +264,7 @@ gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void*
   rc = check_ws(ws_exact(g, g_w != nullptr, g_x != nullptr), ws, ws_bytes);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (implicit_ok(g)) return dev(launch_implicit(g, x, w, g_y, g_w, g_x, ws, st));
   if (g_w) {
     rc = dev(launch_exact_wgrad(g, x, g_y, g_w, ws, st));
     if (rc) return rc;

@@ -303,12 +303,14 @@ ExactArgs make_args(const Geom& g) {
 }  // namespace
 
 size_t ws_exact(const Geom& g, bool want_gw, bool want_gx) {
+  if (implicit_ok(g)) return ws_implicit(g, want_gw, want_gx);
   if (!gemm_path(g)) return 0;
   return col_bytes(g, want_gw, want_gx) + aux_bytes(g, want_gw, want_gx);
 }
 
 hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, float* g_w, void* ws,
                               hipStream_t st) {
+  if (implicit_ok(g)) return launch_implicit(g, x, nullptr, g_y, g_w, nullptr, ws, st);
   if (gemm_path(g)) {
     const void* xcol = x;
     char* wsb = static_cast<char*>(ws);
@@ -343,6 +345,7 @@ hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, flo
 
 hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, void* g_x, void* ws,
                               hipStream_t st) {
+  if (implicit_ok(g)) return launch_implicit(g, nullptr, w, g_y, nullptr, g_x, ws, st);
   if (gemm_path(g)) {
     const Geom q = dgrad_geom(g);
     if (pointwise_plain(g)) return launch_mfma_dgrad(q, g_y, w, nullptr, g_x, nullptr, st);

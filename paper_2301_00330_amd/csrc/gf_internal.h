@@ -145,4 +145,12 @@ hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, flo
 hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, void* g_x, void* ws,
                               hipStream_t st);
 
+
+// S5 for dense stride-1 "same"-size layers: implicit GEMMs without a column tensor
+// (gf_implicit.hip).  ws as sized by ws_implicit().
+bool implicit_ok(const Geom& g);
+size_t ws_implicit(const Geom& g, bool want_gw, bool want_gx);
+hipError_t launch_implicit(const Geom& g, const void* x, const void* w, const void* g_y, float* g_w, void* g_x,
+                           void* ws, hipStream_t st);
+
 }  // namespace gf

@@ -282,6 +282,11 @@ EXACT_CASES = [
     (3, 72, 136, 14, 14, 3, 1, 1, 1, 1), (2, 64, 96, 7, 7, 3, 1, 1, 1, 1), (2, 40, 80, 14, 14, 3, 2, 1, 1, 1),
     (2, 32, 48, 24, 24, 3, 1, 6, 6, 1), (4, 130, 70, 8, 8, 1, 1, 0, 1, 1), (2, 256, 288, 16, 16, 3, 1, 1, 1, 1),
     (1, 24, 24, 56, 56, 1, 1, 0, 1, 1), (2, 16, 24, 9, 7, 3, 2, 1, 1, 1),
+    # dense stride-1 "same"-size layers (implicit-GEMM kernels): odd maps, taps that leave the
+    # image entirely, a tensor barely longer than one vector, planes that are not vector multiples
+    (2, 8, 5, 9, 7, 3, 1, 1, 1, 1), (1, 8, 1, 3, 3, 3, 1, 1, 1, 1), (1, 8, 8, 6, 6, 3, 1, 7, 7, 1),
+    (2, 16, 8, 10, 10, 5, 1, 4, 2, 1), (5, 24, 40, 7, 7, 3, 1, 1, 1, 1), (3, 136, 72, 14, 14, 3, 1, 1, 1, 1),
+    (1, 8, 264, 20, 12, 3, 1, 2, 2, 1),
 ]
 
 
