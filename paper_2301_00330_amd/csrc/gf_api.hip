@@ -219,6 +219,7 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
                               hipMemcpyDeviceToDevice, st));
       if (rc) return rc;
     }
+    if (implicit_ok(g)) return dev(launch_implicit(g, x_u, w, g_y, g_w, g_x, ws, st));
     rc = dev(launch_exact_wgrad(g, x_u, g_y, g_w, ws, st));
     if (rc) return rc;
     return dev(launch_exact_dgrad(g, w, g_y, g_x, ws, st));

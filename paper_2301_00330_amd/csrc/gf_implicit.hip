@@ -1,17 +1,26 @@
-// Vanilla back-propagation (Sec. 3.1) of dense stride-1 convolutions whose output map is as
-// wide as the input map ("same" padding), as implicit GEMMs on the MFMA cores of gfx950:
+// Vanilla back-propagation (Sec. 3.1) of dense convolutions as implicit GEMMs on the MFMA cores
+// of gfx950:
 //
-//   weight gradient  g_th[co, ci, t] = sum_{n, k} g_y[n, co, k] * x[n, ci, k + dW(t)]      (k: output pixel)
+//   weight gradient  g_th[co, ci, t] = sum_{n, k} g_y[n, co, k] * xs[n, ci, k + dW(t)]      (k: output pixel)
 //   input gradient   g_x[n, ci, j]   = sum_{t, co} th[co, ci, t] * g_y[n, co, j + dD(t)]   (j: input pixel)
 //
-// For such layers the pixel a tap reads is the flattened pixel index plus a constant,
+// Stride 1, output map as wide as the input map ("same" padding): the pixel a tap reads is
+// the flattened pixel index plus a constant,
 //   dW(t) = (u d - p) W + (v d - p),   dD(t) = (p - u d) W_y + (p - v d),   t = (u, v),
 // wherever the tap stays inside the image; where it leaves it the factor is a zero of the
 // padding.  So no column tensor is built: the shifted operand is read straight from the
 // tensor with 16-byte loads at 2- or 4-byte alignment, and a byte table [tap][8 pixels] says
-// which of the eight elements are padding.  Planes are addressed as if they held HWp = 8 *
+// which of the eight elements are padding.  Planes are addressed as if they held 8 *
 // ceil(HW / 8) pixels, so that a vector never straddles two images; the surplus positions
 // are masked like padding.
+//
+// Stride s > 1: x is first split into its s x s phase planes xq[a, b][n, ci, i, j] =
+// x[n, ci, s i + a, s j + b], stored with the row pitch W_y of the output map.  Tap (u, v) of
+// output pixel (i, j) reads x[s i + u d - p, s j + v d - p], which is one fixed phase plane at
+// (i, j) plus a constant: the same kernels run with a per-tap offset that includes the phase
+// plane.  The input gradient is computed phase by phase (each phase of g_x receives the taps
+// whose parity matches, so no multiplication is wasted on the zeros of a zero-inserted g_y)
+// into phase planes that one more pass interleaves into g_x.
 //
 // Tiles: 256-lane blocks of 2 x 2 waves, each wave TM x TN MFMA tiles of 16 x 16
 // (v_mfma_f32_16x16x32_bf16 / v_mfma_f32_16x16x4_f32); operands are staged through LDS one
@@ -114,62 +123,125 @@ __device__ __forceinline__ uint32_t vec_mask(uint32_t byte, int q) {
 }
 
 // ---------------------------------------------------------------------------
-// Padding tables.  tabw[t][k / 8] bit e: output pixel k + e exists and tap t of it reads an
-// input pixel inside the image (weight gradient); tabd[t][j / 8] bit e: input pixel j + e
-// exists and tap t reaches it from an output pixel inside the map (input gradient).
+// Set-up.  With e = u d - p, f = v d - p (tap offsets on the input side) and, for stride s,
+// a = e mod s, b = f mod s (the phase plane the tap reads), Hq = ceil(H / s), Wq = W_y:
+//   tapw[t]        = phase(a, b) * N Ci Hq Wq + floor(e / s) * Wq + floor(f / s)
+//   tabw[t][k / 8] bit i: output pixel k + i exists and tap t of it reads inside the image
+//   per phase ph = (a, b) of g_x, the taps with (a + p - u d) and (b + p - v d) divisible by s:
+//   tapd[ph][kk]   = {t, ((a + p - u d) / s) * W_y + (b + p - v d) / s},  ntap[ph] of them
+//   tabd[ph][t][j / 8] bit i: position j + i of the phase plane exists and that tap reaches it
+//                             from an output pixel inside the map
 // ---------------------------------------------------------------------------
-struct TabArgs {
+struct PrepArgs {
   uint8_t* tabw;
   uint8_t* tabd;
-  int H, W, Hy, Wy, Kw, KK, d, p, nvw, nvd;
+  int* tapw;    // [KK]
+  int2* tapd;   // [s*s][KK]
+  int* ntap;    // [s*s]
+  int N, Ci, H, W, Hy, Wy, Hq, Wq, Kw, KK, s, d, p, nvw, nvd;
 };
 
-__device__ __forceinline__ void pad_table_body(const TabArgs& a, int block) {
+__device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
+
+__device__ __forceinline__ void prep_tables(const PrepArgs& a, int block) {
   const int e0 = block * kThreads + threadIdx.x;
-  const int nmax = a.nvw > a.nvd ? a.nvw : a.nvd;
+  const int nph = a.s * a.s;
+  const int nmax = a.nvw > a.nvd * nph ? a.nvw : a.nvd * nph;
+  if (block == 0 && threadIdx.x < nph) {  // tap list of one phase of g_x
+    const int ph = threadIdx.x, pa = ph / a.s, pb = ph - pa * a.s;
+    int cnt = 0;
+    for (int t = 0; t < a.KK; ++t) {
+      const int u = t / a.Kw, v = t - u * a.Kw;
+      const int ea = pa + a.p - u * a.d, eb = pb + a.p - v * a.d;
+      const int qa = floor_div(ea, a.s), qb = floor_div(eb, a.s);
+      if (qa * a.s == ea && qb * a.s == eb) a.tapd[ph * a.KK + cnt++] = make_int2(t, qa * a.Wy + qb);
+    }
+    a.ntap[ph] = cnt;
+  }
   if (e0 >= a.KK * nmax) return;
   const int t = e0 / nmax, g = e0 - t * nmax;
   const int u = t / a.Kw, v = t - u * a.Kw;
+  const int e = u * a.d - a.p, f = v * a.d - a.p;
+  if (g == 0) {
+    const int qe = floor_div(e, a.s), qf = floor_div(f, a.s);
+    const int ph = (e - qe * a.s) * a.s + (f - qf * a.s);
+    a.tapw[t] = ph * (a.N * a.Ci * a.Hq * a.Wq) + qe * a.Wq + qf;
+  }
   if (g < a.nvw) {
     uint32_t m = 0;
-    for (int e = 0; e < 8; ++e) {
-      const int k = g * 8 + e;
+    for (int i = 0; i < 8; ++i) {
+      const int k = g * 8 + i;
       if (k >= a.Hy * a.Wy) break;
       const int hy = k / a.Wy, wy = k - hy * a.Wy;
-      const int hs = hy + u * a.d - a.p, ws = wy + v * a.d - a.p;
-      if (hs >= 0 && hs < a.H && ws >= 0 && ws < a.W) m |= 1u << e;
+      const int hs = hy * a.s + e, ws = wy * a.s + f;
+      if (hs >= 0 && hs < a.H && ws >= 0 && ws < a.W) m |= 1u << i;
     }
     a.tabw[t * a.nvw + g] = (uint8_t)m;
   }
-  if (g < a.nvd) {
+  if (g < a.nvd * nph) {
+    const int ph = g / a.nvd, gg = g - ph * a.nvd;
+    const int pa = ph / a.s, pb = ph - pa * a.s;
+    const int ea = pa + a.p - u * a.d, eb = pb + a.p - v * a.d;
+    const int qa = floor_div(ea, a.s), qb = floor_div(eb, a.s);
     uint32_t m = 0;
-    for (int e = 0; e < 8; ++e) {
-      const int j = g * 8 + e;
-      if (j >= a.H * a.W) break;
-      const int h = j / a.W, w = j - h * a.W;
-      const int hs = h + a.p - u * a.d, ws = w + a.p - v * a.d;
-      if (hs >= 0 && hs < a.Hy && ws >= 0 && ws < a.Wy) m |= 1u << e;
+    if (qa * a.s == ea && qb * a.s == eb) {
+      for (int i = 0; i < 8; ++i) {
+        const int j = gg * 8 + i;
+        if (j >= a.Hq * a.Wq) break;
+        const int h = j / a.Wq, w = j - h * a.Wq;
+        const int hs = h + qa, ws = w + qb;
+        if (hs >= 0 && hs < a.Hy && ws >= 0 && ws < a.Wy) m |= 1u << i;
+      }
     }
-    a.tabd[t * a.nvd + g] = (uint8_t)m;
+    a.tabd[(ph * a.KK + t) * a.nvd + gg] = (uint8_t)m;
   }
 }
 
-// One set-up launch: the first `tab_blocks` blocks fill the padding tables, the others write the
+// One set-up launch.  Blocks [0, tab_blocks): tables and tap lists.  Then w_blocks blocks write the
 // kernel tap-major with c_o contiguous, wt[(t * Ci + ci) * Co + co] = w[(co * Ci + ci) * KK + t]
-// (only when the input gradient is wanted: wt != null).
+// (input gradient only).  Then the phase planes of x (weight gradient of a strided layer only).
 template <class T>
-__global__ __launch_bounds__(kThreads) void prep_k(TabArgs tab, int tab_blocks, const T* w, T* wt, int Co,
-                                                  int Ci, int KK) {
-  if ((int)blockIdx.x < tab_blocks) {
-    pad_table_body(tab, blockIdx.x);
+__global__ __launch_bounds__(kThreads) void prep_k(PrepArgs a, int tab_blocks, int w_blocks, const T* w, T* wt,
+                                                  int Co, const T* x, T* xq) {
+  int b = blockIdx.x;
+  if (b < tab_blocks) {
+    prep_tables(a, b);
     return;
   }
-  const int e = ((int)blockIdx.x - tab_blocks) * kThreads + threadIdx.x;
-  if (e >= Co * Ci * KK) return;
-  const int co = e % Co;
-  const int row = e / Co;
-  const int ci = row % Ci, t = row / Ci;
-  wt[e] = w[((long)co * Ci + ci) * KK + t];
+  b -= tab_blocks;
+  if (b < w_blocks) {
+    const int e = b * kThreads + threadIdx.x;
+    if (e >= Co * a.Ci * a.KK) return;
+    const int co = e % Co;
+    const int row = e / Co;
+    const int ci = row % a.Ci, t = row / a.Ci;
+    wt[e] = w[((long)co * a.Ci + ci) * a.KK + t];
+    return;
+  }
+  b -= w_blocks;
+  const int PQ = a.Hq * a.Wq;
+  const int total = a.s * a.s * a.N * a.Ci * PQ;
+  const int e = b * kThreads + threadIdx.x;
+  if (e >= total) return;
+  const int pos = e % PQ, plane = e / PQ;        // plane = (ph * N + n) * Ci + ci
+  const int i = pos / a.Wq, j = pos - i * a.Wq;
+  const int nc = plane % (a.N * a.Ci), ph = plane / (a.N * a.Ci);
+  const int h = i * a.s + ph / a.s, ww = j * a.s + ph % a.s;
+  const bool ok = h < a.H && ww < a.W;
+  const T val = x[((long)nc * a.H + (ok ? h : 0)) * a.W + (ok ? ww : 0)];
+  xq[e] = ok ? val : from_f32<T>(0.f);
+}
+
+// g_x[n, ci, h, w] = gxq[phase(h mod s, w mod s)][n, ci, h / s, w / s]
+template <class T>
+__global__ __launch_bounds__(kThreads) void interleave_k(const T* gxq, T* gx, int NC, int H, int W, int Hq,
+                                                        int Wq, int s) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= NC * H * W) return;
+  const int w = e % W, r = e / W;
+  const int h = r % H, nc = r / H;
+  const int ph = (h % s) * s + (w % s);
+  gx[e] = gxq[((long)ph * NC + nc) * (Hq * Wq) + (h / s) * Wq + (w / s)];
 }
 
 // ---------------------------------------------------------------------------
@@ -180,14 +252,15 @@ struct XWgradArgs {
   const void* x;
   float* part;
   const uint8_t* tab;
-  int N, Ci, Co, KK, Kw, W, d, p;
-  int HW, HWy, HWyp, nv;
+  const int* tapw;        // per tap: offset of the element of the x operand that output pixel 0 reads
+  int N, Ci, Co, KK;
+  int HW, HWy, HWyp, nv;  // plane of the x operand (a phase plane for strided layers), plane of g_y
   int nchunks, chunks_per_z, nz;
   int tx, tiles, R;       // c_i tiles, c_i tiles * c_o tiles, tiles * KK
   int xcd_slabs;          // 1: slab z runs on XCD z % 8
   int inner_ok;           // 1: a shifted vector of an inner image (0 < n < N - 1) stays inside the tensors
   int total_x, total_gy;
-  FastDiv d_hwyp, d_r, d_tiles, d_tx, d_kw;
+  FastDiv d_hwyp, d_r, d_tiles, d_tx;
 };
 
 // KV = 16-byte vectors of K per staged row.  One-dimensional grid.  The hardware hands
@@ -222,8 +295,7 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
   if (z >= a.nz) return;  // uniform for the block
   const int t = (int)a.d_tiles.div((uint32_t)rest), tile = rest - t * a.tiles;
   const int by = (int)a.d_tx.div((uint32_t)tile), bx = tile - by * a.tx;
-  const int u = (int)a.d_kw.div((uint32_t)t), v = t - u * a.Kw;
-  const int delta = (u * a.d - a.p) * a.W + (v * a.d - a.p);
+  const int delta = a.tapw[t];
   const int m0 = by * BM, n0 = bx * BN;
   const int kc0 = z * a.chunks_per_z;
   const int kc1 = min(kc0 + a.chunks_per_z, a.nchunks);
@@ -396,10 +468,12 @@ __global__ __launch_bounds__(kThreads) void xfinalize_k(const float* part, float
 struct XDgradArgs {
   const void* gy;
   const void* wt;   // [KK][Ci][Co]
-  void* gx;
+  void* gx;         // g_x, or its phase planes [s*s][N][Ci][HW] for a strided layer
   const uint8_t* tab;
-  int N, Ci, Co, KK, Kw, Wy, d, p;
-  int HW, HWp, HWy, nv, Jp;
+  const int2* tapd; // [phase][KK]: {tap, offset of the g_y element that position 0 reads}
+  const int* ntap;  // [phase]
+  int N, Ci, Co, KK;
+  int HW, HWp, HWy, nv, Jp;  // plane of the output (a phase plane for strided layers), plane of g_y
   int total_gy;
   int inner_ok;   // 1: a shifted vector of an inner image (0 < n < N - 1) stays inside g_y
   FastDiv d_hwp;
@@ -461,15 +535,18 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
 #pragma unroll
   for (int i = 0; i < LA; ++i) rowa[i] = min(m0 + rowa0 + RPP * i, a.Ci - 1) * a.Co + via * VE;
 
+  const int ph = blockIdx.z;                     // phase of g_x (0 for stride 1)
+  const int2* taps = a.tapd + ph * a.KK;
+  const int ntap = a.ntap[ph];
+  const uint8_t* tab = a.tab + (long)ph * a.KK * a.nv;
+
   uint4 ra[LA], rb[PB * RPS];
   uint32_t mb = 0, off = 0;
-  auto tap_delta = [&](int t) {
-    const int u = t / a.Kw, v = t - u * a.Kw;
-    return (a.p - u * a.d) * a.Wy + (a.p - v * a.d);
-  };
-  auto fetch = [&](int t, int k0) {
-    const int cb = colbase + tap_delta(t);
-    mb = img ? vec_mask<T>(a.tab[t * a.nv + (q >> 3)], q) : 0u;
+  auto fetch = [&](int kk, int k0) {
+    const int2 ti = taps[kk];
+    const int t = ti.x;
+    const int cb = colbase + ti.y;
+    mb = img ? vec_mask<T>(tab[t * a.nv + (q >> 3)], q) : 0u;
     off = 0;
     const bool kfull = k0 + BK <= a.Co;
 #pragma unroll
@@ -510,9 +587,9 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
       *reinterpret_cast<uint4*>(d + 4) = o1;
     }
   };
-  auto stage = [&](int t, int k0) {
+  auto stage = [&](int kk, int k0) {
     if (off) {  // first or last rows of g_y only: shift the moved vectors back
-      const int cb = colbase + tap_delta(t);
+      const int cb = colbase + taps[kk].y;
 #pragma unroll
       for (int i = 0; i < PB; ++i)
 #pragma unroll
@@ -559,14 +636,14 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  fetch(0, 0);
+  if (ntap > 0) fetch(0, 0);
   const int r = lane & 15, kg = lane >> 4;
-  for (int t = 0; t < a.KK; ++t)
+  for (int t = 0; t < ntap; ++t)
     for (int c = 0; c < nck; ++c) {
       stage(t, c * BK);
       __syncthreads();
       if (c + 1 < nck) fetch(t, (c + 1) * BK);
-      else if (t + 1 < a.KK) fetch(t + 1, 0);
+      else if (t + 1 < ntap) fetch(t + 1, 0);
       if constexpr (sizeof(T) == 2) {
 #pragma unroll
         for (int ks = 0; ks < BK / KSTEP; ++ks) {  // 32 k = 16 pair rows per MFMA
@@ -605,7 +682,7 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
   // the two wave rows of the tile go out one after the other through an LDS tile of BM / 2
   // rows (rounded once to the storage type), as 16-byte runs of pixels
   T* Cs = reinterpret_cast<T*>(smem);
-  T* out = static_cast<T*>(a.gx);
+  T* out = static_cast<T*>(a.gx) + (long)ph * a.N * a.Ci * a.HW;
   constexpr int HM = BM / 2;
   for (int half = 0; half < 2; ++half) {
     if (wm == half) {
@@ -645,47 +722,69 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// largest |tap offset| in flattened pixels
-long max_shift(const Geom& g) {
+int up8(int v) { return (v + 7) / 8 * 8; }
+
+// Geometry of the implicit GEMMs: PQ = plane of the x operand / of the g_x output (the phase
+// plane Hq x Wq for strided layers, the image itself for stride 1), PY = plane of g_y.
+struct XGeo {
+  int s, nph, Hq, Wq, PQ, PY;
+};
+
+XGeo make_xgeo(const Geom& g) {
+  XGeo q;
+  q.s = g.s;
+  q.nph = g.s * g.s;
+  q.Hq = g.s == 1 ? g.H : (g.H + g.s - 1) / g.s;
+  q.Wq = g.s == 1 ? g.W : g.Wy;
+  q.PQ = q.Hq * q.Wq;
+  q.PY = g.Hy * g.Wy;
+  return q;
+}
+
+// largest |tap offset| in flattened pixels of a plane of pitch Wq
+long max_shift(const Geom& g, const XGeo& q) {
   const long a = g.p, b = (long)g.dl * ((g.Kh > g.Kw ? g.Kh : g.Kw) - 1) - g.p;
-  return (a > b ? a : b) * (g.W + 1);
+  return ((a > b ? a : b) / g.s + 1) * (q.Wq + 1);
 }
 
 // one image holds more elements than a tap reaches: then only the first and the last image
 // of a tensor need clamped loads
-bool inner_images_safe(const Geom& g) {
-  long skew = (long)g.H * g.W - (long)g.Hy * g.Wy;  // the planes of x and g_y may differ in height
+bool inner_images_safe(const Geom& g, const XGeo& q) {
+  long skew = (long)q.PQ - q.PY;  // the planes of the two operands may differ in height
   if (skew < 0) skew = -skew;
-  const long need = max_shift(g) + 16 + skew;
-  return (long)g.Ci * g.H * g.W >= need && (long)g.Co * g.Hy * g.Wy >= need;
+  const long need = max_shift(g, q) + 16 + skew;
+  return (long)g.Ci * q.PQ >= need && (long)g.Co * q.PY >= need;
 }
 
-int hwp_of(int hw) { return (hw + 7) / 8 * 8; }
-
 struct XPlan {
-  size_t off_tabw, off_tabd, off_wp, off_part, total;
-  int nvw, nvd, nz, chunks_per_z, nchunks, bm, bn, kv;
+  size_t off_tabw, off_tabd, off_taps, off_wt, off_xq, off_gxq, off_part, total;
+  int nvw, nvd, nz, chunks_per_z, nchunks, bm, bn;
 };
 
 // workspace layout, tile shape of the weight-gradient block and its number of K slabs
 template <class T>
 XPlan make_plan(const Geom& g, bool want_gw, bool want_gx) {
+  const XGeo q = make_xgeo(g);
   XPlan p = {};
-  p.nvw = hwp_of(g.Hy * g.Wy) / 8;
-  p.nvd = hwp_of(g.H * g.W) / 8;
+  p.nvw = up8(q.PY) / 8;
+  p.nvd = up8(q.PQ) / 8;
   size_t off = 0;
   p.off_tabw = off; off += align256((size_t)g.KK * p.nvw);
-  p.off_tabd = off; off += align256((size_t)g.KK * p.nvd);
-  p.off_wp = off;
+  p.off_tabd = off; off += align256((size_t)q.nph * g.KK * p.nvd);
+  p.off_taps = off; off += align256(sizeof(int) * ((size_t)g.KK + 2 * (size_t)q.nph * g.KK + q.nph));
+  p.off_wt = off;
   if (want_gx) off += align256((size_t)g.KK * g.Co * g.Ci * g.b);
+  p.off_xq = off;
+  if (want_gw && g.s > 1) off += align256((size_t)q.nph * g.N * g.Ci * q.PQ * g.b);
+  p.off_gxq = off;
+  if (want_gx && g.s > 1) off += align256((size_t)q.nph * g.N * g.Ci * q.PQ * g.b);
   p.off_part = off;
   if (want_gw) {
     const bool small = g.Co <= 64 || g.Ci <= 64;   // 64 x 64 tiles for few channels
     p.bm = small ? 64 : 128;
     p.bn = small ? 64 : 128;
-    p.kv = 16;
-    const int bk = p.kv * Mma<T>::VE;
-    p.nchunks = cdiv((long)g.N * hwp_of(g.Hy * g.Wy), bk);
+    const int bk = 16 * Mma<T>::VE;
+    p.nchunks = cdiv((long)g.N * up8(q.PY), bk);
     const long tiles = (long)cdiv(g.Co, p.bm) * cdiv(g.Ci, p.bn) * g.KK;
     const long slots = small ? 1024 : 512;      // blocks the chip holds at once
     long nz = slots / tiles;
@@ -700,43 +799,64 @@ XPlan make_plan(const Geom& g, bool want_gw, bool want_gx) {
   return p;
 }
 
+struct XTaps {
+  int* tapw;
+  int2* tapd;
+  int* ntap;
+};
+
+XTaps taps_of(const Geom& g, const XGeo& q, const XPlan& p, char* ws) {
+  XTaps t;
+  int* base = reinterpret_cast<int*>(ws + p.off_taps);
+  t.tapd = reinterpret_cast<int2*>(base);            // 8-byte aligned: first in the region
+  t.tapw = base + 2 * q.nph * g.KK;
+  t.ntap = t.tapw + g.KK;
+  return t;
+}
+
 template <class T>
-hipError_t launch_prep(const Geom& g, const XPlan& p, char* ws, const void* w, bool want_gx, hipStream_t st) {
-  TabArgs t;
-  t.tabw = reinterpret_cast<uint8_t*>(ws + p.off_tabw);
-  t.tabd = reinterpret_cast<uint8_t*>(ws + p.off_tabd);
-  t.H = g.H; t.W = g.W; t.Hy = g.Hy; t.Wy = g.Wy; t.Kw = g.Kw; t.KK = g.KK; t.d = g.dl; t.p = g.p;
-  t.nvw = p.nvw; t.nvd = p.nvd;
-  const int nmax = p.nvw > p.nvd ? p.nvw : p.nvd;
+hipError_t launch_prep(const Geom& g, const XGeo& q, const XPlan& p, char* ws, const void* x, const void* w,
+                       bool want_gw, bool want_gx, hipStream_t st) {
+  const XTaps tp = taps_of(g, q, p, ws);
+  PrepArgs a;
+  a.tabw = reinterpret_cast<uint8_t*>(ws + p.off_tabw);
+  a.tabd = reinterpret_cast<uint8_t*>(ws + p.off_tabd);
+  a.tapw = tp.tapw; a.tapd = tp.tapd; a.ntap = tp.ntap;
+  a.N = g.N; a.Ci = g.Ci; a.H = g.H; a.W = g.W; a.Hy = g.Hy; a.Wy = g.Wy; a.Hq = q.Hq; a.Wq = q.Wq;
+  a.Kw = g.Kw; a.KK = g.KK; a.s = g.s; a.d = g.dl; a.p = g.p; a.nvw = p.nvw; a.nvd = p.nvd;
+  const int nmax = p.nvw > p.nvd * q.nph ? p.nvw : p.nvd * q.nph;
   const int tab_blocks = cdiv((long)g.KK * nmax, kThreads);
   const int w_blocks = want_gx ? cdiv((long)g.Co * g.Ci * g.KK, kThreads) : 0;
-  hipLaunchKernelGGL(prep_k<T>, dim3(tab_blocks + w_blocks), dim3(kThreads), 0, st, t, tab_blocks,
-                     static_cast<const T*>(w), reinterpret_cast<T*>(ws + p.off_wp), g.Co, g.Ci, g.KK);
+  const int x_blocks = (want_gw && g.s > 1) ? cdiv((long)q.nph * g.N * g.Ci * q.PQ, kThreads) : 0;
+  hipLaunchKernelGGL(prep_k<T>, dim3(tab_blocks + w_blocks + x_blocks), dim3(kThreads), 0, st, a, tab_blocks,
+                     w_blocks, static_cast<const T*>(w), reinterpret_cast<T*>(ws + p.off_wt), g.Co,
+                     static_cast<const T*>(x), reinterpret_cast<T*>(ws + p.off_xq));
   return hipGetLastError();
 }
 
 template <class T>
-hipError_t wgrad_t(const Geom& g, const XPlan& p, const void* x, const void* g_y, float* g_w, char* wsb,
-                   hipStream_t st) {
+hipError_t wgrad_t(const Geom& g, const XGeo& q, const XPlan& p, const void* x, const void* g_y, float* g_w,
+                   char* wsb, hipStream_t st) {
   XWgradArgs a;
-  a.gy = g_y; a.x = x;
+  a.gy = g_y;
+  a.x = g.s > 1 ? static_cast<const void*>(wsb + p.off_xq) : x;
   a.part = reinterpret_cast<float*>(wsb + p.off_part);
   a.tab = reinterpret_cast<const uint8_t*>(wsb + p.off_tabw);
-  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.KK = g.KK; a.Kw = g.Kw; a.W = g.W; a.d = g.dl; a.p = g.p;
-  a.HW = g.H * g.W; a.HWy = g.Hy * g.Wy; a.HWyp = hwp_of(a.HWy); a.nv = p.nvw;
+  a.tapw = taps_of(g, q, p, wsb).tapw;
+  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.KK = g.KK;
+  a.HW = q.PQ; a.HWy = q.PY; a.HWyp = up8(q.PY); a.nv = p.nvw;
   a.nchunks = p.nchunks; a.chunks_per_z = p.chunks_per_z; a.nz = p.nz;
   a.tx = cdiv(g.Ci, p.bn);
   a.tiles = a.tx * cdiv(g.Co, p.bm);
   a.R = a.tiles * g.KK;
   a.xcd_slabs = p.nz >= 8 ? 1 : 0;
-  a.inner_ok = inner_images_safe(g) ? 1 : 0;
-  a.total_x = g.N * g.Ci * a.HW;
-  a.total_gy = g.N * g.Co * a.HWy;
+  a.inner_ok = inner_images_safe(g, q) ? 1 : 0;
+  a.total_x = q.nph * g.N * g.Ci * q.PQ;
+  a.total_gy = g.N * g.Co * q.PY;
   a.d_hwyp = FastDiv((uint32_t)a.HWyp);
   a.d_r = FastDiv((uint32_t)a.R);
   a.d_tiles = FastDiv((uint32_t)a.tiles);
   a.d_tx = FastDiv((uint32_t)a.tx);
-  a.d_kw = FastDiv((uint32_t)g.Kw);
   const dim3 grid(a.xcd_slabs ? 8 * a.R * cdiv(p.nz, 8) : a.R * p.nz);
   if (p.bm == 64)
     hipLaunchKernelGGL((xwgrad_k<T, 2, 2, 16>), grid, dim3(kThreads), 0, st, a);
@@ -751,58 +871,73 @@ hipError_t wgrad_t(const Geom& g, const XPlan& p, const void* x, const void* g_y
 }
 
 template <class T>
-hipError_t dgrad_t(const Geom& g, const XPlan& p, const void* g_y, void* g_x, char* wsb, hipStream_t st) {
+hipError_t dgrad_t(const Geom& g, const XGeo& q, const XPlan& p, const void* g_y, void* g_x, char* wsb,
+                   hipStream_t st) {
+  const XTaps tp = taps_of(g, q, p, wsb);
   XDgradArgs a;
-  a.gy = g_y; a.wt = wsb + p.off_wp; a.gx = g_x;
+  a.gy = g_y; a.wt = wsb + p.off_wt;
+  a.gx = g.s > 1 ? static_cast<void*>(wsb + p.off_gxq) : g_x;
   a.tab = reinterpret_cast<const uint8_t*>(wsb + p.off_tabd);
-  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.KK = g.KK; a.Kw = g.Kw; a.Wy = g.Wy; a.d = g.dl; a.p = g.p;
-  a.HW = g.H * g.W; a.HWp = hwp_of(a.HW); a.HWy = g.Hy * g.Wy; a.nv = p.nvd;
+  a.tapd = tp.tapd; a.ntap = tp.ntap;
+  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.KK = g.KK;
+  a.HW = q.PQ; a.HWp = up8(q.PQ); a.HWy = q.PY; a.nv = p.nvd;
   a.Jp = g.N * a.HWp;
-  a.total_gy = g.N * g.Co * a.HWy;
-  a.inner_ok = inner_images_safe(g) ? 1 : 0;
+  a.total_gy = g.N * g.Co * q.PY;
+  a.inner_ok = inner_images_safe(g, q) ? 1 : 0;
   a.d_hwp = FastDiv((uint32_t)a.HWp);
   // tile shape: 128 x 128 when that still gives about two blocks per compute unit, else narrower
-  const long t128 = (long)cdiv(a.Jp, 128) * cdiv(g.Ci, 128);
+  const long t128 = (long)cdiv(a.Jp, 128) * cdiv(g.Ci, 128) * q.nph;
   if (g.Ci > 64 && t128 >= 400) {
-    hipLaunchKernelGGL((xdgrad_k<T, 4, 4, 8>), dim3(cdiv(a.Jp, 128), cdiv(g.Ci, 128)), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((xdgrad_k<T, 4, 4, 8>), dim3(cdiv(a.Jp, 128), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
   } else if (g.Ci > 64) {
-    hipLaunchKernelGGL((xdgrad_k<T, 4, 2, 16>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 128)), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((xdgrad_k<T, 4, 2, 16>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
   } else {
-    hipLaunchKernelGGL((xdgrad_k<T, 2, 2, 16>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 64)), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((xdgrad_k<T, 2, 2, 16>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 64), q.nph), dim3(kThreads), 0, st, a);
   }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || g.s == 1) return e;
+  const long tot = (long)g.N * g.Ci * g.H * g.W;
+  hipLaunchKernelGGL(interleave_k<T>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
+                     reinterpret_cast<const T*>(wsb + p.off_gxq), static_cast<T*>(g_x), g.N * g.Ci, g.H, g.W,
+                     q.Hq, q.Wq, g.s);
   return hipGetLastError();
 }
 
 template <class T>
 hipError_t implicit_t(const Geom& g, const void* x, const void* w, const void* g_y, float* g_w, void* g_x,
                       void* ws, hipStream_t st) {
+  const XGeo q = make_xgeo(g);
   const XPlan p = make_plan<T>(g, g_w != nullptr, g_x != nullptr);
   char* wsb = static_cast<char*>(ws);
-  hipError_t e = launch_prep<T>(g, p, wsb, w, g_x != nullptr, st);
+  hipError_t e = launch_prep<T>(g, q, p, wsb, x, w, g_w != nullptr, g_x != nullptr, st);
   if (e != hipSuccess) return e;
   if (g_w) {
-    e = wgrad_t<T>(g, p, x, g_y, g_w, wsb, st);
+    e = wgrad_t<T>(g, q, p, x, g_y, g_w, wsb, st);
     if (e != hipSuccess) return e;
   }
-  if (g_x) e = dgrad_t<T>(g, p, g_y, g_x, wsb, st);
+  if (g_x) e = dgrad_t<T>(g, q, p, g_y, g_x, wsb, st);
   return e;
 }
 
 }  // namespace
 
-// dense stride-1 layers with W_y == W, channel counts that are multiples of the vector length,
-// a kernel larger than 1 x 1 and every index (plus the largest tap offset) below 2^31
+// Dense layers with channel counts that are multiples of the vector length, whose tap offsets
+// are constant in flattened pixels: stride 1 with W_y == W, or stride s with ceil(W / s) <= W_y
+// (phase planes of pitch W_y); every index (plus the largest tap offset) below 2^31.
 bool implicit_ok(const Geom& g) {
   const int ve = 16 / g.b;
-  if (g.g != 1 || g.s != 1 || g.Wy != g.W || g.KK > 1024) return false;
+  if (g.g != 1 || g.KK > 1024 || g.s > 4) return false;
+  if (g.s == 1 ? g.Wy != g.W : (g.W + g.s - 1) / g.s > g.Wy) return false;
   if (g.Ci % ve != 0 || g.Co % ve != 0) return false;
+  const XGeo q = make_xgeo(g);
   const long lim = 2147483647L;
-  const long hwp = hwp_of(g.H * g.W), hwyp = hwp_of(g.Hy * g.Wy);
-  const long reach = max_shift(g) + 1024;
-  const long tx = (long)g.N * g.Ci * g.H * g.W, ty = (long)g.N * g.Co * g.Hy * g.Wy;
+  const long pqp = up8(q.PQ), pyp = up8(q.PY);
+  const long reach = max_shift(g, q) + 1024;
+  const long tx = (long)q.nph * g.N * g.Ci * q.PQ, ty = (long)g.N * g.Co * q.PY;
   if (tx < ve || ty < ve) return false;
-  if (tx + reach + hwp >= lim || ty + reach + hwyp >= lim) return false;
-  if ((long)g.N * hwp + 1024 >= lim || (long)g.N * hwyp + 1024 >= lim) return false;
+  if (tx + reach + pqp >= lim || ty + reach + pyp >= lim) return false;
+  if ((long)g.N * g.Ci * g.H * g.W >= lim) return false;
+  if ((long)g.N * pqp + 1024 >= lim || (long)g.N * pyp + 1024 >= lim) return false;
   if ((long)g.KK * g.Co * g.Ci >= lim) return false;
   if (cdiv(g.Ci, 64) > 65535 || cdiv(g.Co, 64) > 65535) return false;
   if ((long)cdiv(g.Ci, 64) * cdiv(g.Co, 64) * g.KK * 8 * 130 >= lim) return false;  // one-dimensional grid

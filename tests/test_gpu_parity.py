@@ -287,6 +287,11 @@ EXACT_CASES = [
     (2, 8, 5, 9, 7, 3, 1, 1, 1, 1), (1, 8, 1, 3, 3, 3, 1, 1, 1, 1), (1, 8, 8, 6, 6, 3, 1, 7, 7, 1),
     (2, 16, 8, 10, 10, 5, 1, 4, 2, 1), (5, 24, 40, 7, 7, 3, 1, 1, 1, 1), (3, 136, 72, 14, 14, 3, 1, 1, 1, 1),
     (1, 8, 264, 20, 12, 3, 1, 2, 2, 1),
+    # dense strided layers with ceil(W / s) == W_y (phase planes): odd maps, stride 3, a strided 1x1
+    # (phases of g_x that no tap reaches), dilation, 5x5, many channels
+    (2, 16, 16, 8, 8, 1, 2, 0, 1, 1), (2, 8, 16, 15, 13, 3, 2, 1, 1, 1), (1, 8, 8, 12, 12, 3, 3, 1, 1, 1),
+    (2, 16, 8, 12, 12, 3, 2, 2, 2, 1), (1, 8, 8, 11, 9, 5, 2, 2, 1, 1), (3, 136, 72, 14, 14, 3, 2, 1, 1, 1),
+    (3, 64, 128, 7, 7, 3, 2, 1, 1, 1),
 ]
 
 
