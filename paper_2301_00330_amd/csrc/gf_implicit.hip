@@ -476,7 +476,7 @@ struct XDgradArgs {
   int HW, HWp, HWy, nv, Jp;  // plane of the output (a phase plane for strided layers), plane of g_y
   int total_gy;
   int inner_ok;   // 1: a shifted vector of an inner image (0 < n < N - 1) stays inside g_y
-  FastDiv d_hwp;
+  FastDiv d_hwp, d_nck;  // d_nck: by the number of K chunks per tap of the launched tile shape
 };
 
 template <class T, int BM, int BN, int KV>
@@ -489,7 +489,9 @@ constexpr int xdgrad_smem_bytes() {
   return tile > out ? tile : out;
 }
 
-template <class T, int TM, int TN, int KV>
+// DEPTH = K chunks a lane keeps in flight in registers (two measured no faster than one: the
+// loop is bound by LDS traffic, not by the latency of the global loads)
+template <class T, int TM, int TN, int KV, int DEPTH>
 __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
   constexpr int WM = 2, WN = 2;
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
@@ -540,26 +542,32 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
   const int ntap = a.ntap[ph];
   const uint8_t* tab = a.tab + (long)ph * a.KK * a.nv;
 
-  uint4 ra[LA], rb[PB * RPS];
-  uint32_t mb = 0, off = 0;
-  auto fetch = [&](int kk, int k0) {
+  struct Regs {
+    uint4 ra[LA], rb[PB * RPS];
+    uint32_t mb, off;
+  };
+  Regs regs[DEPTH];
+  const int iters = ntap * nck;
+  auto fetch = [&](Regs& g, int it) {
+    const int kk = (int)a.d_nck.div((uint32_t)it);
+    const int k0 = (it - kk * nck) * BK;
     const int2 ti = taps[kk];
     const int t = ti.x;
     const int cb = colbase + ti.y;
-    mb = img ? vec_mask<T>(tab[t * a.nv + (q >> 3)], q) : 0u;
-    off = 0;
+    g.mb = img ? vec_mask<T>(tab[t * a.nv + (q >> 3)], q) : 0u;
+    g.off = 0;
     const bool kfull = k0 + BK <= a.Co;
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
       const int kv = min(k0 + via * VE, a.Co - VE) - via * VE;  // keeps the vector inside its row
-      ra[i] = *reinterpret_cast<const uint4*>(wt + ((long)t * cico + rowa[i] + kv));
+      g.ra[i] = *reinterpret_cast<const uint4*>(wt + ((long)t * cico + rowa[i] + kv));
     }
     if (inner && kfull) {
 #pragma unroll
       for (int i = 0; i < PB; ++i)
 #pragma unroll
         for (int h = 0; h < RPS; ++h)
-          rb[i * RPS + h] = load_vec<T>(gy + (cb + (k0 + (wrb0 + i * WSTEP) * RPS + h) * a.HWy));
+          g.rb[i * RPS + h] = load_vec<T>(gy + (cb + (k0 + (wrb0 + i * WSTEP) * RPS + h) * a.HWy));
     } else {
 #pragma unroll
       for (int i = 0; i < PB; ++i)
@@ -568,8 +576,8 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
           const int k = min(k0 + (wrb0 + i * WSTEP) * RPS + h, a.Co - 1);
           const int o = cb + k * a.HWy;
           const int oc = min(max(o, 0), a.total_gy - VE);
-          off |= (o != oc) ? 1u << (i * RPS + h) : 0u;
-          rb[i * RPS + h] = load_vec<T>(gy + oc);
+          g.off |= (o != oc) ? 1u << (i * RPS + h) : 0u;
+          g.rb[i * RPS + h] = load_vec<T>(gy + oc);
         }
     }
   };
@@ -587,8 +595,10 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
       *reinterpret_cast<uint4*>(d + 4) = o1;
     }
   };
-  auto stage = [&](int kk, int k0) {
-    if (off) {  // first or last rows of g_y only: shift the moved vectors back
+  auto stage = [&](Regs& g, int it) {
+    const int kk = (int)a.d_nck.div((uint32_t)it);
+    const int k0 = (it - kk * nck) * BK;
+    if (g.off) {  // first or last rows of g_y only: shift the moved vectors back
       const int cb = colbase + taps[kk].y;
 #pragma unroll
       for (int i = 0; i < PB; ++i)
@@ -596,27 +606,27 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
         for (int h = 0; h < RPS; ++h) {
           const int k = min(k0 + (wrb0 + i * WSTEP) * RPS + h, a.Co - 1);
           const int o = cb + k * a.HWy;
-          rb[i * RPS + h] = realign<T>(rb[i * RPS + h], min(max(o - min(max(o, 0), a.total_gy - VE), -VE), VE));
+          g.rb[i * RPS + h] = realign<T>(g.rb[i * RPS + h], min(max(o - min(max(o, 0), a.total_gy - VE), -VE), VE));
         }
     }
     const bool kfull = k0 + BK <= a.Co;
     if (rows_full && kfull) {
 #pragma unroll
-      for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4*>(As + (rowa0 + RPP * i) * RB + via * 16) = ra[i];
+      for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4*>(As + (rowa0 + RPP * i) * RB + via * 16) = g.ra[i];
     } else {
       const bool kok = k0 + via * VE < a.Co;   // C_o is a multiple of VE: a vector is in or out
 #pragma unroll
       for (int i = 0; i < LA; ++i) {
         const int row = rowa0 + RPP * i;
-        *reinterpret_cast<uint4*>(As + row * RB + via * 16) = (kok && m0 + row < a.Ci) ? ra[i] : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(As + row * RB + via * 16) = (kok && m0 + row < a.Ci) ? g.ra[i] : make_uint4(0, 0, 0, 0);
       }
     }
     uint32_t wb[4];
-    expand_mask<T>(mb, wb);
+    expand_mask<T>(g.mb, wb);
     if (kfull) {
 #pragma unroll
       for (int i = 0; i < PB; ++i)
-        put(Bs + (wrb0 + i * WSTEP) * SB + vib * VE, and4(rb[i * RPS], wb), and4(rb[i * RPS + RPS - 1], wb));
+        put(Bs + (wrb0 + i * WSTEP) * SB + vib * VE, and4(g.rb[i * RPS], wb), and4(g.rb[i * RPS + RPS - 1], wb));
     } else {
 #pragma unroll
       for (int i = 0; i < PB; ++i) {
@@ -624,7 +634,7 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
         uint4 val[2];
 #pragma unroll
         for (int h = 0; h < RPS; ++h)
-          val[h] = k0 + wr * RPS + h < a.Co ? and4(rb[i * RPS + h], wb) : make_uint4(0, 0, 0, 0);
+          val[h] = k0 + wr * RPS + h < a.Co ? and4(g.rb[i * RPS + h], wb) : make_uint4(0, 0, 0, 0);
         put(Bs + wr * SB + vib * VE, val[0], val[RPS - 1]);
       }
     }
@@ -636,14 +646,18 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (ntap > 0) fetch(0, 0);
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd)
+    if (dd < iters) fetch(regs[dd], dd);
   const int r = lane & 15, kg = lane >> 4;
-  for (int t = 0; t < ntap; ++t)
-    for (int c = 0; c < nck; ++c) {
-      stage(t, c * BK);
+  for (int it0 = 0; it0 < iters; it0 += DEPTH) {
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) {
+      const int it = it0 + dd;
+      if (it >= iters) break;  // uniform
+      stage(regs[dd], it);
       __syncthreads();
-      if (c + 1 < nck) fetch(t, (c + 1) * BK);
-      else if (t + 1 < ntap) fetch(t + 1, 0);
+      if (it + DEPTH < iters) fetch(regs[dd], it + DEPTH);
       if constexpr (sizeof(T) == 2) {
 #pragma unroll
         for (int ks = 0; ks < BK / KSTEP; ++ks) {  // 32 k = 16 pair rows per MFMA
@@ -678,6 +692,7 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
       }
       __syncthreads();
     }
+  }
 
   // the two wave rows of the tile go out one after the other through an LDS tile of BM / 2
   // rows (rounded once to the storage type), as 16-byte runs of pixels
@@ -758,7 +773,7 @@ bool inner_images_safe(const Geom& g, const XGeo& q) {
 
 struct XPlan {
   size_t off_tabw, off_tabd, off_taps, off_wt, off_xq, off_gxq, off_part, total;
-  int nvw, nvd, nz, chunks_per_z, nchunks, bm, bn;
+  int nvw, nvd, nz, chunks_per_z, nchunks, bm, bn, kv;
 };
 
 // workspace layout, tile shape of the weight-gradient block and its number of K slabs
@@ -783,7 +798,8 @@ XPlan make_plan(const Geom& g, bool want_gw, bool want_gx) {
     const bool small = g.Co <= 64 || g.Ci <= 64;   // 64 x 64 tiles for few channels
     p.bm = small ? 64 : 128;
     p.bn = small ? 64 : 128;
-    const int bk = 16 * Mma<T>::VE;
+    p.kv = 16;   // 256 bytes of K per staged row (128 measured 5-15 % slower)
+    const int bk = p.kv * Mma<T>::VE;
     p.nchunks = cdiv((long)g.N * up8(q.PY), bk);
     const long tiles = (long)cdiv(g.Co, p.bm) * cdiv(g.Ci, p.bn) * g.KK;
     const long slots = small ? 1024 : 512;      // blocks the chip holds at once
@@ -887,12 +903,16 @@ hipError_t dgrad_t(const Geom& g, const XGeo& q, const XPlan& p, const void* g_y
   a.d_hwp = FastDiv((uint32_t)a.HWp);
   // tile shape: 128 x 128 when that still gives about two blocks per compute unit, else narrower
   const long t128 = (long)cdiv(a.Jp, 128) * cdiv(g.Ci, 128) * q.nph;
+  constexpr int VE = Mma<T>::VE;
   if (g.Ci > 64 && t128 >= 400) {
-    hipLaunchKernelGGL((xdgrad_k<T, 4, 4, 8>), dim3(cdiv(a.Jp, 128), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
+    a.d_nck = FastDiv((uint32_t)cdiv(g.Co, 8 * VE));
+    hipLaunchKernelGGL((xdgrad_k<T, 4, 4, 8, 1>), dim3(cdiv(a.Jp, 128), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
   } else if (g.Ci > 64) {
-    hipLaunchKernelGGL((xdgrad_k<T, 4, 2, 16>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
+    a.d_nck = FastDiv((uint32_t)cdiv(g.Co, 16 * VE));
+    hipLaunchKernelGGL((xdgrad_k<T, 4, 2, 16, 1>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
   } else {
-    hipLaunchKernelGGL((xdgrad_k<T, 2, 2, 16>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 64), q.nph), dim3(kThreads), 0, st, a);
+    a.d_nck = FastDiv((uint32_t)cdiv(g.Co, 16 * VE));
+    hipLaunchKernelGGL((xdgrad_k<T, 2, 2, 16, 1>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 64), q.nph), dim3(kThreads), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || g.s == 1) return e;
