@@ -37,6 +37,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
+constexpr double kPlainWgradMinFlops = 6e9;  // below, the 64 x 64 tiles of the S3 kernel (merged with S4 in one launch) are faster
 
 template <class T> struct Mma;
 template <> struct Mma<bf16_t> {
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
   if (z >= a.nz) return;  // uniform for the block
   const int t = (int)a.d_tiles.div((uint32_t)rest), tile = rest - t * a.tiles;
   const int by = (int)a.d_tx.div((uint32_t)tile), bx = tile - by * a.tx;
-  const int delta = a.tapw[t];
+  const int delta = a.tapw ? a.tapw[t] : 0;  // no tables: plain contraction of two maps of the same size
   const int m0 = by * BM, n0 = bx * BN;
   const int kc0 = z * a.chunks_per_z;
   const int kc1 = min(kc0 + a.chunks_per_z, a.nchunks);
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
     const int nn = min(n, a.N - 1);
     const int rem = a.HWy - q;
     ma = (!img || rem <= 0) ? 0u : (rem >= VE ? FULL : (1u << rem) - 1u);
-    mb = img ? vec_mask<T>(a.tab[t * a.nv + (q >> 3)], q) : 0u;
+    mb = a.tab ? (img ? vec_mask<T>(a.tab[t * a.nv + (q >> 3)], q) : 0u) : ma;
     const int basea = nn * coHWy + q, baseb = nn * ciHW + q;
     off = 0;
     if (a.inner_ok && nn > 0 && nn < a.N - 1) {  // inner images: a shifted vector cannot leave the tensors
@@ -939,7 +940,69 @@ hipError_t implicit_t(const Geom& g, const void* x, const void* w, const void* g
   return e;
 }
 
+// K slabs of the plain contraction part[z][co][ci] = sum_{n, p} a[n, co, p] * b[n, ci, p] over maps of P pixels
+template <class T>
+void plain_plan(const Geom& g, int* nz, int* chunks_per_z, int* nchunks) {
+  const int bk = 16 * Mma<T>::VE;
+  *nchunks = cdiv((long)g.N * up8(g.P), bk);
+  const long tiles = (long)cdiv(g.Co, 128) * cdiv(g.Ci, 128);
+  long z = 512 / tiles;
+  const long most = *nchunks / 2 > 0 ? *nchunks / 2 : 1;
+  if (z > most) z = most;
+  if (z < 1) z = 1;
+  *chunks_per_z = cdiv(*nchunks, z);
+  *nz = cdiv(*nchunks, *chunks_per_z);
+}
+
+template <class T>
+hipError_t plain_wgrad_t(const Geom& g, const void* x_u, const void* gy_u, float* part, int* nz_out,
+                         hipStream_t st) {
+  XWgradArgs a;
+  a.gy = gy_u; a.x = x_u; a.part = part;
+  a.tab = nullptr; a.tapw = nullptr;
+  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.KK = 1;
+  a.HW = g.P; a.HWy = g.P; a.HWyp = up8(g.P); a.nv = 0;
+  plain_plan<T>(g, &a.nz, &a.chunks_per_z, &a.nchunks);
+  a.tx = cdiv(g.Ci, 128);
+  a.tiles = a.tx * cdiv(g.Co, 128);
+  a.R = a.tiles;
+  a.xcd_slabs = a.nz >= 8 ? 1 : 0;
+  a.inner_ok = ((long)g.Ci * g.P >= 16 && (long)g.Co * g.P >= 16) ? 1 : 0;
+  a.total_x = g.N * g.Ci * g.P;
+  a.total_gy = g.N * g.Co * g.P;
+  a.d_hwyp = FastDiv((uint32_t)a.HWyp);
+  a.d_r = FastDiv((uint32_t)a.R);
+  a.d_tiles = FastDiv((uint32_t)a.tiles);
+  a.d_tx = FastDiv((uint32_t)a.tx);
+  *nz_out = a.nz;
+  const dim3 grid(a.xcd_slabs ? 8 * a.R * cdiv(a.nz, 8) : a.R * a.nz);
+  hipLaunchKernelGGL((xwgrad_k<T, 4, 4, 16>), grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+// The filtered weight gradient (Eq. 5) of a large dense layer is the same contraction with one
+// tap and no padding: these are the 128 x 128 tiles of the exact weight gradient on x_u and gy_u.
+bool plain_wgrad_ok(const Geom& g) {
+  const long lim = 2147483647L;
+  if (g.g != 1 || g.Co < 128 || g.Ci < 128) return false;
+  if ((long)g.N * g.Ci * g.P + 1024 >= lim || (long)g.N * g.Co * g.P + 1024 >= lim) return false;
+  if ((long)g.N * up8(g.P) + 1024 >= lim || (long)g.N * g.Ci * g.P < 16 || (long)g.N * g.Co * g.P < 16) return false;
+  return 2.0 * g.Co * g.Ci * g.N * g.P >= kPlainWgradMinFlops;
+}
+
+int plain_wgrad_splits(const Geom& g) {
+  int nz, cpz, nch;
+  if (g.dtype == GF_BF16) plain_plan<bf16_t>(g, &nz, &cpz, &nch); else plain_plan<float>(g, &nz, &cpz, &nch);
+  return nz;
+}
+
+hipError_t launch_plain_wgrad(const Geom& g, const void* x_u, const void* gy_u, float* part, int* nz_out,
+                              hipStream_t st) {
+  return g.dtype == GF_BF16 ? plain_wgrad_t<bf16_t>(g, x_u, gy_u, part, nz_out, st)
+                            : plain_wgrad_t<float>(g, x_u, gy_u, part, nz_out, st);
+}
 
 // Dense layers with channel counts that are multiples of the vector length, whose tap offsets
 // are constant in flattened pixels: stride 1 with W_y == W, or stride s with ceil(W / s) <= W_y

@@ -150,6 +150,11 @@ hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, voi
 // (gf_implicit.hip).  ws as sized by ws_implicit().
 bool implicit_ok(const Geom& g);
 size_t ws_implicit(const Geom& g, bool want_gw, bool want_gx);
+// plain contraction part[z][co][ci] = sum_{n, p} gy_u * x_u on the same 128 x 128 tiles (large dense S3)
+bool plain_wgrad_ok(const Geom& g);
+int plain_wgrad_splits(const Geom& g);
+hipError_t launch_plain_wgrad(const Geom& g, const void* x_u, const void* gy_u, float* part, int* nz_out,
+                              hipStream_t st);
 hipError_t launch_implicit(const Geom& g, const void* x, const void* w, const void* g_y, float* g_w, void* g_x,
                            void* ws, hipStream_t st);
 

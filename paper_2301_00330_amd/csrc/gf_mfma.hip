@@ -901,6 +901,10 @@ int wgrad_chunks(const Geom& g) {
 // one chunk per block is slower on the 144 x 24 x 25088 and 512 x 512 x 1024 problems).
 int mfma_wgrad_splits(const Geom& g, int* chunks_per_z) {
   const int nchunks = wgrad_chunks(g);
+  if (plain_wgrad_ok(g)) {
+    if (chunks_per_z) *chunks_per_z = 0;
+    return plain_wgrad_splits(g);
+  }
   int bm, bn;
   wgrad_tile(wgrad_shape(g), &bm, &bn);
   const int tiles = cdiv(g.Co, bm) * cdiv(g.Ci, bn);
@@ -941,6 +945,7 @@ static hipError_t wgrad_t(const Geom& g, const void* x_u, const void* gy_u, floa
 
 hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, float* part,
                              int* nz_out, hipStream_t st) {
+  if (plain_wgrad_ok(g)) return launch_plain_wgrad(g, x_u, gy_u, part, nz_out, st);
   if (g.dtype == GF_BF16) return wgrad_t<bf16_t>(g, x_u, gy_u, part, nz_out, st);
   return wgrad_t<float>(g, x_u, gy_u, part, nz_out, st);
 }
@@ -1060,6 +1065,9 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
     return dgrad_launch<T, 2, 2, 2, 2>(a, false, st);
   }
   if (ksplit) return dgrad_ksplit_launch<T, 64>(a, vec, st);
+  // many tiles: 128 x 128 halves the operand re-reads from L2, which bound the 64 x 64 tiling
+  if (vec && g.Ci >= 256 && (long)cdiv(a.Jtot, 128) * cdiv(g.Ci, 128) >= 512)
+    return dgrad_launch<T, 4, 4, 2, 2>(a, vec, st);
   if (g.Ci <= 32) return dgrad_launch<T, 2, 2, 1, 4>(a, vec, st);
   if (vec && g.Ci >= 256 && !full && (long)g.N * g.P * g.Co * g.b >= kHugeOperandBytes)
     return dgrad_launch<T, 4, 4, 4, 1>(a, vec, st);  // huge gy_u (column tensor): read it once
@@ -1072,7 +1080,7 @@ template <class T>
 static bool s3s4_ok(const Geom& g) {
   constexpr int VE = Mma<T>::VE;
   if (g.g != 1 || g.Ci % VE != 0) return false;
-  if (wgrad_shape(g) == 4) return false;
+  if (wgrad_shape(g) == 4 || plain_wgrad_ok(g)) return false;
   const bool runs = dgrad_full_ok<T>(g);
   if (!runs && !dgrad_planes_ok(g)) return false;
   if (g.P % VE != 0) {  // image-block loaders on both sides
