@@ -265,6 +265,7 @@ struct ExpandArgs {
   float scalar;
   int C, H, W, rx, Hp, Wp;
   int total;  // planes * H * W
+  FastDiv d_hw, d_w, d_rx, d_c, d_p;
 };
 
 template <class T, class S>
@@ -275,20 +276,27 @@ __global__ __launch_bounds__(kThreads) void expand_k(ExpandArgs a) {
   const int e0 = (blockIdx.x * kThreads + threadIdx.x) * V;
   if (e0 >= a.total) return;
   const int HW = a.H * a.W;
-  int plane = e0 / HW;
+  int plane = (int)a.d_hw.div((uint32_t)e0);
   int rem = e0 - plane * HW;
-  int h = rem / a.W;
+  int h = (int)a.d_w.div((uint32_t)rem);
   int w = rem - h * a.W;
-  int hp = h / a.rx, hr = h - hp * a.rx;
-  int wp = w / a.rx, wr = w - wp * a.rx;
-  float sc = a.scalar * (a.chscale ? a.chscale[plane % a.C] : 1.f);
+  int hp = (int)a.d_rx.div((uint32_t)h), hr = h - hp * a.rx;
+  int wp = (int)a.d_rx.div((uint32_t)w), wr = w - wp * a.rx;
   const int P = a.Hp * a.Wp;
-  T vals[V];
+  // source index and channel of every element first, then all loads together (a load inside
+  // the stepping loop would be waited for before the next one is issued)
+  int sidx[V], chan[V];
+  const int last = a.total - 1 - e0;  // elements past the end repeat the last valid one
+  int c = plane - (int)a.d_c.div((uint32_t)plane) * a.C;
 #pragma unroll
   for (int k = 0; k < V; ++k) {
-    float v = 0.f;
-    if (e0 + k < a.total) v = to_f32(src[(long)plane * P + hp * a.Wp + wp]) * sc;
-    vals[k] = from_f32<T>(v);
+    if (k <= last) {
+      sidx[k] = plane * P + hp * a.Wp + wp;
+      chan[k] = c;
+    } else {
+      sidx[k] = sidx[k > 0 ? k - 1 : 0];
+      chan[k] = chan[k > 0 ? k - 1 : 0];
+    }
     // advance one output element
     ++w;
     if (++wr == a.rx) { wr = 0; ++wp; }
@@ -299,14 +307,82 @@ __global__ __launch_bounds__(kThreads) void expand_k(ExpandArgs a) {
       if (h == a.H) {
         h = 0; hp = 0; hr = 0;
         ++plane;
-        sc = a.scalar * (a.chscale ? a.chscale[plane % a.C] : 1.f);
+        if (++c == a.C) c = 0;
       }
     }
   }
+  S sv[V];
+  float scv[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) sv[k] = src[sidx[k]];
+#pragma unroll
+  for (int k = 0; k < V; ++k) scv[k] = a.chscale ? a.chscale[chan[k]] : 1.f;
+  T vals[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) vals[k] = from_f32<T>(to_f32(sv[k]) * (a.scalar * scv[k]));
   if (e0 + V <= a.total) {
     *reinterpret_cast<uint4*>(out + e0) = *reinterpret_cast<const uint4*>(vals);
   } else {
     for (int k = 0; e0 + k < a.total; ++k) out[e0 + k] = vals[k];
+  }
+}
+
+// The same for small or unaligned maps, through LDS: a block writes 8192 consecutive output
+// elements, which belong to a few whole or partial planes; their scaled source values
+// (planes * P of them, at most kExpandLdsMax) are first loaded with coalesced reads, then every
+// lane gathers its 16-byte run from LDS.  Same arithmetic as expand_k: src * (scalar * chscale).
+constexpr int kExpandLdsMax = 4096;
+constexpr int kExpandPerBlock = kThreads * 32;
+
+template <class T, class S>
+__global__ __launch_bounds__(kThreads) void expand_lds_k(ExpandArgs a) {
+  constexpr int V = 16 / (int)sizeof(T);
+  constexpr int PER = kExpandPerBlock / (kThreads * V);  // 16-byte runs per lane
+  __shared__ float sval[kExpandLdsMax];
+  const S* src = static_cast<const S*>(a.src);
+  T* out = static_cast<T*>(a.out);
+  const int HW = a.H * a.W, P = a.Hp * a.Wp;
+  const int b0 = blockIdx.x * kExpandPerBlock;
+  const int b1 = min(b0 + kExpandPerBlock, a.total);
+  const int plane0 = (int)a.d_hw.div((uint32_t)b0);
+  const int plane1 = (int)a.d_hw.div((uint32_t)(b1 - 1));
+  const int nsrc = (plane1 - plane0 + 1) * P;
+  for (int i = threadIdx.x; i < nsrc; i += kThreads) {
+    const int pl = plane0 + (int)a.d_p.div((uint32_t)i);
+    const int c = pl - (int)a.d_c.div((uint32_t)pl) * a.C;
+    const float sc = a.scalar * (a.chscale ? a.chscale[c] : 1.f);
+    sval[i] = to_f32(src[(long)plane0 * P + i]) * sc;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
+    const int e0 = b0 + (it * kThreads + threadIdx.x) * V;
+    if (e0 >= b1) break;
+    int plane = (int)a.d_hw.div((uint32_t)e0);
+    int rem = e0 - plane * HW;
+    int h = (int)a.d_w.div((uint32_t)rem);
+    int w = rem - h * a.W;
+    int hp = (int)a.d_rx.div((uint32_t)h), hr = h - hp * a.rx;
+    int wp = (int)a.d_rx.div((uint32_t)w), wr = w - wp * a.rx;
+    int base = (plane - plane0) * P;
+    T vals[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      vals[k] = from_f32<T>(sval[min(base + hp * a.Wp + wp, nsrc - 1)]);
+      ++w;
+      if (++wr == a.rx) { wr = 0; ++wp; }
+      if (w == a.W) {
+        w = 0; wp = 0; wr = 0;
+        ++h;
+        if (++hr == a.rx) { hr = 0; ++hp; }
+        if (h == a.H) { h = 0; hp = 0; hr = 0; base += P; }
+      }
+    }
+    if (e0 + V <= a.total) {
+      *reinterpret_cast<uint4*>(out + e0) = *reinterpret_cast<const uint4*>(vals);
+    } else {
+      for (int k = 0; e0 + k < a.total; ++k) out[e0 + k] = vals[k];
+    }
   }
 }
 
@@ -409,6 +485,16 @@ hipError_t launch_expand(const S* src, T* out, const float* chscale, float scala
   a.Hp = Hp;
   a.Wp = Wp;
   a.total = (int)(planes * H * W);
+  a.d_hw = FastDiv((uint32_t)(H * W));
+  a.d_w = FastDiv((uint32_t)W);
+  a.d_rx = FastDiv((uint32_t)rx);
+  a.d_c = FastDiv((uint32_t)C);
+  a.d_p = FastDiv((uint32_t)(Hp * Wp));
+  // planes a block of kExpandPerBlock outputs can touch, times the values per plane
+  if (((long)kExpandPerBlock / (H * W) + 2) * Hp * Wp <= kExpandLdsMax) {
+    hipLaunchKernelGGL((expand_lds_k<T, S>), dim3(cdiv(a.total, kExpandPerBlock)), dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+  }
   constexpr int V = 16 / (int)sizeof(T);
   const int blocks = cdiv(cdiv(a.total, V), kThreads);
   hipLaunchKernelGGL((expand_k<T, S>), dim3(blocks), dim3(kThreads), 0, st, a);

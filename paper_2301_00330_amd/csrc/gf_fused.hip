@@ -1,11 +1,12 @@
-// One launch for the whole filtered backward of a depthwise layer (stride 1):
+// One launch for the whole filtered backward of a depthwise layer:
 // gradient filter (Eq. 2), weight gradient (Eq. 5) and input gradient (Eq. 3).
 // g_y is read once; the patch means are rounded to the storage type exactly as the
 // stand-alone filter stores them, multiplied with x_u for the weight-gradient
 // partial, scaled by the kernel sum (text after Eq. 3, formed in the kernel) and
-// written back over the same pixel positions as g_x.  Two variants mirror the two
+// written back over the same pixel positions as g_x.  Two stride-1 variants mirror the two
 // patch-reduction kernels: register rows for 16-byte-aligned maps, LDS-staged
-// flat planes for small or ragged maps.
+// flat planes for small or ragged maps.  Strided layers use a third, LDS-staged variant
+// with separate images of the g_y run and of the (s^2 times larger) g_x run.
 #include "gf_internal.h"
 
 namespace gf {
@@ -28,9 +29,11 @@ struct DwFusedArgs {
   // rows variant
   int ipr, ipp, cpp;  // items per row / per plane, chunks per plane
   FastDiv d_ipr, d_cpp, d_c;
-  // LDS variant
+  // LDS variants
   int ppb;            // planes per block
   FastDiv d_wp, d_p;
+  // strided LDS variant: g_y is [planes, Hy, Wy], patches q on g_y and qx = q * stride on g_x
+  int Hy, Wy, qx;
 };
 
 // fixed-order block sum of one float per lane; result valid in lane 0 of the block
@@ -261,6 +264,116 @@ __global__ __launch_bounds__(kThreads) void dw_fused_lds_k(DwFusedArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Strided LDS variant.  A block owns ppb whole planes: the flat run of g_y ([Hy, Wy] per plane)
+// is loaded into LDS, every lane reduces one q x q patch (in-bounds pixels only) and writes
+// the input-gradient value to the patch's qx x qx pixels of an LDS image of the g_x run
+// ([H, W] per plane), which is then stored with coalesced vectors.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(kThreads) void dw_fused_strided_k(DwFusedArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int HW = a.H * a.W, HWy = a.Hy * a.Wy;
+  const int pl0 = blockIdx.x * a.ppb;
+  const int np = min(a.ppb, a.planes - pl0);
+  // layout: [g_y run, 16-aligned][g_x run, 16-aligned][prods: ppb * P floats][sc: ppb floats]
+  const int in_bytes = ((a.ppb * HWy * (int)sizeof(T) + 32) + 15) & ~15;
+  const int out_bytes = ((a.ppb * HW * (int)sizeof(T) + 32) + 15) & ~15;
+  unsigned char* obuf = smem + in_bytes;
+  float* prods = reinterpret_cast<float*>(obuf + out_bytes);
+  float* scs = prods + a.ppb * a.P;
+  // ---- load the g_y run
+  const long ib0 = (long)pl0 * HWy * (long)sizeof(T);
+  const long ia0 = ib0 & ~15L;
+  const int ispan = (int)(ib0 + (long)np * HWy * (long)sizeof(T) - ia0);
+  const int invec = ispan >> 4;
+  const int ishift = (int)(ib0 - ia0);
+  const uint4* src = reinterpret_cast<const uint4*>(static_cast<const unsigned char*>(a.gy) + ia0);
+  uint4* in4 = reinterpret_cast<uint4*>(smem);
+  for (int v = tid; v < invec; v += 4 * kThreads) {
+    uint4 rg[4];
+    int idx[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) idx[k] = min(v + k * kThreads, invec - 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) rg[k] = src[idx[k]];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) in4[idx[k]] = rg[k];
+  }
+  {
+    const int tail0 = invec << 4;
+    const int ntail = (ispan - tail0) / (int)sizeof(T);
+    if (tid < ntail)
+      reinterpret_cast<T*>(smem + tail0)[tid] =
+          reinterpret_cast<const T*>(reinterpret_cast<const unsigned char*>(src) + tail0)[tid];
+  }
+  if (tid < np) {
+    const int pl = pl0 + tid;
+    const int c = pl - (int)a.d_c.div((uint32_t)pl) * a.C;
+    scs[tid] = kernel_sum_of(static_cast<const T*>(a.w), c, a.KK) * a.scale;
+  }
+  __syncthreads();
+  // ---- patch means, products with x_u, replicated values into the g_x image
+  const long ob0 = (long)pl0 * HW * (long)sizeof(T);
+  const long oa0 = ob0 & ~15L;
+  const int oshift = (int)(ob0 - oa0);
+  const int ospan = oshift + np * HW * (int)sizeof(T);
+  const T* lin = reinterpret_cast<const T*>(smem + ishift);   // lin[e], e relative to the first g_y plane
+  T* lout = reinterpret_cast<T*>(obuf + oshift);              // lout[e], e relative to the first g_x plane
+  const T* xu = static_cast<const T*>(a.xu) + (long)pl0 * a.P;
+  T* gyu = a.gyu ? static_cast<T*>(a.gyu) + (long)pl0 * a.P : nullptr;
+  const int nout = np * a.P;
+  const int q = a.q, qx = a.qx;
+  for (int lo = tid; lo < nout; lo += kThreads) {
+    const int lp = (int)a.d_p.div((uint32_t)lo);  // local plane
+    const int pp = lo - lp * a.P;
+    const int hp = (int)a.d_wp.div((uint32_t)pp);
+    const int wp = pp - hp * a.Wp;
+    const int ch = min(q, a.Hy - hp * q);
+    const int cw = min(q, a.Wy - wp * q);
+    const int base = lp * HWy + hp * q * a.Wy + wp * q;
+    const float xval = to_f32(xu[lo]);
+    float acc = 0.f;
+    for (int i = 0; i < ch; ++i)
+      for (int j = 0; j < cw; ++j) acc += to_f32(lin[base + i * a.Wy + j]);
+    const T mean = from_f32<T>(acc / (float)(ch * cw));
+    const float m = to_f32(mean);
+    if (gyu) gyu[lo] = mean;
+    prods[lo] = m * xval;
+    const T g = from_f32<T>(m * scs[lp]);
+    const int oh = min(qx, a.H - hp * qx), ow = min(qx, a.W - wp * qx);
+    const int obase = lp * HW + hp * qx * a.W + wp * qx;
+    for (int i = 0; i < oh; ++i)
+      for (int j = 0; j < ow; ++j) lout[obase + i * a.W + j] = g;
+  }
+  __syncthreads();
+  // ---- store the g_x run: whole vectors strictly inside it, head and tail by element
+  T* out = static_cast<T*>(a.gx);
+  unsigned char* dstb = static_cast<unsigned char*>(a.gx) + oa0;
+  const uint4* o4 = reinterpret_cast<const uint4*>(obuf);
+  const int onvec = ospan >> 4;
+  const int v0 = oshift ? 1 : 0;  // the first vector is shared with the previous block's planes
+  for (int v = tid + v0; v < onvec; v += kThreads) *reinterpret_cast<uint4*>(dstb + ((long)v << 4)) = o4[v];
+  if (oshift) {
+    const int nhead = (16 - oshift) / (int)sizeof(T);  // elements of this block in vector 0
+    if (tid < nhead && tid < np * HW) out[(long)pl0 * HW + tid] = lout[tid];
+  }
+  {
+    const int tail0 = onvec << 4;
+    const int ntail = (ospan - tail0) / (int)sizeof(T);
+    const int efirst = (tail0 - oshift) / (int)sizeof(T);
+    if (tid < ntail && efirst + tid >= 0) out[(long)pl0 * HW + efirst + tid] = lout[efirst + tid];
+  }
+  // per-plane dot product in fixed order
+  if (tid < np) {
+    float s = 0.f;
+    const float* pr = prods + tid * a.P;
+    for (int k = 0; k < a.P; ++k) s += pr[k];
+    a.part[pl0 + tid] = s;
+  }
+}
+
 template <class T>
 bool rows_variant_ok(const Geom& g) {
   constexpr int VE = Vec16<T>::N;
@@ -282,11 +395,29 @@ int lds_planes_per_block(const Geom& g) {
   return (int)ppb;
 }
 
+template <class T>
+int strided_planes_per_block(const Geom& g) {
+  const long per_plane = ((long)g.H * g.W + (long)g.Hy * g.Wy) * sizeof(T) + (long)g.P * 4 + 4;
+  long ppb = (kLdsBudget - 128) / per_plane;
+  const long planes = (long)g.N * g.Ci;
+  if (ppb > planes / 1024) ppb = planes / 1024;  // keep ~4 blocks per CU when the tensor allows
+  if (ppb > kThreads) ppb = kThreads;
+  const long fit = (64 * 1024 - 128) / per_plane;
+  if (ppb < 1) ppb = fit >= 1 ? 1 : 0;
+  return (int)ppb;
+}
+
 }  // namespace
 
 // shapes the fused depthwise launch handles; *nz = number of partial slabs per channel
 bool dw_fused_ok(const Geom& g, int* nz) {
-  if (!(g.Cg == 1 && g.Og == 1) || g.s != 1 || g.r < 2) return false;
+  if (!(g.Cg == 1 && g.Og == 1) || g.r < 2) return false;
+  if (g.s != 1) {  // strided: whole planes of g_y and g_x side by side in LDS
+    const int ppb = g.dtype == GF_BF16 ? strided_planes_per_block<bf16_t>(g) : strided_planes_per_block<float>(g);
+    if (ppb < 1) return false;
+    if (nz) *nz = g.N;
+    return true;
+  }
   if (g.Hy != g.H || g.Wy != g.W) return false;
   const bool rows = g.dtype == GF_BF16 ? rows_variant_ok<bf16_t>(g) : rows_variant_ok<float>(g);
   if (rows) {
@@ -309,8 +440,19 @@ static hipError_t dw_fused_t(const Geom& g, const void* g_y, const void* x_u, co
   a.gy = g_y; a.xu = x_u; a.w = w; a.gyu = gy_u; a.gx = g_x; a.part = part;
   a.C = g.Ci; a.H = g.H; a.W = g.W; a.Hp = g.Hp; a.Wp = g.Wp; a.P = g.P; a.KK = g.KK; a.q = g.r;
   a.planes = g.N * g.Ci;
-  a.scale = 1.f;  // stride 1
+  a.scale = 1.f / ((float)g.s * (float)g.s);
   a.d_c = FastDiv((uint32_t)g.Ci);
+  if (g.s != 1) {
+    a.Hy = g.Hy; a.Wy = g.Wy; a.qx = g.rx;
+    a.ppb = strided_planes_per_block<T>(g);
+    a.d_wp = FastDiv((uint32_t)g.Wp);
+    a.d_p = FastDiv((uint32_t)g.P);
+    const int in_bytes = ((a.ppb * g.Hy * g.Wy * (int)sizeof(T) + 32) + 15) & ~15;
+    const int out_bytes = ((a.ppb * g.H * g.W * (int)sizeof(T) + 32) + 15) & ~15;
+    const size_t lds = (size_t)in_bytes + out_bytes + (size_t)a.ppb * g.P * 4 + (size_t)a.ppb * 4;
+    hipLaunchKernelGGL(dw_fused_strided_k<T>, dim3(cdiv(a.planes, a.ppb)), dim3(kThreads), lds, st, a);
+    return hipGetLastError();
+  }
   if (rows_variant_ok<T>(g)) {
     constexpr int VE = Vec16<T>::N;
     const int IW = VE > g.r ? VE : g.r;

@@ -196,6 +196,10 @@ FUSED_EXTRA = [
     (3, 10, 10, 7, 7, 3, 1, 1, 1, 10, 4),         # ragged, r = 4
     (2, 9, 9, 9, 9, 3, 1, 1, 1, 9, 3),            # r = 3 (run-time patch size)
     (1, 3, 3, 5, 5, 5, 1, 2, 1, 3, 8),            # one patch per plane, tiny tensor
+    (5, 33, 33, 15, 13, 3, 2, 1, 1, 33, 2),       # depthwise, strided, odd map and odd plane count (one-pass strided variant)
+    (2, 10, 10, 18, 18, 3, 3, 1, 1, 10, 2),       # depthwise, stride 3
+    (3, 16, 16, 28, 28, 3, 2, 1, 1, 16, 4),       # depthwise, strided, ragged patches on g_y (14 = 3 x 4 + 2)
+    (1, 3, 3, 6, 6, 3, 2, 1, 1, 3, 8),            # depthwise, strided, one patch per plane
     (3, 24, 144, 56, 56, 1, 1, 0, 1, 1, 2),       # MobileNetV2 expand shape
     (3, 144, 24, 56, 56, 1, 1, 0, 1, 1, 2),       # MobileNetV2 project shape
     (2, 40, 56, 32, 32, 3, 1, 1, 1, 1, 4),        # 3x3, r = 4, channels not multiples of 16
