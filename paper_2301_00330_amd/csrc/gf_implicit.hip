@@ -62,18 +62,9 @@ template <class T> struct Unal;
 template <> struct __attribute__((packed, aligned(2))) Unal<bf16_t> { uint32_t w[4]; };
 template <> struct __attribute__((packed, aligned(4))) Unal<float> { uint32_t w[4]; };
 
-// Elements o .. o + VE - 1 of a tensor of `total` (>= VE) elements.  The load is clamped into
-// the tensor; `sh` tells realign() by how many elements the data is off.  Elements whose own
-// address lies outside the tensor come out as zeros after realign().
-template <class T>
-__device__ __forceinline__ uint4 load_clamped(const T* base, int total, int o, int& sh) {
-  constexpr int VE = Mma<T>::VE;
-  const int oc = min(max(o, 0), total - VE);
-  sh = min(max(o - oc, -VE), VE);
-  const Unal<T> v = *reinterpret_cast<const Unal<T>*>(base + oc);
-  return make_uint4(v.w[0], v.w[1], v.w[2], v.w[3]);
-}
-
+// 16 bytes from an element-aligned address.  Loads near the ends of a tensor are issued at an
+// offset clamped into the tensor; realign() then shifts the vector by the difference, and the
+// elements whose own address lies outside the tensor come out as zeros.
 template <class T>
 __device__ __forceinline__ uint4 load_vec(const T* p) {
   const Unal<T> v = *reinterpret_cast<const Unal<T>*>(p);
