@@ -232,12 +232,17 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
     return dev(launch_finalize(part, g_w, g.Ci, nz, g.KK, 1.f / ((float)g.s * (float)g.s), st));
   }
   void* gyu = gy_u ? gy_u : static_cast<void*>(wsb);
-  rc = dev(launch_patch_reduce(g_y, gyu, (long)g.N * g.Co, g.Hy, g.Wy, g.r, true, g.dtype, st));
+  const bool merged = mfma_s3s4_ok(g);
+  // the kernel sums (S2) ride along with the filter launch when the merged launch needs them
+  KsumJob ksum = {w, wsb + off_i, g.Co * g.Ci, g.KK};
+  const bool ride = merged && g.KK > 1;
+  rc = dev(launch_patch_reduce(g_y, gyu, (long)g.N * g.Co, g.Hy, g.Wy, g.r, true, g.dtype, st,
+                               ride ? &ksum : nullptr));
   if (rc) return rc;
-  if (mfma_s3s4_ok(g)) {  // dense, aligned: weight and input gradient share one launch
+  if (merged) {  // dense: weight and input gradient share one launch
     float* part = reinterpret_cast<float*>(wsb + off_w);
     int nzs = 0;
-    rc = dev(launch_mfma_s3s4(g, x_u, gyu, w, wsb + off_i, part, &nzs, g_x, st));
+    rc = dev(launch_mfma_s3s4(g, x_u, gyu, w, wsb + off_i, part, &nzs, g_x, st, ride));
     if (rc) return rc;
     return dev(launch_finalize(part, g_w, g.Co * g.Ci, nzs, g.KK, 1.f / ((float)g.s * (float)g.s), st));
   }

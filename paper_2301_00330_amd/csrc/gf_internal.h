@@ -95,9 +95,18 @@ struct FastDiv {
 
 // ---- launchers; each returns the hipError_t of its launches ----------------
 
-// S0 / S1: out[plane, hp, wp] = sum or mean of in[plane] over q x q patches.
+// S2 as a side job of another launch: out[e] = spatial sum of kernel e (pairs of them, KK taps
+// each), rounded to the storage type.
+struct KsumJob {
+  const void* w;
+  void* out;
+  int pairs, KK;
+};
+
+// S0 / S1: out[plane, hp, wp] = sum or mean of in[plane] over q x q patches.  With `ksum` the
+// same launch also forms the kernel sums (extra blocks at the end of the grid).
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
-                               bool mean, int dtype, hipStream_t st);
+                               bool mean, int dtype, hipStream_t st, const KsumJob* ksum = nullptr);
 
 // S2: wsum[co, cl] = sum over taps of w[co, cl, :, :], fp32.
 hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int dtype,
@@ -125,7 +134,8 @@ hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, voi
 // both gradients of a dense layer in one launch (then launch_finalize on `part`, nz slabs)
 bool mfma_s3s4_ok(const Geom& g);
 hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
-                            void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st);
+                            void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st,
+                            bool wsum_ready = false);
 // true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
 bool mfma_dgrad_writes_full(const Geom& g);
 

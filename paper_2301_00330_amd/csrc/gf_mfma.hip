@@ -1137,10 +1137,14 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
 
 template <class T>
 static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const void* w, void* wsum_t,
-                         float* part, int* nz_out, void* g_x, hipStream_t st) {
+                         float* part, int* nz_out, void* g_x, hipStream_t st, bool wsum_ready) {
   const T* wt = nullptr;
-  hipError_t e = kernel_sum_if_needed<T>(g, w, wsum_t, &wt, st);
-  if (e != hipSuccess) return e;
+  if (wsum_ready && g.KK > 1) {
+    wt = static_cast<const T*>(wsum_t);  // formed by an earlier launch of the same call
+  } else {
+    hipError_t e = kernel_sum_if_needed<T>(g, w, wsum_t, &wt, st);
+    if (e != hipSuccess) return e;
+  }
   WgradMfmaArgs wa;
   wa.gyu = gy_u; wa.xu = x_u; wa.part = part;
   wa.Ci = g.Ci; wa.Co = g.Co; wa.P = g.P; wa.Ktot = g.N * g.P;
@@ -1174,9 +1178,10 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
 }
 
 hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
-                            void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st) {
-  if (g.dtype == GF_BF16) return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st);
-  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st);
+                            void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st,
+                            bool wsum_ready) {
+  if (g.dtype == GF_BF16) return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready);
+  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready);
 }
 
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,

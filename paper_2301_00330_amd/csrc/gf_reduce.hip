@@ -32,13 +32,28 @@ struct ReduceArgs {
   int ipr;           // items per row (rows kernel)
   int total_items;   // total_strips * ipr
   FastDiv d_hp, d_wp, d_ipr;
+  // side job (text after Eq. 3): blocks from ks_block0 on form kernel sums instead
+  const void* ks_w;
+  void* ks_out;
+  int ks_pairs, ks_KK, ks_block0;
 };
+
+// the kernel-sum side job; true if this block belongs to it (uniform for the block)
+template <class T>
+__device__ __forceinline__ bool ksum_side_job(const ReduceArgs& a) {
+  if (a.ks_pairs == 0 || (int)blockIdx.x < a.ks_block0) return false;
+  const int e = ((int)blockIdx.x - a.ks_block0) * kThreads + threadIdx.x;
+  if (e < a.ks_pairs)
+    static_cast<T*>(a.ks_out)[e] = from_f32<T>(kernel_sum_of(static_cast<const T*>(a.ks_w), e, a.ks_KK));
+  return true;
+}
 
 // ---------------------------------------------------------------------------
 // rows kernel: requires W % max(VE, Q) == 0 and (W * sizeof(T)) % 16 == 0
 // ---------------------------------------------------------------------------
 template <class T, int Q, int U>
 __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
+  if (ksum_side_job<T>(a)) return;
   constexpr int VE = Vec16<T>::N;            // elements per 16-byte vector
   constexpr int IW = VE > Q ? VE : Q;        // elements of one row an item covers
   constexpr int VW = IW / VE;                // vectors per row per item
@@ -112,6 +127,7 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
 // ---------------------------------------------------------------------------
 template <class T, int QT>  // QT: compile-time patch size, 0 = run-time
 __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
+  if (ksum_side_job<T>(a)) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int s0 = blockIdx.x * a.spb;
@@ -184,10 +200,12 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
 // Fallback without LDS for strips too large to stage: one lane per patch.
 template <class T>
 __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
+  if (ksum_side_job<T>(a)) return;
   const T* in = static_cast<const T*>(a.in);
   T* out = static_cast<T*>(a.out);
   const long nout = (long)a.total_strips * a.Wp;
-  for (long o = (long)blockIdx.x * kThreads + threadIdx.x; o < nout; o += (long)gridDim.x * kThreads) {
+  for (long o = (long)blockIdx.x * kThreads + threadIdx.x; o < nout;
+       o += (long)(a.ks_pairs ? a.ks_block0 : (int)gridDim.x) * kThreads) {
     const int strip = (int)(o / a.Wp);
     const int wp = (int)(o - (long)strip * a.Wp);
     const int pl = strip / a.Hp;
@@ -212,7 +230,8 @@ hipError_t launch_rows(ReduceArgs& a, hipStream_t st) {
   a.total_items = a.total_strips * a.ipr;
   a.d_ipr = FastDiv((uint32_t)a.ipr);
   const int blocks = cdiv(a.total_items, kThreads * U);
-  hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks), dim3(kThreads), 0, st, a);
+  a.ks_block0 = blocks;
+  hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -237,7 +256,8 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
     const long nout = (long)a.total_strips * a.Wp;
     int blocks = (int)((nout + kThreads - 1) / kThreads);
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks), dim3(kThreads), 0, st, a);
+    a.ks_block0 = blocks;
+    hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
     return hipGetLastError();
   }
   int spb = (int)((kLdsBudget - 32) / strip_bytes);
@@ -249,22 +269,27 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
   a.spb = spb;
   const size_t lds = (size_t)spb * strip_bytes + 32;
   const int blocks = (a.total_strips + spb - 1) / spb;
+  a.ks_block0 = blocks;
+  const dim3 grid(blocks + cdiv(a.ks_pairs, kThreads));
   if (a.q == 2)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 2>), dim3(blocks), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 2>), grid, dim3(kThreads), lds, st, a);
   else if (a.q == 4)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 4>), dim3(blocks), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 4>), grid, dim3(kThreads), lds, st, a);
   else if (a.q == 8)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 8>), dim3(blocks), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 8>), grid, dim3(kThreads), lds, st, a);
   else
-    hipLaunchKernelGGL((patch_reduce_lds<T, 0>), dim3(blocks), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 0>), grid, dim3(kThreads), lds, st, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
-                               bool mean, int dtype, hipStream_t st) {
+                               bool mean, int dtype, hipStream_t st, const KsumJob* ksum) {
   ReduceArgs a = {};
+  if (ksum) {
+    a.ks_w = ksum->w; a.ks_out = ksum->out; a.ks_pairs = ksum->pairs; a.ks_KK = ksum->KK;
+  }
   a.in = in;
   a.out = out;
   a.H = H;
