@@ -93,6 +93,7 @@ PAPER_CASES = Config(7, "on-device test cases of Table 7", 32,
                          [(128, 120, 160), (256, 60, 80), (512, 30, 40), (512, 14, 14), (256, 14, 14),
                           (128, 28, 28), (64, 56, 56)])),
                      ("f32",), (2, 4), "relu", "kaiming", 1.0)
+CONFIGS[7] = PAPER_CASES
 
 
 def torch_dtype(name: str):

@@ -391,6 +391,26 @@ def test_config5_sub_batch(oracle, li, dtype):
     check_layer_full(oracle, cfg, cfg.layers[li], dtype, 2, N=16)
 
 
+@pytest.mark.parametrize("r", [2, 4])
+@pytest.mark.parametrize("li", [0, 1, 2, 3, 5, 6])
+def test_paper_cases_sub_batch(oracle, li, r):
+    """The paper's own on-device test shapes (Supp. E, Table 7), fp32, one or two images."""
+    cfg = WL.CONFIGS[7]
+    check_layer_full(oracle, cfg, cfg.layers[li], "f32", r, N=1 if li < 2 else 2)
+
+
+@pytest.mark.parametrize("li", [3, 4, 5])
+def test_paper_cases_exact(oracle, li):
+    """Vanilla BP (the paper's baseline) at the Table 7 shapes with small maps, fp32."""
+    cfg = WL.CONFIGS[7]
+    layer = cfg.layers[li]
+    d = T.desc_for(layer, 2, 1, "f32")
+    x, w, gy = WL.make_inputs(cfg, layer, "f32", N=2)
+    g_w, g_x = T.conv_bwd_exact(d, x.cuda(), w.cuda(), gy.cuda())
+    ref_gw, ref_gx = oracle.bwd_exact(odesc(oracle, d), to64(x), to64(w), to64(gy))
+    assert rel_err(g_w, ref_gw) <= TOL["f32"] and rel_err(g_x, ref_gx) <= TOL["f32"]
+
+
 def test_config4_full_size_sampled(oracle):
     """Config 4's largest layer at its full batch, in the launch configuration the
     benchmark uses; the oracle evaluates sampled outputs one by one: a weight
