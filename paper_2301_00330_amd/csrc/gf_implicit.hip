@@ -28,34 +28,14 @@
 // so what limits them is the bytes a compute unit has in flight: chunks are 256 bytes of K
 // per row where registers allow it.
 #include "gf_internal.h"
+#include "gf_mma.h"
 
 namespace gf {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kThreads = 256;
 constexpr double kPlainWgradMinFlops = 6e9;  // below, the 64 x 64 tiles of the S3 kernel (merged with S4 in one launch) are faster
-
-template <class T> struct Mma;
-template <> struct Mma<bf16_t> {
-  static constexpr int KSTEP = 32, VE = 8;   // k per MFMA, elements per 16-byte vector
-  static constexpr uint32_t FULL = 0xffu;
-};
-template <> struct Mma<float> {
-  static constexpr int KSTEP = 4, VE = 4;
-  static constexpr uint32_t FULL = 0xfu;
-};
-
-__device__ __forceinline__ f32x4 mma16(const uint4& a, const uint4& b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mma16(float a, float b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-}
 
 // 16 bytes at the natural alignment of one element
 template <class T> struct Unal;

@@ -16,36 +16,14 @@
 // while bf16 rows are interleaved in k-pairs on the way into LDS so that a lane
 // picks up its 8 k-values with four 32-bit reads.
 #include "gf_internal.h"
+#include "gf_mma.h"
 
 namespace gf {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kThreads = 256;
 constexpr int kRowBytes = 128 + 16;  // one staged row: 128 data bytes + 16 pad (K-major tiles)
-
-template <class T> struct Mma;
-template <> struct Mma<bf16_t> {
-  static constexpr int KSTEP = 32;  // k per MFMA
-  static constexpr int BK = 64;     // k per staged chunk (128 bytes)
-  static constexpr int VE = 8;
-};
-template <> struct Mma<float> {
-  static constexpr int KSTEP = 4;
-  static constexpr int BK = 32;
-  static constexpr int VE = 4;
-};
-
-__device__ __forceinline__ f32x4 mma16(const uint4& a, const uint4& b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mma16(float a, float b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-}
 
 template <class T> __device__ __forceinline__ uint32_t bits_of(T v);
 template <> __device__ __forceinline__ uint32_t bits_of<float>(float v) { return __float_as_uint(v); }
