@@ -1,7 +1,11 @@
 // Vanilla back-propagation of a conv layer (Sec. 3.1): g_theta = g_y (F) x and
 // g_x = g_y (*) rot180(theta), with stride, zero padding, dilation and groups.
-// Shape-generic direct kernels: one lane per g_x element (gather over the taps
-// that reach it) and one block per weight-gradient element.
+//  * dense layers whose tap offsets are constant in flattened pixels ("same"-size stride 1,
+//    "same"-padded strided layers) are handed to the implicit-GEMM kernels (gf_implicit.hip);
+//  * other dense layers: the shifted operand is written once per tap to a column tensor in
+//    the workspace and the MFMA GEMMs of the filtered path do the contractions;
+//  * grouped / depthwise layers: shape-generic direct kernels, one lane per g_x element
+//    (gather over the taps that reach it) and one block per weight-gradient element.
 #include "gf_internal.h"
 
 namespace gf {
