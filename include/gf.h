@@ -70,7 +70,8 @@ typedef enum gf_op {
   GF_OP_BWD_WEIGHT = 0,
   GF_OP_BWD_INPUT = 1,
   GF_OP_BWD_EXACT = 2,
-  GF_OP_BWD_FILTERED = 3
+  GF_OP_BWD_FILTERED = 3,
+  GF_OP_BWD_CHAINED = 4
 } gf_op;
 
 /* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
@@ -147,6 +148,21 @@ gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const vo
 gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const void* x_u,
                                const void* w, void* gy_u, float* g_w, void* g_x, void* ws,
                                size_t ws_bytes, void* stream);
+
+/* Backward of one layer inside a chain of gradient-filtered layers with nothing but
+ * convolutions between them.  The input gradient of Eq. 3 is constant on every
+ * input-side patch, so the filter of the layer below (Eq. 2, patch size r * stride of
+ * this layer) would return exactly the one value per patch that this layer computed:
+ * such layers can hand each other reduced maps only.  gy_u [N, C_out, H_p, W_p] is the
+ * incoming filtered gradient (from gf_filter_grad at the top of the chain, else the
+ * g_x of the layer above); the call computes g_w (Eq. 5) and g_x (Eq. 3), with
+ * reduced_out != 0 as the reduced map [N, C_in, H_p, W_p] to pass on, else at full
+ * resolution.  Same results as gf_conv_bwd_weight + gf_conv_bwd_input (g_x bit for
+ * bit, g_w up to the order of the fp32 partial sums); fewer launches, and neither the
+ * full-resolution write nor the next layer's read of it. */
+gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const void* x_u,
+                              const void* w, float* g_w, void* g_x, int reduced_out, void* ws,
+                              size_t ws_bytes, void* stream);
 
 /* Vanilla back-propagation of the layer (Sec. 3.1): g_w = g_y (F) x and
  * g_x = g_y (*) rot180(w), zero padding, with stride, dilation and groups.

@@ -16,10 +16,11 @@ LIB_PATH = os.path.join(HERE, "libgf.so")
 GF_OK = 0
 GF_ERR_NULL, GF_ERR_BAD_DESC, GF_ERR_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_DEVICE = range(1, 7)
 GF_F32, GF_BF16 = 0, 1
-GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED = 0, 1, 2, 3
+GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BWD_CHAINED = 0, 1, 2, 3, 4
 
 EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_filter_grad",
-           "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_exact",
+           "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_chained",
+           "gf_conv_bwd_exact",
            "gf_cost_model",
            "gf_status_string", "gf_version")
 
@@ -90,6 +91,7 @@ def lib() -> C.CDLL:
         L.gf_conv_bwd_input.argtypes = [dp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_conv_bwd_exact.argtypes = [dp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_filtered.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.gf_conv_bwd_chained.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_cost_model.argtypes = [dp, C.POINTER(_Cost)]
         L.gf_status_string.argtypes = [C.c_int]
         L.gf_status_string.restype = C.c_char_p
@@ -161,6 +163,13 @@ def gf_conv_bwd_filtered(d: ConvDesc, g_y: int, x_u: int, w: int, gy_u: int, g_w
     cd = d.c()
     _chk(lib().gf_conv_bwd_filtered(C.byref(cd), g_y, x_u, w, gy_u, g_w, g_x, ws, ws_bytes, stream),
          "gf_conv_bwd_filtered")
+
+
+def gf_conv_bwd_chained(d: ConvDesc, gy_u: int, x_u: int, w: int, g_w: int, g_x: int,
+                        reduced_out: bool, ws: int, ws_bytes: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_conv_bwd_chained(C.byref(cd), gy_u, x_u, w, g_w, g_x, int(bool(reduced_out)), ws,
+                                   ws_bytes, stream), "gf_conv_bwd_chained")
 
 
 def gf_conv_bwd_exact(d: ConvDesc, x: int, w: int, g_y: int, g_w: int, g_x: int, ws: int,

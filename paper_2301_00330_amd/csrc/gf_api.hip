@@ -71,10 +71,24 @@ static size_t ws_filtered(const Geom& g, bool own_gyu, size_t* off_w, size_t* of
   return o + ws_bwd_input(g, false);
 }
 
+// chained entry: [weight-gradient workspace][input-gradient workspace]
+static size_t ws_chained(const Geom& g, size_t* off_i) {
+  if (g.r == 1) {
+    if (off_i) *off_i = 0;
+    return ws_exact(g, true, true);
+  }
+  const size_t o = align256(ws_bwd_weight(g));
+  if (off_i) *off_i = o;
+  const size_t a = ws_bwd_input(g, true), b = ws_bwd_input(g, false);
+  return o + (a > b ? a : b);
+}
+
 static size_t ws_need(const Geom& g, int op, bool reduced_out) {
   switch (op) {
     case GF_OP_BWD_FILTERED:
       return ws_filtered(g, true, nullptr, nullptr);
+    case GF_OP_BWD_CHAINED:
+      return ws_chained(g, nullptr);
     case GF_OP_BWD_WEIGHT:
       return g.r == 1 ? ws_exact(g, true, false) : ws_bwd_weight(g);
     case GF_OP_BWD_INPUT:
@@ -126,7 +140,7 @@ gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int
 
 gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
   if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT &&
-      op != GF_OP_BWD_FILTERED)
+      op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED)
     return GF_ERR_BAD_DESC;
   if (!desc) return GF_ERR_NULL;
   gf_conv_desc d1;
@@ -249,6 +263,45 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
   rc = dev(launch_gf_bwd_weight(g, x_u, gyu, g_w, wsb + off_w, st));
   if (rc) return rc;
   return dev(launch_gf_bwd_input(g, gyu, w, g_x, false, wsb + off_i, st));
+}
+
+gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const void* x_u,
+                              const void* w, float* g_w, void* g_x, int reduced_out, void* ws,
+                              size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!gy_u || !x_u || !w || !g_w || !g_x) return GF_ERR_NULL;
+  if (!aligned16(gy_u) || !aligned16(x_u) || !aligned16(w) || !aligned16(g_w) || !aligned16(g_x))
+    return GF_ERR_UNSUPPORTED;
+  size_t off_i = 0;
+  rc = check_ws(ws_chained(g, &off_i), ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* wsb = static_cast<char*>(ws);
+  const float scale = 1.f / ((float)g.s * (float)g.s);
+  if (g.r == 1) {  // the maps are the full maps: vanilla BP
+    if (implicit_ok(g)) return dev(launch_implicit(g, x_u, w, gy_u, g_w, g_x, ws, st));
+    rc = dev(launch_exact_wgrad(g, x_u, gy_u, g_w, ws, st));
+    if (rc) return rc;
+    return dev(launch_exact_dgrad(g, w, gy_u, g_x, ws, st));
+  }
+  if (reduced_out && is_depthwise_layer(g)) {  // one pass over gy_u and x_u
+    float* part = reinterpret_cast<float*>(wsb);
+    rc = dev(launch_dw_chain(g, x_u, gy_u, w, part, g_x, st));
+    if (rc) return rc;
+    return dev(launch_finalize(part, g_w, g.Ci, g.N, g.KK, scale, st));
+  }
+  if (mfma_s3s4_ok(g, reduced_out != 0)) {  // dense: both contractions in one launch
+    float* part = reinterpret_cast<float*>(wsb);
+    int nzs = 0;
+    rc = dev(launch_mfma_s3s4(g, x_u, gy_u, w, wsb + off_i, part, &nzs, g_x, st, false, reduced_out != 0));
+    if (rc) return rc;
+    return dev(launch_finalize(part, g_w, g.Co * g.Ci, nzs, g.KK, scale, st));
+  }
+  rc = dev(launch_gf_bwd_weight(g, x_u, gy_u, g_w, wsb, st));
+  if (rc) return rc;
+  return dev(launch_gf_bwd_input(g, gy_u, w, g_x, reduced_out != 0, wsb + off_i, st));
 }
 
 gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void* w,

@@ -121,6 +121,34 @@ __global__ __launch_bounds__(kThreads) void dw_dot_vec_k(const T* xu, const T* g
 }
 
 // ---------------------------------------------------------------------------
+// Depthwise layer inside a chain of filtered layers: the weight-gradient partial of a plane
+// (as dw_dot_k) and, in the same pass over gy_u, the reduced input gradient
+// gxu[plane, p] = gy_u[plane, p] * (scalar * kernel sum of the plane's channel)   (Eq. 3).
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(kThreads) void dw_chain_k(const T* xu, const T* gyu, const T* w, float* part,
+                                                      T* gxu, int planes, int P, int L, int C, int KK,
+                                                      float scalar) {
+  const int gid = blockIdx.x * kThreads + threadIdx.x;
+  const int plane = gid / L;
+  const int lane = gid - plane * L;
+  float acc = 0.f;
+  if (plane < planes) {
+    const T* a = xu + (long)plane * P;
+    const T* b = gyu + (long)plane * P;
+    T* o = gxu + (long)plane * P;
+    const float sc = scalar * kernel_sum_of(w, plane % C, KK);
+    for (int p = lane; p < P; p += L) {
+      const float gv = to_f32(b[p]);
+      acc += to_f32(a[p]) * gv;
+      o[p] = from_f32<T>(gv * sc);
+    }
+  }
+  for (int m = L >> 1; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (plane < planes && lane == 0) part[plane] = acc;
+}
+
+// ---------------------------------------------------------------------------
 // S3 generic: part[z, co, cl] = sum_{n in slab z} sum_p gy_u[n,co,p] * x_u[n,ci,p]
 // 64 x 64 output tile per block, 4 x 4 per lane, K chunks of 16 patches.
 // ---------------------------------------------------------------------------
@@ -521,6 +549,8 @@ int wgrad_splits(const Geom& g) {
 
 }  // namespace
 
+bool is_depthwise_layer(const Geom& g) { return is_depthwise(g); }
+
 hipError_t launch_finalize(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
                            hipStream_t st) {
   return launch_finalize_impl(part, g_w, pairs, nz, KK, scale, st);
@@ -678,6 +708,25 @@ hipError_t launch_gf_bwd_input(const Geom& g, const void* gy_u, const void* w, v
                                static_cast<bf16_t*>(g_x), reduced_out, ws, st);
   return bwd_input_t<float>(g, static_cast<const float*>(gy_u), static_cast<const float*>(w),
                             static_cast<float*>(g_x), reduced_out, ws, st);
+}
+
+// Depthwise layer of a chain: partial dot products [N, C] and the reduced input gradient in one
+// launch (then launch_finalize with nz = N).
+hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, const void* w, float* part,
+                           void* g_xu, hipStream_t st) {
+  const int planes = g.N * g.Ci;
+  const int L = dw_lanes(g.P);
+  const int blocks = cdiv((long)planes * L, kThreads);
+  const float scalar = 1.f / ((float)g.s * (float)g.s);
+  if (g.dtype == GF_BF16)
+    hipLaunchKernelGGL(dw_chain_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const bf16_t*>(x_u),
+                       static_cast<const bf16_t*>(gy_u), static_cast<const bf16_t*>(w), part,
+                       static_cast<bf16_t*>(g_xu), planes, g.P, L, g.Ci, g.KK, scalar);
+  else
+    hipLaunchKernelGGL(dw_chain_k<float>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const float*>(x_u),
+                       static_cast<const float*>(gy_u), static_cast<const float*>(w), part,
+                       static_cast<float*>(g_xu), planes, g.P, L, g.Ci, g.KK, scalar);
+  return hipGetLastError();
 }
 
 }  // namespace gf

@@ -132,10 +132,15 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
                              void* full, hipStream_t st);
 // both gradients of a dense layer in one launch (then launch_finalize on `part`, nz slabs)
-bool mfma_s3s4_ok(const Geom& g);
+// With `reduced` the input gradient is written as the reduced map [N, Ci, P] instead of g_x.
+bool mfma_s3s4_ok(const Geom& g, bool reduced = false);
 hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
                             void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st,
-                            bool wsum_ready = false);
+                            bool wsum_ready = false, bool reduced = false);
+// depthwise layer of a chain of filtered layers (gf_filtered.hip): partials [N, C] + reduced g_x
+bool is_depthwise_layer(const Geom& g);
+hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, const void* w, float* part,
+                           void* g_xu, hipStream_t st);
 // true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
 bool mfma_dgrad_writes_full(const Geom& g);
 

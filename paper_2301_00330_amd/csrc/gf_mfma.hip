@@ -1055,10 +1055,14 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
 // both gradients in one launch: every shape the 64 x 64 (or 32 x 128) input-gradient block handles
 // without splitting K among its waves
 template <class T>
-static bool s3s4_ok(const Geom& g) {
+static bool s3s4_ok(const Geom& g, bool reduced) {
   constexpr int VE = Mma<T>::VE;
   if (g.g != 1 || g.Ci % VE != 0) return false;
   if (wgrad_shape(g) == 4 || plain_wgrad_ok(g)) return false;
+  if (reduced) {  // reduced map out: vector columns, or image blocks on both sides
+    if (g.P % VE == 0) return true;
+    return wgrad_flat(g, nullptr) && g.P <= 64 && ((long)g.Co * g.P * sizeof(T)) % 16 == 0;
+  }
   const bool runs = dgrad_full_ok<T>(g);
   if (!runs && !dgrad_planes_ok(g)) return false;
   if (g.P % VE != 0) {  // image-block loaders on both sides
@@ -1068,7 +1072,9 @@ static bool s3s4_ok(const Geom& g) {
   return true;
 }
 
-bool mfma_s3s4_ok(const Geom& g) { return g.dtype == GF_BF16 ? s3s4_ok<bf16_t>(g) : s3s4_ok<float>(g); }
+bool mfma_s3s4_ok(const Geom& g, bool reduced) {
+  return g.dtype == GF_BF16 ? s3s4_ok<bf16_t>(g, reduced) : s3s4_ok<float>(g, reduced);
+}
 
 template <class T, int WTM, int WTN, int WWM, int WWN>
 static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& da, int nz, hipStream_t st) {
@@ -1094,7 +1100,7 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
       hipLaunchKernelGGL((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 64>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     return hipGetLastError();
   }
-  if (da.planes_mode) {
+  if (da.planes_mode || da.flatb) {  // column tiles of whole images
     gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
     const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 64);
     if (vec)
@@ -1115,7 +1121,7 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
 
 template <class T>
 static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const void* w, void* wsum_t,
-                         float* part, int* nz_out, void* g_x, hipStream_t st, bool wsum_ready) {
+                         float* part, int* nz_out, void* g_x, hipStream_t st, bool wsum_ready, bool reduced) {
   const T* wt = nullptr;
   if (wsum_ready && g.KK > 1) {
     wt = static_cast<const T*>(wsum_t);  // formed by an earlier launch of the same call
@@ -1141,7 +1147,15 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
   da.d_wp = FastDiv((uint32_t)g.Wp);
   da.planes_mode = 0; da.ipt = 0; da.cols_per_tile = 0; da.rows_per_pass = 0;
   da.N = g.N; da.veca = 1; da.flatb = 0;
-  if (!dgrad_full_ok<T>(g)) {  // plane mode, as in dgrad_t
+  if (reduced) {  // reduced map out, as in dgrad_t
+    da.dst = g_x;
+    da.full = nullptr;
+    if (g.P % Mma<T>::VE != 0) {
+      da.flatb = 1;
+      da.ipt = images_per_tile(g, 64, 64);
+      da.cols_per_tile = da.ipt * g.P;
+    }
+  } else if (!dgrad_full_ok<T>(g)) {  // plane mode, as in dgrad_t
     da.planes_mode = 1;
     da.ipt = images_per_tile(g, 64, 64);
     da.cols_per_tile = da.ipt * g.P;
@@ -1157,9 +1171,10 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
 
 hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
                             void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st,
-                            bool wsum_ready) {
-  if (g.dtype == GF_BF16) return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready);
-  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready);
+                            bool wsum_ready, bool reduced) {
+  if (g.dtype == GF_BF16)
+    return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready, reduced);
+  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready, reduced);
 }
 
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,

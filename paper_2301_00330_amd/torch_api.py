@@ -127,6 +127,21 @@ def conv_bwd_filtered(d: B.ConvDesc, g_y: torch.Tensor, x_u: torch.Tensor, w: to
     return g_w, g_x, gy_u
 
 
+def conv_bwd_chained(d: B.ConvDesc, gy_u: torch.Tensor, x_u: torch.Tensor, w: torch.Tensor,
+                     reduced_out: bool = True, ws: Workspace | None = None):
+    """(g_w, g_x) from one call of gf_conv_bwd_chained; g_x is the reduced map unless reduced_out is False."""
+    s = shapes(d)
+    _check(gy_u, d, s["gy_u"], "gy_u")
+    _check(x_u, d, s["x_u"], "x_u")
+    _check(w, d, s["w"], "w")
+    g_w = torch.empty(s["w"], dtype=torch.float32, device=gy_u.device)
+    g_x = torch.empty(s["g_x_u"] if reduced_out else s["x"], dtype=gy_u.dtype, device=gy_u.device)
+    p, n = _ws(gy_u, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_CHAINED))
+    B.gf_conv_bwd_chained(d, B.ptr(gy_u), B.ptr(x_u), B.ptr(w), B.ptr(g_w), B.ptr(g_x), reduced_out, p, n,
+                          _stream())
+    return g_w, g_x
+
+
 def conv_bwd_exact(d: B.ConvDesc, x, w, g_y, want_gw: bool = True, want_gx: bool = True,
                    ws: Workspace | None = None):
     s = shapes(d.with_(r=1))

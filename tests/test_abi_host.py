@@ -83,6 +83,25 @@ def test_pointer_and_workspace_errors(lib):
     with pytest.raises(B.GfError) as ei:
         B.gf_conv_bwd_exact(d, 0, 0, FAKE, 0, 0, 0, 0)
     assert ei.value.status == B.GF_ERR_NULL
+    # the chained and the fused entry: null pointers, then the workspace, before anything is enqueued
+    for reduced in (True, False):
+        with pytest.raises(B.GfError) as ei:
+            B.gf_conv_bwd_chained(d, 0, FAKE, FAKE, FAKE, FAKE, reduced, FAKE, 1 << 30)
+        assert ei.value.status == B.GF_ERR_NULL
+        need_c = B.gf_workspace_bytes(d, B.GF_OP_BWD_CHAINED)
+        assert need_c > 0
+        with pytest.raises(B.GfError) as ei:
+            B.gf_conv_bwd_chained(d, FAKE, FAKE, FAKE, FAKE, FAKE, reduced, FAKE, need_c - 1)
+        assert ei.value.status == B.GF_ERR_WORKSPACE
+        with pytest.raises(B.GfError) as ei:
+            B.gf_conv_bwd_chained(d, FAKE, FAKE + 2, FAKE, FAKE, FAKE, reduced, FAKE, need_c)
+        assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered(d, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0)
+    assert ei.value.status == B.GF_ERR_WORKSPACE
+    with pytest.raises(B.GfError) as ei:
+        B.gf_workspace_bytes(d, 99)
+    assert ei.value.status == B.GF_ERR_BAD_DESC
     # wrong struct_size
     cd = d.c()
     cd.struct_size = 8

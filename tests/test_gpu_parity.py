@@ -245,6 +245,76 @@ def test_fused_entry_matches_separate_calls(oracle, case, dtype, want_gyu):
     assert rel_err(g_x, ref_gx) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("reduced_out", [True, False])
+@pytest.mark.parametrize("case", GF_CASES + FUSED_EXTRA)
+def test_chained_entry_matches_separate_calls(oracle, case, dtype, reduced_out):
+    """gf_conv_bwd_chained (the layer inside a chain: reduced gradient in, reduced or full
+    gradient out) against the oracle and against gf_conv_bwd_weight + gf_conv_bwd_input:
+    g_x bit for bit, g_w within the fp32 summation tolerance."""
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, r, dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 61, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 62, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    gyu = randn((N, Co, Hp, Wp), 63, dtype, scale=1e-2)
+    x_u = rounded(oracle.pool_activation(od, to64(x)), dtype).cuda()
+    gyug, wg = gyu.cuda(), w.cuda()
+    g_w, g_x = T.conv_bwd_chained(d, gyug, x_u, wg, reduced_out=reduced_out)
+    s_gw = T.conv_bwd_weight(d, x_u, gyug)
+    s_gx = T.conv_bwd_input(d, gyug, wg, reduced_out=reduced_out)
+    torch.cuda.synchronize()
+    assert torch.equal(g_x, s_gx)
+    assert float((g_w - s_gw).abs().max()) <= 1e-5 * float(s_gw.abs().max() + 1e-30)
+    assert rel_err(g_w, oracle.bwd_weight(od, to64(x_u), to64(gyu))) <= TOL[dtype]
+    assert rel_err(g_x, oracle.bwd_input(od, to64(gyu), to64(w), reduced_out=reduced_out)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chain_of_layers_equals_layer_by_layer(oracle, dtype):
+    """The MobileNetV2 block of configuration 2, back to front (project, depthwise, expand), at a
+    sub-batch.  Chained: one filter at the top, reduced maps handed down, full resolution only at
+    the bottom.  Layer by layer: every layer gets the full-resolution gradient and filters it
+    itself.  With r = 2 every patch mean of a patch-constant map is exact, so the two agree bit
+    for bit on every g_x; the weight gradients agree to the summation tolerance; the fp32 run is
+    also checked against the oracle run layer by layer in fp64."""
+    cfg = WL.CONFIGS[2]
+    N, r = 4, 2
+    expand, dw, project = cfg.layers
+    ds = [T.desc_for(L, N, r, dtype) for L in (project, dw, expand)]
+    xs, ws = [], []
+    for i, L in enumerate((project, dw, expand)):
+        x, w, gy = WL.make_inputs(cfg, L, dtype, N=N, seed=900 + i)
+        xs.append(x); ws.append(w)
+        if i == 0:
+            g_top = gy
+    xus = [T.pool_activation(d, x.cuda()) for d, x in zip(ds, xs)]
+    # layer by layer
+    g = g_top.cuda()
+    lbl_gw = []
+    for d, xu, w in zip(ds, xus, ws):
+        gw, g, _ = T.conv_bwd_filtered(d, g, xu, w.cuda())
+        lbl_gw.append(gw)
+    lbl_gx = g
+    # chained
+    gu = T.filter_grad(ds[0], g_top.cuda())
+    ch_gw = []
+    for i, (d, xu, w) in enumerate(zip(ds, xus, ws)):
+        gw, gu = T.conv_bwd_chained(d, gu, xu, w.cuda(), reduced_out=(i < 2))
+        ch_gw.append(gw)
+    torch.cuda.synchronize()
+    assert torch.equal(gu, lbl_gx)
+    for a, b in zip(ch_gw, lbl_gw):
+        assert float((a - b).abs().max()) <= 1e-5 * float(b.abs().max() + 1e-30)
+    if dtype == "f32":
+        ref = to64(g_top)
+        for i, (d, x, w) in enumerate(zip(ds, xs, ws)):
+            rgw, ref, _, _ = oracle.gf_backward(odesc(oracle, d), to64(x), to64(w), ref)
+            assert rel_err(ch_gw[i], rgw) <= 5e-5     # three chained fp32 layers
+        assert rel_err(gu, ref) <= 5e-5
+
+
 def test_fused_entry_r1_is_vanilla_bp(oracle):
     d = mk(2, 6, 8, 9, 9, 3, 1, 1, 1, 1, 1, "f32")
     od = odesc(oracle, d)

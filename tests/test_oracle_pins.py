@@ -162,6 +162,33 @@ def test_filter_fixed_point_and_idempotence(oracle, H, W, r):
         np.testing.assert_allclose(f1 * r * r, oracle.pool_activation(d, g), rtol=1e-13)
 
 
+@pytest.mark.parametrize("s,r,K,p", [(1, 2, 3, 1), (1, 4, 1, 0), (2, 2, 3, 1), (1, 3, 3, 1)])
+def test_chain_of_filtered_layers_can_pass_reduced_maps(oracle, s, r, K, p):
+    """Two stacked layers, nothing between them.  The upper layer's input gradient (Eq. 3) is
+    constant on its input-side patches (size r * stride), so the lower layer's gradient filter
+    (Eq. 2) with that patch size returns exactly the upper layer's one value per patch: the
+    reduced map can be handed down instead of the full-resolution gradient, and every
+    gradient of the lower layer comes out the same."""
+    H = W = 12
+    up = D(oracle, N=2, C_in=3, C_out=4, H_in=H, W_in=W, K_h=K, K_w=K, stride=s, pad=p, r=r)
+    lo = D(oracle, N=2, C_in=2, C_out=3, H_in=H, W_in=W, K_h=3, K_w=3, pad=1, r=r * s)  # its output is the upper input
+    g = rng(5 + s + r)
+    Hy, Wy, _, _ = oracle.out_shape(up)
+    g_y = g.standard_normal((2, 4, Hy, Wy))
+    w_up = g.standard_normal((4, 3, K, K))
+    w_lo = g.standard_normal((3, 2, 3, 3))
+    x_lo = g.standard_normal((2, 2, H, W))
+    gyu_up = oracle.filter_grad(up, g_y)
+    gx_full = oracle.bwd_input(up, gyu_up, w_up)                      # [2, 3, H, W]
+    gx_red = oracle.bwd_input(up, gyu_up, w_up, reduced_out=True)     # [2, 3, H/(r s), W/(r s)]
+    np.testing.assert_allclose(oracle.filter_grad(lo, gx_full), gx_red, rtol=1e-14, atol=1e-300)
+    xu_lo = oracle.pool_activation(lo, x_lo)
+    # lower layer fed the full gradient (filters it itself) vs fed the reduced map directly
+    ref = oracle.gf_backward(lo, x_lo, w_lo, gx_full)
+    np.testing.assert_allclose(oracle.bwd_weight(lo, xu_lo, gx_red), ref[0], rtol=1e-12, atol=1e-300)
+    np.testing.assert_allclose(oracle.bwd_input(lo, gx_red, w_lo), ref[1], rtol=1e-12, atol=1e-300)
+
+
 GF_CASES = [
     # N Ci Co H  W  K s p d g r
     (2, 3, 4, 8, 8, 3, 1, 1, 1, 1, 2),
