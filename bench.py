@@ -75,6 +75,8 @@ class LayerBufs:
         self.ws_f = torch.empty(max(self.ws_f_bytes, 256), dtype=torch.uint8, device="cuda")
         self.e_w = None
         self.e_x = None
+        self.g_xu = None   # reduced input gradient (chained mode)
+        self.ws_c = None
 
     def nbytes(self):
         ts = [self.x, self.w, self.gy, self.x_u, self.gy_u, self.g_w, self.g_x, self.ws_w, self.ws_i, self.ws_f]
@@ -186,6 +188,65 @@ def measure(args, dtype, full):
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = N / (ms_per_step * 1e-3)
+
+    # ---- secondary: the layers as a chain that hands reduced maps from layer to layer ----
+    chained = None
+    if full and cfg.chain and r > 1:
+        order = list(cfg.chain)                       # back to front
+        for bs in sets:
+            for lb in bs:
+                s_ = T.shapes(lb.d)
+                lb.g_xu = torch.empty(s_["g_x_u"], dtype=lb.x.dtype, device="cuda")
+                nb = B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_CHAINED)
+                lb.ws_c = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+
+        def step_chained(bufset):
+            s = st()
+            for lb in bufset:
+                enqueue_pool(lb, s)                   # forward-time S0, unchanged
+            top = bufset[order[0]]
+            B.gf_filter_grad(top.d, P(top.gy), P(top.gy_u), s)
+            gin = top.gy_u
+            for k, li in enumerate(order):
+                lb = bufset[li]
+                last = k == len(order) - 1
+                gout = lb.g_x if last else lb.g_xu
+                B.gf_conv_bwd_chained(lb.d, P(gin), P(lb.x_u), P(lb.w), P(lb.g_w), P(gout), not last,
+                                      P(lb.ws_c), lb.ws_c.numel(), s)
+                gin = gout
+
+        for i in range(max(args.warmup, 1)):
+            step_chained(sets[i % nsets])
+        torch.cuda.synchronize()
+        cgraphs = None
+        if not args.no_graph:
+            cgraphs = []
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for bs in sets:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):
+                        step_chained(bs)
+                    cgraphs.append(g)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            for g in cgraphs:
+                g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            if cgraphs is not None:
+                cgraphs[i % nsets].replay()
+            else:
+                step_chained(sets[i % nsets])
+        torch.cuda.synchronize()
+        cms = (time.perf_counter() - t0) * 1e3 / args.steps
+        chained = {"ms_per_step": round(cms, 5), "value": round(N / (cms * 1e-3), 1), "unit": "images/s",
+                   "note": "same layers and S0 launches, but only the top layer's g_y is filtered: "
+                           "gf_conv_bwd_chained hands the reduced input gradient of a layer to the layer below "
+                           "(valid for a stack of stride-1 convolutions with nothing between them); full "
+                           "resolution is written only at the bottom"}
 
     # eager launches for comparison (host launch overhead included)
     torch.cuda.synchronize()
@@ -361,6 +422,8 @@ def measure(args, dtype, full):
         "per_layer": per_layer,
         "exact_bp": exact,
     }
+    if chained is not None:
+        out["chained_block"] = chained
     del sets, one, graphs
     torch.cuda.empty_cache()
     if full and args.pmc_calibration:

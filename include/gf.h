@@ -34,8 +34,9 @@
  *    (true for every "same"-padded layer), else GF_ERR_SHAPE.
  *  - r == 1 means vanilla back-propagation (Sec. 4.2): x_u and gy_u are then
  *    the full maps x and g_y (x_u is [N, C_in, H_in, W_in]), the two reduction
- *    entries are plain copies, and gf_conv_bwd_weight / gf_conv_bwd_input
- *    evaluate the exact K_h x K_w contractions of Sec. 3.1.
+ *    entries are plain copies, and gf_conv_bwd_weight / gf_conv_bwd_input /
+ *    gf_conv_bwd_filtered / gf_conv_bwd_chained evaluate the exact K_h x K_w
+ *    contractions of Sec. 3.1.
  *  - Dilation only affects H_y and the exact entry: the filtered formulas read
  *    the tap's own padded patch wherever it lands (Supp. B "Boundary Elements").
  *  - Results are deterministic: no floating-point atomics, so two calls on the
