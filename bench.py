@@ -73,6 +73,8 @@ class LayerBufs:
         self.ws_e = torch.empty(max(self.ws_e_bytes, 256), dtype=torch.uint8, device="cuda")
         self.ws_f_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED)
         self.ws_f = torch.empty(max(self.ws_f_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.ws_s = torch.empty(max(B.gf_workspace_bytes(d, B.GF_OP_FILTER_SNR), 256), dtype=torch.uint8, device="cuda")
+        self.stats = torch.zeros(2, dtype=torch.float64, device="cuda")
         self.e_w = None
         self.e_x = None
         self.g_xu = None   # reduced input gradient (chained mode)
@@ -130,6 +132,8 @@ def measure(args, dtype, full):
 
     def enqueue_pool(lb, s): B.gf_pool_activation(lb.d, P(lb.x), P(lb.x_u), s)
     def enqueue_filter(lb, s): B.gf_filter_grad(lb.d, P(lb.gy), P(lb.gy_u), s)
+    def enqueue_filter_snr(lb, s):
+        B.gf_filter_grad_snr(lb.d, P(lb.gy), P(lb.gy_u), P(lb.stats), P(lb.ws_s), lb.ws_s.numel(), s)
     def enqueue_bww(lb, s): B.gf_conv_bwd_weight(lb.d, P(lb.x_u), P(lb.gy_u), P(lb.g_w), P(lb.ws_w), lb.ws_w.numel(), s)
     def enqueue_bwi(lb, s): B.gf_conv_bwd_input(lb.d, P(lb.gy_u), P(lb.w), P(lb.g_x), False, P(lb.ws_i), lb.ws_i.numel(), s)
 
@@ -318,6 +322,10 @@ def measure(args, dtype, full):
             row[name] = {"us": round(us, 2), "GBps": round(by / us * 1e-3, 1), "bytes": by}
             if name != "pool_activation":
                 tot_us += us
+        if r > 1:   # the filter with its by-product, the noise figures of Eq. (8)
+            us = time_stage(enqueue_filter_snr, li)
+            e_, v_ = sets[0][li].stats.tolist()
+            row["filter_grad_snr"] = {"us": round(us, 2), "snr": round(e_ / v_, 4) if v_ > 0 else None}
         fl = cost[li]["flops_bwd_weight"] + cost[li]["flops_bwd_input"]
         row["separate_calls_us"] = round(tot_us, 2)     # gf_filter_grad + gf_conv_bwd_weight + gf_conv_bwd_input
         tot_us = time_stage(enqueue_fused, li)

@@ -72,7 +72,8 @@ typedef enum gf_op {
   GF_OP_BWD_INPUT = 1,
   GF_OP_BWD_EXACT = 2,
   GF_OP_BWD_FILTERED = 3,
-  GF_OP_BWD_CHAINED = 4
+  GF_OP_BWD_CHAINED = 4,
+  GF_OP_FILTER_SNR = 5
 } gf_op;
 
 /* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
@@ -123,6 +124,16 @@ gf_status gf_pool_activation(const gf_conv_desc* desc, const void* x, void* x_u,
 /* The gradient filter (Eq. 2): gy_u = mean of g_y over each r x r patch, one
  * value per patch (the matrix of unique values, Sec. 3.3). */
 gf_status gf_filter_grad(const gf_conv_desc* desc, const void* g_y, void* gy_u, void* stream);
+
+/* The gradient filter together with its noise figures (Sec. 3.4, first line of Eq. 8 read in the
+ * pixel domain by Parseval; Fig. 5 plots accuracy against this ratio): beside gy_u the call
+ * writes, to two doubles in device memory,
+ *   stats[0] = sum over the tensor of g_y^2                      (energy of the signal)
+ *   stats[1] = sum of (g_y - mean of its patch)^2                (energy the filter removes)
+ * so that SNR = stats[0] / stats[1].  The means are the unrounded fp32 patch means; partial
+ * sums are added in a fixed order (deterministic).  ws: gf_workspace_bytes(GF_OP_FILTER_SNR). */
+gf_status gf_filter_grad_snr(const gf_conv_desc* desc, const void* g_y, void* gy_u, double* stats,
+                             void* ws, size_t ws_bytes, void* stream);
 
 /* Filtered weight gradient (Eq. 5): the Frobenius inner product of x_u and gy_u
  * over (n, patch) for every (c_o, c_i) pair of a group, scaled by 1/stride^2 and

@@ -124,6 +124,16 @@ def filter_grad(d: Desc, g_y) -> np.ndarray:
     return out
 
 
+def filter_snr(d: Desc, g_y):
+    """(energy, noise) of the filter (first line of Eq. 8 in the pixel domain); SNR = energy / noise."""
+    Hy, Wy, Hp, Wp = out_shape(d)
+    g_y = _in(g_y, (d.N, d.C_out, Hy, Wy))
+    e, v = C.c_double(0.0), C.c_double(0.0)
+    cd = d._c()
+    _chk(_L().gf_ref_filter_snr(C.byref(cd), _p(g_y), C.byref(e), C.byref(v)), "filter_snr")
+    return e.value, v.value
+
+
 def pool_activation(d: Desc, x) -> np.ndarray:
     x = _in(x, (d.N, d.C_in, d.H_in, d.W_in))
     out = np.empty(xu_shape(d), np.float64)

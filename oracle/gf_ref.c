@@ -8,6 +8,7 @@
 #include "gf_ref.h"
 
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -82,6 +83,30 @@ int gf_ref_filter_grad(const gf_ref_desc* d, const double* g_y, double* gy_u) {
   if (rc) return rc;
   if (!g_y || !gy_u) return REF_NULL;
   patch_reduce(g_y, gy_u, (long)d->N * d->C_out, Hy, Wy, d->r, 1);
+  return REF_OK;
+}
+
+int gf_ref_filter_snr(const gf_ref_desc* d, const double* g_y, double* energy, double* noise) {
+  int Hy, Wy, Hp, Wp;
+  int rc = gf_ref_out_shape(d, &Hy, &Wy, &Hp, &Wp);
+  if (rc) return rc;
+  if (!g_y || !energy || !noise) return REF_NULL;
+  long planes = (long)d->N * d->C_out;
+  double* gy_u = (double*)malloc(sizeof(double) * (size_t)planes * Hp * Wp);
+  if (!gy_u) return REF_NULL;
+  patch_reduce(g_y, gy_u, planes, Hy, Wy, d->r, 1);
+  double e = 0.0, v = 0.0;
+  for (long pl = 0; pl < planes; ++pl)
+    for (int h = 0; h < Hy; ++h)
+      for (int w = 0; w < Wy; ++w) {
+        double g = g_y[((size_t)pl * Hy + h) * Wy + w];
+        double m = gy_u[((size_t)pl * Hp + h / d->r) * Wp + w / d->r]; /* the value g~_y has at (h, w) */
+        e += g * g;
+        v += (g - m) * (g - m);
+      }
+  free(gy_u);
+  *energy = e;
+  *noise = v;
   return REF_OK;
 }
 

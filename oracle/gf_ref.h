@@ -58,6 +58,10 @@ int gf_ref_out_shape(const gf_ref_desc* d, int* H_out, int* W_out, int* H_p, int
 
 /* S1, Eq. (2): gy_u[n,c,hp,wp] = mean of g_y over the patch.  [N,C_out,H_p,W_p] */
 int gf_ref_filter_grad(const gf_ref_desc* d, const double* g_y, double* gy_u);
+/* Noise of the filter, first line of Eq. (8) taken in the pixel domain (per patch the DFT keeps
+ * sums of squares up to the common factor r^2, so the ratio is the same):
+ *   *energy = sum g_y^2,  *noise = sum (g_y - its patch mean)^2,  SNR = energy / noise.   */
+int gf_ref_filter_snr(const gf_ref_desc* d, const double* g_y, double* energy, double* noise);
 /* S0, text after Eq. (5): x_u[n,c,hp,wp] = sum of x over the r_x x r_x patch.
  * [N,C_in,H_p,W_p]; with r == 1 it is a copy of x, [N,C_in,H_in,W_in].          */
 int gf_ref_pool_activation(const gf_ref_desc* d, const double* x, double* x_u);

@@ -17,8 +17,9 @@ GF_OK = 0
 GF_ERR_NULL, GF_ERR_BAD_DESC, GF_ERR_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_DEVICE = range(1, 7)
 GF_F32, GF_BF16 = 0, 1
 GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BWD_CHAINED = 0, 1, 2, 3, 4
+GF_OP_FILTER_SNR = 5
 
-EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_filter_grad",
+EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_filter_grad", "gf_filter_grad_snr",
            "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_chained",
            "gf_conv_bwd_exact",
            "gf_cost_model",
@@ -87,6 +88,7 @@ def lib() -> C.CDLL:
         L.gf_workspace_bytes.argtypes = [dp, C.c_int, C.POINTER(C.c_size_t)]
         L.gf_pool_activation.argtypes = [dp, vp, vp, vp]
         L.gf_filter_grad.argtypes = [dp, vp, vp, vp]
+        L.gf_filter_grad_snr.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_weight.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_input.argtypes = [dp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_conv_bwd_exact.argtypes = [dp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -163,6 +165,11 @@ def gf_conv_bwd_filtered(d: ConvDesc, g_y: int, x_u: int, w: int, gy_u: int, g_w
     cd = d.c()
     _chk(lib().gf_conv_bwd_filtered(C.byref(cd), g_y, x_u, w, gy_u, g_w, g_x, ws, ws_bytes, stream),
          "gf_conv_bwd_filtered")
+
+
+def gf_filter_grad_snr(d: ConvDesc, g_y: int, gy_u: int, stats: int, ws: int, ws_bytes: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_filter_grad_snr(C.byref(cd), g_y, gy_u, stats, ws, ws_bytes, stream), "gf_filter_grad_snr")
 
 
 def gf_conv_bwd_chained(d: ConvDesc, gy_u: int, x_u: int, w: int, g_w: int, g_x: int,

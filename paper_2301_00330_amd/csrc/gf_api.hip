@@ -89,6 +89,8 @@ static size_t ws_need(const Geom& g, int op, bool reduced_out) {
       return ws_filtered(g, true, nullptr, nullptr);
     case GF_OP_BWD_CHAINED:
       return ws_chained(g, nullptr);
+    case GF_OP_FILTER_SNR:
+      return (size_t)patch_reduce_max_blocks((long)g.N * g.Co, g.Hy, g.Wy, g.r) * 2 * sizeof(float);
     case GF_OP_BWD_WEIGHT:
       return g.r == 1 ? ws_exact(g, true, false) : ws_bwd_weight(g);
     case GF_OP_BWD_INPUT:
@@ -140,7 +142,7 @@ gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int
 
 gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
   if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT &&
-      op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED)
+      op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED && op != GF_OP_FILTER_SNR)
     return GF_ERR_BAD_DESC;
   if (!desc) return GF_ERR_NULL;
   gf_conv_desc d1;
@@ -263,6 +265,19 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
   rc = dev(launch_gf_bwd_weight(g, x_u, gyu, g_w, wsb + off_w, st));
   if (rc) return rc;
   return dev(launch_gf_bwd_input(g, gyu, w, g_x, false, wsb + off_i, st));
+}
+
+gf_status gf_filter_grad_snr(const gf_conv_desc* desc, const void* g_y, void* gy_u, double* stats,
+                             void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!g_y || !gy_u || !stats) return GF_ERR_NULL;
+  if (!aligned16(g_y) || !aligned16(gy_u) || !aligned16(stats)) return GF_ERR_UNSUPPORTED;
+  rc = check_ws(ws_need(g, GF_OP_FILTER_SNR, false), ws, ws_bytes);
+  if (rc) return rc;
+  return dev(launch_filter_stats(g_y, gy_u, (long)g.N * g.Co, g.Hy, g.Wy, g.r, g.dtype,
+                                 static_cast<float*>(ws), stats, static_cast<hipStream_t>(stream)));
 }
 
 gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const void* x_u,

@@ -108,6 +108,13 @@ struct KsumJob {
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
                                bool mean, int dtype, hipStream_t st, const KsumJob* ksum = nullptr);
 
+// S1 with the noise figures of the filter: gy_u as launch_patch_reduce(mean), plus
+// stats[0] = sum g_y^2 and stats[1] = sum (g_y - patch mean)^2 (doubles, device memory);
+// `part` holds patch_reduce_max_blocks() float pairs.
+long patch_reduce_max_blocks(long planes, int H, int W, int q);
+hipError_t launch_filter_stats(const void* g_y, void* gy_u, long planes, int H, int W, int q, int dtype,
+                               float* part, double* stats, hipStream_t st);
+
 // S2: wsum[co, cl] = sum over taps of w[co, cl, :, :], fp32.
 hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int dtype,
                              hipStream_t st);

@@ -36,7 +36,26 @@ struct ReduceArgs {
   const void* ks_w;
   void* ks_out;
   int ks_pairs, ks_KK, ks_block0;
+  // noise figures of the filter (STATS kernels): per-block partial sums {sum v^2, sum (v - patch mean)^2}
+  float2* stats_part;
 };
+
+// Fixed-order sum over the block of two floats per lane; block 0's lane 0 ... every block's
+// lane 0 writes its pair.  `red` is 2 * (kThreads / 64) floats of LDS.
+__device__ __forceinline__ void block_stats(float e, float n, float* red, float2* dst) {
+  for (int m = 32; m > 0; m >>= 1) {
+    e += __shfl_xor(e, m, 64);
+    n += __shfl_xor(n, m, 64);
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { red[2 * wave] = e; red[2 * wave + 1] = n; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float se = 0.f, sn = 0.f;
+    for (int k = 0; k < kThreads / 64; ++k) { se += red[2 * k]; sn += red[2 * k + 1]; }
+    dst[blockIdx.x] = make_float2(se, sn);
+  }
+}
 
 // the kernel-sum side job; true if this block belongs to it (uniform for the block)
 template <class T>
@@ -51,9 +70,11 @@ __device__ __forceinline__ bool ksum_side_job(const ReduceArgs& a) {
 // ---------------------------------------------------------------------------
 // rows kernel: requires W % max(VE, Q) == 0 and (W * sizeof(T)) % 16 == 0
 // ---------------------------------------------------------------------------
-template <class T, int Q, int U>
+template <class T, int Q, int U, bool STATS = false>
 __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
   if (ksum_side_job<T>(a)) return;
+  __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
+  float energy = 0.f, noise = 0.f;
   constexpr int VE = Vec16<T>::N;            // elements per 16-byte vector
   constexpr int IW = VE > Q ? VE : Q;        // elements of one row an item covers
   constexpr int VW = IW / VE;                // vectors per row per item
@@ -103,12 +124,31 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
       }
     const float den = a.mean ? (float)(rows[u] * Q) : 1.f;
     T res[NOUT];
+    float mean[NOUT];
 #pragma unroll
     for (int o = 0; o < NOUT; ++o) {
       float acc = 0.f;
 #pragma unroll
       for (int j = 0; j < Q; ++j) acc += colsum[o * Q + j];
-      res[o] = from_f32<T>(acc / den);
+      mean[o] = acc / den;
+      res[o] = from_f32<T>(mean[o]);
+    }
+    if constexpr (STATS) {  // second pass over the registers: energy and distance to the patch mean
+#pragma unroll
+      for (int i = 0; i < Q; ++i)
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+          float f[VE];
+          Vec16<T>::unpack(v[u][i][k], f);
+          const bool keep = i < rows[u];
+#pragma unroll
+          for (int e = 0; e < VE; ++e) {
+            const float val = keep ? f[e] : 0.f;
+            const float dv = keep ? f[e] - mean[(k * VE + e) / Q] : 0.f;
+            energy += val * val;
+            noise += dv * dv;
+          }
+        }
     }
     T* dst = out + (long)strip[u] * a.Wp + col[u] * NOUT;
     if constexpr (NOUT * sizeof(T) == 8) {
@@ -120,14 +160,17 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
       for (int o = 0; o < NOUT; ++o) dst[o] = res[o];
     }
   }
+  if constexpr (STATS) block_stats(energy, noise, red, a.stats_part);
 }
 
 // ---------------------------------------------------------------------------
 // LDS kernel: any shape whose strip fits the staging buffer
 // ---------------------------------------------------------------------------
-template <class T, int QT>  // QT: compile-time patch size, 0 = run-time
+template <class T, int QT, bool STATS = false>  // QT: compile-time patch size, 0 = run-time
 __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
   if (ksum_side_job<T>(a)) return;
+  __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
+  float energy = 0.f, noise = 0.f;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int s0 = blockIdx.x * a.spb;
@@ -194,13 +237,28 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
       }
     if (a.mean) acc = acc / (float)(ch * cw);
     out[s0 * a.Wp + lo] = from_f32<T>(acc);
+    if constexpr (STATS) {
+#pragma unroll
+      for (int i = 0; i < q; ++i)
+#pragma unroll
+        for (int j = 0; j < q; ++j) {
+          const bool ok = i < ch && j < cw;
+          const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
+          const float dv = val - acc;
+          energy += ok ? val * val : 0.f;
+          noise += ok ? dv * dv : 0.f;
+        }
+    }
   }
+  if constexpr (STATS) block_stats(energy, noise, red, a.stats_part);
 }
 
 // Fallback without LDS for strips too large to stage: one lane per patch.
-template <class T>
+template <class T, bool STATS = false>
 __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
   if (ksum_side_job<T>(a)) return;
+  __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
+  float energy = 0.f, noise = 0.f;
   const T* in = static_cast<const T*>(a.in);
   T* out = static_cast<T*>(a.out);
   const long nout = (long)a.total_strips * a.Wp;
@@ -218,11 +276,49 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
       for (int j = 0; j < cw; ++j) acc += to_f32(p[(long)i * a.W + j]);
     if (a.mean) acc = acc / (float)(ch * cw);
     out[o] = from_f32<T>(acc);
+    if constexpr (STATS) {
+      for (int i = 0; i < ch; ++i)
+        for (int j = 0; j < cw; ++j) {
+          const float val = to_f32(p[(long)i * a.W + j]);
+          energy += val * val;
+          noise += (val - acc) * (val - acc);
+        }
+    }
+  }
+  if constexpr (STATS) block_stats(energy, noise, red, a.stats_part);
+}
+
+// stats[0] = sum of the blocks' energies, stats[1] = sum of their noise terms, in double: one
+// block, every lane a strided share of the partials, then a fixed tree (same result every run)
+constexpr int kFinalThreads = 1024;
+__global__ __launch_bounds__(kFinalThreads) void stats_final_k(const float2* part, int n, double* stats) {
+  __shared__ double red[2 * (kFinalThreads / 64)];
+  double e = 0.0, v = 0.0;
+  for (int i = threadIdx.x; i < n; i += kFinalThreads) {
+    const float2 p = part[i];
+    e += (double)p.x;
+    v += (double)p.y;
+  }
+  for (int m = 32; m > 0; m >>= 1) {
+    e += __shfl_xor(e, m, 64);
+    v += __shfl_xor(v, m, 64);
+  }
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane == 0) { red[2 * wave] = e; red[2 * wave + 1] = v; }
+  __syncthreads();
+  if (wave == 0) {
+    e = lane < kFinalThreads / 64 ? red[2 * lane] : 0.0;
+    v = lane < kFinalThreads / 64 ? red[2 * lane + 1] : 0.0;
+    for (int m = 8; m > 0; m >>= 1) {
+      e += __shfl_xor(e, m, 64);
+      v += __shfl_xor(v, m, 64);
+    }
+    if (lane == 0) { stats[0] = e; stats[1] = v; }
   }
 }
 
 template <class T, int Q>
-hipError_t launch_rows(ReduceArgs& a, hipStream_t st) {
+hipError_t launch_rows(ReduceArgs& a, hipStream_t st, int* nblocks) {
   constexpr int VE = Vec16<T>::N;
   constexpr int IW = VE > Q ? VE : Q;
   constexpr int U = (Q >= 8) ? 1 : 2;  // vectors in flight per lane: U * Q * VW (U = 4 measured slower)
@@ -231,7 +327,11 @@ hipError_t launch_rows(ReduceArgs& a, hipStream_t st) {
   a.d_ipr = FastDiv((uint32_t)a.ipr);
   const int blocks = cdiv(a.total_items, kThreads * U);
   a.ks_block0 = blocks;
-  hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+  if (a.stats_part)
+    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+  *nblocks = blocks;
   return hipGetLastError();
 }
 
@@ -243,12 +343,13 @@ bool rows_ok(int W, int q) {
   return W % IW == 0 && (W * (int)sizeof(T)) % 16 == 0;
 }
 
+// *nblocks: the number of reduction blocks launched (side-job blocks not counted)
 template <class T>
-hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
+hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
   if (rows_ok<T>(a.W, a.q) && (long)a.total_strips * (a.W / 4) < 2147483647L) {
-    if (a.q == 2) return launch_rows<T, 2>(a, st);
-    if (a.q == 4) return launch_rows<T, 4>(a, st);
-    return launch_rows<T, 8>(a, st);
+    if (a.q == 2) return launch_rows<T, 2>(a, st, nblocks);
+    if (a.q == 4) return launch_rows<T, 4>(a, st, nblocks);
+    return launch_rows<T, 8>(a, st, nblocks);
   }
   const long strip_bytes = (long)imin_host(a.q, a.H) * a.W * (long)sizeof(T);
   if (strip_bytes + 32 > kLdsMax) {
@@ -257,7 +358,11 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
     int blocks = (int)((nout + kThreads - 1) / kThreads);
     if (blocks > 65536) blocks = 65536;
     a.ks_block0 = blocks;
-    hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+    if (a.stats_part)
+      hipLaunchKernelGGL((patch_reduce_direct<T, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else
+      hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+    *nblocks = blocks;
     return hipGetLastError();
   }
   int spb = (int)((kLdsBudget - 32) / strip_bytes);
@@ -270,6 +375,17 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
   const size_t lds = (size_t)spb * strip_bytes + 32;
   const int blocks = (a.total_strips + spb - 1) / spb;
   a.ks_block0 = blocks;
+  *nblocks = blocks;
+  if (a.stats_part) {
+    const dim3 sgrid(blocks);
+    if (a.q == 2)
+      hipLaunchKernelGGL((patch_reduce_lds<T, 2, true>), sgrid, dim3(kThreads), lds, st, a);
+    else if (a.q == 4)
+      hipLaunchKernelGGL((patch_reduce_lds<T, 4, true>), sgrid, dim3(kThreads), lds, st, a);
+    else
+      hipLaunchKernelGGL((patch_reduce_lds<T, 0, true>), sgrid, dim3(kThreads), lds, st, a);
+    return hipGetLastError();
+  }
   const dim3 grid(blocks + cdiv(a.ks_pairs, kThreads));
   if (a.q == 2)
     hipLaunchKernelGGL((patch_reduce_lds<T, 2>), grid, dim3(kThreads), lds, st, a);
@@ -284,9 +400,37 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st) {
 
 }  // namespace
 
+// upper bound of the blocks any variant uses for this shape (size of the partial buffer)
+long patch_reduce_max_blocks(long planes, int H, int W, int q) {
+  const long strips = planes * cdiv(H, q);
+  const long a = cdiv(strips * cdiv(W, 4), kThreads) + 1;   // rows variant: at least 4 elements per item
+  const long b = strips + 1;                                // LDS variant: at least one strip per block
+  const long c = 65536;                                     // direct variant
+  return (a > b ? a : b) > c ? (a > b ? a : b) : c;
+}
+
+hipError_t launch_filter_stats(const void* g_y, void* gy_u, long planes, int H, int W, int q, int dtype,
+                               float* part, double* stats, hipStream_t st) {
+  ReduceArgs a = {};
+  int blocks = 0;
+  a.stats_part = reinterpret_cast<float2*>(part);
+  a.in = g_y; a.out = gy_u; a.H = H; a.W = W; a.q = q;
+  a.Hp = cdiv(H, q); a.Wp = cdiv(W, q);
+  a.total_in = (int)(planes * H * W);
+  a.total_strips = (int)(planes * a.Hp);
+  a.mean = 1;
+  a.d_hp = FastDiv((uint32_t)a.Hp);
+  a.d_wp = FastDiv((uint32_t)a.Wp);
+  hipError_t e = dtype == GF_BF16 ? launch_t<bf16_t>(a, st, &blocks) : launch_t<float>(a, st, &blocks);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(stats_final_k, dim3(1), dim3(kFinalThreads), 0, st, a.stats_part, blocks, stats);
+  return hipGetLastError();
+}
+
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
                                bool mean, int dtype, hipStream_t st, const KsumJob* ksum) {
   ReduceArgs a = {};
+  int blocks = 0;
   if (ksum) {
     a.ks_w = ksum->w; a.ks_out = ksum->out; a.ks_pairs = ksum->pairs; a.ks_KK = ksum->KK;
   }
@@ -302,8 +446,8 @@ hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, in
   a.mean = mean ? 1 : 0;
   a.d_hp = FastDiv((uint32_t)a.Hp);
   a.d_wp = FastDiv((uint32_t)a.Wp);
-  if (dtype == GF_BF16) return launch_t<bf16_t>(a, st);
-  return launch_t<float>(a, st);
+  if (dtype == GF_BF16) return launch_t<bf16_t>(a, st, &blocks);
+  return launch_t<float>(a, st, &blocks);
 }
 
 }  // namespace gf

@@ -127,6 +127,17 @@ def conv_bwd_filtered(d: B.ConvDesc, g_y: torch.Tensor, x_u: torch.Tensor, w: to
     return g_w, g_x, gy_u
 
 
+def filter_grad_snr(d: B.ConvDesc, g_y: torch.Tensor, ws: Workspace | None = None):
+    """(gy_u, stats) with stats = [sum g_y^2, sum (g_y - patch mean)^2] as a float64 device tensor."""
+    s = shapes(d)
+    _check(g_y, d, s["g_y"], "g_y")
+    gy_u = torch.empty(s["gy_u"], dtype=g_y.dtype, device=g_y.device)
+    stats = torch.empty(2, dtype=torch.float64, device=g_y.device)
+    p, n = _ws(g_y, ws).get(B.gf_workspace_bytes(d, B.GF_OP_FILTER_SNR))
+    B.gf_filter_grad_snr(d, B.ptr(g_y), B.ptr(gy_u), B.ptr(stats), p, n, _stream())
+    return gy_u, stats
+
+
 def conv_bwd_chained(d: B.ConvDesc, gy_u: torch.Tensor, x_u: torch.Tensor, w: torch.Tensor,
                      reduced_out: bool = True, ws: Workspace | None = None):
     """(g_w, g_x) from one call of gf_conv_bwd_chained; g_x is the reduced map unless reduced_out is False."""

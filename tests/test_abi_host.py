@@ -96,6 +96,18 @@ def test_pointer_and_workspace_errors(lib):
         with pytest.raises(B.GfError) as ei:
             B.gf_conv_bwd_chained(d, FAKE, FAKE + 2, FAKE, FAKE, FAKE, reduced, FAKE, need_c)
         assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    # the filter with its noise figures
+    need_s = B.gf_workspace_bytes(d, B.GF_OP_FILTER_SNR)
+    assert need_s >= 8
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad_snr(d, FAKE, FAKE, 0, FAKE, need_s)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad_snr(d, FAKE, FAKE, FAKE, FAKE, need_s - 1)
+    assert ei.value.status == B.GF_ERR_WORKSPACE
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad_snr(d, FAKE, FAKE, FAKE + 8, FAKE, need_s)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
     with pytest.raises(B.GfError) as ei:
         B.gf_conv_bwd_filtered(d, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0)
     assert ei.value.status == B.GF_ERR_WORKSPACE

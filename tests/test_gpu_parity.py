@@ -111,6 +111,49 @@ def test_patch_layout_bit_exact(oracle, H, W, r, s, dtype):
     assert np.array_equal(to64(gy_u), ref_g)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", REDUCE_CASES + [(2, 3, 9, 9, 1, 1), (8, 64, 56, 56, 2, 1), (8, 96, 28, 28, 4, 1)])
+def test_filter_with_noise_figures(oracle, case, dtype):
+    """The filter's by-product (Sec. 3.4, first line of Eq. 8): energy of g_y and of what the
+    filter removes, against the fp64 oracle on the same (rounded) input; the filtered map itself
+    is the one gf_filter_grad writes, bit for bit."""
+    N, C, H, W, r, s = case
+    d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    gy = randn((N, C, Hy, Wy), 13, dtype) + 0.25
+    gyg = gy.cuda()
+    gy_u, stats = T.filter_grad_snr(d, gyg)
+    plain = T.filter_grad(d, gyg)
+    torch.cuda.synchronize()
+    assert torch.equal(gy_u, plain)
+    e, v = oracle.filter_snr(odesc(oracle, d), to64(gy))
+    got = stats.cpu().numpy()
+    assert abs(got[0] - e) <= 1e-5 * e
+    if r == 1 or (Hy <= 1 and Wy <= 1):
+        assert got[1] == 0.0 and v == 0.0
+    else:
+        assert abs(got[1] - v) <= 1e-5 * v
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H,W,r", [(8, 8, 2), (16, 16, 4), (16, 16, 8), (14, 14, 2), (32, 32, 2)])
+def test_noise_figures_bit_exact_on_integers(oracle, H, W, r, dtype):
+    """Small integers times r*r: means and squares are integers and every partial sum stays
+    below 2^24 (at most 6144 terms of at most 96^2), so both sums equal the oracle's whatever
+    the order; a patch-constant map has no noise at all."""
+    N, C = 2, 3
+    d = mk(N, C, C, H, W, K=3, p=1, r=r, dtype=dtype)
+    gy = WL.integer_coded((N, C, H, W), 8, lo=-3, hi=3, dtype=dtype) * (r * r)
+    _, stats = T.filter_grad_snr(d, gy.cuda())
+    e, v = oracle.filter_snr(odesc(oracle, d), to64(gy))
+    assert stats.cpu().tolist() == [e, v]
+    const = WL.integer_coded((N, C, H // r, W // r), 9, dtype=dtype)
+    const = const.repeat_interleave(r, 2).repeat_interleave(r, 3).contiguous()
+    gy_u, stats = T.filter_grad_snr(d, const.cuda())
+    assert stats[1].item() == 0.0 and stats[0].item() == float((to64(const) ** 2).sum())
+    assert torch.equal(gy_u.cpu(), const[:, :, ::r, ::r])
+
+
 def test_r1_reductions_are_copies():
     d = mk(2, 3, 4, 14, 14, K=3, s=2, p=1, r=1, dtype="bf16")
     x = randn((2, 3, 14, 14), 1, "bf16").cuda()

@@ -393,6 +393,72 @@ def test_closed_forms(oracle):
         assert c["act_elems_gf"] / c["act_elems_exact"] == 1 / (r * r)
 
 
+# ----------------------------------------------------------------------------
+# noise of the filter (Sec. 3.4, first line of Eq. 8)
+# ----------------------------------------------------------------------------
+def test_filter_snr_hand_example(oracle):
+    # one 2x2 patch {1, 2, 3, 6}: mean 3, energy 1 + 4 + 9 + 36 = 50, noise 4 + 1 + 0 + 9 = 14
+    d = D(oracle, N=1, C_in=1, C_out=1, H_in=2, W_in=2, K_h=1, K_w=1, r=2)
+    e, v = oracle.filter_snr(d, np.array([1.0, 2.0, 3.0, 6.0]).reshape(1, 1, 2, 2))
+    assert e == 50.0 and v == 14.0
+    # ragged 3x3 map with r = 2: patches {1,2,4,5}, {3,6}, {7,8}, {9}; means 3, 4.5, 7.5, 9
+    g = np.arange(1.0, 10.0).reshape(1, 1, 3, 3)
+    d = D(oracle, N=1, C_in=1, C_out=1, H_in=3, W_in=3, K_h=1, K_w=1, r=2)
+    e, v = oracle.filter_snr(d, g)
+    assert e == 285.0
+    assert v == (4 + 1 + 1 + 4) + 2 * 1.5 ** 2 + 2 * 0.5 ** 2 + 0.0
+
+
+def test_filter_snr_is_the_spectral_ratio_of_eq8(oracle):
+    # Eq. (8), first line, is written on the patch's DFT.  Per patch the filtered signal is
+    # constant, so its DFT keeps the DC bin of G_y and nothing else: the noise is the AC energy
+    # and the signal the total energy, both r^2 times their pixel-domain sums (numpy's fft2).
+    r_ = rng(21)
+    for r in (2, 4):
+        N, C, H, W = 2, 3, 4 * r, 3 * r
+        g = r_.standard_normal((N, C, H, W)) + 0.7
+        d = D(oracle, N=N, C_in=C, C_out=C, H_in=H, W_in=W, K_h=1, K_w=1, r=r)
+        e, v = oracle.filter_snr(d, g)
+        tot = ac = 0.0
+        for n, c, hp, wp in itertools.product(range(N), range(C), range(H // r), range(W // r)):
+            G = np.fft.fft2(g[n, c, hp * r:(hp + 1) * r, wp * r:(wp + 1) * r])
+            P = np.abs(G) ** 2
+            tot += P.sum()
+            ac += P.sum() - P[0, 0]
+        np.testing.assert_allclose(e * r * r, tot, rtol=1e-12)
+        np.testing.assert_allclose(v * r * r, ac, rtol=1e-12)
+        assert e / v > 1.0
+
+
+def test_filter_snr_identities(oracle):
+    r_ = rng(22)
+    N, C, H, W, r = 2, 2, 7, 10, 4   # ragged in both directions
+    d = D(oracle, N=N, C_in=C, C_out=C, H_in=H, W_in=W, K_h=1, K_w=1, r=r)
+    g = r_.standard_normal((N, C, H, W))
+    e, v = oracle.filter_snr(d, g)
+    # energy is the plain sum of squares; the means split it: energy = noise + sum cnt * mean^2
+    np.testing.assert_allclose(e, (g ** 2).sum(), rtol=1e-13)
+    m = oracle.filter_grad(d, g)
+    cnt = F.avg_pool2d(torch.ones(1, 1, H, W, dtype=torch.float64), r, ceil_mode=True,
+                       divisor_override=1).numpy()
+    np.testing.assert_allclose(e - v, (cnt * m ** 2).sum(), rtol=1e-12)
+    # scaling g scales both sums by the square: the ratio does not move
+    e3, v3 = oracle.filter_snr(d, 3.0 * g)
+    np.testing.assert_allclose([e3, v3], [9 * e, 9 * v], rtol=1e-13)
+    # a patch-constant gradient passes the filter unchanged: no noise
+    gc = np.kron(r_.standard_normal((N, C, 2, 3)), np.ones((r, r)))[:, :, :H, :W]
+    ec, vc = oracle.filter_snr(d, gc)
+    assert vc <= 1e-28 * ec
+    # r = 1: the filter is the identity
+    d1 = D(oracle, N=N, C_in=C, C_out=C, H_in=H, W_in=W, K_h=1, K_w=1, r=1)
+    assert oracle.filter_snr(d1, g)[1] == 0.0
+    # a larger patch removes more (nested patches): noise(r = 4) >= noise(r = 2)
+    d2 = D(oracle, N=N, C_in=C, C_out=C, H_in=8, W_in=8, K_h=1, K_w=1, r=2)
+    d4 = D(oracle, N=N, C_in=C, C_out=C, H_in=8, W_in=8, K_h=1, K_w=1, r=4)
+    g8 = r_.standard_normal((N, C, 8, 8))
+    assert oracle.filter_snr(d4, g8)[1] >= oracle.filter_snr(d2, g8)[1]
+
+
 def test_descriptor_rejection(oracle):
     ok = dict(N=1, C_in=4, C_out=4, H_in=8, W_in=8, K_h=3, K_w=3, pad=1, r=2)
     oracle.out_shape(D(oracle, **ok))
