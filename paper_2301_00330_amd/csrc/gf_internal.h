@@ -37,6 +37,27 @@ __device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
   return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
 }
 
+// Loads and stores of data that is touched once per launch (the full-resolution maps): the
+// non-temporal hint keeps them from displacing what the caches could reuse and lets written
+// lines leave the L2 while the kernel still runs instead of at its end.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t r = __builtin_nontemporal_load(static_cast<const u32x4_t*>(p));
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ void store_stream16(void* p, const uint4& v) {
+  const u32x4_t r = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(r, static_cast<u32x4_t*>(p));
+}
+__device__ __forceinline__ void store_stream8(void* p, const uint2& v) {
+  const u32x2_t r = {v.x, v.y};
+  __builtin_nontemporal_store(r, static_cast<u32x2_t*>(p));
+}
+__device__ __forceinline__ void store_stream4(void* p, uint32_t v) {
+  __builtin_nontemporal_store(v, static_cast<uint32_t*>(p));
+}
+
 template <class T> struct Vec16;
 template <> struct Vec16<float> {
   static constexpr int N = 4;

@@ -304,6 +304,9 @@ struct DgradMfmaArgs {
   // plane mode (small or unaligned maps): a tile's columns are `ipt` whole images, so the
   // full-resolution output of a tile row range is one contiguous run of planes per image
   int planes_mode, ipt, cols_per_tile, rows_per_pass;
+  // patch-row mode of the full-resolution store: a tile's columns are `prt` whole patch rows, so
+  // the rx * prt pixel rows it produces for one c_i are one contiguous run of memory
+  int prt;
   // operand loading when P is not a multiple of the vector length: veca = the kernel matrix can
   // still be read with vectors; flatb = gy_u is read as whole-image blocks (column tiles are
   // `ipt` whole images) and scattered into the tile
@@ -551,6 +554,34 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
         }
         __syncthreads();
       }
+    return;
+  }
+  if (a.full && a.prt > 0) {
+    // lane = one 16-byte vector of the contiguous run (prt patch rows x rx pixel rows x W pixels)
+    // that a c_i row of the tile owns; consecutive lanes store consecutive vectors, `rpp` rows
+    // of c_i per pass.  (host: W == Wp * rx, W % VE == 0, rx a power of two, ipr <= kThreads)
+    T* out = static_cast<T*>(a.full);
+    const int rx = a.rx, sh = 31 - __builtin_clz(rx);
+    const int vpr = a.W / VE;                 // vectors per pixel row
+    const int ipr = a.prt * rx * vpr;         // vectors per c_i row of the tile
+    const int rpp = kThreads / ipr;
+    const int rl = tid / ipr, slot = tid - rl * ipr;
+    const int pr = slot / (rx * vpr), rem = slot - pr * rx * vpr;
+    const int i = rem / vpr, vv = rem - i * vpr;
+    const int gr = bx * a.prt + pr;           // patch row counted over the whole batch
+    const int Hp = a.P / a.Wp;
+    const int n = gr / Hp, hp = gr - n * Hp;
+    const int h = hp * rx + i;
+    if (rl >= rpp || pr * a.Wp >= jend - j0 || h >= a.H) return;
+    const T* src = Cs + pr * a.Wp;
+    T* d = out + (((long)n * a.Ci + m0) * a.H + h) * a.W + vv * VE;
+    const int rows_valid = min(BM, a.Ci - m0);
+    for (int row = rl; row < rows_valid; row += rpp) {
+      T vals[VE];
+#pragma unroll
+      for (int e = 0; e < VE; ++e) vals[e] = src[row * SC + ((vv * VE + e) >> sh)];
+      store_stream16(d + (long)row * a.H * a.W, *reinterpret_cast<const uint4*>(vals));
+    }
     return;
   }
   if (a.full) {
@@ -825,10 +856,28 @@ hipError_t wgrad_launch(WgradMfmaArgs& a, int nz, bool vec, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Column tiles of the input-gradient GEMM when neither whole images nor image blocks are used:
+// whole patch rows if the full-resolution store can use them (see DgradMfmaArgs::prt), else BN.
+template <class T>
+void dgrad_column_tiles(DgradMfmaArgs& a, int BN) {
+  constexpr int VE = Mma<T>::VE;
+  a.prt = 0;
+  a.cols_per_tile = BN;
+  if (!a.full || a.Wp > BN) return;
+  const int per_patch_row = a.rx * (a.W / VE);   // vectors of one patch row of one c_i
+  if (per_patch_row > kThreads) return;
+  int prt = BN / a.Wp;
+  if (prt > kThreads / per_patch_row) prt = kThreads / per_patch_row;
+  while (prt > 0 && (prt * a.Wp) % VE != 0) --prt;   // tiles start on vector boundaries of gy_u
+  if (prt < 1) return;
+  a.prt = prt;
+  a.cols_per_tile = prt * a.Wp;
+}
+
 template <class T, int TM, int TN, int WM, int WN>
 hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
-  if (!a.planes_mode && !a.flatb) a.cols_per_tile = BN;
+  if (!a.planes_mode && !a.flatb) dgrad_column_tiles<T>(a, BN);
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, BM), 1);
   if (vec)
     hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
@@ -930,7 +979,7 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
 
 template <class T, int BN>
 hipError_t dgrad_ksplit_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
-  if (!a.planes_mode) a.cols_per_tile = BN;
+  if (!a.planes_mode) dgrad_column_tiles<T>(a, BN);
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, 32), 1);
   if (vec)
     hipLaunchKernelGGL((dgrad_ksplit_k<T, BN, true>), grid, dim3(kThreads), 0, st, a);
@@ -1012,6 +1061,7 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   a.rx = g.rx;
   a.d_wp = FastDiv((uint32_t)g.Wp);
   a.planes_mode = 0;
+  a.prt = 0;
   a.ipt = 0;
   a.cols_per_tile = 0;
   a.rows_per_pass = 0;
@@ -1090,7 +1140,7 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
       da.ipt = images_per_tile(g, bn, 32);
       da.cols_per_tile = da.ipt * g.P;
     } else {
-      da.cols_per_tile = bn;
+      dgrad_column_tiles<T>(da, bn);
     }
     gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
     const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 32);
@@ -1109,7 +1159,7 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
       hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     return hipGetLastError();
   }
-  da.cols_per_tile = g.Ci <= 32 ? 128 : 64;
+  dgrad_column_tiles<T>(da, g.Ci <= 32 ? 128 : 64);
   gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
   const int nd = gr.dgx * cdiv(g.Ci, g.Ci <= 32 ? 32 : 64);
   if (g.Ci <= 32)
@@ -1145,7 +1195,7 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
   da.d_p = FastDiv((uint32_t)g.P);
   da.full = g_x; da.H = g.H; da.W = g.W; da.Wp = g.Wp; da.rx = g.rx;
   da.d_wp = FastDiv((uint32_t)g.Wp);
-  da.planes_mode = 0; da.ipt = 0; da.cols_per_tile = 0; da.rows_per_pass = 0;
+  da.planes_mode = 0; da.prt = 0; da.ipt = 0; da.cols_per_tile = 0; da.rows_per_pass = 0;
   da.N = g.N; da.veca = 1; da.flatb = 0;
   if (reduced) {  // reduced map out, as in dgrad_t
     da.dst = g_x;

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
       const int ri = min(i, rows[u] - 1);
 #pragma unroll
       for (int k = 0; k < VW; ++k)
-        v[u][i][k] = *reinterpret_cast<const uint4*>(p + (long)ri * a.W + k * VE);
+        v[u][i][k] = load_stream16(p + (long)ri * a.W + k * VE);
     }
   }
 #pragma unroll
@@ -152,9 +152,9 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
     }
     T* dst = out + (long)strip[u] * a.Wp + col[u] * NOUT;
     if constexpr (NOUT * sizeof(T) == 8) {
-      *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(res);
+      store_stream8(dst, *reinterpret_cast<const uint2*>(res));
     } else if constexpr (NOUT * sizeof(T) == 4) {
-      *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(res);
+      store_stream4(dst, *reinterpret_cast<const uint32_t*>(res));
     } else {
 #pragma unroll
       for (int o = 0; o < NOUT; ++o) dst[o] = res[o];
@@ -321,7 +321,7 @@ template <class T, int Q>
 hipError_t launch_rows(ReduceArgs& a, hipStream_t st, int* nblocks) {
   constexpr int VE = Vec16<T>::N;
   constexpr int IW = VE > Q ? VE : Q;
-  constexpr int U = (Q >= 8) ? 1 : 2;  // vectors in flight per lane: U * Q * VW (U = 4 measured slower)
+  constexpr int U = 1;
   a.ipr = a.W / IW;
   a.total_items = a.total_strips * a.ipr;
   a.d_ipr = FastDiv((uint32_t)a.ipr);
