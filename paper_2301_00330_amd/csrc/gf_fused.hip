@@ -44,9 +44,20 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   __syncthreads();
   float s = 0.f;
   if (threadIdx.x == 0)
-    for (int k = 0; k < kThreads / 64; ++k) s += red[k];
+    for (int k = 0; k < (int)(blockDim.x >> 6); ++k) s += red[k];
   __syncthreads();
   return s;
+}
+
+constexpr int kMaxRowsThreads = 512;
+
+// Blocks of the rows variant: a plane's items are cut into `cpp` equal chunks of at most 512 and
+// a block has just enough waves for one chunk (a fixed 256 would leave a quarter of the lanes
+// idle on a 56 x 56 plane, which has 392 items).
+inline int rows_chunks(int ipp, int* nthreads) {
+  const int cpp = cdiv(ipp, kMaxRowsThreads);
+  *nthreads = 64 * cdiv(cdiv(ipp, cpp), 64);
+  return cpp;
 }
 
 // ---------------------------------------------------------------------------
@@ -54,12 +65,12 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // block = (U consecutive planes, one chunk of 256 items); lane u-th item belongs to plane u
 // ---------------------------------------------------------------------------
 template <class T, int Q, int U>
-__global__ __launch_bounds__(kThreads) void dw_fused_rows_k(DwFusedArgs a) {
+__global__ __launch_bounds__(kMaxRowsThreads) void dw_fused_rows_k(DwFusedArgs a) {
   constexpr int VE = Vec16<T>::N;
   constexpr int IW = VE > Q ? VE : Q;
   constexpr int VW = IW / VE;
   constexpr int NOUT = IW / Q;
-  __shared__ float red[kThreads / 64];
+  __shared__ float red[kMaxRowsThreads / 64];
   const T* gy = static_cast<const T*>(a.gy);
   const T* xu = static_cast<const T*>(a.xu);
   const T* w = static_cast<const T*>(a.w);
@@ -67,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void dw_fused_rows_k(DwFusedArgs a) {
   T* gyu = static_cast<T*>(a.gyu);
   const int pg = (int)a.d_cpp.div(blockIdx.x);
   const int chunk = blockIdx.x - pg * a.cpp;
-  const int item = chunk * kThreads + threadIdx.x;
+  const int item = chunk * (int)blockDim.x + threadIdx.x;
   const bool item_ok = item < a.ipp;
   const int itc = min(item, a.ipp - 1);
   const int hp = (int)a.d_ipr.div((uint32_t)itc);
@@ -424,7 +435,8 @@ bool dw_fused_ok(const Geom& g, int* nz) {
     const int VE = 16 / g.b;
     const int IW = VE > g.r ? VE : g.r;
     const int ipp = g.Hp * (g.W / IW);
-    if (nz) *nz = g.N * cdiv(ipp, kThreads);
+    int nthreads;
+    if (nz) *nz = g.N * rows_chunks(ipp, &nthreads);
     return true;
   }
   const int ppb = g.dtype == GF_BF16 ? lds_planes_per_block<bf16_t>(g) : lds_planes_per_block<float>(g);
@@ -458,16 +470,14 @@ static hipError_t dw_fused_t(const Geom& g, const void* g_y, const void* x_u, co
     const int IW = VE > g.r ? VE : g.r;
     a.ipr = g.W / IW;
     a.ipp = g.Hp * a.ipr;
-    a.cpp = cdiv(a.ipp, kThreads);
+    int nthreads;
+    a.cpp = rows_chunks(a.ipp, &nthreads);
     a.d_ipr = FastDiv((uint32_t)a.ipr);
     a.d_cpp = FastDiv((uint32_t)a.cpp);
-    if (g.r == 8) {
-      hipLaunchKernelGGL((dw_fused_rows_k<T, 8, 1>), dim3(a.planes * a.cpp), dim3(kThreads), 0, st, a);
-    } else {
-      const int blocks = cdiv(a.planes, 2) * a.cpp;
-      if (g.r == 2) hipLaunchKernelGGL((dw_fused_rows_k<T, 2, 2>), dim3(blocks), dim3(kThreads), 0, st, a);
-      else hipLaunchKernelGGL((dw_fused_rows_k<T, 4, 2>), dim3(blocks), dim3(kThreads), 0, st, a);
-    }
+    const dim3 grid(a.planes * a.cpp), block(nthreads);
+    if (g.r == 8) hipLaunchKernelGGL((dw_fused_rows_k<T, 8, 1>), grid, block, 0, st, a);
+    else if (g.r == 2) hipLaunchKernelGGL((dw_fused_rows_k<T, 2, 1>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((dw_fused_rows_k<T, 4, 1>), grid, block, 0, st, a);
     return hipGetLastError();
   }
   a.ppb = lds_planes_per_block<T>(g);
