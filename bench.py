@@ -123,10 +123,10 @@ def measure(args, dtype, full):
     set_bytes = sum(lb.nbytes() for lb in one)
     # enough sets that (a) a step never finds its inputs in the 256 MB memory-side cache and (b) the
     # per-stage timings, which rotate over ONE layer's tensors only, do not either (>= 1 GB of the
-    # largest tensor), within 12 GB in total
+    # largest tensor), within 12 GB in total and 48 sets (tiny workloads stay cache-resident)
     largest = max(max(lb.x.numel() * lb.x.element_size(), lb.gy.numel() * lb.gy.element_size()) for lb in one)
-    nsets = args.sets or max(3, int(768e6 // set_bytes) + 1,
-                             min(int(1.0e9 // largest) + 1, max(1, int(12e9 // set_bytes))))
+    nsets = args.sets or min(48, max(3, int(768e6 // set_bytes) + 1,
+                                     min(int(1.0e9 // largest) + 1, max(1, int(12e9 // set_bytes)))))
     sets = [one] + [[LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)] for _ in range(nsets - 1)]
     log(f"workload cfg{cfg.cfg_id} '{cfg.name}' N={N} r={r} dtype={dtype}: {set_bytes / 1e6:.1f} MB per set x {nsets} sets")
 
