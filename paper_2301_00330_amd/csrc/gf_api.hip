@@ -64,6 +64,11 @@ static size_t ws_filtered(const Geom& g, bool own_gyu, size_t* off_w, size_t* of
     if (off_i) *off_i = 0;
     return (size_t)nz * g.Ci * sizeof(float);
   }
+  if (onepass_ok(g, &nz)) {
+    if (off_w) *off_w = 0;
+    if (off_i) *off_i = 0;
+    return (size_t)nz * g.Co * g.Ci * sizeof(float);
+  }
   size_t o = own_gyu ? align256((size_t)g.N * g.Co * g.P * g.b) : 0;
   if (off_w) *off_w = o;
   o += align256(ws_bwd_weight(g));
@@ -246,6 +251,12 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
     rc = dev(launch_dw_fused(g, g_y, x_u, w, gy_u, g_x, part, st));
     if (rc) return rc;
     return dev(launch_finalize(part, g_w, g.Ci, nz, g.KK, 1.f / ((float)g.s * (float)g.s), st));
+  }
+  if (onepass_ok(g, &nz)) {  // pointwise with few input channels: g_y is read once
+    float* part = static_cast<float*>(ws);
+    rc = dev(launch_onepass(g, g_y, x_u, w, gy_u, g_x, part, st));
+    if (rc) return rc;
+    return dev(launch_finalize(part, g_w, g.Co * g.Ci, nz, g.KK, 1.f, st));
   }
   void* gyu = gy_u ? gy_u : static_cast<void*>(wsb);
   const bool merged = mfma_s3s4_ok(g);

@@ -159,6 +159,12 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
                              int* nz_out, hipStream_t st);
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
                              void* full, hipStream_t st);
+// whole filtered backward of a pointwise stride-1 layer with at most 32 input channels in one
+// launch (then launch_finalize on `part`, *nz slabs of Co * Ci); gy_u may be null
+bool onepass_ok(const Geom& g, int* nz);
+hipError_t launch_onepass(const Geom& g, const void* g_y, const void* x_u, const void* w, void* gy_u,
+                          void* g_x, float* part, hipStream_t st);
+
 // both gradients of a dense layer in one launch (then launch_finalize on `part`, nz slabs)
 // With `reduced` the input gradient is written as the reduced map [N, Ci, P] instead of g_x.
 bool mfma_s3s4_ok(const Geom& g, bool reduced = false);

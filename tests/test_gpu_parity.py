@@ -249,6 +249,13 @@ FUSED_EXTRA = [
     (5, 16, 16, 16, 16, 3, 1, 1, 1, 1, 2),        # several units per block, W_p = 8
     (2, 20, 36, 64, 64, 1, 1, 0, 1, 1, 8),        # r = 8
     (1, 64, 64, 22, 24, 3, 1, 1, 1, 1, 2),        # ragged H (22 = 11 x 2), W_p = 12
+    # pointwise layers with few input channels (one-pass kernel) and their mirror shapes
+    (3, 8, 256, 15, 16, 1, 1, 0, 1, 1, 2),        # ragged H, tiles straddle images, eight chunks of C_y, C_x < 16
+    (2, 160, 32, 6, 16, 1, 1, 0, 1, 1, 2),        # many input channels: the merged-launch path; three patch rows per image
+    (1, 32, 72, 10, 128, 1, 1, 0, 1, 1, 2),       # W_p = 64: one patch row per tile; partial last chunk
+    (5, 24, 48, 28, 28, 1, 1, 0, 1, 1, 2),        # W_p = 14 (narrow x_u loads), four patch rows per tile, tail tile
+    (2, 96, 24, 8, 24, 1, 1, 0, 1, 1, 2),         # project shape, W_p = 12
+    (7, 16, 40, 6, 8, 1, 1, 0, 1, 1, 2),          # W_p = 4: sixteen patch rows per tile, two images and a tail
 ]
 
 
