@@ -4,7 +4,8 @@
 //    "same"-padded strided layers) are handed to the implicit-GEMM kernels (gf_implicit.hip);
 //  * other dense layers: the shifted operand is written once per tap to a column tensor in
 //    the workspace and the MFMA GEMMs of the filtered path do the contractions;
-//  * grouped / depthwise layers: shape-generic direct kernels, one lane per g_x element
+//  * depthwise layers whose planes fit LDS: plane-staged kernels (gf_dwexact.hip);
+//  * other grouped layers: shape-generic direct kernels, one lane per g_x element
 //    (gather over the taps that reach it) and one block per weight-gradient element.
 #include "gf_internal.h"
 
@@ -308,7 +309,7 @@ ExactArgs make_args(const Geom& g) {
 
 size_t ws_exact(const Geom& g, bool want_gw, bool want_gx) {
   if (implicit_ok(g)) return ws_implicit(g, want_gw, want_gx);
-  if (!gemm_path(g)) return 0;
+  if (!gemm_path(g)) return want_gw && dw_exact_wgrad_ok(g) ? ws_dw_exact_wgrad(g) : 0;
   return col_bytes(g, want_gw, want_gx) + aux_bytes(g, want_gw, want_gx);
 }
 
@@ -335,6 +336,7 @@ hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, flo
     if (e != hipSuccess) return e;
     return launch_finalize(part, g_w, q.Co * q.Ci, nz, 1, 1.f, st);
   }
+  if (dw_exact_wgrad_ok(g)) return launch_dw_exact_wgrad(g, x, g_y, g_w, ws, st);
   ExactArgs a = make_args(g);
   a.x = x;
   a.gy = g_y;
@@ -369,6 +371,7 @@ hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, voi
     if (e != hipSuccess) return e;
     return launch_mfma_dgrad(q, ws, wt, nullptr, g_x, nullptr, st);
   }
+  if (dw_exact_dgrad_ok(g)) return launch_dw_exact_dgrad(g, w, g_y, g_x, st);
   ExactArgs a = make_args(g);
   a.w = w;
   a.gy = g_y;

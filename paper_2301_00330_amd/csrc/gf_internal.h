@@ -159,6 +159,14 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
                              int* nz_out, hipStream_t st);
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,
                              void* full, hipStream_t st);
+// vanilla BP of depthwise layers whose planes fit LDS (ws: ws_dw_exact_wgrad bytes for the weight gradient)
+bool dw_exact_dgrad_ok(const Geom& g);
+bool dw_exact_wgrad_ok(const Geom& g);
+size_t ws_dw_exact_wgrad(const Geom& g);
+hipError_t launch_dw_exact_dgrad(const Geom& g, const void* w, const void* g_y, void* g_x, hipStream_t st);
+hipError_t launch_dw_exact_wgrad(const Geom& g, const void* x, const void* g_y, float* g_w, void* ws,
+                                 hipStream_t st);
+
 // whole filtered backward of a pointwise stride-1 layer with at most 32 input channels in one
 // launch (then launch_finalize on `part`, *nz slabs of Co * Ci); gy_u may be null
 bool onepass_ok(const Geom& g, int* nz);

@@ -416,6 +416,13 @@ EXACT_CASES = [
     (2, 16, 16, 8, 8, 1, 2, 0, 1, 1), (2, 8, 16, 15, 13, 3, 2, 1, 1, 1), (1, 8, 8, 12, 12, 3, 3, 1, 1, 1),
     (2, 16, 8, 12, 12, 3, 2, 2, 2, 1), (1, 8, 8, 11, 9, 5, 2, 2, 1, 1), (3, 136, 72, 14, 14, 3, 2, 1, 1, 1),
     (3, 64, 128, 7, 7, 3, 2, 1, 1, 1),
+    # depthwise layers (plane-staged kernels): a block per plane (56x56), a wave per plane with odd,
+    # unaligned planes (7x7), stride 2 on an odd map, dilation, 5x5, no padding, stride 3,
+    # 7x7 taps (weight gradient on the generic kernel), a plane too large for LDS in fp32
+    (2, 16, 16, 56, 56, 3, 1, 1, 1, 16), (8, 40, 40, 7, 7, 3, 1, 1, 1, 40), (3, 10, 10, 15, 13, 3, 2, 1, 1, 10),
+    (2, 6, 6, 12, 12, 3, 1, 2, 2, 6), (2, 5, 5, 11, 11, 5, 1, 2, 1, 5), (2, 7, 7, 9, 10, 3, 1, 0, 1, 7),
+    (2, 9, 9, 14, 14, 3, 3, 1, 1, 9), (1, 4, 4, 10, 10, 7, 1, 3, 1, 4), (1, 3, 3, 100, 90, 3, 1, 1, 1, 3),
+    (5, 33, 33, 14, 14, 5, 2, 2, 1, 33),
 ]
 
 
