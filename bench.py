@@ -402,7 +402,7 @@ def measure(args, dtype, full):
                  "speedup_vs_torch_miopen_block": round(sum(mi_us) / sum(gf_us), 2),
                  "speedup_vs_own_entry_block": round(sum(ex_us) / sum(gf_us), 2),
                  "note": "filtered = gf_conv_bwd_filtered (S1+S2+S3+S4) per layer; own entry = gf_conv_bwd_exact "
-                         "(dense stride-1: implicit MFMA GEMMs; other dense: column tensor + MFMA GEMMs; depthwise: direct "
+                         "(dense stride-1: implicit MFMA GEMMs; other dense: column tensor + MFMA GEMMs; depthwise: plane-staged "
                          "kernels), cold; torch = autograd of "
                          "F.conv2d (MIOpen), hot cache, for context"}
 
