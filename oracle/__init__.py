@@ -142,6 +142,17 @@ def pool_activation(d: Desc, x) -> np.ndarray:
     return out
 
 
+def pool_activation_mask(d: Desc, x, hi: float = float("inf")):
+    """(x_u, m_u): the patch sums of x and the fraction of each patch through which a ReLU
+    (clipped at `hi`) that produced x passes a gradient."""
+    x = _in(x, (d.N, d.C_in, d.H_in, d.W_in))
+    x_u = np.empty(xu_shape(d), np.float64)
+    m_u = np.empty(xu_shape(d), np.float64)
+    cd = d._c()
+    _chk(_L().gf_ref_pool_activation_mask(C.byref(cd), _p(x), C.c_double(hi), _p(x_u), _p(m_u)), "pool_activation_mask")
+    return x_u, m_u
+
+
 def kernel_sum(d: Desc, w) -> np.ndarray:
     w = _in(w, w_shape(d))
     out = np.empty((d.C_out, d.C_in // d.groups), np.float64)

@@ -120,6 +120,20 @@ int gf_ref_pool_activation(const gf_ref_desc* d, const double* x, double* x_u) {
   return REF_OK;
 }
 
+int gf_ref_pool_activation_mask(const gf_ref_desc* d, const double* x, double hi, double* x_u, double* m_u) {
+  int rc = gf_ref_pool_activation(d, x, x_u);
+  if (rc) return rc;
+  if (!m_u) return REF_NULL;
+  size_t total = (size_t)d->N * d->C_in * d->H_in * d->W_in;
+  double* pass = (double*)malloc(sizeof(double) * total);
+  if (!pass) return REF_NULL;
+  for (size_t e = 0; e < total; ++e) pass[e] = (x[e] > 0.0 && x[e] < hi) ? 1.0 : 0.0;
+  int q = d->r == 1 ? 1 : d->r * d->stride;
+  patch_reduce(pass, m_u, (long)d->N * d->C_in, d->H_in, d->W_in, q, 1);   /* mean over in-bounds pixels */
+  free(pass);
+  return REF_OK;
+}
+
 int gf_ref_kernel_sum(const gf_ref_desc* d, const double* w, double* w_sum) {
   int rc = check_desc(d);
   if (rc) return rc;

@@ -65,6 +65,12 @@ int gf_ref_filter_snr(const gf_ref_desc* d, const double* g_y, double* energy, d
 /* S0, text after Eq. (5): x_u[n,c,hp,wp] = sum of x over the r_x x r_x patch.
  * [N,C_in,H_p,W_p]; with r == 1 it is a copy of x, [N,C_in,H_in,W_in].          */
 int gf_ref_pool_activation(const gf_ref_desc* d, const double* x, double* x_u);
+/* S0 for a layer whose input is the output of a ReLU (hi = +inf) or of a clipped ReLU
+ * (0 < x < hi passes the gradient): beside x_u, m_u[n,c,hp,wp] = the fraction of the patch's
+ * in-bounds pixels through which that non-linearity passes a gradient.  With the upper layer's
+ * input gradient constant on every patch (Eq. 3), the gradient filter of the layer below
+ * (Eq. 2, patch r_x) applied to the masked gradient returns that constant times m_u.        */
+int gf_ref_pool_activation_mask(const gf_ref_desc* d, const double* x, double hi, double* x_u, double* m_u);
 /* S2, text after Eq. (3): w_sum[c_o,c_i'] = sum over taps.  [C_out, C_in/groups] */
 int gf_ref_kernel_sum(const gf_ref_desc* d, const double* w, double* w_sum);
 /* S3, Eq. (5): Frobenius inner product of x_u and gy_u over (n, patch), scaled

@@ -189,6 +189,51 @@ def test_chain_of_filtered_layers_can_pass_reduced_maps(oracle, s, r, K, p):
     np.testing.assert_allclose(oracle.bwd_input(lo, gx_red, w_lo), ref[1], rtol=1e-12, atol=1e-300)
 
 
+@pytest.mark.parametrize("act", ["relu", "relu6"])
+@pytest.mark.parametrize("s,r,H", [(1, 2, 12), (1, 4, 10), (2, 2, 14), (1, 3, 7)])
+def test_chain_across_a_relu_needs_the_mask_fraction_only(oracle, s, r, H, act):
+    """Two stacked layers with a (clipped) ReLU between them.  torch's autograd of the
+    non-linearity (a library routine) turns the upper layer's patch-constant input gradient into
+    the lower layer's g_y; the lower layer's filter (Eq. 2, patch r * stride) of it equals the
+    reduced input gradient times the fraction of each patch that the non-linearity lets through,
+    which is what the masked activation pooling returns beside x_u."""
+    W = H
+    q = r * s
+    up = D(oracle, N=2, C_in=3, C_out=4, H_in=H, W_in=W, K_h=3, K_w=3, stride=s, pad=1, r=r)
+    lo = D(oracle, N=2, C_in=2, C_out=3, H_in=H, W_in=W, K_h=3, K_w=3, pad=1, r=q)
+    g = rng(40 + s + r + H)
+    Hy, Wy, _, _ = oracle.out_shape(up)
+    pre = torch.tensor(g.standard_normal((2, 3, H, W)) * 4.0 + 2.0, requires_grad=True)   # output of the lower layer (+BN)
+    post = F.relu(pre) if act == "relu" else F.relu6(pre)                                    # input of the upper layer
+    hi = float("inf") if act == "relu" else 6.0
+    x_up = post.detach().numpy()
+    gyu_up = oracle.filter_grad(up, g.standard_normal((2, 4, Hy, Wy)))
+    w_up = g.standard_normal((4, 3, 3, 3))
+    gx_full = oracle.bwd_input(up, gyu_up, w_up)                      # gradient w.r.t. `post`
+    gx_red = oracle.bwd_input(up, gyu_up, w_up, reduced_out=True)
+    post.backward(torch.tensor(gx_full))
+    g_pre = pre.grad.numpy()                                          # what reaches the lower layer
+    x_u, m_u = oracle.pool_activation_mask(up, x_up, hi)
+    np.testing.assert_allclose(x_u, oracle.pool_activation(up, x_up), rtol=0, atol=0)
+    np.testing.assert_allclose(oracle.filter_grad(lo, g_pre), gx_red * m_u, rtol=1e-13, atol=1e-300)
+    # the fraction itself: average pooling of the 0/1 mask over in-bounds pixels (library routine)
+    mask = torch.tensor(((x_up > 0) & (x_up < hi)).astype(np.float64))
+    ref = F.avg_pool2d(mask, q, ceil_mode=True, count_include_pad=False).numpy()
+    np.testing.assert_allclose(m_u, ref, rtol=1e-15, atol=0)
+    assert 0.0 < m_u.mean() < 1.0 and ((m_u > 0) & (m_u < 1)).any()
+
+
+def test_mask_fraction_hand_example(oracle):
+    d = D(oracle, N=1, C_in=1, C_out=1, H_in=3, W_in=3, K_h=1, K_w=1, r=2)
+    x = np.array([[-1.0, 2.0, 7.0], [0.0, 3.0, 5.0], [6.5, 0.5, -2.0]]).reshape(1, 1, 3, 3)
+    x_u, m = oracle.pool_activation_mask(d, x)
+    # patches {-1, 2, 0, 3}, {7, 5}, {6.5, 0.5}, {-2}: x = 0 passes nothing
+    assert m.reshape(-1).tolist() == [0.5, 1.0, 1.0, 0.0]
+    assert x_u.reshape(-1).tolist() == [4.0, 12.0, 7.0, -2.0]
+    _, m6 = oracle.pool_activation_mask(d, x, 6.0)
+    assert m6.reshape(-1).tolist() == [0.5, 0.5, 0.5, 0.0]
+
+
 GF_CASES = [
     # N Ci Co H  W  K s p d g r
     (2, 3, 4, 8, 8, 3, 1, 1, 1, 1, 2),
