@@ -220,10 +220,18 @@ def measure(args, dtype, full):
                 nb = B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_CHAINED)
                 lb.ws_c = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
 
-        def step_chained(bufset):
+        clip = list(cfg.chain_clip) if cfg.chain_clip else [0.0] * len(layers)
+        for bs in sets:
+            for li, lb in enumerate(bs):
+                lb.m_u = torch.empty_like(lb.x_u) if clip[li] > 0 else None
+
+        def step_chained(bufset, masked=False):
             s = st()
-            for lb in bufset:
-                enqueue_pool(lb, s)                   # forward-time S0, unchanged
+            for li, lb in enumerate(bufset):          # forward-time S0 (with the mask fraction below a ReLU)
+                if masked and lb.m_u is not None:
+                    B.gf_pool_activation_mask(lb.d, P(lb.x), clip[li], P(lb.x_u), P(lb.m_u), s)
+                else:
+                    enqueue_pool(lb, s)
             top = bufset[order[0]]
             B.gf_filter_grad(top.d, P(top.gy), P(top.gy_u), s)
             gin = top.gy_u
@@ -231,7 +239,8 @@ def measure(args, dtype, full):
                 lb = bufset[li]
                 last = k == len(order) - 1
                 gout = lb.g_x if last else lb.g_xu
-                B.gf_conv_bwd_chained(lb.d, P(gin), P(lb.x_u), P(lb.w), P(lb.g_w), P(gout), not last,
+                m = P(lb.m_u) if (masked and not last and lb.m_u is not None) else 0
+                B.gf_conv_bwd_chained(lb.d, P(gin), P(lb.x_u), P(lb.w), P(lb.g_w), P(gout), not last, m,
                                       P(lb.ws_c), lb.ws_c.numel(), s)
                 gin = gout
 
@@ -262,7 +271,21 @@ def measure(args, dtype, full):
                 step_chained(sets[i % nsets])
         torch.cuda.synchronize()
         cms = (time.perf_counter() - t0) * 1e3 / args.steps
+        mms = None
+        if any(c > 0 for c in clip):   # the same chain with the clipped ReLUs of the block between the layers
+            for i in range(max(args.warmup, 1)):
+                step_chained(sets[i % nsets], True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                step_chained(sets[i % nsets], True)
+            torch.cuda.synchronize()
+            mms = (time.perf_counter() - t0) * 1e3 / args.steps
         chained = {"ms_per_step": round(cms, 5), "value": round(N / (cms * 1e-3), 1), "unit": "images/s",
+                   "with_relu6_masks_ms_per_step": None if mms is None else round(mms, 5),
+                   "with_relu6_masks_note": "plain launches; S0 of the layers below a ReLU6 also writes the mask "
+                                            "fraction (gf_pool_activation_mask), the reduced input gradient is "
+                                            "multiplied by it inside the chained call",
                    "note": "same layers and S0 launches, but only the top layer's g_y is filtered: "
                            "gf_conv_bwd_chained hands the reduced input gradient of a layer to the layer below "
                            "(valid for a stack of stride-1 convolutions with nothing between them); full "

@@ -121,6 +121,16 @@ gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes);
  * loop keeps for the backward pass instead of x (Sec. 4.3). */
 gf_status gf_pool_activation(const gf_conv_desc* desc, const void* x, void* x_u, void* stream);
 
+/* The same for a layer whose input x is the output of a ReLU (hi = +infinity) or of a clipped
+ * ReLU (hi = 6 for ReLU6), for chains of filtered layers (see gf_conv_bwd_chained): beside x_u
+ * it writes m_u [N, C_in, H_p, W_p] (storage type), the share of each patch's in-bounds pixels
+ * with 0 < x < hi, i.e. the patch average of the gradient mask of that non-linearity.  Eq. 2
+ * of the layer below, applied to this layer's patch-constant input gradient (Eq. 3) times the
+ * mask, is that gradient's one value per patch times m_u.  hi <= 0 or NaN: GF_ERR_BAD_DESC.
+ * With r == 1, x_u is a copy of x and m_u the mask itself, [N, C_in, H_in, W_in]. */
+gf_status gf_pool_activation_mask(const gf_conv_desc* desc, const void* x, float hi, void* x_u, void* m_u,
+                                  void* stream);
+
 /* The gradient filter (Eq. 2): gy_u = mean of g_y over each r x r patch, one
  * value per patch (the matrix of unique values, Sec. 3.3). */
 gf_status gf_filter_grad(const gf_conv_desc* desc, const void* g_y, void* gy_u, void* stream);
@@ -171,10 +181,14 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
  * reduced_out != 0 as the reduced map [N, C_in, H_p, W_p] to pass on, else at full
  * resolution.  Same results as gf_conv_bwd_weight + gf_conv_bwd_input (g_x bit for
  * bit, g_w up to the order of the fp32 partial sums); fewer launches, and neither the
- * full-resolution write nor the next layer's read of it. */
+ * full-resolution write nor the next layer's read of it.  mask_u (NULL: none) is the m_u of
+ * gf_pool_activation_mask for this layer's input: with a (clipped) ReLU below this layer the
+ * reduced g_x is multiplied by it (product formed in fp32, rounded once), which is what the
+ * filter of the layer below would return for the masked gradient.  It needs reduced_out != 0
+ * (or r == 1, where it is the full mask); else GF_ERR_UNSUPPORTED. */
 gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const void* x_u,
-                              const void* w, float* g_w, void* g_x, int reduced_out, void* ws,
-                              size_t ws_bytes, void* stream);
+                              const void* w, float* g_w, void* g_x, int reduced_out, const void* mask_u,
+                              void* ws, size_t ws_bytes, void* stream);
 
 /* Vanilla back-propagation of the layer (Sec. 3.1): g_w = g_y (F) x and
  * g_x = g_y (*) rot180(w), zero padding, with stride, dilation and groups.

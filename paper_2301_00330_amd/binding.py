@@ -19,7 +19,8 @@ GF_F32, GF_BF16 = 0, 1
 GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BWD_CHAINED = 0, 1, 2, 3, 4
 GF_OP_FILTER_SNR = 5
 
-EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_filter_grad", "gf_filter_grad_snr",
+EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_mask", "gf_filter_grad",
+           "gf_filter_grad_snr",
            "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_chained",
            "gf_conv_bwd_exact",
            "gf_cost_model",
@@ -93,7 +94,8 @@ def lib() -> C.CDLL:
         L.gf_conv_bwd_input.argtypes = [dp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_conv_bwd_exact.argtypes = [dp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_filtered.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
-        L.gf_conv_bwd_chained.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
+        L.gf_conv_bwd_chained.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int, vp, vp, C.c_size_t, vp]
+        L.gf_pool_activation_mask.argtypes = [dp, vp, C.c_float, vp, vp, vp]
         L.gf_cost_model.argtypes = [dp, C.POINTER(_Cost)]
         L.gf_status_string.argtypes = [C.c_int]
         L.gf_status_string.restype = C.c_char_p
@@ -173,10 +175,15 @@ def gf_filter_grad_snr(d: ConvDesc, g_y: int, gy_u: int, stats: int, ws: int, ws
 
 
 def gf_conv_bwd_chained(d: ConvDesc, gy_u: int, x_u: int, w: int, g_w: int, g_x: int,
-                        reduced_out: bool, ws: int, ws_bytes: int, stream: int = 0):
+                        reduced_out: bool, mask_u: int, ws: int, ws_bytes: int, stream: int = 0):
     cd = d.c()
-    _chk(lib().gf_conv_bwd_chained(C.byref(cd), gy_u, x_u, w, g_w, g_x, int(bool(reduced_out)), ws,
+    _chk(lib().gf_conv_bwd_chained(C.byref(cd), gy_u, x_u, w, g_w, g_x, int(bool(reduced_out)), mask_u, ws,
                                    ws_bytes, stream), "gf_conv_bwd_chained")
+
+
+def gf_pool_activation_mask(d: ConvDesc, x: int, hi: float, x_u: int, m_u: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_pool_activation_mask(C.byref(cd), x, C.c_float(hi), x_u, m_u, stream), "gf_pool_activation_mask")
 
 
 def gf_conv_bwd_exact(d: ConvDesc, x: int, w: int, g_y: int, g_w: int, g_x: int, ws: int,

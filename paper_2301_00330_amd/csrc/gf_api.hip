@@ -278,6 +278,19 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
   return dev(launch_gf_bwd_input(g, gyu, w, g_x, false, wsb + off_i, st));
 }
 
+gf_status gf_pool_activation_mask(const gf_conv_desc* desc, const void* x, float hi, void* x_u, void* m_u,
+                                  void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (!x || !x_u || !m_u) return GF_ERR_NULL;
+  if (!aligned16(x) || !aligned16(x_u) || !aligned16(m_u)) return GF_ERR_UNSUPPORTED;
+  if (!(hi > 0.f)) return GF_ERR_BAD_DESC;
+  // r == 1: patches of one pixel (x_u is x, m_u the mask itself)
+  return dev(launch_pool_mask(x, x_u, m_u, (long)g.N * g.Ci, g.H, g.W, g.rx, hi, g.dtype,
+                              static_cast<hipStream_t>(stream)));
+}
+
 gf_status gf_filter_grad_snr(const gf_conv_desc* desc, const void* g_y, void* gy_u, double* stats,
                              void* ws, size_t ws_bytes, void* stream) {
   Geom g;
@@ -291,15 +304,34 @@ gf_status gf_filter_grad_snr(const gf_conv_desc* desc, const void* g_y, void* gy
                                  static_cast<float*>(ws), stats, static_cast<hipStream_t>(stream)));
 }
 
+// *mask_done: the launches have already multiplied the reduced g_x by mask_u
+static gf_status chained_body(const Geom& g, const void* gy_u, const void* x_u, const void* w, float* g_w,
+                              void* g_x, int reduced_out, const void* mask_u, bool* mask_done, void* ws,
+                              size_t ws_bytes, void* stream);
+
 gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const void* x_u,
-                              const void* w, float* g_w, void* g_x, int reduced_out, void* ws,
-                              size_t ws_bytes, void* stream) {
+                              const void* w, float* g_w, void* g_x, int reduced_out, const void* mask_u,
+                              void* ws, size_t ws_bytes, void* stream) {
   Geom g;
   gf_status rc = make_geom(desc, &g);
   if (rc) return rc;
   if (!gy_u || !x_u || !w || !g_w || !g_x) return GF_ERR_NULL;
-  if (!aligned16(gy_u) || !aligned16(x_u) || !aligned16(w) || !aligned16(g_w) || !aligned16(g_x))
+  if (!aligned16(gy_u) || !aligned16(x_u) || !aligned16(w) || !aligned16(g_w) || !aligned16(g_x) ||
+      !aligned16(mask_u))
     return GF_ERR_UNSUPPORTED;
+  // the mask fraction exists on the patch grid only: a full-resolution g_x cannot take it
+  if (mask_u && g.r > 1 && !reduced_out) return GF_ERR_UNSUPPORTED;
+  bool mask_done = false;
+  rc = chained_body(g, gy_u, x_u, w, g_w, g_x, reduced_out, mask_u, &mask_done, ws, ws_bytes, stream);
+  if (rc || !mask_u || mask_done) return rc;
+  const long n = g.r == 1 ? (long)g.N * g.Ci * g.H * g.W : (long)g.N * g.Ci * g.P;
+  return dev(launch_mask_mul(g_x, mask_u, n, g.dtype, static_cast<hipStream_t>(stream)));
+}
+
+static gf_status chained_body(const Geom& g, const void* gy_u, const void* x_u, const void* w, float* g_w,
+                              void* g_x, int reduced_out, const void* mask_u, bool* mask_done, void* ws,
+                              size_t ws_bytes, void* stream) {
+  gf_status rc;
   size_t off_i = 0;
   rc = check_ws(ws_chained(g, &off_i), ws, ws_bytes);
   if (rc) return rc;
@@ -314,14 +346,17 @@ gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const 
   }
   if (reduced_out && is_depthwise_layer(g)) {  // one pass over gy_u and x_u
     float* part = reinterpret_cast<float*>(wsb);
-    rc = dev(launch_dw_chain(g, x_u, gy_u, w, part, g_x, st));
+    rc = dev(launch_dw_chain(g, x_u, gy_u, w, part, g_x, mask_u, st));
+    *mask_done = true;
     if (rc) return rc;
     return dev(launch_finalize(part, g_w, g.Ci, g.N, g.KK, scale, st));
   }
   if (mfma_s3s4_ok(g, reduced_out != 0)) {  // dense: both contractions in one launch
     float* part = reinterpret_cast<float*>(wsb);
     int nzs = 0;
-    rc = dev(launch_mfma_s3s4(g, x_u, gy_u, w, wsb + off_i, part, &nzs, g_x, st, false, reduced_out != 0));
+    rc = dev(launch_mfma_s3s4(g, x_u, gy_u, w, wsb + off_i, part, &nzs, g_x, st, false, reduced_out != 0,
+                              reduced_out ? mask_u : nullptr));
+    *mask_done = reduced_out != 0;
     if (rc) return rc;
     return dev(launch_finalize(part, g_w, g.Co * g.Ci, nzs, g.KK, scale, st));
   }

@@ -127,8 +127,8 @@ __global__ __launch_bounds__(kThreads) void dw_dot_vec_k(const T* xu, const T* g
 // ---------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(kThreads) void dw_chain_k(const T* xu, const T* gyu, const T* w, float* part,
-                                                      T* gxu, int planes, int P, int L, int C, int KK,
-                                                      float scalar) {
+                                                      T* gxu, const T* mask, int planes, int P, int L, int C,
+                                                      int KK, float scalar) {
   const int gid = blockIdx.x * kThreads + threadIdx.x;
   const int plane = gid / L;
   const int lane = gid - plane * L;
@@ -137,11 +137,14 @@ __global__ __launch_bounds__(kThreads) void dw_chain_k(const T* xu, const T* gyu
     const T* a = xu + (long)plane * P;
     const T* b = gyu + (long)plane * P;
     T* o = gxu + (long)plane * P;
+    const T* mk = mask ? mask + (long)plane * P : nullptr;
     const float sc = scalar * kernel_sum_of(w, plane % C, KK);
     for (int p = lane; p < P; p += L) {
       const float gv = to_f32(b[p]);
       acc += to_f32(a[p]) * gv;
-      o[p] = from_f32<T>(gv * sc);
+      T v = from_f32<T>(gv * sc);
+      if (mk) v = from_f32<T>(to_f32(v) * to_f32(mk[p]));   // the rounded value times the mask fraction
+      o[p] = v;
     }
   }
   for (int m = L >> 1; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
@@ -713,7 +716,7 @@ hipError_t launch_gf_bwd_input(const Geom& g, const void* gy_u, const void* w, v
 // Depthwise layer of a chain: partial dot products [N, C] and the reduced input gradient in one
 // launch (then launch_finalize with nz = N).
 hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, const void* w, float* part,
-                           void* g_xu, hipStream_t st) {
+                           void* g_xu, const void* mask_u, hipStream_t st) {
   const int planes = g.N * g.Ci;
   const int L = dw_lanes(g.P);
   const int blocks = cdiv((long)planes * L, kThreads);
@@ -721,11 +724,13 @@ hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, con
   if (g.dtype == GF_BF16)
     hipLaunchKernelGGL(dw_chain_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const bf16_t*>(x_u),
                        static_cast<const bf16_t*>(gy_u), static_cast<const bf16_t*>(w), part,
-                       static_cast<bf16_t*>(g_xu), planes, g.P, L, g.Ci, g.KK, scalar);
+                       static_cast<bf16_t*>(g_xu), static_cast<const bf16_t*>(mask_u), planes, g.P, L, g.Ci, g.KK,
+                       scalar);
   else
     hipLaunchKernelGGL(dw_chain_k<float>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const float*>(x_u),
                        static_cast<const float*>(gy_u), static_cast<const float*>(w), part,
-                       static_cast<float*>(g_xu), planes, g.P, L, g.Ci, g.KK, scalar);
+                       static_cast<float*>(g_xu), static_cast<const float*>(mask_u), planes, g.P, L, g.Ci, g.KK,
+                       scalar);
   return hipGetLastError();
 }
 

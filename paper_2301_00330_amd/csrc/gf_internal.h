@@ -136,6 +136,13 @@ long patch_reduce_max_blocks(long planes, int H, int W, int q);
 hipError_t launch_filter_stats(const void* g_y, void* gy_u, long planes, int H, int W, int q, int dtype,
                                float* part, double* stats, hipStream_t st);
 
+// S0 with the mask fraction: x_u as launch_patch_reduce(sum), m_u[patch] = share of the patch's
+// in-bounds elements with 0 < x < hi (storage type)
+hipError_t launch_pool_mask(const void* x, void* x_u, void* m_u, long planes, int H, int W, int q, float hi,
+                            int dtype, hipStream_t st);
+// dst[e] = dst[e] * m[e] (storage type, fp32 product rounded once)
+hipError_t launch_mask_mul(void* dst, const void* m, long n, int dtype, hipStream_t st);
+
 // S2: wsum[co, cl] = sum over taps of w[co, cl, :, :], fp32.
 hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int dtype,
                              hipStream_t st);
@@ -173,16 +180,17 @@ bool onepass_ok(const Geom& g, int* nz);
 hipError_t launch_onepass(const Geom& g, const void* g_y, const void* x_u, const void* w, void* gy_u,
                           void* g_x, float* part, hipStream_t st);
 
-// both gradients of a dense layer in one launch (then launch_finalize on `part`, nz slabs)
+// both gradients of a dense layer in one launch (then launch_finalize on `part`, nz slabs);
+// mask_u: with `reduced`, the reduced input gradient is multiplied by this map of the same shape
 // With `reduced` the input gradient is written as the reduced map [N, Ci, P] instead of g_x.
 bool mfma_s3s4_ok(const Geom& g, bool reduced = false);
 hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
                             void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st,
-                            bool wsum_ready = false, bool reduced = false);
+                            bool wsum_ready = false, bool reduced = false, const void* mask_u = nullptr);
 // depthwise layer of a chain of filtered layers (gf_filtered.hip): partials [N, C] + reduced g_x
 bool is_depthwise_layer(const Geom& g);
 hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, const void* w, float* part,
-                           void* g_xu, hipStream_t st);
+                           void* g_xu, const void* mask_u, hipStream_t st);
 // true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
 bool mfma_dgrad_writes_full(const Geom& g);
 

@@ -294,6 +294,7 @@ struct DgradMfmaArgs {
   const void* gyu;
   const void* wt;   // [Co][Ci] in the storage type: the 1x1 kernel itself or the rounded kernel sum
   void* dst;        // [N, Ci, P] in the storage type
+  const void* mask; // nullable, [N, Ci, P]: the reduced map is multiplied by it (rounded value times mask, rounded)
   int Ci, Co, P, Jtot;
   float scale;
   FastDiv d_p;
@@ -626,16 +627,29 @@ __device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* 
     const int row = s / VPR, vi = s - row * VPR;
     const int ci = m0 + row, j = j0 + vi * VE;
     if (ci >= a.Ci || j >= jend) continue;
+    const T* mask = static_cast<const T*>(a.mask);
     if (VEC) {
       const int n = (int)a.d_p.div((uint32_t)j);
       const int p = j - n * a.P;
-      *reinterpret_cast<uint4*>(dst + ((long)n * a.Ci + ci) * a.P + p) =
-          *reinterpret_cast<const uint4*>(Cs + row * SC + vi * VE);
+      const long o = ((long)n * a.Ci + ci) * a.P + p;
+      uint4 v = *reinterpret_cast<const uint4*>(Cs + row * SC + vi * VE);
+      if (mask) {
+        float f[VE], m[VE];
+        Vec16<T>::unpack(v, f);
+        Vec16<T>::unpack(*reinterpret_cast<const uint4*>(mask + o), m);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) f[e] *= m[e];
+        v = Vec16<T>::pack(f);
+      }
+      *reinterpret_cast<uint4*>(dst + o) = v;
     } else {
       for (int e = 0; e < VE && j + e < jend; ++e) {
         const int n = (int)a.d_p.div((uint32_t)(j + e));
         const int p = j + e - n * a.P;
-        dst[((long)n * a.Ci + ci) * a.P + p] = Cs[row * SC + vi * VE + e];
+        const long o = ((long)n * a.Ci + ci) * a.P + p;
+        T v = Cs[row * SC + vi * VE + e];
+        if (mask) v = from_f32<T>(to_f32(v) * to_f32(mask[o]));
+        dst[o] = v;
       }
     }
   }
@@ -1048,6 +1062,7 @@ static hipError_t dgrad_t(const Geom& g, const void* gy_u, const void* w, void* 
   a.gyu = gy_u;
   a.wt = wt;
   a.dst = dst;
+  a.mask = nullptr;
   a.Ci = g.Ci;
   a.Co = g.Co;
   a.P = g.P;
@@ -1171,7 +1186,8 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
 
 template <class T>
 static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const void* w, void* wsum_t,
-                         float* part, int* nz_out, void* g_x, hipStream_t st, bool wsum_ready, bool reduced) {
+                         float* part, int* nz_out, void* g_x, hipStream_t st, bool wsum_ready, bool reduced,
+                         const void* mask_u) {
   const T* wt = nullptr;
   if (wsum_ready && g.KK > 1) {
     wt = static_cast<const T*>(wsum_t);  // formed by an earlier launch of the same call
@@ -1189,7 +1205,7 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
   wa.d_p = FastDiv((uint32_t)g.P);
   *nz_out = nz;
   DgradMfmaArgs da;
-  da.gyu = gy_u; da.wt = wt; da.dst = nullptr;
+  da.gyu = gy_u; da.wt = wt; da.dst = nullptr; da.mask = nullptr;
   da.Ci = g.Ci; da.Co = g.Co; da.P = g.P; da.Jtot = g.N * g.P;
   da.scale = 1.f / ((float)g.s * (float)g.s);
   da.d_p = FastDiv((uint32_t)g.P);
@@ -1199,6 +1215,7 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
   da.N = g.N; da.veca = 1; da.flatb = 0;
   if (reduced) {  // reduced map out, as in dgrad_t
     da.dst = g_x;
+    da.mask = mask_u;
     da.full = nullptr;
     if (g.P % Mma<T>::VE != 0) {
       da.flatb = 1;
@@ -1221,10 +1238,10 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
 
 hipError_t launch_mfma_s3s4(const Geom& g, const void* x_u, const void* gy_u, const void* w,
                             void* wsum_t, float* part, int* nz_out, void* g_x, hipStream_t st,
-                            bool wsum_ready, bool reduced) {
+                            bool wsum_ready, bool reduced, const void* mask_u) {
   if (g.dtype == GF_BF16)
-    return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready, reduced);
-  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready, reduced);
+    return s3s4_t<bf16_t>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready, reduced, mask_u);
+  return s3s4_t<float>(g, x_u, gy_u, w, wsum_t, part, nz_out, g_x, st, wsum_ready, reduced, mask_u);
 }
 
 hipError_t launch_mfma_dgrad(const Geom& g, const void* gy_u, const void* w, void* wsum_t, void* dst,

@@ -18,6 +18,8 @@ namespace gf {
 namespace {
 
 constexpr int kThreads = 256;
+// what a reduction launch produces beside the patch sums / means
+constexpr int kPlain = 0, kStats = 1, kMask = 2;
 constexpr int kLdsBudget = 32 * 1024;  // per block: 5 blocks fit a CU's 160 KB
 constexpr int kLdsMax = 64 * 1024;
 
@@ -36,8 +38,11 @@ struct ReduceArgs {
   const void* ks_w;
   void* ks_out;
   int ks_pairs, ks_KK, ks_block0;
-  // noise figures of the filter (STATS kernels): per-block partial sums {sum v^2, sum (v - patch mean)^2}
+  // noise figures of the filter (kStats kernels): per-block partial sums {sum v^2, sum (v - patch mean)^2}
   float2* stats_part;
+  // kMask kernels: out2[patch] = fraction of the patch's in-bounds elements with 0 < v < mask_hi
+  void* out2;
+  float mask_hi;
 };
 
 // Fixed-order sum over the block of two floats per lane; block 0's lane 0 ... every block's
@@ -70,8 +75,9 @@ __device__ __forceinline__ bool ksum_side_job(const ReduceArgs& a) {
 // ---------------------------------------------------------------------------
 // rows kernel: requires W % max(VE, Q) == 0 and (W * sizeof(T)) % 16 == 0
 // ---------------------------------------------------------------------------
-template <class T, int Q, int U, bool STATS = false>
+template <class T, int Q, int U, int MODE = kPlain>
 __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
+  constexpr bool STATS = MODE == kStats;
   if (ksum_side_job<T>(a)) return;
   __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
   float energy = 0.f, noise = 0.f;
@@ -150,6 +156,27 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
           }
         }
     }
+    if constexpr (MODE == kMask) {  // second pass over the registers: how many elements pass a gradient
+      T frac[NOUT];
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) {
+        float cnt = 0.f;
+#pragma unroll
+        for (int i = 0; i < Q; ++i)
+#pragma unroll
+          for (int j = 0; j < Q; ++j) {
+            const int e = o * Q + j;
+            float f[VE];
+            Vec16<T>::unpack(v[u][i][e / VE], f);
+            const float val = f[e % VE];
+            cnt += (i < rows[u] && val > 0.f && val < a.mask_hi) ? 1.f : 0.f;
+          }
+        frac[o] = from_f32<T>(cnt / (float)(rows[u] * Q));
+      }
+      T* d2 = static_cast<T*>(a.out2) + (long)strip[u] * a.Wp + col[u] * NOUT;
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) d2[o] = frac[o];
+    }
     T* dst = out + (long)strip[u] * a.Wp + col[u] * NOUT;
     if constexpr (NOUT * sizeof(T) == 8) {
       store_stream8(dst, *reinterpret_cast<const uint2*>(res));
@@ -166,8 +193,9 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
 // ---------------------------------------------------------------------------
 // LDS kernel: any shape whose strip fits the staging buffer
 // ---------------------------------------------------------------------------
-template <class T, int QT, bool STATS = false>  // QT: compile-time patch size, 0 = run-time
+template <class T, int QT, int MODE = kPlain>  // QT: compile-time patch size, 0 = run-time
 __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
+  constexpr bool STATS = MODE == kStats;
   if (ksum_side_job<T>(a)) return;
   __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
   float energy = 0.f, noise = 0.f;
@@ -237,6 +265,18 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
       }
     if (a.mean) acc = acc / (float)(ch * cw);
     out[s0 * a.Wp + lo] = from_f32<T>(acc);
+    if constexpr (MODE == kMask) {
+      float cnt = 0.f;
+#pragma unroll
+      for (int i = 0; i < q; ++i)
+#pragma unroll
+        for (int j = 0; j < q; ++j) {
+          const bool ok = i < ch && j < cw;
+          const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
+          cnt += (ok && val > 0.f && val < a.mask_hi) ? 1.f : 0.f;
+        }
+      static_cast<T*>(a.out2)[s0 * a.Wp + lo] = from_f32<T>(cnt / (float)(ch * cw));
+    }
     if constexpr (STATS) {
 #pragma unroll
       for (int i = 0; i < q; ++i)
@@ -254,8 +294,9 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
 }
 
 // Fallback without LDS for strips too large to stage: one lane per patch.
-template <class T, bool STATS = false>
+template <class T, int MODE = kPlain>
 __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
+  constexpr bool STATS = MODE == kStats;
   if (ksum_side_job<T>(a)) return;
   __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
   float energy = 0.f, noise = 0.f;
@@ -276,6 +317,15 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
       for (int j = 0; j < cw; ++j) acc += to_f32(p[(long)i * a.W + j]);
     if (a.mean) acc = acc / (float)(ch * cw);
     out[o] = from_f32<T>(acc);
+    if constexpr (MODE == kMask) {
+      float cnt = 0.f;
+      for (int i = 0; i < ch; ++i)
+        for (int j = 0; j < cw; ++j) {
+          const float val = to_f32(p[(long)i * a.W + j]);
+          cnt += (val > 0.f && val < a.mask_hi) ? 1.f : 0.f;
+        }
+      static_cast<T*>(a.out2)[o] = from_f32<T>(cnt / (float)(ch * cw));
+    }
     if constexpr (STATS) {
       for (int i = 0; i < ch; ++i)
         for (int j = 0; j < cw; ++j) {
@@ -328,7 +378,9 @@ hipError_t launch_rows(ReduceArgs& a, hipStream_t st, int* nblocks) {
   const int blocks = cdiv(a.total_items, kThreads * U);
   a.ks_block0 = blocks;
   if (a.stats_part)
-    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, kStats>), dim3(blocks), dim3(kThreads), 0, st, a);
+  else if (a.out2)
+    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, kMask>), dim3(blocks), dim3(kThreads), 0, st, a);
   else
     hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
   *nblocks = blocks;
@@ -359,7 +411,9 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
     if (blocks > 65536) blocks = 65536;
     a.ks_block0 = blocks;
     if (a.stats_part)
-      hipLaunchKernelGGL((patch_reduce_direct<T, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+      hipLaunchKernelGGL((patch_reduce_direct<T, kStats>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else if (a.out2)
+      hipLaunchKernelGGL((patch_reduce_direct<T, kMask>), dim3(blocks), dim3(kThreads), 0, st, a);
     else
       hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
     *nblocks = blocks;
@@ -379,11 +433,21 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
   if (a.stats_part) {
     const dim3 sgrid(blocks);
     if (a.q == 2)
-      hipLaunchKernelGGL((patch_reduce_lds<T, 2, true>), sgrid, dim3(kThreads), lds, st, a);
+      hipLaunchKernelGGL((patch_reduce_lds<T, 2, kStats>), sgrid, dim3(kThreads), lds, st, a);
     else if (a.q == 4)
-      hipLaunchKernelGGL((patch_reduce_lds<T, 4, true>), sgrid, dim3(kThreads), lds, st, a);
+      hipLaunchKernelGGL((patch_reduce_lds<T, 4, kStats>), sgrid, dim3(kThreads), lds, st, a);
     else
-      hipLaunchKernelGGL((patch_reduce_lds<T, 0, true>), sgrid, dim3(kThreads), lds, st, a);
+      hipLaunchKernelGGL((patch_reduce_lds<T, 0, kStats>), sgrid, dim3(kThreads), lds, st, a);
+    return hipGetLastError();
+  }
+  if (a.out2) {
+    const dim3 sgrid(blocks);
+    if (a.q == 2)
+      hipLaunchKernelGGL((patch_reduce_lds<T, 2, kMask>), sgrid, dim3(kThreads), lds, st, a);
+    else if (a.q == 4)
+      hipLaunchKernelGGL((patch_reduce_lds<T, 4, kMask>), sgrid, dim3(kThreads), lds, st, a);
+    else
+      hipLaunchKernelGGL((patch_reduce_lds<T, 0, kMask>), sgrid, dim3(kThreads), lds, st, a);
     return hipGetLastError();
   }
   const dim3 grid(blocks + cdiv(a.ks_pairs, kThreads));
@@ -425,6 +489,35 @@ hipError_t launch_filter_stats(const void* g_y, void* gy_u, long planes, int H, 
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(stats_final_k, dim3(1), dim3(kFinalThreads), 0, st, a.stats_part, blocks, stats);
   return hipGetLastError();
+}
+
+template <class T>
+__global__ __launch_bounds__(kThreads) void mask_mul_k(T* dst, const T* m, long n) {
+  const long e = (long)blockIdx.x * kThreads + threadIdx.x;
+  if (e < n) dst[e] = from_f32<T>(to_f32(dst[e]) * to_f32(m[e]));
+}
+
+hipError_t launch_mask_mul(void* dst, const void* m, long n, int dtype, hipStream_t st) {
+  const dim3 grid((unsigned)((n + kThreads - 1) / kThreads)), block(kThreads);
+  if (dtype == GF_BF16)
+    hipLaunchKernelGGL(mask_mul_k<bf16_t>, grid, block, 0, st, static_cast<bf16_t*>(dst), static_cast<const bf16_t*>(m), n);
+  else
+    hipLaunchKernelGGL(mask_mul_k<float>, grid, block, 0, st, static_cast<float*>(dst), static_cast<const float*>(m), n);
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_mask(const void* x, void* x_u, void* m_u, long planes, int H, int W, int q, float hi,
+                            int dtype, hipStream_t st) {
+  ReduceArgs a = {};
+  int blocks = 0;
+  a.in = x; a.out = x_u; a.out2 = m_u; a.mask_hi = hi; a.H = H; a.W = W; a.q = q;
+  a.Hp = cdiv(H, q); a.Wp = cdiv(W, q);
+  a.total_in = (int)(planes * H * W);
+  a.total_strips = (int)(planes * a.Hp);
+  a.mean = 0;
+  a.d_hp = FastDiv((uint32_t)a.Hp);
+  a.d_wp = FastDiv((uint32_t)a.Wp);
+  return dtype == GF_BF16 ? launch_t<bf16_t>(a, st, &blocks) : launch_t<float>(a, st, &blocks);
 }
 
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,

@@ -80,6 +80,17 @@ def pool_activation(d: B.ConvDesc, x: torch.Tensor, out: torch.Tensor | None = N
     return out
 
 
+def pool_activation_mask(d: B.ConvDesc, x: torch.Tensor, hi: float = float("inf")):
+    """(x_u, m_u): patch sums of x and the share of each patch with 0 < x < hi (the gradient mask of the
+    ReLU / clipped ReLU that produced x, averaged over the patch)."""
+    s = shapes(d)
+    _check(x, d, s["x"], "x")
+    x_u = torch.empty(s["x_u"], dtype=x.dtype, device=x.device)
+    m_u = torch.empty(s["x_u"], dtype=x.dtype, device=x.device)
+    B.gf_pool_activation_mask(d, B.ptr(x), hi, B.ptr(x_u), B.ptr(m_u), _stream())
+    return x_u, m_u
+
+
 def filter_grad(d: B.ConvDesc, g_y: torch.Tensor, out: torch.Tensor | None = None):
     s = shapes(d)
     _check(g_y, d, s["g_y"], "g_y")
@@ -139,17 +150,20 @@ def filter_grad_snr(d: B.ConvDesc, g_y: torch.Tensor, ws: Workspace | None = Non
 
 
 def conv_bwd_chained(d: B.ConvDesc, gy_u: torch.Tensor, x_u: torch.Tensor, w: torch.Tensor,
-                     reduced_out: bool = True, ws: Workspace | None = None):
-    """(g_w, g_x) from one call of gf_conv_bwd_chained; g_x is the reduced map unless reduced_out is False."""
+                     reduced_out: bool = True, mask_u: torch.Tensor | None = None, ws: Workspace | None = None):
+    """(g_w, g_x) from one call of gf_conv_bwd_chained; g_x is the reduced map unless reduced_out is False.
+    mask_u (from pool_activation_mask of this layer's input) is multiplied into the reduced g_x."""
     s = shapes(d)
     _check(gy_u, d, s["gy_u"], "gy_u")
     _check(x_u, d, s["x_u"], "x_u")
     _check(w, d, s["w"], "w")
     g_w = torch.empty(s["w"], dtype=torch.float32, device=gy_u.device)
     g_x = torch.empty(s["g_x_u"] if reduced_out else s["x"], dtype=gy_u.dtype, device=gy_u.device)
+    if mask_u is not None:
+        _check(mask_u, d, tuple(g_x.shape), "mask_u")
     p, n = _ws(gy_u, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_CHAINED))
-    B.gf_conv_bwd_chained(d, B.ptr(gy_u), B.ptr(x_u), B.ptr(w), B.ptr(g_w), B.ptr(g_x), reduced_out, p, n,
-                          _stream())
+    B.gf_conv_bwd_chained(d, B.ptr(gy_u), B.ptr(x_u), B.ptr(w), B.ptr(g_w), B.ptr(g_x), reduced_out,
+                          0 if mask_u is None else B.ptr(mask_u), p, n, _stream())
     return g_w, g_x
 
 

@@ -86,16 +86,31 @@ def test_pointer_and_workspace_errors(lib):
     # the chained and the fused entry: null pointers, then the workspace, before anything is enqueued
     for reduced in (True, False):
         with pytest.raises(B.GfError) as ei:
-            B.gf_conv_bwd_chained(d, 0, FAKE, FAKE, FAKE, FAKE, reduced, FAKE, 1 << 30)
+            B.gf_conv_bwd_chained(d, 0, FAKE, FAKE, FAKE, FAKE, reduced, 0, FAKE, 1 << 30)
         assert ei.value.status == B.GF_ERR_NULL
         need_c = B.gf_workspace_bytes(d, B.GF_OP_BWD_CHAINED)
         assert need_c > 0
         with pytest.raises(B.GfError) as ei:
-            B.gf_conv_bwd_chained(d, FAKE, FAKE, FAKE, FAKE, FAKE, reduced, FAKE, need_c - 1)
+            B.gf_conv_bwd_chained(d, FAKE, FAKE, FAKE, FAKE, FAKE, reduced, 0, FAKE, need_c - 1)
         assert ei.value.status == B.GF_ERR_WORKSPACE
         with pytest.raises(B.GfError) as ei:
-            B.gf_conv_bwd_chained(d, FAKE, FAKE + 2, FAKE, FAKE, FAKE, reduced, FAKE, need_c)
+            B.gf_conv_bwd_chained(d, FAKE, FAKE + 2, FAKE, FAKE, FAKE, reduced, 0, FAKE, need_c)
         assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    # a mask on a full-resolution output of a filtered layer is refused; so is a misaligned mask
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_chained(d, FAKE, FAKE, FAKE, FAKE, FAKE, False, FAKE, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_chained(d, FAKE, FAKE, FAKE, FAKE, FAKE, True, FAKE + 4, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    # masked activation pooling
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation_mask(d, FAKE, 6.0, FAKE, 0)
+    assert ei.value.status == B.GF_ERR_NULL
+    for bad_hi in (0.0, -1.0, float("nan")):
+        with pytest.raises(B.GfError) as ei:
+            B.gf_pool_activation_mask(d, FAKE, bad_hi, FAKE, FAKE)
+        assert ei.value.status == B.GF_ERR_BAD_DESC
     # the filter with its noise figures
     need_s = B.gf_workspace_bytes(d, B.GF_OP_FILTER_SNR)
     assert need_s >= 8

@@ -154,6 +154,59 @@ def test_noise_figures_bit_exact_on_integers(oracle, H, W, r, dtype):
     assert torch.equal(gy_u.cpu(), const[:, :, ::r, ::r])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("hi", [float("inf"), 6.0])
+@pytest.mark.parametrize("case", REDUCE_CASES + [(2, 3, 9, 9, 1, 1), (4, 24, 56, 56, 2, 1)])
+def test_pool_with_mask_fraction(oracle, case, dtype, hi):
+    """gf_pool_activation_mask: x_u bit-identical to gf_pool_activation, m_u = the share of each patch
+    through which a (clipped) ReLU passes a gradient, against the oracle on the same rounded x."""
+    N, C, H, W, r, s = case
+    d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+    x = (randn((N, C, H, W), 21, dtype) * 4.0 + 2.0).clamp(min=0.0)     # a ReLU output with values beyond 6
+    xg = x.cuda()
+    x_u, m_u = T.pool_activation_mask(d, xg, hi)
+    plain = T.pool_activation(d, xg)
+    torch.cuda.synchronize()
+    assert torch.equal(x_u, plain)
+    _, ref_m = oracle.pool_activation_mask(odesc(oracle, d), to64(x), hi)
+    assert tuple(m_u.shape) == ref_m.shape
+    # counts over at most 64 pixels divided by the in-bounds count: one rounding of an exact quotient
+    assert np.abs(to64(m_u) - ref_m).max() <= (4e-3 if dtype == "bf16" else 1e-6)
+    pow2 = (r * s) in (1, 2, 4, 8) and H % (r * s) == 0 and W % (r * s) == 0
+    if pow2:
+        assert np.array_equal(to64(m_u), ref_m)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [(3, 24, 40, 12, 12, 1, 1, 0, 1, 1, 2), (4, 48, 48, 12, 12, 3, 1, 1, 1, 48, 2),
+                                  (2, 32, 48, 14, 14, 3, 2, 1, 1, 1, 2), (2, 16, 16, 24, 24, 3, 1, 6, 6, 1, 4),
+                                  (3, 12, 18, 10, 10, 3, 1, 1, 1, 3, 2), (3, 24, 144, 56, 56, 1, 1, 0, 1, 1, 2)])
+def test_chained_entry_with_mask(oracle, case, dtype):
+    """A layer above a ReLU in a chain: the reduced input gradient times the mask fraction is what the
+    lower layer's filter would make of the masked full-resolution gradient (oracle: exactly that)."""
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, r, dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = (randn((N, Ci, H, W), 61, dtype) * 2.0 + 0.5).clamp(min=0.0)
+    w = randn((Co, Ci // g, K, K), 62, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    gyu = randn((N, Co, Hp, Wp), 63, dtype, scale=1e-2)
+    x_u, m_u = T.pool_activation_mask(d, x.cuda())
+    g_w, g_xu = T.conv_bwd_chained(d, gyu.cuda(), x_u, w.cuda(), reduced_out=True, mask_u=m_u)
+    g_w0, g_xu0 = T.conv_bwd_chained(d, gyu.cuda(), x_u, w.cuda(), reduced_out=True)
+    torch.cuda.synchronize()
+    assert torch.equal(g_w, g_w0)
+    # oracle: full-resolution gradient of the upper layer, masked by the ReLU, filtered by the layer below
+    gx_full = oracle.bwd_input(od, to64(gyu), to64(w))
+    masked = gx_full * (to64(x) > 0)
+    lower = oracle.Desc(N=N, C_in=1, C_out=Ci, H_in=H, W_in=W, K_h=1, K_w=1, r=r * s)
+    ref = oracle.filter_grad(lower, masked)
+    assert rel_err(g_xu, ref) <= TOL[dtype]
+    # and it is the unmasked result times the fraction, rounded once
+    prod = (g_xu0.float() * m_u.float()).to(g_xu0.dtype)
+    assert torch.equal(g_xu, prod)
+
+
 def test_r1_reductions_are_copies():
     d = mk(2, 3, 4, 14, 14, K=3, s=2, p=1, r=1, dtype="bf16")
     x = randn((2, 3, 14, 14), 1, "bf16").cuda()
