@@ -162,9 +162,10 @@ gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const vo
  * of Fig. 2(a)): the gradient filter on g_y (Eq. 2), then the weight gradient
  * (Eq. 5) from the stored x_u and the input gradient (Eq. 3) from w.  Same results
  * as gf_filter_grad + gf_conv_bwd_weight + gf_conv_bwd_input: gy_u and g_x bit for
- * bit, g_w up to the order of the fp32 partial sums.  For depthwise stride-1 layers
- * it is a single pass over g_y; dense layers run the filter and then both
- * contractions in one launch; other layers run the three steps back to back.
+ * bit, g_w up to the order of the fp32 partial sums.  For depthwise layers and for
+ * pointwise stride-1 layers with at most 32 input channels it is a single pass over
+ * g_y; other dense layers run the filter and then both contractions in one launch;
+ * the remaining layers run the three steps back to back.
  * gy_u may be NULL if the caller does not want the filtered gradient itself.  With r == 1, x_u is x and
  * the call is vanilla back-propagation. */
 gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const void* x_u,

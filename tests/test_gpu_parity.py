@@ -549,6 +549,28 @@ def test_config2_full_size(oracle, li, dtype):
     check_layer_full(oracle, cfg, cfg.layers[li], dtype, 2)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("li", [0, 1, 2])
+def test_config2_full_size_one_call(oracle, li, dtype):
+    """The call bench.py times (gf_conv_bwd_filtered at N = 32): one-pass kernels for the expand and the
+    depthwise layer, filter + merged launch for the project layer, against the oracle end to end."""
+    cfg = WL.CONFIGS[2]
+    layer = cfg.layers[li]
+    d = T.desc_for(layer, cfg.N, 2, dtype)
+    od = odesc(oracle, d)
+    x, w, gy = WL.make_inputs(cfg, layer, dtype)
+    x_u = T.pool_activation(d, x.cuda())
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=True)
+    g_w2, g_x2, none = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(g_x, g_x2) and torch.equal(g_w, g_w2)
+    ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    tol = TOL[dtype]
+    assert rel_err(gy_u, ref_gyu) <= tol, "gy_u"
+    assert rel_err(g_w, ref_gw) <= tol, "g_w"
+    assert rel_err(g_x, ref_gx) <= tol, "g_x"
+
+
 @pytest.mark.parametrize("r", [2, 4])
 @pytest.mark.parametrize("li", [0, 1, 2])
 def test_config3_full_size(oracle, li, r):
