@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) idx[k] = min(v + k * kThreads, nvec - 1);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) rg[k] = src[idx[k]];
+    for (int k = 0; k < 4; ++k) rg[k] = load_stream16(src + idx[k]);
 #pragma unroll
     for (int k = 0; k < 4; ++k) dst[idx[k]] = rg[k];
   }
