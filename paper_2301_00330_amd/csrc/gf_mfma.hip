@@ -44,6 +44,27 @@ __device__ __forceinline__ uint4 load_cols(const T* base, long img_stride, int j
     const uint4 v = *reinterpret_cast<const uint4*>(base + (long)n * img_stride + p);
     return j < jtot ? v : make_uint4(0, 0, 0, 0);
   }
+  if (P >= VE) {
+    // Branch-free, with element-aligned 16-byte loads that are always issued (so that a lane's loads
+    // stay in flight together): the part of the vector that lies in image n comes from a load
+    // pulled back into that image and shifted; the part that lies in image n + 1 (only when the
+    // vector crosses the boundary) from a load at the start of the next image, shifted the other
+    // way; elements past jtot are cleared.
+    const int jc = min(j, jtot - 1);
+    const int n = (int)d_p.div((uint32_t)jc);
+    const int p = jc - n * P;
+    const int pa = min(p, P - VE);
+    const int k1 = min(VE, P - p);                         // elements that belong to image n
+    const int nlast = (int)d_p.div((uint32_t)(jtot - 1));  // last image this row holds columns of
+    const uint4 va = load_vec<T>(base + (long)n * img_stride + pa);
+    const uint4 vb = load_vec<T>(base + (long)min(n + 1, nlast) * img_stride);
+    const uint4 a = realign<T>(va, p - pa);
+    const uint4 b = realign<T>(vb, -k1);
+    uint4 v = make_uint4(a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w);
+    const int keep = jtot - j;                             // elements of the vector before jtot
+    if (keep < VE) v = keep <= 0 ? make_uint4(0, 0, 0, 0) : realign<T>(realign<T>(v, -(VE - keep)), VE - keep);
+    return v;
+  }
   uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
   for (int e = 0; e < VE; ++e) {
@@ -873,7 +894,7 @@ hipError_t wgrad_launch(WgradMfmaArgs& a, int nz, bool vec, hipStream_t st) {
 // Column tiles of the input-gradient GEMM when neither whole images nor image blocks are used:
 // whole patch rows if the full-resolution store can use them (see DgradMfmaArgs::prt), else BN.
 template <class T>
-void dgrad_column_tiles(DgradMfmaArgs& a, int BN) {
+void dgrad_column_tiles(DgradMfmaArgs& a, int BN, int BM) {
   constexpr int VE = Mma<T>::VE;
   a.prt = 0;
   a.cols_per_tile = BN;
@@ -882,7 +903,15 @@ void dgrad_column_tiles(DgradMfmaArgs& a, int BN) {
   if (per_patch_row > kThreads) return;
   int prt = BN / a.Wp;
   if (prt > kThreads / per_patch_row) prt = kThreads / per_patch_row;
-  while (prt > 0 && (prt * a.Wp) % VE != 0) --prt;   // tiles start on vector boundaries of gy_u
+  // small problems: rather more, narrower tiles than a chip that is mostly idle
+  const long patch_rows = (long)a.Jtot / a.Wp;
+  const long want = patch_rows * cdiv(a.Ci, BM) / 128;
+  if (want < prt) prt = want < 1 ? 1 : (int)want;
+  int up = prt;   // tiles start on vector boundaries of gy_u: the nearest count of patch rows that does
+  while (up <= BN / a.Wp && up <= kThreads / per_patch_row && (up * a.Wp) % VE != 0) ++up;
+  if (up <= BN / a.Wp && up <= kThreads / per_patch_row) prt = up;
+  else
+    while (prt > 0 && (prt * a.Wp) % VE != 0) --prt;
   if (prt < 1) return;
   a.prt = prt;
   a.cols_per_tile = prt * a.Wp;
@@ -891,7 +920,7 @@ void dgrad_column_tiles(DgradMfmaArgs& a, int BN) {
 template <class T, int TM, int TN, int WM, int WN>
 hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
-  if (!a.planes_mode && !a.flatb) dgrad_column_tiles<T>(a, BN);
+  if (!a.planes_mode && !a.flatb) dgrad_column_tiles<T>(a, BN, BM);
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, BM), 1);
   if (vec)
     hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
@@ -951,6 +980,9 @@ int mfma_wgrad_splits(const Geom& g, int* chunks_per_z) {
   const int tiles = cdiv(g.Co, bm) * cdiv(g.Ci, bn);
   int nz = cdiv(1024, tiles);
   if (nz > cdiv(nchunks, 4)) nz = cdiv(nchunks, 4);
+  // ... unless that leaves most of the chip idle (short K, few tiles): then fewer chunks per block
+  const int fill = cdiv(256, tiles);
+  if (nz < fill) nz = fill < nchunks ? fill : nchunks;
   if (nz < 1) nz = 1;
   const int cpz = cdiv(nchunks, nz);
   if (chunks_per_z) *chunks_per_z = cpz;
@@ -993,7 +1025,7 @@ hipError_t launch_mfma_wgrad(const Geom& g, const void* x_u, const void* gy_u, f
 
 template <class T, int BN>
 hipError_t dgrad_ksplit_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
-  if (!a.planes_mode) dgrad_column_tiles<T>(a, BN);
+  if (!a.planes_mode) dgrad_column_tiles<T>(a, BN, 32);
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, 32), 1);
   if (vec)
     hipLaunchKernelGGL((dgrad_ksplit_k<T, BN, true>), grid, dim3(kThreads), 0, st, a);
@@ -1007,7 +1039,8 @@ static bool dgrad_full_ok(const Geom& g) {
   constexpr int VE = Mma<T>::VE;
   const int rx = g.rx;
   if (rx != 2 && rx != 4 && rx != 8) return false;
-  if (g.P % VE != 0 || g.Ci % VE != 0) return false;   // vector loads of the operands
+  if (g.Ci % VE != 0) return false;                     // vector loads of the kernel matrix
+  // (P need not be a vector multiple: gy_u is then read with element-aligned 16-byte loads)
   if (g.W != g.Wp * rx || g.W % VE != 0) return false;  // no ragged patch columns, aligned rows
   if (rx < VE && g.Wp % (VE / rx) != 0) return false;   // a pixel run never leaves its patch row
   return true;
@@ -1155,7 +1188,7 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
       da.ipt = images_per_tile(g, bn, 32);
       da.cols_per_tile = da.ipt * g.P;
     } else {
-      dgrad_column_tiles<T>(da, bn);
+      dgrad_column_tiles<T>(da, bn, 32);
     }
     gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
     const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 32);
@@ -1174,7 +1207,7 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
       hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     return hipGetLastError();
   }
-  dgrad_column_tiles<T>(da, g.Ci <= 32 ? 128 : 64);
+  dgrad_column_tiles<T>(da, g.Ci <= 32 ? 128 : 64, g.Ci <= 32 ? 32 : 64);
   gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
   const int nd = gr.dgx * cdiv(g.Ci, g.Ci <= 32 ? 32 : 64);
   if (g.Ci <= 32)

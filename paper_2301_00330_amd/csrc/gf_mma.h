@@ -35,4 +35,37 @@ __device__ __forceinline__ f32x4 mma16(float a, float b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
+
+// 16 bytes at the natural alignment of one element
+template <class T> struct Unal;
+template <> struct __attribute__((packed, aligned(2))) Unal<bf16_t> { uint32_t w[4]; };
+template <> struct __attribute__((packed, aligned(4))) Unal<float> { uint32_t w[4]; };
+
+// 16 bytes from an element-aligned address.  Loads near the ends of a tensor are issued at an
+// offset clamped into the tensor; realign() then shifts the vector by the difference, and the
+// elements whose own address lies outside the tensor come out as zeros.
+template <class T>
+__device__ __forceinline__ uint4 load_vec(const T* p) {
+  const Unal<T> v = *reinterpret_cast<const Unal<T>*>(p);
+  return make_uint4(v.w[0], v.w[1], v.w[2], v.w[3]);
+}
+
+template <class T>
+__device__ __forceinline__ uint4 realign(const uint4& v, int sh) {  // out[e] = in[e + sh]
+  constexpr int VE = Mma<T>::VE;
+  if (sh == 0) return v;
+  if (sh >= VE || sh <= -VE) return make_uint4(0, 0, 0, 0);
+  uint64_t lo = (uint64_t)v.x | ((uint64_t)v.y << 32), hi = (uint64_t)v.z | ((uint64_t)v.w << 32);
+  int bits = sh * 8 * (int)sizeof(T);  // 0 < |bits| < 128
+  if (bits > 0) {
+    if (bits >= 64) { lo = hi >> (bits - 64); hi = 0; }
+    else { lo = (lo >> bits) | (hi << (64 - bits)); hi >>= bits; }
+  } else {
+    bits = -bits;
+    if (bits >= 64) { hi = lo << (bits - 64); lo = 0; }
+    else { hi = (hi << bits) | (lo >> (64 - bits)); lo <<= bits; }
+  }
+  return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
 }  // namespace gf
