@@ -1157,14 +1157,16 @@ static bool s3s4_ok(const Geom& g, bool reduced) {
   constexpr int VE = Mma<T>::VE;
   if (g.g != 1 || g.Ci % VE != 0) return false;
   if (wgrad_shape(g) == 4 || plain_wgrad_ok(g)) return false;
-  if (reduced) {  // reduced map out: vector columns, or image blocks on both sides
-    if (g.P % VE == 0) return true;
+  if (reduced) {  // reduced map out: vector columns, element-aligned vectors, or image blocks on both sides
+    if (g.P % VE == 0 || g.P > 64) return true;
     return wgrad_flat(g, nullptr) && g.P <= 64 && ((long)g.Co * g.P * sizeof(T)) % 16 == 0;
   }
   const bool runs = dgrad_full_ok<T>(g);
   if (!runs && !dgrad_planes_ok(g)) return false;
-  if (g.P % VE != 0) {  // image-block loaders on both sides
-    if (runs || !wgrad_flat(g, nullptr)) return false;
+  if (g.P % VE != 0) {
+    if (runs) return g.P >= VE;   // element-aligned vector loads of gy_u, pixel-run / patch-row store
+    // plane mode: image-block loaders on both sides
+    if (!wgrad_flat(g, nullptr)) return false;
     if (g.P > 64 || ((long)g.Co * g.P * sizeof(T)) % 16 != 0) return false;
   }
   return true;
@@ -1210,10 +1212,14 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
   dgrad_column_tiles<T>(da, g.Ci <= 32 ? 128 : 64, g.Ci <= 32 ? 32 : 64);
   gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
   const int nd = gr.dgx * cdiv(g.Ci, g.Ci <= 32 ? 32 : 64);
-  if (g.Ci <= 32)
-    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, true, false>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
-  else
-    hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, false>), dim3(gr.nw + nd), dim3(kThreads), 0, st, wa, da, gr);
+  const dim3 grid(gr.nw + nd), block(kThreads);
+  if (g.Ci <= 32) {
+    if (vec) hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, true, false>), grid, block, 0, st, wa, da, gr);
+    else hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, false, false>), grid, block, 0, st, wa, da, gr);
+  } else {
+    if (vec) hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, false>), grid, block, 0, st, wa, da, gr);
+    else hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, false>), grid, block, 0, st, wa, da, gr);
+  }
   return hipGetLastError();
 }
 
@@ -1250,7 +1256,7 @@ static hipError_t s3s4_t(const Geom& g, const void* x_u, const void* gy_u, const
     da.dst = g_x;
     da.mask = mask_u;
     da.full = nullptr;
-    if (g.P % Mma<T>::VE != 0) {
+    if (g.P % Mma<T>::VE != 0 && g.P <= 64) {
       da.flatb = 1;
       da.ipt = images_per_tile(g, 64, 64);
       da.cols_per_tile = da.ipt * g.P;
