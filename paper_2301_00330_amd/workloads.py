@@ -72,7 +72,7 @@ CONFIGS = {
     1: Config(1, "single 3x3 conv", 1, (_c3("conv3x3_16", 16, 16, 16),), ("f32",), (2,), "normal", "normal", 1.0),
     2: Config(2, "MobileNetV2 inverted-residual block @56x56", 32,
               (_pw("expand_24_144", 24, 144, 56), _dw("dw_144", 144, 56), _pw("project_144_24", 144, 24, 56)),
-              ("f32", "bf16"), (2,), "normal", "kaiming", 1e-2, chain=(2, 1, 0), chain_clip=(0.0, 6.0, 6.0)),
+              ("f32", "bf16"), (2, 4), "normal", "kaiming", 1e-2, chain=(2, 1, 0), chain_clip=(0.0, 6.0, 6.0)),
     3: Config(3, "ResNet-18 tail", 64,
               (_c3("conv_256_256@14", 256, 256, 14), _c3("conv_256_512_s2@14", 256, 512, 14, stride=2),
                _c3("conv_512_512@7", 512, 512, 7, count=3)),

@@ -552,13 +552,15 @@ def test_config2_full_size(oracle, li, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("r", [2, 4])
 @pytest.mark.parametrize("li", [0, 1, 2])
-def test_config2_full_size_one_call(oracle, li, dtype):
-    """The call bench.py times (gf_conv_bwd_filtered at N = 32): one-pass kernels for the expand and the
-    depthwise layer, filter + merged launch for the project layer, against the oracle end to end."""
+def test_config2_full_size_one_call(oracle, li, r, dtype):
+    """The call bench.py times (gf_conv_bwd_filtered at N = 32): at r = 2 one-pass kernels for the expand
+    and the depthwise layer, filter + merged launch for the project layer; at r = 4 (P = 196, no vector
+    multiple in bf16) filter + merged launch with element-aligned loads; against the oracle end to end."""
     cfg = WL.CONFIGS[2]
     layer = cfg.layers[li]
-    d = T.desc_for(layer, cfg.N, 2, dtype)
+    d = T.desc_for(layer, cfg.N, r, dtype)
     od = odesc(oracle, d)
     x, w, gy = WL.make_inputs(cfg, layer, dtype)
     x_u = T.pool_activation(d, x.cuda())
