@@ -23,6 +23,8 @@ struct DwExactArgs {
   float* part;   // [N, C, K * K]
   int C, H, W, Hy, Wy, K, s, p, dl;
   int planes, ppb;
+  // stride-1 kernels: the staged operand sits in a zero frame of `halo` pixels (PH x PW per plane)
+  int halo, PH, PW;
   FastDiv d_hw, d_w, d_hwy, d_wy, d_c;
 };
 
@@ -53,6 +55,51 @@ __device__ __forceinline__ T* stage_run(const void* base, long e0, long e1, unsi
     reinterpret_cast<T*>(buf + tail0)[tid] =
         reinterpret_cast<const T*>(reinterpret_cast<const unsigned char*>(src) + tail0)[tid];
   return reinterpret_cast<T*>(buf + (int)(byte0 - a0));
+}
+
+// The same run of whole planes [pl0, pl0 + npl) of an [*, H, W] tensor, but laid out in LDS as
+// [npl][PH][PW] with the plane at row `top`, column `left` of a zero frame, so that the tap loops
+// need no bounds checks.  `buf` must have been cleared (the frame) before the call.
+template <class T>
+__device__ __forceinline__ void stage_padded(const void* base, int pl0, int npl, int H, int W, int top, int left,
+                                             int PH, int PW, const FastDiv& d_hw, const FastDiv& d_w, T* buf,
+                                             int tid) {
+  constexpr int VE = 16 / (int)sizeof(T);
+  const int HW = H * W;
+  const long e0 = (long)pl0 * HW, e1 = e0 + (long)npl * HW;
+  const long byte0 = e0 * (long)sizeof(T), byte1 = e1 * (long)sizeof(T);
+  const long a0 = byte0 & ~15L;
+  const int lead = (int)((byte0 - a0) / (long)sizeof(T));   // elements of the first vector that precede the run
+  const int nvec = (int)((byte1 - a0) >> 4);                // whole vectors that end inside the run
+  const uint4* src = reinterpret_cast<const uint4*>(static_cast<const unsigned char*>(base) + a0);
+  const int count = npl * HW;
+  auto put = [&](int e, T val) {   // e: element index relative to the run
+    const int pl = (int)d_hw.div((uint32_t)e);
+    const int rem = e - pl * HW;
+    const int h = (int)d_w.div((uint32_t)rem);
+    buf[(pl * PH + h + top) * PW + rem - h * W + left] = val;
+  };
+  for (int v = tid; v < nvec; v += 4 * kThreads) {
+    uint4 rg[4];
+    int idx[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) idx[k] = min(v + k * kThreads, nvec - 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) rg[k] = load_stream16(src + idx[k]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (v + k * kThreads >= nvec) continue;
+      const T* el = reinterpret_cast<const T*>(&rg[k]);
+#pragma unroll
+      for (int i = 0; i < VE; ++i) {
+        const int e = idx[k] * VE + i - lead;
+        if (e >= 0) put(e, el[i]);
+      }
+    }
+  }
+  // elements behind the last whole vector (the run ends where the tensor may end)
+  const int tail0 = nvec * VE - lead;
+  if (tid < count - tail0 && tail0 + tid >= 0) put(tail0 + tid, static_cast<const T*>(base)[e0 + tail0 + tid]);
 }
 
 // ---------------------------------------------------------------------------
@@ -132,6 +179,135 @@ __global__ __launch_bounds__(kThreads) void dw_exact_dgrad_k(DwExactArgs a) {
     const int ntail = (span - tail0) / (int)sizeof(T);
     const int efirst = (tail0 - oshift) / (int)sizeof(T);
     if (tid < ntail && efirst + tid >= 0) out[e0 + efirst + tid] = gxs[efirst + tid];
+  }
+}
+
+// stride 1: g_y staged in a zero frame, no bounds checks in the tap loop
+template <class T, int K, bool WAVE>
+__global__ __launch_bounds__(kThreads) void dw_exact_dgrad_s1_k(DwExactArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pl0 = blockIdx.x * a.ppb;
+  const int npl = min(a.ppb, a.planes - pl0);
+  const int HW = a.H * a.W;
+  const int pad_elems = a.ppb * a.PH * a.PW;
+  const int in_bytes = (pad_elems * (int)sizeof(T) + 15) & ~15;
+  T* gys = reinterpret_cast<T*>(smem);
+  for (int i = tid; i < (in_bytes >> 4); i += kThreads) reinterpret_cast<uint4*>(smem)[i] = make_uint4(0, 0, 0, 0);
+  __syncthreads();
+  stage_padded<T>(a.gy, pl0, npl, a.Hy, a.Wy, a.halo, a.halo, a.PH, a.PW, a.d_hwy, a.d_wy, gys, tid);
+  const long obyte0 = (long)pl0 * HW * (long)sizeof(T);
+  const long oa0 = obyte0 & ~15L;
+  const int oshift = (int)(obyte0 - oa0);
+  T* gxs = reinterpret_cast<T*>(smem + in_bytes + oshift);
+  const T* w = static_cast<const T*>(a.w);
+  __syncthreads();
+  const int first = WAVE ? wave : 0, step = WAVE ? kThreads / 64 : 1;
+  const int t0 = WAVE ? lane : tid, tstep = WAVE ? 64 : kThreads;
+  int off[K * K];   // tap (u, v) reads g_y[h + p - u d][w + p - v d]
+#pragma unroll
+  for (int u = 0; u < K; ++u)
+#pragma unroll
+    for (int v = 0; v < K; ++v) off[u * K + v] = (a.p + a.halo - u * a.dl) * a.PW + a.p + a.halo - v * a.dl;
+  for (int pl = first; pl < npl; pl += step) {
+    const int gpl = pl0 + pl;
+    const int c = gpl - (int)a.d_c.div((uint32_t)gpl) * a.C;
+    float wk[K * K];
+#pragma unroll
+    for (int t = 0; t < K * K; ++t) wk[t] = to_f32(w[(long)c * (K * K) + t]);
+    const T* src = gys + pl * a.PH * a.PW;
+    T* dst = gxs + pl * HW;
+    for (int e = t0; e < HW; e += tstep) {
+      const int h = (int)a.d_w.div((uint32_t)e);
+      const int ww = e - h * a.W;
+      const T* q = src + h * a.PW + ww;
+      float acc = 0.f;
+#pragma unroll
+      for (int t = 0; t < K * K; ++t) acc += wk[t] * to_f32(q[off[t]]);
+      dst[e] = from_f32<T>(acc);
+    }
+  }
+  __syncthreads();
+  T* out = static_cast<T*>(a.gx);
+  const long e0 = (long)pl0 * HW;
+  const int span = oshift + npl * HW * (int)sizeof(T);
+  const int nvec = span >> 4;
+  unsigned char* img = smem + in_bytes;
+  unsigned char* dstb = reinterpret_cast<unsigned char*>(out) + oa0;
+  for (int v = tid + (oshift ? 1 : 0); v < nvec; v += kThreads)
+    store_stream16(dstb + ((long)v << 4), *reinterpret_cast<const uint4*>(img + (v << 4)));
+  if (oshift) {
+    const int nhead = min((16 - oshift) / (int)sizeof(T), npl * HW);
+    if (tid < nhead) out[e0 + tid] = gxs[tid];
+  }
+  {
+    const int tail0 = nvec << 4;
+    const int ntail = (span - tail0) / (int)sizeof(T);
+    const int efirst = (tail0 - oshift) / (int)sizeof(T);
+    if (tid < ntail && efirst + tid >= 0) out[e0 + efirst + tid] = gxs[efirst + tid];
+  }
+}
+
+// stride 1: x staged in a zero frame of p pixels, no bounds checks in the tap loop
+template <class T, int K, bool WAVE>
+__global__ __launch_bounds__(kThreads) void dw_exact_wgrad_s1_k(DwExactArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ float red[kThreads / 64][K * K];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pl0 = blockIdx.x * a.ppb;
+  const int npl = min(a.ppb, a.planes - pl0);
+  const int HWy = a.Hy * a.Wy;
+  const int pad_elems = a.ppb * a.PH * a.PW;
+  const int x_bytes = (pad_elems * (int)sizeof(T) + 15) & ~15;
+  T* xs = reinterpret_cast<T*>(smem);
+  for (int i = tid; i < (x_bytes >> 4); i += kThreads) reinterpret_cast<uint4*>(smem)[i] = make_uint4(0, 0, 0, 0);
+  __syncthreads();
+  stage_padded<T>(a.x, pl0, npl, a.H, a.W, a.halo, a.halo, a.PH, a.PW, a.d_hw, a.d_w, xs, tid);
+  const T* gys = stage_run<T>(a.gy, (long)pl0 * HWy, (long)(pl0 + npl) * HWy, smem + x_bytes, tid);
+  __syncthreads();
+  const int first = WAVE ? wave : 0, step = WAVE ? kThreads / 64 : 1;
+  const int t0 = WAVE ? lane : tid, tstep = WAVE ? 64 : kThreads;
+  int off[K * K];   // tap (u, v) of output (i, j) reads x[i - p + u d][j - p + v d]; the frame is p wide
+#pragma unroll
+  for (int u = 0; u < K; ++u)
+#pragma unroll
+    for (int v = 0; v < K; ++v) off[u * K + v] = (u * a.dl) * a.PW + v * a.dl;
+  for (int pl = first; pl < npl; pl += step) {
+    const T* xp = xs + pl * a.PH * a.PW;
+    const T* gp = gys + pl * HWy;
+    float acc[K * K];
+#pragma unroll
+    for (int t = 0; t < K * K; ++t) acc[t] = 0.f;
+    for (int e = t0; e < HWy; e += tstep) {
+      const int i = (int)a.d_wy.div((uint32_t)e);
+      const int j = e - i * a.Wy;
+      const float g = to_f32(gp[e]);
+      const T* q = xp + i * a.PW + j;
+#pragma unroll
+      for (int t = 0; t < K * K; ++t) acc[t] += to_f32(q[off[t]]) * g;
+    }
+#pragma unroll
+    for (int t = 0; t < K * K; ++t)
+      for (int m = 32; m > 0; m >>= 1) acc[t] += __shfl_xor(acc[t], m, 64);
+    float* dst = a.part + (long)(pl0 + pl) * (K * K);
+    if constexpr (WAVE) {
+      if (lane == 0) {
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) dst[t] = acc[t];
+      }
+    } else {
+      if (lane == 0) {
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) red[wave][t] = acc[t];
+      }
+      __syncthreads();
+      if (tid < K * K) {
+        float sm = 0.f;
+        for (int k = 0; k < kThreads / 64; ++k) sm += red[k][tid];
+        dst[tid] = sm;
+      }
+      __syncthreads();
+    }
   }
 }
 
@@ -232,14 +408,25 @@ DwExactArgs make_args(const Geom& g) {
 
 }  // namespace
 
+// LDS bytes per plane of the two kernels (stride 1: the staged operand carries its zero frame)
+static int dgrad_halo(const Geom& g) { const int h = (g.Kh - 1) * g.dl - g.p; return g.s == 1 && h > 0 ? h : 0; }
+static long dgrad_per_plane(const Geom& g) {
+  const int h = dgrad_halo(g);
+  return ((long)(g.Hy + 2 * h) * (g.Wy + 2 * h) + (long)g.H * g.W) * g.b;
+}
+static long wgrad_per_plane(const Geom& g) {
+  const int h = g.s == 1 ? g.p : 0;
+  return ((long)(g.H + 2 * h) * (g.W + 2 * h) + (long)g.Hy * g.Wy) * g.b;
+}
+
 bool dw_exact_dgrad_ok(const Geom& g) {
   if (!shape_ok(g) || (g.Kh != 3 && g.Kh != 5 && g.Kh != 7)) return false;
-  return ((long)g.H * g.W + (long)g.Hy * g.Wy) * g.b + 96 <= kLdsBudget;
+  return dgrad_per_plane(g) + 96 <= kLdsBudget;
 }
 
 bool dw_exact_wgrad_ok(const Geom& g) {
   if (!shape_ok(g) || (g.Kh != 3 && g.Kh != 5)) return false;
-  return ((long)g.H * g.W + (long)g.Hy * g.Wy) * g.b + 96 <= kLdsBudget;
+  return wgrad_per_plane(g) + 96 <= kLdsBudget;
 }
 
 size_t ws_dw_exact_wgrad(const Geom& g) { return (size_t)g.N * g.Ci * g.KK * sizeof(float); }
@@ -247,8 +434,13 @@ size_t ws_dw_exact_wgrad(const Geom& g) { return (size_t)g.N * g.Ci * g.KK * siz
 template <class T, int K, int S>
 static hipError_t dgrad_launch_s(DwExactArgs& a, bool wave, size_t lds, hipStream_t st) {
   const dim3 grid(cdiv(a.planes, a.ppb)), block(kThreads);
-  if (wave) hipLaunchKernelGGL((dw_exact_dgrad_k<T, K, S, true>), grid, block, lds, st, a);
-  else hipLaunchKernelGGL((dw_exact_dgrad_k<T, K, S, false>), grid, block, lds, st, a);
+  if constexpr (S == 1) {
+    if (wave) hipLaunchKernelGGL((dw_exact_dgrad_s1_k<T, K, true>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((dw_exact_dgrad_s1_k<T, K, false>), grid, block, lds, st, a);
+  } else {
+    if (wave) hipLaunchKernelGGL((dw_exact_dgrad_k<T, K, S, true>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((dw_exact_dgrad_k<T, K, S, false>), grid, block, lds, st, a);
+  }
   return hipGetLastError();
 }
 
@@ -269,10 +461,13 @@ static hipError_t dgrad_launch_t(DwExactArgs& a, bool wave, size_t lds, hipStrea
 hipError_t launch_dw_exact_dgrad(const Geom& g, const void* w, const void* g_y, void* g_x, hipStream_t st) {
   DwExactArgs a = make_args(g);
   a.w = w; a.gy = g_y; a.gx = g_x;
-  const long per_plane = ((long)g.H * g.W + (long)g.Hy * g.Wy) * g.b;
-  a.ppb = planes_per_block(g, per_plane);
+  a.ppb = planes_per_block(g, dgrad_per_plane(g));
   const bool wave = g.H * g.W <= 256 && a.ppb >= 4;
-  const int in_bytes = ((a.ppb * g.Hy * g.Wy * g.b + 32) + 15) & ~15;
+  a.halo = dgrad_halo(g);
+  a.PH = g.Hy + 2 * a.halo;
+  a.PW = g.Wy + 2 * a.halo;
+  const int in_bytes = g.s == 1 ? ((a.ppb * a.PH * a.PW * g.b + 15) & ~15)
+                                : (((a.ppb * g.Hy * g.Wy * g.b + 32) + 15) & ~15);
   const int out_bytes = ((a.ppb * g.H * g.W * g.b + 32) + 15) & ~15;
   const size_t lds = (size_t)in_bytes + out_bytes;
   if (g.dtype == GF_BF16) return dgrad_launch_t<bf16_t>(a, wave, lds, st);
@@ -282,8 +477,13 @@ hipError_t launch_dw_exact_dgrad(const Geom& g, const void* w, const void* g_y, 
 template <class T, int K>
 static hipError_t wgrad_launch(DwExactArgs& a, bool wave, size_t lds, hipStream_t st) {
   const dim3 grid(cdiv(a.planes, a.ppb)), block(kThreads);
-  if (wave) hipLaunchKernelGGL((dw_exact_wgrad_k<T, K, true>), grid, block, lds, st, a);
-  else hipLaunchKernelGGL((dw_exact_wgrad_k<T, K, false>), grid, block, lds, st, a);
+  if (a.s == 1) {
+    if (wave) hipLaunchKernelGGL((dw_exact_wgrad_s1_k<T, K, true>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((dw_exact_wgrad_s1_k<T, K, false>), grid, block, lds, st, a);
+  } else {
+    if (wave) hipLaunchKernelGGL((dw_exact_wgrad_k<T, K, true>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((dw_exact_wgrad_k<T, K, false>), grid, block, lds, st, a);
+  }
   return hipGetLastError();
 }
 
@@ -291,10 +491,13 @@ hipError_t launch_dw_exact_wgrad(const Geom& g, const void* x, const void* g_y, 
                                  hipStream_t st) {
   DwExactArgs a = make_args(g);
   a.x = x; a.gy = g_y; a.part = static_cast<float*>(ws);
-  const long per_plane = ((long)g.H * g.W + (long)g.Hy * g.Wy) * g.b;
-  a.ppb = planes_per_block(g, per_plane);
+  a.ppb = planes_per_block(g, wgrad_per_plane(g));
   const bool wave = g.Hy * g.Wy <= 256 && a.ppb >= 4;
-  const int x_bytes = ((a.ppb * g.H * g.W * g.b + 32) + 15) & ~15;
+  a.halo = g.s == 1 ? g.p : 0;
+  a.PH = g.H + 2 * a.halo;
+  a.PW = g.W + 2 * a.halo;
+  const int x_bytes = g.s == 1 ? ((a.ppb * a.PH * a.PW * g.b + 15) & ~15)
+                               : (((a.ppb * g.H * g.W * g.b + 32) + 15) & ~15);
   const int y_bytes = ((a.ppb * g.Hy * g.Wy * g.b + 32) + 15) & ~15;
   const size_t lds = (size_t)x_bytes + y_bytes;
   hipError_t e;
