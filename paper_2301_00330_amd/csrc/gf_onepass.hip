@@ -20,7 +20,9 @@ namespace gf {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int KC = 32;   // channels of g_y per chunk (one bf16 MFMA k-step)
+// channels of g_y per chunk: 32 (one bf16 MFMA k-step), 16 for fp32 at r = 4, where a chunk of 32
+// would need 32 vectors per lane and buffer
+template <class T, int Q> constexpr int chunk_of() { return sizeof(T) == 4 && Q == 4 ? 16 : 32; }
 constexpr int BN = 64;   // padded patch columns per tile (N of the input gradient, K of the weight gradient)
 
 struct OnePassArgs {
@@ -51,7 +53,7 @@ template <> struct XWord<16> { typedef u32x4_t type; };
 // LDS strides (elements): rows stay 16-byte aligned and consecutive rows fall into different banks
 template <class T> constexpr int pad_of() { return 16 / (int)sizeof(T); }
 
-template <class T, int CIT>
+template <class T, int CIT, int KC>
 struct Layout {
   static constexpr bool BF = sizeof(T) == 2;
   static constexpr int SB = BN + pad_of<T>();       // Bs / Xs / Cs rows: [row][col]
@@ -69,11 +71,12 @@ struct Layout {
 // XB: bytes per x_u load (4, 8 or 16; the host picks what the row alignment allows)
 template <class T, int Q, int CIT, int XB>
 __global__ __launch_bounds__(kThreads) void onepass_k(OnePassArgs a) {
-  using L = Layout<T, CIT>;
+  constexpr int KC = chunk_of<T, Q>();
+  using L = Layout<T, CIT, KC>;
   constexpr bool BF = L::BF;
   constexpr int VE = Mma<T>::VE;
   constexpr int NOUT = VE / Q;                       // patches per 16-byte item
-  constexpr int MAXI = (KC * BN * Q / VE) / kThreads;  // items per lane and chunk: 4 (fp32), 2 (bf16) at Q = 2
+  constexpr int MAXI = (KC * BN * Q / VE) / kThreads;  // items per lane and chunk: 4 (fp32), 2 (bf16) at Q = 2; 4 at Q = 4
   constexpr int SB = L::SB, ST = L::ST;
   constexpr int SW = CIT * 16 + 4;                   // fp32 Wt row
   constexpr int XV = XB / (int)sizeof(T);            // x_u elements per load
@@ -238,8 +241,8 @@ __global__ __launch_bounds__(kThreads) void onepass_k(OnePassArgs a) {
         }
       }
     }
-    // 3. weight gradient of the chunk's 32 channels: 2 x CIT tiles over the four waves
-    for (int t = wave; t < 2 * CIT; t += 4) {
+    // 3. weight gradient of the chunk's channels: (KC / 16) x CIT tiles over the four waves
+    for (int t = wave; t < (KC / 16) * CIT; t += 4) {
       const int mt = t / CIT, nt = t - mt * CIT;
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
       if constexpr (BF) {
@@ -313,13 +316,16 @@ template <class T>
 bool plan(const Geom& g, OnePassArgs* out, int* cit, int* xb) {
   constexpr int VE = 16 / (int)sizeof(T);
   if (g.g != 1 || g.s != 1 || g.KK != 1 || g.Hy != g.H || g.Wy != g.W) return false;
-  if (g.r != 2) return false;
+  if (g.r != 2 && g.r != 4) return false;
+  // fp32 at r = 4 (chunks of 16 channels, twice the barriers) measured slower than filter + merged launch
+  if (g.r == 4 && sizeof(T) == 4) return false;
+  const int KC = g.r == 4 ? chunk_of<T, 4>() : chunk_of<T, 2>();
   if (g.W % VE != 0 || g.W != g.Wp * g.r || g.Wp > BN) return false;
   if (g.Ci % VE != 0) return false;
   // few c_i tiles (the expand shape).  With many c_i tiles and one chunk (the project shape) the
   // same kernel was measured no faster than filter + merged GEMM launch, so it is not built.
   const int tiles_ci = cdiv(g.Ci, 16), nchunks = cdiv(g.Co, KC);
-  if (tiles_ci > 2 || nchunks > 8) return false;
+  if (tiles_ci > 2 || nchunks * KC > 256) return false;
   const int CIT = 2;
   OnePassArgs a = {};
   a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.H = g.H; a.W = g.W; a.Hp = g.Hp; a.Wp = g.Wp; a.P = g.P;
@@ -346,7 +352,7 @@ bool plan(const Geom& g, OnePassArgs* out, int* cit, int* xb) {
   a.d_hp = FastDiv((uint32_t)g.Hp);
   a.d_xvr = FastDiv((uint32_t)a.xvr);
   a.d_xvc = FastDiv((uint32_t)(prt * a.xvr));
-  const int lds = Layout<T, 2>::bytes(nchunks);
+  const int lds = g.r == 4 ? Layout<T, 2, chunk_of<T, 4>()>::bytes(nchunks) : Layout<T, 2, chunk_of<T, 2>()>::bytes(nchunks);
   if (lds > 80 * 1024) return false;
   if (out) *out = a;
   if (cit) *cit = CIT;
@@ -354,14 +360,14 @@ bool plan(const Geom& g, OnePassArgs* out, int* cit, int* xb) {
   return true;
 }
 
-template <class T, int CIT>
+template <class T, int Q, int CIT>
 hipError_t launch_x(OnePassArgs& a, int xb, hipStream_t st) {
   const int tiles = cdiv(a.units, a.prt);
-  const size_t lds = (size_t)Layout<T, CIT>::bytes(a.nchunks);
+  const size_t lds = (size_t)Layout<T, CIT, chunk_of<T, Q>()>::bytes(a.nchunks);
   const dim3 grid(tiles), block(kThreads);
-  if (xb == 16) hipLaunchKernelGGL((onepass_k<T, 2, CIT, 16>), grid, block, lds, st, a);
-  else if (xb == 8) hipLaunchKernelGGL((onepass_k<T, 2, CIT, 8>), grid, block, lds, st, a);
-  else hipLaunchKernelGGL((onepass_k<T, 2, CIT, 4>), grid, block, lds, st, a);
+  if (xb == 16) hipLaunchKernelGGL((onepass_k<T, Q, CIT, 16>), grid, block, lds, st, a);
+  else if (xb == 8) hipLaunchKernelGGL((onepass_k<T, Q, CIT, 8>), grid, block, lds, st, a);
+  else hipLaunchKernelGGL((onepass_k<T, Q, CIT, 4>), grid, block, lds, st, a);
   return hipGetLastError();
 }
 
@@ -372,7 +378,7 @@ hipError_t onepass_t(const Geom& g, const void* g_y, const void* x_u, const void
   int cit = 0, xb = 0;
   if (!plan<T>(g, &a, &cit, &xb)) return hipErrorInvalidValue;
   a.gy = g_y; a.xu = x_u; a.w = w; a.gyu = gy_u; a.gx = g_x; a.part = part;
-  return launch_x<T, 2>(a, xb, st);
+  return g.r == 4 ? launch_x<T, 4, 2>(a, xb, st) : launch_x<T, 2, 2>(a, xb, st);
 }
 
 }  // namespace

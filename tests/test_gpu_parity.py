@@ -309,6 +309,8 @@ FUSED_EXTRA = [
     (5, 24, 48, 28, 28, 1, 1, 0, 1, 1, 2),        # W_p = 14 (narrow x_u loads), four patch rows per tile, tail tile
     (2, 96, 24, 8, 24, 1, 1, 0, 1, 1, 2),         # project shape, W_p = 12
     (7, 16, 40, 6, 8, 1, 1, 0, 1, 1, 2),          # W_p = 4: sixteen patch rows per tile, two images and a tail
+    (2, 16, 48, 10, 16, 1, 1, 0, 1, 1, 4),        # one-pass kernel at r = 4: ragged H, tiles straddle images
+    (1, 32, 272, 8, 64, 1, 1, 0, 1, 1, 4),        # ... many chunks of C_y (fp32: 17 chunks of 16 -> the merged-launch path)
     (3, 24, 144, 56, 56, 1, 1, 0, 1, 1, 4),       # expand / project shapes at r = 4: P = 196 is no vector multiple in bf16
     (3, 144, 24, 56, 56, 1, 1, 0, 1, 1, 4),
 ]
