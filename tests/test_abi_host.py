@@ -152,3 +152,14 @@ def test_shapes_and_cost_model_against_oracle(lib, oracle):
         c, oc = B.gf_cost_model(d), oracle.cost_model(o)
         for k, v in oc.items():
             assert c[k] == pytest.approx(v, rel=1e-12), k
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; --gpus above 1 must exit with a message, before touching the GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
