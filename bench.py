@@ -155,9 +155,12 @@ def measure(args, dtype, full):
               ("bwd_weight", enqueue_bww), ("bwd_input", enqueue_bwi))
 
     def step(bufset):
+        # the order of a training step: the activations are pooled on the way forward (first layer
+        # first), the backward pass then walks the layers from the last to the first
         s = st()
         for lb in bufset:
             enqueue_pool(lb, s)      # forward-time S0
+        for lb in reversed(bufset):
             enqueue_fused(lb, s)     # S1 + S2 + S3 + S4
 
     # ---- warm-up (eager), then optional graph capture of one step per buffer set ----
