@@ -163,3 +163,26 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/gf.h must compile as C99 on its own (the boundary is a C ABI) and a C program that
+    only takes the addresses of the declared entry points must link against libgf.so."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    names = re.findall(r"\b(gf_[a-z0-9_]+)\s*\(", open(os.path.join(root, "include", "gf.h")).read())
+    names = sorted(set(n for n in names if n in B.EXPORTS))
+    assert len(names) == len(B.EXPORTS)
+    src = tmp_path / "use_gf.c"
+    src.write_text('#include "gf.h"\n#include <stdio.h>\ntypedef void (*fn_t)(void);\nint main(void) {\n  fn_t p[] = {'
+                   + ", ".join(f"(fn_t){n}" for n in names)
+                   + '};\n  printf("%d %d\\n", (int)(sizeof p / sizeof p[0]), gf_version());\n  return 0;\n}\n')
+    exe = tmp_path / "use_gf"
+    libdir = os.path.join(root, "paper_2301_00330_amd")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", f"-I{os.path.join(root, 'include')}", str(src),
+                        f"-L{libdir}", "-lgf", f"-Wl,-rpath,{libdir}", "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
