@@ -382,22 +382,40 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
     }
 }
 
-// g_w[co, ci, t] = sum_z part[z][t][co][ci], slabs added in index order; one lane per (t, co, ci)
+// g_w[co, ci, t] = sum_z part[z][t][co][ci].  A block owns kThreads / G consecutive (co, ci) pairs of
+// one tap; lane (g, e) adds the slabs z = g, g + G, ... of pair e (four loads in flight, consecutive
+// lanes on consecutive pairs), the G partial sums of a pair are then added in index order: the
+// result does not depend on scheduling.  G = 1 for large outputs, more lanes per pair for small
+// outputs with many slabs (a single lane would walk hundreds of slabs one latency at a time).
+template <int G>
 __global__ __launch_bounds__(kThreads) void xfinalize_k(const float* part, float* g_w, int pairs, int KK,
                                                        int nz) {
-  const int e = blockIdx.x * kThreads + threadIdx.x;
+  constexpr int OPB = kThreads / G;
+  __shared__ float red[G][OPB];
+  const int g = threadIdx.x / OPB, el = threadIdx.x - g * OPB;
+  const int e = blockIdx.x * OPB + el;
   const int t = blockIdx.y;
-  if (e >= pairs) return;
-  const float* p = part + (long)t * pairs + e;
+  const float* p = part + (long)t * pairs + min(e, pairs - 1);
   const long zs = (long)KK * pairs;
   float s = 0.f;
-  int z = 0;
-  for (; z + 3 < nz; z += 4) {
-    const float v0 = p[z * zs], v1 = p[(z + 1) * zs], v2 = p[(z + 2) * zs], v3 = p[(z + 3) * zs];
+  int z = g;
+  for (; z + 3 * G < nz; z += 4 * G) {
+    const float v0 = p[z * zs], v1 = p[(z + G) * zs], v2 = p[(z + 2 * G) * zs], v3 = p[(z + 3 * G) * zs];
     s += v0; s += v1; s += v2; s += v3;
   }
-  for (; z < nz; ++z) s += p[z * zs];
-  g_w[(long)e * KK + t] = s;
+  for (; z < nz; z += G) s += p[z * zs];
+  if constexpr (G == 1) {
+    if (e < pairs) g_w[(long)e * KK + t] = s;
+  } else {
+    red[g][el] = s;
+    __syncthreads();
+    if (g == 0 && e < pairs) {
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < G; ++k) sum += red[k][el];
+      g_w[(long)e * KK + t] = sum;
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -821,8 +839,17 @@ hipError_t wgrad_t(const Geom& g, const XGeo& q, const XPlan& p, const void* x, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int pairs = g.Co * g.Ci;
-  hipLaunchKernelGGL(xfinalize_k, dim3(cdiv(pairs, kThreads), g.KK), dim3(kThreads), 0, st, a.part, g_w, pairs,
-                     g.KK, p.nz);
+  // lanes per output: enough blocks for the chip when the output is small and the slabs are many
+  const long outs = (long)pairs * g.KK;
+  if (outs <= 16384 && p.nz >= 64)
+    hipLaunchKernelGGL(xfinalize_k<16>, dim3(cdiv(pairs, kThreads / 16), g.KK), dim3(kThreads), 0, st, a.part, g_w,
+                       pairs, g.KK, p.nz);
+  else if (outs <= 131072 && p.nz >= 16)
+    hipLaunchKernelGGL(xfinalize_k<4>, dim3(cdiv(pairs, kThreads / 4), g.KK), dim3(kThreads), 0, st, a.part, g_w,
+                       pairs, g.KK, p.nz);
+  else
+    hipLaunchKernelGGL(xfinalize_k<1>, dim3(cdiv(pairs, kThreads), g.KK), dim3(kThreads), 0, st, a.part, g_w, pairs,
+                       g.KK, p.nz);
   return hipGetLastError();
 }
 
