@@ -378,7 +378,10 @@ hipError_t onepass_t(const Geom& g, const void* g_y, const void* x_u, const void
   int cit = 0, xb = 0;
   if (!plan<T>(g, &a, &cit, &xb)) return hipErrorInvalidValue;
   a.gy = g_y; a.xu = x_u; a.w = w; a.gyu = gy_u; a.gx = g_x; a.part = part;
-  return g.r == 4 ? launch_x<T, 4, 2>(a, xb, st) : launch_x<T, 2, 2>(a, xb, st);
+  if constexpr (sizeof(T) == 2) {   // r = 4 is built for bf16 only (see plan)
+    if (g.r == 4) return launch_x<T, 4, 2>(a, xb, st);
+  }
+  return launch_x<T, 2, 2>(a, xb, st);
 }
 
 }  // namespace
