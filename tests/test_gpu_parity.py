@@ -352,6 +352,92 @@ def test_fused_entry_matches_separate_calls(oracle, case, dtype, want_gyu):
     assert rel_err(g_x, ref_gx) <= TOL[dtype]
 
 
+def _random_cases(count, seed):
+    """Seeded random layers that satisfy the patch-grid rule ("same"-padded), mixing the properties that
+    select kernels: aligned and odd map widths, channel counts that are / are not vector multiples, few
+    and many channels, pointwise / 3x3 / 5x5, stride, dilation, depthwise and grouped."""
+    rs = np.random.RandomState(seed)
+    out = []
+    while len(out) < count:
+        K = int(rs.choice([1, 1, 3, 3, 5]))
+        dl = int(rs.choice([1, 1, 2])) if K > 1 else 1
+        s = int(rs.choice([1, 1, 1, 2]))
+        r = int(rs.choice([2, 2, 2, 4, 3]))
+        W = int(rs.choice([8, 12, 16, 24, 28, 32, 56, 7, 9, 14, 15, 20]))
+        H = int(rs.choice([W, max(4, W - 3), W + 2, 6]))
+        kind = rs.choice(["dense", "dense", "dense", "dw", "grouped"])
+        if kind == "dw":
+            Ci = Co = int(rs.choice([3, 8, 16, 24, 40]))
+            g = Ci
+        elif kind == "grouped":
+            g = int(rs.choice([2, 4]))
+            Ci, Co = g * int(rs.choice([2, 4, 6])), g * int(rs.choice([3, 4, 8]))
+        else:
+            g = 1
+            Ci = int(rs.choice([8, 16, 24, 32, 40, 72, 96, 144, 10]))
+            Co = int(rs.choice([8, 24, 32, 48, 80, 144, 160, 12]))
+        p = dl * (K - 1) // 2
+        N = int(rs.choice([1, 2, 3, 5]))
+        if (H + 2 * p - dl * (K - 1) - 1) // s + 1 < 1:
+            continue
+        out.append((N, Ci, Co, H, W, K, s, p, dl, g, r))
+    return out
+
+
+RANDOM_CASES = _random_cases(48, 20230100)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", RANDOM_CASES)
+def test_random_layers_one_call_and_chain(oracle, case, dtype):
+    """gf_conv_bwd_filtered and gf_conv_bwd_chained (reduced and full output) on seeded random layers,
+    each against the oracle on the same rounded inputs."""
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, r, dtype)
+    try:
+        Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    except B.GfError as e:          # the generator may produce a layer that breaks the patch-grid rule
+        assert e.status == B.GF_ERR_SHAPE
+        pytest.skip("patch grids of x and g_y differ")
+    od = odesc(oracle, d)
+    x = randn((N, Ci, H, W), 71, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 72, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    gy = randn((N, Co, Hy, Wy), 73, dtype, scale=1e-2)
+    x_u = T.pool_activation(d, x.cuda())
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=True)
+    c_gw, c_gxu = T.conv_bwd_chained(d, gy_u, x_u, w.cuda(), reduced_out=True)
+    f_gw, f_gx = T.conv_bwd_chained(d, gy_u, x_u, w.cuda(), reduced_out=False)
+    torch.cuda.synchronize()
+    ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    tol = TOL[dtype]
+    assert rel_err(x_u, ref_xu) <= tol, "x_u"
+    assert rel_err(gy_u, ref_gyu) <= tol, "gy_u"
+    assert rel_err(g_w, ref_gw) <= tol, "g_w"
+    assert rel_err(g_x, ref_gx) <= tol, "g_x"
+    assert rel_err(c_gw, ref_gw) <= tol and rel_err(f_gw, ref_gw) <= tol, "chained g_w"
+    assert rel_err(f_gx, ref_gx) <= tol, "chained g_x"
+    ref_red = oracle.bwd_input(od, to64(gy_u), to64(w), reduced_out=True)
+    assert rel_err(c_gxu, ref_red) <= tol, "chained reduced g_x"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", RANDOM_CASES[:24])
+def test_random_layers_exact(oracle, case, dtype):
+    """Vanilla BP on the same random layers (r = 1 lifts the patch-grid rule)."""
+    N, Ci, Co, H, W, K, s, p, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K, s, p, dl, g, 1, dtype)
+    Hy, Wy, _, _ = B.gf_out_shape(d)
+    od = odesc(oracle, d)
+    x = randn((N, Ci, H, W), 81, dtype)
+    w = randn((Co, Ci // g, K, K), 82, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    gy = randn((N, Co, Hy, Wy), 83, dtype, scale=1e-2)
+    g_w, g_x = T.conv_bwd_exact(d, x.cuda(), w.cuda(), gy.cuda())
+    torch.cuda.synchronize()
+    ref_gw, ref_gx = oracle.bwd_exact(od, to64(x), to64(w), to64(gy))
+    assert rel_err(g_w, ref_gw) <= TOL[dtype], "g_w"
+    assert rel_err(g_x, ref_gx) <= TOL[dtype], "g_x"
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("reduced_out", [True, False])
 @pytest.mark.parametrize("case", GF_CASES + FUSED_EXTRA)
