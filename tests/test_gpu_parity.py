@@ -387,8 +387,27 @@ def _random_cases(count, seed):
 RANDOM_CASES = _random_cases(48, 20230100)
 
 
+def _random_pointwise_cases(count, seed):
+    """Pointwise stride-1 layers on aligned maps: the shapes of the one-pass kernel (few input channels)
+    and of the patch-row store epilogue, with odd heights, tiles that straddle images and tail tiles."""
+    rs = np.random.RandomState(seed)
+    out = []
+    for _ in range(count):
+        r = int(rs.choice([2, 2, 4]))
+        W = int(rs.choice([8, 16, 24, 32, 40, 56, 64, 112]))
+        H = int(rs.choice([r, 2 * r + 1, 3 * r, 9, 14, 28]))
+        Ci = int(rs.choice([8, 16, 24, 32, 48, 144]))
+        Co = int(rs.choice([8, 24, 40, 96, 144, 272]))
+        N = int(rs.choice([1, 2, 3, 7]))
+        out.append((N, Ci, Co, H, W, 1, 1, 0, 1, 1, r))
+    return out
+
+
+RANDOM_POINTWISE = _random_pointwise_cases(32, 330)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("case", RANDOM_CASES)
+@pytest.mark.parametrize("case", RANDOM_CASES + RANDOM_POINTWISE)
 def test_random_layers_one_call_and_chain(oracle, case, dtype):
     """gf_conv_bwd_filtered and gf_conv_bwd_chained (reduced and full output) on seeded random layers,
     each against the oracle on the same rounded inputs."""
@@ -405,9 +424,11 @@ def test_random_layers_one_call_and_chain(oracle, case, dtype):
     gy = randn((N, Co, Hy, Wy), 73, dtype, scale=1e-2)
     x_u = T.pool_activation(d, x.cuda())
     g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=True)
+    n_gw, n_gx, _ = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=False)
     c_gw, c_gxu = T.conv_bwd_chained(d, gy_u, x_u, w.cuda(), reduced_out=True)
     f_gw, f_gx = T.conv_bwd_chained(d, gy_u, x_u, w.cuda(), reduced_out=False)
     torch.cuda.synchronize()
+    assert torch.equal(n_gx, g_x) and torch.equal(n_gw, g_w)
     ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
     tol = TOL[dtype]
     assert rel_err(x_u, ref_xu) <= tol, "x_u"
