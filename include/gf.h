@@ -60,7 +60,7 @@ typedef enum gf_status {
   GF_ERR_SHAPE = 3,       /* kernel larger than the padded input, or the patch grids
                              of x and g_y differ                                     */
   GF_ERR_UNSUPPORTED = 4, /* legal but not implemented (e.g. a misaligned pointer,
-                             more than 2^31-1 elements in one tensor)                */
+                             more than 2^31 - 2^20 elements in one tensor)           */
   GF_ERR_WORKSPACE = 5,   /* ws is NULL or smaller than gf_workspace_bytes says      */
   GF_ERR_DEVICE = 6       /* the HIP runtime refused a launch                        */
 } gf_status;

@@ -34,8 +34,9 @@ gf_status make_geom(const gf_conv_desc* d, Geom* o) {
   g.P = g.Hp * g.Wp;
   g.dtype = d->dtype;
   g.b = d->dtype == GF_BF16 ? 2 : 4;
-  // 32-bit element indexing inside the kernels
-  const long lim = 2147483647L;
+  // 32-bit element indexing inside the kernels; the margin keeps the index of the last block's
+  // last lane, which may point past the end before it is checked, below 2^31 as well
+  const long lim = (1L << 31) - (1L << 20);
   if ((long)g.N * g.Ci * g.H * g.W > lim || (long)g.N * g.Co * g.Hy * g.Wy > lim ||
       (long)g.Co * g.Cg * g.KK > lim)
     return GF_ERR_UNSUPPORTED;

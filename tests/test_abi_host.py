@@ -29,6 +29,16 @@ def test_exports_match_header(lib):
     assert B.gf_version() >= 100
 
 
+def test_largest_accepted_tensor(lib):
+    """Kernels index elements with 32 bits: a tensor may hold up to 2^31 - 2^20 elements."""
+    big = dict(N=1, C_in=2047, C_out=2047, H_in=1024, W_in=1024, K_h=1, K_w=1, pad=0, r=2)
+    assert B.gf_out_shape(B.ConvDesc(**big)) == (1024, 1024, 512, 512)
+    for over in (dict(W_in=1025), dict(C_in=2048), dict(C_out=2048)):
+        with pytest.raises(B.GfError) as ei:
+            B.gf_out_shape(B.ConvDesc(**{**big, **over}))
+        assert ei.value.status == B.GF_ERR_UNSUPPORTED
+
+
 OK = dict(N=2, C_in=4, C_out=8, H_in=8, W_in=8, K_h=3, K_w=3, pad=1, r=2)
 FAKE = 0x1000  # non-null, 16-byte aligned; never dereferenced because validation fails first
 
@@ -39,7 +49,7 @@ FAKE = 0x1000  # non-null, 16-byte aligned; never dereferenced because validatio
     (dict(dtype=7), B.GF_ERR_BAD_DESC), (dict(pad=0), B.GF_ERR_SHAPE), (dict(K_h=19, K_w=19), B.GF_ERR_SHAPE),
     (dict(N=1 << 20, C_in=1 << 10, H_in=64, W_in=64), B.GF_ERR_UNSUPPORTED),
 ])
-def test_descriptor_errors(lib, bad, status):
+def test_descriptor_errors(lib, bad, status):  # the last case: 2^36 elements
     d = B.ConvDesc(**{**OK, **bad})
     for call in (lambda: B.gf_out_shape(d),
                  lambda: B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT),

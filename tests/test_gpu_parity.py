@@ -755,6 +755,59 @@ def test_config4_full_size_sampled(oracle):
     assert np.abs(to64(gx_c[n:n + 1, c0:c0 + 8]) - ref).max() <= TOL[dtype] * gx_max
 
 
+# Just under 2^31 elements per tensor: the most the entry points accept (the kernels index
+# elements with 32 bits).  Sampled outputs at both ends of every tensor against the oracle.
+MAX_CASES = [
+    ("pointwise", dict(Ci=256, Co=256, H=256, W=256, K=1, p=0, g=1), 2),
+    ("depthwise", dict(Ci=256, Co=256, H=256, W=256, K=3, p=1, g=256), 2),
+    ("pointwise ragged", dict(Ci=256, Co=256, H=255, W=257, K=1, p=0, g=1), 4),
+    ("depthwise ragged", dict(Ci=256, Co=256, H=255, W=257, K=3, p=1, g=256), 4),
+]
+
+
+@pytest.mark.parametrize("case", MAX_CASES, ids=[c[0] for c in MAX_CASES])
+def test_largest_tensors_sampled(oracle, case):
+    _, kw, r = case
+    dtype, N = "bf16", 127
+    d = mk(N, r=r, dtype=dtype, **kw)
+    C, H, W, K, dw = kw["Ci"], kw["H"], kw["W"], kw["K"], kw["g"] > 1
+    assert 2**31 - 2**25 < N * C * H * W < 2**31
+    gen = torch.Generator(device="cuda").manual_seed(31)
+    x = torch.randn((N, C, H, W), generator=gen, device="cuda", dtype=torch.bfloat16).abs_()
+    gy = torch.randn((N, C, H, W), generator=gen, device="cuda", dtype=torch.bfloat16)
+    w = (torch.randn((C, 1 if dw else C, K, K), generator=gen, device="cuda") * 0.05).to(torch.bfloat16)
+    x_u = T.pool_activation(d, x)
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy, x_u, w, want_gyu=True)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    gw_max, gx_max = float(g_w.abs().max()), float(g_x.abs().max())
+    assert gw_max > 0 and gx_max > 0
+    ends = [0, N - 1]
+    chans = [slice(0, 4), slice(C - 4, C)]
+    for n in ends:
+        for cs in chans:  # reduced maps, first and last planes
+            sd = oracle.Desc(N=1, C_in=4, C_out=4, H_in=H, W_in=W, r=r)
+            assert rel_err(x_u[n:n + 1, cs], oracle.pool_activation(sd, to64(x[n:n + 1, cs]))) <= tol
+            assert rel_err(gy_u[n:n + 1, cs], oracle.filter_grad(sd, to64(gy[n:n + 1, cs]))) <= tol
+    if dw:
+        for cs in chans:
+            sd = oracle.Desc(N=N, C_in=4, C_out=4, H_in=H, W_in=W, K_h=K, K_w=K, pad=kw["p"], groups=4, r=r)
+            ref_gw, ref_gx, _, _ = oracle.gf_backward(sd, to64(x[:, cs]), to64(w[cs]), to64(gy[:, cs]))
+            assert np.abs(to64(g_w[cs]) - ref_gw).max() <= tol * gw_max
+            assert np.abs(to64(g_x[:, cs]) - ref_gx).max() <= tol * gx_max
+    else:
+        for co, ci in [(0, 0), (C - 1, C - 1), (3, C - 2), (C - 5, 1)]:
+            sd = oracle.Desc(N=N, C_in=1, C_out=1, H_in=H, W_in=W, r=r)
+            ref_gw, _, _, _ = oracle.gf_backward(sd, to64(x[:, ci:ci + 1]), to64(w[co:co + 1, ci:ci + 1]),
+                                                 to64(gy[:, co:co + 1]))
+            assert abs(float(g_w[co, ci, 0, 0]) - ref_gw[0, 0, 0, 0]) <= tol * gw_max
+        for n in ends:
+            for cs in chans:
+                sd = oracle.Desc(N=1, C_in=4, C_out=C, H_in=H, W_in=W, r=r)
+                ref = oracle.bwd_input(sd, oracle.filter_grad(sd, to64(gy[n:n + 1])), to64(w[:, cs]))
+                assert np.abs(to64(g_x[n:n + 1, cs]) - ref).max() <= tol * gx_max
+
+
 def test_repeat_runs_are_bit_identical():
     """No floating-point atomics anywhere: two runs must agree bit for bit."""
     cfg = WL.CONFIGS[2]
