@@ -87,7 +87,7 @@ __device__ __forceinline__ void prep_tables(const PrepArgs& a, int block) {
   const int e0 = block * kThreads + threadIdx.x;
   const int nph = a.s * a.s;
   const int nmax = a.nvw > a.nvd * nph ? a.nvw : a.nvd * nph;
-  if (block == 0 && threadIdx.x < nph) {  // tap list of one phase of g_x
+  if (block == 0 && (int)threadIdx.x < nph) {  // tap list of one phase of g_x
     const int ph = threadIdx.x, pa = ph / a.s, pb = ph - pa * a.s;
     int cnt = 0;
     for (int t = 0; t < a.KK; ++t) {
@@ -464,7 +464,6 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
   constexpr int PB = KP * VPB / kThreads;        // word-row slots per lane
   constexpr int WSTEP = kThreads / VPB;          // word rows between a lane's slots
   constexpr int SC = BN + VE;                    // element stride of the output staging tile
-  constexpr uint32_t FULL = Mma<T>::FULL;
   static_assert(kThreads % VPB == 0 && PB >= 1 && PB * RPS <= 16 && LA >= 1, "slot layout");
   __shared__ __attribute__((aligned(16))) unsigned char smem[xdgrad_smem_bytes<T, BM, BN, KV>()];
   unsigned char* As = smem;

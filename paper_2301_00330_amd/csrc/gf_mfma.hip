@@ -395,6 +395,10 @@ constexpr int dgrad_smem_words() {
   return tile > out ? tile : out;
 }
 
+template <class T, int BM, int BN, bool VEC>
+__device__ __forceinline__ void dgrad_epilogue(const DgradMfmaArgs& a, const T* Cs, unsigned char* Es,
+                                               int bx, int m0, int j0, int jend, int tid);
+
 // block (bx, by) = (column tile, c_i tile); smem: dgrad_smem_words() words; Es: plane staging
 // buffer (only touched in plane mode)
 template <class T, int TM, int TN, int WM, int WN, bool VEC>

@@ -335,6 +335,9 @@ bool plan(const Geom& g, OnePassArgs* out, int* cit, int* xb) {
   const int per_patch_row = g.r * a.ipr;   // output vectors of one patch row of one c_i
   if (per_patch_row > kThreads) return false;
   if (prt > kThreads / per_patch_row) prt = kThreads / per_patch_row;
+  // fewer patch rows per tile when the tiles would not fill the chip (the kernel is bound by the
+  // bytes in flight, not by the MFMA columns a narrow tile leaves idle)
+  while (prt > 1 && cdiv(a.units, prt) < 384) --prt;
   a.prt = prt;
   a.cols = prt * g.Wp;
   a.ppi = prt * a.ipr;
