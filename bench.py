@@ -96,7 +96,8 @@ def main():
     others = [d for d in WL.CONFIGS[args.config].dtypes if d != out["dtype"]]
     if others and not args.single_dtype:
         o = measure(args, others[0], full=False)
-        out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer")}
+        out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer",
+                                                "chained_block") if k in o}
     print(json.dumps(out), flush=True)
 
 
@@ -214,7 +215,7 @@ def measure(args, dtype, full):
 
     # ---- secondary: the layers as a chain that hands reduced maps from layer to layer ----
     chained = None
-    if full and cfg.chain and r > 1:
+    if cfg.chain and r > 1:
         order = list(cfg.chain)                       # back to front
         for bs in sets:
             for lb in bs:
