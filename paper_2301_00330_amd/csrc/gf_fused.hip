@@ -220,6 +220,7 @@ __global__ __launch_bounds__(kThreads) void dw_fused_lds_k(DwFusedArgs a) {
   T* gyu = a.gyu ? static_cast<T*>(a.gyu) + (long)pl0 * a.P : nullptr;
   const int nout = np * a.P;
   const int q = QT ? QT : a.q;
+  constexpr int UQ = QT ? QT : 1;  // unroll count of the q x q loops (1: run-time q, no unrolling)
   for (int lo = tid; lo < nout; lo += kThreads) {
     const int lp = (int)a.d_p.div((uint32_t)lo);  // local plane
     const int pp = lo - lp * a.P;
@@ -230,9 +231,9 @@ __global__ __launch_bounds__(kThreads) void dw_fused_lds_k(DwFusedArgs a) {
     const int base = lp * HW + hp * q * a.W + wp * q;
     const float xval = to_f32(xu[lo]);
     float acc = 0.f;
-#pragma unroll
+#pragma unroll UQ
     for (int i = 0; i < q; ++i)
-#pragma unroll
+#pragma unroll UQ
       for (int j = 0; j < q; ++j) {
         const bool ok = i < ch && j < cw;
         const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
@@ -243,9 +244,9 @@ __global__ __launch_bounds__(kThreads) void dw_fused_lds_k(DwFusedArgs a) {
     if (gyu) gyu[lo] = mean;
     prods[lo] = m * xval;
     const T g = from_f32<T>(m * scs[lp]);
-#pragma unroll
+#pragma unroll UQ
     for (int i = 0; i < q; ++i)
-#pragma unroll
+#pragma unroll UQ
       for (int j = 0; j < q; ++j)
         if (i < ch && j < cw) lds[base + i * a.W + j] = g;
   }

@@ -252,12 +252,13 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
     const int cw = min(a.q, a.W - wp * a.q);
     const int base = (pl0 + dpl) * HW + hp * a.q * a.W + wp * a.q - e0;
     const int q = QT ? QT : a.q;
+    constexpr int UQ = QT ? QT : 1;  // unroll count of the q x q loops (1: run-time q, no unrolling)
     float acc = 0.f;
     // uniform q x q loop (no divergent branches): out-of-patch positions read the patch's
     // first element and are not added
-#pragma unroll
+#pragma unroll UQ
     for (int i = 0; i < q; ++i)
-#pragma unroll
+#pragma unroll UQ
       for (int j = 0; j < q; ++j) {
         const bool ok = i < ch && j < cw;
         const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
@@ -267,9 +268,9 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
     out[s0 * a.Wp + lo] = from_f32<T>(acc);
     if constexpr (MODE == kMask) {
       float cnt = 0.f;
-#pragma unroll
+#pragma unroll UQ
       for (int i = 0; i < q; ++i)
-#pragma unroll
+#pragma unroll UQ
         for (int j = 0; j < q; ++j) {
           const bool ok = i < ch && j < cw;
           const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
@@ -278,9 +279,9 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
       static_cast<T*>(a.out2)[s0 * a.Wp + lo] = from_f32<T>(cnt / (float)(ch * cw));
     }
     if constexpr (STATS) {
-#pragma unroll
+#pragma unroll UQ
       for (int i = 0; i < q; ++i)
-#pragma unroll
+#pragma unroll UQ
         for (int j = 0; j < q; ++j) {
           const bool ok = i < ch && j < cw;
           const float val = to_f32(lds[base + (ok ? i * a.W + j : 0)]);
