@@ -50,6 +50,9 @@ def parse():
                     help="end with five plain 256 MiB device copies (a kernel of known traffic, used to\n"
                          "scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--table", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--fig3", action="store_true",
+                    help="instead of the benchmark: the three cost lines of the paper's Fig. 3 (vanilla BP, fewer\n"
+                         "unique elements only, gradient filtering) as measured time on the layer of its footnote")
     return ap.parse_args()
 
 
@@ -91,6 +94,9 @@ def main():
         log("bench.py: this build measures ONE GPU only (the path has no multi-GPU part); "
             "run with --gpus 1")
         sys.exit(2)
+    if args.fig3:
+        print(json.dumps(fig3(args)), flush=True)
+        return
     out = measure(args, args.dtype, full=True)
     from paper_2301_00330_amd import workloads as WL
     others = [d for d in WL.CONFIGS[args.config].dtypes if d != out["dtype"]]
@@ -99,6 +105,110 @@ def main():
         out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer",
                                                 "chained_block") if k in o}
     print(json.dumps(out), flush=True)
+
+
+def fig3(args):
+    """Sec. 4.2 / Fig. 3 on this GPU: the layer of the figure's footnote (3x3, 192 -> 64 channels, 120 x 160
+    map) under the three cost lines of the analysis -- vanilla BP; 'fewer unique elements' only, i.e. the
+    same K x K backward run on the r^2-smaller maps (gf_conv_bwd_exact on the reduced shape); and gradient
+    filtering with the collapsed kernel (Eq. 3 / Eq. 5).  Times are per call, cold (rotating buffer sets),
+    from HIP events around back-to-back launches; FLOPs are the closed forms of Eq. 1 and Eq. 12."""
+    import torch
+    import paper_2301_00330_amd.binding as B
+    import paper_2301_00330_amd.torch_api as T
+    from paper_2301_00330_amd import workloads as WL
+
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dtype = args.dtype
+    td = WL.torch_dtype(dtype)
+    N, Ci, Co, H, W, K = 8, 192, 64, 120, 160, 3
+    code = B.GF_BF16 if dtype == "bf16" else B.GF_F32
+    P = B.ptr
+    gen = torch.Generator(device="cpu").manual_seed(230100330 + 3)
+    hx = torch.randn((N, Ci, H, W), generator=gen).abs().to(td)
+    hw = (torch.randn((Co, Ci, K, K), generator=gen) * (2.0 / (Ci * K * K)) ** 0.5).to(td)
+    hg = (torch.randn((N, Co, H, W), generator=gen) * 1e-2).to(td)
+    nsets = 8   # 118 MB of x (fp32) per set: rotation keeps every call out of the 256 MB memory-side cache
+
+    def ws_for(d, op):
+        return torch.empty(max(B.gf_workspace_bytes(d, op), 256), dtype=torch.uint8, device="cuda")
+
+    def timed(fn, reps=5):
+        s = int(torch.cuda.current_stream().cuda_stream)
+        for k in range(nsets):
+            fn(k, s)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            for k in range(nsets):
+                fn(k, s)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * nsets)
+
+    xs = [hx.cuda() for _ in range(nsets)]
+    gs = [hg.cuda() for _ in range(nsets)]
+    w = hw.cuda()
+    gws = [torch.empty((Co, Ci, K, K), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    gxs = [torch.empty_like(xs[0]) for _ in range(nsets)]
+    d1 = B.ConvDesc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, stride=1, pad=1, dilation=1, groups=1,
+                    r=1, dtype=code)
+    ws1 = ws_for(d1, B.GF_OP_BWD_EXACT)
+    cost1 = B.gf_cost_model(d1)
+    rows = []
+    t_gx = timed(lambda k, s: B.gf_conv_bwd_exact(d1, 0, P(w), P(gs[k]), 0, P(gxs[k]), P(ws1), ws1.numel(), s))
+    t_all = timed(lambda k, s: B.gf_conv_bwd_exact(d1, P(xs[k]), P(w), P(gs[k]), P(gws[k]), P(gxs[k]), P(ws1),
+                                                   ws1.numel(), s))
+    rows.append({"line": "vanilla BP", "r": 1, "flops_gx_per_image": cost1["flops_exact_gx"],
+                 "gx_us": round(t_gx, 1), "backward_us": round(t_all, 1)})
+    for r in (2, 4, 8):
+        d = d1.with_(r=r)
+        sh = T.shapes(d)
+        xus = [torch.empty(sh["x_u"], dtype=td, device="cuda") for _ in range(nsets)]
+        gus = [torch.empty(sh["gy_u"], dtype=td, device="cuda") for _ in range(nsets)]
+        for k in range(nsets):
+            B.gf_pool_activation(d, P(xs[k]), P(xus[k]), 0)
+        cost = B.gf_cost_model(d)
+        # fewer unique elements only: the exact K x K backward on the reduced maps
+        ds = d1.with_(H_in=sh["x_u"][2], W_in=sh["x_u"][3])
+        wss = ws_for(ds, B.GF_OP_BWD_EXACT)
+        gxr = [torch.empty(sh["x_u"], dtype=td, device="cuda") for _ in range(nsets)]
+
+        def small_gx(k, s):
+            B.gf_filter_grad(d, P(gs[k]), P(gus[k]), s)
+            B.gf_conv_bwd_exact(ds, 0, P(w), P(gus[k]), 0, P(gxr[k]), P(wss), wss.numel(), s)
+
+        def small_all(k, s):
+            B.gf_filter_grad(d, P(gs[k]), P(gus[k]), s)
+            B.gf_conv_bwd_exact(ds, P(xus[k]), P(w), P(gus[k]), P(gws[k]), P(gxr[k]), P(wss), wss.numel(), s)
+
+        rows.append({"line": "fewer unique elements only", "r": r,
+                     "flops_gx_per_image": cost1["flops_exact_gx"] / (r * r),
+                     "gx_us": round(timed(small_gx), 1), "backward_us": round(timed(small_all), 1)})
+        # gradient filtering: Eq. 2, then Eq. 3 (and Eq. 5)
+        wsi, wsf = ws_for(d, B.GF_OP_BWD_INPUT), ws_for(d, B.GF_OP_BWD_FILTERED)
+
+        def gf_gx(k, s):
+            B.gf_filter_grad(d, P(gs[k]), P(gus[k]), s)
+            B.gf_conv_bwd_input(d, P(gus[k]), P(w), P(gxs[k]), False, P(wsi), wsi.numel(), s)
+
+        def gf_all(k, s):
+            B.gf_conv_bwd_filtered(d, P(gs[k]), P(xus[k]), P(w), 0, P(gws[k]), P(gxs[k]), P(wsf), wsf.numel(), s)
+
+        rows.append({"line": "gradient filtering", "r": r, "flops_gx_per_image": cost["flops_gf_gx"],
+                     "gx_us": round(timed(gf_gx), 1), "backward_us": round(timed(gf_all), 1)})
+        del xus, gus, gxr
+    log(f"Fig. 3 layer: 3x3, {Ci} -> {Co} channels, {H} x {W}, N={N}, {dtype}; times per call in us")
+    log(f"{'line':30s} {'r':>2s} {'MFLOP g_x / image':>18s} {'g_x us':>9s} {'g_w + g_x us':>13s}")
+    for q in rows:
+        log(f"{q['line']:30s} {q['r']:2d} {q['flops_gx_per_image'] / 1e6:18.1f} {q['gx_us']:9.1f} {q['backward_us']:13.1f}")
+    return {"figure": "Fig. 3 (Sec. 4.2) as measured time", "n_gpus": 1, "dtype": dtype, "data": "synthetic",
+            "layer": {"N": N, "C_in": Ci, "C_out": Co, "H": H, "W": W, "K": K}, "unit": "us per call",
+            "note": "g_x columns include the gradient filter (Eq. 2) where it applies; the pooling of x is forward-time work",
+            "lines": rows}
 
 
 def measure(args, dtype, full):

@@ -755,6 +755,26 @@ def test_config4_full_size_sampled(oracle):
     assert np.abs(to64(gx_c[n:n + 1, c0:c0 + 8]) - ref).max() <= TOL[dtype] * gx_max
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fewer_unique_elements_only_variant(oracle, dtype):
+    """Sec. 4.2, first saving only (the middle cost line of Fig. 3): the K x K backward on the
+    r^2-smaller maps is the exact entry called with the reduced shape, fed by the two reductions."""
+    N, Ci, Co, H, W, K, r = 2, 24, 16, 20, 28, 3, 2
+    d = mk(N, Ci, Co, H, W, K=K, p=1, r=r, dtype=dtype)
+    ds = mk(N, Ci, Co, H // r, W // r, K=K, p=1, r=1, dtype=dtype)
+    x, w, gy = randn((N, Ci, H, W), 1, dtype, relu=True), randn((Co, Ci, K, K), 2, dtype, 0.1), randn((N, Co, H, W), 3, dtype)
+    x_u = T.pool_activation(d, x.cuda())
+    gy_u = T.filter_grad(d, gy.cuda())
+    g_w, g_x = T.conv_bwd_exact(ds, x_u, w.cuda(), gy_u)
+    torch.cuda.synchronize()
+    od, ods = odesc(oracle, d), odesc(oracle, ds)
+    # the oracle continues from the GPU's (rounded) reduced maps, which were checked on their own
+    assert rel_err(x_u, oracle.pool_activation(od, to64(x))) <= TOL[dtype]
+    assert rel_err(gy_u, oracle.filter_grad(od, to64(gy))) <= TOL[dtype]
+    ref_gw, ref_gx = oracle.bwd_exact(ods, to64(x_u), to64(w), to64(gy_u))
+    assert rel_err(g_w, ref_gw) <= TOL[dtype] and rel_err(g_x, ref_gx) <= TOL[dtype]
+
+
 # Just under 2^31 elements per tensor: the most the entry points accept (the kernels index
 # elements with 32 bits).  Sampled outputs at both ends of every tensor against the oracle.
 MAX_CASES = [
