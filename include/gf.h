@@ -20,6 +20,10 @@
  *    owned by the caller; the library never allocates, frees or keeps one.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work on it: they never synchronise and never throw.
+ *    The device that owns the stream and the pointers must be the calling
+ *    thread's current device.  The library keeps no state, so calls from
+ *    several threads or on several streams need no locking as long as their
+ *    outputs and workspaces do not overlap; every call may be stream-captured.
  *  - The return value is a gf_status.  Descriptor, pointer, shape and workspace
  *    errors are detected on the host BEFORE anything is enqueued, so a failed
  *    call has no effect on the device.  GF_ERR_DEVICE reports a failed launch.
