@@ -828,6 +828,77 @@ def test_largest_tensors_sampled(oracle, case):
                 assert np.abs(to64(g_x[n:n + 1, cs]) - ref).max() <= tol * gx_max
 
 
+def test_entry_points_replay_from_a_hip_graph():
+    """Every entry point only enqueues kernels (and device copies at r = 1), so a captured
+    sequence must replay to the same bits as plain launches -- checked on three replays with
+    new inputs written in place and eager work between them."""
+    cfg = WL.CONFIGS[2]
+    N, dtype = 4, "bf16"
+    P = B.ptr
+    jobs = []
+    for layer in cfg.layers:
+        for r in (2, 1):
+            d = T.desc_for(layer, N, r, dtype)
+            x, w, gy = (t.cuda() for t in WL.make_inputs(cfg, layer, dtype, N=N))
+            sh = T.shapes(d)
+            buf = dict(d=d, x=x, w=w, gy=gy)
+            for name, key, dt in (("x_u", "x_u", x.dtype), ("gy_u", "gy_u", x.dtype), ("g_x", "x", x.dtype),
+                                  ("g_xu", "g_x_u", x.dtype), ("e_x", "x", x.dtype),
+                                  ("g_w", "w", torch.float32), ("c_w", "w", torch.float32), ("e_w", "w", torch.float32)):
+                buf[name] = torch.zeros(sh[key], dtype=dt, device="cuda")
+            buf["stats"] = torch.zeros(2, dtype=torch.float64, device="cuda")
+            for op in (B.GF_OP_BWD_FILTERED, B.GF_OP_BWD_CHAINED, B.GF_OP_BWD_EXACT, B.GF_OP_FILTER_SNR):
+                buf[op] = torch.empty(max(B.gf_workspace_bytes(d, op), 256), dtype=torch.uint8, device="cuda")
+            jobs.append(buf)
+    outs = ("x_u", "gy_u", "g_x", "g_xu", "e_x", "g_w", "c_w", "e_w", "stats")
+
+    def enqueue(s):
+        for b in jobs:
+            d = b["d"]
+            B.gf_pool_activation(d, P(b["x"]), P(b["x_u"]), s)
+            B.gf_conv_bwd_filtered(d, P(b["gy"]), P(b["x_u"]), P(b["w"]), P(b["gy_u"]), P(b["g_w"]), P(b["g_x"]),
+                                   P(b[B.GF_OP_BWD_FILTERED]), b[B.GF_OP_BWD_FILTERED].numel(), s)
+            B.gf_conv_bwd_chained(d, P(b["gy_u"]), P(b["x_u"]), P(b["w"]), P(b["c_w"]), P(b["g_xu"]), True, 0,
+                                  P(b[B.GF_OP_BWD_CHAINED]), b[B.GF_OP_BWD_CHAINED].numel(), s)
+            B.gf_conv_bwd_exact(d, P(b["x"]), P(b["w"]), P(b["gy"]), P(b["e_w"]), P(b["e_x"]),
+                                P(b[B.GF_OP_BWD_EXACT]), b[B.GF_OP_BWD_EXACT].numel(), s)
+            if d.r > 1:
+                B.gf_filter_grad_snr(d, P(b["gy"]), P(b["gy_u"]), P(b["stats"]), P(b[B.GF_OP_FILTER_SNR]),
+                                     b[B.GF_OP_FILTER_SNR].numel(), s)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [[b[k].clone() for k in outs] for b in jobs]
+
+    def clear():
+        for b in jobs:
+            for k in outs:
+                b[k].zero_()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        enqueue(int(side.cuda_stream))      # warm-up outside the capture
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            enqueue(int(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for b in jobs:   # new inputs, written in place (the graph holds the addresses)
+            b["gy"].mul_(-1.5 - rep)
+            b["x"].add_(0.25 * (rep + 1))
+        clear()
+        enqueue(int(torch.cuda.current_stream().cuda_stream))
+        eager = snapshot()
+        clear()
+        g.replay()
+        replay = snapshot()
+        for je, jr in zip(eager, replay):
+            for k, a, c in zip(outs, je, jr):
+                assert torch.equal(a, c), (rep, k)
+
+
 def test_repeat_runs_are_bit_identical():
     """No floating-point atomics anywhere: two runs must agree bit for bit."""
     cfg = WL.CONFIGS[2]
