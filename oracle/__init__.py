@@ -211,6 +211,75 @@ def conv_fwd(d: Desc, x, w) -> np.ndarray:
     return y
 
 
+# ---- gradient filtering on 8-bit codes (reading of Supp. H, see gf_ref.h) ----
+
+def _q(a, shape) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.int8)
+    if tuple(a.shape) != tuple(shape):
+        raise OracleError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def _pq(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_byte))
+
+
+def quantize_q8(v, inv_delta: float) -> np.ndarray:
+    """codes = clip(round_half_even(float32(v) * inv_delta), -127, 127), int8, same shape."""
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    q = np.empty(v.shape, np.int8)
+    _chk(_L().gf_ref_quantize_q8(_p(v), C.c_long(v.size), C.c_float(inv_delta), _pq(q)), "quantize_q8")
+    return q
+
+
+def filter_grad_q8(d: Desc, g_y, inv_delta: float) -> np.ndarray:
+    return quantize_q8(filter_grad(d, g_y), inv_delta)
+
+
+def pool_activation_q8(d: Desc, x, inv_delta: float) -> np.ndarray:
+    return quantize_q8(pool_activation(d, x), inv_delta)
+
+
+def kernel_sum_q8(d: Desc, w, inv_delta: float) -> np.ndarray:
+    return quantize_q8(kernel_sum(d, w), inv_delta)
+
+
+def _scale32(d: Desc, scale: float) -> np.float32:
+    """step-size product times 1/s^2, formed in binary32 as the library's host code forms it"""
+    return np.float32(scale) / (np.float32(d.stride) * np.float32(d.stride))
+
+
+def bwd_weight_q8(d: Desc, x_q, gy_q, scale: float) -> np.ndarray:
+    """Eq. 5 on codes, float32 [C_out, C_in/groups, K_h, K_w]: float32(integer sum) * scale / s^2 on every tap."""
+    Hy, Wy, Hp, Wp = out_shape(d)
+    x_q = _q(x_q, (d.N, d.C_in, Hp, Wp))
+    gy_q = _q(gy_q, (d.N, d.C_out, Hp, Wp))
+    acc = np.empty((d.C_out, d.C_in // d.groups), np.int64)
+    cd = d._c()
+    _chk(_L().gf_ref_bwd_weight_q8(C.byref(cd), _pq(x_q), _pq(gy_q), acc.ctypes.data_as(C.POINTER(C.c_longlong))),
+         "bwd_weight_q8")
+    val = acc.astype(np.float32) * _scale32(d, scale)
+    return np.ascontiguousarray(np.broadcast_to(val[:, :, None, None], w_shape(d)))
+
+
+def bwd_input_q8(d: Desc, gy_q, w_q, scale: float, reduced_out: bool = False) -> np.ndarray:
+    """Eq. 3 on codes, float32: float32(integer sum) * scale / s^2, one value per patch
+    ([N, C_in, H_p, W_p]) or replicated over the input-side patches ([N, C_in, H_in, W_in])."""
+    Hy, Wy, Hp, Wp = out_shape(d)
+    gy_q = _q(gy_q, (d.N, d.C_out, Hp, Wp))
+    w_q = _q(w_q, (d.C_out, d.C_in // d.groups))
+    acc = np.empty((d.N, d.C_in, Hp, Wp), np.int64)
+    cd = d._c()
+    _chk(_L().gf_ref_bwd_input_q8(C.byref(cd), _pq(gy_q), _pq(w_q), acc.ctypes.data_as(C.POINTER(C.c_longlong))),
+         "bwd_input_q8")
+    val = acc.astype(np.float32) * _scale32(d, scale)
+    if reduced_out:
+        return val
+    rx = d.r * d.stride
+    full = np.repeat(np.repeat(val, rx, axis=2), rx, axis=3)
+    return np.ascontiguousarray(full[:, :, :d.H_in, :d.W_in])
+
+
 def cost_model(d: Desc) -> dict:
     c = _Cost()
     cd = d._c()

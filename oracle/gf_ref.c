@@ -7,6 +7,7 @@
  */
 #include "gf_ref.h"
 
+#include <math.h>
 #include <stddef.h>
 #include <stdlib.h>
 #include <string.h>
@@ -330,6 +331,64 @@ int gf_ref_bwd_input(const gf_ref_desc* d, const double* gy_u, const double* w, 
                 g_x[(((size_t)n * d->C_in + ci) * d->H_in + h) * d->W_in + ww] = acc;
           }
         }
+    }
+  return REF_OK;
+}
+
+int gf_ref_quantize_q8(const double* v, long n, float inv_delta, signed char* q) {
+  if (!v || !q) return REF_NULL;
+  if (!(inv_delta > 0.0f)) return REF_BAD_DESC;
+  for (long i = 0; i < n; ++i) {
+    float t = (float)v[i] * inv_delta; /* binary32 product */
+    float r = rintf(t);                /* round half to even (default rounding mode) */
+    if (r > 127.0f) r = 127.0f;
+    if (r < -127.0f) r = -127.0f;
+    q[i] = (signed char)r;
+  }
+  return REF_OK;
+}
+
+int gf_ref_bwd_weight_q8(const gf_ref_desc* d, const signed char* x_q, const signed char* gy_q, long long* acc) {
+  int Hy, Wy, Hp, Wp;
+  int rc = gf_ref_out_shape(d, &Hy, &Wy, &Hp, &Wp);
+  if (rc) return rc;
+  if (!x_q || !gy_q || !acc) return REF_NULL;
+  if (d->r == 1) return REF_BAD_DESC; /* codes are defined for the reduced maps only */
+  int Cg = d->C_in / d->groups, Og = d->C_out / d->groups;
+  size_t P = (size_t)Hp * Wp;
+  for (int co = 0; co < d->C_out; ++co) {
+    int g = co / Og;
+    for (int cl = 0; cl < Cg; ++cl) {
+      int ci = g * Cg + cl;
+      long long a = 0;
+      for (int n = 0; n < d->N; ++n)
+        for (size_t q = 0; q < P; ++q)
+          a += (long long)x_q[((size_t)n * d->C_in + ci) * P + q] * (long long)gy_q[((size_t)n * d->C_out + co) * P + q];
+      acc[(size_t)co * Cg + cl] = a;
+    }
+  }
+  return REF_OK;
+}
+
+int gf_ref_bwd_input_q8(const gf_ref_desc* d, const signed char* gy_q, const signed char* w_q, long long* acc) {
+  int Hy, Wy, Hp, Wp;
+  int rc = gf_ref_out_shape(d, &Hy, &Wy, &Hp, &Wp);
+  if (rc) return rc;
+  if (!gy_q || !w_q || !acc) return REF_NULL;
+  if (d->r == 1) return REF_BAD_DESC;
+  int Cg = d->C_in / d->groups, Og = d->C_out / d->groups;
+  size_t P = (size_t)Hp * Wp;
+  for (int n = 0; n < d->N; ++n)
+    for (int ci = 0; ci < d->C_in; ++ci) {
+      int g = ci / Cg, cl = ci % Cg;
+      for (size_t q = 0; q < P; ++q) {
+        long long a = 0;
+        for (int ol = 0; ol < Og; ++ol) {
+          int co = g * Og + ol;
+          a += (long long)gy_q[((size_t)n * d->C_out + co) * P + q] * (long long)w_q[(size_t)co * Cg + cl];
+        }
+        acc[((size_t)n * d->C_in + ci) * P + q] = a;
+      }
     }
   return REF_OK;
 }

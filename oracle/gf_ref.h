@@ -88,6 +88,21 @@ int gf_ref_bwd_exact(const gf_ref_desc* d, const double* x, const double* w, con
 /* Forward convolution y = conv(x, theta) (Sec. 3.1), used to pin the backward. */
 int gf_ref_conv_fwd(const gf_ref_desc* d, const double* x, const double* w, double* y);
 
+/* ---- gradient filtering on 8-bit codes (Supp. H combines the method with 8-bit gradient
+ * quantisation but fixes no quantiser; reading taken here: one step size per tensor, symmetric
+ * signed codes, round half to even, clipped to +-127 -- the per-tensor scheme of the 8-bit training
+ * methods the supplement cites, without their stochastic rounding).  The reduced maps gy_u, x_u and
+ * the kernel sum are held as codes; Eq. 5 and Eq. 3 are then integer contractions, exact, and the
+ * caller scales the integer once by the product of the two step sizes (and 1/s^2). ---- */
+/* q[i] = clip(round_half_even((float)v[i] * inv_delta), -127, 127); the product and the rounding are
+ * taken in binary32, the precision in which the GPU kernels take the same decision. */
+int gf_ref_quantize_q8(const double* v, long n, float inv_delta, signed char* q);
+/* Eq. 5 on codes: acc[c_o, c_i'] = sum over (n, patch) of x_q * gy_q.  [C_out, C_in/groups], exact. */
+int gf_ref_bwd_weight_q8(const gf_ref_desc* d, const signed char* x_q, const signed char* gy_q, long long* acc);
+/* Eq. 3 on codes: acc[n, c_i, patch] = sum over the group's c_o of gy_q * w_q, w_q [C_out, C_in/groups]
+ * the codes of the kernel sum.  [N, C_in, H_p, W_p], exact. */
+int gf_ref_bwd_input_q8(const gf_ref_desc* d, const signed char* gy_q, const signed char* w_q, long long* acc);
+
 int gf_ref_cost_model(const gf_ref_desc* d, gf_ref_cost* out);
 
 /* Number of threads the OpenMP build will use (1 when built without OpenMP). */

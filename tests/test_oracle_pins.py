@@ -518,3 +518,96 @@ def test_descriptor_rejection(oracle):
             oracle.out_shape(D(oracle, **kw))
     # with r == 1 the unpadded layer is legal (exact BP has no grid rule)
     oracle.out_shape(D(oracle, **{**ok, "pad": 0, "r": 1}))
+
+
+# ---------------------------------------------------------------------------
+# gradient filtering on 8-bit codes (reading of Supp. H: per-tensor step size, round half to even,
+# clip to +-127, exact integer contractions)
+# ---------------------------------------------------------------------------
+def test_q8_codes_by_hand(oracle):
+    v = np.array([0.5, 1.5, -2.5, 2.5, 1000.0, -1000.0, 0.49, 126.5, 127.5, -0.5, 3.0])
+    #            ties go to the even code; values beyond the range are clipped, never -128
+    want = np.array([0, 2, -2, 2, 127, -127, 0, 126, 127, 0, 3], np.int8)
+    assert np.array_equal(oracle.quantize_q8(v, 1.0), want)
+    # the step size enters as its reciprocal: delta = 0.25
+    assert np.array_equal(oracle.quantize_q8(np.array([0.25, 0.3, -0.4, 40.0]), 4.0), np.array([1, 1, -2, 127], np.int8))
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_q8(v, 0.0)
+
+
+def test_q8_round_trip_error_is_half_a_step(oracle):
+    r_ = rng(81)
+    v = r_.standard_normal(5000) * 3.0
+    delta = float(np.abs(v).max() / 127.0)
+    q = oracle.quantize_q8(v, 1.0 / delta)
+    assert q.min() >= -127 and q.max() == 127 or q.min() == -127
+    assert np.abs(q.astype(np.float64) * delta - v).max() <= 0.5 * delta * (1 + 1e-5)
+
+
+@pytest.mark.parametrize("g,s", [(1, 1), (2, 1), (1, 2), (6, 1)])
+def test_q8_contractions_are_the_float_formulas_on_the_codes(oracle, g, s):
+    """Integer sums of products of small integers are exact in fp64 too: Eq. 5 / Eq. 3 of the
+    (independently pinned) fp64 oracle, fed the codes as numbers, must give the same integers."""
+    r_ = rng(82 + g + s)
+    N, Ci, Co, H, W, r = 2, 6, 12, 8, 12, 2
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=3, K_w=3, stride=s, pad=1, groups=g, r=r)
+    _, _, Hp, Wp = oracle.out_shape(d)
+    x_q = r_.integers(-127, 128, (N, Ci, Hp, Wp)).astype(np.int8)
+    gy_q = r_.integers(-127, 128, (N, Co, Hp, Wp)).astype(np.int8)
+    w_q = r_.integers(-127, 128, (Co, Ci // g)).astype(np.int8)
+    s2 = float(s * s)
+    gw8 = oracle.bwd_weight_q8(d, x_q, gy_q, 1.0)
+    ref = oracle.bwd_weight(d, x_q.astype(np.float64), gy_q.astype(np.float64))   # carries 1/s^2 already
+    assert gw8.dtype == np.float32 and np.array_equal(gw8.astype(np.float64), ref)
+    # Eq. 3 reads the kernel through its spatial sum only: a 1x1 layer whose kernel is the codes
+    d1 = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=1, K_w=1, stride=s, pad=0, groups=g, r=r)
+    for reduced in (True, False):
+        gx8 = oracle.bwd_input_q8(d, gy_q, w_q, 1.0, reduced_out=reduced)
+        ref = oracle.bwd_input(d1, gy_q.astype(np.float64), w_q.astype(np.float64)[:, :, None, None], reduced_out=reduced)
+        assert np.array_equal(gx8.astype(np.float64), ref), reduced
+    # the step-size product is one binary32 factor on the integer
+    gw_s = oracle.bwd_weight_q8(d, x_q, gy_q, 0.375)
+    assert np.array_equal(gw_s, (gw8 * np.float32(s2)) * (np.float32(0.375) / np.float32(s2)))
+
+
+def test_q8_contractions_brute_force(oracle):
+    r_ = rng(85)
+    N, Ci, Co, H, W, r, g = 1, 4, 6, 4, 6, 2, 2
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=1, K_w=1, groups=g, r=r)
+    Hp, Wp, Cg, Og = 2, 3, Ci // g, Co // g
+    x_q = r_.integers(-127, 128, (N, Ci, Hp, Wp)).astype(np.int8)
+    gy_q = r_.integers(-127, 128, (N, Co, Hp, Wp)).astype(np.int8)
+    w_q = r_.integers(-127, 128, (Co, Cg)).astype(np.int8)
+    gw = oracle.bwd_weight_q8(d, x_q, gy_q, 1.0)
+    gx = oracle.bwd_input_q8(d, gy_q, w_q, 1.0, reduced_out=True)
+    for co in range(Co):
+        for cl in range(Cg):
+            ci = (co // Og) * Cg + cl
+            want = sum(int(x_q[0, ci, i, j]) * int(gy_q[0, co, i, j]) for i in range(Hp) for j in range(Wp))
+            assert int(gw[co, cl, 0, 0]) == want
+    for ci in range(Ci):
+        grp, cl = ci // Cg, ci % Cg
+        for i in range(Hp):
+            for j in range(Wp):
+                want = sum(int(gy_q[0, grp * Og + ol, i, j]) * int(w_q[grp * Og + ol, cl]) for ol in range(Og))
+                assert int(gx[0, ci, i, j]) == want
+
+
+def test_q8_path_approaches_the_float_path(oracle):
+    """With the step sizes at max|.| / 127 the two gradients stay within a few step sizes' worth of
+    the unquantised Eq. 5 / Eq. 3 (errors of single codes are <= half a step and average out)."""
+    r_ = rng(86)
+    d = D(oracle, N=4, C_in=16, C_out=24, H_in=16, W_in=16, K_h=3, K_w=3, pad=1, r=2)
+    x = np.abs(r_.standard_normal((4, 16, 16, 16)))
+    gy = r_.standard_normal((4, 24, 16, 16))
+    w = r_.standard_normal((24, 16, 3, 3)) * 0.1
+    x_u, gy_u, ws = oracle.pool_activation(d, x), oracle.filter_grad(d, gy), oracle.kernel_sum(d, w)
+    dx, dg, dw = (float(np.abs(t).max() / 127.0) for t in (x_u, gy_u, ws))
+    x_q = oracle.pool_activation_q8(d, x, 1.0 / dx)
+    gy_q = oracle.filter_grad_q8(d, gy, 1.0 / dg)
+    w_q = oracle.kernel_sum_q8(d, w, 1.0 / dw)
+    assert np.array_equal(x_q, oracle.quantize_q8(x_u, 1.0 / dx))
+    gw8, gx8 = oracle.bwd_weight_q8(d, x_q, gy_q, dx * dg), oracle.bwd_input_q8(d, gy_q, w_q, dg * dw)
+    gw, gx = oracle.bwd_weight(d, x_u, gy_u), oracle.bwd_input(d, gy_u, w)
+    assert np.abs(gw8 - gw).max() <= 0.02 * np.abs(gw).max()
+    assert np.abs(gx8 - gx).max() <= 0.03 * np.abs(gx).max()
