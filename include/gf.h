@@ -77,7 +77,9 @@ typedef enum gf_op {
   GF_OP_BWD_EXACT = 2,
   GF_OP_BWD_FILTERED = 3,
   GF_OP_BWD_CHAINED = 4,
-  GF_OP_FILTER_SNR = 5
+  GF_OP_FILTER_SNR = 5,
+  GF_OP_BWD_WEIGHT_Q8 = 6,
+  GF_OP_BWD_INPUT_Q8 = 7
 } gf_op;
 
 /* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
@@ -194,6 +196,40 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
 gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const void* x_u,
                               const void* w, float* g_w, void* g_x, int reduced_out, const void* mask_u,
                               void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Gradient filtering on signed 8-bit codes.  Supp. H combines the method with 8-bit
+ * gradient quantisation and fixes no quantiser; the reading taken here is the per-tensor scheme
+ * of the 8-bit training methods it cites, without their stochastic rounding: a tensor v is held
+ * as codes q = clip(round_half_even(v * inv_delta), -127, 127) with ONE step size delta = 1 /
+ * inv_delta that the caller chooses (e.g. a running max|v| / 127).  The reduced maps and the
+ * kernel sum are held as codes, Eq. 5 and Eq. 3 become integer contractions, which are exact,
+ * and the integer is scaled once: `scale` is the product of the two step sizes, the library
+ * multiplies by 1/stride^2.  Codes are int8 tensors in the layout of the map they stand for,
+ * 16-byte aligned.  r == 1 (no reduced maps) and inv_delta <= 0: GF_ERR_UNSUPPORTED /
+ * GF_ERR_BAD_DESC.  The product and the rounding of the code are taken in fp32. ---- */
+
+/* S1 with code output: gy_q [N, C_out, H_p, W_p] = codes of the r x r patch means of g_y (Eq. 2). */
+gf_status gf_filter_grad_q8(const gf_conv_desc* desc, const void* g_y, float inv_delta, int8_t* gy_q,
+                            void* stream);
+
+/* S0 with code output: x_q [N, C_in, H_p, W_p] = codes of the r_x x r_x patch sums of x. */
+gf_status gf_pool_activation_q8(const gf_conv_desc* desc, const void* x, float inv_delta, int8_t* x_q,
+                                void* stream);
+
+/* S2 with code output: w_q [C_out, C_in/groups] = codes of the spatial kernel sums (text after Eq. 3). */
+gf_status gf_kernel_sum_q8(const gf_conv_desc* desc, const void* w, float inv_delta, int8_t* w_q,
+                           void* stream);
+
+/* Eq. 5 on codes: g_w[c_o, c_i, all taps] = float(sum over (n, patch) of x_q * gy_q) * scale / stride^2,
+ * the integer sum exact (64 bits), converted and scaled in fp32.  ws: GF_OP_BWD_WEIGHT_Q8. */
+gf_status gf_conv_bwd_weight_q8(const gf_conv_desc* desc, const int8_t* x_q, const int8_t* gy_q, float scale,
+                                float* g_w, void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 3 on codes: g_x = float(sum over the group's c_o of gy_q * w_q) * scale / stride^2, rounded once
+ * to the storage type; every pixel of an input-side patch receives its patch's value, or, with
+ * reduced_out != 0, one value per patch is written ([N, C_in, H_p, W_p]).  ws: GF_OP_BWD_INPUT_Q8. */
+gf_status gf_conv_bwd_input_q8(const gf_conv_desc* desc, const int8_t* gy_q, const int8_t* w_q, float scale,
+                               void* g_x, int reduced_out, void* ws, size_t ws_bytes, void* stream);
 
 /* Vanilla back-propagation of the layer (Sec. 3.1): g_w = g_y (F) x and
  * g_x = g_y (*) rot180(w), zero padding, with stride, dilation and groups.

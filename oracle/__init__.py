@@ -259,7 +259,7 @@ def bwd_weight_q8(d: Desc, x_q, gy_q, scale: float) -> np.ndarray:
     _chk(_L().gf_ref_bwd_weight_q8(C.byref(cd), _pq(x_q), _pq(gy_q), acc.ctypes.data_as(C.POINTER(C.c_longlong))),
          "bwd_weight_q8")
     val = acc.astype(np.float32) * _scale32(d, scale)
-    return np.ascontiguousarray(np.broadcast_to(val[:, :, None, None], w_shape(d)))
+    return np.broadcast_to(val[:, :, None, None], w_shape(d)).copy()
 
 
 def bwd_input_q8(d: Desc, gy_q, w_q, scale: float, reduced_out: bool = False) -> np.ndarray:

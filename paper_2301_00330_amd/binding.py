@@ -18,11 +18,14 @@ GF_ERR_NULL, GF_ERR_BAD_DESC, GF_ERR_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE
 GF_F32, GF_BF16 = 0, 1
 GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BWD_CHAINED = 0, 1, 2, 3, 4
 GF_OP_FILTER_SNR = 5
+GF_OP_BWD_WEIGHT_Q8, GF_OP_BWD_INPUT_Q8 = 6, 7
 
 EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_mask", "gf_filter_grad",
            "gf_filter_grad_snr",
            "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_chained",
            "gf_conv_bwd_exact",
+           "gf_filter_grad_q8", "gf_pool_activation_q8", "gf_kernel_sum_q8", "gf_conv_bwd_weight_q8",
+           "gf_conv_bwd_input_q8",
            "gf_cost_model",
            "gf_status_string", "gf_version")
 
@@ -96,6 +99,11 @@ def lib() -> C.CDLL:
         L.gf_conv_bwd_filtered.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_chained.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.gf_pool_activation_mask.argtypes = [dp, vp, C.c_float, vp, vp, vp]
+        L.gf_filter_grad_q8.argtypes = [dp, vp, C.c_float, vp, vp]
+        L.gf_pool_activation_q8.argtypes = [dp, vp, C.c_float, vp, vp]
+        L.gf_kernel_sum_q8.argtypes = [dp, vp, C.c_float, vp, vp]
+        L.gf_conv_bwd_weight_q8.argtypes = [dp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+        L.gf_conv_bwd_input_q8.argtypes = [dp, vp, vp, C.c_float, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_cost_model.argtypes = [dp, C.POINTER(_Cost)]
         L.gf_status_string.argtypes = [C.c_int]
         L.gf_status_string.restype = C.c_char_p
@@ -191,6 +199,35 @@ def gf_conv_bwd_exact(d: ConvDesc, x: int, w: int, g_y: int, g_w: int, g_x: int,
     cd = d.c()
     _chk(lib().gf_conv_bwd_exact(C.byref(cd), x, w, g_y, g_w, g_x, ws, ws_bytes, stream),
          "gf_conv_bwd_exact")
+
+
+def gf_filter_grad_q8(d: ConvDesc, g_y: int, inv_delta: float, gy_q: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_filter_grad_q8(C.byref(cd), g_y, inv_delta, gy_q, stream), "gf_filter_grad_q8")
+
+
+def gf_pool_activation_q8(d: ConvDesc, x: int, inv_delta: float, x_q: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_pool_activation_q8(C.byref(cd), x, inv_delta, x_q, stream), "gf_pool_activation_q8")
+
+
+def gf_kernel_sum_q8(d: ConvDesc, w: int, inv_delta: float, w_q: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_kernel_sum_q8(C.byref(cd), w, inv_delta, w_q, stream), "gf_kernel_sum_q8")
+
+
+def gf_conv_bwd_weight_q8(d: ConvDesc, x_q: int, gy_q: int, scale: float, g_w: int, ws: int, ws_bytes: int,
+                          stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_conv_bwd_weight_q8(C.byref(cd), x_q, gy_q, scale, g_w, ws, ws_bytes, stream),
+         "gf_conv_bwd_weight_q8")
+
+
+def gf_conv_bwd_input_q8(d: ConvDesc, gy_q: int, w_q: int, scale: float, g_x: int, reduced_out: bool, ws: int,
+                         ws_bytes: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_conv_bwd_input_q8(C.byref(cd), gy_q, w_q, scale, g_x, int(bool(reduced_out)), ws, ws_bytes,
+                                    stream), "gf_conv_bwd_input_q8")
 
 
 def gf_cost_model(d: ConvDesc) -> dict:

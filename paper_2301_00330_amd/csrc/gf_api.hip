@@ -97,6 +97,10 @@ static size_t ws_need(const Geom& g, int op, bool reduced_out) {
       return ws_chained(g, nullptr);
     case GF_OP_FILTER_SNR:
       return (size_t)patch_reduce_max_blocks((long)g.N * g.Co, g.Hy, g.Wy, g.r) * 2 * sizeof(float);
+    case GF_OP_BWD_WEIGHT_Q8:
+      return ws_bwd_weight_q8(g);
+    case GF_OP_BWD_INPUT_Q8:
+      return ws_bwd_input_q8(g, reduced_out);
     case GF_OP_BWD_WEIGHT:
       return g.r == 1 ? ws_exact(g, true, false) : ws_bwd_weight(g);
     case GF_OP_BWD_INPUT:
@@ -148,7 +152,8 @@ gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int
 
 gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
   if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT &&
-      op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED && op != GF_OP_FILTER_SNR)
+      op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED && op != GF_OP_FILTER_SNR &&
+      op != GF_OP_BWD_WEIGHT_Q8 && op != GF_OP_BWD_INPUT_Q8)
     return GF_ERR_BAD_DESC;
   if (!desc) return GF_ERR_NULL;
   gf_conv_desc d1;
@@ -189,6 +194,71 @@ gf_status gf_filter_grad(const gf_conv_desc* desc, const void* g_y, void* gy_u, 
   if (g.r == 1)
     return dev(hipMemcpyAsync(gy_u, g_y, (size_t)planes * g.Hy * g.Wy * g.b, hipMemcpyDeviceToDevice, st));
   return dev(launch_patch_reduce(g_y, gy_u, planes, g.Hy, g.Wy, g.r, true, g.dtype, st));
+}
+
+// descriptor and step-size checks common to the entry points on 8-bit codes
+static gf_status q8_geom(const gf_conv_desc* desc, float factor, Geom* g) {
+  gf_status rc = make_geom(desc, g);
+  if (rc) return rc;
+  if (!(factor > 0.f) || factor > 3.0e38f) return GF_ERR_BAD_DESC;   // also rejects NaN and infinity
+  if (!q8_shape_ok(*g)) return GF_ERR_UNSUPPORTED;
+  return GF_OK;
+}
+
+gf_status gf_filter_grad_q8(const gf_conv_desc* desc, const void* g_y, float inv_delta, int8_t* gy_q,
+                            void* stream) {
+  Geom g;
+  gf_status rc = q8_geom(desc, inv_delta, &g);
+  if (rc) return rc;
+  if (!g_y || !gy_q) return GF_ERR_NULL;
+  if (!aligned16(g_y) || !aligned16(gy_q)) return GF_ERR_UNSUPPORTED;
+  return dev(launch_patch_reduce_q8(g_y, gy_q, (long)g.N * g.Co, g.Hy, g.Wy, g.r, true, inv_delta, g.dtype,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+gf_status gf_pool_activation_q8(const gf_conv_desc* desc, const void* x, float inv_delta, int8_t* x_q,
+                                void* stream) {
+  Geom g;
+  gf_status rc = q8_geom(desc, inv_delta, &g);
+  if (rc) return rc;
+  if (!x || !x_q) return GF_ERR_NULL;
+  if (!aligned16(x) || !aligned16(x_q)) return GF_ERR_UNSUPPORTED;
+  return dev(launch_patch_reduce_q8(x, x_q, (long)g.N * g.Ci, g.H, g.W, g.rx, false, inv_delta, g.dtype,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+gf_status gf_kernel_sum_q8(const gf_conv_desc* desc, const void* w, float inv_delta, int8_t* w_q,
+                           void* stream) {
+  Geom g;
+  gf_status rc = q8_geom(desc, inv_delta, &g);
+  if (rc) return rc;
+  if (!w || !w_q) return GF_ERR_NULL;
+  if (!aligned16(w) || !aligned16(w_q)) return GF_ERR_UNSUPPORTED;
+  return dev(launch_kernel_sum_q8(g, w, inv_delta, w_q, static_cast<hipStream_t>(stream)));
+}
+
+gf_status gf_conv_bwd_weight_q8(const gf_conv_desc* desc, const int8_t* x_q, const int8_t* gy_q, float scale,
+                                float* g_w, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = q8_geom(desc, scale, &g);
+  if (rc) return rc;
+  if (!x_q || !gy_q || !g_w) return GF_ERR_NULL;
+  if (!aligned16(x_q) || !aligned16(gy_q) || !aligned16(g_w)) return GF_ERR_UNSUPPORTED;
+  rc = check_ws(ws_bwd_weight_q8(g), ws, ws_bytes);
+  if (rc) return rc;
+  return dev(launch_bwd_weight_q8(g, x_q, gy_q, scale, g_w, ws, static_cast<hipStream_t>(stream)));
+}
+
+gf_status gf_conv_bwd_input_q8(const gf_conv_desc* desc, const int8_t* gy_q, const int8_t* w_q, float scale,
+                               void* g_x, int reduced_out, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = q8_geom(desc, scale, &g);
+  if (rc) return rc;
+  if (!gy_q || !w_q || !g_x) return GF_ERR_NULL;
+  if (!aligned16(gy_q) || !aligned16(w_q) || !aligned16(g_x)) return GF_ERR_UNSUPPORTED;
+  rc = check_ws(ws_bwd_input_q8(g, reduced_out != 0), ws, ws_bytes);
+  if (rc) return rc;
+  return dev(launch_bwd_input_q8(g, gy_q, w_q, scale, g_x, reduced_out != 0, ws, static_cast<hipStream_t>(stream)));
 }
 
 gf_status gf_conv_bwd_weight(const gf_conv_desc* desc, const void* x_u, const void* gy_u,

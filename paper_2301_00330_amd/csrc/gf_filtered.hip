@@ -704,6 +704,15 @@ static hipError_t bwd_input_t(const Geom& g, const T* gy_u, const T* w, T* g_x, 
   return launch_expand<T, float>(red, g_x, nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
 }
 
+hipError_t launch_expand_f32(const Geom& g, const float* red, void* g_x, hipStream_t st) {
+  const long planes = (long)g.N * g.Ci;
+  if (g.dtype == GF_BF16)
+    return launch_expand<bf16_t, float>(red, static_cast<bf16_t*>(g_x), nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx,
+                                        g.Hp, g.Wp, st);
+  return launch_expand<float, float>(red, static_cast<float*>(g_x), nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx, g.Hp,
+                                     g.Wp, st);
+}
+
 hipError_t launch_gf_bwd_input(const Geom& g, const void* gy_u, const void* w, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st) {
   if (g.dtype == GF_BF16)

@@ -129,6 +129,21 @@ struct KsumJob {
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
                                bool mean, int dtype, hipStream_t st, const KsumJob* ksum = nullptr);
 
+// ---- 8-bit codes (gf_q8.hip; the reductions with code output live in gf_reduce.hip) ----
+// S0 / S1 with the result as signed 8-bit codes: round_half_even(value * inv_delta), clipped to +-127
+hipError_t launch_patch_reduce_q8(const void* in, int8_t* out_q, long planes, int H, int W, int q, bool mean,
+                                  float inv_delta, int dtype, hipStream_t st);
+bool q8_shape_ok(const Geom& g);
+hipError_t launch_kernel_sum_q8(const Geom& g, const void* w, float inv_delta, int8_t* w_q, hipStream_t st);
+size_t ws_bwd_weight_q8(const Geom& g);
+size_t ws_bwd_input_q8(const Geom& g, bool reduced_out);
+hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* gy_q, float scale, float* g_w,
+                                void* ws, hipStream_t st);
+hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float scale, void* g_x,
+                               bool reduced_out, void* ws, hipStream_t st);
+// full-resolution g_x from an fp32 reduced map [N, C_in, H_p, W_p] (rounded once to the storage type)
+hipError_t launch_expand_f32(const Geom& g, const float* red, void* g_x, hipStream_t st);
+
 // S1 with the noise figures of the filter: gy_u as launch_patch_reduce(mean), plus
 // stats[0] = sum g_y^2 and stats[1] = sum (g_y - patch mean)^2 (doubles, device memory);
 // `part` holds patch_reduce_max_blocks() float pairs.

@@ -1,0 +1,303 @@
+// Gradient filtering on signed 8-bit codes (Supp. H combines the method with 8-bit gradient
+// quantisation).  The reduced maps gy_u and x_u and the kernel sum are held as codes with one step
+// size per tensor (round half to even, clipped to +-127); Eq. 5 and Eq. 3 then are integer
+// contractions, which are exact, and the integer is scaled once by the product of the two step
+// sizes and 1/s^2.
+//
+//  * kernel_sum_q8_k   -- codes of the spatial kernel sum (text after Eq. 3)
+//  * q8_wgrad_mfma_k   -- Eq. 5 for dense layers whose reduced plane is a multiple of 16 patches:
+//                         v_mfma_i32_16x16x64_i8 on 64 x 64 tiles, K = (n, patch) split into slabs,
+//                         int32 partial slabs (a slab holds few enough products not to overflow),
+//                         q8_finalize_k adds them in 64 bits and scales
+//  * q8_wgrad_pair_k   -- Eq. 5 for every other layer (groups, depthwise, unaligned planes): one
+//                         block per (c_o, c_i) pair, 64-bit sums
+//  * q8_dgrad_k        -- Eq. 3: one lane per (n, c_i, patch), the group's c_o walked in the lane;
+//                         writes the reduced map (storage type) or an fp32 map that the expansion
+//                         kernel of the floating-point path replicates to full resolution
+#include "gf_internal.h"
+
+namespace gf {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowBytes = 128 + 16;  // one staged row: 128 codes (K) + pad
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int8_t q8_code(float v, float inv) {
+  const float r = fminf(fmaxf(__builtin_rintf(v * inv), -127.f), 127.f);
+  return (int8_t)(int)r;
+}
+
+template <class T>
+__global__ __launch_bounds__(kThreads) void kernel_sum_q8_k(const T* w, int8_t* w_q, int pairs, int KK, float inv) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e < pairs) w_q[e] = q8_code(kernel_sum_of(w, e, KK), inv);
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 5, dense, P % 16 == 0: part[z, co, ci] = sum over the K chunks of slab z of gy_q * x_q
+// ---------------------------------------------------------------------------
+struct Q8WgradArgs {
+  const int8_t* gyq;
+  const int8_t* xq;
+  int* part;
+  int Ci, Co, P, Ktot;
+  int nchunks, chunks_per_z;
+  FastDiv d_p;
+};
+
+// 16 codes of row `base` (one channel of every image, images img_stride apart) from flat column
+// k = (n, p), k a multiple of 16 (a vector never leaves its image because 16 | P); zero beyond ktot
+__device__ __forceinline__ uint4 load_codes(const int8_t* base, long img_stride, int k, int ktot, int P,
+                                            const FastDiv& d_p) {
+  const int kc = min(k, ktot - 16);
+  const int n = (int)d_p.div((uint32_t)kc);
+  const int p = kc - n * P;
+  const uint4 v = *reinterpret_cast<const uint4*>(base + (long)n * img_stride + p);
+  return k < ktot ? v : make_uint4(0, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(kThreads) void q8_wgrad_mfma_k(Q8WgradArgs a) {
+  constexpr int BM = 64, BN = 64, BK = 128;
+  __shared__ __attribute__((aligned(16))) unsigned char As[BM * kRowBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * kRowBytes];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int kc0 = blockIdx.z * a.chunks_per_z;
+  const int kc1 = min(kc0 + a.chunks_per_z, a.nchunks);
+  uint4 ra[2], rb[2];
+  auto fetch = [&](int kc) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
+      const int co = m0 + row, ci = n0 + row;
+      const uint4 va = load_codes(a.gyq + (long)min(co, a.Co - 1) * a.P, (long)a.Co * a.P, kc * BK + vi * 16,
+                                  a.Ktot, a.P, a.d_p);
+      const uint4 vb = load_codes(a.xq + (long)min(ci, a.Ci - 1) * a.P, (long)a.Ci * a.P, kc * BK + vi * 16,
+                                  a.Ktot, a.P, a.d_p);
+      ra[i] = co < a.Co ? va : make_uint4(0, 0, 0, 0);
+      rb[i] = ci < a.Ci ? vb : make_uint4(0, 0, 0, 0);
+    }
+  };
+  i32x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = i32x4{0, 0, 0, 0};
+  if (kc0 < kc1) fetch(kc0);
+  const int r = lane & 15, kg = lane >> 4;
+  for (int kc = kc0; kc < kc1; ++kc) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int s = tid + i * kThreads;
+      *reinterpret_cast<uint4*>(As + (s >> 3) * kRowBytes + (s & 7) * 16) = ra[i];
+      *reinterpret_cast<uint4*>(Bs + (s >> 3) * kRowBytes + (s & 7) * 16) = rb[i];
+    }
+    __syncthreads();
+    if (kc + 1 < kc1) fetch(kc + 1);
+    // A: lane holds row lane % 16, k = 16 * (lane / 16) .. + 15 of the 64-wide k-step; B alike
+#pragma unroll
+    for (int ks = 0; ks < BK / 64; ++ks) {
+      i32x4 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        fa[i] = *reinterpret_cast<const i32x4*>(As + ((wm * 2 + i) * 16 + r) * kRowBytes + ks * 64 + kg * 16);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        fb[j] = *reinterpret_cast<const i32x4*>(Bs + ((wn * 2 + j) * 16 + r) * kRowBytes + ks * 64 + kg * 16);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  // D[i = 4 * (lane / 16) + v][j = lane % 16] of every 16 x 16 tile
+  int* dst = a.part + (long)blockIdx.z * a.Co * a.Ci;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int ci = n0 + (wn * 2 + j) * 16 + (lane & 15);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int co = m0 + (wm * 2 + i) * 16 + 4 * (lane >> 4) + v;
+        if (co < a.Co && ci < a.Ci) dst[(long)co * a.Ci + ci] = acc[i][j][v];
+      }
+    }
+}
+
+// g_w[pair, all taps] = float(sum over the slabs, 64 bits) * scale
+__global__ __launch_bounds__(kThreads) void q8_finalize_k(const int* part, float* g_w, int pairs, int nz, int KK,
+                                                         float scale) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= pairs) return;
+  long long s = 0;
+  for (int z = 0; z < nz; ++z) s += part[(long)z * pairs + e];
+  const float v = (float)s * scale;
+  for (int t = 0; t < KK; ++t) g_w[(long)e * KK + t] = v;
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 5, any layer: block = one (c_o, c_i') pair
+// ---------------------------------------------------------------------------
+struct Q8PairArgs {
+  const int8_t* gyq;
+  const int8_t* xq;
+  float* g_w;
+  int N, Ci, Co, Cg, Og, P, KK;
+  float scale;
+};
+
+__global__ __launch_bounds__(kThreads) void q8_wgrad_pair_k(Q8PairArgs a) {
+  __shared__ long long red[kThreads / 64];
+  const int pair = blockIdx.x;
+  const int co = pair / a.Cg, cl = pair - co * a.Cg;
+  const int ci = (co / a.Og) * a.Cg + cl;
+  long long s = 0;
+  for (int n = 0; n < a.N; ++n) {
+    const int8_t* gp = a.gyq + ((long)n * a.Co + co) * a.P;
+    const int8_t* xp = a.xq + ((long)n * a.Ci + ci) * a.P;
+    int part = 0;   // |product| <= 127^2: a lane adds at most P / 256 + 1 of them per image
+    for (int p = threadIdx.x; p < a.P; p += kThreads) part += (int)gp[p] * (int)xp[p];
+    s += part;
+  }
+  for (int m = 32; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long t = 0;
+    for (int k = 0; k < kThreads / 64; ++k) t += red[k];
+    const float v = (float)t * a.scale;
+    for (int k = 0; k < a.KK; ++k) a.g_w[(long)pair * a.KK + k] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 3: dst[n, ci, p] = float(sum over the group's c_o of gy_q[n, co, p] * w_q[co, cl]) * scale
+// ---------------------------------------------------------------------------
+struct Q8DgradArgs {
+  const int8_t* gyq;
+  const int8_t* wq;
+  void* dst;
+  int N, Ci, Co, Cg, Og, P;
+  long total;   // N * Ci * P
+  float scale;
+  FastDiv d_p, d_ci;
+};
+
+template <class D>
+__global__ __launch_bounds__(kThreads) void q8_dgrad_k(Q8DgradArgs a) {
+  const long e = (long)blockIdx.x * kThreads + threadIdx.x;
+  if (e >= a.total) return;
+  const int plane = (int)a.d_p.div((uint32_t)e);   // n * Ci + ci   (total < 2^31, checked on the host)
+  const int p = (int)e - plane * a.P;
+  const int n = (int)a.d_ci.div((uint32_t)plane);
+  const int ci = plane - n * a.Ci;
+  const int grp = ci / a.Cg, cl = ci - grp * a.Cg;
+  const int8_t* gp = a.gyq + ((long)n * a.Co + (long)grp * a.Og) * a.P + p;
+  const int8_t* wp = a.wq + (long)grp * a.Og * a.Cg + cl;
+  int acc = 0;   // Og * 127^2 < 2^31 for Og <= 133 000 (checked on the host)
+  for (int ol = 0; ol < a.Og; ++ol) acc += (int)gp[(long)ol * a.P] * (int)wp[(long)ol * a.Cg];
+  static_cast<D*>(a.dst)[e] = from_f32<D>((float)acc * a.scale);
+}
+
+}  // namespace
+
+// most products an int32 sum can take: 127^2 * n < 2^31
+constexpr long kMaxTerms32 = 133000;
+
+hipError_t launch_kernel_sum_q8(const Geom& g, const void* w, float inv_delta, int8_t* w_q, hipStream_t st) {
+  const int pairs = g.Co * g.Cg;
+  const dim3 grid(cdiv(pairs, kThreads)), block(kThreads);
+  if (g.dtype == GF_BF16)
+    hipLaunchKernelGGL(kernel_sum_q8_k<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(w), w_q, pairs, g.KK, inv_delta);
+  else
+    hipLaunchKernelGGL(kernel_sum_q8_k<float>, grid, block, 0, st, static_cast<const float*>(w), w_q, pairs, g.KK, inv_delta);
+  return hipGetLastError();
+}
+
+static bool q8_wgrad_mfma_ok(const Geom& g) { return g.g == 1 && g.P % 16 == 0 && g.Co >= 16 && g.Ci >= 16; }
+
+// K slabs of the MFMA kernel: ~1024 blocks, at least two chunks per block, and few enough
+// products per slab for the int32 partial sums
+static int q8_wgrad_splits(const Geom& g, int* chunks_per_z) {
+  const int nchunks = cdiv((long)g.N * g.P, 128);
+  const int tiles = cdiv(g.Co, 64) * cdiv(g.Ci, 64);
+  int nz = cdiv(1024, tiles);
+  if (nz > cdiv(nchunks, 2)) nz = cdiv(nchunks, 2);
+  if (nz < 1) nz = 1;
+  int cpz = cdiv(nchunks, nz);
+  if ((long)cpz * 128 > kMaxTerms32) cpz = (int)(kMaxTerms32 / 128);
+  *chunks_per_z = cpz;
+  return cdiv(nchunks, cpz);
+}
+
+size_t ws_bwd_weight_q8(const Geom& g) {
+  if (!q8_wgrad_mfma_ok(g)) return 0;
+  int cpz;
+  return (size_t)q8_wgrad_splits(g, &cpz) * g.Co * g.Ci * sizeof(int);
+}
+
+hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* gy_q, float scale, float* g_w,
+                                void* ws, hipStream_t st) {
+  const float fscale = scale / ((float)g.s * (float)g.s);
+  if (q8_wgrad_mfma_ok(g)) {
+    Q8WgradArgs a;
+    a.gyq = gy_q; a.xq = x_q; a.part = static_cast<int*>(ws);
+    a.Ci = g.Ci; a.Co = g.Co; a.P = g.P; a.Ktot = g.N * g.P;
+    a.nchunks = cdiv((long)g.N * g.P, 128);
+    const int nz = q8_wgrad_splits(g, &a.chunks_per_z);
+    a.d_p = FastDiv((uint32_t)g.P);
+    hipLaunchKernelGGL(q8_wgrad_mfma_k, dim3(cdiv(g.Ci, 64), cdiv(g.Co, 64), nz), dim3(kThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int pairs = g.Co * g.Ci;
+    hipLaunchKernelGGL(q8_finalize_k, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, a.part, g_w, pairs, nz, g.KK,
+                       fscale);
+    return hipGetLastError();
+  }
+  Q8PairArgs a;
+  a.gyq = gy_q; a.xq = x_q; a.g_w = g_w;
+  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P; a.KK = g.KK;
+  a.scale = fscale;
+  hipLaunchKernelGGL(q8_wgrad_pair_k, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+// the input gradient at full resolution goes through an fp32 reduced map in the workspace
+size_t ws_bwd_input_q8(const Geom& g, bool reduced_out) {
+  return reduced_out ? 0 : (size_t)g.N * g.Ci * g.P * sizeof(float);
+}
+
+bool q8_shape_ok(const Geom& g) {
+  // 64-bit sums where they are long; the int32 sums of q8_dgrad_k and q8_wgrad_pair_k stay in range
+  return g.r > 1 && g.Og <= kMaxTerms32 && (long)(g.P / kThreads + 1) <= kMaxTerms32;
+}
+
+hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float scale, void* g_x,
+                               bool reduced_out, void* ws, hipStream_t st) {
+  Q8DgradArgs a;
+  a.gyq = gy_q; a.wq = w_q;
+  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P;
+  a.total = (long)g.N * g.Ci * g.P;
+  a.scale = scale / ((float)g.s * (float)g.s);
+  a.d_p = FastDiv((uint32_t)g.P);
+  a.d_ci = FastDiv((uint32_t)g.Ci);
+  const dim3 grid(cdiv(a.total, kThreads)), block(kThreads);
+  if (reduced_out) {
+    a.dst = g_x;
+    if (g.dtype == GF_BF16) hipLaunchKernelGGL(q8_dgrad_k<bf16_t>, grid, block, 0, st, a);
+    else hipLaunchKernelGGL(q8_dgrad_k<float>, grid, block, 0, st, a);
+    return hipGetLastError();
+  }
+  a.dst = ws;
+  hipLaunchKernelGGL(q8_dgrad_k<float>, grid, block, 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_expand_f32(g, static_cast<const float*>(ws), g_x, st);
+}
+
+}  // namespace gf

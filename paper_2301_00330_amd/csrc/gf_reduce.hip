@@ -19,7 +19,7 @@ namespace {
 
 constexpr int kThreads = 256;
 // what a reduction launch produces beside the patch sums / means
-constexpr int kPlain = 0, kStats = 1, kMask = 2;
+constexpr int kPlain = 0, kStats = 1, kMask = 2, kQ8 = 3;
 constexpr int kLdsBudget = 32 * 1024;  // per block: 5 blocks fit a CU's 160 KB
 constexpr int kLdsMax = 64 * 1024;
 
@@ -43,7 +43,15 @@ struct ReduceArgs {
   // kMask kernels: out2[patch] = fraction of the patch's in-bounds elements with 0 < v < mask_hi
   void* out2;
   float mask_hi;
+  // kQ8 kernels: `out` holds signed 8-bit codes of the patch sum / mean (see q8_code), q_inv = 1 / step size
+  float q_inv;
 };
+
+// code of a value on a grid of step 1 / inv: round half to even, clipped to +-127 (never -128)
+__device__ __forceinline__ int8_t q8_code(float v, float inv) {
+  const float r = fminf(fmaxf(__builtin_rintf(v * inv), -127.f), 127.f);
+  return (int8_t)(int)r;
+}
 
 // Fixed-order sum over the block of two floats per lane; block 0's lane 0 ... every block's
 // lane 0 writes its pair.  `red` is 2 * (kThreads / 64) floats of LDS.
@@ -177,6 +185,12 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
 #pragma unroll
       for (int o = 0; o < NOUT; ++o) d2[o] = frac[o];
     }
+    if constexpr (MODE == kQ8) {
+      int8_t* d8 = static_cast<int8_t*>(a.out) + (long)strip[u] * a.Wp + col[u] * NOUT;
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) d8[o] = q8_code(mean[o], a.q_inv);
+      continue;
+    }
     T* dst = out + (long)strip[u] * a.Wp + col[u] * NOUT;
     if constexpr (NOUT * sizeof(T) == 8) {
       store_stream8(dst, *reinterpret_cast<const uint2*>(res));
@@ -265,7 +279,10 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
         acc += ok ? val : 0.f;
       }
     if (a.mean) acc = acc / (float)(ch * cw);
-    out[s0 * a.Wp + lo] = from_f32<T>(acc);
+    if constexpr (MODE == kQ8)
+      static_cast<int8_t*>(a.out)[s0 * a.Wp + lo] = q8_code(acc, a.q_inv);
+    else
+      out[s0 * a.Wp + lo] = from_f32<T>(acc);
     if constexpr (MODE == kMask) {
       float cnt = 0.f;
 #pragma unroll UQ
@@ -317,7 +334,10 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_direct(ReduceArgs a) {
     for (int i = 0; i < ch; ++i)
       for (int j = 0; j < cw; ++j) acc += to_f32(p[(long)i * a.W + j]);
     if (a.mean) acc = acc / (float)(ch * cw);
-    out[o] = from_f32<T>(acc);
+    if constexpr (MODE == kQ8)
+      static_cast<int8_t*>(a.out)[o] = q8_code(acc, a.q_inv);
+    else
+      out[o] = from_f32<T>(acc);
     if constexpr (MODE == kMask) {
       float cnt = 0.f;
       for (int i = 0; i < ch; ++i)
@@ -368,7 +388,7 @@ __global__ __launch_bounds__(kFinalThreads) void stats_final_k(const float2* par
   }
 }
 
-template <class T, int Q>
+template <class T, int Q, int MODE>
 hipError_t launch_rows(ReduceArgs& a, hipStream_t st, int* nblocks) {
   constexpr int VE = Vec16<T>::N;
   constexpr int IW = VE > Q ? VE : Q;
@@ -378,12 +398,8 @@ hipError_t launch_rows(ReduceArgs& a, hipStream_t st, int* nblocks) {
   a.d_ipr = FastDiv((uint32_t)a.ipr);
   const int blocks = cdiv(a.total_items, kThreads * U);
   a.ks_block0 = blocks;
-  if (a.stats_part)
-    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, kStats>), dim3(blocks), dim3(kThreads), 0, st, a);
-  else if (a.out2)
-    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, kMask>), dim3(blocks), dim3(kThreads), 0, st, a);
-  else
-    hipLaunchKernelGGL((patch_reduce_rows<T, Q, U>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+  // the kernel-sum side job (plain mode only) runs in extra blocks at the end of the grid
+  hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, MODE>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
   *nblocks = blocks;
   return hipGetLastError();
 }
@@ -396,13 +412,14 @@ bool rows_ok(int W, int q) {
   return W % IW == 0 && (W * (int)sizeof(T)) % 16 == 0;
 }
 
-// *nblocks: the number of reduction blocks launched (side-job blocks not counted)
-template <class T>
-hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
+// One reduction launch in mode MODE.  *nblocks: the number of reduction blocks launched
+// (side-job blocks not counted)
+template <class T, int MODE>
+hipError_t launch_mode(ReduceArgs& a, hipStream_t st, int* nblocks) {
   if (rows_ok<T>(a.W, a.q) && (long)a.total_strips * (a.W / 4) < 2147483647L) {
-    if (a.q == 2) return launch_rows<T, 2>(a, st, nblocks);
-    if (a.q == 4) return launch_rows<T, 4>(a, st, nblocks);
-    return launch_rows<T, 8>(a, st, nblocks);
+    if (a.q == 2) return launch_rows<T, 2, MODE>(a, st, nblocks);
+    if (a.q == 4) return launch_rows<T, 4, MODE>(a, st, nblocks);
+    return launch_rows<T, 8, MODE>(a, st, nblocks);
   }
   const long strip_bytes = (long)imin_host(a.q, a.H) * a.W * (long)sizeof(T);
   if (strip_bytes + 32 > kLdsMax) {
@@ -411,12 +428,7 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
     int blocks = (int)((nout + kThreads - 1) / kThreads);
     if (blocks > 65536) blocks = 65536;
     a.ks_block0 = blocks;
-    if (a.stats_part)
-      hipLaunchKernelGGL((patch_reduce_direct<T, kStats>), dim3(blocks), dim3(kThreads), 0, st, a);
-    else if (a.out2)
-      hipLaunchKernelGGL((patch_reduce_direct<T, kMask>), dim3(blocks), dim3(kThreads), 0, st, a);
-    else
-      hipLaunchKernelGGL(patch_reduce_direct<T>, dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((patch_reduce_direct<T, MODE>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
     *nblocks = blocks;
     return hipGetLastError();
   }
@@ -431,36 +443,25 @@ hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
   const int blocks = (a.total_strips + spb - 1) / spb;
   a.ks_block0 = blocks;
   *nblocks = blocks;
-  if (a.stats_part) {
-    const dim3 sgrid(blocks);
-    if (a.q == 2)
-      hipLaunchKernelGGL((patch_reduce_lds<T, 2, kStats>), sgrid, dim3(kThreads), lds, st, a);
-    else if (a.q == 4)
-      hipLaunchKernelGGL((patch_reduce_lds<T, 4, kStats>), sgrid, dim3(kThreads), lds, st, a);
-    else
-      hipLaunchKernelGGL((patch_reduce_lds<T, 0, kStats>), sgrid, dim3(kThreads), lds, st, a);
-    return hipGetLastError();
-  }
-  if (a.out2) {
-    const dim3 sgrid(blocks);
-    if (a.q == 2)
-      hipLaunchKernelGGL((patch_reduce_lds<T, 2, kMask>), sgrid, dim3(kThreads), lds, st, a);
-    else if (a.q == 4)
-      hipLaunchKernelGGL((patch_reduce_lds<T, 4, kMask>), sgrid, dim3(kThreads), lds, st, a);
-    else
-      hipLaunchKernelGGL((patch_reduce_lds<T, 0, kMask>), sgrid, dim3(kThreads), lds, st, a);
-    return hipGetLastError();
-  }
   const dim3 grid(blocks + cdiv(a.ks_pairs, kThreads));
   if (a.q == 2)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 2>), grid, dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 2, MODE>), grid, dim3(kThreads), lds, st, a);
   else if (a.q == 4)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 4>), grid, dim3(kThreads), lds, st, a);
-  else if (a.q == 8)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 8>), grid, dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 4, MODE>), grid, dim3(kThreads), lds, st, a);
+  else if (MODE == kPlain && a.q == 8)   // the plain mode also has an unrolled variant for q = 8
+    hipLaunchKernelGGL((patch_reduce_lds<T, MODE == kPlain ? 8 : 0, MODE>), grid, dim3(kThreads), lds, st, a);
   else
-    hipLaunchKernelGGL((patch_reduce_lds<T, 0>), grid, dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL((patch_reduce_lds<T, 0, MODE>), grid, dim3(kThreads), lds, st, a);
   return hipGetLastError();
+}
+
+// the mode follows from what the arguments ask for
+template <class T>
+hipError_t launch_t(ReduceArgs& a, hipStream_t st, int* nblocks) {
+  if (a.q_inv > 0.f) return launch_mode<T, kQ8>(a, st, nblocks);
+  if (a.stats_part) return launch_mode<T, kStats>(a, st, nblocks);
+  if (a.out2) return launch_mode<T, kMask>(a, st, nblocks);
+  return launch_mode<T, kPlain>(a, st, nblocks);
 }
 
 }  // namespace
@@ -516,6 +517,20 @@ hipError_t launch_pool_mask(const void* x, void* x_u, void* m_u, long planes, in
   a.total_in = (int)(planes * H * W);
   a.total_strips = (int)(planes * a.Hp);
   a.mean = 0;
+  a.d_hp = FastDiv((uint32_t)a.Hp);
+  a.d_wp = FastDiv((uint32_t)a.Wp);
+  return dtype == GF_BF16 ? launch_t<bf16_t>(a, st, &blocks) : launch_t<float>(a, st, &blocks);
+}
+
+hipError_t launch_patch_reduce_q8(const void* in, int8_t* out_q, long planes, int H, int W, int q, bool mean,
+                                  float inv_delta, int dtype, hipStream_t st) {
+  ReduceArgs a = {};
+  int blocks = 0;
+  a.in = in; a.out = out_q; a.q_inv = inv_delta; a.H = H; a.W = W; a.q = q;
+  a.Hp = cdiv(H, q); a.Wp = cdiv(W, q);
+  a.total_in = (int)(planes * H * W);
+  a.total_strips = (int)(planes * a.Hp);
+  a.mean = mean ? 1 : 0;
   a.d_hp = FastDiv((uint32_t)a.Hp);
   a.d_wp = FastDiv((uint32_t)a.Wp);
   return dtype == GF_BF16 ? launch_t<bf16_t>(a, st, &blocks) : launch_t<float>(a, st, &blocks);

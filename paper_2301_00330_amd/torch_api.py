@@ -182,3 +182,51 @@ def conv_bwd_exact(d: B.ConvDesc, x, w, g_y, want_gw: bool = True, want_gx: bool
     B.gf_conv_bwd_exact(d, B.ptr(x) if want_gw else 0, B.ptr(w) if want_gx else 0, B.ptr(g_y),
                         B.ptr(g_w), B.ptr(g_x), p, n, _stream())
     return g_w, g_x
+
+
+# ---- gradient filtering on signed 8-bit codes (one step size per tensor, chosen by the caller) ----
+
+def filter_grad_q8(d: B.ConvDesc, g_y: torch.Tensor, inv_delta: float) -> torch.Tensor:
+    s = shapes(d)
+    _check(g_y, d, s["g_y"], "g_y")
+    out = torch.empty(s["gy_u"], dtype=torch.int8, device=g_y.device)
+    B.gf_filter_grad_q8(d, B.ptr(g_y), inv_delta, B.ptr(out), _stream())
+    return out
+
+
+def pool_activation_q8(d: B.ConvDesc, x: torch.Tensor, inv_delta: float) -> torch.Tensor:
+    s = shapes(d)
+    _check(x, d, s["x"], "x")
+    out = torch.empty(s["x_u"], dtype=torch.int8, device=x.device)
+    B.gf_pool_activation_q8(d, B.ptr(x), inv_delta, B.ptr(out), _stream())
+    return out
+
+
+def kernel_sum_q8(d: B.ConvDesc, w: torch.Tensor, inv_delta: float) -> torch.Tensor:
+    s = shapes(d)
+    _check(w, d, s["w"], "w")
+    out = torch.empty(s["w"][:2], dtype=torch.int8, device=w.device)
+    B.gf_kernel_sum_q8(d, B.ptr(w), inv_delta, B.ptr(out), _stream())
+    return out
+
+
+def conv_bwd_weight_q8(d: B.ConvDesc, x_q: torch.Tensor, gy_q: torch.Tensor, scale: float,
+                       ws: Workspace | None = None) -> torch.Tensor:
+    s = shapes(d)
+    _check(x_q, d, s["x_u"], "x_q", torch.int8)
+    _check(gy_q, d, s["gy_u"], "gy_q", torch.int8)
+    g_w = torch.empty(s["w"], dtype=torch.float32, device=x_q.device)
+    p, n = _ws(x_q, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT_Q8))
+    B.gf_conv_bwd_weight_q8(d, B.ptr(x_q), B.ptr(gy_q), scale, B.ptr(g_w), p, n, _stream())
+    return g_w
+
+
+def conv_bwd_input_q8(d: B.ConvDesc, gy_q: torch.Tensor, w_q: torch.Tensor, scale: float,
+                      reduced_out: bool = False, ws: Workspace | None = None) -> torch.Tensor:
+    s = shapes(d)
+    _check(gy_q, d, s["gy_u"], "gy_q", torch.int8)
+    _check(w_q, d, s["w"][:2], "w_q", torch.int8)
+    g_x = torch.empty(s["g_x_u"] if reduced_out else s["x"], dtype=_tdtype(d), device=gy_q.device)
+    p, n = _ws(gy_q, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT_Q8))
+    B.gf_conv_bwd_input_q8(d, B.ptr(gy_q), B.ptr(w_q), scale, B.ptr(g_x), reduced_out, p, n, _stream())
+    return g_x

@@ -22,7 +22,7 @@ def lib():
 def test_exports_match_header(lib):
     hdr = open(os.path.join(ROOT, "include", "gf.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(gf_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(gf_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -196,3 +196,32 @@ def test_header_is_plain_c(tmp_path):
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", f"-I{os.path.join(root, 'include')}", str(src),
                         f"-L{libdir}", "-lgf", f"-Wl,-rpath,{libdir}", "-o", str(exe)], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_q8_entry_errors(lib):
+    d = B.ConvDesc(**OK)
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        for call in (lambda: B.gf_filter_grad_q8(d, FAKE, bad, FAKE),
+                     lambda: B.gf_pool_activation_q8(d, FAKE, bad, FAKE),
+                     lambda: B.gf_kernel_sum_q8(d, FAKE, bad, FAKE),
+                     lambda: B.gf_conv_bwd_weight_q8(d, FAKE, FAKE, bad, FAKE, FAKE, 1 << 30),
+                     lambda: B.gf_conv_bwd_input_q8(d, FAKE, FAKE, bad, FAKE, True, FAKE, 1 << 30)):
+            with pytest.raises(B.GfError) as ei:
+                call()
+            assert ei.value.status == B.GF_ERR_BAD_DESC
+    # codes stand for reduced maps: r = 1 has none
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad_q8(d.with_(r=1), FAKE, 1.0, FAKE)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_weight_q8(d, 0, FAKE, 1.0, FAKE, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_filter_grad_q8(d, FAKE + 4, 1.0, FAKE)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    # full-resolution input gradient needs the fp32 reduced map as workspace
+    need = B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT_Q8)
+    assert need == d.N * d.C_in * 4 * 4 * 4
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_input_q8(d, FAKE, FAKE, 1.0, FAKE, False, FAKE, need - 1)
+    assert ei.value.status == B.GF_ERR_WORKSPACE

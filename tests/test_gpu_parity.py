@@ -775,6 +775,137 @@ def test_fewer_unique_elements_only_variant(oracle, dtype):
     assert rel_err(g_w, ref_gw) <= TOL[dtype] and rel_err(g_x, ref_gx) <= TOL[dtype]
 
 
+# ---------------------------------------------------------------------------
+# Gradient filtering on 8-bit codes (reading of Supp. H)
+# ---------------------------------------------------------------------------
+def check_codes(oracle, q_gpu: torch.Tensor, v64: np.ndarray, inv_delta: float, what: str):
+    """The code is decided in fp32 on both sides, but from sums added in different orders: codes
+    must agree except where the scaled value sits within 1e-3 of a rounding boundary (there either
+    neighbour is right), and never differ by more than one."""
+    ref = oracle.quantize_q8(v64, inv_delta).astype(np.int64)
+    got = q_gpu.detach().cpu().numpy().astype(np.int64)
+    assert got.shape == ref.shape, what
+    t = np.clip(v64 * float(np.float32(inv_delta)), -127.0, 127.0)
+    near_tie = np.abs(np.abs(t - np.floor(t)) - 0.5) < 1e-3
+    diff = np.abs(got - ref)
+    assert diff.max() <= 1, what
+    assert not np.any((diff > 0) & ~near_tie), what
+    assert got.min() >= -127, what
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", REDUCE_CASES)
+def test_q8_pool_and_filter_codes(oracle, case, dtype):
+    N, C, H, W, r, s = case
+    d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = randn((N, C, H, W), 21, dtype, relu=True)
+    gy = randn((N, C, Hy, Wy), 22, dtype)
+    od = odesc(oracle, d)
+    ref_x, ref_g = oracle.pool_activation(od, to64(x)), oracle.filter_grad(od, to64(gy))
+    inv_x, inv_g = 127.0 / float(np.abs(ref_x).max()), 127.0 / float(np.abs(ref_g).max())
+    x_q = T.pool_activation_q8(d, x.cuda(), inv_x)
+    gy_q = T.filter_grad_q8(d, gy.cuda(), inv_g)
+    torch.cuda.synchronize()
+    assert x_q.dtype == torch.int8 and tuple(x_q.shape) == (N, C, Hp, Wp)
+    check_codes(oracle, x_q, ref_x, inv_x, "x_q")
+    check_codes(oracle, gy_q, ref_g, inv_g, "gy_q")
+    assert int(x_q.max()) == 127   # the largest value lands on the last code
+    # values beyond the range are clipped to +-127, never -128
+    g8 = T.filter_grad_q8(d, gy.cuda(), 1000.0 * inv_g)
+    assert int(g8.min()) >= -127 and int(g8.to(torch.int32).abs().max()) == 127
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H,W,r,s", [(8, 8, 2, 1), (56, 56, 2, 1), (64, 64, 8, 1), (16, 16, 2, 2), (7, 7, 2, 1),
+                                     (14, 14, 4, 1)])
+def test_q8_codes_bit_exact_on_integers(oracle, H, W, r, s, dtype):
+    """Integer-coded maps (exact sums and means): the codes must match bit for bit, ties included."""
+    N, C = 3, 5
+    d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = WL.integer_coded((N, C, H, W), 5, dtype=dtype)
+    gy = WL.integer_coded((N, C, Hy, Wy), 6, dtype=dtype) * (r * r)
+    od = odesc(oracle, d)
+    for inv in (0.5, 0.25, 1.0):   # halves and quarters of integers: many exact ties
+        x_q = T.pool_activation_q8(d, x.cuda(), inv)
+        gy_q = T.filter_grad_q8(d, gy.cuda(), inv)
+        assert np.array_equal(x_q.cpu().numpy(), oracle.pool_activation_q8(od, to64(x), inv))
+        assert np.array_equal(gy_q.cpu().numpy(), oracle.filter_grad_q8(od, to64(gy), inv))
+
+
+Q8_LAYERS = [
+    # N  Ci  Co   H   W  K  s  g   r     note
+    (4, 24, 144, 56, 56, 1, 1, 1, 2),     # dense, plane of 784 codes: MFMA weight gradient
+    (4, 144, 24, 56, 56, 1, 1, 1, 2),
+    (3, 40, 72, 32, 32, 3, 1, 1, 2),      # ragged channel tiles, 3x3 (kernel sum of 9 taps)
+    (2, 64, 64, 64, 64, 3, 1, 1, 4),      # r = 4
+    (2, 32, 48, 32, 32, 3, 2, 1, 2),      # stride 2: plane 8 x 8, factor 1/4
+    (4, 24, 144, 56, 56, 1, 1, 1, 4),     # plane of 196 codes: not a multiple of 16 -> pair kernel
+    (3, 16, 24, 14, 14, 3, 1, 1, 2),      # 7 x 7 plane
+    (3, 12, 18, 9, 11, 3, 1, 3, 2),       # groups, ragged patches
+    (4, 144, 144, 56, 56, 3, 1, 144, 2),  # depthwise
+    (2, 32, 32, 15, 15, 3, 2, 32, 2),     # depthwise, stride 2, ragged
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", Q8_LAYERS)
+def test_q8_contractions_bit_exact(oracle, case, dtype):
+    """Eq. 5 / Eq. 3 on given codes: the integer sums are exact and the one fp32 scaling is the same
+    operation on both sides, so g_w and g_x (both forms) must match bit for bit."""
+    N, Ci, Co, H, W, K, s, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, s=s, p=K // 2, g=g, r=r, dtype=dtype)
+    od = odesc(oracle, d)
+    _, _, Hp, Wp = B.gf_out_shape(d)
+    rs = np.random.default_rng(91)
+    x_q = rs.integers(-127, 128, (N, Ci, Hp, Wp)).astype(np.int8)
+    gy_q = rs.integers(-127, 128, (N, Co, Hp, Wp)).astype(np.int8)
+    w_q = rs.integers(-127, 128, (Co, Ci // g)).astype(np.int8)
+    scale = 3.1e-5
+    tq = lambda a: torch.from_numpy(a).cuda()
+    g_w = T.conv_bwd_weight_q8(d, tq(x_q), tq(gy_q), scale)
+    g_x = T.conv_bwd_input_q8(d, tq(gy_q), tq(w_q), scale)
+    g_xu = T.conv_bwd_input_q8(d, tq(gy_q), tq(w_q), scale, reduced_out=True)
+    torch.cuda.synchronize()
+    assert torch.equal(g_w.cpu(), torch.from_numpy(oracle.bwd_weight_q8(od, x_q, gy_q, scale)))
+    assert torch.equal(g_x.cpu(), rounded(oracle.bwd_input_q8(od, gy_q, w_q, scale), dtype))
+    assert torch.equal(g_xu.cpu(), rounded(oracle.bwd_input_q8(od, gy_q, w_q, scale, reduced_out=True), dtype))
+    # the extreme codes everywhere: the largest sums the layer can produce
+    big = lambda shape, v: np.full(shape, v, np.int8)
+    g_w = T.conv_bwd_weight_q8(d, tq(big(x_q.shape, 127)), tq(big(gy_q.shape, -127)), 1.0)
+    g_x = T.conv_bwd_input_q8(d, tq(big(gy_q.shape, -127)), tq(big(w_q.shape, -127)), 1.0, reduced_out=True)
+    assert torch.equal(g_w.cpu(), torch.from_numpy(oracle.bwd_weight_q8(od, big(x_q.shape, 127), big(gy_q.shape, -127), 1.0)))
+    assert torch.equal(g_x.cpu(), rounded(oracle.bwd_input_q8(od, big(gy_q.shape, -127), big(w_q.shape, -127), 1.0, True), dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_q8_layer_end_to_end(oracle, dtype):
+    """Config 2's layers, N = 4: codes from the library's own reductions, then both contractions;
+    the oracle continues from the GPU's codes (checked on their own above) and must match bit for bit,
+    and the result stays within a few per cent of the unquantised filtered gradients."""
+    cfg = WL.CONFIGS[2]
+    for layer in cfg.layers:
+        d = T.desc_for(layer, 4, 2, dtype)
+        od = odesc(oracle, d)
+        x, w, gy = WL.make_inputs(cfg, layer, dtype, N=4)
+        ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+        ref_ws = oracle.kernel_sum(od, to64(w))
+        dx, dg, dw = (float(np.abs(t).max()) / 127.0 for t in (ref_xu, ref_gyu, ref_ws))
+        x_q = T.pool_activation_q8(d, x.cuda(), 1.0 / dx)
+        gy_q = T.filter_grad_q8(d, gy.cuda(), 1.0 / dg)
+        w_q = T.kernel_sum_q8(d, w.cuda(), 1.0 / dw)
+        g_w = T.conv_bwd_weight_q8(d, x_q, gy_q, dx * dg)
+        g_x = T.conv_bwd_input_q8(d, gy_q, w_q, dg * dw)
+        torch.cuda.synchronize()
+        check_codes(oracle, w_q, ref_ws, 1.0 / dw, "w_q")
+        xq, gq, wq = (t.cpu().numpy() for t in (x_q, gy_q, w_q))
+        assert torch.equal(g_w.cpu(), torch.from_numpy(oracle.bwd_weight_q8(od, xq, gq, dx * dg)))
+        assert torch.equal(g_x.cpu(), rounded(oracle.bwd_input_q8(od, gq, wq, dg * dw), dtype))
+        assert np.abs(to64(g_w) - ref_gw).max() <= 0.05 * np.abs(ref_gw).max(), layer.name
+        assert np.abs(to64(g_x) - ref_gx).max() <= 0.05 * np.abs(ref_gx).max(), layer.name
+
+
 # Just under 2^31 elements per tensor: the most the entry points accept (the kernels index
 # elements with 32 bits).  Sampled outputs at both ends of every tensor against the oracle.
 MAX_CASES = [
