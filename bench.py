@@ -103,7 +103,7 @@ def main():
     if others and not args.single_dtype:
         o = measure(args, others[0], full=False)
         out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer",
-                                                "chained_block") if k in o}
+                                                "chained_block", "q8_block") if k in o}
     print(json.dumps(out), flush=True)
 
 
@@ -405,6 +405,67 @@ def measure(args, dtype, full):
                            "(valid for a stack of stride-1 convolutions with nothing between them); full "
                            "resolution is written only at the bottom"}
 
+    # ---- secondary: the same step on signed 8-bit codes (reading of Supp. H) ----
+    q8 = None
+    if r > 1:
+        for bs in sets:
+            for lb in bs:
+                s_ = T.shapes(lb.d)
+                lb.x_q = torch.empty(s_["x_u"], dtype=torch.int8, device="cuda")
+                lb.gy_q = torch.empty(s_["gy_u"], dtype=torch.int8, device="cuda")
+                lb.w_q = torch.empty(s_["w"][:2], dtype=torch.int8, device="cuda")
+                lb.ws_q = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_WEIGHT_Q8),
+                                          B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_INPUT_Q8), 256),
+                                      dtype=torch.uint8, device="cuda")
+        # step sizes: max|.| / 127 of the reduced maps and of the kernel sum (the caller's choice; formed
+        # once here from the floating-point maps of the first buffer set, outside the timed region)
+        deltas = []
+        for lb in one:
+            enqueue_pool(lb, st())
+            enqueue_filter(lb, st())
+            torch.cuda.synchronize()
+            dx = float(lb.x_u.float().abs().max()) / 127.0
+            dg = float(lb.gy_u.float().abs().max()) / 127.0
+            dw = float(lb.w.float().sum(dim=(2, 3)).abs().max()) / 127.0
+            deltas.append((dx or 1.0, dg or 1.0, dw or 1.0))
+
+        def q8_pool(lb, s, li): B.gf_pool_activation_q8(lb.d, P(lb.x), 1.0 / deltas[li][0], P(lb.x_q), s)
+        def q8_filter(lb, s, li): B.gf_filter_grad_q8(lb.d, P(lb.gy), 1.0 / deltas[li][1], P(lb.gy_q), s)
+        def q8_ksum(lb, s, li): B.gf_kernel_sum_q8(lb.d, P(lb.w), 1.0 / deltas[li][2], P(lb.w_q), s)
+        def q8_bww(lb, s, li):
+            B.gf_conv_bwd_weight_q8(lb.d, P(lb.x_q), P(lb.gy_q), deltas[li][0] * deltas[li][1], P(lb.g_w),
+                                    P(lb.ws_q), lb.ws_q.numel(), s)
+        def q8_bwi(lb, s, li):
+            B.gf_conv_bwd_input_q8(lb.d, P(lb.gy_q), P(lb.w_q), deltas[li][1] * deltas[li][2], P(lb.g_x), False,
+                                   P(lb.ws_q), lb.ws_q.numel(), s)
+
+        def step_q8(bufset):
+            s = st()
+            for li, lb in enumerate(bufset):
+                q8_pool(lb, s, li)
+            for li in reversed(range(len(bufset))):
+                lb = bufset[li]
+                q8_filter(lb, s, li)
+                q8_ksum(lb, s, li)
+                q8_bww(lb, s, li)
+                q8_bwi(lb, s, li)
+
+        for i in range(max(args.warmup, 1)):
+            step_q8(sets[i % nsets])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step_q8(sets[i % nsets])
+        torch.cuda.synchronize()
+        qms = (time.perf_counter() - t0) * 1e3 / args.steps
+        q8 = {"ms_per_step": round(qms, 5), "value": round(N / (qms * 1e-3), 1), "unit": "images/s",
+              "arithmetic": "int8 codes, int32 / int64 sums, one fp32 scaling",
+              "stored_activation_bytes_per_step": int(sum(lb.x_q.numel() for lb in one)),
+              "stored_activation_bytes_per_step_float_path": int(sum(lb.x_u.numel() * lb.x_u.element_size() for lb in one)),
+              "note": "plain launches; per layer gf_pool_activation_q8, then gf_filter_grad_q8, gf_kernel_sum_q8, "
+                      "gf_conv_bwd_weight_q8 and gf_conv_bwd_input_q8 (full-resolution g_x in the storage type); "
+                      "the step is bound by reading g_y and writing g_x, which the codes do not shrink"}
+
     # the other launch mode for comparison (eager includes the host's launch overhead)
     other_ms = timed(args.steps, not use_graph) if graphs is not None else None
 
@@ -474,6 +535,11 @@ def measure(args, dtype, full):
             us = time_stage(enqueue_filter_snr, li)
             e_, v_ = sets[0][li].stats.tolist()
             row["filter_grad_snr"] = {"us": round(us, 2), "snr": round(e_ / v_, 4) if v_ > 0 else None}
+        if q8 is not None:   # the stages of the same layer on 8-bit codes
+            row["q8_us"] = {name: round(time_stage(lambda lb, s, f=fn: f(lb, s, li), li), 2)
+                            for name, fn in (("pool_activation_q8", q8_pool), ("filter_grad_q8", q8_filter),
+                                             ("kernel_sum_q8", q8_ksum), ("bwd_weight_q8", q8_bww),
+                                             ("bwd_input_q8", q8_bwi))}
         fl = cost[li]["flops_bwd_weight"] + cost[li]["flops_bwd_input"]
         row["separate_calls_us"] = round(tot_us, 2)     # gf_filter_grad + gf_conv_bwd_weight + gf_conv_bwd_input
         tot_us = time_stage(enqueue_fused, li)
@@ -586,6 +652,8 @@ def measure(args, dtype, full):
     }
     if chained is not None:
         out["chained_block"] = chained
+    if q8 is not None:
+        out["q8_block"] = q8
     del sets, one, graphs
     torch.cuda.empty_cache()
     if full and args.pmc_calibration:

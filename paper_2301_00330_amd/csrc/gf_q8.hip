@@ -10,10 +10,13 @@
 //                         int32 partial slabs (a slab holds few enough products not to overflow),
 //                         q8_finalize_k adds them in 64 bits and scales
 //  * q8_wgrad_pair_k   -- Eq. 5 for every other layer (groups, depthwise, unaligned planes): one
-//                         block per (c_o, c_i) pair, 64-bit sums
-//  * q8_dgrad_k        -- Eq. 3: one lane per (n, c_i, patch), the group's c_o walked in the lane;
-//                         writes the reduced map (storage type) or an fp32 map that the expansion
-//                         kernel of the floating-point path replicates to full resolution
+//                         block per (c_o, c_i) pair, v_dot4_i32_i8 on 32-bit words where the plane
+//                         allows it, 64-bit sums
+//  * q8_dgrad_tile_k   -- Eq. 3 for planes that are multiples of four codes: a lane owns four patches
+//                         of four (or one) input channels and walks the group's c_o
+//  * q8_dgrad_k        -- Eq. 3 for the other planes: one lane per (n, c_i, patch)
+//    both write the reduced map (storage type), or an fp32 map that the expansion kernel of the
+//    floating-point path replicates to full resolution
 #include "gf_internal.h"
 
 namespace gf {
@@ -129,15 +132,25 @@ __global__ __launch_bounds__(kThreads) void q8_wgrad_mfma_k(Q8WgradArgs a) {
     }
 }
 
-// g_w[pair, all taps] = float(sum over the slabs, 64 bits) * scale
+// g_w[pair, all taps] = float(sum over the slabs, 64 bits) * scale; 16 lanes share an output
+// (each takes every 16th slab, four loads in flight), then a shuffle tree
 __global__ __launch_bounds__(kThreads) void q8_finalize_k(const int* part, float* g_w, int pairs, int nz, int KK,
                                                          float scale) {
-  const int e = blockIdx.x * kThreads + threadIdx.x;
-  if (e >= pairs) return;
+  const int sub = threadIdx.x & 15;
+  const int e = blockIdx.x * (kThreads / 16) + (threadIdx.x >> 4);
+  const int ec = min(e, pairs - 1);
   long long s = 0;
-  for (int z = 0; z < nz; ++z) s += part[(long)z * pairs + e];
+  int z = sub;
+  for (; z + 48 < nz; z += 64) {
+    const int v0 = part[(long)z * pairs + ec], v1 = part[(long)(z + 16) * pairs + ec];
+    const int v2 = part[(long)(z + 32) * pairs + ec], v3 = part[(long)(z + 48) * pairs + ec];
+    s += ((long long)v0 + v1) + ((long long)v2 + v3);
+  }
+  for (; z < nz; z += 16) s += part[(long)z * pairs + ec];
+  for (int m = 8; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
+  if (e >= pairs) return;
   const float v = (float)s * scale;
-  for (int t = 0; t < KK; ++t) g_w[(long)e * KK + t] = v;
+  for (int t = sub; t < KK; t += 16) g_w[(long)e * KK + t] = v;
 }
 
 // ---------------------------------------------------------------------------
@@ -149,20 +162,41 @@ struct Q8PairArgs {
   float* g_w;
   int N, Ci, Co, Cg, Og, P, KK;
   float scale;
+  FastDiv d_per;   // words (P / 4) or codes (P) per plane
 };
 
+// V4: the plane is a multiple of four codes, so rows are read as 32-bit words and multiplied with
+// v_dot4_i32_i8.  A lane adds at most 1024 words into an int32 before it moves on to 64 bits.
+template <bool V4>
 __global__ __launch_bounds__(kThreads) void q8_wgrad_pair_k(Q8PairArgs a) {
   __shared__ long long red[kThreads / 64];
   const int pair = blockIdx.x;
   const int co = pair / a.Cg, cl = pair - co * a.Cg;
   const int ci = (co / a.Og) * a.Cg + cl;
+  const int8_t* gbase = a.gyq + (long)co * a.P;
+  const int8_t* xbase = a.xq + (long)ci * a.P;
+  const long gs = (long)a.Co * a.P, xs = (long)a.Ci * a.P;   // image strides
+  const int per = V4 ? a.P / 4 : a.P;                        // words / codes per plane
+  const int tot = a.N * per;                                 // < 2^31 (host)
   long long s = 0;
-  for (int n = 0; n < a.N; ++n) {
-    const int8_t* gp = a.gyq + ((long)n * a.Co + co) * a.P;
-    const int8_t* xp = a.xq + ((long)n * a.Ci + ci) * a.P;
-    int part = 0;   // |product| <= 127^2: a lane adds at most P / 256 + 1 of them per image
-    for (int p = threadIdx.x; p < a.P; p += kThreads) part += (int)gp[p] * (int)xp[p];
-    s += part;
+  int i = threadIdx.x;
+  while (i < tot) {
+    int acc = 0;
+#pragma unroll 4
+    for (int u = 0; u < 1024; ++u) {
+      if (i >= tot) break;
+      const int n = (int)a.d_per.div((uint32_t)i);
+      const int q = i - n * per;
+      if (V4) {
+        const int gv = reinterpret_cast<const int*>(gbase + n * gs)[q];
+        const int xv = reinterpret_cast<const int*>(xbase + n * xs)[q];
+        acc = __builtin_amdgcn_sdot4(gv, xv, acc, false);
+      } else {
+        acc += (int)gbase[n * gs + q] * (int)xbase[n * xs + q];
+      }
+      i += kThreads;
+    }
+    s += acc;
   }
   for (int m = 32; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
@@ -202,6 +236,98 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_k(Q8DgradArgs a) {
   int acc = 0;   // Og * 127^2 < 2^31 for Og <= 133 000 (checked on the host)
   for (int ol = 0; ol < a.Og; ++ol) acc += (int)gp[(long)ol * a.P] * (int)wp[(long)ol * a.Cg];
   static_cast<D*>(a.dst)[e] = from_f32<D>((float)acc * a.scale);
+}
+
+// The same for planes that are multiples of four codes: a lane owns four patches of CT input
+// channels (CT = 4 needs group widths that are multiples of four; CT = 1 is for layers with so few
+// input channels that 4 x 4 tiles would leave most of the chip idle).  Per c_o it reads one word of
+// gy_q (four patches) and one word (or one code) of w_q and adds the 4 CT products.
+struct Q8DgradTileArgs {
+  const int8_t* gyq;
+  const int8_t* wq;
+  void* dst;
+  int N, Ci, Co, Cg, Og, P;
+  int total;   // N * (Ci / CT) * (P / 4)
+  float scale;
+  FastDiv d_p4, d_ct;
+};
+
+__device__ __forceinline__ int code_of(int word, int k) { return (int)(int8_t)(word >> (8 * k)); }
+
+template <class D, int CT>
+__global__ __launch_bounds__(kThreads) void q8_dgrad_tile_k(Q8DgradTileArgs a) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= a.total) return;
+  const int P4 = a.P >> 2, CN = a.Ci / CT;
+  const int planes = (int)a.d_p4.div((uint32_t)e);   // n * CN + c
+  const int q = e - planes * P4;
+  const int n = (int)a.d_ct.div((uint32_t)planes);
+  const int ci0 = (planes - n * CN) * CT;
+  const int grp = ci0 / a.Cg, cl0 = ci0 - grp * a.Cg;   // CT | Cg: the lane's channels share a group
+  const int8_t* gp = a.gyq + ((long)n * a.Co + (long)grp * a.Og) * a.P + 4 * q;
+  const int8_t* wp = a.wq + (long)grp * a.Og * a.Cg + cl0;
+  int acc[CT][4];
+#pragma unroll
+  for (int i = 0; i < CT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0;
+#pragma unroll 4
+  for (int ol = 0; ol < a.Og; ++ol) {
+    const int gv = *reinterpret_cast<const int*>(gp + (long)ol * a.P);
+    int gc[4], wc[CT];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) gc[k] = code_of(gv, k);
+    if constexpr (CT == 4) {
+      const int wv = *reinterpret_cast<const int*>(wp + (long)ol * a.Cg);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) wc[k] = code_of(wv, k);
+    } else {
+      wc[0] = (int)wp[(long)ol * a.Cg];
+    }
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] += wc[i] * gc[j];
+  }
+#pragma unroll
+  for (int i = 0; i < CT; ++i) {
+    D v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = from_f32<D>((float)acc[i][j] * a.scale);
+    D* d = static_cast<D*>(a.dst) + ((long)n * a.Ci + ci0 + i) * a.P + 4 * q;
+    if constexpr (sizeof(D) == 4) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(v);
+    else *reinterpret_cast<uint2*>(d) = *reinterpret_cast<const uint2*>(v);
+  }
+}
+
+template <class D>
+static hipError_t q8_dgrad_launch(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float fscale, void* dst,
+                                  hipStream_t st) {
+  if (g.P % 4 == 0) {
+    // 4 x 4 tiles when they still give the chip ~a wave per SIMD, else one channel per lane
+    const bool wide = g.Cg % 4 == 0 && (long)g.N * (g.Ci / 4) * (g.P / 4) >= 128 * 1024;
+    const int ct = wide ? 4 : 1;
+    Q8DgradTileArgs a;
+    a.gyq = gy_q; a.wq = w_q; a.dst = dst;
+    a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P;
+    a.total = (int)((long)g.N * (g.Ci / ct) * (g.P / 4));
+    a.scale = fscale;
+    a.d_p4 = FastDiv((uint32_t)(g.P / 4));
+    a.d_ct = FastDiv((uint32_t)(g.Ci / ct));
+    const dim3 grid(cdiv(a.total, kThreads)), block(kThreads);
+    if (wide) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 4>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((q8_dgrad_tile_k<D, 1>), grid, block, 0, st, a);
+    return hipGetLastError();
+  }
+  Q8DgradArgs a;
+  a.gyq = gy_q; a.wq = w_q; a.dst = dst;
+  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P;
+  a.total = (long)g.N * g.Ci * g.P;
+  a.scale = fscale;
+  a.d_p = FastDiv((uint32_t)g.P);
+  a.d_ci = FastDiv((uint32_t)g.Ci);
+  hipLaunchKernelGGL(q8_dgrad_k<D>, dim3(cdiv(a.total, kThreads)), dim3(kThreads), 0, st, a);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -255,15 +381,18 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int pairs = g.Co * g.Ci;
-    hipLaunchKernelGGL(q8_finalize_k, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, a.part, g_w, pairs, nz, g.KK,
-                       fscale);
+    hipLaunchKernelGGL(q8_finalize_k, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, a.part, g_w, pairs, nz,
+                       g.KK, fscale);
     return hipGetLastError();
   }
   Q8PairArgs a;
   a.gyq = gy_q; a.xq = x_q; a.g_w = g_w;
   a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P; a.KK = g.KK;
   a.scale = fscale;
-  hipLaunchKernelGGL(q8_wgrad_pair_k, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
+  const bool v4 = g.P % 4 == 0;
+  a.d_per = FastDiv((uint32_t)(v4 ? g.P / 4 : g.P));
+  if (v4) hipLaunchKernelGGL(q8_wgrad_pair_k<true>, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
+  else hipLaunchKernelGGL(q8_wgrad_pair_k<false>, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -279,23 +408,11 @@ bool q8_shape_ok(const Geom& g) {
 
 hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float scale, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st) {
-  Q8DgradArgs a;
-  a.gyq = gy_q; a.wq = w_q;
-  a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P;
-  a.total = (long)g.N * g.Ci * g.P;
-  a.scale = scale / ((float)g.s * (float)g.s);
-  a.d_p = FastDiv((uint32_t)g.P);
-  a.d_ci = FastDiv((uint32_t)g.Ci);
-  const dim3 grid(cdiv(a.total, kThreads)), block(kThreads);
-  if (reduced_out) {
-    a.dst = g_x;
-    if (g.dtype == GF_BF16) hipLaunchKernelGGL(q8_dgrad_k<bf16_t>, grid, block, 0, st, a);
-    else hipLaunchKernelGGL(q8_dgrad_k<float>, grid, block, 0, st, a);
-    return hipGetLastError();
-  }
-  a.dst = ws;
-  hipLaunchKernelGGL(q8_dgrad_k<float>, grid, block, 0, st, a);
-  hipError_t e = hipGetLastError();
+  const float fscale = scale / ((float)g.s * (float)g.s);
+  if (reduced_out)
+    return g.dtype == GF_BF16 ? q8_dgrad_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, st)
+                              : q8_dgrad_launch<float>(g, gy_q, w_q, fscale, g_x, st);
+  hipError_t e = q8_dgrad_launch<float>(g, gy_q, w_q, fscale, ws, st);
   if (e != hipSuccess) return e;
   return launch_expand_f32(g, static_cast<const float*>(ws), g_x, st);
 }

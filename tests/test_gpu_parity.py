@@ -846,6 +846,8 @@ Q8_LAYERS = [
     (3, 12, 18, 9, 11, 3, 1, 3, 2),       # groups, ragged patches
     (4, 144, 144, 56, 56, 3, 1, 144, 2),  # depthwise
     (2, 32, 32, 15, 15, 3, 2, 32, 2),     # depthwise, stride 2, ragged
+    (8, 256, 32, 64, 64, 1, 1, 1, 2),     # many input channels: 4 x 4 register tiles in the input gradient
+    (8, 256, 64, 64, 64, 1, 1, 4, 2),     # the same with groups
 ]
 
 
