@@ -250,14 +250,22 @@ struct Q8DgradTileArgs {
   int total;   // N * (Ci / CT) * (P / 4)
   float scale;
   FastDiv d_p4, d_ct;
+  // full-resolution store (RX > 0): the four patches of a lane lie in one patch row (4 | W_p)
+  int H, W, Wq;   // Wq = W_p / 4
+  FastDiv d_wq;
 };
 
 __device__ __forceinline__ int code_of(int word, int k) { return (int)(int8_t)(word >> (8 * k)); }
 
-template <class D, int CT>
+// SPLIT (1 or 4) neighbouring lanes share a tile and take every SPLIT-th c_o (integer sums, so the
+// order does not matter); it shortens the chain of dependent loads when the tiles are few.
+// RX > 0: instead of the reduced map, every pixel of the RX x RX input-side patches receives its
+// patch's value (rounded once to the storage type, then replicated), as 16-byte runs of pixels.
+template <class D, int CT, int SPLIT, int RX>
 __global__ __launch_bounds__(kThreads) void q8_dgrad_tile_k(Q8DgradTileArgs a) {
-  const int e = blockIdx.x * kThreads + threadIdx.x;
-  if (e >= a.total) return;
+  const int lane_id = blockIdx.x * kThreads + threadIdx.x;
+  if (lane_id >= a.total * SPLIT) return;
+  const int e = lane_id / SPLIT, sub = lane_id - e * SPLIT;
   const int P4 = a.P >> 2, CN = a.Ci / CT;
   const int planes = (int)a.d_p4.div((uint32_t)e);   // n * CN + c
   const int q = e - planes * P4;
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_tile_k(Q8DgradTileArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0;
 #pragma unroll 4
-  for (int ol = 0; ol < a.Og; ++ol) {
+  for (int ol = sub; ol < a.Og; ol += SPLIT) {
     const int gv = *reinterpret_cast<const int*>(gp + (long)ol * a.P);
     int gc[4], wc[CT];
 #pragma unroll
@@ -289,24 +297,71 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_tile_k(Q8DgradTileArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[i][j] += wc[i] * gc[j];
   }
+  if constexpr (SPLIT > 1) {
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        for (int m = SPLIT >> 1; m > 0; m >>= 1) acc[i][j] += __shfl_xor(acc[i][j], m, 64);
+    if (sub != 0) return;
+  }
 #pragma unroll
   for (int i = 0; i < CT; ++i) {
     D v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = from_f32<D>((float)acc[i][j] * a.scale);
-    D* d = static_cast<D*>(a.dst) + ((long)n * a.Ci + ci0 + i) * a.P + 4 * q;
-    if constexpr (sizeof(D) == 4) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(v);
-    else *reinterpret_cast<uint2*>(d) = *reinterpret_cast<const uint2*>(v);
+    if constexpr (RX == 0) {
+      D* d = static_cast<D*>(a.dst) + ((long)n * a.Ci + ci0 + i) * a.P + 4 * q;
+      if constexpr (sizeof(D) == 4) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(v);
+      else *reinterpret_cast<uint2*>(d) = *reinterpret_cast<const uint2*>(v);
+    } else {
+      constexpr int VE = 16 / (int)sizeof(D);     // pixels per 16-byte run
+      constexpr int NV = 4 * RX / VE;             // runs per pixel row of the lane's four patches
+      const int hp = (int)a.d_wq.div((uint32_t)q);
+      const int wq = q - hp * a.Wq;
+      const int h0 = hp * RX, rows = min(RX, a.H - h0);
+      D px[4 * RX];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int k = 0; k < RX; ++k) px[j * RX + k] = v[j];
+      D* d = static_cast<D*>(a.dst) + (((long)n * a.Ci + ci0 + i) * a.H + h0) * a.W + wq * 4 * RX;
+      // one run per lane and row: a wave's store covers whole lines, which is what the streaming
+      // store wants; with several runs per lane each instruction writes parts of lines (plain stores)
+      for (int row = 0; row < rows; ++row)
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          if constexpr (NV == 1) store_stream16(d + (long)row * a.W, *reinterpret_cast<const uint4*>(px));
+          else *reinterpret_cast<uint4*>(d + (long)row * a.W + k * VE) = *reinterpret_cast<const uint4*>(px + k * VE);
+        }
+    }
   }
 }
 
+template <class D, int RX>
+static hipError_t q8_tile_launch(Q8DgradTileArgs& a, int ct, bool split, hipStream_t st) {
+  const dim3 block(kThreads), grid(cdiv((long)a.total * (split ? 4 : 1), kThreads));
+  if (ct == 4 && split) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 4, 4, RX>), grid, block, 0, st, a);
+  else if (ct == 4) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 4, 1, RX>), grid, block, 0, st, a);
+  else if (split) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 1, 4, RX>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((q8_dgrad_tile_k<D, 1, 1, RX>), grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+// the tile kernel can store full resolution itself when a lane's four patches share a patch row and
+// the pixel runs are whole 16-byte vectors
+static bool q8_dgrad_full_ok(const Geom& g) {
+  return g.P % 4 == 0 && g.Wp % 4 == 0 && (g.rx == 2 || g.rx == 4) && g.W == g.Wp * g.rx;
+}
+
+// full: dst is g_x at full resolution (only when q8_dgrad_full_ok), else the reduced map
 template <class D>
 static hipError_t q8_dgrad_launch(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float fscale, void* dst,
-                                  hipStream_t st) {
+                                  bool full, hipStream_t st) {
   if (g.P % 4 == 0) {
-    // 4 x 4 tiles when they still give the chip ~a wave per SIMD, else one channel per lane
-    const bool wide = g.Cg % 4 == 0 && (long)g.N * (g.Ci / 4) * (g.P / 4) >= 128 * 1024;
-    const int ct = wide ? 4 : 1;
+    // 4 x 4 tiles (fewest instructions per product) where the group width allows; when they are too
+    // few to fill the chip and the channel sum is long, four lanes share a tile
+    const int ct = g.Cg % 4 == 0 ? 4 : 1;
     Q8DgradTileArgs a;
     a.gyq = gy_q; a.wq = w_q; a.dst = dst;
     a.N = g.N; a.Ci = g.Ci; a.Co = g.Co; a.Cg = g.Cg; a.Og = g.Og; a.P = g.P;
@@ -314,10 +369,12 @@ static hipError_t q8_dgrad_launch(const Geom& g, const int8_t* gy_q, const int8_
     a.scale = fscale;
     a.d_p4 = FastDiv((uint32_t)(g.P / 4));
     a.d_ct = FastDiv((uint32_t)(g.Ci / ct));
-    const dim3 grid(cdiv(a.total, kThreads)), block(kThreads);
-    if (wide) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 4>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((q8_dgrad_tile_k<D, 1>), grid, block, 0, st, a);
-    return hipGetLastError();
+    a.H = g.H; a.W = g.W; a.Wq = g.Wp / 4 > 0 ? g.Wp / 4 : 1;
+    a.d_wq = FastDiv((uint32_t)a.Wq);
+    const bool split = g.Og >= 32 && a.total < 128 * 1024;
+    if (full && g.rx == 2) return q8_tile_launch<D, 2>(a, ct, split, st);
+    if (full) return q8_tile_launch<D, 4>(a, ct, split, st);
+    return q8_tile_launch<D, 0>(a, ct, split, st);
   }
   Q8DgradArgs a;
   a.gyq = gy_q; a.wq = w_q; a.dst = dst;
@@ -398,7 +455,7 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
 
 // the input gradient at full resolution goes through an fp32 reduced map in the workspace
 size_t ws_bwd_input_q8(const Geom& g, bool reduced_out) {
-  return reduced_out ? 0 : (size_t)g.N * g.Ci * g.P * sizeof(float);
+  return (reduced_out || q8_dgrad_full_ok(g)) ? 0 : (size_t)g.N * g.Ci * g.P * sizeof(float);
 }
 
 bool q8_shape_ok(const Geom& g) {
@@ -409,10 +466,10 @@ bool q8_shape_ok(const Geom& g) {
 hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float scale, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st) {
   const float fscale = scale / ((float)g.s * (float)g.s);
-  if (reduced_out)
-    return g.dtype == GF_BF16 ? q8_dgrad_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, st)
-                              : q8_dgrad_launch<float>(g, gy_q, w_q, fscale, g_x, st);
-  hipError_t e = q8_dgrad_launch<float>(g, gy_q, w_q, fscale, ws, st);
+  if (reduced_out || q8_dgrad_full_ok(g))
+    return g.dtype == GF_BF16 ? q8_dgrad_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, !reduced_out, st)
+                              : q8_dgrad_launch<float>(g, gy_q, w_q, fscale, g_x, !reduced_out, st);
+  hipError_t e = q8_dgrad_launch<float>(g, gy_q, w_q, fscale, ws, false, st);
   if (e != hipSuccess) return e;
   return launch_expand_f32(g, static_cast<const float*>(ws), g_x, st);
 }

@@ -219,9 +219,12 @@ def test_q8_entry_errors(lib):
     with pytest.raises(B.GfError) as ei:
         B.gf_filter_grad_q8(d, FAKE + 4, 1.0, FAKE)
     assert ei.value.status == B.GF_ERR_UNSUPPORTED
-    # full-resolution input gradient needs the fp32 reduced map as workspace
-    need = B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT_Q8)
-    assert need == d.N * d.C_in * 4 * 4 * 4
+    # full-resolution input gradient: no workspace when the kernel stores the pixel runs itself
+    # (patch rows of 4 k patches), else the fp32 reduced map
+    assert B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT_Q8) == 0
+    d12 = d.with_(H_in=12, W_in=12)
+    need = B.gf_workspace_bytes(d12, B.GF_OP_BWD_INPUT_Q8)
+    assert need == d12.N * d12.C_in * 6 * 6 * 4
     with pytest.raises(B.GfError) as ei:
-        B.gf_conv_bwd_input_q8(d, FAKE, FAKE, 1.0, FAKE, False, FAKE, need - 1)
+        B.gf_conv_bwd_input_q8(d12, FAKE, FAKE, 1.0, FAKE, False, FAKE, need - 1)
     assert ei.value.status == B.GF_ERR_WORKSPACE

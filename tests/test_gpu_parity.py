@@ -848,6 +848,7 @@ Q8_LAYERS = [
     (2, 32, 32, 15, 15, 3, 2, 32, 2),     # depthwise, stride 2, ragged
     (8, 256, 32, 64, 64, 1, 1, 1, 2),     # many input channels: 4 x 4 register tiles in the input gradient
     (8, 256, 64, 64, 64, 1, 1, 4, 2),     # the same with groups
+    (2, 8, 12, 30, 32, 3, 1, 1, 4),       # ragged last patch row under the fused full-resolution store
 ]
 
 
