@@ -12,8 +12,11 @@
 //  * q8_wgrad_pair_k   -- Eq. 5 for every other layer (groups, depthwise, unaligned planes): one
 //                         block per (c_o, c_i) pair, v_dot4_i32_i8 on 32-bit words where the plane
 //                         allows it, 64-bit sums
+//  * q8_dgrad_mfma_k   -- Eq. 3 for dense layers with many channels on both sides: the same MFMA after
+//                         a transposing LDS staging (K = c_o is contiguous in neither operand)
 //  * q8_dgrad_tile_k   -- Eq. 3 for planes that are multiples of four codes: a lane owns four patches
-//                         of four (or one) input channels and walks the group's c_o
+//                         of four (or one) input channels and walks the group's c_o; stores the
+//                         full-resolution pixel runs itself where the patch rows allow
 //  * q8_dgrad_k        -- Eq. 3 for the other planes: one lane per (n, c_i, patch)
 //    both write the reduced map (storage type), or an fp32 map that the expansion kernel of the
 //    floating-point path replicates to full resolution
@@ -338,6 +341,114 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_tile_k(Q8DgradTileArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Eq. 3 on the int8 matrix cores, dense layers with many channels on both sides:
+//   dst[n, ci, p] = float(sum_co w_q[co, ci] * gy_q[n, co, p]) * scale     (reduced map)
+// M = c_i, N = (n, p), K = c_o.  Neither operand has K contiguous in memory (w_q is [c_o][c_i],
+// gy_q is [n][c_o][p]), so a block reads 16-byte runs along c_i resp. p and writes them to LDS
+// transposed, byte by byte, as K-major rows; the MFMA fragments are then the same 16-byte reads
+// as in the weight gradient.  64 x 64 tiles, K chunks of 64.  (host: 16 | P, 16 | C_i)
+// ---------------------------------------------------------------------------
+struct Q8DgradMfmaArgs {
+  const int8_t* gyq;
+  const int8_t* wq;
+  void* dst;
+  int Ci, Co, P, Jtot;
+  float scale;
+  FastDiv d_p;
+};
+
+template <class D>
+__global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
+  constexpr int BK = 64, kRow = BK + 16;   // staged row: 64 codes of K + pad
+  __shared__ __attribute__((aligned(16))) unsigned char As[64 * kRow];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[64 * kRow];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  const int k = tid >> 2, vi = tid & 3;          // this lane's K row and 16-wide column group of a chunk
+  // the lane's 16 columns (n, p .. p + 15) do not depend on the chunk
+  const int j = j0 + vi * 16;
+  const int jc = min(j, a.Jtot - 16);
+  const int n = (int)a.d_p.div((uint32_t)jc);
+  const int8_t* gcol = a.gyq + (long)n * a.Co * a.P + (jc - n * a.P);
+  const int ci = m0 + vi * 16;
+  const int8_t* wcol = a.wq + min(ci, a.Ci - 16);
+  auto fetch = [&](int k0, uint4* ra, uint4* rb) {
+    const int co = k0 + k;
+    const int cc = min(co, a.Co - 1);
+    const uint4 va = *reinterpret_cast<const uint4*>(wcol + (long)cc * a.Ci);
+    const uint4 vb = *reinterpret_cast<const uint4*>(gcol + (long)cc * a.P);
+    *ra = (co < a.Co && ci < a.Ci) ? va : make_uint4(0, 0, 0, 0);
+    *rb = (co < a.Co && j < a.Jtot) ? vb : make_uint4(0, 0, 0, 0);
+  };
+  i32x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) acc[i][jj] = i32x4{0, 0, 0, 0};
+  uint4 ra, rb;
+  fetch(0, &ra, &rb);
+  const int r = lane & 15, kg = lane >> 4;
+  for (int k0 = 0; k0 < a.Co; k0 += BK) {
+    {  // transposed staging: code e of the run goes to row (vi * 16 + e), column k
+      const uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb.x, rb.y, rb.z, rb.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        As[(vi * 16 + e) * kRow + k] = (unsigned char)(wa[e >> 2] >> (8 * (e & 3)));
+        Bs[(vi * 16 + e) * kRow + k] = (unsigned char)(wb[e >> 2] >> (8 * (e & 3)));
+      }
+    }
+    __syncthreads();
+    if (k0 + BK < a.Co) fetch(k0 + BK, &ra, &rb);
+    i32x4 fa[2], fb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      fa[i] = *reinterpret_cast<const i32x4*>(As + ((wm * 2 + i) * 16 + r) * kRow + kg * 16);
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+      fb[jj] = *reinterpret_cast<const i32x4*>(Bs + ((wn * 2 + jj) * 16 + r) * kRow + kg * 16);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+        acc[i][jj] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[i], fb[jj], acc[i][jj], 0, 0, 0);
+    __syncthreads();
+  }
+  // D[row = 4 * (lane / 16) + v][col = lane % 16]: rows are c_i, columns (n, p)
+  D* dst = static_cast<D*>(a.dst);
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const int col = j0 + (wn * 2 + jj) * 16 + (lane & 15);
+    if (col >= a.Jtot) continue;
+    const int nn = (int)a.d_p.div((uint32_t)col);
+    const long base = (long)nn * a.Ci * a.P + (col - nn * a.P);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = m0 + (wm * 2 + i) * 16 + 4 * (lane >> 4) + v;
+        if (row < a.Ci) dst[base + (long)row * a.P] = from_f32<D>((float)acc[i][jj][v] * a.scale);
+      }
+  }
+}
+
+static bool q8_dgrad_mfma_ok(const Geom& g) {
+  return g.g == 1 && g.P % 16 == 0 && g.Ci % 16 == 0 && g.Ci >= 64 && g.Co >= 64;
+}
+
+template <class D>
+static hipError_t q8_dgrad_mfma_launch(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float fscale, void* dst,
+                                       hipStream_t st) {
+  Q8DgradMfmaArgs a;
+  a.gyq = gy_q; a.wq = w_q; a.dst = dst;
+  a.Ci = g.Ci; a.Co = g.Co; a.P = g.P; a.Jtot = g.N * g.P;
+  a.scale = fscale;
+  a.d_p = FastDiv((uint32_t)g.P);
+  hipLaunchKernelGGL(q8_dgrad_mfma_k<D>, dim3(cdiv(a.Jtot, 64), cdiv(g.Ci, 64)), dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
 template <class D, int RX>
 static hipError_t q8_tile_launch(Q8DgradTileArgs& a, int ct, bool split, hipStream_t st) {
   const dim3 block(kThreads), grid(cdiv((long)a.total * (split ? 4 : 1), kThreads));
@@ -455,7 +566,9 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
 
 // the input gradient at full resolution goes through an fp32 reduced map in the workspace
 size_t ws_bwd_input_q8(const Geom& g, bool reduced_out) {
-  return (reduced_out || q8_dgrad_full_ok(g)) ? 0 : (size_t)g.N * g.Ci * g.P * sizeof(float);
+  if (reduced_out) return 0;
+  if (!q8_dgrad_mfma_ok(g) && q8_dgrad_full_ok(g)) return 0;
+  return (size_t)g.N * g.Ci * g.P * sizeof(float);
 }
 
 bool q8_shape_ok(const Geom& g) {
@@ -466,6 +579,14 @@ bool q8_shape_ok(const Geom& g) {
 hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float scale, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st) {
   const float fscale = scale / ((float)g.s * (float)g.s);
+  if (q8_dgrad_mfma_ok(g)) {   // many channels on both sides: matrix cores, then the expansion
+    if (reduced_out)
+      return g.dtype == GF_BF16 ? q8_dgrad_mfma_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, st)
+                                : q8_dgrad_mfma_launch<float>(g, gy_q, w_q, fscale, g_x, st);
+    hipError_t e = q8_dgrad_mfma_launch<float>(g, gy_q, w_q, fscale, ws, st);
+    if (e != hipSuccess) return e;
+    return launch_expand_f32(g, static_cast<const float*>(ws), g_x, st);
+  }
   if (reduced_out || q8_dgrad_full_ok(g))
     return g.dtype == GF_BF16 ? q8_dgrad_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, !reduced_out, st)
                               : q8_dgrad_launch<float>(g, gy_q, w_q, fscale, g_x, !reduced_out, st);

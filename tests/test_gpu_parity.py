@@ -849,6 +849,10 @@ Q8_LAYERS = [
     (8, 256, 32, 64, 64, 1, 1, 1, 2),     # many input channels: 4 x 4 register tiles in the input gradient
     (8, 256, 64, 64, 64, 1, 1, 4, 2),     # the same with groups
     (2, 8, 12, 30, 32, 3, 1, 1, 4),       # ragged last patch row under the fused full-resolution store
+    (4, 128, 192, 32, 32, 1, 1, 1, 2),    # many channels on both sides: input gradient on the int8 matrix cores
+    (2, 64, 80, 16, 48, 3, 1, 1, 2),      # ... with a ragged last K chunk (80 = 64 + 16) and 192 columns per image
+    (3, 144, 64, 24, 24, 1, 1, 1, 2),     # ... with a ragged last c_i tile (144 = 2 * 64 + 16)
+    (2, 256, 512, 14, 14, 3, 2, 1, 2),    # ... stride 2, 4 x 4 plane (16 codes: one vector per image and channel)
 ]
 
 
