@@ -98,6 +98,13 @@ __device__ __forceinline__ float kernel_sum_of(const T* w, long pair, int KK) {
   return s;
 }
 
+// Signed 8-bit code of a value on a grid of step 1 / inv: the product and the rounding (half to
+// even) are taken in fp32, the code is clipped to +-127 (never -128)
+__device__ __forceinline__ int8_t q8_code(float v, float inv) {
+  const float r = fminf(fmaxf(__builtin_rintf(v * inv), -127.f), 127.f);
+  return (int8_t)(int)r;
+}
+
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 static inline int imin_host(int a, int b) { return a < b ? a : b; }
 

@@ -30,11 +30,6 @@ constexpr int kThreads = 256;
 constexpr int kRowBytes = 128 + 16;  // one staged row: 128 codes (K) + pad
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ int8_t q8_code(float v, float inv) {
-  const float r = fminf(fmaxf(__builtin_rintf(v * inv), -127.f), 127.f);
-  return (int8_t)(int)r;
-}
-
 template <class T>
 __global__ __launch_bounds__(kThreads) void kernel_sum_q8_k(const T* w, int8_t* w_q, int pairs, int KK, float inv) {
   const int e = blockIdx.x * kThreads + threadIdx.x;
@@ -323,7 +318,7 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_tile_k(Q8DgradTileArgs a) {
       const int hp = (int)a.d_wq.div((uint32_t)q);
       const int wq = q - hp * a.Wq;
       const int h0 = hp * RX, rows = min(RX, a.H - h0);
-      D px[4 * RX];
+      __attribute__((aligned(16))) D px[4 * RX];
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -356,9 +351,14 @@ struct Q8DgradMfmaArgs {
   int Ci, Co, P, Jtot;
   float scale;
   FastDiv d_p;
+  int H, W, Wp;    // full-resolution store (RX > 0)
+  FastDiv d_wp;
 };
 
-template <class D>
+// RX == 0: dst is the reduced map.  RX > 0: dst is g_x at full resolution; the tile is rounded to
+// the storage type in LDS and every lane stores the 16-byte pixel runs of four neighbouring patches
+// of one c_i (host: 4 | W_p, W == W_p * RX).
+template <class D, int RX>
 __global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
   constexpr int BK = 64, kRow = BK + 16;   // staged row: 64 codes of K + pad
   __shared__ __attribute__((aligned(16))) unsigned char As[64 * kRow];
@@ -417,19 +417,56 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
   }
   // D[row = 4 * (lane / 16) + v][col = lane % 16]: rows are c_i, columns (n, p)
   D* dst = static_cast<D*>(a.dst);
+  if constexpr (RX == 0) {
 #pragma unroll
-  for (int jj = 0; jj < 2; ++jj) {
-    const int col = j0 + (wn * 2 + jj) * 16 + (lane & 15);
-    if (col >= a.Jtot) continue;
-    const int nn = (int)a.d_p.div((uint32_t)col);
-    const long base = (long)nn * a.Ci * a.P + (col - nn * a.P);
+    for (int jj = 0; jj < 2; ++jj) {
+      const int col = j0 + (wn * 2 + jj) * 16 + (lane & 15);
+      if (col >= a.Jtot) continue;
+      const int nn = (int)a.d_p.div((uint32_t)col);
+      const long base = (long)nn * a.Ci * a.P + (col - nn * a.P);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int row = m0 + (wm * 2 + i) * 16 + 4 * (lane >> 4) + v;
+          if (row < a.Ci) dst[base + (long)row * a.P] = from_f32<D>((float)acc[i][jj][v] * a.scale);
+        }
+    }
+  } else {
+    constexpr int SC = 64 + 16 / (int)sizeof(D);   // row stride of the staged tile, in elements
+    __shared__ __attribute__((aligned(16))) D Cs[64 * SC];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = m0 + (wm * 2 + i) * 16 + 4 * (lane >> 4) + v;
-        if (row < a.Ci) dst[base + (long)row * a.P] = from_f32<D>((float)acc[i][jj][v] * a.scale);
-      }
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          Cs[((wm * 2 + i) * 16 + 4 * (lane >> 4) + v) * SC + (wn * 2 + jj) * 16 + (lane & 15)] =
+              from_f32<D>((float)acc[i][jj][v] * a.scale);
+    __syncthreads();
+    constexpr int VE = 16 / (int)sizeof(D), NV = 4 * RX / VE;
+    for (int it = tid; it < 64 * 16; it += kThreads) {
+      const int cl = it >> 4, quad = it & 15;          // 16 lanes = the 64 patches of one c_i row
+      const int cc = m0 + cl, jq = j0 + 4 * quad;
+      if (cc >= a.Ci || jq >= a.Jtot) continue;
+      const int nn = (int)a.d_p.div((uint32_t)jq);
+      const int p = jq - nn * a.P;
+      const int hp = (int)a.d_wp.div((uint32_t)p);
+      const int wp0 = p - hp * a.Wp;                   // a multiple of four: the four patches share a row
+      const int h0 = hp * RX, rows = min(RX, a.H - h0);
+      __attribute__((aligned(16))) D px[4 * RX];
+#pragma unroll
+      for (int jx = 0; jx < 4; ++jx)
+#pragma unroll
+        for (int kx = 0; kx < RX; ++kx) px[jx * RX + kx] = Cs[cl * SC + 4 * quad + jx];
+      D* d = dst + (((long)nn * a.Ci + cc) * a.H + h0) * a.W + wp0 * RX;
+      for (int row = 0; row < rows; ++row)
+#pragma unroll
+        for (int kx = 0; kx < NV; ++kx) {
+          if constexpr (NV == 1) store_stream16(d + (long)row * a.W, *reinterpret_cast<const uint4*>(px));
+          else *reinterpret_cast<uint4*>(d + (long)row * a.W + kx * VE) = *reinterpret_cast<const uint4*>(px + kx * VE);
+        }
+    }
   }
 }
 
@@ -437,15 +474,21 @@ static bool q8_dgrad_mfma_ok(const Geom& g) {
   return g.g == 1 && g.P % 16 == 0 && g.Ci % 16 == 0 && g.Ci >= 64 && g.Co >= 64;
 }
 
+// rx: 0 = reduced map, 2 / 4 = full resolution written by the kernel (see q8_dgrad_full_ok)
 template <class D>
 static hipError_t q8_dgrad_mfma_launch(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float fscale, void* dst,
-                                       hipStream_t st) {
+                                       int rx, hipStream_t st) {
   Q8DgradMfmaArgs a;
   a.gyq = gy_q; a.wq = w_q; a.dst = dst;
   a.Ci = g.Ci; a.Co = g.Co; a.P = g.P; a.Jtot = g.N * g.P;
   a.scale = fscale;
   a.d_p = FastDiv((uint32_t)g.P);
-  hipLaunchKernelGGL(q8_dgrad_mfma_k<D>, dim3(cdiv(a.Jtot, 64), cdiv(g.Ci, 64)), dim3(kThreads), 0, st, a);
+  a.H = g.H; a.W = g.W; a.Wp = g.Wp;
+  a.d_wp = FastDiv((uint32_t)g.Wp);
+  const dim3 grid(cdiv(a.Jtot, 64), cdiv(g.Ci, 64)), block(kThreads);
+  if (rx == 2) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 2>), grid, block, 0, st, a);
+  else if (rx == 4) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 4>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 0>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 
@@ -566,8 +609,7 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
 
 // the input gradient at full resolution goes through an fp32 reduced map in the workspace
 size_t ws_bwd_input_q8(const Geom& g, bool reduced_out) {
-  if (reduced_out) return 0;
-  if (!q8_dgrad_mfma_ok(g) && q8_dgrad_full_ok(g)) return 0;
+  if (reduced_out || q8_dgrad_full_ok(g)) return 0;
   return (size_t)g.N * g.Ci * g.P * sizeof(float);
 }
 
@@ -579,11 +621,13 @@ bool q8_shape_ok(const Geom& g) {
 hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* w_q, float scale, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st) {
   const float fscale = scale / ((float)g.s * (float)g.s);
-  if (q8_dgrad_mfma_ok(g)) {   // many channels on both sides: matrix cores, then the expansion
-    if (reduced_out)
-      return g.dtype == GF_BF16 ? q8_dgrad_mfma_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, st)
-                                : q8_dgrad_mfma_launch<float>(g, gy_q, w_q, fscale, g_x, st);
-    hipError_t e = q8_dgrad_mfma_launch<float>(g, gy_q, w_q, fscale, ws, st);
+  if (q8_dgrad_mfma_ok(g)) {   // many channels on both sides: matrix cores
+    if (reduced_out || q8_dgrad_full_ok(g)) {
+      const int rx = reduced_out ? 0 : g.rx;
+      return g.dtype == GF_BF16 ? q8_dgrad_mfma_launch<bf16_t>(g, gy_q, w_q, fscale, g_x, rx, st)
+                                : q8_dgrad_mfma_launch<float>(g, gy_q, w_q, fscale, g_x, rx, st);
+    }
+    hipError_t e = q8_dgrad_mfma_launch<float>(g, gy_q, w_q, fscale, ws, 0, st);
     if (e != hipSuccess) return e;
     return launch_expand_f32(g, static_cast<const float*>(ws), g_x, st);
   }

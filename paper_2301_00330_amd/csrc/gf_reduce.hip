@@ -47,12 +47,6 @@ struct ReduceArgs {
   float q_inv;
 };
 
-// code of a value on a grid of step 1 / inv: round half to even, clipped to +-127 (never -128)
-__device__ __forceinline__ int8_t q8_code(float v, float inv) {
-  const float r = fminf(fmaxf(__builtin_rintf(v * inv), -127.f), 127.f);
-  return (int8_t)(int)r;
-}
-
 // Fixed-order sum over the block of two floats per lane; block 0's lane 0 ... every block's
 // lane 0 writes its pair.  `red` is 2 * (kThreads / 64) floats of LDS.
 __device__ __forceinline__ void block_stats(float e, float n, float* red, float2* dst) {

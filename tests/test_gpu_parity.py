@@ -853,6 +853,7 @@ Q8_LAYERS = [
     (2, 64, 80, 16, 48, 3, 1, 1, 2),      # ... with a ragged last K chunk (80 = 64 + 16) and 192 columns per image
     (3, 144, 64, 24, 24, 1, 1, 1, 2),     # ... with a ragged last c_i tile (144 = 2 * 64 + 16)
     (2, 256, 512, 14, 14, 3, 2, 1, 2),    # ... stride 2, 4 x 4 plane (16 codes: one vector per image and channel)
+    (2, 64, 64, 30, 32, 1, 1, 1, 4),      # ... ragged last patch row under its full-resolution store
 ]
 
 
