@@ -965,6 +965,37 @@ def test_largest_tensors_sampled(oracle, case):
                 sd = oracle.Desc(N=1, C_in=4, C_out=C, H_in=H, W_in=W, r=r)
                 ref = oracle.bwd_input(sd, oracle.filter_grad(sd, to64(gy[n:n + 1])), to64(w[:, cs]))
                 assert np.abs(to64(g_x[n:n + 1, cs]) - ref).max() <= tol * gx_max
+    # the same tensors through the path on 8-bit codes: codes of the end planes, both contractions on slices
+    del g_x
+    inv_x, inv_g = 127.0 / float(x_u.float().abs().max()), 127.0 / float(gy_u.float().abs().max())
+    x_q = T.pool_activation_q8(d, x, inv_x)
+    gy_q = T.filter_grad_q8(d, gy, inv_g)
+    w_q = T.kernel_sum_q8(d, w, 127.0 / float(w.float().sum(dim=(2, 3)).abs().max()))
+    g_w8 = T.conv_bwd_weight_q8(d, x_q, gy_q, 1.0)
+    g_x8 = T.conv_bwd_input_q8(d, gy_q, w_q, 1.0)
+    torch.cuda.synchronize()
+    for n in ends:
+        for cs in chans:
+            sd = oracle.Desc(N=1, C_in=4, C_out=4, H_in=H, W_in=W, r=r)
+            check_codes(oracle, x_q[n:n + 1, cs], oracle.pool_activation(sd, to64(x[n:n + 1, cs])), inv_x, "x_q")
+            check_codes(oracle, gy_q[n:n + 1, cs], oracle.filter_grad(sd, to64(gy[n:n + 1, cs])), inv_g, "gy_q")
+    npq = lambda t: t.cpu().numpy()
+    if dw:
+        for cs in chans:
+            sd = oracle.Desc(N=N, C_in=4, C_out=4, H_in=H, W_in=W, K_h=K, K_w=K, pad=kw["p"], groups=4, r=r)
+            assert torch.equal(g_w8[cs].cpu(), torch.from_numpy(oracle.bwd_weight_q8(sd, npq(x_q[:, cs]), npq(gy_q[:, cs]), 1.0)))
+            ref = oracle.bwd_input_q8(sd, npq(gy_q[:, cs]), npq(w_q[cs]), 1.0)
+            assert torch.equal(g_x8[:, cs].cpu(), rounded(ref, dtype))
+    else:
+        for co, ci in [(0, 0), (C - 1, C - 1), (3, C - 2)]:
+            sd = oracle.Desc(N=N, C_in=1, C_out=1, H_in=H, W_in=W, r=r)
+            ref = oracle.bwd_weight_q8(sd, npq(x_q[:, ci:ci + 1]), npq(gy_q[:, co:co + 1]), 1.0)
+            assert float(g_w8[co, ci, 0, 0]) == float(ref[0, 0, 0, 0])
+        for n in ends:
+            for cs in chans:
+                sd = oracle.Desc(N=1, C_in=4, C_out=C, H_in=H, W_in=W, r=r)
+                ref = oracle.bwd_input_q8(sd, npq(gy_q[n:n + 1]), npq(w_q[:, cs]), 1.0)
+                assert torch.equal(g_x8[n:n + 1, cs].cpu(), rounded(ref, dtype))
 
 
 def test_entry_points_replay_from_a_hip_graph():
