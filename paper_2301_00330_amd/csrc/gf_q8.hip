@@ -5,11 +5,11 @@
 // sizes and 1/s^2.
 //
 //  * kernel_sum_q8_k   -- codes of the spatial kernel sum (text after Eq. 3)
-//  * q8_wgrad_mfma_k   -- Eq. 5 for dense layers whose reduced plane is a multiple of 16 patches:
+//  * q8_wgrad_mfma_k   -- Eq. 5 for dense layers whose reduced plane holds at least 16 patches:
 //                         v_mfma_i32_16x16x64_i8 on 64 x 64 tiles, K = (n, patch) split into slabs,
 //                         int32 partial slabs (a slab holds few enough products not to overflow),
 //                         q8_finalize_k adds them in 64 bits and scales
-//  * q8_wgrad_pair_k   -- Eq. 5 for every other layer (groups, depthwise, unaligned planes): one
+//  * q8_wgrad_pair_k   -- Eq. 5 for every other layer (groups, depthwise, tiny planes): one
 //                         block per (c_o, c_i) pair, v_dot4_i32_i8 on 32-bit words where the plane
 //                         allows it, 64-bit sums
 //  * q8_dgrad_mfma_k   -- Eq. 3 for dense layers with many channels on both sides: the same MFMA after
@@ -59,6 +59,61 @@ __device__ __forceinline__ uint4 load_codes(const int8_t* base, long img_stride,
   return k < ktot ? v : make_uint4(0, 0, 0, 0);
 }
 
+// 16 bytes from an address of any alignment
+struct __attribute__((packed, aligned(1))) Unal16 { uint32_t w[4]; };
+__device__ __forceinline__ uint4 load16_any(const int8_t* p) {
+  const Unal16 v = *reinterpret_cast<const Unal16*>(p);
+  return make_uint4(v.w[0], v.w[1], v.w[2], v.w[3]);
+}
+
+// out byte e = in byte e + sh, zero where e + sh falls outside 0 .. 15
+__device__ __forceinline__ uint4 shift_bytes(const uint4& v, int sh) {
+  if (sh == 0) return v;
+  if (sh >= 16 || sh <= -16) return make_uint4(0, 0, 0, 0);
+  uint64_t lo = (uint64_t)v.x | ((uint64_t)v.y << 32), hi = (uint64_t)v.z | ((uint64_t)v.w << 32);
+  int bits = sh * 8;   // 0 < |bits| < 128
+  if (bits > 0) {
+    if (bits >= 64) { lo = hi >> (bits - 64); hi = 0; }
+    else { lo = (lo >> bits) | (hi << (64 - bits)); hi >>= bits; }
+  } else {
+    bits = -bits;
+    if (bits >= 64) { hi = lo << (bits - 64); lo = 0; }
+    else { hi = (hi << bits) | (lo >> (64 - bits)); lo <<= bits; }
+  }
+  return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
+// The same for planes of any size P >= 16: the run k .. k + 15 may start anywhere in image n and
+// may continue in image n + 1.  Branch-free, both loads always issued: the part that lies in image
+// n comes from a load pulled back into that image and shifted, the part in image n + 1 from a load
+// at the start of the next image shifted the other way; codes at and beyond ktot are cleared.
+__device__ __forceinline__ uint4 load_codes_any(const int8_t* base, long img_stride, int k, int ktot, int P,
+                                                const FastDiv& d_p) {
+  const int kc = min(k, ktot - 1);
+  const int n = (int)d_p.div((uint32_t)kc);
+  const int p = kc - n * P;
+  const int pa = min(p, P - 16);
+  const int k1 = min(16, P - p);                         // codes of the run that belong to image n
+  const int nlast = (int)d_p.div((uint32_t)(ktot - 1));
+  const uint4 va = load16_any(base + (long)n * img_stride + pa);
+  const uint4 vb = load16_any(base + (long)min(n + 1, nlast) * img_stride);
+  const uint4 x = shift_bytes(va, p - pa);
+  const uint4 y = shift_bytes(vb, -k1);
+  uint4 v = make_uint4(x.x | y.x, x.y | y.y, x.z | y.z, x.w | y.w);
+  const int keep = ktot - k;                             // codes of the run before ktot
+  if (keep < 16) v = keep <= 0 ? make_uint4(0, 0, 0, 0) : shift_bytes(shift_bytes(v, -(16 - keep)), 16 - keep);
+  return v;
+}
+
+template <bool VEC>
+__device__ __forceinline__ uint4 load_codes_t(const int8_t* base, long img_stride, int k, int ktot, int P,
+                                              const FastDiv& d_p) {
+  if (VEC) return load_codes(base, img_stride, k, ktot, P, d_p);
+  return load_codes_any(base, img_stride, k, ktot, P, d_p);
+}
+
+// VEC: 16 | P (aligned vector loads); else planes of any size >= 16 through load_codes_any
+template <bool VEC>
 __global__ __launch_bounds__(kThreads) void q8_wgrad_mfma_k(Q8WgradArgs a) {
   constexpr int BM = 64, BN = 64, BK = 128;
   __shared__ __attribute__((aligned(16))) unsigned char As[BM * kRowBytes];
@@ -74,10 +129,10 @@ __global__ __launch_bounds__(kThreads) void q8_wgrad_mfma_k(Q8WgradArgs a) {
     for (int i = 0; i < 2; ++i) {
       const int s = tid + i * kThreads, row = s >> 3, vi = s & 7;
       const int co = m0 + row, ci = n0 + row;
-      const uint4 va = load_codes(a.gyq + (long)min(co, a.Co - 1) * a.P, (long)a.Co * a.P, kc * BK + vi * 16,
-                                  a.Ktot, a.P, a.d_p);
-      const uint4 vb = load_codes(a.xq + (long)min(ci, a.Ci - 1) * a.P, (long)a.Ci * a.P, kc * BK + vi * 16,
-                                  a.Ktot, a.P, a.d_p);
+      const uint4 va = load_codes_t<VEC>(a.gyq + (long)min(co, a.Co - 1) * a.P, (long)a.Co * a.P, kc * BK + vi * 16,
+                                         a.Ktot, a.P, a.d_p);
+      const uint4 vb = load_codes_t<VEC>(a.xq + (long)min(ci, a.Ci - 1) * a.P, (long)a.Ci * a.P, kc * BK + vi * 16,
+                                         a.Ktot, a.P, a.d_p);
       ra[i] = co < a.Co ? va : make_uint4(0, 0, 0, 0);
       rb[i] = ci < a.Ci ? vb : make_uint4(0, 0, 0, 0);
     }
@@ -358,7 +413,7 @@ struct Q8DgradMfmaArgs {
 // RX == 0: dst is the reduced map.  RX > 0: dst is g_x at full resolution; the tile is rounded to
 // the storage type in LDS and every lane stores the 16-byte pixel runs of four neighbouring patches
 // of one c_i (host: 4 | W_p, W == W_p * RX).
-template <class D, int RX>
+template <class D, int RX, bool VEC>
 __global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
   constexpr int BK = 64, kRow = BK + 16;   // staged row: 64 codes of K + pad
   __shared__ __attribute__((aligned(16))) unsigned char As[64 * kRow];
@@ -369,18 +424,15 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
   const int k = tid >> 2, vi = tid & 3;          // this lane's K row and 16-wide column group of a chunk
   // the lane's 16 columns (n, p .. p + 15) do not depend on the chunk
   const int j = j0 + vi * 16;
-  const int jc = min(j, a.Jtot - 16);
-  const int n = (int)a.d_p.div((uint32_t)jc);
-  const int8_t* gcol = a.gyq + (long)n * a.Co * a.P + (jc - n * a.P);
   const int ci = m0 + vi * 16;
   const int8_t* wcol = a.wq + min(ci, a.Ci - 16);
   auto fetch = [&](int k0, uint4* ra, uint4* rb) {
     const int co = k0 + k;
     const int cc = min(co, a.Co - 1);
     const uint4 va = *reinterpret_cast<const uint4*>(wcol + (long)cc * a.Ci);
-    const uint4 vb = *reinterpret_cast<const uint4*>(gcol + (long)cc * a.P);
+    const uint4 vb = load_codes_t<VEC>(a.gyq + (long)cc * a.P, (long)a.Co * a.P, j, a.Jtot, a.P, a.d_p);
     *ra = (co < a.Co && ci < a.Ci) ? va : make_uint4(0, 0, 0, 0);
-    *rb = (co < a.Co && j < a.Jtot) ? vb : make_uint4(0, 0, 0, 0);
+    *rb = co < a.Co ? vb : make_uint4(0, 0, 0, 0);
   };
   i32x4 acc[2][2];
 #pragma unroll
@@ -471,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
 }
 
 static bool q8_dgrad_mfma_ok(const Geom& g) {
-  return g.g == 1 && g.P % 16 == 0 && g.Ci % 16 == 0 && g.Ci >= 64 && g.Co >= 64;
+  return g.g == 1 && g.P >= 16 && g.Ci % 16 == 0 && g.Ci >= 64 && g.Co >= 64;
 }
 
 // rx: 0 = reduced map, 2 / 4 = full resolution written by the kernel (see q8_dgrad_full_ok)
@@ -486,9 +538,15 @@ static hipError_t q8_dgrad_mfma_launch(const Geom& g, const int8_t* gy_q, const 
   a.H = g.H; a.W = g.W; a.Wp = g.Wp;
   a.d_wp = FastDiv((uint32_t)g.Wp);
   const dim3 grid(cdiv(a.Jtot, 64), cdiv(g.Ci, 64)), block(kThreads);
-  if (rx == 2) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 2>), grid, block, 0, st, a);
-  else if (rx == 4) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 4>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 0>), grid, block, 0, st, a);
+  if (g.P % 16 == 0) {
+    if (rx == 2) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 2, true>), grid, block, 0, st, a);
+    else if (rx == 4) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 4, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 0, true>), grid, block, 0, st, a);
+  } else {
+    if (rx == 2) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 2, false>), grid, block, 0, st, a);
+    else if (rx == 4) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 4, false>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 0, false>), grid, block, 0, st, a);
+  }
   return hipGetLastError();
 }
 
@@ -556,7 +614,7 @@ hipError_t launch_kernel_sum_q8(const Geom& g, const void* w, float inv_delta, i
   return hipGetLastError();
 }
 
-static bool q8_wgrad_mfma_ok(const Geom& g) { return g.g == 1 && g.P % 16 == 0 && g.Co >= 16 && g.Ci >= 16; }
+static bool q8_wgrad_mfma_ok(const Geom& g) { return g.g == 1 && g.P >= 16 && g.Co >= 16 && g.Ci >= 16; }
 
 // K slabs of the MFMA kernel: ~1024 blocks, at least two chunks per block, and few enough
 // products per slab for the int32 partial sums
@@ -588,7 +646,9 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
     a.nchunks = cdiv((long)g.N * g.P, 128);
     const int nz = q8_wgrad_splits(g, &a.chunks_per_z);
     a.d_p = FastDiv((uint32_t)g.P);
-    hipLaunchKernelGGL(q8_wgrad_mfma_k, dim3(cdiv(g.Ci, 64), cdiv(g.Co, 64), nz), dim3(kThreads), 0, st, a);
+    const dim3 grid(cdiv(g.Ci, 64), cdiv(g.Co, 64), nz);
+    if (g.P % 16 == 0) hipLaunchKernelGGL(q8_wgrad_mfma_k<true>, grid, dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL(q8_wgrad_mfma_k<false>, grid, dim3(kThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int pairs = g.Co * g.Ci;

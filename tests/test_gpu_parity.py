@@ -854,6 +854,12 @@ Q8_LAYERS = [
     (3, 144, 64, 24, 24, 1, 1, 1, 2),     # ... with a ragged last c_i tile (144 = 2 * 64 + 16)
     (2, 256, 512, 14, 14, 3, 2, 1, 2),    # ... stride 2, 4 x 4 plane (16 codes: one vector per image and channel)
     (2, 64, 64, 30, 32, 1, 1, 1, 4),      # ... ragged last patch row under its full-resolution store
+    (3, 96, 576, 14, 14, 1, 1, 1, 2),     # 7 x 7 planes (49 codes): runs that cross image boundaries, both MFMA kernels
+    (3, 576, 96, 14, 14, 1, 1, 1, 2),
+    (2, 128, 64, 30, 40, 3, 1, 1, 2),     # planes of 300 codes, full-resolution store after unaligned loads
+    (5, 64, 64, 10, 6, 1, 1, 1, 2),       # planes of 15 codes: below one vector, no matrix cores
+    (5, 64, 64, 8, 8, 1, 1, 1, 2),        # planes of exactly 16 codes
+    (1, 64, 64, 10, 8, 1, 1, 1, 2),       # a single image of 20 codes: the last run is cut by the end of the tensor
 ]
 
 
