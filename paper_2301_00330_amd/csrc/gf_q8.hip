@@ -5,7 +5,7 @@
 // sizes and 1/s^2.
 //
 //  * kernel_sum_q8_k   -- codes of the spatial kernel sum (text after Eq. 3)
-//  * q8_wgrad_mfma_k   -- Eq. 5 for dense layers whose reduced plane holds at least 16 patches:
+//  * q8_wgrad_mfma_k   -- Eq. 5 for dense layers with at least 16 channels on both sides:
 //                         v_mfma_i32_16x16x64_i8 on 64 x 64 tiles, K = (n, patch) split into slabs,
 //                         int32 partial slabs (a slab holds few enough products not to overflow),
 //                         q8_finalize_k adds them in 64 bits and scales
@@ -83,12 +83,23 @@ __device__ __forceinline__ uint4 shift_bytes(const uint4& v, int sh) {
   return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
 }
 
-// The same for planes of any size P >= 16: the run k .. k + 15 may start anywhere in image n and
+// The same for planes of any size.  P >= 16: the run k .. k + 15 may start anywhere in image n and
 // may continue in image n + 1.  Branch-free, both loads always issued: the part that lies in image
 // n comes from a load pulled back into that image and shifted, the part in image n + 1 from a load
 // at the start of the next image shifted the other way; codes at and beyond ktot are cleared.
 __device__ __forceinline__ uint4 load_codes_any(const int8_t* base, long img_stride, int k, int ktot, int P,
                                                 const FastDiv& d_p) {
+  if (P < 16) {   // planes smaller than a run (2 x 2, 3 x 3 patch grids): the run is gathered code by code
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int kk = min(k + e, ktot - 1);
+      const int n = (int)d_p.div((uint32_t)kk);
+      const uint32_t c = (uint32_t)(uint8_t)base[(long)n * img_stride + (kk - n * P)];
+      w[e >> 2] |= (k + e < ktot ? c : 0u) << (8 * (e & 3));
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
   const int kc = min(k, ktot - 1);
   const int n = (int)d_p.div((uint32_t)kc);
   const int p = kc - n * P;
@@ -523,7 +534,7 @@ __global__ __launch_bounds__(kThreads) void q8_dgrad_mfma_k(Q8DgradMfmaArgs a) {
 }
 
 static bool q8_dgrad_mfma_ok(const Geom& g) {
-  return g.g == 1 && g.P >= 16 && g.Ci % 16 == 0 && g.Ci >= 64 && g.Co >= 64;
+  return g.g == 1 && g.Ci % 16 == 0 && g.Ci >= 64 && g.Co >= 64;
 }
 
 // rx: 0 = reduced map, 2 / 4 = full resolution written by the kernel (see q8_dgrad_full_ok)
@@ -614,7 +625,7 @@ hipError_t launch_kernel_sum_q8(const Geom& g, const void* w, float inv_delta, i
   return hipGetLastError();
 }
 
-static bool q8_wgrad_mfma_ok(const Geom& g) { return g.g == 1 && g.P >= 16 && g.Co >= 16 && g.Ci >= 16; }
+static bool q8_wgrad_mfma_ok(const Geom& g) { return g.g == 1 && g.Co >= 16 && g.Ci >= 16; }
 
 // K slabs of the MFMA kernel: ~1024 blocks, at least two chunks per block, and few enough
 // products per slab for the int32 partial sums

@@ -857,7 +857,10 @@ Q8_LAYERS = [
     (3, 96, 576, 14, 14, 1, 1, 1, 2),     # 7 x 7 planes (49 codes): runs that cross image boundaries, both MFMA kernels
     (3, 576, 96, 14, 14, 1, 1, 1, 2),
     (2, 128, 64, 30, 40, 3, 1, 1, 2),     # planes of 300 codes, full-resolution store after unaligned loads
-    (5, 64, 64, 10, 6, 1, 1, 1, 2),       # planes of 15 codes: below one vector, no matrix cores
+    (5, 64, 64, 10, 6, 1, 1, 1, 2),       # planes of 15 codes: below one run, gathered code by code
+    (6, 64, 96, 4, 4, 1, 1, 1, 2),        # planes of 4 codes
+    (4, 512, 512, 7, 7, 3, 1, 1, 4),      # 7 x 7 maps at r = 4: 2 x 2 ragged patch grid
+    (1, 16, 16, 4, 4, 1, 1, 1, 2),        # the whole K is four codes
     (5, 64, 64, 8, 8, 1, 1, 1, 2),        # planes of exactly 16 codes
     (1, 64, 64, 10, 8, 1, 1, 1, 2),       # a single image of 20 codes: the last run is cut by the end of the tensor
 ]
