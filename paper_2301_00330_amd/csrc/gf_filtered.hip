@@ -479,6 +479,63 @@ hipError_t launch_expand_rows(ExpandRowsArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// The same for planes small enough to stage, without per-channel factors: a block owns a run of
+// whole consecutive planes (contiguous in the output), builds their pixels in LDS -- every patch
+// value times `scalar`, rounded once to the storage type, written to its r_x x r_x pixels -- and
+// streams the run out with 16-byte vectors.  The planes per block are a multiple of the smallest
+// count whose bytes are a multiple of 16, so every run starts on a 16-byte boundary; only the
+// last block can end with a partial vector.
+struct ExpandPlanesArgs {
+  const void* src;   // [planes, P]
+  void* out;         // [planes, H, W]
+  float scalar;
+  int planes, ppb, H, W, Wp, P, rx;
+  FastDiv d_p, d_wp;
+};
+
+template <class T, class S>
+__global__ __launch_bounds__(kThreads) void expand_planes_k(ExpandPlanesArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T* img = reinterpret_cast<T*>(smem);
+  const int tid = threadIdx.x;
+  const int pl0 = blockIdx.x * a.ppb;
+  const int np = min(a.ppb, a.planes - pl0);
+  const int HW = a.H * a.W;
+  const S* src = static_cast<const S*>(a.src) + (long)pl0 * a.P;
+  for (int i = tid; i < np * a.P; i += kThreads) {
+    const int pl = (int)a.d_p.div((uint32_t)i);
+    const int pp = i - pl * a.P;
+    const int hp = (int)a.d_wp.div((uint32_t)pp);
+    const int wp = pp - hp * a.Wp;
+    const T v = from_f32<T>(to_f32(src[i]) * a.scalar);
+    const int h1 = min(a.H, (hp + 1) * a.rx), w1 = min(a.W, (wp + 1) * a.rx);
+    for (int h = hp * a.rx; h < h1; ++h)
+      for (int w = wp * a.rx; w < w1; ++w) img[pl * HW + h * a.W + w] = v;
+  }
+  __syncthreads();
+  T* out = static_cast<T*>(a.out) + (long)pl0 * HW;
+  const int nelem = np * HW;
+  constexpr int VE = 16 / (int)sizeof(T);
+  const int nvec = nelem / VE;
+  for (int v = tid; v < nvec; v += kThreads)
+    store_stream16(out + (long)v * VE, *reinterpret_cast<const uint4*>(smem + ((long)v << 4)));
+  for (int e = nvec * VE + tid; e < nelem; e += kThreads) out[e] = img[e];
+}
+
+constexpr int kExpandPlanesLds = 32 * 1024;
+
+// planes per block of expand_planes_k, 0 if the planes are too large to stage
+static int expand_planes_per_block(long planes, int H, int W, int elem_bytes) {
+  const long plane_bytes = (long)H * W * elem_bytes;
+  long gcd = 16, r = plane_bytes % 16;
+  while (r) { const long t = gcd % r; gcd = r; r = t; }
+  const long align = 16 / gcd;                                // planes whose bytes are a multiple of 16
+  if (align * plane_bytes > kExpandPlanesLds) return 0;
+  long ppb = (kExpandPlanesLds / (align * plane_bytes)) * align;
+  while (ppb > align && planes / ppb < 1024) ppb -= align;    // enough blocks for the chip
+  return (int)ppb;
+}
+
 template <class T, class S>
 hipError_t launch_expand(const S* src, T* out, const float* chscale, float scalar, long planes,
                          int C, int H, int W, int rx, int Hp, int Wp, hipStream_t st,
@@ -498,6 +555,19 @@ hipError_t launch_expand(const S* src, T* out, const float* chscale, float scala
     if (rx == 4) return launch_expand_rows<T, S, 4>(e, st);
     if (rx == 8) return launch_expand_rows<T, S, 8>(e, st);
     return launch_expand_rows<T, S, 16>(e, st);
+  }
+  if (!wdw && !chscale) {
+    const int ppb = expand_planes_per_block(planes, H, W, (int)sizeof(T));
+    if (ppb > 0) {
+      ExpandPlanesArgs e;
+      e.src = src; e.out = out; e.scalar = scalar;
+      e.planes = (int)planes; e.ppb = ppb; e.H = H; e.W = W; e.Wp = Wp; e.P = Hp * Wp; e.rx = rx;
+      e.d_p = FastDiv((uint32_t)(Hp * Wp));
+      e.d_wp = FastDiv((uint32_t)Wp);
+      hipLaunchKernelGGL((expand_planes_k<T, S>), dim3(cdiv(planes, ppb)), dim3(kThreads),
+                         (size_t)ppb * H * W * sizeof(T), st, e);
+      return hipGetLastError();
+    }
   }
   if (wdw) {  // generic path wants the per-channel sums in memory
     hipError_t err = launch_kernel_sum(wdw, wsum_scratch, C, KK, sizeof(T) == 2 ? GF_BF16 : GF_F32, st);
