@@ -18,8 +18,8 @@
 //                         of four (or one) input channels and walks the group's c_o; stores the
 //                         full-resolution pixel runs itself where the patch rows allow
 //  * q8_dgrad_k        -- Eq. 3 for the other planes: one lane per (n, c_i, patch)
-//    both write the reduced map (storage type), or an fp32 map that the expansion kernel of the
-//    floating-point path replicates to full resolution
+//    all three write the reduced map (storage type), or, where they cannot store full resolution
+//    themselves, an fp32 map that the expansion kernels of the floating-point path replicate
 #include "gf_internal.h"
 
 namespace gf {
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kThreads) void kernel_sum_q8_k(const T* w, int8_t* 
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 5, dense, P % 16 == 0: part[z, co, ci] = sum over the K chunks of slab z of gy_q * x_q
+// Eq. 5, dense: part[z, co, ci] = sum over the K chunks of slab z of gy_q * x_q
 // ---------------------------------------------------------------------------
 struct Q8WgradArgs {
   const int8_t* gyq;
