@@ -206,7 +206,8 @@ gf_status gf_conv_bwd_chained(const gf_conv_desc* desc, const void* gy_u, const 
  * and the integer is scaled once: `scale` is the product of the two step sizes, the library
  * multiplies by 1/stride^2.  Codes are int8 tensors in the layout of the map they stand for,
  * 16-byte aligned.  r == 1 (no reduced maps) and inv_delta <= 0: GF_ERR_UNSUPPORTED /
- * GF_ERR_BAD_DESC.  The product and the rounding of the code are taken in fp32. ---- */
+ * GF_ERR_BAD_DESC.  The product and the rounding of the code are taken in fp32; a NaN gets the
+ * code -127. ---- */
 
 /* S1 with code output: gy_q [N, C_out, H_p, W_p] = codes of the r x r patch means of g_y (Eq. 2). */
 gf_status gf_filter_grad_q8(const gf_conv_desc* desc, const void* g_y, float inv_delta, int8_t* gy_q,

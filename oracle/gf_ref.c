@@ -342,7 +342,7 @@ int gf_ref_quantize_q8(const double* v, long n, float inv_delta, signed char* q)
     float t = (float)v[i] * inv_delta; /* binary32 product */
     float r = rintf(t);                /* round half to even (default rounding mode) */
     if (r > 127.0f) r = 127.0f;
-    if (r < -127.0f) r = -127.0f;
+    if (!(r >= -127.0f)) r = -127.0f; /* also a NaN: it is clipped like minus infinity */
     q[i] = (signed char)r;
   }
   return REF_OK;

@@ -95,7 +95,8 @@ int gf_ref_conv_fwd(const gf_ref_desc* d, const double* x, const double* w, doub
  * the kernel sum are held as codes; Eq. 5 and Eq. 3 are then integer contractions, exact, and the
  * caller scales the integer once by the product of the two step sizes (and 1/s^2). ---- */
 /* q[i] = clip(round_half_even((float)v[i] * inv_delta), -127, 127); the product and the rounding are
- * taken in binary32, the precision in which the GPU kernels take the same decision. */
+ * taken in binary32, the precision in which the GPU kernels take the same decision.  A NaN gets
+ * the code -127 (it fails every comparison of the clip, like minus infinity). */
 int gf_ref_quantize_q8(const double* v, long n, float inv_delta, signed char* q);
 /* Eq. 5 on codes: acc[c_o, c_i'] = sum over (n, patch) of x_q * gy_q.  [C_out, C_in/groups], exact. */
 int gf_ref_bwd_weight_q8(const gf_ref_desc* d, const signed char* x_q, const signed char* gy_q, long long* acc);

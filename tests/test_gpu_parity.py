@@ -834,6 +834,16 @@ def test_q8_codes_bit_exact_on_integers(oracle, H, W, r, s, dtype):
         assert np.array_equal(gy_q.cpu().numpy(), oracle.filter_grad_q8(od, to64(gy), inv))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_q8_codes_of_non_finite_values(oracle, dtype):
+    d = mk(1, 2, 2, 8, 8, K=1, p=0, r=2, dtype=dtype)
+    gy = randn((1, 2, 8, 8), 5, dtype)
+    gy[0, 0, 0, 0], gy[0, 0, 2, 2], gy[0, 1, 4, 4] = float("nan"), float("inf"), float("-inf")
+    q = T.filter_grad_q8(d, gy.cuda(), 3.0).cpu().numpy()
+    assert np.array_equal(q, oracle.filter_grad_q8(odesc(oracle, d), to64(gy), 3.0))
+    assert q[0, 0, 0, 0] == -127 and q[0, 0, 1, 1] == 127 and q[0, 1, 2, 2] == -127
+
+
 Q8_LAYERS = [
     # N  Ci  Co   H   W  K  s  g   r     note
     (4, 24, 144, 56, 56, 1, 1, 1, 2),     # dense, plane of 784 codes: MFMA weight gradient

@@ -533,6 +533,8 @@ def test_q8_codes_by_hand(oracle):
     assert np.array_equal(oracle.quantize_q8(np.array([0.25, 0.3, -0.4, 40.0]), 4.0), np.array([1, 1, -2, 127], np.int8))
     with pytest.raises(oracle.OracleError):
         oracle.quantize_q8(v, 0.0)
+    # infinities are clipped; a NaN fails every comparison of the clip and lands on -127
+    assert np.array_equal(oracle.quantize_q8(np.array([np.inf, -np.inf, np.nan]), 1.0), np.array([127, -127, -127], np.int8))
 
 
 def test_q8_round_trip_error_is_half_a_step(oracle):
