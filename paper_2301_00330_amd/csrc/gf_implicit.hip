@@ -325,11 +325,23 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
     }
   };
 
+  // bf16 with an even number of 16-row blocks per wave in both directions: 32 x 32 x 16 MFMAs
+  constexpr bool BIG = sizeof(T) == 2 && TM % 2 == 0 && TN % 2 == 0;
   f32x4 acc[TM][TN];
+  f32x16 acc32[BIG ? TM / 2 : 1][BIG ? TN / 2 : 1];
+  if constexpr (BIG) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM / 2; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < TN / 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
   if (kc0 < kc1) fetch(kc0);
   const int r = lane & 15, kg = lane >> 4;
@@ -337,6 +349,23 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
     stage(kc);
     __syncthreads();
     if (kc + 1 < kc1) fetch(kc + 1);
+    if constexpr (BIG) {
+      const int r32 = lane & 31, kh = lane >> 5;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        uint4 fa[TM / 2], fb[TN / 2];
+#pragma unroll
+        for (int i = 0; i < TM / 2; ++i)
+          fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * TM + 2 * i) * 16 + r32) * RB + ks * 32 + kh * 16);
+#pragma unroll
+        for (int j = 0; j < TN / 2; ++j)
+          fb[j] = *reinterpret_cast<const uint4*>(Bs + ((wn * TN + 2 * j) * 16 + r32) * RB + ks * 32 + kh * 16);
+#pragma unroll
+        for (int i = 0; i < TM / 2; ++i)
+#pragma unroll
+          for (int j = 0; j < TN / 2; ++j) acc32[i][j] = mma32(fa[i], fb[j], acc32[i][j]);
+      }
+    } else
 #pragma unroll
     for (int ks = 0; ks < BK / KSTEP; ++ks) {
       if constexpr (sizeof(T) == 2) {
@@ -367,8 +396,22 @@ __global__ __launch_bounds__(kThreads) void xwgrad_k(XWgradArgs a) {
     }
     __syncthreads();
   }
-  // D[i = 4 * (lane / 16) + v][j = lane % 16] of every 16 x 16 tile
   float* dst = a.part + ((long)z * a.KK + t) * a.Co * a.Ci;
+  if constexpr (BIG) {  // element v: row 8 * (v / 4) + 4 * (lane / 32) + v % 4, column lane % 32 of a 32 x 32 tile
+#pragma unroll
+    for (int i = 0; i < TM / 2; ++i)
+#pragma unroll
+      for (int j = 0; j < TN / 2; ++j) {
+        const int ci = n0 + (wn * TN + 2 * j) * 16 + (lane & 31);
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+          const int co = m0 + (wm * TM + 2 * i) * 16 + 8 * (vv >> 2) + 4 * (lane >> 5) + (vv & 3);
+          if (co < a.Co && ci < a.Ci) dst[(long)co * a.Ci + ci] = acc32[i][j][vv];
+        }
+      }
+    return;
+  }
+  // D[i = 4 * (lane / 16) + v][j = lane % 16] of every 16 x 16 tile
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -597,11 +640,23 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
     }
   };
 
+  // bf16 with an even number of 16-row blocks per wave in both directions: 32 x 32 x 16 MFMAs
+  constexpr bool BIG = sizeof(T) == 2 && TM % 2 == 0 && TN % 2 == 0;
   f32x4 acc[TM][TN];
+  f32x16 acc32[BIG ? TM / 2 : 1][BIG ? TN / 2 : 1];
+  if constexpr (BIG) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM / 2; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < TN / 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
 #pragma unroll
   for (int dd = 0; dd < DEPTH; ++dd)
@@ -615,7 +670,25 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
       stage(regs[dd], it);
       __syncthreads();
       if (it + DEPTH < iters) fetch(regs[dd], it + DEPTH);
-      if constexpr (sizeof(T) == 2) {
+      if constexpr (BIG) {
+        const int r32 = lane & 31, kh = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {  // 16 k = 8 pair rows per MFMA
+          uint4 fa[TM / 2], fb[TN / 2];
+#pragma unroll
+          for (int i = 0; i < TM / 2; ++i)
+            fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * TM + 2 * i) * 16 + r32) * RB + ks * 32 + kh * 16);
+#pragma unroll
+          for (int j = 0; j < TN / 2; ++j) {
+            const uint32_t* p = Bs + (ks * 8 + kh * 4) * SB + (wn * TN + 2 * j) * 16 + r32;
+            fb[j] = make_uint4(p[0], p[SB], p[2 * SB], p[3 * SB]);
+          }
+#pragma unroll
+          for (int i = 0; i < TM / 2; ++i)
+#pragma unroll
+            for (int j = 0; j < TN / 2; ++j) acc32[i][j] = mma32(fa[i], fb[j], acc32[i][j]);
+        }
+      } else if constexpr (sizeof(T) == 2) {
 #pragma unroll
         for (int ks = 0; ks < BK / KSTEP; ++ks) {  // 32 k = 16 pair rows per MFMA
           uint4 fa[TM], fb[TN];
@@ -658,16 +731,29 @@ __global__ __launch_bounds__(kThreads) void xdgrad_k(XDgradArgs a) {
   constexpr int HM = BM / 2;
   for (int half = 0; half < 2; ++half) {
     if (wm == half) {
+      if constexpr (BIG) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM / 2; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+          for (int j = 0; j < TN / 2; ++j)
 #pragma unroll
-          for (int vv = 0; vv < 4; ++vv) {
-            const int row = i * 16 + 4 * (lane >> 4) + vv;
-            const int col = (wn * TN + j) * 16 + (lane & 15);
-            Cs[row * SC + col] = from_f32<T>(acc[i][j][vv]);
-          }
+            for (int vv = 0; vv < 16; ++vv) {
+              const int row = i * 32 + 8 * (vv >> 2) + 4 * (lane >> 5) + (vv & 3);
+              const int col = (wn * TN + 2 * j) * 16 + (lane & 31);
+              Cs[row * SC + col] = from_f32<T>(acc32[i][j][vv]);
+            }
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int vv = 0; vv < 4; ++vv) {
+              const int row = i * 16 + 4 * (lane >> 4) + vv;
+              const int col = (wn * TN + j) * 16 + (lane & 15);
+              Cs[row * SC + col] = from_f32<T>(acc[i][j][vv]);
+            }
+      }
     }
     __syncthreads();
     for (int s = tid; s < HM * VPB; s += kThreads) {

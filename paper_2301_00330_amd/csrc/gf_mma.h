@@ -31,6 +31,15 @@ __device__ __forceinline__ f32x4 mma16(const uint4& a, const uint4& b, f32x4 c) 
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
+// bf16, 32 x 32 x 16 (v_mfma_f32_32x32x16_bf16): A: lane holds row lane % 32, k = 8 * (lane / 32) .. + 7;
+// B alike with the column; D: element v of the lane is row 8 * (v / 4) + 4 * (lane / 32) + v % 4 of
+// column lane % 32.  A register-only loop of it measures 2.47 PFLOP/s on MI355X, one of the
+// 16 x 16 x 32 form 1.40 PFLOP/s, so MFMA-bound bf16 loops use this one.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ f32x16 mma32(const uint4& a, const uint4& b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                 0, 0, 0);
+}
 __device__ __forceinline__ f32x4 mma16(float a, float b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
