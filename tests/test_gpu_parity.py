@@ -613,6 +613,55 @@ def test_exact_backward(oracle, case, dtype):
     assert none_x is None and torch.equal(only_w, g_w)
 
 
+RECT_EXACT = [
+    # N Ci Co  H   W  Kh Kw s p d g     kernels that are not square
+    (2, 16, 24, 12, 12, 1, 3, 1, 1, 1, 1), (2, 8, 8, 10, 10, 3, 1, 1, 1, 1, 1), (2, 8, 8, 9, 9, 3, 2, 2, 1, 1, 1),
+    (2, 6, 6, 12, 12, 3, 5, 1, 2, 1, 6), (2, 64, 72, 14, 14, 3, 1, 1, 1, 1, 1), (1, 8, 16, 11, 13, 2, 5, 1, 2, 2, 2),
+    (3, 32, 32, 16, 16, 1, 5, 1, 2, 1, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", RECT_EXACT)
+def test_exact_backward_rectangular_kernels(oracle, case, dtype):
+    N, Ci, Co, H, W, Kh, Kw, s, p, dl, g = case
+    d = B.ConvDesc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=Kh, K_w=Kw, stride=s, pad=p, dilation=dl, groups=g,
+                   r=1, dtype=B.GF_BF16 if dtype == "bf16" else B.GF_F32)
+    od = odesc(oracle, d)
+    Hy, Wy, _, _ = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 51, dtype, relu=True)
+    w = randn((Co, Ci // g, Kh, Kw), 52, dtype, scale=0.3)
+    gy = randn((N, Co, Hy, Wy), 53, dtype)
+    ref_gw, ref_gx = oracle.bwd_exact(od, to64(x), to64(w), to64(gy))
+    g_w, g_x = T.conv_bwd_exact(d, x.cuda(), w.cuda(), gy.cuda())
+    assert rel_err(g_w, ref_gw) <= TOL[dtype]
+    assert rel_err(g_x, ref_gx) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [(2, 8, 12, 8, 7, 3, 2, 1, 1, 2), (2, 6, 6, 8, 7, 3, 2, 1, 6, 2),
+                                  (2, 16, 16, 15, 16, 2, 3, 1, 1, 4), (2, 32, 48, 16, 16, 3, 4, 1, 1, 2)])
+def test_filtered_backward_rectangular_kernels(oracle, case, dtype):
+    """Eq. 3 / Eq. 5 read the kernel through its sum over BOTH tap indices and write all K_h x K_w taps."""
+    N, Ci, Co, H, W, Kh, Kw, p, g, r = case
+    d = B.ConvDesc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=Kh, K_w=Kw, stride=1, pad=p, dilation=1, groups=g,
+                   r=r, dtype=B.GF_BF16 if dtype == "bf16" else B.GF_F32)
+    od = odesc(oracle, d)
+    Hy, Wy, _, _ = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 61, dtype, relu=True)
+    w = randn((Co, Ci // g, Kh, Kw), 62, dtype, scale=0.3)
+    gy = randn((N, Co, Hy, Wy), 63, dtype)
+    x_u = T.pool_activation(d, x.cuda())
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=True)
+    s_gw, s_gx = T.conv_bwd_weight(d, x_u, gy_u), T.conv_bwd_input(d, gy_u, w.cuda())
+    torch.cuda.synchronize()
+    ref_gw, ref_gx, _, _ = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    for got_w, got_x in ((g_w, g_x), (s_gw, s_gx)):
+        assert rel_err(got_w, ref_gw) <= TOL[dtype] and rel_err(got_x, ref_gx) <= TOL[dtype]
+    assert tuple(g_w.shape) == (Co, Ci // g, Kh, Kw)
+    assert torch.equal(g_w, g_w[:, :, :1, :1].expand_as(g_w))   # every tap carries the same value
+
+
 # ---------------------------------------------------------------------------
 # whole filtered backward on the benchmark configurations
 # ---------------------------------------------------------------------------

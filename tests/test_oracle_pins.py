@@ -26,6 +26,35 @@ def D(o, **kw):
     return o.Desc(**kw)
 
 
+RECT_CASES = [
+    # N Ci Co H  W  Kh Kw s p d g      kernels that are not square: the two tap loops must not be swapped
+    (2, 3, 4, 7, 6, 1, 3, 1, 1, 1, 1),
+    (1, 4, 6, 9, 9, 3, 1, 2, 1, 1, 2),
+    (2, 4, 4, 8, 8, 2, 3, 1, 2, 2, 4),
+    (1, 2, 3, 6, 7, 5, 2, 1, 2, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", RECT_CASES)
+def test_exact_bp_rectangular_kernels_match_torch_autograd(oracle, case):
+    N, Ci, Co, H, W, Kh, Kw, s, p, dl, g = case
+    d = D(oracle, N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=Kh, K_w=Kw, stride=s, pad=p, dilation=dl, groups=g, r=1)
+    r = rng(hash(case) % 2**31)
+    x = r.standard_normal((N, Ci, H, W))
+    w = r.standard_normal((Co, Ci // g, Kh, Kw))
+    xt, wt = torch.tensor(x, requires_grad=True), torch.tensor(w, requires_grad=True)
+    y = F.conv2d(xt, wt, None, s, p, dl, g)
+    gy = r.standard_normal(tuple(y.shape))
+    y.backward(torch.tensor(gy))
+    assert oracle.out_shape(d)[:2] == tuple(y.shape[2:])
+    np.testing.assert_allclose(oracle.conv_fwd(d, x, w), y.detach().numpy(), rtol=1e-12, atol=1e-12)
+    g_w, g_x = oracle.bwd_exact(d, x, w, gy)
+    np.testing.assert_allclose(g_w, wt.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(g_x, xt.grad.numpy(), rtol=1e-11, atol=1e-11)
+    # the kernel sum runs over both tap indices
+    np.testing.assert_allclose(oracle.kernel_sum(d, w), w.sum(axis=(2, 3)), rtol=1e-13)
+
+
 # ----------------------------------------------------------------------------
 # exact BP (Sec. 3.1) against torch's fp64 autograd, a library routine
 # ----------------------------------------------------------------------------
