@@ -662,6 +662,32 @@ def test_filtered_backward_rectangular_kernels(oracle, case, dtype):
     assert torch.equal(g_w, g_w[:, :, :1, :1].expand_as(g_w))   # every tap carries the same value
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [(2, 8, 12, 12, 12, 3, 3, 1, 1, 2), (2, 16, 16, 24, 18, 3, 3, 1, 16, 2),
+                                  (1, 8, 8, 16, 16, 1, 4, 0, 1, 2), (2, 6, 9, 18, 18, 5, 3, 2, 3, 3)])
+def test_filtered_backward_large_strides(oracle, case, dtype):
+    """Strides 3 and 4: the input-side patch is r * s (6, 8, 9 pixels) and both gradients carry 1 / s^2."""
+    N, Ci, Co, H, W, K, s, p, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, s=s, p=p, g=g, r=r, dtype=dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, _, _ = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 71, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 72, dtype, scale=0.3)
+    gy = randn((N, Co, Hy, Wy), 73, dtype)
+    x_u = T.pool_activation(d, x.cuda())
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=True)
+    s_gw, s_gx = T.conv_bwd_weight(d, x_u, gy_u), T.conv_bwd_input(d, gy_u, w.cuda())
+    c_gw, c_gxu = T.conv_bwd_chained(d, gy_u, x_u, w.cuda(), reduced_out=True)
+    torch.cuda.synchronize()
+    ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    tol = TOL[dtype]
+    assert rel_err(x_u, ref_xu) <= tol and rel_err(gy_u, ref_gyu) <= tol
+    for got_w, got_x in ((g_w, g_x), (s_gw, s_gx)):
+        assert rel_err(got_w, ref_gw) <= tol and rel_err(got_x, ref_gx) <= tol
+    assert rel_err(c_gw, ref_gw) <= tol
+    assert rel_err(c_gxu, oracle.bwd_input(od, ref_gyu, to64(w), reduced_out=True)) <= tol
+
+
 # ---------------------------------------------------------------------------
 # whole filtered backward on the benchmark configurations
 # ---------------------------------------------------------------------------
