@@ -688,6 +688,39 @@ def test_filtered_backward_large_strides(oracle, case, dtype):
     assert rel_err(c_gxu, oracle.bwd_input(od, ref_gyu, to64(w), reduced_out=True)) <= tol
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [(2, 16, 24, 56, 56, 3, 1, 7), (2, 24, 24, 56, 56, 3, 24, 7), (2, 24, 144, 28, 28, 1, 1, 7),
+                                  (2, 16, 16, 30, 44, 3, 1, 6), (1, 8, 8, 64, 64, 3, 1, 16), (2, 12, 12, 21, 21, 3, 12, 21)])
+def test_large_and_odd_patch_sizes(oracle, case, dtype):
+    """r = 7 (the size the paper's pooling figure uses), 6, 16 and a patch as large as the map."""
+    N, Ci, Co, H, W, K, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, p=K // 2, g=g, r=r, dtype=dtype)
+    od = odesc(oracle, d)
+    x = randn((N, Ci, H, W), 81, dtype, relu=True)
+    w = randn((Co, Ci // g, K, K), 82, dtype, scale=0.3)
+    gy = randn((N, Co, H, W), 83, dtype)
+    x_u = T.pool_activation(d, x.cuda())
+    g_w, g_x, gy_u = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=True)
+    s_gw, s_gx = T.conv_bwd_weight(d, x_u, gy_u), T.conv_bwd_input(d, gy_u, w.cuda())
+    torch.cuda.synchronize()
+    ref_gw, ref_gx, ref_xu, ref_gyu = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    tol = TOL[dtype]
+    assert rel_err(x_u, ref_xu) <= tol and rel_err(gy_u, ref_gyu) <= tol
+    for got_w, got_x in ((g_w, g_x), (s_gw, s_gx)):
+        assert rel_err(got_w, ref_gw) <= tol and rel_err(got_x, ref_gx) <= tol
+    # the same on 8-bit codes, continued from the GPU's own codes
+    dx, dg = float(np.abs(ref_xu).max()) / 127.0, float(np.abs(ref_gyu).max()) / 127.0
+    dw = float(np.abs(oracle.kernel_sum(od, to64(w))).max()) / 127.0
+    x_q, gy_q, w_q = T.pool_activation_q8(d, x.cuda(), 1 / dx), T.filter_grad_q8(d, gy.cuda(), 1 / dg), T.kernel_sum_q8(d, w.cuda(), 1 / dw)
+    q_gw, q_gx = T.conv_bwd_weight_q8(d, x_q, gy_q, dx * dg), T.conv_bwd_input_q8(d, gy_q, w_q, dg * dw)
+    torch.cuda.synchronize()
+    check_codes(oracle, x_q, ref_xu, 1 / dx, "x_q")
+    check_codes(oracle, gy_q, ref_gyu, 1 / dg, "gy_q")
+    xq, gq, wq = (t.cpu().numpy() for t in (x_q, gy_q, w_q))
+    assert torch.equal(q_gw.cpu(), torch.from_numpy(oracle.bwd_weight_q8(od, xq, gq, dx * dg)))
+    assert torch.equal(q_gx.cpu(), rounded(oracle.bwd_input_q8(od, gq, wq, dg * dw), dtype))
+
+
 # ---------------------------------------------------------------------------
 # whole filtered backward on the benchmark configurations
 # ---------------------------------------------------------------------------
