@@ -1125,6 +1125,61 @@ def test_largest_tensors_sampled(oracle, case):
                 assert torch.equal(g_x8[n:n + 1, cs].cpu(), rounded(ref, dtype))
 
 
+WS_LAYERS = [
+    # N  Ci  Co   H   W  K  s  g   r
+    (4, 24, 144, 56, 56, 1, 1, 1, 2), (4, 144, 24, 56, 56, 1, 1, 1, 2), (4, 144, 144, 56, 56, 3, 1, 144, 2),
+    (4, 24, 144, 56, 56, 1, 1, 1, 4), (4, 256, 256, 14, 14, 3, 1, 1, 2), (2, 512, 512, 7, 7, 3, 1, 1, 2),
+    (2, 256, 512, 14, 14, 3, 2, 1, 2), (3, 96, 96, 7, 7, 3, 1, 96, 2), (2, 40, 72, 30, 40, 3, 1, 1, 2),
+    (2, 12, 18, 9, 11, 3, 1, 3, 2), (2, 2048, 256, 16, 16, 1, 1, 1, 2), (2, 64, 64, 32, 32, 3, 1, 1, 8),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", WS_LAYERS)
+def test_workspace_sizes_are_sufficient(case, dtype):
+    """Every entry point is given exactly gf_workspace_bytes() of scratch, followed by guard bytes that
+    must come back untouched (a kernel that writes past the reported size would corrupt the caller)."""
+    N, Ci, Co, H, W, K, s, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, s=s, p=K // 2, g=g, r=r, dtype=dtype)
+    sh = T.shapes(d)
+    td = WL.torch_dtype(dtype)
+    P = B.ptr
+    x = randn(sh["x"], 91, dtype, relu=True).cuda()
+    w = randn(sh["w"], 92, dtype, scale=0.3).cuda()
+    gy = randn(sh["g_y"], 93, dtype).cuda()
+    x_u, gy_u = T.pool_activation(d, x), T.filter_grad(d, gy)
+    x_q, gy_q, w_q = T.pool_activation_q8(d, x, 8.0), T.filter_grad_q8(d, gy, 40.0), T.kernel_sum_q8(d, w, 40.0)
+    g_w = torch.empty(sh["w"], dtype=torch.float32, device="cuda")
+    g_x = torch.empty(sh["x"], dtype=td, device="cuda")
+    g_xu = torch.empty(sh["g_x_u"], dtype=td, device="cuda")
+    stats = torch.zeros(2, dtype=torch.float64, device="cuda")
+    GUARD = 4096
+
+    def run(op, call, dd=d):
+        n = B.gf_workspace_bytes(dd, op)
+        buf = torch.full((n + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+        call(P(buf), n)
+        torch.cuda.synchronize()
+        assert bool((buf[n:] == 0xA5).all()), (op, n)
+
+    run(B.GF_OP_BWD_WEIGHT, lambda p, n: B.gf_conv_bwd_weight(d, P(x_u), P(gy_u), P(g_w), p, n))
+    run(B.GF_OP_BWD_INPUT, lambda p, n: B.gf_conv_bwd_input(d, P(gy_u), P(w), P(g_x), False, p, n))
+    run(B.GF_OP_BWD_INPUT, lambda p, n: B.gf_conv_bwd_input(d, P(gy_u), P(w), P(g_xu), True, p, n))
+    run(B.GF_OP_BWD_FILTERED, lambda p, n: B.gf_conv_bwd_filtered(d, P(gy), P(x_u), P(w), P(gy_u), P(g_w), P(g_x), p, n))
+    run(B.GF_OP_BWD_FILTERED, lambda p, n: B.gf_conv_bwd_filtered(d, P(gy), P(x_u), P(w), 0, P(g_w), P(g_x), p, n))
+    run(B.GF_OP_BWD_CHAINED, lambda p, n: B.gf_conv_bwd_chained(d, P(gy_u), P(x_u), P(w), P(g_w), P(g_xu), True, 0, p, n))
+    run(B.GF_OP_BWD_CHAINED, lambda p, n: B.gf_conv_bwd_chained(d, P(gy_u), P(x_u), P(w), P(g_w), P(g_x), False, 0, p, n))
+    run(B.GF_OP_FILTER_SNR, lambda p, n: B.gf_filter_grad_snr(d, P(gy), P(gy_u), P(stats), p, n))
+    run(B.GF_OP_BWD_EXACT, lambda p, n: B.gf_conv_bwd_exact(d, P(x), P(w), P(gy), P(g_w), P(g_x), p, n))
+    run(B.GF_OP_BWD_WEIGHT_Q8, lambda p, n: B.gf_conv_bwd_weight_q8(d, P(x_q), P(gy_q), 1e-3, P(g_w), p, n))
+    run(B.GF_OP_BWD_INPUT_Q8, lambda p, n: B.gf_conv_bwd_input_q8(d, P(gy_q), P(w_q), 1e-3, P(g_x), False, p, n))
+    # r = 1 through the filtered entries (vanilla BP)
+    d1 = d.with_(r=1)
+    run(B.GF_OP_BWD_WEIGHT, lambda p, n: B.gf_conv_bwd_weight(d1, P(x), P(gy), P(g_w), p, n), d1)
+    run(B.GF_OP_BWD_INPUT, lambda p, n: B.gf_conv_bwd_input(d1, P(gy), P(w), P(g_x), False, p, n), d1)
+    run(B.GF_OP_BWD_FILTERED, lambda p, n: B.gf_conv_bwd_filtered(d1, P(gy), P(x), P(w), 0, P(g_w), P(g_x), p, n), d1)
+
+
 def test_entry_points_replay_from_a_hip_graph():
     """Every entry point only enqueues kernels (and device copies at r = 1), so a captured
     sequence must replay to the same bits as plain launches -- checked on three replays with
