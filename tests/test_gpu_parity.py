@@ -1180,6 +1180,66 @@ def test_workspace_sizes_are_sufficient(case, dtype):
     run(B.GF_OP_BWD_FILTERED, lambda p, n: B.gf_conv_bwd_filtered(d1, P(gy), P(x), P(w), 0, P(g_w), P(g_x), p, n), d1)
 
 
+OOB_LAYERS = [
+    # N  Ci  Co   H   W  K  s  g   r      odd and ragged shapes: vector stores must not run over the ends
+    (3, 5, 7, 7, 7, 3, 1, 1, 2), (2, 12, 18, 9, 11, 3, 1, 3, 2), (3, 10, 10, 15, 13, 3, 2, 10, 2), (1, 8, 8, 5, 3, 3, 1, 1, 2),
+    (2, 24, 40, 14, 14, 3, 1, 1, 2), (2, 40, 24, 7, 7, 1, 1, 1, 2), (1, 9, 9, 30, 41, 3, 1, 9, 4), (2, 16, 8, 13, 9, 3, 2, 1, 2),
+    (1, 3, 3, 1, 1, 1, 1, 1, 2), (2, 64, 64, 7, 7, 3, 1, 1, 4), (3, 24, 144, 28, 28, 1, 1, 1, 2), (1, 130, 70, 6, 10, 1, 1, 1, 3),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", OOB_LAYERS)
+def test_outputs_stay_in_bounds(case, dtype):
+    """Every output tensor lies between two guard regions that must come back untouched."""
+    N, Ci, Co, H, W, K, s, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, s=s, p=K // 2, g=g, r=r, dtype=dtype)
+    sh = T.shapes(d)
+    td = WL.torch_dtype(dtype)
+    P = B.ptr
+    GUARD = 4096
+    guarded = []
+
+    def out(shape, dt):
+        n = int(np.prod(shape)) * torch.empty(0, dtype=dt).element_size()
+        pad = (-n) % 256
+        buf = torch.full((GUARD + n + pad + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+        guarded.append((buf, n))
+        return buf[GUARD:GUARD + n].view(dt).view(shape)
+
+    def check(what):
+        torch.cuda.synchronize()
+        for buf, n in guarded:
+            assert bool((buf[:GUARD] == 0xA5).all()) and bool((buf[GUARD + n:] == 0xA5).all()), what
+
+    ws = T.Workspace()
+    wsp = lambda op, dd=d: ws.get(B.gf_workspace_bytes(dd, op))
+    x = randn(sh["x"], 95, dtype, relu=True).cuda()
+    w = randn(sh["w"], 96, dtype, scale=0.3).cuda()
+    gy = randn(sh["g_y"], 97, dtype).cuda()
+    x_u, gy_u, m_u = out(sh["x_u"], td), out(sh["gy_u"], td), out(sh["x_u"], td)
+    B.gf_pool_activation(d, P(x), P(x_u)); check("pool")
+    B.gf_pool_activation_mask(d, P(x), 6.0, P(x_u), P(m_u)); check("pool mask")
+    B.gf_filter_grad(d, P(gy), P(gy_u)); check("filter")
+    stats = out((2,), torch.float64)
+    B.gf_filter_grad_snr(d, P(gy), P(gy_u), P(stats), *wsp(B.GF_OP_FILTER_SNR)); check("snr")
+    g_w, g_x, g_xu = out(sh["w"], torch.float32), out(sh["x"], td), out(sh["g_x_u"], td)
+    B.gf_conv_bwd_weight(d, P(x_u), P(gy_u), P(g_w), *wsp(B.GF_OP_BWD_WEIGHT)); check("S3")
+    B.gf_conv_bwd_input(d, P(gy_u), P(w), P(g_x), False, *wsp(B.GF_OP_BWD_INPUT)); check("S4")
+    B.gf_conv_bwd_input(d, P(gy_u), P(w), P(g_xu), True, *wsp(B.GF_OP_BWD_INPUT)); check("S4 reduced")
+    B.gf_conv_bwd_filtered(d, P(gy), P(x_u), P(w), P(gy_u), P(g_w), P(g_x), *wsp(B.GF_OP_BWD_FILTERED)); check("fused")
+    B.gf_conv_bwd_chained(d, P(gy_u), P(x_u), P(w), P(g_w), P(g_xu), True, P(m_u), *wsp(B.GF_OP_BWD_CHAINED)); check("chained")
+    B.gf_conv_bwd_chained(d, P(gy_u), P(x_u), P(w), P(g_w), P(g_x), False, 0, *wsp(B.GF_OP_BWD_CHAINED)); check("chained full")
+    B.gf_conv_bwd_exact(d, P(x), P(w), P(gy), P(g_w), P(g_x), *wsp(B.GF_OP_BWD_EXACT)); check("exact")
+    x_q, gy_q, w_q = out(sh["x_u"], torch.int8), out(sh["gy_u"], torch.int8), out(sh["w"][:2], torch.int8)
+    B.gf_pool_activation_q8(d, P(x), 8.0, P(x_q)); check("pool q8")
+    B.gf_filter_grad_q8(d, P(gy), 40.0, P(gy_q)); check("filter q8")
+    B.gf_kernel_sum_q8(d, P(w), 40.0, P(w_q)); check("ksum q8")
+    B.gf_conv_bwd_weight_q8(d, P(x_q), P(gy_q), 1e-3, P(g_w), *wsp(B.GF_OP_BWD_WEIGHT_Q8)); check("S3 q8")
+    B.gf_conv_bwd_input_q8(d, P(gy_q), P(w_q), 1e-3, P(g_x), False, *wsp(B.GF_OP_BWD_INPUT_Q8)); check("S4 q8")
+    B.gf_conv_bwd_input_q8(d, P(gy_q), P(w_q), 1e-3, P(g_xu), True, *wsp(B.GF_OP_BWD_INPUT_Q8)); check("S4 q8 reduced")
+
+
 def test_entry_points_replay_from_a_hip_graph():
     """Every entry point only enqueues kernels (and device copies at r = 1), so a captured
     sequence must replay to the same bits as plain launches -- checked on three replays with
