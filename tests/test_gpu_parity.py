@@ -981,6 +981,10 @@ Q8_LAYERS = [
     (1, 16, 16, 4, 4, 1, 1, 1, 2),        # the whole K is four codes
     (5, 64, 64, 8, 8, 1, 1, 1, 2),        # planes of exactly 16 codes
     (1, 64, 64, 10, 8, 1, 1, 1, 2),       # a single image of 20 codes: the last run is cut by the end of the tensor
+    (2, 64, 64, 64, 64, 3, 1, 1, 8),      # input-side patches of 8 pixels: matrix-core kernel ...
+    (2, 16, 24, 64, 64, 1, 1, 1, 8),      # ... register-tile kernel ...
+    (2, 32, 32, 32, 32, 3, 2, 1, 4),      # ... and r = 4 under stride 2
+    (2, 24, 24, 60, 64, 3, 1, 24, 8),     # depthwise, ragged last patch row
 ]
 
 
