@@ -50,6 +50,9 @@ def parse():
                     help="end with five plain 256 MiB device copies (a kernel of known traffic, used to\n"
                          "scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--table", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark: what this GPU sustains in plain probes -- streaming reads,\n"
+                         "writes and copies (HBM) and register-only loops of matrix instructions (MFMA)")
     ap.add_argument("--fig3", action="store_true",
                     help="instead of the benchmark: the three cost lines of the paper's Fig. 3 (vanilla BP, fewer\n"
                          "unique elements only, gradient filtering) as measured time on the layer of its footnote")
@@ -97,6 +100,9 @@ def main():
     if args.fig3:
         print(json.dumps(fig3(args)), flush=True)
         return
+    if args.ceilings:
+        print(json.dumps(ceilings()), flush=True)
+        return
     out = measure(args, args.dtype, full=True)
     from paper_2301_00330_amd import workloads as WL
     others = [d for d in WL.CONFIGS[args.config].dtypes if d != out["dtype"]]
@@ -105,6 +111,69 @@ def main():
         out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer",
                                                 "chained_block", "q8_block") if k in o}
     print(json.dumps(out), flush=True)
+
+
+def ceilings():
+    """Measured ceilings of the two resources the kernels are bound by, from the probes of
+    paper_2301_00330_amd/csrc_probe (a library of their own): cold streaming reads / writes / copies with
+    16-byte vectors over rotating buffers (> 1.2 GB in rotation, so the 256 MB memory-side cache cannot
+    serve them), and register-only loops of independent matrix instructions at 8 waves per SIMD."""
+    import ctypes as C
+    import torch
+    lib_path = os.path.join(ROOT, "paper_2301_00330_amd", "libgf_probe.so")
+    if not os.path.exists(lib_path):
+        raise ImportError(f"{lib_path} is missing: build it with `python -m paper_2301_00330_amd.build`")
+    L = C.CDLL(lib_path)
+    vp = C.c_void_p
+    L.gfp_read.argtypes = [vp, vp, C.c_long, vp]
+    L.gfp_write.argtypes = [vp, C.c_long, vp]
+    L.gfp_copy.argtypes = [vp, vp, C.c_long, vp]
+    L.gfp_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
+    L.gfp_mfma_out_floats.restype = C.c_long
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    st = lambda: int(torch.cuda.current_stream().cuda_stream)
+
+    def timeit(fn, n):
+        fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n   # us per launch
+
+    def ok(rc):
+        if rc != 0:
+            raise RuntimeError(f"probe failed with code {rc}")
+
+    flag = torch.zeros(64, dtype=torch.int32, device="cuda")
+    hbm = []
+    for mb in (36, 72, 256):
+        nb = mb * 1000 * 1000 // 16 * 16
+        nbuf = max(3, int(1.2e9 // nb) + 1)
+        bufs = [torch.empty(nb, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(nbuf)]
+        outs = [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(nbuf)]
+        rd = timeit(lambda i: ok(L.gfp_read(bufs[i % nbuf].data_ptr(), flag.data_ptr(), nb, st())), 4 * nbuf)
+        wr = timeit(lambda i: ok(L.gfp_write(outs[i % nbuf].data_ptr(), nb, st())), 4 * nbuf)
+        cp = timeit(lambda i: ok(L.gfp_copy(bufs[i % nbuf].data_ptr(), outs[i % nbuf].data_ptr(), nb, st())), 4 * nbuf)
+        hbm.append({"MB": mb, "read_us": round(rd, 2), "read_GBps": round(nb / rd * 1e-3, 1),
+                    "write_us": round(wr, 2), "write_GBps": round(nb / wr * 1e-3, 1),
+                    "copy_us": round(cp, 2), "copy_GBps_read_plus_write": round(2 * nb / cp * 1e-3, 1)})
+        log(f"HBM {mb:4d} MB: read {nb / rd * 1e-6:.2f} TB/s, write {nb / wr * 1e-6:.2f} TB/s, copy {2 * nb / cp * 1e-6:.2f} TB/s (read + write)")
+        del bufs, outs
+    mout = torch.empty(int(L.gfp_mfma_out_floats()), dtype=torch.float32, device="cuda")
+    mfma = []
+    for kind, name, iters, peak in ((0, "v_mfma_f32_32x32x16_bf16", 20000, 2500.0), (1, "v_mfma_f32_16x16x32_bf16", 20000, 2500.0),
+                                    (2, "v_mfma_f32_16x16x4_f32", 5000, 157.3), (3, "v_mfma_i32_16x16x64_i8", 20000, 5000.0)):
+        ops = C.c_double(0.0)
+        us = timeit(lambda i: ok(L.gfp_mfma(kind, iters, mout.data_ptr(), C.byref(ops), st())), 3)
+        tops = ops.value / (us * 1e-6) * 1e-12
+        mfma.append({"instruction": name, "T(FL)OPs": round(tops, 1), "datasheet": peak, "frac": round(tops / peak, 3)})
+        log(f"MFMA {name}: {tops:.1f} T(FL)OP/s ({100 * tops / peak:.0f} % of the datasheet figure)")
+    return {"what": "measured ceilings (probes, not library kernels)", "n_gpus": 1, "hbm": hbm, "mfma": mfma}
 
 
 def fig3(args):

@@ -12,6 +12,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgf.so")
 OBJ = os.path.join(HERE, "_build")
+PROBE_SRC = os.path.join(HERE, "csrc_probe", "gf_probe.hip")
+PROBE_LIB = os.path.join(HERE, "libgf_probe.so")
 
 # -packed-fp32-ops off: hand the compiler no packed-FP32 forms (they are not trusted on this target)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -53,6 +55,10 @@ def build(verbose: bool = False) -> str:
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    # the measurement probes of bench.py --ceilings: a library of their own, never loaded by the product path
+    r = subprocess.run([cc, *HIPCC_FLAGS, "-shared", PROBE_SRC, "-o", PROBE_LIB], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for the probes:\n" + r.stderr)
     return LIB
 
 

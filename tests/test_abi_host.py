@@ -228,3 +228,20 @@ def test_q8_entry_errors(lib):
     with pytest.raises(B.GfError) as ei:
         B.gf_conv_bwd_input_q8(d12, FAKE, FAKE, 1.0, FAKE, False, FAKE, need - 1)
     assert ei.value.status == B.GF_ERR_WORKSPACE
+
+
+def test_probe_library_builds_and_exports(lib):
+    """The measurement probes of bench.py --ceilings are a library of their own, built by the same build step."""
+    import ctypes as C
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    path = os.path.join(root, "paper_2301_00330_amd", "libgf_probe.so")
+    assert os.path.exists(path), "run the build step first"
+    L = C.CDLL(path)
+    for name in ("gfp_read", "gfp_write", "gfp_copy", "gfp_mfma", "gfp_mfma_out_floats"):
+        assert getattr(L, name) is not None
+    # argument checks happen on the host before any launch
+    L.gfp_mfma.argtypes = [C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+    ops = C.c_double(0.0)
+    assert L.gfp_mfma(7, 10, FAKE, C.byref(ops), None) == 1 and L.gfp_mfma(0, 0, FAKE, C.byref(ops), None) == 1
+    L.gfp_read.argtypes = [C.c_void_p, C.c_void_p, C.c_long, C.c_void_p]
+    assert L.gfp_read(None, FAKE, 1024, None) == 1 and L.gfp_read(FAKE, FAKE, 8, None) == 1
