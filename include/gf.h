@@ -15,7 +15,12 @@
  *  - Tensors are contiguous NCHW (the paper's index order x[n,c,h,w],
  *    theta[co,ci,u,v]), element type desc->dtype (fp32, or bf16 stored as the
  *    upper 16 bits of an fp32, rounded to nearest even).  Weight gradients are
- *    always fp32.  Accumulation is always fp32.
+ *    always fp32.  Accumulation is always fp32.  Rounding points with bf16
+ *    storage: the reduced maps x_u and gy_u are rounded once when they are formed
+ *    (also inside gf_conv_bwd_filtered, where gy_u never leaves the chip for some
+ *    layers); for dense layers with a kernel larger than 1x1 the kernel sum is
+ *    rounded once before Eq. 3 (depthwise layers keep it in fp32); g_x is rounded
+ *    once when it is stored.
  *  - Every tensor / workspace pointer is a DEVICE pointer, 16-byte aligned,
  *    owned by the caller; the library never allocates, frees or keeps one.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -177,6 +182,22 @@ gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const vo
 gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const void* x_u,
                                const void* w, void* gy_u, float* g_w, void* g_x, void* ws,
                                size_t ws_bytes, void* stream);
+
+/* gf_conv_bwd_filtered for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * minus the workspace, same kernels, same results bit for bit.  The scratch (partial weight
+ * gradients, kernel sums, gy_u when the caller passes none) lives in a static device array of
+ * GF_STATIC_SCRATCH_BYTES inside the library; every GPU the library runs on holds its own copy
+ * until the process ends.  A layer whose gf_workspace_bytes(GF_OP_BWD_FILTERED) exceeds that size
+ * is rejected with GF_ERR_WORKSPACE before anything is enqueued.  The call allocates nothing and
+ * frees nothing; the first call on a device looks the array's address up once (make that call
+ * outside a stream capture).  All calls on one GPU share the one array and it keeps the last
+ * call's contents: calls that overlap in time on the same GPU (different streams or threads)
+ * race -- serialise them or use gf_conv_bwd_filtered with workspaces of their own.  Nothing in
+ * the array has to start at zero. */
+#define GF_STATIC_SCRATCH_BYTES (32u << 20)
+gf_status gf_conv_bwd_filtered_static(const gf_conv_desc* desc, const void* g_y, const void* x_u,
+                                      const void* w, void* gy_u, float* g_w, void* g_x, void* stream);
 
 /* Backward of one layer inside a chain of gradient-filtered layers with nothing but
  * convolutions between them.  The input gradient of Eq. 3 is constant on every

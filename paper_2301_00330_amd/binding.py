@@ -22,7 +22,8 @@ GF_OP_BWD_WEIGHT_Q8, GF_OP_BWD_INPUT_Q8 = 6, 7
 
 EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_mask", "gf_filter_grad",
            "gf_filter_grad_snr",
-           "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_chained",
+           "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_filtered_static",
+           "gf_conv_bwd_chained",
            "gf_conv_bwd_exact",
            "gf_filter_grad_q8", "gf_pool_activation_q8", "gf_kernel_sum_q8", "gf_conv_bwd_weight_q8",
            "gf_conv_bwd_input_q8",
@@ -97,6 +98,7 @@ def lib() -> C.CDLL:
         L.gf_conv_bwd_input.argtypes = [dp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_conv_bwd_exact.argtypes = [dp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_filtered.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.gf_conv_bwd_filtered_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.gf_conv_bwd_chained.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.gf_pool_activation_mask.argtypes = [dp, vp, C.c_float, vp, vp, vp]
         L.gf_filter_grad_q8.argtypes = [dp, vp, C.c_float, vp, vp]
@@ -175,6 +177,16 @@ def gf_conv_bwd_filtered(d: ConvDesc, g_y: int, x_u: int, w: int, gy_u: int, g_w
     cd = d.c()
     _chk(lib().gf_conv_bwd_filtered(C.byref(cd), g_y, x_u, w, gy_u, g_w, g_x, ws, ws_bytes, stream),
          "gf_conv_bwd_filtered")
+
+
+GF_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def gf_conv_bwd_filtered_static(d: ConvDesc, g_y: int, x_u: int, w: int, gy_u: int, g_w: int, g_x: int,
+                                stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_conv_bwd_filtered_static(C.byref(cd), g_y, x_u, w, gy_u, g_w, g_x, stream),
+         "gf_conv_bwd_filtered_static")
 
 
 def gf_filter_grad_snr(d: ConvDesc, g_y: int, gy_u: int, stats: int, ws: int, ws_bytes: int, stream: int = 0):

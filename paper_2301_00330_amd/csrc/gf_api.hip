@@ -2,6 +2,8 @@
 // happens on the host before anything is enqueued.
 #include <string.h>
 
+#include <mutex>
+
 #include "gf_internal.h"
 
 namespace gf {
@@ -15,6 +17,14 @@ gf_status make_geom(const gf_conv_desc* d, Geom* o) {
   if (d->groups < 1 || d->C_in % d->groups || d->C_out % d->groups) return GF_ERR_BAD_DESC;
   if (d->r < 1) return GF_ERR_BAD_DESC;
   if (d->dtype != GF_F32 && d->dtype != GF_BF16) return GF_ERR_BAD_DESC;
+  // 32-bit element indexing inside the kernels; the margin keeps the index of the last block's
+  // last lane, which may point past the end before it is checked, below 2^31 as well.  Every
+  // extent is bounded on its own first, so none of the products below can wrap 64 bits.
+  const long lim = (1L << 31) - (1L << 20);
+  if (d->N > lim || d->C_in > lim || d->C_out > lim || d->H_in > lim || d->W_in > lim || d->K_h > lim ||
+      d->K_w > lim || d->pad > (1 << 30) || d->dilation > (1 << 30))
+    return GF_ERR_UNSUPPORTED;
+  if ((long)d->H_in * d->W_in > lim || (long)d->K_h * d->K_w > lim) return GF_ERR_UNSUPPORTED;
   Geom g;
   g.N = d->N; g.Ci = d->C_in; g.Co = d->C_out; g.H = d->H_in; g.W = d->W_in;
   g.Kh = d->K_h; g.Kw = d->K_w; g.s = d->stride; g.p = d->pad; g.dl = d->dilation;
@@ -30,16 +40,14 @@ gf_status make_geom(const gf_conv_desc* d, Geom* o) {
   if (g.r > 1 && (cdiv(g.H, g.rx) != g.Hp || cdiv(g.W, g.rx) != g.Wp)) return GF_ERR_SHAPE;
   g.Cg = g.Ci / g.g;
   g.Og = g.Co / g.g;
+  // element counts, factor by factor with an early exit (each partial product stays below 2^62)
+  const long hw = (long)g.H * g.W, hwy = (long)g.Hy * g.Wy, kk = (long)g.Kh * g.Kw;
+  if (hwy > lim || hw * g.Ci > lim || hwy * g.Co > lim || kk * g.Cg > lim) return GF_ERR_UNSUPPORTED;
+  if (hw * g.Ci * g.N > lim || hwy * g.Co * g.N > lim || kk * g.Cg * g.Co > lim) return GF_ERR_UNSUPPORTED;
   g.KK = g.Kh * g.Kw;
   g.P = g.Hp * g.Wp;
   g.dtype = d->dtype;
   g.b = d->dtype == GF_BF16 ? 2 : 4;
-  // 32-bit element indexing inside the kernels; the margin keeps the index of the last block's
-  // last lane, which may point past the end before it is checked, below 2^31 as well
-  const long lim = (1L << 31) - (1L << 20);
-  if ((long)g.N * g.Ci * g.H * g.W > lim || (long)g.N * g.Co * g.Hy * g.Wy > lim ||
-      (long)g.Co * g.Cg * g.KK > lim)
-    return GF_ERR_UNSUPPORTED;
   // grid dimensions y (group x channel tile) and z (image) are limited to 65535
   if (g.N > 65535 || (long)g.g * cdiv(g.Cg > g.Og ? g.Cg : g.Og, 16) > 65535) return GF_ERR_UNSUPPORTED;
   *o = g;
@@ -132,7 +140,9 @@ const char* gf_status_string(int s) {
     case GF_ERR_BAD_DESC: return "GF_ERR_BAD_DESC: invalid layer descriptor";
     case GF_ERR_SHAPE: return "GF_ERR_SHAPE: kernel exceeds padded input or patch grids of x and g_y differ";
     case GF_ERR_UNSUPPORTED: return "GF_ERR_UNSUPPORTED: misaligned pointer or tensor too large";
-    case GF_ERR_WORKSPACE: return "GF_ERR_WORKSPACE: workspace missing or too small";
+    case GF_ERR_WORKSPACE:
+      return "GF_ERR_WORKSPACE: workspace missing or too small (static variant: the layer needs more than "
+             "GF_STATIC_SCRATCH_BYTES)";
     case GF_ERR_DEVICE: return "GF_ERR_DEVICE: HIP launch failed";
     default: return "GF_ERR_?: unknown status";
   }
@@ -289,9 +299,46 @@ gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const vo
   return dev(launch_gf_bwd_input(g, gy_u, w, g_x, reduced_out != 0, ws, st));
 }
 
+// file-scope scratch of gf_conv_bwd_filtered_static: each GPU the library runs on holds its own copy
+// at its own address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it returns is what launches and copies are given.
+static __device__ __align__(256) unsigned char scratch[GF_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex scratch_mu;
+static void* scratch_ptr[kMaxDevices];   // per device, filled on the first call with that device current
+
+static gf_status static_scratch(void** out) {
+  int devid = -1;
+  if (hipGetDevice(&devid) != hipSuccess || devid < 0 || devid >= kMaxDevices) return GF_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[devid]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GF_ERR_DEVICE;
+    scratch_ptr[devid] = p;
+  }
+  *out = scratch_ptr[devid];
+  return GF_OK;
+}
+
+static gf_status filtered_body(const gf_conv_desc* desc, const void* g_y, const void* x_u, const void* w,
+                               void* gy_u, float* g_w, void* g_x, void* ws, size_t ws_bytes, bool ws_static,
+                               void* stream);
+
 gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const void* x_u,
                                const void* w, void* gy_u, float* g_w, void* g_x, void* ws,
                                size_t ws_bytes, void* stream) {
+  return filtered_body(desc, g_y, x_u, w, gy_u, g_w, g_x, ws, ws_bytes, false, stream);
+}
+
+gf_status gf_conv_bwd_filtered_static(const gf_conv_desc* desc, const void* g_y, const void* x_u,
+                                      const void* w, void* gy_u, float* g_w, void* g_x, void* stream) {
+  return filtered_body(desc, g_y, x_u, w, gy_u, g_w, g_x, nullptr, GF_STATIC_SCRATCH_BYTES, true, stream);
+}
+
+static gf_status filtered_body(const gf_conv_desc* desc, const void* g_y, const void* x_u, const void* w,
+                               void* gy_u, float* g_w, void* g_x, void* ws, size_t ws_bytes, bool ws_static,
+                               void* stream) {
   Geom g;
   gf_status rc = make_geom(desc, &g);
   if (rc) return rc;
@@ -301,6 +348,11 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
     return GF_ERR_UNSUPPORTED;
   size_t off_w = 0, off_i = 0;
   const size_t need = ws_filtered(g, gy_u == nullptr, &off_w, &off_i);
+  if (ws_static) {  // the library's own scratch: size check first, then this device's address of it
+    if (need > ws_bytes) return GF_ERR_WORKSPACE;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+  }
   rc = check_ws(need, ws, ws_bytes);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
