@@ -46,7 +46,8 @@ def shapes(d: B.ConvDesc) -> dict:
 
 
 class Workspace:
-    """A reusable device scratch buffer (grown on demand, never inside a call to libgf)."""
+    """A reusable device scratch buffer (grown on demand, never inside a call to libgf).  One
+    Workspace serves ONE stream at a time: two calls that may run concurrently need two."""
 
     def __init__(self, device="cuda"):
         self.device = device
@@ -56,6 +57,10 @@ class Workspace:
         if nbytes == 0:
             return 0, 0
         if self.buf is None or self.buf.numel() < nbytes:
+            if self.buf is not None:
+                # the old buffer goes back to the caching allocator: tell it that work already
+                # enqueued on the current stream may still be using it
+                self.buf.record_stream(torch.cuda.current_stream(self.buf.device))
             self.buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
         return int(self.buf.data_ptr()), int(self.buf.numel())
 
@@ -64,9 +69,11 @@ _default_ws = {}
 
 
 def _ws(t: torch.Tensor, ws: Workspace | None) -> Workspace:
+    """The caller's workspace, else a default one per (device, current stream): calls on different
+    streams may overlap in time and must not share scratch memory."""
     if ws is not None:
         return ws
-    key = str(t.device)
+    key = (str(t.device), int(torch.cuda.current_stream(t.device).cuda_stream))
     if key not in _default_ws:
         _default_ws[key] = Workspace(t.device)
     return _default_ws[key]

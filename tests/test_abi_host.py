@@ -39,6 +39,43 @@ def test_largest_accepted_tensor(lib):
         assert ei.value.status == B.GF_ERR_UNSUPPORTED
 
 
+def test_element_count_cannot_wrap(lib):
+    """Extents whose product passes 2^64 (16 * 4096 * 2^24 * 2^24 = 2^64 wraps to 0 in 64 bits) and
+    other products beyond 2^63 are refused like any tensor that is too large."""
+    for kw in (dict(N=16, C_in=4096, C_out=4096, H_in=1 << 24, W_in=1 << 24, K_h=3, K_w=3, pad=1, groups=4096),
+               dict(N=1 << 15, C_in=1 << 16, C_out=1 << 16, H_in=1 << 16, W_in=1 << 16, K_h=1, K_w=1, pad=0),
+               dict(N=1, C_in=1 << 20, C_out=1 << 20, H_in=1 << 12, W_in=1 << 12, K_h=1 << 11, K_w=1 << 11, pad=1023),
+               dict(N=1, C_in=1, C_out=1, H_in=(1 << 31) - 1, W_in=(1 << 31) - 1, K_h=1, K_w=1, pad=0)):
+        d = B.ConvDesc(r=2, **kw)
+        for call in (lambda: B.gf_out_shape(d), lambda: B.gf_workspace_bytes(d, B.GF_OP_FILTER_SNR),
+                     lambda: B.gf_filter_grad(d, FAKE, FAKE)):
+            with pytest.raises(B.GfError) as ei:
+                call()
+            assert ei.value.status == B.GF_ERR_UNSUPPORTED
+
+
+def test_static_scratch_entry_host_checks(lib):
+    """gf_conv_bwd_filtered_static: descriptor, pointer and size errors come before any device call."""
+    d = B.ConvDesc(**OK)
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_static(d, 0, FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_static(d, FAKE, FAKE, FAKE + 8, FAKE, FAKE, FAKE)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_static(d.with_(r=0), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert ei.value.status == B.GF_ERR_BAD_DESC
+    big = B.ConvDesc(N=8, C_in=2048, C_out=256, H_in=64, W_in=64, r=2, dtype=B.GF_BF16)
+    assert B.gf_workspace_bytes(big, B.GF_OP_BWD_FILTERED) > B.GF_STATIC_SCRATCH_BYTES
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_static(big, FAKE, FAKE, FAKE, 0, FAKE, FAKE)
+    assert ei.value.status == B.GF_ERR_WORKSPACE
+    hdr = open(os.path.join(ROOT, "include", "gf.h")).read()
+    m = re.search(r"#define\s+GF_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", hdr)
+    assert m and int(m.group(1)) << int(m.group(2)) == B.GF_STATIC_SCRATCH_BYTES
+
+
 OK = dict(N=2, C_in=4, C_out=8, H_in=8, W_in=8, K_h=3, K_w=3, pad=1, r=2)
 FAKE = 0x1000  # non-null, 16-byte aligned; never dereferenced because validation fails first
 
