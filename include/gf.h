@@ -195,7 +195,7 @@ gf_status gf_conv_bwd_filtered(const gf_conv_desc* desc, const void* g_y, const 
  * call's contents: calls that overlap in time on the same GPU (different streams or threads)
  * race -- serialise them or use gf_conv_bwd_filtered with workspaces of their own.  Nothing in
  * the array has to start at zero. */
-#define GF_STATIC_SCRATCH_BYTES (32u << 20)
+#define GF_STATIC_SCRATCH_BYTES (64u << 20)
 gf_status gf_conv_bwd_filtered_static(const gf_conv_desc* desc, const void* g_y, const void* x_u,
                                       const void* w, void* gy_u, float* g_w, void* g_x, void* stream);
 
@@ -265,6 +265,13 @@ gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void*
 gf_status gf_cost_model(const gf_conv_desc* desc, gf_cost* out);
 
 const char* gf_status_string(int status);
+
+/* Tracing aid (process-wide; NULL removes it): `fn` is called on the calling thread right before
+ * (phase 0) and right after (phase 1) every kernel any entry point enqueues, with the kernel's name
+ * and the stream, e.g. to record events around each launch or to list the launches of a call.  The
+ * observer must not call into this library.  Not meant to stay set in production loops. */
+typedef void (*gf_launch_observer_fn)(void* user, const char* kernel, int phase, void* stream);
+void gf_set_launch_observer(gf_launch_observer_fn fn, void* user);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int gf_version(void);

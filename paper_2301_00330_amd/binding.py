@@ -28,7 +28,7 @@ EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_
            "gf_filter_grad_q8", "gf_pool_activation_q8", "gf_kernel_sum_q8", "gf_conv_bwd_weight_q8",
            "gf_conv_bwd_input_q8",
            "gf_cost_model",
-           "gf_status_string", "gf_version")
+           "gf_status_string", "gf_version", "gf_set_launch_observer")
 
 
 class _Desc(C.Structure):
@@ -110,6 +110,8 @@ def lib() -> C.CDLL:
         L.gf_status_string.argtypes = [C.c_int]
         L.gf_status_string.restype = C.c_char_p
         L.gf_version.restype = C.c_int
+        L.gf_set_launch_observer.argtypes = [LAUNCH_OBSERVER, vp]
+        L.gf_set_launch_observer.restype = None
         for name in EXPORTS:
             getattr(L, name)
         _lib = L
@@ -128,6 +130,23 @@ def _chk(status: int, where: str):
 def ptr(t) -> int:
     """Device address of a torch tensor (None -> NULL)."""
     return 0 if t is None else int(t.data_ptr())
+
+
+LAUNCH_OBSERVER = C.CFUNCTYPE(None, C.c_void_p, C.c_char_p, C.c_int, C.c_void_p)
+_observer_keepalive = None
+
+
+def gf_set_launch_observer(fn=None):
+    """fn(kernel_name: str, phase: int, stream: int) is called before (0) / after (1) every kernel launch
+    of the library; None removes the observer."""
+    global _observer_keepalive
+    if fn is None:
+        lib().gf_set_launch_observer(LAUNCH_OBSERVER(0), None)
+        _observer_keepalive = None
+        return
+    cb = LAUNCH_OBSERVER(lambda user, name, phase, stream: fn(name.decode(), int(phase), int(stream or 0)))
+    lib().gf_set_launch_observer(cb, None)
+    _observer_keepalive = cb
 
 
 def gf_version() -> int:
@@ -179,7 +198,7 @@ def gf_conv_bwd_filtered(d: ConvDesc, g_y: int, x_u: int, w: int, gy_u: int, g_w
          "gf_conv_bwd_filtered")
 
 
-GF_STATIC_SCRATCH_BYTES = 32 << 20
+GF_STATIC_SCRATCH_BYTES = 64 << 20
 
 
 def gf_conv_bwd_filtered_static(d: ConvDesc, g_y: int, x_u: int, w: int, gy_u: int, g_w: int, g_x: int,

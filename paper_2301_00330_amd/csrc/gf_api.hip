@@ -2,6 +2,7 @@
 // happens on the host before anything is enqueued.
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "gf_internal.h"
@@ -54,6 +55,22 @@ gf_status make_geom(const gf_conv_desc* d, Geom* o) {
   return GF_OK;
 }
 
+static std::atomic<gf_launch_observer_fn> g_observer{nullptr};
+static std::atomic<void*> g_observer_user{nullptr};
+
+void observe_launch(const char* kernel_expr, int phase, hipStream_t st) {
+  const gf_launch_observer_fn fn = g_observer.load(std::memory_order_relaxed);
+  if (!fn) return;
+  // the launch site's kernel expression, e.g. "(wgrad_mfma_k<T, TM, TN, WM, WN, true>)": keep the name
+  char name[64];
+  const char* p = kernel_expr;
+  while (*p == '(' || *p == ' ') ++p;
+  size_t n = 0;
+  while (p[n] && p[n] != '<' && p[n] != ')' && p[n] != ' ' && n + 1 < sizeof(name)) { name[n] = p[n]; ++n; }
+  name[n] = 0;
+  fn(g_observer_user.load(std::memory_order_relaxed), name, phase, static_cast<void*>(st));
+}
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static gf_status dev(hipError_t e) { return e == hipSuccess ? GF_OK : GF_ERR_DEVICE; }
@@ -66,6 +83,11 @@ static size_t ws_filtered(const Geom& g, bool own_gyu, size_t* off_w, size_t* of
     if (off_w) *off_w = 0;
     if (off_i) *off_i = 0;
     return ws_exact(g, true, true);
+  }
+  if (dense_ok(g)) {
+    if (off_w) *off_w = 0;
+    if (off_i) *off_i = 0;
+    return ws_dense(g, true, true);
   }
   int nz = 0;
   if (dw_fused_ok(g, &nz)) {
@@ -91,6 +113,10 @@ static size_t ws_chained(const Geom& g, size_t* off_i) {
     if (off_i) *off_i = 0;
     return ws_exact(g, true, true);
   }
+  if (dense_ok(g)) {
+    if (off_i) *off_i = 0;
+    return ws_dense(g, true, true);
+  }
   const size_t o = align256(ws_bwd_weight(g));
   if (off_i) *off_i = o;
   const size_t a = ws_bwd_input(g, true), b = ws_bwd_input(g, false);
@@ -110,9 +136,9 @@ static size_t ws_need(const Geom& g, int op, bool reduced_out) {
     case GF_OP_BWD_INPUT_Q8:
       return ws_bwd_input_q8(g, reduced_out);
     case GF_OP_BWD_WEIGHT:
-      return g.r == 1 ? ws_exact(g, true, false) : ws_bwd_weight(g);
+      return g.r == 1 ? ws_exact(g, true, false) : dense_ok(g) ? ws_dense(g, true, false) : ws_bwd_weight(g);
     case GF_OP_BWD_INPUT:
-      return g.r == 1 ? ws_exact(g, false, true) : ws_bwd_input(g, reduced_out);
+      return g.r == 1 ? ws_exact(g, false, true) : dense_ok(g) ? ws_dense(g, false, true) : ws_bwd_input(g, reduced_out);
     default:
       return ws_exact(g, true, true);
   }
@@ -131,7 +157,13 @@ using namespace gf;
 
 extern "C" {
 
-int gf_version(void) { return 100; }
+int gf_version(void) { return 200; }
+
+void gf_set_launch_observer(gf_launch_observer_fn fn, void* user) {
+  g_observer.store(nullptr, std::memory_order_relaxed);
+  g_observer_user.store(user, std::memory_order_relaxed);
+  g_observer.store(fn, std::memory_order_release);
+}
 
 const char* gf_status_string(int s) {
   switch (s) {
@@ -282,6 +314,7 @@ gf_status gf_conv_bwd_weight(const gf_conv_desc* desc, const void* x_u, const vo
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (g.r == 1) return dev(launch_exact_wgrad(g, x_u, gy_u, g_w, ws, st));
+  if (dense_ok(g)) return dev(launch_dense(g, gy_u, false, x_u, nullptr, nullptr, g_w, nullptr, false, nullptr, ws, st));
   return dev(launch_gf_bwd_weight(g, x_u, gy_u, g_w, ws, st));
 }
 
@@ -296,6 +329,8 @@ gf_status gf_conv_bwd_input(const gf_conv_desc* desc, const void* gy_u, const vo
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (g.r == 1) return dev(launch_exact_dgrad(g, w, gy_u, g_x, ws, st));
+  if (dense_ok(g))
+    return dev(launch_dense(g, gy_u, false, nullptr, w, nullptr, nullptr, g_x, reduced_out != 0, nullptr, ws, st));
   return dev(launch_gf_bwd_input(g, gy_u, w, g_x, reduced_out != 0, ws, st));
 }
 
@@ -368,6 +403,8 @@ static gf_status filtered_body(const gf_conv_desc* desc, const void* g_y, const 
     if (rc) return rc;
     return dev(launch_exact_dgrad(g, w, g_y, g_x, ws, st));
   }
+  if (dense_ok(g))  // small maps: filter + relayout, then both contractions with their slab sums
+    return dev(launch_dense(g, g_y, true, x_u, w, gy_u, g_w, g_x, false, nullptr, ws, st));
   int nz = 0;
   if (dw_fused_ok(g, &nz)) {
     float* part = static_cast<float*>(ws);
@@ -466,6 +503,11 @@ static gf_status chained_body(const Geom& g, const void* gy_u, const void* x_u, 
     rc = dev(launch_exact_wgrad(g, x_u, gy_u, g_w, ws, st));
     if (rc) return rc;
     return dev(launch_exact_dgrad(g, w, gy_u, g_x, ws, st));
+  }
+  if (dense_ok(g)) {
+    *mask_done = reduced_out != 0;
+    return dev(launch_dense(g, gy_u, false, x_u, w, nullptr, g_w, g_x, reduced_out != 0,
+                            reduced_out ? mask_u : nullptr, ws, st));
   }
   if (reduced_out && is_depthwise_layer(g)) {  // one pass over gy_u and x_u
     float* part = reinterpret_cast<float*>(wsb);

@@ -1,0 +1,655 @@
+// Dense layers (groups == 1) on small maps -- the 7x7 / 14x14 tails of ResNet and MobileNetV2 --
+// in TWO launches per layer:
+//
+//   1. dense_prep_k: the gradient filter (Eq. 2) over runs of whole planes staged in LDS; the patch
+//      means leave the block three times over: in the caller's layout [N, C_y, P] (if wanted), as
+//      GYT [C_y][J] (row = output channel, J = N * P columns) and as GYN [J][C_y] (row = patch).
+//      Extra blocks at the end of the grid relay x_u to XUT [C_x][J], form the kernel sums
+//      (text after Eq. 3) as WT [C_x][C_y], clear the K padding of all four matrices and zero the
+//      tickets of launch 2.  With these layouts both contractions are plain "NT" products of
+//      row-major matrices with K contiguous, rows 128-byte aligned and K padded to whole chunks:
+//        weight gradient (Eq. 5):  g_th~[co][ci] = sum_j  GYT[co][j]  * XUT[ci][j]
+//        input gradient  (Eq. 3):  g_x~u[ci][j]  = sum_co WT[ci][co]  * GYN[j][co]
+//      so neither the patch count of a plane (49, 16, 4 ...) nor image boundaries show up in the
+//      operand loaders any more.
+//   2. dense_gemm_k: one grid whose blocks are (tile, K slab) pairs of the two products.  Operands
+//      go global -> registers (one chunk ahead) -> LDS rows of 128 + 16 bytes -> 16-byte fragment
+//      reads -> MFMA (v_mfma_f32_32x32x16_bf16, v_mfma_f32_16x16x4_f32).  A slab's partial tile goes
+//      to the workspace; the block that takes the last ticket of a tile adds the slabs in slab
+//      order (so the result does not depend on which block that is) and runs the epilogue:
+//      scale and replicate to the K_h x K_w taps, or round once and write whole planes of g_x
+//      (every patch value to its r_x x r_x pixels, built in LDS, stored as one contiguous run).
+//      No separate slab-sum launch, no float atomics.
+//
+// Blocks are numbered so that the blocks one XCD receives (block index mod 8) share operands:
+// a K slab of the weight gradient, a group of images of the input gradient.
+#include "gf_internal.h"
+#include "gf_mma.h"
+
+namespace gf {
+
+bool patch_reduce_uses_rows(int dtype, long planes, int H, int W, int q);  // gf_reduce.hip
+
+namespace {
+
+constexpr int kT = 256;
+constexpr int kPitch = 128 + 16;       // bytes of one staged operand row
+constexpr int kTile = 64;              // block tile (rows and columns)
+constexpr int kEsBytes = 16 * 1024;    // LDS image of the planes one epilogue pass stores
+constexpr int kPrepInBytes = 24 * 1024;
+
+template <class T> struct El;
+template <> struct El<float> { static constexpr int KB = 32, VE = 4; };    // elements per 128-byte chunk / 16-byte vector
+template <> struct El<bf16_t> { static constexpr int KB = 64, VE = 8; };
+
+// ---------------------------------------------------------------------------
+// launch 1: filter + relayout
+// ---------------------------------------------------------------------------
+struct PrepArgs {
+  const void* in;      // [planes][H][W]: g_y, or gy_u itself with q = 1
+  int planes, C, H, W, q, Hp, Wp, P, mean, vfirst, R;
+  long total_in;       // planes * H * W
+  FastDiv d_p, d_wp, d_c;
+  void* gyu;           // nullable [planes][P]
+  void* gyt;           // nullable [C][ldj]
+  void* gyn;           // nullable [J][ldc]
+  long ldj, ldc;
+  int J;
+  // side jobs
+  const void* xu;      // nullable [N][Ci][P] -> xut [Ci][ldj]
+  void* xut;
+  int Ci, nxu;         // nxu = N * Ci * P
+  FastDiv d_cip;       // / (Ci * P)
+  const void* w;       // nullable [Co][Ci][KK] -> wt [Ci][ldc], kernel sums rounded to the storage type
+  void* wt;
+  int Co, KK;
+  int* tickets;
+  int ntickets;
+  int blk_xu0, blk_w0, blk_pad0, blk_end;
+};
+
+template <class T>
+__device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  T* xut = static_cast<T*>(a.xut);
+  T* wt = static_cast<T*>(a.wt);
+  if (b < a.blk_w0) {   // x_u [n][ci][p] -> XUT [ci][n * P + p]
+    const T* xu = static_cast<const T*>(a.xu);
+    const int e = (b - a.blk_xu0) * kT + tid;
+    if (e < a.nxu) {
+      const int n = (int)a.d_cip.div((uint32_t)e);
+      const int rem = e - n * a.Ci * a.P;
+      const int ci = (int)a.d_p.div((uint32_t)rem);
+      const int p = rem - ci * a.P;
+      xut[(long)ci * a.ldj + (long)n * a.P + p] = xu[e];
+    }
+    return;
+  }
+  if (b < a.blk_pad0) {  // WT [ci][co] = spatial sum of theta[co][ci], rounded once (1x1: theta itself)
+    const T* w = static_cast<const T*>(a.w);
+    const int e = (b - a.blk_w0) * kT + tid;
+    if (e < a.Ci * a.Co) {
+      const int ci = (int)a.d_c.div((uint32_t)e);   // d_c divides by Co here (set by the host)
+      const int co = e - ci * a.Co;
+      const long pair = (long)co * a.Ci + ci;
+      wt[(long)ci * a.ldc + co] = a.KK == 1 ? w[pair] : from_f32<T>(kernel_sum_of(w, pair, a.KK));
+    }
+    return;
+  }
+  // K padding of the four matrices, tickets
+  const int padj = (int)(a.ldj - a.J), padc = (int)(a.ldc - a.Co);
+  const int lane0 = (b - a.blk_pad0) * kT + tid, step = (a.blk_end - a.blk_pad0) * kT;
+  const T zero = from_f32<T>(0.f);
+  if (padj > 0) {
+    if (a.gyt)
+      for (int e = lane0; e < a.C * padj; e += step) static_cast<T*>(a.gyt)[(long)(e / padj) * a.ldj + a.J + e % padj] = zero;
+    if (a.xut)
+      for (int e = lane0; e < a.Ci * padj; e += step) xut[(long)(e / padj) * a.ldj + a.J + e % padj] = zero;
+  }
+  if (padc > 0) {
+    if (a.gyn)
+      for (int e = lane0; e < a.J * padc; e += step) static_cast<T*>(a.gyn)[(long)(e / padc) * a.ldc + a.Co + e % padc] = zero;
+    if (a.wt)
+      for (int e = lane0; e < a.Ci * padc; e += step) wt[(long)(e / padc) * a.ldc + a.Co + e % padc] = zero;
+  }
+  for (int e = lane0; e < a.ntickets; e += step) a.tickets[e] = 0;
+}
+
+template <class T>
+__global__ __launch_bounds__(kT) void dense_prep_k(PrepArgs a) {
+  if ((int)blockIdx.x >= a.blk_xu0) { prep_side_jobs<T>(a); return; }
+  constexpr int VE = El<T>::VE;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int pl0 = blockIdx.x * a.R;
+  const int npl = min(a.R, a.planes - pl0);
+  const int HW = a.H * a.W;
+  // the block's planes are one contiguous run that starts on a 16-byte boundary (R is a multiple of 8)
+  const long e0 = (long)pl0 * HW;
+  const int nel = npl * HW;
+  const T* src = static_cast<const T*>(a.in) + e0;
+  T* lin = reinterpret_cast<T*>(smem);
+  const int nvec = nel / VE;
+  for (int v = tid; v < nvec; v += kT)
+    reinterpret_cast<uint4*>(lin)[v] = load_stream16(reinterpret_cast<const uint4*>(src) + v);
+  for (int e = nvec * VE + tid; e < nel; e += kT) lin[e] = src[e];
+  T* lout = lin + ((a.R * HW + VE - 1) / VE) * VE;   // [npl][P + 1]
+  const int PP = a.P + 1;
+  __syncthreads();
+  const int q = a.q;
+  for (int idx = tid; idx < npl * a.P; idx += kT) {
+    const int pl = (int)a.d_p.div((uint32_t)idx);
+    const int p = idx - pl * a.P;
+    const int hp = (int)a.d_wp.div((uint32_t)p);
+    const int wp = p - hp * a.Wp;
+    const int ch = min(q, a.H - hp * q), cw = min(q, a.W - wp * q);
+    const T* base = lin + pl * HW + hp * q * a.W + wp * q;
+    float acc = 0.f;
+    if (a.vfirst) {   // the order of the register kernel of gf_filter_grad: columns first, then across
+      for (int j = 0; j < cw; ++j) {
+        float col = 0.f;
+        for (int i = 0; i < ch; ++i) col += to_f32(base[i * a.W + j]);
+        acc += col;
+      }
+    } else {          // the order of its LDS kernel: row by row
+      for (int i = 0; i < ch; ++i)
+        for (int j = 0; j < cw; ++j) acc += to_f32(base[i * a.W + j]);
+    }
+    if (a.mean) acc = acc / (float)(ch * cw);
+    lout[pl * PP + p] = from_f32<T>(acc);
+  }
+  __syncthreads();
+  const int nout = npl * a.P;
+  if (a.gyu) {   // caller's layout: one contiguous run
+    T* d = static_cast<T*>(a.gyu) + (long)pl0 * a.P;
+    for (int idx = tid; idx < nout; idx += kT) {
+      const int pl = (int)a.d_p.div((uint32_t)idx);
+      d[idx] = lout[pl * PP + idx - pl * a.P];
+    }
+  }
+  if (a.gyt) {   // row = channel, runs of P along j
+    T* d = static_cast<T*>(a.gyt);
+    for (int idx = tid; idx < nout; idx += kT) {
+      const int pl = (int)a.d_p.div((uint32_t)idx);
+      const int p = idx - pl * a.P;
+      const int n = (int)a.d_c.div((uint32_t)(pl0 + pl));
+      const int c = pl0 + pl - n * a.C;
+      d[(long)c * a.ldj + (long)n * a.P + p] = lout[pl * PP + p];
+    }
+  }
+  if (a.gyn) {   // row = (n, p), consecutive lanes = consecutive channels
+    T* d = static_cast<T*>(a.gyn);
+    for (int idx = tid; idx < nout; idx += kT) {
+      const int p = idx / npl;
+      const int pl = idx - p * npl;
+      const int n = (int)a.d_c.div((uint32_t)(pl0 + pl));
+      const int c = pl0 + pl - n * a.C;
+      d[((long)n * a.P + p) * a.ldc + c] = lout[pl * PP + p];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launch 2: both products, split over K slabs, finished by the last block of each tile
+// ---------------------------------------------------------------------------
+struct GemmArgs {
+  int Ci, Co, N, P, J, KK;
+  // weight gradient: C[co][ci], K = j
+  const void* gyt;
+  const void* xut;
+  long ldj;
+  float* g_w;
+  float wscale;
+  float* partW;
+  int* tickW;
+  int w_tm, w_tn, w_nz, w_cpz, w_chunks, nW, nW8;
+  // input gradient: C[ci][j], K = co; a column tile holds `ipt` whole images
+  const void* wt;
+  const void* gyn;
+  long ldc;
+  void* out;           // [N, Ci, H, W], or [N, Ci, P] with `reduced`
+  const void* mask;    // nullable [N, Ci, P] (reduced only)
+  int reduced;
+  float dscale;
+  float* partD;
+  int* tickD;
+  int d_tm, d_tn, d_nz, d_cpz, d_chunks, nD, nD8;
+  int ipt, H, W, Wp, rx, HW, epr;
+  FastDiv d_p, d_wp;
+};
+
+template <class T> struct Acc;
+template <> struct Acc<float> { typedef f32x4 type; static constexpr int BASE = 16, NV = 4; };
+template <> struct Acc<bf16_t> { typedef f32x16 type; static constexpr int BASE = 32, NV = 16; };
+
+// row of the base MFMA tile that element v of lane `lane` holds (the column is lane % BASE)
+template <class T> __device__ __forceinline__ int acc_row(int lane, int v);
+template <> __device__ __forceinline__ int acc_row<float>(int lane, int v) { return 4 * (lane >> 4) + v; }
+template <> __device__ __forceinline__ int acc_row<bf16_t>(int lane, int v) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// acc += A[m0 .. m0+63][chunks kc0 .. kc1) * B[n0 .. n0+63][same chunks]^T; rows past M / Nn read the
+// last valid row (their results are never stored).  WT: base MFMA tiles per wave and direction.
+template <class T, int WT>
+__device__ __forceinline__ void mainloop(const T* A, long lda, int M, int m0, const T* B, long ldb, int Nn, int n0,
+                                         int kc0, int kc1, unsigned char* As, unsigned char* Bs,
+                                         typename Acc<T>::type (&acc)[WT][WT]) {
+  constexpr int KB = El<T>::KB, VE = El<T>::VE, BASE = Acc<T>::BASE;
+  constexpr int LV = kTile * 8 / kT;   // 16-byte vectors per lane, operand and chunk
+  static_assert(2 * WT * BASE == kTile, "tile shape");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const T* pa[LV];
+  const T* pb[LV];
+#pragma unroll
+  for (int i = 0; i < LV; ++i) {
+    const int s = tid + i * kT, row = s >> 3, vi = s & 7;
+    pa[i] = A + (long)min(m0 + row, M - 1) * lda + vi * VE;
+    pb[i] = B + (long)min(n0 + row, Nn - 1) * ldb + vi * VE;
+  }
+  uint4 ra[LV], rb[LV];
+  auto fetch = [&](int kc) {
+#pragma unroll
+    for (int i = 0; i < LV; ++i) {
+      ra[i] = *reinterpret_cast<const uint4*>(pa[i] + (long)kc * KB);
+      rb[i] = *reinterpret_cast<const uint4*>(pb[i] + (long)kc * KB);
+    }
+  };
+  if (kc0 < kc1) fetch(kc0);
+  for (int kc = kc0; kc < kc1; ++kc) {
+#pragma unroll
+    for (int i = 0; i < LV; ++i) {
+      const int s = tid + i * kT;
+      *reinterpret_cast<uint4*>(As + (s >> 3) * kPitch + (s & 7) * 16) = ra[i];
+      *reinterpret_cast<uint4*>(Bs + (s >> 3) * kPitch + (s & 7) * 16) = rb[i];
+    }
+    __syncthreads();
+    if (kc + 1 < kc1) fetch(kc + 1);
+    if constexpr (sizeof(T) == 2) {
+      const int r = lane & 31, kg = lane >> 5;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {   // 16 k per MFMA, 64 per chunk
+        uint4 fa[WT], fb[WT];
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+          fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * WT + i) * 32 + r) * kPitch + ks * 32 + kg * 16);
+#pragma unroll
+        for (int j = 0; j < WT; ++j)
+          fb[j] = *reinterpret_cast<const uint4*>(Bs + ((wn * WT + j) * 32 + r) * kPitch + ks * 32 + kg * 16);
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+#pragma unroll
+          for (int j = 0; j < WT; ++j) acc[i][j] = mma32(fa[i], fb[j], acc[i][j]);
+      }
+    } else {
+      // one 16-byte read per operand row and 16 k; MFMA number e of the four that follow takes
+      // element e of every lane's vector (k = 16 ks + 4 (lane / 16) + e on both sides)
+      const int r = lane & 15, kg = lane >> 4;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        uint4 fa[WT], fb[WT];
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+          fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * WT + i) * 16 + r) * kPitch + ks * 64 + kg * 16);
+#pragma unroll
+        for (int j = 0; j < WT; ++j)
+          fb[j] = *reinterpret_cast<const uint4*>(Bs + ((wn * WT + j) * 16 + r) * kPitch + ks * 64 + kg * 16);
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+#pragma unroll
+          for (int j = 0; j < WT; ++j) {
+            acc[i][j] = mma16(__uint_as_float(fa[i].x), __uint_as_float(fb[j].x), acc[i][j]);
+            acc[i][j] = mma16(__uint_as_float(fa[i].y), __uint_as_float(fb[j].y), acc[i][j]);
+            acc[i][j] = mma16(__uint_as_float(fa[i].z), __uint_as_float(fb[j].z), acc[i][j]);
+            acc[i][j] = mma16(__uint_as_float(fa[i].w), __uint_as_float(fb[j].w), acc[i][j]);
+          }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// The tile of this block as a [64][64] fp32 slab in the workspace, then the ticket: true for the block
+// that arrives last (all slabs of the tile are then visible to it).
+template <class T, int WT>
+__device__ __forceinline__ bool publish_partial(typename Acc<T>::type (&acc)[WT][WT], float* slab, int* ticket,
+                                                int nz, int* s_flag) {
+  constexpr int BASE = Acc<T>::BASE, NV = Acc<T>::NV;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+  for (int i = 0; i < WT; ++i)
+#pragma unroll
+    for (int j = 0; j < WT; ++j)
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int row = (wm * WT + i) * BASE + acc_row<T>(lane, v);
+        const int col = (wn * WT + j) * BASE + (lane & (BASE - 1));
+        slab[row * kTile + col] = acc[i][j][v];
+      }
+  __threadfence();   // this lane's slab stores are visible device-wide before the ticket is taken
+  __syncthreads();
+  if (tid == 0) *s_flag = atomicAdd(ticket, 1) == nz - 1;
+  __syncthreads();
+  const bool last = *s_flag != 0;
+  if (last) __threadfence();   // the other blocks' slabs, published before their tickets
+  return last;
+}
+
+// rows r0 .. r0+epr of the finished tile into Cs[epr][kTile + 1]: from the registers (one slab) or
+// as the sum of the tile's slabs in slab order
+template <class T, int WT>
+__device__ __forceinline__ void gather_rows(typename Acc<T>::type (&acc)[WT][WT], const float* slabs, int nz,
+                                            int r0, int epr, float* Cs) {
+  constexpr int BASE = Acc<T>::BASE, NV = Acc<T>::NV, SC = kTile + 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (nz == 1) {
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+#pragma unroll
+      for (int j = 0; j < WT; ++j)
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int row = (wm * WT + i) * BASE + acc_row<T>(lane, v) - r0;
+          const int col = (wn * WT + j) * BASE + (lane & (BASE - 1));
+          if (row >= 0 && row < epr) Cs[row * SC + col] = acc[i][j][v];
+        }
+    return;
+  }
+  for (int e = tid; e < epr * kTile; e += kT) {
+    const int row = e >> 6, col = e & 63;
+    const float* p = slabs + (r0 + row) * kTile + col;
+    float s = p[0];
+    for (int z = 1; z < nz; ++z) s += p[(long)z * kTile * kTile];
+    Cs[row * SC + col] = s;
+  }
+}
+
+template <class T, int WT>
+__device__ __forceinline__ void wgrad_block(const GemmArgs& a, int L, unsigned char* smem, int* s_flag) {
+  typename Acc<T>::type acc[WT][WT];
+#pragma unroll
+  for (int i = 0; i < WT; ++i)
+#pragma unroll
+    for (int j = 0; j < WT; ++j)
+#pragma unroll
+      for (int v = 0; v < Acc<T>::NV; ++v) acc[i][j][v] = 0.f;
+  const int tiles = a.w_tm * a.w_tn;
+  const int z = L / tiles, t = L - z * tiles;
+  const int tmi = t / a.w_tn, tni = t - tmi * a.w_tn;
+  const int m0 = tmi * kTile, n0 = tni * kTile;
+  const int kc0 = z * a.w_cpz, kc1 = min(kc0 + a.w_cpz, a.w_chunks);
+  mainloop<T, WT>(static_cast<const T*>(a.gyt), a.ldj, a.Co, m0, static_cast<const T*>(a.xut), a.ldj, a.Ci, n0,
+                  kc0, kc1, smem, smem + kTile * kPitch, acc);
+  const float* slabs = a.partW + (long)t * a.w_nz * kTile * kTile;
+  if (a.w_nz > 1 &&
+      !publish_partial<T, WT>(acc, a.partW + ((long)t * a.w_nz + z) * kTile * kTile, a.tickW + t, a.w_nz, s_flag))
+    return;
+  constexpr int SC = kTile + 1, EPR = 32;
+  float* Cs = reinterpret_cast<float*>(smem);
+  const int tid = threadIdx.x;
+  const int ncol = min(kTile, a.Ci - n0);
+  const int run = ncol * a.KK;   // one c_o row of the tile is one contiguous run of g_w
+  for (int r0 = 0; r0 < kTile && m0 + r0 < a.Co; r0 += EPR) {
+    __syncthreads();
+    gather_rows<T, WT>(acc, slabs, a.w_nz, r0, EPR, Cs);
+    __syncthreads();
+    const int nr = min(EPR, a.Co - m0 - r0);
+    for (int e = tid; e < nr * run; e += kT) {
+      const int row = e / run, rem = e - row * run;
+      a.g_w[((long)(m0 + r0 + row) * a.Ci + n0) * a.KK + rem] = Cs[row * SC + rem / a.KK] * a.wscale;
+    }
+  }
+}
+
+template <class T, int WT>
+__device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned char* smem, int* s_flag) {
+  typename Acc<T>::type acc[WT][WT];
+#pragma unroll
+  for (int i = 0; i < WT; ++i)
+#pragma unroll
+    for (int j = 0; j < WT; ++j)
+#pragma unroll
+      for (int v = 0; v < Acc<T>::NV; ++v) acc[i][j][v] = 0.f;
+  // image group slowest: the blocks one XCD receives share their rows of GYN
+  const int per_group = a.d_tm * a.d_nz;
+  const int tni = L / per_group, rem = L - tni * per_group;
+  const int z = rem / a.d_tm, tmi = rem - z * a.d_tm;
+  const int t = tni * a.d_tm + tmi;
+  const int m0 = tmi * kTile;                 // first c_i
+  const int img0 = tni * a.ipt;               // first image
+  const int j0 = img0 * a.P;
+  const int kc0 = z * a.d_cpz, kc1 = min(kc0 + a.d_cpz, a.d_chunks);
+  mainloop<T, WT>(static_cast<const T*>(a.wt), a.ldc, a.Ci, m0, static_cast<const T*>(a.gyn), a.ldc, a.J, j0,
+                  kc0, kc1, smem, smem + kTile * kPitch, acc);
+  const float* slabs = a.partD + (long)t * a.d_nz * kTile * kTile;
+  if (a.d_nz > 1 &&
+      !publish_partial<T, WT>(acc, a.partD + ((long)t * a.d_nz + z) * kTile * kTile, a.tickD + t, a.d_nz, s_flag))
+    return;
+  constexpr int SC = kTile + 1;
+  float* Cs = reinterpret_cast<float*>(smem);
+  T* Es = reinterpret_cast<T*>(smem + 32 * SC * sizeof(float));   // 16-byte aligned: 32 * 65 * 4 = 8320
+  const int tid = threadIdx.x;
+  const int nimg = min(a.ipt, a.N - img0);
+  T* out = static_cast<T*>(a.out);
+  const T* mask = static_cast<const T*>(a.mask);
+  constexpr int VE = El<T>::VE;
+  for (int r0 = 0; r0 < kTile && m0 + r0 < a.Ci; r0 += a.epr) {
+    __syncthreads();
+    gather_rows<T, WT>(acc, slabs, a.d_nz, r0, a.epr, Cs);
+    __syncthreads();
+    const int nr = min(a.epr, a.Ci - m0 - r0);
+    if (a.reduced) {   // one value per patch: rows of an image are one contiguous run of nr * P
+      for (int il = 0; il < nimg; ++il) {
+        const long o0 = ((long)(img0 + il) * a.Ci + m0 + r0) * a.P;
+        for (int e = tid; e < nr * a.P; e += kT) {
+          const int row = (int)a.d_p.div((uint32_t)e);
+          T v = from_f32<T>(Cs[row * SC + il * a.P + e - row * a.P] * a.dscale);
+          if (mask) v = from_f32<T>(to_f32(v) * to_f32(mask[o0 + e]));
+          out[o0 + e] = v;
+        }
+      }
+      continue;
+    }
+    for (int il = 0; il < nimg; ++il) {
+      // every patch value, rounded once, to its r_x x r_x pixels of the LDS image of the run
+      for (int e = tid; e < nr * a.P; e += kT) {
+        const int row = (int)a.d_p.div((uint32_t)e);
+        const int pp = e - row * a.P;
+        const int hp = (int)a.d_wp.div((uint32_t)pp);
+        const int wp = pp - hp * a.Wp;
+        const T val = from_f32<T>(Cs[row * SC + il * a.P + pp] * a.dscale);
+        const int h1 = min(a.H, (hp + 1) * a.rx), w1 = min(a.W, (wp + 1) * a.rx);
+        for (int h = hp * a.rx; h < h1; ++h)
+          for (int ww = wp * a.rx; ww < w1; ++ww) Es[row * a.HW + h * a.W + ww] = val;
+      }
+      __syncthreads();
+      // planes (n, m0 + r0 ...) are consecutive in memory and start on a 16-byte boundary
+      T* d = out + ((long)(img0 + il) * a.Ci + m0 + r0) * a.HW;
+      const int nel = nr * a.HW, nvec = nel / VE;
+      for (int v = tid; v < nvec; v += kT)
+        store_stream16(reinterpret_cast<uint4*>(d) + v, reinterpret_cast<const uint4*>(Es)[v]);
+      for (int e = nvec * VE + tid; e < nel; e += kT) d[e] = Es[e];
+      __syncthreads();
+    }
+  }
+}
+
+constexpr int kOperandBytes = 2 * kTile * kPitch;
+constexpr int kEpilogueBytes = 32 * (kTile + 1) * 4 + kEsBytes;
+constexpr int kGemmSmemBytes = kOperandBytes > kEpilogueBytes ? kOperandBytes : kEpilogueBytes;
+
+template <class T>
+__global__ __launch_bounds__(kT) void dense_gemm_k(GemmArgs a) {
+  constexpr int WT = kTile / 2 / Acc<T>::BASE;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kGemmSmemBytes];
+  __shared__ int s_flag;
+  // blocks b, b + 8, b + 16 ... run on one XCD: give them consecutive work items of one product
+  int b = blockIdx.x;
+  if (b < a.nW8) {
+    const int L = (b & 7) * (a.nW8 >> 3) + (b >> 3);
+    if (L < a.nW) wgrad_block<T, WT>(a, L, smem, &s_flag);
+    return;
+  }
+  b -= a.nW8;
+  const int L = (b & 7) * (a.nD8 >> 3) + (b >> 3);
+  if (L < a.nD) dgrad_block<T, WT>(a, L, smem, &s_flag);
+}
+
+long round_up(long v, long m) { return (v + m - 1) / m * m; }
+
+struct Plan {
+  long ldj, ldc;
+  int w_tm, w_tn, w_nz, w_cpz, w_chunks;
+  int d_tm, d_tn, d_nz, d_cpz, d_chunks, ipt, epr;
+  size_t off_tick, off_gyt, off_xut, off_gyn, off_wt, off_pw, off_pd, total;
+};
+
+int slabs_for(int tiles, int chunks, int want_blocks) {
+  int nz = cdiv(want_blocks, tiles);
+  const int most = chunks / 4 > 1 ? chunks / 4 : 1;   // at least four chunks per block
+  if (nz > most) nz = most;
+  if (nz < 1) nz = 1;
+  return nz;
+}
+
+Plan make_plan(const Geom& g, bool want_w, bool want_d) {
+  Plan p;
+  const int KB = g.b == 2 ? 64 : 32;
+  const long J = (long)g.N * g.P;
+  p.ldj = round_up(J, KB);
+  p.ldc = round_up(g.Co, KB);
+  p.w_tm = cdiv(g.Co, kTile);
+  p.w_tn = cdiv(g.Ci, kTile);
+  p.w_chunks = (int)(p.ldj / KB);
+  p.w_nz = slabs_for(p.w_tm * p.w_tn, p.w_chunks, 768);
+  p.w_cpz = cdiv(p.w_chunks, p.w_nz);
+  p.w_nz = cdiv(p.w_chunks, p.w_cpz);
+  p.ipt = kTile / g.P;
+  // small batches: rather more column tiles than a chip that is mostly idle
+  while (p.ipt > 1 && (long)cdiv(g.N, p.ipt) * cdiv(g.Ci, kTile) < 256) --p.ipt;
+  p.d_tm = cdiv(g.Ci, kTile);
+  p.d_tn = cdiv(g.N, p.ipt);
+  p.d_chunks = (int)(p.ldc / KB);
+  p.d_nz = slabs_for(p.d_tm * p.d_tn, p.d_chunks, 768);
+  p.d_cpz = cdiv(p.d_chunks, p.d_nz);
+  p.d_nz = cdiv(p.d_chunks, p.d_cpz);
+  const int plane_bytes = g.H * g.W * g.b;
+  p.epr = 32 * plane_bytes <= kEsBytes ? 32 : 16 * plane_bytes <= kEsBytes ? 16 : 8;
+  auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  size_t o = 0;
+  p.off_tick = o; o += al(((size_t)p.w_tm * p.w_tn + (size_t)p.d_tm * p.d_tn) * sizeof(int));
+  p.off_gyt = o; if (want_w) o += al((size_t)g.Co * p.ldj * g.b);
+  p.off_xut = o; if (want_w) o += al((size_t)g.Ci * p.ldj * g.b);
+  p.off_gyn = o; if (want_d) o += al((size_t)J * p.ldc * g.b);
+  p.off_wt = o; if (want_d) o += al((size_t)g.Ci * p.ldc * g.b);
+  p.off_pw = o; if (want_w && p.w_nz > 1) o += al((size_t)p.w_tm * p.w_tn * p.w_nz * kTile * kTile * sizeof(float));
+  p.off_pd = o; if (want_d && p.d_nz > 1) o += al((size_t)p.d_tm * p.d_tn * p.d_nz * kTile * kTile * sizeof(float));
+  p.total = o;
+  return p;
+}
+
+int prep_planes_per_block(const Geom& g, int H, int W) {
+  int R = kPrepInBytes / (H * W * g.b) / 8 * 8;
+  if (R > 32) R = 32;
+  if (R < 8) R = 8;
+  return R;
+}
+
+template <class T>
+hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* x_u, const void* w, void* gy_u_out,
+                    float* g_w, void* g_x, bool reduced, const void* mask_u, void* ws, hipStream_t st) {
+  const bool want_w = g_w != nullptr, want_d = g_x != nullptr;
+  const Plan p = make_plan(g, want_w, want_d);
+  char* wsb = static_cast<char*>(ws);
+  const int J = g.N * g.P;
+  PrepArgs a;
+  a.in = src;
+  a.planes = g.N * g.Co;
+  a.C = g.Co;
+  if (src_is_gy) { a.H = g.Hy; a.W = g.Wy; a.q = g.r; a.mean = 1; }
+  else { a.H = g.Hp; a.W = g.Wp; a.q = 1; a.mean = 0; }
+  a.Hp = g.Hp; a.Wp = g.Wp; a.P = g.P;
+  a.vfirst = src_is_gy && patch_reduce_uses_rows(g.dtype, a.planes, a.H, a.W, a.q) ? 1 : 0;
+  a.R = prep_planes_per_block(g, a.H, a.W);
+  a.total_in = (long)a.planes * a.H * a.W;
+  a.d_p = FastDiv((uint32_t)g.P);
+  a.d_wp = FastDiv((uint32_t)g.Wp);
+  a.d_c = FastDiv((uint32_t)g.Co);
+  a.gyu = gy_u_out;
+  a.gyt = want_w ? wsb + p.off_gyt : nullptr;
+  a.gyn = want_d ? wsb + p.off_gyn : nullptr;
+  a.ldj = p.ldj; a.ldc = p.ldc; a.J = J;
+  a.xu = want_w ? x_u : nullptr;
+  a.xut = want_w ? wsb + p.off_xut : nullptr;
+  a.Ci = g.Ci;
+  a.nxu = g.N * g.Ci * g.P;
+  a.d_cip = FastDiv((uint32_t)(g.Ci * g.P));
+  a.w = want_d ? w : nullptr;
+  a.wt = want_d ? wsb + p.off_wt : nullptr;
+  a.Co = g.Co; a.KK = g.KK;
+  a.tickets = reinterpret_cast<int*>(wsb + p.off_tick);
+  a.ntickets = p.w_tm * p.w_tn + p.d_tm * p.d_tn;
+  const int nred = cdiv(a.planes, a.R);
+  a.blk_xu0 = nred;
+  a.blk_w0 = a.blk_xu0 + (want_w ? cdiv(a.nxu, kT) : 0);
+  a.blk_pad0 = a.blk_w0 + (want_d ? cdiv(g.Ci * g.Co, kT) : 0);
+  a.blk_end = a.blk_pad0 + 8;
+  const int VE = El<T>::VE;
+  const size_t lds = (size_t)((a.R * a.H * a.W + VE - 1) / VE * VE + a.R * (g.P + 1)) * sizeof(T) + 16;
+  GF_LAUNCH(dense_prep_k<T>, dim3(a.blk_end), dim3(kT), lds, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  GemmArgs q;
+  q.Ci = g.Ci; q.Co = g.Co; q.N = g.N; q.P = g.P; q.J = J; q.KK = g.KK;
+  q.gyt = a.gyt; q.xut = a.xut; q.ldj = p.ldj;
+  q.g_w = g_w;
+  q.wscale = 1.f / ((float)g.s * (float)g.s);
+  q.partW = reinterpret_cast<float*>(wsb + p.off_pw);
+  q.tickW = a.tickets;
+  q.w_tm = p.w_tm; q.w_tn = p.w_tn; q.w_nz = p.w_nz; q.w_cpz = p.w_cpz; q.w_chunks = p.w_chunks;
+  q.nW = want_w ? p.w_tm * p.w_tn * p.w_nz : 0;
+  q.nW8 = (q.nW + 7) & ~7;
+  q.wt = a.wt; q.gyn = a.gyn; q.ldc = p.ldc;
+  q.out = g_x; q.mask = reduced ? mask_u : nullptr; q.reduced = reduced ? 1 : 0;
+  q.dscale = q.wscale;
+  q.partD = reinterpret_cast<float*>(wsb + p.off_pd);
+  q.tickD = a.tickets + p.w_tm * p.w_tn;
+  q.d_tm = p.d_tm; q.d_tn = p.d_tn; q.d_nz = p.d_nz; q.d_cpz = p.d_cpz; q.d_chunks = p.d_chunks;
+  q.nD = want_d ? p.d_tm * p.d_tn * p.d_nz : 0;
+  q.nD8 = (q.nD + 7) & ~7;
+  q.ipt = p.ipt; q.H = g.H; q.W = g.W; q.Wp = g.Wp; q.rx = g.rx; q.HW = g.H * g.W; q.epr = p.epr;
+  q.d_p = a.d_p; q.d_wp = a.d_wp;
+  GF_LAUNCH(dense_gemm_k<T>, dim3(q.nW8 + q.nD8), dim3(kT), 0, st, q);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Layers this path takes: dense, filtered, at most 64 patches per plane (a column tile of the
+// input gradient is whole images), planes of at most 256 pixels, C_x a multiple of 8 (every run of
+// planes the epilogue stores then starts on a 16-byte boundary).
+bool dense_ok(const Geom& g) {
+  if (g.g != 1 || g.r == 1) return false;
+  if (g.P > kTile || (long)g.H * g.W > 256 || (long)g.Hy * g.Wy > 256) return false;
+  if (g.Ci % 8 != 0) return false;
+  // 32-bit indices of the relaid-out matrices
+  const long KB = g.b == 2 ? 64 : 32;
+  const long J = (long)g.N * g.P;
+  const long lim = (1L << 31) - (1L << 20);
+  if (round_up(J, KB) * (g.Co > g.Ci ? g.Co : g.Ci) > lim || J * round_up(g.Co, KB) > lim) return false;
+  return true;
+}
+
+size_t ws_dense(const Geom& g, bool want_w, bool want_d) { return make_plan(g, want_w, want_d).total; }
+
+hipError_t launch_dense(const Geom& g, const void* src, bool src_is_gy, const void* x_u, const void* w,
+                        void* gy_u_out, float* g_w, void* g_x, bool reduced, const void* mask_u, void* ws,
+                        hipStream_t st) {
+  if (g.dtype == GF_BF16)
+    return launch_t<bf16_t>(g, src, src_is_gy, x_u, w, gy_u_out, g_w, g_x, reduced, mask_u, ws, st);
+  return launch_t<float>(g, src, src_is_gy, x_u, w, gy_u_out, g_w, g_x, reduced, mask_u, ws, st);
+}
+
+}  // namespace gf

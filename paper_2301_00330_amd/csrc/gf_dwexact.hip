@@ -435,11 +435,11 @@ template <class T, int K, int S>
 static hipError_t dgrad_launch_s(DwExactArgs& a, bool wave, size_t lds, hipStream_t st) {
   const dim3 grid(cdiv(a.planes, a.ppb)), block(kThreads);
   if constexpr (S == 1) {
-    if (wave) hipLaunchKernelGGL((dw_exact_dgrad_s1_k<T, K, true>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((dw_exact_dgrad_s1_k<T, K, false>), grid, block, lds, st, a);
+    if (wave) GF_LAUNCH((dw_exact_dgrad_s1_k<T, K, true>), grid, block, lds, st, a);
+    else GF_LAUNCH((dw_exact_dgrad_s1_k<T, K, false>), grid, block, lds, st, a);
   } else {
-    if (wave) hipLaunchKernelGGL((dw_exact_dgrad_k<T, K, S, true>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((dw_exact_dgrad_k<T, K, S, false>), grid, block, lds, st, a);
+    if (wave) GF_LAUNCH((dw_exact_dgrad_k<T, K, S, true>), grid, block, lds, st, a);
+    else GF_LAUNCH((dw_exact_dgrad_k<T, K, S, false>), grid, block, lds, st, a);
   }
   return hipGetLastError();
 }
@@ -478,11 +478,11 @@ template <class T, int K>
 static hipError_t wgrad_launch(DwExactArgs& a, bool wave, size_t lds, hipStream_t st) {
   const dim3 grid(cdiv(a.planes, a.ppb)), block(kThreads);
   if (a.s == 1) {
-    if (wave) hipLaunchKernelGGL((dw_exact_wgrad_s1_k<T, K, true>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((dw_exact_wgrad_s1_k<T, K, false>), grid, block, lds, st, a);
+    if (wave) GF_LAUNCH((dw_exact_wgrad_s1_k<T, K, true>), grid, block, lds, st, a);
+    else GF_LAUNCH((dw_exact_wgrad_s1_k<T, K, false>), grid, block, lds, st, a);
   } else {
-    if (wave) hipLaunchKernelGGL((dw_exact_wgrad_k<T, K, true>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((dw_exact_wgrad_k<T, K, false>), grid, block, lds, st, a);
+    if (wave) GF_LAUNCH((dw_exact_wgrad_k<T, K, true>), grid, block, lds, st, a);
+    else GF_LAUNCH((dw_exact_wgrad_k<T, K, false>), grid, block, lds, st, a);
   }
   return hipGetLastError();
 }

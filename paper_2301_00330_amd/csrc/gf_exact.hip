@@ -288,13 +288,13 @@ hipError_t launch_col(const Geom& g, const void* src, void* dst, bool gather_inp
     r.d_kw = FastDiv((uint32_t)g.Kw);
     long nb = ((long)r.total_vec + kThreads - 1) / kThreads;
     if (nb > (1 << 20)) nb = 1 << 20;
-    hipLaunchKernelGGL(im2col_rows_k<T>, dim3((int)nb), dim3(kThreads), 0, st, r);
+    GF_LAUNCH(im2col_rows_k<T>, dim3((int)nb), dim3(kThreads), 0, st, r);
     return hipGetLastError();
   }
   long blocks = (a.total / VE + kThreads - 1) / kThreads;
   if (blocks > (1 << 20)) blocks = 1 << 20;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(im2col_k<T>, dim3((int)blocks), dim3(kThreads), 0, st, a);
+  GF_LAUNCH(im2col_k<T>, dim3((int)blocks), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -343,9 +343,9 @@ hipError_t launch_exact_wgrad(const Geom& g, const void* x, const void* g_y, flo
   a.gw = g_w;
   const int blocks = g.Co * g.Cg * g.KK;
   if (g.dtype == GF_BF16)
-    hipLaunchKernelGGL(exact_wgrad_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, a);
+    GF_LAUNCH(exact_wgrad_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL(exact_wgrad_k<float>, dim3(blocks), dim3(kThreads), 0, st, a);
+    GF_LAUNCH(exact_wgrad_k<float>, dim3(blocks), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -362,10 +362,10 @@ hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, voi
     void* wt = wsb + align256((size_t)g.N * g.Co * g.KK * g.H * g.W * g.b);
     const int tot = g.Co * g.Ci * g.KK;
     if (g.dtype == GF_BF16)
-      hipLaunchKernelGGL(permute_w_k<bf16_t>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
+      GF_LAUNCH(permute_w_k<bf16_t>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
                          static_cast<const bf16_t*>(w), static_cast<bf16_t*>(wt), g.Co, g.Ci, g.KK);
     else
-      hipLaunchKernelGGL(permute_w_k<float>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
+      GF_LAUNCH(permute_w_k<float>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
                          static_cast<const float*>(w), static_cast<float*>(wt), g.Co, g.Ci, g.KK);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -380,9 +380,9 @@ hipError_t launch_exact_dgrad(const Geom& g, const void* w, const void* g_y, voi
   int blocks = cdiv(a.total, kThreads);
   if (blocks > 1 << 20) blocks = 1 << 20;
   if (g.dtype == GF_BF16)
-    hipLaunchKernelGGL(exact_dgrad_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, a);
+    GF_LAUNCH(exact_dgrad_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL(exact_dgrad_k<float>, dim3(blocks), dim3(kThreads), 0, st, a);
+    GF_LAUNCH(exact_dgrad_k<float>, dim3(blocks), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 

@@ -59,11 +59,11 @@ __global__ __launch_bounds__(kThreads) void finalize_gw_k(const float* part, flo
 hipError_t launch_finalize_impl(const float* part, float* g_w, int pairs, int nz, int KK, float scale,
                                 hipStream_t st) {
   if (nz >= 32)
-    hipLaunchKernelGGL(finalize_gw_k<16>, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
+    GF_LAUNCH(finalize_gw_k<16>, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
   else if (nz >= 8)
-    hipLaunchKernelGGL(finalize_gw_k<4>, dim3(cdiv(pairs, kThreads / 4)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
+    GF_LAUNCH(finalize_gw_k<4>, dim3(cdiv(pairs, kThreads / 4)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
   else
-    hipLaunchKernelGGL(finalize_gw_k<1>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
+    GF_LAUNCH(finalize_gw_k<1>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st, part, g_w, pairs, nz, KK, scale);
   return hipGetLastError();
 }
 
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void expand_rows_k(ExpandRowsArgs a) {
 
 template <class T, class S, int RX>
 hipError_t launch_expand_rows(ExpandRowsArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((expand_rows_k<T, S, RX>), dim3(cdiv(a.total_items, kThreads)), dim3(kThreads),
+  GF_LAUNCH((expand_rows_k<T, S, RX>), dim3(cdiv(a.total_items, kThreads)), dim3(kThreads),
                      0, st, a);
   return hipGetLastError();
 }
@@ -564,7 +564,7 @@ hipError_t launch_expand(const S* src, T* out, const float* chscale, float scala
       e.planes = (int)planes; e.ppb = ppb; e.H = H; e.W = W; e.Wp = Wp; e.P = Hp * Wp; e.rx = rx;
       e.d_p = FastDiv((uint32_t)(Hp * Wp));
       e.d_wp = FastDiv((uint32_t)Wp);
-      hipLaunchKernelGGL((expand_planes_k<T, S>), dim3(cdiv(planes, ppb)), dim3(kThreads),
+      GF_LAUNCH((expand_planes_k<T, S>), dim3(cdiv(planes, ppb)), dim3(kThreads),
                          (size_t)ppb * H * W * sizeof(T), st, e);
       return hipGetLastError();
     }
@@ -593,12 +593,12 @@ hipError_t launch_expand(const S* src, T* out, const float* chscale, float scala
   a.d_p = FastDiv((uint32_t)(Hp * Wp));
   // planes a block of kExpandPerBlock outputs can touch, times the values per plane
   if (((long)kExpandPerBlock / (H * W) + 2) * Hp * Wp <= kExpandLdsMax) {
-    hipLaunchKernelGGL((expand_lds_k<T, S>), dim3(cdiv(a.total, kExpandPerBlock)), dim3(kThreads), 0, st, a);
+    GF_LAUNCH((expand_lds_k<T, S>), dim3(cdiv(a.total, kExpandPerBlock)), dim3(kThreads), 0, st, a);
     return hipGetLastError();
   }
   constexpr int V = 16 / (int)sizeof(T);
   const int blocks = cdiv(cdiv(a.total, V), kThreads);
-  hipLaunchKernelGGL((expand_k<T, S>), dim3(blocks), dim3(kThreads), 0, st, a);
+  GF_LAUNCH((expand_k<T, S>), dim3(blocks), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -633,10 +633,10 @@ hipError_t launch_kernel_sum(const void* w, float* wsum, long pairs, int KK, int
                              hipStream_t st) {
   const int blocks = cdiv(pairs, kThreads);
   if (dtype == GF_BF16)
-    hipLaunchKernelGGL(kernel_sum_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
+    GF_LAUNCH(kernel_sum_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
                        static_cast<const bf16_t*>(w), wsum, (int)pairs, KK);
   else
-    hipLaunchKernelGGL(kernel_sum_k<float>, dim3(blocks), dim3(kThreads), 0, st,
+    GF_LAUNCH(kernel_sum_k<float>, dim3(blocks), dim3(kThreads), 0, st,
                        static_cast<const float*>(w), wsum, (int)pairs, KK);
   return hipGetLastError();
 }
@@ -664,22 +664,22 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
       const int L = dw_lanes(cdiv(nvec, 2));
       const int blocks = cdiv((long)planes * L, kThreads);
       if (g.dtype == GF_BF16)
-        hipLaunchKernelGGL(dw_dot_vec_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
+        GF_LAUNCH(dw_dot_vec_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
                            static_cast<const bf16_t*>(x_u), static_cast<const bf16_t*>(gy_u), part,
                            planes, nvec, L);
       else
-        hipLaunchKernelGGL(dw_dot_vec_k<float>, dim3(blocks), dim3(kThreads), 0, st,
+        GF_LAUNCH(dw_dot_vec_k<float>, dim3(blocks), dim3(kThreads), 0, st,
                            static_cast<const float*>(x_u), static_cast<const float*>(gy_u), part,
                            planes, nvec, L);
     } else {
     const int L = dw_lanes(g.P);
     const int blocks = cdiv((long)planes * L, kThreads);
     if (g.dtype == GF_BF16)
-      hipLaunchKernelGGL(dw_dot_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
+      GF_LAUNCH(dw_dot_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st,
                          static_cast<const bf16_t*>(x_u), static_cast<const bf16_t*>(gy_u), part,
                          planes, g.P, L);
     else
-      hipLaunchKernelGGL(dw_dot_k<float>, dim3(blocks), dim3(kThreads), 0, st,
+      GF_LAUNCH(dw_dot_k<float>, dim3(blocks), dim3(kThreads), 0, st,
                          static_cast<const float*>(x_u), static_cast<const float*>(gy_u), part,
                          planes, g.P, L);
     }
@@ -703,9 +703,9 @@ hipError_t launch_gf_bwd_weight(const Geom& g, const void* x_u, const void* gy_u
     a.n_per_z = cdiv(g.N, nz);
     dim3 grid(cdiv(g.Cg, 64), g.g * a.tiles_co, nz);
     if (g.dtype == GF_BF16)
-      hipLaunchKernelGGL(gf_wgrad_tile_k<bf16_t>, grid, dim3(kThreads), 0, st, a);
+      GF_LAUNCH(gf_wgrad_tile_k<bf16_t>, grid, dim3(kThreads), 0, st, a);
     else
-      hipLaunchKernelGGL(gf_wgrad_tile_k<float>, grid, dim3(kThreads), 0, st, a);
+      GF_LAUNCH(gf_wgrad_tile_k<float>, grid, dim3(kThreads), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -762,13 +762,13 @@ static hipError_t bwd_input_t(const Geom& g, const T* gy_u, const T* w, T* g_x, 
   dim3 grid(cdiv(g.P, 64), g.g * a.tiles_ci, g.N);
   if (reduced_out) {
     a.dst = g_x;
-    hipLaunchKernelGGL((gf_dgrad_tile_k<T, T>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((gf_dgrad_tile_k<T, T>), grid, dim3(kThreads), 0, st, a);
     return hipGetLastError();
   }
   float* red = reinterpret_cast<float*>(static_cast<char*>(ws) +
                                         align256((size_t)g.Co * g.Cg * sizeof(float)));
   a.dst = red;
-  hipLaunchKernelGGL((gf_dgrad_tile_k<T, float>), grid, dim3(kThreads), 0, st, a);
+  GF_LAUNCH((gf_dgrad_tile_k<T, float>), grid, dim3(kThreads), 0, st, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_expand<T, float>(red, g_x, nullptr, 1.f, planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
@@ -801,12 +801,12 @@ hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, con
   const int blocks = cdiv((long)planes * L, kThreads);
   const float scalar = 1.f / ((float)g.s * (float)g.s);
   if (g.dtype == GF_BF16)
-    hipLaunchKernelGGL(dw_chain_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const bf16_t*>(x_u),
+    GF_LAUNCH(dw_chain_k<bf16_t>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const bf16_t*>(x_u),
                        static_cast<const bf16_t*>(gy_u), static_cast<const bf16_t*>(w), part,
                        static_cast<bf16_t*>(g_xu), static_cast<const bf16_t*>(mask_u), planes, g.P, L, g.Ci, g.KK,
                        scalar);
   else
-    hipLaunchKernelGGL(dw_chain_k<float>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const float*>(x_u),
+    GF_LAUNCH(dw_chain_k<float>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const float*>(x_u),
                        static_cast<const float*>(gy_u), static_cast<const float*>(w), part,
                        static_cast<float*>(g_xu), static_cast<const float*>(mask_u), planes, g.P, L, g.Ci, g.KK,
                        scalar);

@@ -463,7 +463,7 @@ static hipError_t dw_fused_t(const Geom& g, const void* g_y, const void* x_u, co
     const int in_bytes = ((a.ppb * g.Hy * g.Wy * (int)sizeof(T) + 32) + 15) & ~15;
     const int out_bytes = ((a.ppb * g.H * g.W * (int)sizeof(T) + 32) + 15) & ~15;
     const size_t lds = (size_t)in_bytes + out_bytes + (size_t)a.ppb * g.P * 4 + (size_t)a.ppb * 4;
-    hipLaunchKernelGGL(dw_fused_strided_k<T>, dim3(cdiv(a.planes, a.ppb)), dim3(kThreads), lds, st, a);
+    GF_LAUNCH(dw_fused_strided_k<T>, dim3(cdiv(a.planes, a.ppb)), dim3(kThreads), lds, st, a);
     return hipGetLastError();
   }
   if (rows_variant_ok<T>(g)) {
@@ -476,9 +476,9 @@ static hipError_t dw_fused_t(const Geom& g, const void* g_y, const void* x_u, co
     a.d_ipr = FastDiv((uint32_t)a.ipr);
     a.d_cpp = FastDiv((uint32_t)a.cpp);
     const dim3 grid(a.planes * a.cpp), block(nthreads);
-    if (g.r == 8) hipLaunchKernelGGL((dw_fused_rows_k<T, 8, 1>), grid, block, 0, st, a);
-    else if (g.r == 2) hipLaunchKernelGGL((dw_fused_rows_k<T, 2, 1>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((dw_fused_rows_k<T, 4, 1>), grid, block, 0, st, a);
+    if (g.r == 8) GF_LAUNCH((dw_fused_rows_k<T, 8, 1>), grid, block, 0, st, a);
+    else if (g.r == 2) GF_LAUNCH((dw_fused_rows_k<T, 2, 1>), grid, block, 0, st, a);
+    else GF_LAUNCH((dw_fused_rows_k<T, 4, 1>), grid, block, 0, st, a);
     return hipGetLastError();
   }
   a.ppb = lds_planes_per_block<T>(g);
@@ -487,9 +487,9 @@ static hipError_t dw_fused_t(const Geom& g, const void* g_y, const void* x_u, co
   const int run_bytes = ((a.ppb * g.H * g.W * (int)sizeof(T) + 32) + 15) & ~15;
   const size_t lds = (size_t)run_bytes + (size_t)a.ppb * g.P * 4 + (size_t)a.ppb * 4;
   const int blocks = cdiv(a.planes, a.ppb);
-  if (g.r == 2) hipLaunchKernelGGL((dw_fused_lds_k<T, 2>), dim3(blocks), dim3(kThreads), lds, st, a);
-  else if (g.r == 4) hipLaunchKernelGGL((dw_fused_lds_k<T, 4>), dim3(blocks), dim3(kThreads), lds, st, a);
-  else hipLaunchKernelGGL((dw_fused_lds_k<T, 0>), dim3(blocks), dim3(kThreads), lds, st, a);
+  if (g.r == 2) GF_LAUNCH((dw_fused_lds_k<T, 2>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else if (g.r == 4) GF_LAUNCH((dw_fused_lds_k<T, 4>), dim3(blocks), dim3(kThreads), lds, st, a);
+  else GF_LAUNCH((dw_fused_lds_k<T, 0>), dim3(blocks), dim3(kThreads), lds, st, a);
   return hipGetLastError();
 }
 

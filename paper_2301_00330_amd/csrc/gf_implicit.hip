@@ -887,7 +887,7 @@ hipError_t launch_prep(const Geom& g, const XGeo& q, const XPlan& p, char* ws, c
   const int tab_blocks = cdiv((long)g.KK * nmax, kThreads);
   const int w_blocks = want_gx ? cdiv((long)g.Co * g.Ci * g.KK, kThreads) : 0;
   const int x_blocks = (want_gw && g.s > 1) ? cdiv((long)q.nph * g.N * g.Ci * q.PQ, kThreads) : 0;
-  hipLaunchKernelGGL(prep_k<T>, dim3(tab_blocks + w_blocks + x_blocks), dim3(kThreads), 0, st, a, tab_blocks,
+  GF_LAUNCH(prep_k<T>, dim3(tab_blocks + w_blocks + x_blocks), dim3(kThreads), 0, st, a, tab_blocks,
                      w_blocks, static_cast<const T*>(w), reinterpret_cast<T*>(ws + p.off_wt), g.Co,
                      static_cast<const T*>(x), reinterpret_cast<T*>(ws + p.off_xq));
   return hipGetLastError();
@@ -918,22 +918,22 @@ hipError_t wgrad_t(const Geom& g, const XGeo& q, const XPlan& p, const void* x, 
   a.d_tx = FastDiv((uint32_t)a.tx);
   const dim3 grid(a.xcd_slabs ? 8 * a.R * cdiv(p.nz, 8) : a.R * p.nz);
   if (p.bm == 64)
-    hipLaunchKernelGGL((xwgrad_k<T, 2, 2, 16>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((xwgrad_k<T, 2, 2, 16>), grid, dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL((xwgrad_k<T, 4, 4, 16>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((xwgrad_k<T, 4, 4, 16>), grid, dim3(kThreads), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int pairs = g.Co * g.Ci;
   // lanes per output: enough blocks for the chip when the output is small and the slabs are many
   const long outs = (long)pairs * g.KK;
   if (outs <= 16384 && p.nz >= 64)
-    hipLaunchKernelGGL(xfinalize_k<16>, dim3(cdiv(pairs, kThreads / 16), g.KK), dim3(kThreads), 0, st, a.part, g_w,
+    GF_LAUNCH(xfinalize_k<16>, dim3(cdiv(pairs, kThreads / 16), g.KK), dim3(kThreads), 0, st, a.part, g_w,
                        pairs, g.KK, p.nz);
   else if (outs <= 131072 && p.nz >= 16)
-    hipLaunchKernelGGL(xfinalize_k<4>, dim3(cdiv(pairs, kThreads / 4), g.KK), dim3(kThreads), 0, st, a.part, g_w,
+    GF_LAUNCH(xfinalize_k<4>, dim3(cdiv(pairs, kThreads / 4), g.KK), dim3(kThreads), 0, st, a.part, g_w,
                        pairs, g.KK, p.nz);
   else
-    hipLaunchKernelGGL(xfinalize_k<1>, dim3(cdiv(pairs, kThreads), g.KK), dim3(kThreads), 0, st, a.part, g_w, pairs,
+    GF_LAUNCH(xfinalize_k<1>, dim3(cdiv(pairs, kThreads), g.KK), dim3(kThreads), 0, st, a.part, g_w, pairs,
                        g.KK, p.nz);
   return hipGetLastError();
 }
@@ -958,18 +958,18 @@ hipError_t dgrad_t(const Geom& g, const XGeo& q, const XPlan& p, const void* g_y
   constexpr int VE = Mma<T>::VE;
   if (g.Ci > 64 && t128 >= 400) {
     a.d_nck = FastDiv((uint32_t)cdiv(g.Co, 8 * VE));
-    hipLaunchKernelGGL((xdgrad_k<T, 4, 4, 8, 1>), dim3(cdiv(a.Jp, 128), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
+    GF_LAUNCH((xdgrad_k<T, 4, 4, 8, 1>), dim3(cdiv(a.Jp, 128), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
   } else if (g.Ci > 64) {
     a.d_nck = FastDiv((uint32_t)cdiv(g.Co, 16 * VE));
-    hipLaunchKernelGGL((xdgrad_k<T, 4, 2, 16, 1>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
+    GF_LAUNCH((xdgrad_k<T, 4, 2, 16, 1>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 128), q.nph), dim3(kThreads), 0, st, a);
   } else {
     a.d_nck = FastDiv((uint32_t)cdiv(g.Co, 16 * VE));
-    hipLaunchKernelGGL((xdgrad_k<T, 2, 2, 16, 1>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 64), q.nph), dim3(kThreads), 0, st, a);
+    GF_LAUNCH((xdgrad_k<T, 2, 2, 16, 1>), dim3(cdiv(a.Jp, 64), cdiv(g.Ci, 64), q.nph), dim3(kThreads), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || g.s == 1) return e;
   const long tot = (long)g.N * g.Ci * g.H * g.W;
-  hipLaunchKernelGGL(interleave_k<T>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
+  GF_LAUNCH(interleave_k<T>, dim3(cdiv(tot, kThreads)), dim3(kThreads), 0, st,
                      reinterpret_cast<const T*>(wsb + p.off_gxq), static_cast<T*>(g_x), g.N * g.Ci, g.H, g.W,
                      q.Hq, q.Wq, g.s);
   return hipGetLastError();
@@ -1027,7 +1027,7 @@ hipError_t plain_wgrad_t(const Geom& g, const void* x_u, const void* gy_u, float
   a.d_tx = FastDiv((uint32_t)a.tx);
   *nz_out = a.nz;
   const dim3 grid(a.xcd_slabs ? 8 * a.R * cdiv(a.nz, 8) : a.R * a.nz);
-  hipLaunchKernelGGL((xwgrad_k<T, 4, 4, 16>), grid, dim3(kThreads), 0, st, a);
+  GF_LAUNCH((xwgrad_k<T, 4, 4, 16>), grid, dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 

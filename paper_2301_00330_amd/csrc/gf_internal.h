@@ -21,6 +21,16 @@ struct Geom {
 
 gf_status make_geom(const gf_conv_desc* d, Geom* g);
 
+// Launch observer (gf_set_launch_observer): told, on the host, right before (phase 0) and right
+// after (phase 1) every kernel the library enqueues.  No observer set: one relaxed load per launch.
+void observe_launch(const char* kernel_expr, int phase, hipStream_t st);
+#define GF_LAUNCH(kern, grid, block, shmem, st, ...)                   \
+  do {                                                                 \
+    ::gf::observe_launch(#kern, 0, st);                                \
+    hipLaunchKernelGGL(kern, grid, block, shmem, st, __VA_ARGS__);     \
+    ::gf::observe_launch(#kern, 1, st);                                \
+  } while (0)
+
 typedef __bf16 bf16_t;
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
@@ -215,6 +225,15 @@ hipError_t launch_dw_chain(const Geom& g, const void* x_u, const void* gy_u, con
                            void* g_xu, const void* mask_u, hipStream_t st);
 // true when the input-gradient GEMM can replicate its tile to [N, Ci, H, W] itself (pass `full`)
 bool mfma_dgrad_writes_full(const Geom& g);
+
+// Dense layers on small maps (gf_dense.hip): filter / relayout launch + one launch for both products with
+// the slab sums folded in.  src: g_y (src_is_gy) or the filtered gradient gy_u; g_w or g_x may be null
+// to skip that gradient; gy_u_out (nullable) receives the filtered gradient in the caller's layout.
+bool dense_ok(const Geom& g);
+size_t ws_dense(const Geom& g, bool want_w, bool want_d);
+hipError_t launch_dense(const Geom& g, const void* src, bool src_is_gy, const void* x_u, const void* w,
+                        void* gy_u_out, float* g_w, void* g_x, bool reduced, const void* mask_u, void* ws,
+                        hipStream_t st);
 
 // One-pass filtered backward of a depthwise stride-1 layer (gf_fused.hip): filter, weight
 // gradient partials ([nz, C] in `part`, to be finalized) and input gradient.

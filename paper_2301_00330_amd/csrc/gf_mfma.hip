@@ -889,9 +889,9 @@ hipError_t wgrad_launch(WgradMfmaArgs& a, int nz, bool vec, hipStream_t st) {
   constexpr int BM = WM * TM * 16, BN = WN * TN * 16;
   dim3 grid(cdiv(a.Ci, BN), cdiv(a.Co, BM), nz);
   if (vec)
-    hipLaunchKernelGGL((wgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((wgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL((wgrad_mfma_k<T, TM, TN, WM, WN, false>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((wgrad_mfma_k<T, TM, TN, WM, WN, false>), grid, dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -927,9 +927,9 @@ hipError_t dgrad_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   if (!a.planes_mode && !a.flatb) dgrad_column_tiles<T>(a, BN, BM);
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, BM), 1);
   if (vec)
-    hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((dgrad_mfma_k<T, TM, TN, WM, WN, true>), grid, dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL((dgrad_mfma_k<T, TM, TN, WM, WN, false>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((dgrad_mfma_k<T, TM, TN, WM, WN, false>), grid, dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -1032,9 +1032,9 @@ hipError_t dgrad_ksplit_launch(DgradMfmaArgs& a, bool vec, hipStream_t st) {
   if (!a.planes_mode) dgrad_column_tiles<T>(a, BN, 32);
   dim3 grid(cdiv(a.Jtot, a.cols_per_tile), cdiv(a.Ci, 32), 1);
   if (vec)
-    hipLaunchKernelGGL((dgrad_ksplit_k<T, BN, true>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((dgrad_ksplit_k<T, BN, true>), grid, dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL((dgrad_ksplit_k<T, BN, false>), grid, dim3(kThreads), 0, st, a);
+    GF_LAUNCH((dgrad_ksplit_k<T, BN, false>), grid, dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -1076,7 +1076,7 @@ static hipError_t kernel_sum_if_needed(const Geom& g, const void* w, void* wsum_
   *wt = static_cast<const T*>(w);
   if (g.KK == 1) return hipSuccess;
   const int pairs = g.Co * g.Ci;
-  hipLaunchKernelGGL(kernel_sum_t_k<T>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st,
+  GF_LAUNCH(kernel_sum_t_k<T>, dim3(cdiv(pairs, kThreads)), dim3(kThreads), 0, st,
                      static_cast<const T*>(w), static_cast<T*>(wsum_t), pairs, g.KK);
   *wt = static_cast<const T*>(wsum_t);
   return hipGetLastError();
@@ -1199,18 +1199,18 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
     gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
     const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 32);
     if (bn == 32)
-      hipLaunchKernelGGL((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 32>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+      GF_LAUNCH((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 32>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     else
-      hipLaunchKernelGGL((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 64>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+      GF_LAUNCH((s3s4_ksplit_k<T, WTM, WTN, WWM, WWN, 64>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     return hipGetLastError();
   }
   if (da.planes_mode || da.flatb) {  // column tiles of whole images
     gr.dgx = cdiv(da.Jtot, da.cols_per_tile);
     const int grid = gr.nw + gr.dgx * cdiv(g.Ci, 64);
     if (vec)
-      hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+      GF_LAUNCH((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     else
-      hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
+      GF_LAUNCH((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, true>), dim3(grid), dim3(kThreads), 0, st, wa, da, gr);
     return hipGetLastError();
   }
   dgrad_column_tiles<T>(da, g.Ci <= 32 ? 128 : 64, g.Ci <= 32 ? 32 : 64);
@@ -1218,11 +1218,11 @@ static hipError_t s3s4_launch(const Geom& g, WgradMfmaArgs& wa, DgradMfmaArgs& d
   const int nd = gr.dgx * cdiv(g.Ci, g.Ci <= 32 ? 32 : 64);
   const dim3 grid(gr.nw + nd), block(kThreads);
   if (g.Ci <= 32) {
-    if (vec) hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, true, false>), grid, block, 0, st, wa, da, gr);
-    else hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, false, false>), grid, block, 0, st, wa, da, gr);
+    if (vec) GF_LAUNCH((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, true, false>), grid, block, 0, st, wa, da, gr);
+    else GF_LAUNCH((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 1, 4, false, false>), grid, block, 0, st, wa, da, gr);
   } else {
-    if (vec) hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, false>), grid, block, 0, st, wa, da, gr);
-    else hipLaunchKernelGGL((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, false>), grid, block, 0, st, wa, da, gr);
+    if (vec) GF_LAUNCH((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, true, false>), grid, block, 0, st, wa, da, gr);
+    else GF_LAUNCH((s3s4_mfma_k<T, WTM, WTN, WWM, WWN, 2, 2, 2, 2, false, false>), grid, block, 0, st, wa, da, gr);
   }
   return hipGetLastError();
 }

@@ -368,9 +368,9 @@ hipError_t launch_x(OnePassArgs& a, int xb, hipStream_t st) {
   const int tiles = cdiv(a.units, a.prt);
   const size_t lds = (size_t)Layout<T, CIT, chunk_of<T, Q>()>::bytes(a.nchunks);
   const dim3 grid(tiles), block(kThreads);
-  if (xb == 16) hipLaunchKernelGGL((onepass_k<T, Q, CIT, 16>), grid, block, lds, st, a);
-  else if (xb == 8) hipLaunchKernelGGL((onepass_k<T, Q, CIT, 8>), grid, block, lds, st, a);
-  else hipLaunchKernelGGL((onepass_k<T, Q, CIT, 4>), grid, block, lds, st, a);
+  if (xb == 16) GF_LAUNCH((onepass_k<T, Q, CIT, 16>), grid, block, lds, st, a);
+  else if (xb == 8) GF_LAUNCH((onepass_k<T, Q, CIT, 8>), grid, block, lds, st, a);
+  else GF_LAUNCH((onepass_k<T, Q, CIT, 4>), grid, block, lds, st, a);
   return hipGetLastError();
 }
 

@@ -550,13 +550,13 @@ static hipError_t q8_dgrad_mfma_launch(const Geom& g, const int8_t* gy_q, const 
   a.d_wp = FastDiv((uint32_t)g.Wp);
   const dim3 grid(cdiv(a.Jtot, 64), cdiv(g.Ci, 64)), block(kThreads);
   if (g.P % 16 == 0) {
-    if (rx == 2) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 2, true>), grid, block, 0, st, a);
-    else if (rx == 4) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 4, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 0, true>), grid, block, 0, st, a);
+    if (rx == 2) GF_LAUNCH((q8_dgrad_mfma_k<D, 2, true>), grid, block, 0, st, a);
+    else if (rx == 4) GF_LAUNCH((q8_dgrad_mfma_k<D, 4, true>), grid, block, 0, st, a);
+    else GF_LAUNCH((q8_dgrad_mfma_k<D, 0, true>), grid, block, 0, st, a);
   } else {
-    if (rx == 2) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 2, false>), grid, block, 0, st, a);
-    else if (rx == 4) hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 4, false>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((q8_dgrad_mfma_k<D, 0, false>), grid, block, 0, st, a);
+    if (rx == 2) GF_LAUNCH((q8_dgrad_mfma_k<D, 2, false>), grid, block, 0, st, a);
+    else if (rx == 4) GF_LAUNCH((q8_dgrad_mfma_k<D, 4, false>), grid, block, 0, st, a);
+    else GF_LAUNCH((q8_dgrad_mfma_k<D, 0, false>), grid, block, 0, st, a);
   }
   return hipGetLastError();
 }
@@ -564,10 +564,10 @@ static hipError_t q8_dgrad_mfma_launch(const Geom& g, const int8_t* gy_q, const 
 template <class D, int RX>
 static hipError_t q8_tile_launch(Q8DgradTileArgs& a, int ct, bool split, hipStream_t st) {
   const dim3 block(kThreads), grid(cdiv((long)a.total * (split ? 4 : 1), kThreads));
-  if (ct == 4 && split) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 4, 4, RX>), grid, block, 0, st, a);
-  else if (ct == 4) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 4, 1, RX>), grid, block, 0, st, a);
-  else if (split) hipLaunchKernelGGL((q8_dgrad_tile_k<D, 1, 4, RX>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((q8_dgrad_tile_k<D, 1, 1, RX>), grid, block, 0, st, a);
+  if (ct == 4 && split) GF_LAUNCH((q8_dgrad_tile_k<D, 4, 4, RX>), grid, block, 0, st, a);
+  else if (ct == 4) GF_LAUNCH((q8_dgrad_tile_k<D, 4, 1, RX>), grid, block, 0, st, a);
+  else if (split) GF_LAUNCH((q8_dgrad_tile_k<D, 1, 4, RX>), grid, block, 0, st, a);
+  else GF_LAUNCH((q8_dgrad_tile_k<D, 1, 1, RX>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 
@@ -606,7 +606,7 @@ static hipError_t q8_dgrad_launch(const Geom& g, const int8_t* gy_q, const int8_
   a.scale = fscale;
   a.d_p = FastDiv((uint32_t)g.P);
   a.d_ci = FastDiv((uint32_t)g.Ci);
-  hipLaunchKernelGGL(q8_dgrad_k<D>, dim3(cdiv(a.total, kThreads)), dim3(kThreads), 0, st, a);
+  GF_LAUNCH(q8_dgrad_k<D>, dim3(cdiv(a.total, kThreads)), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -619,9 +619,9 @@ hipError_t launch_kernel_sum_q8(const Geom& g, const void* w, float inv_delta, i
   const int pairs = g.Co * g.Cg;
   const dim3 grid(cdiv(pairs, kThreads)), block(kThreads);
   if (g.dtype == GF_BF16)
-    hipLaunchKernelGGL(kernel_sum_q8_k<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(w), w_q, pairs, g.KK, inv_delta);
+    GF_LAUNCH(kernel_sum_q8_k<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(w), w_q, pairs, g.KK, inv_delta);
   else
-    hipLaunchKernelGGL(kernel_sum_q8_k<float>, grid, block, 0, st, static_cast<const float*>(w), w_q, pairs, g.KK, inv_delta);
+    GF_LAUNCH(kernel_sum_q8_k<float>, grid, block, 0, st, static_cast<const float*>(w), w_q, pairs, g.KK, inv_delta);
   return hipGetLastError();
 }
 
@@ -658,12 +658,12 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
     const int nz = q8_wgrad_splits(g, &a.chunks_per_z);
     a.d_p = FastDiv((uint32_t)g.P);
     const dim3 grid(cdiv(g.Ci, 64), cdiv(g.Co, 64), nz);
-    if (g.P % 16 == 0) hipLaunchKernelGGL(q8_wgrad_mfma_k<true>, grid, dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL(q8_wgrad_mfma_k<false>, grid, dim3(kThreads), 0, st, a);
+    if (g.P % 16 == 0) GF_LAUNCH(q8_wgrad_mfma_k<true>, grid, dim3(kThreads), 0, st, a);
+    else GF_LAUNCH(q8_wgrad_mfma_k<false>, grid, dim3(kThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int pairs = g.Co * g.Ci;
-    hipLaunchKernelGGL(q8_finalize_k, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, a.part, g_w, pairs, nz,
+    GF_LAUNCH(q8_finalize_k, dim3(cdiv(pairs, kThreads / 16)), dim3(kThreads), 0, st, a.part, g_w, pairs, nz,
                        g.KK, fscale);
     return hipGetLastError();
   }
@@ -673,8 +673,8 @@ hipError_t launch_bwd_weight_q8(const Geom& g, const int8_t* x_q, const int8_t* 
   a.scale = fscale;
   const bool v4 = g.P % 4 == 0;
   a.d_per = FastDiv((uint32_t)(v4 ? g.P / 4 : g.P));
-  if (v4) hipLaunchKernelGGL(q8_wgrad_pair_k<true>, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
-  else hipLaunchKernelGGL(q8_wgrad_pair_k<false>, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
+  if (v4) GF_LAUNCH(q8_wgrad_pair_k<true>, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
+  else GF_LAUNCH(q8_wgrad_pair_k<false>, dim3(g.Co * g.Cg), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }
 

@@ -393,7 +393,7 @@ hipError_t launch_rows(ReduceArgs& a, hipStream_t st, int* nblocks) {
   const int blocks = cdiv(a.total_items, kThreads * U);
   a.ks_block0 = blocks;
   // the kernel-sum side job (plain mode only) runs in extra blocks at the end of the grid
-  hipLaunchKernelGGL((patch_reduce_rows<T, Q, U, MODE>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+  GF_LAUNCH((patch_reduce_rows<T, Q, U, MODE>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
   *nblocks = blocks;
   return hipGetLastError();
 }
@@ -422,7 +422,7 @@ hipError_t launch_mode(ReduceArgs& a, hipStream_t st, int* nblocks) {
     int blocks = (int)((nout + kThreads - 1) / kThreads);
     if (blocks > 65536) blocks = 65536;
     a.ks_block0 = blocks;
-    hipLaunchKernelGGL((patch_reduce_direct<T, MODE>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
+    GF_LAUNCH((patch_reduce_direct<T, MODE>), dim3(blocks + cdiv(a.ks_pairs, kThreads)), dim3(kThreads), 0, st, a);
     *nblocks = blocks;
     return hipGetLastError();
   }
@@ -439,13 +439,13 @@ hipError_t launch_mode(ReduceArgs& a, hipStream_t st, int* nblocks) {
   *nblocks = blocks;
   const dim3 grid(blocks + cdiv(a.ks_pairs, kThreads));
   if (a.q == 2)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 2, MODE>), grid, dim3(kThreads), lds, st, a);
+    GF_LAUNCH((patch_reduce_lds<T, 2, MODE>), grid, dim3(kThreads), lds, st, a);
   else if (a.q == 4)
-    hipLaunchKernelGGL((patch_reduce_lds<T, 4, MODE>), grid, dim3(kThreads), lds, st, a);
+    GF_LAUNCH((patch_reduce_lds<T, 4, MODE>), grid, dim3(kThreads), lds, st, a);
   else if (MODE == kPlain && a.q == 8)   // the plain mode also has an unrolled variant for q = 8
-    hipLaunchKernelGGL((patch_reduce_lds<T, MODE == kPlain ? 8 : 0, MODE>), grid, dim3(kThreads), lds, st, a);
+    GF_LAUNCH((patch_reduce_lds<T, MODE == kPlain ? 8 : 0, MODE>), grid, dim3(kThreads), lds, st, a);
   else
-    hipLaunchKernelGGL((patch_reduce_lds<T, 0, MODE>), grid, dim3(kThreads), lds, st, a);
+    GF_LAUNCH((patch_reduce_lds<T, 0, MODE>), grid, dim3(kThreads), lds, st, a);
   return hipGetLastError();
 }
 
@@ -483,7 +483,7 @@ hipError_t launch_filter_stats(const void* g_y, void* gy_u, long planes, int H, 
   a.d_wp = FastDiv((uint32_t)a.Wp);
   hipError_t e = dtype == GF_BF16 ? launch_t<bf16_t>(a, st, &blocks) : launch_t<float>(a, st, &blocks);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(stats_final_k, dim3(1), dim3(kFinalThreads), 0, st, a.stats_part, blocks, stats);
+  GF_LAUNCH(stats_final_k, dim3(1), dim3(kFinalThreads), 0, st, a.stats_part, blocks, stats);
   return hipGetLastError();
 }
 
@@ -496,9 +496,9 @@ __global__ __launch_bounds__(kThreads) void mask_mul_k(T* dst, const T* m, long 
 hipError_t launch_mask_mul(void* dst, const void* m, long n, int dtype, hipStream_t st) {
   const dim3 grid((unsigned)((n + kThreads - 1) / kThreads)), block(kThreads);
   if (dtype == GF_BF16)
-    hipLaunchKernelGGL(mask_mul_k<bf16_t>, grid, block, 0, st, static_cast<bf16_t*>(dst), static_cast<const bf16_t*>(m), n);
+    GF_LAUNCH(mask_mul_k<bf16_t>, grid, block, 0, st, static_cast<bf16_t*>(dst), static_cast<const bf16_t*>(m), n);
   else
-    hipLaunchKernelGGL(mask_mul_k<float>, grid, block, 0, st, static_cast<float*>(dst), static_cast<const float*>(m), n);
+    GF_LAUNCH(mask_mul_k<float>, grid, block, 0, st, static_cast<float*>(dst), static_cast<const float*>(m), n);
   return hipGetLastError();
 }
 
@@ -551,6 +551,12 @@ hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, in
   a.d_wp = FastDiv((uint32_t)a.Wp);
   if (dtype == GF_BF16) return launch_t<bf16_t>(a, st, &blocks);
   return launch_t<float>(a, st, &blocks);
+}
+
+// true when launch_patch_reduce sums a patch in the order of the register kernel (columns first)
+bool patch_reduce_uses_rows(int dtype, long planes, int H, int W, int q) {
+  const bool ok = dtype == GF_BF16 ? rows_ok<bf16_t>(W, q) : rows_ok<float>(W, q);
+  return ok && planes * cdiv(H, q) * (W / 4) < 2147483647L;
 }
 
 }  // namespace gf

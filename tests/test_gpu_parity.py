@@ -1325,3 +1325,27 @@ def test_repeat_runs_are_bit_identical():
         b = run_layer(d, x, w, gy)
         for u, v in zip(a, b):
             assert torch.equal(u, v)
+
+
+# ---------------------------------------------------------------------------
+# the launch observer (tracing aid)
+# ---------------------------------------------------------------------------
+def test_launch_observer_lists_the_kernels_of_a_call():
+    """gf_set_launch_observer reports every kernel a call enqueues, before and after the launch, and
+    nothing once it is removed.  A dense layer on a small map is two launches: filter + relayout,
+    then both contractions with their slab sums."""
+    d = mk(4, 32, 48, 14, 14, K=3, p=1, r=2, dtype="bf16")
+    x_u = randn((4, 32, 7, 7), 1, "bf16").cuda()
+    w = randn((48, 32, 3, 3), 2, "bf16", scale=0.1).cuda()
+    gy = randn((4, 48, 14, 14), 3, "bf16").cuda()
+    seen = []
+    B.gf_set_launch_observer(lambda name, phase, stream: seen.append((name, phase)))
+    try:
+        T.conv_bwd_filtered(d, gy, x_u, w)
+    finally:
+        B.gf_set_launch_observer(None)
+    torch.cuda.synchronize()
+    assert seen == [("dense_prep_k", 0), ("dense_prep_k", 1), ("dense_gemm_k", 0), ("dense_gemm_k", 1)]
+    n = len(seen)
+    T.conv_bwd_filtered(d, gy, x_u, w)
+    assert len(seen) == n
