@@ -1332,12 +1332,12 @@ def test_repeat_runs_are_bit_identical():
 # ---------------------------------------------------------------------------
 def test_launch_observer_lists_the_kernels_of_a_call():
     """gf_set_launch_observer reports every kernel a call enqueues, before and after the launch, and
-    nothing once it is removed.  A dense layer on a small map is two launches: filter + relayout,
+    nothing once it is removed.  A dense fp32 layer on a small map is two launches: filter + relayout,
     then both contractions with their slab sums."""
-    d = mk(4, 32, 48, 14, 14, K=3, p=1, r=2, dtype="bf16")
-    x_u = randn((4, 32, 7, 7), 1, "bf16").cuda()
-    w = randn((48, 32, 3, 3), 2, "bf16", scale=0.1).cuda()
-    gy = randn((4, 48, 14, 14), 3, "bf16").cuda()
+    d = mk(4, 32, 48, 14, 14, K=3, p=1, r=2, dtype="f32")
+    x_u = randn((4, 32, 7, 7), 1, "f32").cuda()
+    w = randn((48, 32, 3, 3), 2, "f32", scale=0.1).cuda()
+    gy = randn((4, 48, 14, 14), 3, "f32").cuda()
     seen = []
     B.gf_set_launch_observer(lambda name, phase, stream: seen.append((name, phase)))
     try:
