@@ -1,15 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the gradient-filtered conv backward hot path on one MI355X.
 
-A "step" is one pass of the whole filtered path over one batch of the workload:
-for every conv layer of the block, the forward-time activation pooling, the
-gradient filter, the kernel sum, the filtered weight gradient and the filtered
-input gradient.  The default workload is the MobileNetV2 inverted-residual block
-backward (N=32, 56x56, expand 24->144, depthwise 3x3, project 144->24, r=2).
-Inputs are seeded synthetic tensors resident in HBM before the timed region; the
-buffer sets rotate so that no step finds its tensors in the last-level cache.
+A "step" is one pass of the whole filtered path over one batch of a workload:
+for every conv layer, the forward-time activation pooling (gf_pool_activation),
+then the gradient filter, the kernel sum, the filtered weight gradient and the
+filtered input gradient in one call (gf_conv_bwd_filtered).  The default run
+times ALL five benchmark configurations (each dtype and patch size of each) and
+prints one JSON line: the headline is the largest workload (configuration 5:
+the last conv layers of a MobileNetV2-shaped net, N=128, fp32, r=2), the others
+are listed under "per_config".  Inputs are seeded synthetic tensors resident in
+HBM before the timed region; buffer sets rotate so that no step finds its
+tensors in the last-level cache.
 
-Prints one JSON line (see the keys below); everything else goes to stderr.
+Everything except the JSON line goes to stderr.
 """
 from __future__ import annotations
 
@@ -23,8 +26,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
-MFMA_BF16_PEAK_TFLOPS = 2500.0
-MFMA_F32_PEAK_TFLOPS = 157.3
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense matrix-core peaks
+HEADLINE = (5, "f32", 2)
 
 
 def log(*a):
@@ -36,81 +39,31 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--dtype", choices=["bf16", "f32"], default="f32",
-                    help="storage dtype of the headline number (fp32 is the paper's precision); the other\n"
-                         "dtype of the configuration is measured too and reported under 'other_dtype'")
-    ap.add_argument("--single-dtype", action="store_true", help="skip the second dtype")
-    ap.add_argument("--config", type=int, default=2, help="workload: configuration id in workloads.CONFIGS")
-    ap.add_argument("--r", type=int, default=0, help="patch size (default: the configuration's first)")
+    ap.add_argument("--configs", default="5,1,2,3,4",
+                    help="configuration ids to time (the first (config, dtype, r) of the list that matches the\n"
+                         "headline workload (5, f32, 2) is the headline; without it the first one measured is)")
+    ap.add_argument("--only", default="", help="CFG:DTYPE:R -- time this one combination only")
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (default: enough for > 768 MB)")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches only (no HIP-graph replays)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-exact", action="store_true")
+    ap.add_argument("--no-exact", action="store_true", help="skip vanilla BP at the same shapes (speed-up denominator)")
+    ap.add_argument("--miopen", action="store_true", help="also time torch's conv backward (MIOpen) as context")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the chained block (configuration 2) and the step on 8-bit codes")
+    ap.add_argument("--step-only", default="",
+                    help="CFG:DTYPE:R -- run only warm-up + steps of that step with plain launches and print a\n"
+                         "short JSON line (the command the rocprofv3 summaries under profiles/ are made with)")
     ap.add_argument("--pmc-calibration", action="store_true",
-                    help="end with five plain 256 MiB device copies (a kernel of known traffic, used to\n"
-                         "scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    ap.add_argument("--table", action="store_true", help="also print a per-layer table to stderr")
+                    help="with --step-only: end with five plain 256 MiB device copies (a kernel of known traffic,\n"
+                         "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark: what this GPU sustains in plain probes -- streaming reads,\n"
                          "writes and copies (HBM) and register-only loops of matrix instructions (MFMA)")
     ap.add_argument("--fig3", action="store_true",
                     help="instead of the benchmark: the three cost lines of the paper's Fig. 3 (vanilla BP, fewer\n"
                          "unique elements only, gradient filtering) as measured time on the layer of its footnote")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="f32", help="storage type for --fig3")
     return ap.parse_args()
-
-
-class LayerBufs:
-    """Device tensors of one layer in one buffer set, plus raw pointers for the C ABI."""
-
-    def __init__(self, T, B, d, x, w, gy, torch):
-        s = T.shapes(d)
-        self.d = d
-        self.x, self.w, self.gy = x.cuda(), w.cuda(), gy.cuda()
-        dt = self.x.dtype
-        self.x_u = torch.empty(s["x_u"], dtype=dt, device="cuda")
-        self.gy_u = torch.empty(s["gy_u"], dtype=dt, device="cuda")
-        self.g_w = torch.empty(s["w"], dtype=torch.float32, device="cuda")
-        self.g_x = torch.empty(s["x"], dtype=dt, device="cuda")
-        self.ws_w_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT)
-        self.ws_i_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_INPUT)
-        self.ws_e_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_EXACT)
-        self.ws_w = torch.empty(max(self.ws_w_bytes, 256), dtype=torch.uint8, device="cuda")
-        self.ws_i = torch.empty(max(self.ws_i_bytes, 256), dtype=torch.uint8, device="cuda")
-        self.ws_e = torch.empty(max(self.ws_e_bytes, 256), dtype=torch.uint8, device="cuda")
-        self.ws_f_bytes = B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED)
-        self.ws_f = torch.empty(max(self.ws_f_bytes, 256), dtype=torch.uint8, device="cuda")
-        self.ws_s = torch.empty(max(B.gf_workspace_bytes(d, B.GF_OP_FILTER_SNR), 256), dtype=torch.uint8, device="cuda")
-        self.stats = torch.zeros(2, dtype=torch.float64, device="cuda")
-        self.e_w = None
-        self.e_x = None
-        self.g_xu = None   # reduced input gradient (chained mode)
-        self.ws_c = None
-
-    def nbytes(self):
-        ts = [self.x, self.w, self.gy, self.x_u, self.gy_u, self.g_w, self.g_x, self.ws_w, self.ws_i, self.ws_f]
-        return sum(t.numel() * t.element_size() for t in ts)
-
-
-def main():
-    args = parse()
-    if args.gpus != 1:
-        log("bench.py: this build measures ONE GPU only (the path has no multi-GPU part); "
-            "run with --gpus 1")
-        sys.exit(2)
-    if args.fig3:
-        print(json.dumps(fig3(args)), flush=True)
-        return
-    if args.ceilings:
-        print(json.dumps(ceilings()), flush=True)
-        return
-    out = measure(args, args.dtype, full=True)
-    from paper_2301_00330_amd import workloads as WL
-    others = [d for d in WL.CONFIGS[args.config].dtypes if d != out["dtype"]]
-    if others and not args.single_dtype:
-        o = measure(args, others[0], full=False)
-        out["other_dtype"] = {k: o[k] for k in ("dtype", "value", "unit", "ms_per_step", "roofline", "per_layer",
-                                                "chained_block", "q8_block") if k in o}
-    print(json.dumps(out), flush=True)
 
 
 def ceilings():
@@ -280,7 +233,168 @@ def fig3(args):
             "lines": rows}
 
 
-def measure(args, dtype, full):
+
+class LayerBufs:
+    """Device tensors of one layer in one buffer set, plus raw pointers for the C ABI."""
+
+    def __init__(self, T, B, d, x, w, gy, torch):
+        s = T.shapes(d)
+        self.d = d
+        self.x, self.w, self.gy = x.cuda(), w.cuda(), gy.cuda()
+        dt = self.x.dtype
+        self.x_u = torch.empty(s["x_u"], dtype=dt, device="cuda")
+        self.g_w = torch.empty(s["w"], dtype=torch.float32, device="cuda")
+        self.g_x = torch.empty(s["x"], dtype=dt, device="cuda")
+        self.ws_f = torch.empty(max(B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED), 256), dtype=torch.uint8, device="cuda")
+        self.ws_e = None
+        self.e_w = self.e_x = None
+
+    def nbytes(self):
+        ts = [self.x, self.w, self.gy, self.x_u, self.g_w, self.g_x, self.ws_f]
+        return sum(t.numel() * t.element_size() for t in ts)
+
+
+# Which algorithmic quantities a kernel of the library moves, by name (the names the launch observer
+# reports).  Values: keys of layer_costs() below; "mfma" marks the contraction kernels.
+KERNEL_RULES = (
+    ("dense_gemm_k", ("bytes_bwd_weight", "bytes_bwd_input"), True),
+    ("s3s4_", ("bytes_bwd_weight", "bytes_bwd_input"), True),
+    ("wgrad_", ("bytes_bwd_weight",), True), ("plain_wgrad", ("bytes_bwd_weight",), True),
+    ("dgrad_", ("bytes_bwd_input",), True),
+    ("dense_prep_k", ("bytes_filter",), False),
+    ("onepass_k", ("bytes_fused",), False), ("dw_fused", ("bytes_fused",), False),
+    ("dw_dot", ("bytes_bwd_weight",), False), ("expand", ("bytes_bwd_input",), False),
+    ("patch_reduce", ("bytes_reduce",), False),
+)
+
+
+def layer_costs(B, d):
+    """Algorithmic HBM bytes and FLOPs of one layer: gf_cost_model's figures (each tensor read or written
+    once by the step that owns it), plus `bytes_fused`, what a single pass over the layer must move: read
+    g_y, x_u and the kernel, write g_x and g_w."""
+    c = B.gf_cost_model(d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    b = 2 if d.dtype == B.GF_BF16 else 4
+    wel = d.C_out * (d.C_in // d.groups) * d.K_h * d.K_w
+    c["bytes_fused"] = (b * d.N * (d.C_out * Hy * Wy + d.C_in * Hp * Wp + d.C_in * d.H_in * d.W_in) + (b + 4) * wel)
+    c["bytes_backward"] = c["bytes_filter"] + c["bytes_bwd_weight"] + c["bytes_bwd_input"]
+    c["flops_backward"] = c["flops_bwd_weight"] + c["flops_bwd_input"]
+    return c
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log("bench.py: this build measures ONE GPU only (the path has no multi-GPU part); "
+            "run with --gpus 1")
+        sys.exit(2)
+    if args.fig3:
+        print(json.dumps(fig3(args)), flush=True)
+        return
+    if args.ceilings:
+        print(json.dumps(ceilings()), flush=True)
+        return
+    from paper_2301_00330_amd import workloads as WL
+    if args.step_only:
+        c, dt, r = args.step_only.split(":")
+        print(json.dumps(step_only(args, int(c), dt, int(r))), flush=True)
+        return
+    if args.only:
+        c, dt, r = args.only.split(":")
+        combos = [(int(c), dt, int(r))]
+    else:
+        combos = []
+        for c in (int(v) for v in args.configs.split(",")):
+            cfg = WL.CONFIGS[c]
+            combos += [(c, dt, r) for dt in cfg.dtypes for r in cfg.rs]
+        if HEADLINE in combos:   # headline first
+            combos.remove(HEADLINE)
+            combos.insert(0, HEADLINE)
+    t_start = time.time()
+    results = []
+    exact_cache = {}
+    for (c, dt, r) in combos:
+        results.append(measure(args, c, dt, r, exact_cache))
+        log(f"  [{time.time() - t_start:6.1f} s] cfg{c} {dt} r={r}: {results[-1]['ms_per_step'] * 1e3:.1f} us per step, "
+            f"{results[-1]['images_per_s']:.0f} images/s, step at {100 * results[-1]['step_roofline']['frac']:.0f} % of HBM peak, "
+            f"dominant kernel {results[-1]['roofline']['kernel']} at {100 * results[-1]['roofline']['frac']:.0f} % of its "
+            f"{results[-1]['roofline']['bound']} peak")
+    head = results[0]
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(head["cfg"], head["dtype"], head["r"])
+    out = {
+        "metric": "filtered_conv_backward_images_per_sec", "value": head["images_per_s"], "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"],
+                   "step": "for every layer: gf_pool_activation, then gf_conv_bwd_filtered (gradient filter, kernel sum, "
+                           "weight and input gradient)",
+                   "launch": head["launch"], "buffer_sets": head["buffer_sets"], "cache": "cold (rotating sets)"},
+        "roofline": head["roofline"],
+        "step_roofline": head["step_roofline"],
+        "cpu_baseline": cpu,
+        "speedup_vs_exact_bp": head.get("speedup_vs_exact_bp"),
+        "per_config": results,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def build_sets(args, cfg, dtype, r, torch, B, T, WL):
+    host = [WL.make_inputs(cfg, L, dtype) for L in cfg.layers]
+    descs = [T.desc_for(L, cfg.N, r, dtype) for L in cfg.layers]
+    one = [LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)]
+    set_bytes = sum(lb.nbytes() for lb in one)
+    # enough sets that (a) a step never finds its inputs in the 256 MB memory-side cache and (b) the
+    # per-call timings, which rotate over ONE layer's tensors only, do not either (>= 1 GB of the
+    # largest tensor), within 12 GB in total and 48 sets (tiny workloads stay cache-resident)
+    largest = max(max(lb.x.numel() * lb.x.element_size(), lb.gy.numel() * lb.gy.element_size()) for lb in one)
+    nsets = args.sets or min(48, max(3, int(768e6 // set_bytes) + 1,
+                                     min(int(1.0e9 // largest) + 1, max(1, int(12e9 // set_bytes)))))
+    sets = [one] + [[LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)] for _ in range(nsets - 1)]
+    return host, descs, sets, set_bytes
+
+
+def step_only(args, c, dtype, r):
+    """Warm-up + exactly --steps steps with plain launches, nothing else: the command behind the
+    rocprofv3 kernel-trace and counter summaries under profiles/."""
+    import torch
+    import paper_2301_00330_amd.binding as B
+    import paper_2301_00330_amd.torch_api as T
+    from paper_2301_00330_amd import workloads as WL
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    cfg = WL.CONFIGS[c]
+    host, descs, sets, set_bytes = build_sets(args, cfg, dtype, r, torch, B, T, WL)
+    P = B.ptr
+    s = int(torch.cuda.current_stream().cuda_stream)
+
+    def step(bufset):
+        for lb in bufset:
+            B.gf_pool_activation(lb.d, P(lb.x), P(lb.x_u), s)
+        for lb in reversed(bufset):
+            B.gf_conv_bwd_filtered(lb.d, P(lb.gy), P(lb.x_u), P(lb.w), 0, P(lb.g_w), P(lb.g_x), P(lb.ws_f), lb.ws_f.numel(), s)
+
+    for i in range(max(args.warmup, 1)):
+        step(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    return {"step_only": f"cfg{c}:{dtype}:r{r}", "steps": args.steps, "warmup": args.warmup, "launch": "eager",
+            "ms_per_step": round(ms, 5), "buffer_sets": len(sets)}
+
+
+def measure(args, c, dtype, r, exact_cache):
     import torch
     import paper_2301_00330_amd.binding as B
     import paper_2301_00330_amd.torch_api as T
@@ -289,25 +403,11 @@ def measure(args, dtype, full):
     B.lib()  # no fallback: fail here if libgf.so is missing
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    cfg = WL.CONFIGS[args.config]
-    r = args.r or cfg.rs[0]
-    if dtype not in cfg.dtypes:
-        dtype = cfg.dtypes[0]
+    cfg = WL.CONFIGS[c]
     N = cfg.N
     layers = list(cfg.layers)
-
-    # ---- inputs: seeded on the host, copied once into several HBM-resident buffer sets ----
-    host = [WL.make_inputs(cfg, L, dtype) for L in layers]
-    descs = [T.desc_for(L, N, r, dtype) for L in layers]
-    one = [LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)]
-    set_bytes = sum(lb.nbytes() for lb in one)
-    # enough sets that (a) a step never finds its inputs in the 256 MB memory-side cache and (b) the
-    # per-stage timings, which rotate over ONE layer's tensors only, do not either (>= 1 GB of the
-    # largest tensor), within 12 GB in total and 48 sets (tiny workloads stay cache-resident)
-    largest = max(max(lb.x.numel() * lb.x.element_size(), lb.gy.numel() * lb.gy.element_size()) for lb in one)
-    nsets = args.sets or min(48, max(3, int(768e6 // set_bytes) + 1,
-                                     min(int(1.0e9 // largest) + 1, max(1, int(12e9 // set_bytes)))))
-    sets = [one] + [[LayerBufs(T, B, d, *h, torch) for d, h in zip(descs, host)] for _ in range(nsets - 1)]
+    host, descs, sets, set_bytes = build_sets(args, cfg, dtype, r, torch, B, T, WL)
+    nsets = len(sets)
     log(f"workload cfg{cfg.cfg_id} '{cfg.name}' N={N} r={r} dtype={dtype}: {set_bytes / 1e6:.1f} MB per set x {nsets} sets")
 
     def st():
@@ -316,11 +416,6 @@ def measure(args, dtype, full):
     P = B.ptr
 
     def enqueue_pool(lb, s): B.gf_pool_activation(lb.d, P(lb.x), P(lb.x_u), s)
-    def enqueue_filter(lb, s): B.gf_filter_grad(lb.d, P(lb.gy), P(lb.gy_u), s)
-    def enqueue_filter_snr(lb, s):
-        B.gf_filter_grad_snr(lb.d, P(lb.gy), P(lb.gy_u), P(lb.stats), P(lb.ws_s), lb.ws_s.numel(), s)
-    def enqueue_bww(lb, s): B.gf_conv_bwd_weight(lb.d, P(lb.x_u), P(lb.gy_u), P(lb.g_w), P(lb.ws_w), lb.ws_w.numel(), s)
-    def enqueue_bwi(lb, s): B.gf_conv_bwd_input(lb.d, P(lb.gy_u), P(lb.w), P(lb.g_x), False, P(lb.ws_i), lb.ws_i.numel(), s)
 
     def enqueue_fused(lb, s):   # filter + weight gradient + input gradient in one call
         B.gf_conv_bwd_filtered(lb.d, P(lb.gy), P(lb.x_u), P(lb.w), 0, P(lb.g_w), P(lb.g_x), P(lb.ws_f), lb.ws_f.numel(), s)
@@ -329,10 +424,8 @@ def measure(args, dtype, full):
         if lb.e_w is None:
             lb.e_w = torch.empty_like(lb.g_w)
             lb.e_x = torch.empty_like(lb.g_x)
+            lb.ws_e = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_EXACT), 256), dtype=torch.uint8, device="cuda")
         B.gf_conv_bwd_exact(lb.d, P(lb.x), P(lb.w), P(lb.gy), P(lb.e_w), P(lb.e_x), P(lb.ws_e), lb.ws_e.numel(), s)
-
-    STAGES = (("pool_activation", enqueue_pool), ("filter_grad", enqueue_filter),
-              ("bwd_weight", enqueue_bww), ("bwd_input", enqueue_bwi))
 
     def step(bufset):
         # the order of a training step: the activations are pooled on the way forward (first layer
@@ -365,17 +458,14 @@ def measure(args, dtype, full):
             g.replay()
         torch.cuda.synchronize()
 
-    def run_steps(k, use_graph):
+    def timed(k, use_graph):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         for i in range(k):
             if use_graph:
                 graphs[i % nsets].replay()
             else:
                 step(sets[i % nsets])
-
-    def timed(k, use_graph):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(k, use_graph)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / k
 
@@ -390,159 +480,12 @@ def measure(args, dtype, full):
 
     # ---- the timed region: exactly --steps steps ----
     ms_per_step = timed(args.steps, use_graph)
-    value = N / (ms_per_step * 1e-3)
 
-    # ---- secondary: the layers as a chain that hands reduced maps from layer to layer ----
-    chained = None
-    if cfg.chain and r > 1:
-        order = list(cfg.chain)                       # back to front
-        for bs in sets:
-            for lb in bs:
-                s_ = T.shapes(lb.d)
-                lb.g_xu = torch.empty(s_["g_x_u"], dtype=lb.x.dtype, device="cuda")
-                nb = B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_CHAINED)
-                lb.ws_c = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
-
-        clip = list(cfg.chain_clip) if cfg.chain_clip else [0.0] * len(layers)
-        for bs in sets:
-            for li, lb in enumerate(bs):
-                lb.m_u = torch.empty_like(lb.x_u) if clip[li] > 0 else None
-
-        def step_chained(bufset, masked=False):
-            s = st()
-            for li, lb in enumerate(bufset):          # forward-time S0 (with the mask fraction below a ReLU)
-                if masked and lb.m_u is not None:
-                    B.gf_pool_activation_mask(lb.d, P(lb.x), clip[li], P(lb.x_u), P(lb.m_u), s)
-                else:
-                    enqueue_pool(lb, s)
-            top = bufset[order[0]]
-            B.gf_filter_grad(top.d, P(top.gy), P(top.gy_u), s)
-            gin = top.gy_u
-            for k, li in enumerate(order):
-                lb = bufset[li]
-                last = k == len(order) - 1
-                gout = lb.g_x if last else lb.g_xu
-                m = P(lb.m_u) if (masked and not last and lb.m_u is not None) else 0
-                B.gf_conv_bwd_chained(lb.d, P(gin), P(lb.x_u), P(lb.w), P(lb.g_w), P(gout), not last, m,
-                                      P(lb.ws_c), lb.ws_c.numel(), s)
-                gin = gout
-
-        for i in range(max(args.warmup, 1)):
-            step_chained(sets[i % nsets])
-        torch.cuda.synchronize()
-        cgraphs = None
-        if not args.no_graph:
-            cgraphs = []
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                for bs in sets:
-                    g = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(g, stream=side):
-                        step_chained(bs)
-                    cgraphs.append(g)
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            for g in cgraphs:
-                g.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            if cgraphs is not None:
-                cgraphs[i % nsets].replay()
-            else:
-                step_chained(sets[i % nsets])
-        torch.cuda.synchronize()
-        cms = (time.perf_counter() - t0) * 1e3 / args.steps
-        mms = None
-        if any(c > 0 for c in clip):   # the same chain with the clipped ReLUs of the block between the layers
-            for i in range(max(args.warmup, 1)):
-                step_chained(sets[i % nsets], True)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(args.steps):
-                step_chained(sets[i % nsets], True)
-            torch.cuda.synchronize()
-            mms = (time.perf_counter() - t0) * 1e3 / args.steps
-        chained = {"ms_per_step": round(cms, 5), "value": round(N / (cms * 1e-3), 1), "unit": "images/s",
-                   "with_relu6_masks_ms_per_step": None if mms is None else round(mms, 5),
-                   "with_relu6_masks_note": "plain launches; S0 of the layers below a ReLU6 also writes the mask "
-                                            "fraction (gf_pool_activation_mask), the reduced input gradient is "
-                                            "multiplied by it inside the chained call",
-                   "note": "same layers and S0 launches, but only the top layer's g_y is filtered: "
-                           "gf_conv_bwd_chained hands the reduced input gradient of a layer to the layer below "
-                           "(valid for a stack of stride-1 convolutions with nothing between them); full "
-                           "resolution is written only at the bottom"}
-
-    # ---- secondary: the same step on signed 8-bit codes (reading of Supp. H) ----
-    q8 = None
-    if r > 1:
-        for bs in sets:
-            for lb in bs:
-                s_ = T.shapes(lb.d)
-                lb.x_q = torch.empty(s_["x_u"], dtype=torch.int8, device="cuda")
-                lb.gy_q = torch.empty(s_["gy_u"], dtype=torch.int8, device="cuda")
-                lb.w_q = torch.empty(s_["w"][:2], dtype=torch.int8, device="cuda")
-                lb.ws_q = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_WEIGHT_Q8),
-                                          B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_INPUT_Q8), 256),
-                                      dtype=torch.uint8, device="cuda")
-        # step sizes: max|.| / 127 of the reduced maps and of the kernel sum (the caller's choice; formed
-        # once here from the floating-point maps of the first buffer set, outside the timed region)
-        deltas = []
-        for lb in one:
-            enqueue_pool(lb, st())
-            enqueue_filter(lb, st())
-            torch.cuda.synchronize()
-            dx = float(lb.x_u.float().abs().max()) / 127.0
-            dg = float(lb.gy_u.float().abs().max()) / 127.0
-            dw = float(lb.w.float().sum(dim=(2, 3)).abs().max()) / 127.0
-            deltas.append((dx or 1.0, dg or 1.0, dw or 1.0))
-
-        def q8_pool(lb, s, li): B.gf_pool_activation_q8(lb.d, P(lb.x), 1.0 / deltas[li][0], P(lb.x_q), s)
-        def q8_filter(lb, s, li): B.gf_filter_grad_q8(lb.d, P(lb.gy), 1.0 / deltas[li][1], P(lb.gy_q), s)
-        def q8_ksum(lb, s, li): B.gf_kernel_sum_q8(lb.d, P(lb.w), 1.0 / deltas[li][2], P(lb.w_q), s)
-        def q8_bww(lb, s, li):
-            B.gf_conv_bwd_weight_q8(lb.d, P(lb.x_q), P(lb.gy_q), deltas[li][0] * deltas[li][1], P(lb.g_w),
-                                    P(lb.ws_q), lb.ws_q.numel(), s)
-        def q8_bwi(lb, s, li):
-            B.gf_conv_bwd_input_q8(lb.d, P(lb.gy_q), P(lb.w_q), deltas[li][1] * deltas[li][2], P(lb.g_x), False,
-                                   P(lb.ws_q), lb.ws_q.numel(), s)
-
-        def step_q8(bufset):
-            s = st()
-            for li, lb in enumerate(bufset):
-                q8_pool(lb, s, li)
-            for li in reversed(range(len(bufset))):
-                lb = bufset[li]
-                q8_filter(lb, s, li)
-                q8_ksum(lb, s, li)
-                q8_bww(lb, s, li)
-                q8_bwi(lb, s, li)
-
-        for i in range(max(args.warmup, 1)):
-            step_q8(sets[i % nsets])
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            step_q8(sets[i % nsets])
-        torch.cuda.synchronize()
-        qms = (time.perf_counter() - t0) * 1e3 / args.steps
-        q8 = {"ms_per_step": round(qms, 5), "value": round(N / (qms * 1e-3), 1), "unit": "images/s",
-              "arithmetic": "int8 codes, int32 / int64 sums, one fp32 scaling",
-              "stored_activation_bytes_per_step": int(sum(lb.x_q.numel() for lb in one)),
-              "stored_activation_bytes_per_step_float_path": int(sum(lb.x_u.numel() * lb.x_u.element_size() for lb in one)),
-              "note": "plain launches; per layer gf_pool_activation_q8, then gf_filter_grad_q8, gf_kernel_sum_q8, "
-                      "gf_conv_bwd_weight_q8 and gf_conv_bwd_input_q8 (full-resolution g_x in the storage type); "
-                      "the step is bound by reading g_y and writing g_x, which the codes do not shrink"}
-
-    # the other launch mode for comparison (eager includes the host's launch overhead)
-    other_ms = timed(args.steps, not use_graph) if graphs is not None else None
-
-    # ---- per-kernel durations with HIP events on the launch stream (cold, rotating sets) ----
-    def time_stage(fn, li, reps=8):
-        """Average GPU time of one launch of stage `fn` on layer `li`, cold: a HIP graph holding
-        one launch per buffer set (twice over) is replayed `reps` times between two events on
-        the launch stream, so neither host launch latency nor cache reuse enters the figure."""
+    # ---- per-call durations with HIP events on the launch stream (cold, rotating sets) ----
+    def time_call(fn, li, reps=6):
+        """Average GPU time of one call `fn` on layer `li`, cold: a HIP graph holding one call per
+        buffer set (twice over) is replayed between two events on the launch stream, so neither
+        host launch latency nor cache reuse enters the figure."""
         per_graph = 2 * nsets
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -566,92 +509,104 @@ def measure(args, dtype, full):
             g.replay()
         ev1.record()
         torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) * 1e3 / (reps * per_graph)   # microseconds per launch
+        return ev0.elapsed_time(ev1) * 1e3 / (reps * per_graph)   # microseconds per call
 
-    def time_isolated(fn, li, reps=6):
-        """Average duration of ONE launch, each bracketed by its own pair of events on the launch
-        stream (eager, cold buffers).  This is the figure rocprofv3 reports per dispatch; it
-        includes the launch ramp-up and drain that back-to-back launches overlap."""
-        s = st()
-        evs = []
-        for k in range(nsets):
-            fn(sets[k][li], s)
-        torch.cuda.synchronize()
-        for rep in range(reps):
-            for k in range(nsets):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                fn(sets[k][li], s)
-                e1.record()
-                evs.append((e0, e1))
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in evs) * 1e3 / len(evs)
+    cost = [layer_costs(B, d) for d in descs]
 
-    cost = [B.gf_cost_model(d) for d in descs]
-    stage_bytes = {"pool_activation": "bytes_pool", "filter_grad": "bytes_filter",
-                   "bwd_weight": "bytes_bwd_weight", "bwd_input": "bytes_bwd_input"}
+    # ---- which kernels the step launches, and how long each runs: the launch observer of the library
+    # brackets every launch of a few eager steps with a pair of events on the launch stream ----
+    trace = []            # (kind, layer, kernel, ev0, ev1)
+    cur = {"kind": None, "li": -1, "ev": None}
+
+    def observer(name, phase, stream):
+        if phase == 0:
+            cur["ev"] = torch.cuda.Event(enable_timing=True)
+            cur["ev"].record()
+        else:
+            e1 = torch.cuda.Event(enable_timing=True)
+            e1.record()
+            trace.append((cur["kind"], cur["li"], name, cur["ev"], e1))
+
+    traced_steps = 3 * nsets if nsets <= 8 else nsets
+    B.gf_set_launch_observer(observer)
+    try:
+        for i in range(traced_steps):
+            bs = sets[i % nsets]
+            s = st()
+            for li, lb in enumerate(bs):
+                cur["kind"], cur["li"] = "pool", li
+                enqueue_pool(lb, s)
+            for li in reversed(range(len(bs))):
+                cur["kind"], cur["li"] = "backward", li
+                enqueue_fused(bs[li], s)
+    finally:
+        B.gf_set_launch_observer(None)
+    torch.cuda.synchronize()
+    # what a pair of events adds to a launch: the same single-launch call, once as event pairs around eager
+    # launches (above) and once replayed back to back from a graph between two events
+    li_big = max(range(len(layers)), key=lambda i: cost[i]["bytes_pool"])
+    pool_replay_us = time_call(enqueue_pool, li_big)
+    pool_pair = [a.elapsed_time(b) * 1e3 for k, li, n, a, b in trace if k == "pool" and li == li_big]
+    pair_overhead_us = max(0.0, sum(pool_pair) / len(pool_pair) - pool_replay_us)
+    kernels = {}
+    for kind, li, name, e0, e1 in trace:
+        k = kernels.setdefault(name, {"us": 0.0, "launches": 0, "bytes": 0.0, "flops": 0.0, "mfma": False})
+        k["us"] += e0.elapsed_time(e1) * 1e3
+        k["launches"] += 1
+        for prefix, keys, mfma in KERNEL_RULES:
+            if name.startswith(prefix):
+                for key in keys:
+                    if key == "bytes_reduce":
+                        key = "bytes_pool" if kind == "pool" else "bytes_filter"
+                    k["bytes"] += cost[li][key]
+                if mfma:
+                    k["mfma"] = True
+                    k["flops"] += cost[li]["flops_backward"] if len(keys) == 2 else cost[li]["flops_bwd_weight"]
+                break
+    klist = []
+    for name, k in kernels.items():
+        avg = k["us"] / k["launches"]
+        corr = max(avg - pair_overhead_us, 0.1)
+        klist.append({"kernel": name, "launches_per_step": round(k["launches"] / traced_steps, 2),
+                      "avg_launch_us_event_pair": round(avg, 2), "avg_launch_us": round(corr, 2),
+                      "bytes_per_launch": k["bytes"] / k["launches"], "flops_per_launch": k["flops"] / k["launches"],
+                      "mfma": k["mfma"], "step_share_us": round(corr * k["launches"] / traced_steps, 2)})
+    klist.sort(key=lambda q: -q["step_share_us"])
+    dom = klist[0]
+    ridge = MFMA_PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if dom["mfma"] and dom["bytes_per_launch"] > 0 and dom["flops_per_launch"] / dom["bytes_per_launch"] > ridge:
+        ach = dom["flops_per_launch"] / dom["avg_launch_us"] * 1e-6      # TFLOP/s
+        roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_PEAK_TFLOPS[dtype],
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS[dtype], 4)}
+    else:
+        ach = dom["bytes_per_launch"] / dom["avg_launch_us"] * 1e-3      # GB/s
+        roofline = {"kernel": dom["kernel"], "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4)}
+    roofline.update({"avg_launch_us": dom["avg_launch_us"], "launches_per_step": dom["launches_per_step"],
+                     "bytes_per_launch": dom["bytes_per_launch"], "flops_per_launch": dom["flops_per_launch"],
+                     "method": "events around every launch of the step's kernels (launch observer), minus what an event "
+                               "pair adds to a launch (the same single-launch call timed as event pairs and as back-to-back "
+                               "graph replays)", "event_pair_overhead_us": round(pair_overhead_us, 2),
+                     "traffic": traffic_from_profile(cfg.cfg_id, dtype, r, dom["kernel"])})
+    step_bytes = sum(q["bytes_pool"] + q["bytes_backward"] for q in cost)
+    step_flops = sum(q["flops_backward"] for q in cost)
+    step_roofline = {"bytes": step_bytes, "flops": step_flops,
+                     "achieved": round(step_bytes / (ms_per_step * 1e-3) * 1e-9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(step_bytes / (ms_per_step * 1e-3) * 1e-9 / HBM_PEAK_GBS, 4),
+                     "note": "algorithmic bytes of all calls of the step (each tensor read or written once by the step that "
+                             "owns it) over the step time"}
+
+    # ---- per layer: the two calls of the step, cold, and vanilla BP at the same shape ----
     per_layer = []
-    for li, L in enumerate(layers):
-        row = {"layer": L.name}
-        tot_us = 0.0
-        for name, fn in STAGES:
-            us = time_stage(fn, li)
-            by = cost[li][stage_bytes[name]]
-            row[name] = {"us": round(us, 2), "GBps": round(by / us * 1e-3, 1), "bytes": by}
-            if name != "pool_activation":
-                tot_us += us
-        if r > 1:   # the filter with its by-product, the noise figures of Eq. (8)
-            us = time_stage(enqueue_filter_snr, li)
-            e_, v_ = sets[0][li].stats.tolist()
-            row["filter_grad_snr"] = {"us": round(us, 2), "snr": round(e_ / v_, 4) if v_ > 0 else None}
-        if q8 is not None:   # the stages of the same layer on 8-bit codes
-            row["q8_us"] = {name: round(time_stage(lambda lb, s, f=fn: f(lb, s, li), li), 2)
-                            for name, fn in (("pool_activation_q8", q8_pool), ("filter_grad_q8", q8_filter),
-                                             ("kernel_sum_q8", q8_ksum), ("bwd_weight_q8", q8_bww),
-                                             ("bwd_input_q8", q8_bwi))}
-        fl = cost[li]["flops_bwd_weight"] + cost[li]["flops_bwd_input"]
-        row["separate_calls_us"] = round(tot_us, 2)     # gf_filter_grad + gf_conv_bwd_weight + gf_conv_bwd_input
-        tot_us = time_stage(enqueue_fused, li)
-        row["backward_us"] = round(tot_us, 2)           # S1 + S2 + S3 + S4 in one call (pooling is forward-time)
-        by = cost[li]["bytes_filter"] + cost[li]["bytes_bwd_weight"] + cost[li]["bytes_bwd_input"]
-        row["backward_GBps"] = round(by / tot_us * 1e-3, 1)
-        row["images_per_s"] = round(N / (tot_us * 1e-6), 1)
-        row["tflops"] = round(fl / tot_us * 1e-6, 3)
-        per_layer.append(row)
-
-    # the reduction kernel (patch_reduce_rows) runs 2x per layer and moves most of the bytes
-    red_us = [per_layer[li][k]["us"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
-    red_by = [per_layer[li][k]["bytes"] for li in range(len(layers)) for k in ("pool_activation", "filter_grad")]
-    iso_us = [time_isolated(fn, li) for li in range(len(layers)) for fn in (enqueue_pool, enqueue_filter)]
-    achieved = sum(red_by) / sum(iso_us) * 1e-3      # GB/s, algorithmic bytes / per-launch duration
-    pipelined = sum(red_by) / sum(red_us) * 1e-3     # same launches back to back in a graph
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_patch_reduce_rows_cfg{cfg.cfg_id}_{dtype}.txt")
-    if os.path.exists(tpath):   # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch="):
-                traffic = float(line.split("=")[1])
-    # `achieved`: the kernel's six launch shapes of a step, each replayed back to back from a graph
-    # over rotating cold buffers between two events on the launch stream; this average launch
-    # duration is the one rocprofv3's kernel trace reports for the same command.  The figures with
-    # one event pair around every single eager launch (which adds the events' own cost of ~3 us
-    # to each launch) are kept beside it.
-    roofline = {"kernel": "patch_reduce_rows", "bound": "hbm", "achieved": round(pipelined, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pipelined / HBM_PEAK_GBS, 4),
-                "avg_launch_us": round(sum(red_us) / len(red_us), 2),
-                "achieved_event_pair_per_launch": round(achieved, 1),
-                "frac_event_pair_per_launch": round(achieved / HBM_PEAK_GBS, 4),
-                "avg_launch_us_event_pair_per_launch": round(sum(iso_us) / len(iso_us), 2),
-                "bytes_per_launch": sum(red_by) / len(red_by), "traffic": traffic}
-
-    # ---- exact BP at the same shapes (speed-up denominator) ----
-    exact = None
-    if full and not args.no_exact:
+    ekey = (c, dtype)
+    if not args.no_exact and ekey not in exact_cache:
+        exact_cache[ekey] = [time_call(enqueue_exact, li, reps=1) for li in range(len(layers))]
+    ex_us = exact_cache.get(ekey)
+    mi_us = None
+    if args.miopen:
         import torch.nn.functional as F
-        ex_us, mi_us = [], []
+        mi_us = []
         for li, L in enumerate(layers):
-            ex_us.append(time_stage(enqueue_exact, li, reps=1))
-            # context: PyTorch-ROCm's (MIOpen) conv backward, both gradients, same tensors
             lb = sets[0][li]
             xg = lb.x.detach().clone().requires_grad_(True)
             wg = lb.w.detach().clone().requires_grad_(True)
@@ -667,71 +622,221 @@ def measure(args, dtype, full):
             torch.cuda.synchronize()
             mi_us.append(e0.elapsed_time(e1) * 1e3 / 10)
             del xg, wg, y
-        gf_us = [row["backward_us"] for row in per_layer]
-        exact = {"own_entry_us": [round(u, 1) for u in ex_us],
-                 "torch_miopen_us": [round(u, 1) for u in mi_us],
-                 "speedup_vs_torch_miopen": [round(e / g, 2) for e, g in zip(mi_us, gf_us)],
-                 "speedup_vs_torch_miopen_block": round(sum(mi_us) / sum(gf_us), 2),
-                 "speedup_vs_own_entry_block": round(sum(ex_us) / sum(gf_us), 2),
-                 "note": "filtered = gf_conv_bwd_filtered (S1+S2+S3+S4) per layer; own entry = gf_conv_bwd_exact "
-                         "(dense stride-1: implicit MFMA GEMMs; other dense: column tensor + MFMA GEMMs; depthwise: plane-staged "
-                         "kernels), cold; torch = autograd of "
-                         "F.conv2d (MIOpen), hot cache, for context"}
+    for li, L in enumerate(layers):
+        s0 = time_call(enqueue_pool, li)
+        bw = time_call(enqueue_fused, li)
+        q = cost[li]
+        row = {"layer": L.name, "pool_us": round(s0, 2), "pool_GBps": round(q["bytes_pool"] / s0 * 1e-3, 1),
+               "backward_us": round(bw, 2), "backward_bytes": q["bytes_backward"],
+               "backward_GBps": round(q["bytes_backward"] / bw * 1e-3, 1),
+               "backward_hbm_frac": round(q["bytes_backward"] / bw * 1e-3 / HBM_PEAK_GBS, 4),
+               "backward_TFLOPs": round(q["flops_backward"] / bw * 1e-6, 3),
+               "images_per_s": round(N / (bw * 1e-6), 1)}
+        # the launches of one backward call (the trace repeats them every step)
+        names = [name for kind, l2, name, _, _ in trace if kind == "backward" and l2 == li]
+        row["kernels"] = names[:len(names) // traced_steps]
+        if ex_us is not None:
+            row["exact_bp_us"] = round(ex_us[li], 1)
+            row["speedup_vs_exact_bp"] = round(ex_us[li] / bw, 2)
+        if mi_us is not None:
+            row["torch_miopen_us"] = round(mi_us[li], 1)
+            row["speedup_vs_torch_miopen"] = round(mi_us[li] / bw, 2)
+        per_layer.append(row)
 
-    # ---- CPU oracle on the host cores (reported baseline only) ----
-    cpu = None
-    if full and not args.no_cpu_baseline:
-        import oracle
-        f64 = lambda t: t.to(torch.float64).numpy()
-        prep = []
-        for L, d, (x, w, gy) in zip(layers, descs, host):
-            od = oracle.Desc(N=N, C_in=L.C_in, C_out=L.C_out, H_in=L.H, W_in=L.W, K_h=L.K, K_w=L.K,
-                             stride=L.stride, pad=L.pad, dilation=L.dilation, groups=L.groups, r=r)
-            prep.append((od, f64(x), f64(w), f64(gy)))
-        oracle.gf_backward(*prep[0])     # build + warm
-        reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 5:
-            t0 = time.perf_counter()
-            for od, x, w, gy in prep:
-                oracle.gf_backward(od, x, w, gy)
-            t_cpu += time.perf_counter() - t0
-            reps += 1
-        cpu = {"value": round(N / (t_cpu / reps), 2), "unit": "images/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": f"the full workload (all {len(layers)} layers, N={N}), fp64, mean of {reps} passes"}
-
-    if args.table:
-        for row in per_layer:
-            log(json.dumps(row))
-
-    out = {
-        "metric": "filtered_conv_backward_images_per_sec", "value": round(value, 1), "unit": "images/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"cfg{cfg.cfg_id}: {cfg.name}, N={N}, r={r}, "
-                               + " + ".join(L.name for L in layers),
-                   "step": "gf_pool_activation + gf_conv_bwd_filtered (filter, kernel sum, weight and input gradient) for every layer",
-                   "launch": "hip-graph replay" if use_graph else "eager", "buffer_sets": nsets,
-                   "cache": "cold (rotating sets)"},
-        "roofline": roofline,
-        "cpu_baseline": cpu,
-        "other_launch_mode_ms_per_step": None if other_ms is None else round(other_ms, 5),
-        "launch_calibration_ms_per_step": calib,
-        "per_layer": per_layer,
-        "exact_bp": exact,
-    }
-    if chained is not None:
-        out["chained_block"] = chained
-    if q8 is not None:
-        out["q8_block"] = q8
-    del sets, one, graphs
+    out = {"cfg": c, "dtype": dtype, "r": r, "N": N,
+           "workload": f"cfg{cfg.cfg_id}: {cfg.name}, N={N}, r={r}, {dtype}: " + " + ".join(L.name for L in layers),
+           "ms_per_step": round(ms_per_step, 5), "images_per_s": round(N / (ms_per_step * 1e-3), 1),
+           "launch": "hip-graph replay" if use_graph else "eager", "launch_calibration_ms_per_step": calib,
+           "buffer_sets": nsets, "roofline": roofline, "step_roofline": step_roofline,
+           "kernels": klist, "per_layer": per_layer}
+    if ex_us is not None:
+        tot_b = sum(row["backward_us"] for row in per_layer)
+        out["speedup_vs_exact_bp"] = round(sum(ex_us) / tot_b, 2)
+        out["exact_bp_note"] = "gf_conv_bwd_exact (both gradients) per layer, cold, against gf_conv_bwd_filtered per layer"
+    if mi_us is not None:
+        out["speedup_vs_torch_miopen"] = round(sum(mi_us) / sum(row["backward_us"] for row in per_layer), 2)
+    if args.extras:
+        out.update(extras(args, cfg, dtype, r, sets, torch, B, T))
+    del sets, graphs
     torch.cuda.empty_cache()
-    if full and args.pmc_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
+    return out
+
+
+def traffic_from_profile(cfg_id, dtype, r, kernel):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+    (profiles/traffic_<kernel>_cfg<id>_<dtype>_r<r>.txt, line 'traffic_bytes_per_launch=...'), or None."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_cfg{cfg_id}_{dtype}_r{r}.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=")[1])
+    return None
+
+
+def cpu_baseline(c, dtype, r):
+    """The CPU oracle as it stands on this machine's host cores, on a bounded sample of the headline
+    workload: filtered backward and vanilla BP, all threads and one thread (reported baseline only)."""
+    import ctypes
+    import torch
+    import oracle
+    from paper_2301_00330_amd import workloads as WL
+    cfg = WL.CONFIGS[c]
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    f64 = lambda t: t.to(torch.float64).numpy()
+
+    def prep(n):
+        out = []
+        for L in cfg.layers:
+            x, w, gy = WL.make_inputs(cfg, L, dtype, N=n)
+            od = oracle.Desc(N=n, C_in=L.C_in, C_out=L.C_out, H_in=L.H, W_in=L.W, K_h=L.K, K_w=L.K,
+                             stride=L.stride, pad=L.pad, dilation=L.dilation, groups=L.groups, r=r)
+            out.append((od, f64(x), f64(w), f64(gy)))
+        return out
+
+    def run(items, exact):
+        t0 = time.perf_counter()
+        for od, x, w, gy in items:
+            if exact:
+                oracle.bwd_exact(od, x, w, gy)
+            else:
+                oracle.gf_backward(od, x, w, gy)
+        return time.perf_counter() - t0
+
+    threads = oracle.num_threads()
+    gomp = ctypes.CDLL("libgomp.so.1")
+    n_all, n_one, n_ex, n_ex1 = min(cfg.N, 32), min(cfg.N, 8), min(cfg.N, 8), min(cfg.N, 1)
+    oracle.gf_backward(*prep(1)[0])     # build + warm
+    items = prep(n_all)
+    t_f = min(run(items, False) for _ in range(2))
+    t_e = run(prep(n_ex), True)
+    gomp.omp_set_num_threads(1)
+    try:
+        t_f1 = run(prep(n_one), False)
+        t_e1 = run(prep(n_ex1), True)
+    finally:
+        gomp.omp_set_num_threads(threads)
+    return {"value": round(n_all / t_f, 2), "unit": "images/s", "cores": threads, "kind": "oracle",
+            "sample": f"filtered backward (all {len(cfg.layers)} layers of cfg{c}, {dtype} inputs, fp64 arithmetic) on "
+                      f"{n_all} of {cfg.N} images, best of 2 passes",
+            "cpu_model": model,
+            "single_thread": {"value": round(n_one / t_f1, 2), "unit": "images/s", "cores": 1, "sample": f"{n_one} images, one pass"},
+            "exact_bp": {"value": round(n_ex / t_e, 2), "unit": "images/s", "cores": threads,
+                         "sample": f"gf_ref_bwd_exact (brute-force direct convolution) on {n_ex} images, one pass"},
+            "exact_bp_single_thread": {"value": round(n_ex1 / t_e1, 2), "unit": "images/s", "cores": 1,
+                                       "sample": f"{n_ex1} image(s), one pass"}}
+
+
+
+def extras(args, cfg, dtype, r, sets, torch, B, T):
+    """Secondary measurements (--extras): the layers as a chain that hands reduced maps from layer to layer
+    (configurations whose layers form a stack), and the same step on signed 8-bit codes."""
+    P = B.ptr
+    nsets = len(sets)
+    N = cfg.N
+    out = {}
+
+    def st():
+        return int(torch.cuda.current_stream().cuda_stream)
+
+    def run(fn):
+        for i in range(max(args.warmup, 1)):
+            fn(sets[i % nsets])
         torch.cuda.synchronize()
-        del src, dst
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fn(sets[i % nsets])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    if cfg.chain and r > 1:
+        order = list(cfg.chain)                       # back to front
+        clip = list(cfg.chain_clip) if cfg.chain_clip else [0.0] * len(cfg.layers)
+        for bs in sets:
+            for li, lb in enumerate(bs):
+                s_ = T.shapes(lb.d)
+                lb.gy_u = torch.empty(s_["gy_u"], dtype=lb.x.dtype, device="cuda")
+                lb.g_xu = torch.empty(s_["g_x_u"], dtype=lb.x.dtype, device="cuda")
+                lb.ws_c = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_CHAINED), 256), dtype=torch.uint8, device="cuda")
+                lb.m_u = torch.empty_like(lb.x_u) if clip[li] > 0 else None
+
+        def step_chained(bufset, masked=False):
+            s = st()
+            for li, lb in enumerate(bufset):          # forward-time S0 (with the mask fraction below a ReLU)
+                if masked and lb.m_u is not None:
+                    B.gf_pool_activation_mask(lb.d, P(lb.x), clip[li], P(lb.x_u), P(lb.m_u), s)
+                else:
+                    B.gf_pool_activation(lb.d, P(lb.x), P(lb.x_u), s)
+            top = bufset[order[0]]
+            B.gf_filter_grad(top.d, P(top.gy), P(top.gy_u), s)
+            gin = top.gy_u
+            for k, li in enumerate(order):
+                lb = bufset[li]
+                last = k == len(order) - 1
+                gout = lb.g_x if last else lb.g_xu
+                m = P(lb.m_u) if (masked and not last and lb.m_u is not None) else 0
+                B.gf_conv_bwd_chained(lb.d, P(gin), P(lb.x_u), P(lb.w), P(lb.g_w), P(gout), not last, m,
+                                      P(lb.ws_c), lb.ws_c.numel(), s)
+                gin = gout
+
+        cms = run(step_chained)
+        mms = run(lambda bs: step_chained(bs, True)) if any(v > 0 for v in clip) else None
+        out["chained_block"] = {
+            "ms_per_step": round(cms, 5), "images_per_s": round(N / (cms * 1e-3), 1),
+            "with_relu6_masks_ms_per_step": None if mms is None else round(mms, 5),
+            "note": "plain launches; same layers and S0 launches, but only the top layer's g_y is filtered: "
+                    "gf_conv_bwd_chained hands the reduced input gradient of a layer to the layer below; full "
+                    "resolution is written only at the bottom; with masks, S0 of the layers below a ReLU6 also writes "
+                    "the mask fraction and the reduced input gradient is multiplied by it inside the chained call"}
+    if r > 1:
+        one = sets[0]
+        for bs in sets:
+            for lb in bs:
+                s_ = T.shapes(lb.d)
+                lb.x_q = torch.empty(s_["x_u"], dtype=torch.int8, device="cuda")
+                lb.gy_q = torch.empty(s_["gy_u"], dtype=torch.int8, device="cuda")
+                lb.w_q = torch.empty(s_["w"][:2], dtype=torch.int8, device="cuda")
+                lb.ws_q = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_WEIGHT_Q8),
+                                          B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_INPUT_Q8), 256),
+                                      dtype=torch.uint8, device="cuda")
+        # step sizes: max|.| / 127 of the reduced maps and of the kernel sum (the caller's choice; formed
+        # once here from the floating-point maps of the first buffer set, outside the timed region)
+        deltas = []
+        for lb in one:
+            gy_u = T.filter_grad(lb.d, lb.gy)
+            x_u = T.pool_activation(lb.d, lb.x)
+            torch.cuda.synchronize()
+            dx = float(x_u.float().abs().max()) / 127.0
+            dg = float(gy_u.float().abs().max()) / 127.0
+            dw = float(lb.w.float().sum(dim=(2, 3)).abs().max()) / 127.0
+            deltas.append((dx or 1.0, dg or 1.0, dw or 1.0))
+
+        def step_q8(bufset):
+            s = st()
+            for li, lb in enumerate(bufset):
+                B.gf_pool_activation_q8(lb.d, P(lb.x), 1.0 / deltas[li][0], P(lb.x_q), s)
+            for li in reversed(range(len(bufset))):
+                lb = bufset[li]
+                dx, dg, dw = deltas[li]
+                B.gf_filter_grad_q8(lb.d, P(lb.gy), 1.0 / dg, P(lb.gy_q), s)
+                B.gf_kernel_sum_q8(lb.d, P(lb.w), 1.0 / dw, P(lb.w_q), s)
+                B.gf_conv_bwd_weight_q8(lb.d, P(lb.x_q), P(lb.gy_q), dx * dg, P(lb.g_w), P(lb.ws_q), lb.ws_q.numel(), s)
+                B.gf_conv_bwd_input_q8(lb.d, P(lb.gy_q), P(lb.w_q), dg * dw, P(lb.g_x), False, P(lb.ws_q), lb.ws_q.numel(), s)
+
+        qms = run(step_q8)
+        out["q8_block"] = {
+            "ms_per_step": round(qms, 5), "images_per_s": round(N / (qms * 1e-3), 1),
+            "arithmetic": "int8 codes, int32 / int64 sums, one fp32 scaling",
+            "stored_activation_bytes_per_step": int(sum(lb.x_q.numel() for lb in one)),
+            "stored_activation_bytes_per_step_float_path": int(sum(lb.x_u.numel() * lb.x_u.element_size() for lb in one)),
+            "note": "plain launches; per layer gf_pool_activation_q8, then gf_filter_grad_q8, gf_kernel_sum_q8, "
+                    "gf_conv_bwd_weight_q8 and gf_conv_bwd_input_q8 (full-resolution g_x in the storage type)"}
     return out
 
 
