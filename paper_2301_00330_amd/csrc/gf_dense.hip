@@ -4,7 +4,7 @@
 //   1. dense_prep_k: the gradient filter (Eq. 2) over runs of whole planes staged in LDS; the patch
 //      means leave the block three times over: in the caller's layout [N, C_y, P] (if wanted), as
 //      GYT [C_y][J] (row = output channel, J = N * P columns) and as GYN [J][C_y] (row = patch).
-//      Extra blocks at the end of the grid relay x_u to XUT [C_x][J], form the kernel sums
+//      Extra blocks at the head of the grid relay x_u to XUT [C_x][J], form the kernel sums
 //      (text after Eq. 3) as WT [C_x][C_y], clear the K padding of all four matrices and zero the
 //      tickets of launch 2.  With these layouts both contractions are plain "NT" products of
 //      matrices with K contiguous and padded to whole chunks.  The four matrices are stored
@@ -57,6 +57,7 @@ __device__ __forceinline__ long blk(int row, int k, int chunks) {
 struct PrepArgs {
   const void* in;      // [planes][H][W]: g_y, or gy_u itself with q = 1
   int planes, C, H, W, q, Hp, Wp, P, mean, vfirst, R;
+  int pw_log;          // log2 of the patch count padded to a power of two (lanes per plane slot)
   long total_in;       // planes * H * W
   FastDiv d_p, d_wp, d_c;
   void* gyu;           // nullable [planes][P]
@@ -77,7 +78,7 @@ struct PrepArgs {
   int Co, KK;
   int* tickets;
   int ntickets;
-  int blk_xu0, blk_w0, blk_pad0, blk_end;
+  int blk_w0, blk_pad0, blk_red0;   // block ranges: [x_u relay | kernel sums | padding and tickets | filter runs]
 };
 
 template <class T>
@@ -88,7 +89,7 @@ __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
   T* wt = static_cast<T*>(a.wt);
   if (b < a.blk_w0) {   // x_u [n][ci][p] -> XUT [ci][n * P + p]
     const T* xu = static_cast<const T*>(a.xu);
-    const int e = (b - a.blk_xu0) * kT + tid;
+    const int e = b * kT + tid;
     if (e < a.nxu) {
       const int n = (int)a.d_cip.div((uint32_t)e);
       const int rem = e - n * a.Ci * a.P;
@@ -126,7 +127,7 @@ __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
   }
   // K padding of the four matrices, tickets
   const int padj = a.kpj - a.J, padc = a.kpc - a.Co;
-  const int lane0 = (b - a.blk_pad0) * kT + tid, step = (a.blk_end - a.blk_pad0) * kT;
+  const int lane0 = (b - a.blk_pad0) * kT + tid, step = (a.blk_red0 - a.blk_pad0) * kT;
   const T zero = from_f32<T>(0.f);
   if (padj > 0) {
     if (a.gyt)
@@ -145,76 +146,106 @@ __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
 
 template <class T>
 __global__ __launch_bounds__(kT) void dense_prep_k(PrepArgs a) {
-  if ((int)blockIdx.x >= a.blk_xu0) { prep_side_jobs<T>(a); return; }
+  // side jobs first: their blocks start first and overlap with the filter blocks
+  if ((int)blockIdx.x < a.blk_red0) { prep_side_jobs<T>(a); return; }
   constexpr int VE = El<T>::VE;
+  constexpr int MAXV = kPrepInBytes / 16 / kT;   // 16-byte vectors of a run per lane
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
-  const int pl0 = blockIdx.x * a.R;
-  const int npl = min(a.R, a.planes - pl0);
   const int HW = a.H * a.W;
-  // the block's planes are one contiguous run that starts on a 16-byte boundary (R is a multiple of 8)
-  const long e0 = (long)pl0 * HW;
-  const int nel = npl * HW;
-  const T* src = static_cast<const T*>(a.in) + e0;
   T* lin = reinterpret_cast<T*>(smem);
-  const int nvec = nel / VE;
-  for (int v = tid; v < nvec; v += kT)
-    reinterpret_cast<uint4*>(lin)[v] = load_stream16(reinterpret_cast<const uint4*>(src) + v);
-  for (int e = nvec * VE + tid; e < nel; e += kT) lin[e] = src[e];
-  T* lout = lin + ((a.R * HW + VE - 1) / VE) * VE;   // [npl][P + 1]
+  T* lout = lin + ((a.R * HW + VE - 1) / VE) * VE;   // [planes of the run][P + 1]
   const int PP = a.P + 1;
-  __syncthreads();
   const int q = a.q;
-  for (int idx = tid; idx < npl * a.P; idx += kT) {
-    const int pl = (int)a.d_p.div((uint32_t)idx);
-    const int p = idx - pl * a.P;
-    const int hp = (int)a.d_wp.div((uint32_t)p);
-    const int wp = p - hp * a.Wp;
-    const int ch = min(q, a.H - hp * q), cw = min(q, a.W - wp * q);
-    const T* base = lin + pl * HW + hp * q * a.W + wp * q;
-    float acc = 0.f;
-    if (a.vfirst) {   // the order of the register kernel of gf_filter_grad: columns first, then across
-      for (int j = 0; j < cw; ++j) {
-        float col = 0.f;
-        for (int i = 0; i < ch; ++i) col += to_f32(base[i * a.W + j]);
-        acc += col;
+  const int nruns = (a.planes + a.R - 1) / a.R;
+  const int stride = (int)gridDim.x - a.blk_red0;
+  // A block walks runs of R whole planes (contiguous, 16-byte aligned starts: R is a multiple of 8);
+  // the next run's loads are in flight while the current one is reduced and written.
+  u32x4_t v[MAXV];
+  auto prefetch = [&](int run) __attribute__((always_inline)) {
+    const int pl0 = run * a.R;
+    const int nvec = min(a.R, a.planes - pl0) * HW / VE;
+    const u32x4_t* src = reinterpret_cast<const u32x4_t*>(static_cast<const T*>(a.in) + (long)pl0 * HW);
+    if (nvec == 0) return;   // a tensor shorter than one vector: its elements are copied one by one below
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int k = tid + i * kT;
+      v[i] = __builtin_nontemporal_load(src + min(k, nvec - 1));   // clamped: always issued
+    }
+  };
+  // patch of this lane: tx = patch index (padded to a power of two), ty = plane slot
+  const int tx = tid & ((1 << a.pw_log) - 1), ty = tid >> a.pw_log;
+  const int txc = min(tx, a.P - 1);
+  const int hp = (int)a.d_wp.div((uint32_t)txc), wp = txc - hp * a.Wp;
+  const int ch = min(q, a.H - hp * q), cw = min(q, a.W - wp * q);
+  const int poff = hp * q * a.W + wp * q;
+  const int cnt = ch * cw;
+  const bool cnt_pow2 = (cnt & (cnt - 1)) == 0;
+  const float inv_cnt = 1.f / (float)cnt;
+  int run = (int)blockIdx.x - a.blk_red0;
+  if (run < nruns) prefetch(run);
+  for (; run < nruns; run += stride) {
+    const int pl0 = run * a.R;
+    const int npl = min(a.R, a.planes - pl0);
+    const int nel = npl * HW, nvec = nel / VE;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int k = tid + i * kT;
+      if (k < nvec) reinterpret_cast<u32x4_t*>(lin)[k] = v[i];
+    }
+    {  // fewer than 16 trailing bytes (only where the tensor ends)
+      const T* src = static_cast<const T*>(a.in) + (long)pl0 * HW;
+      for (int e = nvec * VE + tid; e < nel; e += kT) lin[e] = src[e];
+    }
+    if (run + stride < nruns) prefetch(run + stride);
+    __syncthreads();
+    // lane = (plane slot, patch): the patch geometry is fixed per lane (no divisions inside the loops)
+    if (tx < a.P) {
+      for (int pl = ty; pl < npl; pl += kT >> a.pw_log) {
+        const T* base = lin + pl * HW + poff;
+        float acc = 0.f;
+        if (a.vfirst) {   // the order of the register kernel of gf_filter_grad: columns first, then across
+          for (int j = 0; j < cw; ++j) {
+            float col = 0.f;
+            for (int i = 0; i < ch; ++i) col += to_f32(base[i * a.W + j]);
+            acc += col;
+          }
+        } else {          // the order of its LDS kernel: row by row
+          for (int i = 0; i < ch; ++i)
+            for (int j = 0; j < cw; ++j) acc += to_f32(base[i * a.W + j]);
+        }
+        // a power-of-two count divides exactly either way; anything else takes the true quotient
+        if (a.mean) acc = cnt_pow2 ? acc * inv_cnt : acc / (float)(ch * cw);
+        lout[pl * PP + tx] = from_f32<T>(acc);
       }
-    } else {          // the order of its LDS kernel: row by row
-      for (int i = 0; i < ch; ++i)
-        for (int j = 0; j < cw; ++j) acc += to_f32(base[i * a.W + j]);
     }
-    if (a.mean) acc = acc / (float)(ch * cw);
-    lout[pl * PP + p] = from_f32<T>(acc);
-  }
-  __syncthreads();
-  const int nout = npl * a.P;
-  if (a.gyu) {   // caller's layout: one contiguous run
-    T* d = static_cast<T*>(a.gyu) + (long)pl0 * a.P;
-    for (int idx = tid; idx < nout; idx += kT) {
-      const int pl = (int)a.d_p.div((uint32_t)idx);
-      d[idx] = lout[pl * PP + idx - pl * a.P];
+    __syncthreads();
+    // first plane of the run as (image, channel); the run's planes follow in channel order
+    const int n0 = (int)a.d_c.div((uint32_t)pl0), c0 = pl0 - n0 * a.C;
+    if (a.gyu && tx < a.P) {   // caller's layout: one contiguous run
+      T* d = static_cast<T*>(a.gyu) + (long)pl0 * a.P;
+      for (int pl = ty; pl < npl; pl += kT >> a.pw_log) d[pl * a.P + tx] = lout[pl * PP + tx];
     }
-  }
-  if (a.gyt) {   // row = channel, runs of P along j
-    T* d = static_cast<T*>(a.gyt);
-    for (int idx = tid; idx < nout; idx += kT) {
-      const int pl = (int)a.d_p.div((uint32_t)idx);
-      const int p = idx - pl * a.P;
-      const int n = (int)a.d_c.div((uint32_t)(pl0 + pl));
-      const int c = pl0 + pl - n * a.C;
-      d[blk<El<T>::KB>(c, n * a.P + p, a.chj)] = lout[pl * PP + p];
+    if (a.gyt && tx < a.P) {   // row = channel, runs of P along j
+      T* d = static_cast<T*>(a.gyt);
+      for (int pl = ty; pl < npl; pl += kT >> a.pw_log) {
+        int n = n0, c = c0 + pl;
+        while (c >= a.C) { c -= a.C; ++n; }
+        d[blk<El<T>::KB>(c, n * a.P + tx, a.chj)] = lout[pl * PP + tx];
+      }
     }
-  }
-  if (a.gyn) {   // row = (n, p), consecutive lanes = consecutive channels
-    T* d = static_cast<T*>(a.gyn);
-    for (int idx = tid; idx < nout; idx += kT) {
-      const int p = idx / npl;
-      const int pl = idx - p * npl;
-      const int n = (int)a.d_c.div((uint32_t)(pl0 + pl));
-      const int c = pl0 + pl - n * a.C;
-      const int tn = (int)a.d_ipt.div((uint32_t)n);
-      d[blk<El<T>::KB>(64 * tn + (n - tn * a.ipt) * a.P + p, c, a.chc)] = lout[pl * PP + p];
+    if (a.gyn) {   // row = (n, p), consecutive lanes = consecutive channels (32 plane slots x 8 patches per pass)
+      T* d = static_cast<T*>(a.gyn);
+      const int pl = tid & 31;
+      if (pl < npl) {
+        int n = n0, c = c0 + pl;
+        while (c >= a.C) { c -= a.C; ++n; }
+        const int tn = (int)a.d_ipt.div((uint32_t)n);
+        const int row0 = 64 * tn + (n - tn * a.ipt) * a.P;
+        for (int p = tid >> 5; p < a.P; p += kT >> 5) d[blk<El<T>::KB>(row0 + p, c, a.chc)] = lout[pl * PP + p];
+      }
     }
+    __syncthreads();   // lin and lout are rewritten by the next run
   }
 }
 
@@ -648,6 +679,8 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
   a.Hp = g.Hp; a.Wp = g.Wp; a.P = g.P;
   a.vfirst = src_is_gy && patch_reduce_uses_rows(g.dtype, a.planes, a.H, a.W, a.q) ? 1 : 0;
   a.R = prep_planes_per_block(g, a.H, a.W);
+  a.pw_log = 0;
+  while ((1 << a.pw_log) < g.P) ++a.pw_log;
   a.total_in = (long)a.planes * a.H * a.W;
   a.d_p = FastDiv((uint32_t)g.P);
   a.d_wp = FastDiv((uint32_t)g.Wp);
@@ -668,14 +701,15 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
   a.Co = g.Co; a.KK = g.KK;
   a.tickets = reinterpret_cast<int*>(wsb + p.off_tick);
   a.ntickets = p.w_tm * p.w_tn + p.d_tm * p.d_tn;
-  const int nred = cdiv(a.planes, a.R);
-  a.blk_xu0 = nred;
-  a.blk_w0 = a.blk_xu0 + (want_w ? cdiv(a.nxu, kT) : 0);
+  a.blk_w0 = want_w ? cdiv(a.nxu, kT) : 0;
   a.blk_pad0 = a.blk_w0 + (want_d ? cdiv(g.Ci, 32) * cdiv(g.Co, 32) : 0);
-  a.blk_end = a.blk_pad0 + 8;
+  a.blk_red0 = a.blk_pad0 + 8;
+  // filter blocks: at most eight per CU, each walks its share of the runs
+  const int nruns = cdiv(a.planes, a.R);
+  const int nred = nruns < 2048 ? nruns : 2048;
   const int VE = El<T>::VE;
   const size_t lds = (size_t)((a.R * a.H * a.W + VE - 1) / VE * VE + a.R * (g.P + 1)) * sizeof(T) + 16;
-  GF_LAUNCH(dense_prep_k<T>, dim3(a.blk_end), dim3(kT), lds, st, a);
+  GF_LAUNCH(dense_prep_k<T>, dim3(a.blk_red0 + nred), dim3(kT), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
