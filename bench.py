@@ -259,7 +259,7 @@ class LayerBufs:
 KERNEL_RULES = (
     ("dense_gemm_k", ("bytes_bwd_weight", "bytes_bwd_input"), True),
     ("s3s4_", ("bytes_bwd_weight", "bytes_bwd_input"), True),
-    ("wgrad_", ("bytes_bwd_weight",), True), ("plain_wgrad", ("bytes_bwd_weight",), True),
+    ("wgrad_", ("bytes_bwd_weight",), True), ("xwgrad_k", ("bytes_bwd_weight",), True),
     ("dgrad_", ("bytes_bwd_input",), True),
     ("dense_prep_k", ("bytes_filter",), False),
     ("onepass_k", ("bytes_fused",), False), ("dw_fused", ("bytes_fused",), False),
@@ -328,8 +328,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": head["workload"],
-                   "step": "for every layer: gf_pool_activation, then gf_conv_bwd_filtered (gradient filter, kernel sum, "
-                           "weight and input gradient)",
+                   "step": "gf_pool_activation_batch over all layers (one launch), then for every layer gf_conv_bwd_filtered "
+                           "(gradient filter, kernel sum, weight and input gradient)",
                    "launch": head["launch"], "buffer_sets": head["buffer_sets"], "cache": "cold (rotating sets)"},
         "roofline": head["roofline"],
         "step_roofline": head["step_roofline"],
@@ -370,9 +370,10 @@ def step_only(args, c, dtype, r):
     P = B.ptr
     s = int(torch.cuda.current_stream().cuda_stream)
 
+    pool_batches = [B.PoolBatch([lb.d for lb in bs], [P(lb.x) for lb in bs], [P(lb.x_u) for lb in bs]) for bs in sets]
+
     def step(bufset):
-        for lb in bufset:
-            B.gf_pool_activation(lb.d, P(lb.x), P(lb.x_u), s)
+        B.gf_pool_activation_batch(pool_batches[sets.index(bufset)], s)
         for lb in reversed(bufset):
             B.gf_conv_bwd_filtered(lb.d, P(lb.gy), P(lb.x_u), P(lb.w), 0, P(lb.g_w), P(lb.g_x), P(lb.ws_f), lb.ws_f.numel(), s)
 
@@ -427,18 +428,20 @@ def measure(args, c, dtype, r, exact_cache):
             lb.ws_e = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_EXACT), 256), dtype=torch.uint8, device="cuda")
         B.gf_conv_bwd_exact(lb.d, P(lb.x), P(lb.w), P(lb.gy), P(lb.e_w), P(lb.e_x), P(lb.ws_e), lb.ws_e.numel(), s)
 
-    def step(bufset):
-        # the order of a training step: the activations are pooled on the way forward (first layer
-        # first), the backward pass then walks the layers from the last to the first
+    # forward-time S0 of all layers of the step in one launch
+    pool_batches = [B.PoolBatch([lb.d for lb in bs], [P(lb.x) for lb in bs], [P(lb.x_u) for lb in bs]) for bs in sets]
+
+    def step(k):
+        # the activations are pooled on the way forward, the backward pass then walks the layers
+        # from the last to the first
         s = st()
-        for lb in bufset:
-            enqueue_pool(lb, s)      # forward-time S0
-        for lb in reversed(bufset):
-            enqueue_fused(lb, s)     # S1 + S2 + S3 + S4
+        B.gf_pool_activation_batch(pool_batches[k], s)     # S0
+        for lb in reversed(sets[k]):
+            enqueue_fused(lb, s)                            # S1 + S2 + S3 + S4
 
     # ---- warm-up (eager), then optional graph capture of one step per buffer set ----
     for i in range(max(args.warmup, 1)):
-        step(sets[i % nsets])
+        step(i % nsets)
     torch.cuda.synchronize()
 
     graphs = None
@@ -447,10 +450,10 @@ def measure(args, c, dtype, r, exact_cache):
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            for bs in sets:
+            for k in range(nsets):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=side):
-                    step(bs)
+                    step(k)
                 graphs.append(g)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
@@ -465,7 +468,7 @@ def measure(args, c, dtype, r, exact_cache):
             if use_graph:
                 graphs[i % nsets].replay()
             else:
-                step(sets[i % nsets])
+                step(i % nsets)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / k
 
@@ -533,9 +536,8 @@ def measure(args, c, dtype, r, exact_cache):
         for i in range(traced_steps):
             bs = sets[i % nsets]
             s = st()
-            for li, lb in enumerate(bs):
-                cur["kind"], cur["li"] = "pool", li
-                enqueue_pool(lb, s)
+            cur["kind"], cur["li"] = "pool", -1
+            B.gf_pool_activation_batch(pool_batches[i % nsets], s)
             for li in reversed(range(len(bs))):
                 cur["kind"], cur["li"] = "backward", li
                 enqueue_fused(bs[li], s)
@@ -544,10 +546,27 @@ def measure(args, c, dtype, r, exact_cache):
     torch.cuda.synchronize()
     # what a pair of events adds to a launch: the same single-launch call, once as event pairs around eager
     # launches (above) and once replayed back to back from a graph between two events
-    li_big = max(range(len(layers)), key=lambda i: cost[i]["bytes_pool"])
-    pool_replay_us = time_call(enqueue_pool, li_big)
-    pool_pair = [a.elapsed_time(b) * 1e3 for k, li, n, a, b in trace if k == "pool" and li == li_big]
-    pair_overhead_us = max(0.0, sum(pool_pair) / len(pool_pair) - pool_replay_us)
+    def enqueue_pool_batch(lb, s):   # (time_call hands over layer 0 of a set: look the set up)
+        B.gf_pool_activation_batch(pool_batches[set_of[id(lb)]], s)
+
+    set_of = {id(bs[0]): k for k, bs in enumerate(sets)}
+    pool_replay_us = time_call(enqueue_pool_batch, 0)
+    # what a pair of events adds to a launch: one single-launch call (the pooling of the layer with the
+    # smallest input, so that the difference is not lost in the kernel's own run-to-run spread), once as
+    # event pairs around eager launches and once replayed back to back from a graph between two events
+    li_cal = min(range(len(layers)), key=lambda i: cost[i]["bytes_pool"])
+    cal_replay_us = time_call(enqueue_pool, li_cal)
+    pairs = []
+    for rep in range(4):
+        for k in range(nsets):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            enqueue_pool(sets[k][li_cal], st())
+            e1.record()
+            pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    cal_pair_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
+    pair_overhead_us = max(0.0, cal_pair_us - cal_replay_us)
     kernels = {}
     for kind, li, name, e0, e1 in trace:
         k = kernels.setdefault(name, {"us": 0.0, "launches": 0, "bytes": 0.0, "flops": 0.0, "mfma": False})
@@ -556,9 +575,10 @@ def measure(args, c, dtype, r, exact_cache):
         for prefix, keys, mfma in KERNEL_RULES:
             if name.startswith(prefix):
                 for key in keys:
-                    if key == "bytes_reduce":
-                        key = "bytes_pool" if kind == "pool" else "bytes_filter"
-                    k["bytes"] += cost[li][key]
+                    if key == "bytes_reduce" and kind == "pool":     # the batch launch pools every layer
+                        k["bytes"] += sum(q["bytes_pool"] for q in cost)
+                    else:
+                        k["bytes"] += cost[li]["bytes_filter" if key == "bytes_reduce" else key]
                 if mfma:
                     k["mfma"] = True
                     k["flops"] += cost[li]["flops_backward"] if len(keys) == 2 else cost[li]["flops_bwd_weight"]
@@ -647,7 +667,7 @@ def measure(args, c, dtype, r, exact_cache):
            "workload": f"cfg{cfg.cfg_id}: {cfg.name}, N={N}, r={r}, {dtype}: " + " + ".join(L.name for L in layers),
            "ms_per_step": round(ms_per_step, 5), "images_per_s": round(N / (ms_per_step * 1e-3), 1),
            "launch": "hip-graph replay" if use_graph else "eager", "launch_calibration_ms_per_step": calib,
-           "buffer_sets": nsets, "roofline": roofline, "step_roofline": step_roofline,
+           "buffer_sets": nsets, "pool_batch_us": round(pool_replay_us, 2), "roofline": roofline, "step_roofline": step_roofline,
            "kernels": klist, "per_layer": per_layer}
     if ex_us is not None:
         tot_b = sum(row["backward_us"] for row in per_layer)

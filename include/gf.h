@@ -132,6 +132,15 @@ gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes);
  * loop keeps for the backward pass instead of x (Sec. 4.3). */
 gf_status gf_pool_activation(const gf_conv_desc* desc, const void* x, void* x_u, void* stream);
 
+/* gf_pool_activation for `count` layers in ONE launch (a training step that holds the inputs of several
+ * layers, e.g. a recomputed block, pools them together: the small tensors of a network's tail are a few
+ * microseconds of work each and a launch costs as much).  descs: HOST array of `count` descriptors; x, x_u:
+ * HOST arrays of `count` device pointers.  Every x_u[i] is bit-identical to what gf_pool_activation writes
+ * for descs[i].  All layers must share one dtype (else GF_ERR_UNSUPPORTED); layers with r == 1 are copied.
+ * count < 1 or > 4096: GF_ERR_BAD_DESC.  Nothing is enqueued unless every layer passes validation. */
+gf_status gf_pool_activation_batch(int32_t count, const gf_conv_desc* descs, const void* const* x,
+                                   void* const* x_u, void* stream);
+
 /* The same for a layer whose input x is the output of a ReLU (hi = +infinity) or of a clipped
  * ReLU (hi = 6 for ReLU6), for chains of filtered layers (see gf_conv_bwd_chained): beside x_u
  * it writes m_u [N, C_in, H_p, W_p] (storage type), the share of each patch's in-bounds pixels

@@ -20,7 +20,8 @@ GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BW
 GF_OP_FILTER_SNR = 5
 GF_OP_BWD_WEIGHT_Q8, GF_OP_BWD_INPUT_Q8 = 6, 7
 
-EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_mask", "gf_filter_grad",
+EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_batch",
+           "gf_pool_activation_mask", "gf_filter_grad",
            "gf_filter_grad_snr",
            "gf_conv_bwd_weight", "gf_conv_bwd_input", "gf_conv_bwd_filtered", "gf_conv_bwd_filtered_static",
            "gf_conv_bwd_chained",
@@ -92,6 +93,7 @@ def lib() -> C.CDLL:
         L.gf_out_shape.argtypes = [dp, i32p, i32p, i32p, i32p]
         L.gf_workspace_bytes.argtypes = [dp, C.c_int, C.POINTER(C.c_size_t)]
         L.gf_pool_activation.argtypes = [dp, vp, vp, vp]
+        L.gf_pool_activation_batch.argtypes = [C.c_int32, dp, C.POINTER(vp), C.POINTER(vp), vp]
         L.gf_filter_grad.argtypes = [dp, vp, vp, vp]
         L.gf_filter_grad_snr.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_weight.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -170,6 +172,22 @@ def gf_workspace_bytes(d: ConvDesc, op: int) -> int:
 def gf_pool_activation(d: ConvDesc, x: int, x_u: int, stream: int = 0):
     cd = d.c()
     _chk(lib().gf_pool_activation(C.byref(cd), x, x_u, stream), "gf_pool_activation")
+
+
+class PoolBatch:
+    """Marshalled arguments of gf_pool_activation_batch (build once, call many times)."""
+
+    def __init__(self, descs, xs, x_us):
+        n = len(descs)
+        assert n == len(xs) == len(x_us)
+        self.n = n
+        self.descs = (_Desc * max(n, 1))(*[d.c() for d in descs])
+        self.xs = (C.c_void_p * max(n, 1))(*xs)
+        self.x_us = (C.c_void_p * max(n, 1))(*x_us)
+
+
+def gf_pool_activation_batch(batch: PoolBatch, stream: int = 0):
+    _chk(lib().gf_pool_activation_batch(batch.n, batch.descs, batch.xs, batch.x_us, stream), "gf_pool_activation_batch")
 
 
 def gf_filter_grad(d: ConvDesc, g_y: int, gy_u: int, stream: int = 0):

@@ -4,6 +4,7 @@
 
 #include <atomic>
 #include <mutex>
+#include <vector>
 
 #include "gf_internal.h"
 
@@ -223,6 +224,36 @@ gf_status gf_pool_activation(const gf_conv_desc* desc, const void* x, void* x_u,
   if (g.r == 1)
     return dev(hipMemcpyAsync(x_u, x, (size_t)planes * g.H * g.W * g.b, hipMemcpyDeviceToDevice, st));
   return dev(launch_patch_reduce(x, x_u, planes, g.H, g.W, g.rx, false, g.dtype, st));
+}
+
+gf_status gf_pool_activation_batch(int32_t count, const gf_conv_desc* descs, const void* const* x, void* const* x_u,
+                                   void* stream) {
+  if (count < 1 || count > 4096) return GF_ERR_BAD_DESC;
+  if (!descs || !x || !x_u) return GF_ERR_NULL;
+  // every layer is validated before anything is enqueued
+  std::vector<Geom> gs((size_t)count);
+  for (int i = 0; i < count; ++i) {
+    gf_status rc = make_geom(&descs[i], &gs[i]);
+    if (rc) return rc;
+    if (!x[i] || !x_u[i]) return GF_ERR_NULL;
+    if (!aligned16(x[i]) || !aligned16(x_u[i])) return GF_ERR_UNSUPPORTED;
+    if (gs[i].dtype != gs[0].dtype) return GF_ERR_UNSUPPORTED;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  std::vector<PoolJob> jobs;
+  jobs.reserve((size_t)count);
+  for (int i = 0; i < count; ++i) {
+    const Geom& g = gs[i];
+    const long planes = (long)g.N * g.Ci;
+    if (g.r == 1) {   // vanilla BP keeps x itself
+      gf_status rc = dev(hipMemcpyAsync(x_u[i], x[i], (size_t)planes * g.H * g.W * g.b, hipMemcpyDeviceToDevice, st));
+      if (rc) return rc;
+      continue;
+    }
+    jobs.push_back(PoolJob{x[i], x_u[i], planes, g.H, g.W, g.rx});
+  }
+  if (jobs.empty()) return GF_OK;
+  return dev(launch_pool_batch(jobs.data(), (int)jobs.size(), gs[0].dtype, st));
 }
 
 gf_status gf_filter_grad(const gf_conv_desc* desc, const void* g_y, void* gy_u, void* stream) {

@@ -146,6 +146,15 @@ struct KsumJob {
 hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, int W, int q,
                                bool mean, int dtype, hipStream_t st, const KsumJob* ksum = nullptr);
 
+// S0 of several tensors in one launch: out[plane, hp, wp] = sum of in[plane] over q x q patches
+struct PoolJob {
+  const void* in;
+  void* out;
+  long planes;
+  int H, W, q;
+};
+hipError_t launch_pool_batch(const PoolJob* jobs, int count, int dtype, hipStream_t st);
+
 // ---- 8-bit codes (gf_q8.hip; the reductions with code output live in gf_reduce.hip) ----
 // S0 / S1 with the result as signed 8-bit codes: round_half_even(value * inv_delta), clipped to +-127
 hipError_t launch_patch_reduce_q8(const void* in, int8_t* out_q, long planes, int H, int W, int q, bool mean,

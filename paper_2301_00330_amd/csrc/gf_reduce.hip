@@ -78,9 +78,8 @@ __device__ __forceinline__ bool ksum_side_job(const ReduceArgs& a) {
 // rows kernel: requires W % max(VE, Q) == 0 and (W * sizeof(T)) % 16 == 0
 // ---------------------------------------------------------------------------
 template <class T, int Q, int U, int MODE = kPlain>
-__global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
+__device__ __forceinline__ void rows_body(const ReduceArgs& a, const int blk) {
   constexpr bool STATS = MODE == kStats;
-  if (ksum_side_job<T>(a)) return;
   __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
   float energy = 0.f, noise = 0.f;
   constexpr int VE = Vec16<T>::N;            // elements per 16-byte vector
@@ -91,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
   T* out = static_cast<T*>(a.out);
   uint4 v[U][Q][VW];
   int strip[U], col[U], rows[U];
-  const int t0 = blockIdx.x * (kThreads * U) + threadIdx.x;
+  const int t0 = blk * (kThreads * U) + threadIdx.x;
   // all loads are issued unconditionally (indices clamped into the tensor) so that the
   // U * Q * VW vectors of a lane are in flight together; invalid ones are dropped below
 #pragma unroll
@@ -198,18 +197,23 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
   if constexpr (STATS) block_stats(energy, noise, red, a.stats_part);
 }
 
+template <class T, int Q, int U, int MODE = kPlain>
+__global__ __launch_bounds__(kThreads) void patch_reduce_rows(ReduceArgs a) {
+  if (ksum_side_job<T>(a)) return;
+  rows_body<T, Q, U, MODE>(a, blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------
 // LDS kernel: any shape whose strip fits the staging buffer
 // ---------------------------------------------------------------------------
 template <class T, int QT, int MODE = kPlain>  // QT: compile-time patch size, 0 = run-time
-__global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
+__device__ __forceinline__ void lds_body(const ReduceArgs& a, const int blk) {
   constexpr bool STATS = MODE == kStats;
-  if (ksum_side_job<T>(a)) return;
   __shared__ float red[STATS ? 2 * (kThreads / 64) : 1];
   float energy = 0.f, noise = 0.f;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
-  const int s0 = blockIdx.x * a.spb;
+  const int s0 = blk * a.spb;
   const int s1 = min(s0 + a.spb, a.total_strips);
   const int pl0 = (int)a.d_hp.div((uint32_t)s0);
   const int hp0 = s0 - pl0 * a.Hp;
@@ -303,6 +307,43 @@ __global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
     }
   }
   if constexpr (STATS) block_stats(energy, noise, red, a.stats_part);
+}
+
+template <class T, int QT, int MODE = kPlain>
+__global__ __launch_bounds__(kThreads) void patch_reduce_lds(ReduceArgs a) {
+  if (ksum_side_job<T>(a)) return;
+  lds_body<T, QT, MODE>(a, blockIdx.x);
+}
+
+// ---------------------------------------------------------------------------
+// Several tensors in ONE launch (the activation pooling of all layers of a step): every block looks up
+// the job its index falls into and runs that job's variant of the two kernels above.
+// ---------------------------------------------------------------------------
+constexpr int kMaxBatch = 16;
+enum { kVarRows2, kVarRows4, kVarRows8, kVarLds2, kVarLds4, kVarLds8, kVarLds0 };
+struct BatchArgs {
+  int njobs;
+  int first_block[kMaxBatch + 1];
+  int variant[kMaxBatch];
+  ReduceArgs job[kMaxBatch];
+};
+static_assert(sizeof(BatchArgs) <= 3584, "the job table travels as a kernel argument");
+
+template <class T>
+__global__ __launch_bounds__(kThreads) void patch_reduce_batch_k(BatchArgs b) {
+  int j = 0;
+  while (j + 1 < b.njobs && (int)blockIdx.x >= b.first_block[j + 1]) ++j;
+  const int blk = (int)blockIdx.x - b.first_block[j];
+  const ReduceArgs& a = b.job[j];
+  switch (b.variant[j]) {
+    case kVarRows2: rows_body<T, 2, 1, kPlain>(a, blk); break;
+    case kVarRows4: rows_body<T, 4, 1, kPlain>(a, blk); break;
+    case kVarRows8: rows_body<T, 8, 1, kPlain>(a, blk); break;
+    case kVarLds2: lds_body<T, 2, kPlain>(a, blk); break;
+    case kVarLds4: lds_body<T, 4, kPlain>(a, blk); break;
+    case kVarLds8: lds_body<T, 8, kPlain>(a, blk); break;
+    default: lds_body<T, 0, kPlain>(a, blk); break;
+  }
 }
 
 // Fallback without LDS for strips too large to stage: one lane per patch.
@@ -551,6 +592,83 @@ hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, in
   a.d_wp = FastDiv((uint32_t)a.Wp);
   if (dtype == GF_BF16) return launch_t<bf16_t>(a, st, &blocks);
   return launch_t<float>(a, st, &blocks);
+}
+
+// How launch_mode would run this plain reduction: the variant and its block count (and a.spb / a.ipr ...
+// filled in), or false when it needs the kernel without LDS.
+template <class T>
+static bool plan_plain(ReduceArgs& a, int* variant, int* blocks, size_t* lds) {
+  *lds = 0;
+  if (rows_ok<T>(a.W, a.q) && (long)a.total_strips * (a.W / 4) < 2147483647L) {
+    constexpr int VE = Vec16<T>::N;
+    const int IW = VE > a.q ? VE : a.q;
+    a.ipr = a.W / IW;
+    a.total_items = a.total_strips * a.ipr;
+    a.d_ipr = FastDiv((uint32_t)a.ipr);
+    *blocks = cdiv(a.total_items, kThreads);
+    *variant = a.q == 2 ? kVarRows2 : a.q == 4 ? kVarRows4 : kVarRows8;
+    return true;
+  }
+  const long strip_bytes = (long)imin_host(a.q, a.H) * a.W * (long)sizeof(T);
+  if (strip_bytes + 32 > kLdsMax) return false;
+  int spb = (int)((kLdsBudget - 32) / strip_bytes);
+  if (spb < 1) spb = 1;
+  const int want_blocks = 2048;
+  if (a.total_strips / spb < want_blocks) spb = a.total_strips / want_blocks;
+  if (spb < 1) spb = 1;
+  a.spb = spb;
+  *lds = (size_t)spb * strip_bytes + 32;
+  *blocks = (a.total_strips + spb - 1) / spb;
+  *variant = a.q == 2 ? kVarLds2 : a.q == 4 ? kVarLds4 : a.q == 8 ? kVarLds8 : kVarLds0;
+  return true;
+}
+
+template <class T>
+static hipError_t batch_t(const PoolJob* jobs, int count, hipStream_t st) {
+  int i = 0;
+  while (i < count) {
+    BatchArgs b = {};
+    size_t lds_max = 0;
+    int blocks_total = 0;
+    while (i < count && b.njobs < kMaxBatch) {
+      const PoolJob& pj = jobs[i];
+      ReduceArgs a = {};
+      a.in = pj.in; a.out = pj.out; a.H = pj.H; a.W = pj.W; a.q = pj.q;
+      a.Hp = cdiv(pj.H, pj.q); a.Wp = cdiv(pj.W, pj.q);
+      a.total_in = (int)(pj.planes * pj.H * pj.W);
+      a.total_strips = (int)(pj.planes * a.Hp);
+      a.mean = 0;
+      a.d_hp = FastDiv((uint32_t)a.Hp);
+      a.d_wp = FastDiv((uint32_t)a.Wp);
+      int variant = 0, blocks = 0;
+      size_t lds = 0;
+      if (!plan_plain<T>(a, &variant, &blocks, &lds)) {   // a strip larger than LDS: a launch of its own
+        if (b.njobs > 0) break;
+        hipError_t e = launch_patch_reduce(pj.in, pj.out, pj.planes, pj.H, pj.W, pj.q, false,
+                                           sizeof(T) == 2 ? GF_BF16 : GF_F32, st, nullptr);
+        if (e != hipSuccess) return e;
+        ++i;
+        continue;
+      }
+      b.first_block[b.njobs] = blocks_total;
+      b.variant[b.njobs] = variant;
+      b.job[b.njobs] = a;
+      ++b.njobs;
+      blocks_total += blocks;
+      if (lds > lds_max) lds_max = lds;
+      ++i;
+    }
+    if (b.njobs == 0) continue;
+    b.first_block[b.njobs] = blocks_total;
+    GF_LAUNCH(patch_reduce_batch_k<T>, dim3(blocks_total), dim3(kThreads), lds_max, st, b);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_pool_batch(const PoolJob* jobs, int count, int dtype, hipStream_t st) {
+  return dtype == GF_BF16 ? batch_t<bf16_t>(jobs, count, st) : batch_t<float>(jobs, count, st);
 }
 
 // true when launch_patch_reduce sums a patch in the order of the register kernel (columns first)

@@ -87,6 +87,17 @@ def pool_activation(d: B.ConvDesc, x: torch.Tensor, out: torch.Tensor | None = N
     return out
 
 
+def pool_activation_batch(descs, xs):
+    """x_u of several layers from one launch (gf_pool_activation_batch)."""
+    outs = []
+    for d, x in zip(descs, xs):
+        s = shapes(d)
+        _check(x, d, s["x"], "x")
+        outs.append(torch.empty(s["x_u"], dtype=x.dtype, device=x.device))
+    B.gf_pool_activation_batch(B.PoolBatch(descs, [B.ptr(x) for x in xs], [B.ptr(o) for o in outs]), _stream())
+    return outs
+
+
 def pool_activation_mask(d: B.ConvDesc, x: torch.Tensor, hi: float = float("inf")):
     """(x_u, m_u): patch sums of x and the share of each patch with 0 < x < hi (the gradient mask of the
     ReLU / clipped ReLU that produced x, averaged over the patch)."""

@@ -282,3 +282,23 @@ def test_probe_library_builds_and_exports(lib):
     assert L.gfp_mfma(7, 10, FAKE, C.byref(ops), None) == 1 and L.gfp_mfma(0, 0, FAKE, C.byref(ops), None) == 1
     L.gfp_read.argtypes = [C.c_void_p, C.c_void_p, C.c_long, C.c_void_p]
     assert L.gfp_read(None, FAKE, 1024, None) == 1 and L.gfp_read(FAKE, FAKE, 8, None) == 1
+
+
+def test_pool_batch_host_checks(lib):
+    """gf_pool_activation_batch validates every layer before anything is enqueued."""
+    d = B.ConvDesc(**OK)
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation_batch(B.PoolBatch([], [], []))
+    assert ei.value.status == B.GF_ERR_BAD_DESC
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation_batch(B.PoolBatch([d, d], [FAKE, 0], [FAKE, FAKE]))
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation_batch(B.PoolBatch([d, d.with_(r=0)], [FAKE, FAKE], [FAKE, FAKE]))
+    assert ei.value.status == B.GF_ERR_BAD_DESC
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation_batch(B.PoolBatch([d, d.with_(dtype=B.GF_BF16)], [FAKE, FAKE], [FAKE, FAKE]))
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    with pytest.raises(B.GfError) as ei:
+        B.gf_pool_activation_batch(B.PoolBatch([d, d], [FAKE, FAKE + 4], [FAKE, FAKE]))
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED

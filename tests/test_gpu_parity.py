@@ -1349,3 +1349,40 @@ def test_launch_observer_lists_the_kernels_of_a_call():
     n = len(seen)
     T.conv_bwd_filtered(d, gy, x_u, w)
     assert len(seen) == n
+
+
+# ---------------------------------------------------------------------------
+# activation pooling of several layers in one launch
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pool_activation_batch_is_bit_identical(oracle, dtype):
+    """gf_pool_activation_batch against gf_pool_activation layer by layer (bit for bit) and against the
+    oracle: register and LDS variants of every patch size, ragged maps, a strided layer (r_x = 4), a
+    layer with r = 1 (copied), a strip too large for LDS (launch of its own in the middle of the list)
+    and more layers than one launch holds."""
+    cases = [(2, 3, 8, 8, 2, 1), (3, 5, 7, 7, 2, 1), (3, 5, 7, 7, 4, 1), (2, 4, 14, 14, 2, 2), (1, 2, 56, 56, 2, 1),
+             (2, 3, 64, 64, 8, 1), (1, 3, 9, 5, 3, 1), (2, 2, 7, 7, 7, 1), (2, 3, 9, 9, 1, 1), (1, 1, 12, 9000, 8, 1),
+             (4, 37, 7, 7, 2, 1), (2, 3, 30, 40, 4, 1), (1, 2, 160, 120, 2, 1), (2, 24, 56, 56, 4, 1), (1, 1, 1, 1, 2, 1),
+             (2, 3, 16, 16, 2, 1), (3, 4, 28, 28, 2, 1), (2, 8, 14, 14, 4, 1), (1, 2, 32, 32, 8, 1), (2, 6, 15, 13, 2, 2)]
+    descs, xs = [], []
+    for k, (N, C, H, W, r, s) in enumerate(cases):
+        descs.append(mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype))
+        xs.append(randn((N, C, H, W), 100 + k, dtype).cuda())
+    outs = T.pool_activation_batch(descs, xs)
+    torch.cuda.synchronize()
+    assert len(outs) == len(cases)
+    for d, x, got in zip(descs, xs, outs):
+        one = T.pool_activation(d, x)
+        assert torch.equal(got, one)
+        assert rel_err(got, oracle.pool_activation(odesc(oracle, d), to64(x))) <= TOL[dtype]
+
+
+def test_pool_activation_batch_full_config5(oracle):
+    """The call bench.py times: all ten layers of configuration 5 at N = 128, fp32, in one launch."""
+    cfg = WL.CONFIGS[5]
+    descs = [T.desc_for(L, cfg.N, 2, "f32") for L in cfg.layers]
+    xs = [WL.make_inputs(cfg, L, "f32")[0] for L in cfg.layers]
+    outs = T.pool_activation_batch(descs, [x.cuda() for x in xs])
+    torch.cuda.synchronize()
+    for d, x, got in zip(descs, xs, outs):
+        assert rel_err(got, oracle.pool_activation(odesc(oracle, d), to64(x))) <= 1e-5
