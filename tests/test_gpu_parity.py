@@ -343,10 +343,12 @@ def test_fused_entry_matches_separate_calls(oracle, case, dtype, want_gyu):
         assert gy_u is None
     gw_tol = 1e-5 if dtype == "f32" else 1e-5   # same rounded operands, only the fp32 summation order differs
     assert float((g_w - s_gw).abs().max()) <= gw_tol * float(s_gw.abs().max() + 1e-30)
-    # and against the oracle, end to end from the same inputs
+    # and against the oracle: the filter from the same g_y; the two contractions from the oracle's own
+    # filtered gradient rounded once to the storage type (where the library rounds it too)
     ref_gyu = oracle.filter_grad(od, to64(gy))
-    ref_gw = oracle.bwd_weight(od, to64(x_u), to64(s_gyu))
-    ref_gx = oracle.bwd_input(od, to64(s_gyu), to64(w))
+    ref_gyu_r = to64(rounded(ref_gyu, dtype))
+    ref_gw = oracle.bwd_weight(od, to64(x_u), ref_gyu_r)
+    ref_gx = oracle.bwd_input(od, ref_gyu_r, to64(w))
     assert rel_err(s_gyu, ref_gyu) <= TOL[dtype]
     assert rel_err(g_w, ref_gw) <= TOL[dtype]
     assert rel_err(g_x, ref_gx) <= TOL[dtype]
