@@ -530,12 +530,21 @@ def measure(args, c, dtype, r, exact_cache):
             e1.record()
             trace.append((cur["kind"], cur["li"], name, cur["ev"], e1))
 
+    # The events must measure the GPU, not the host: recording two events and a launch from Python takes
+    # longer than a short kernel runs, and a kernel that finds the queue empty is timed from the moment
+    # the event before it completed.  Ahead of every traced step the stream therefore gets a kernel that
+    # only waits (torch's device sleep, ~1.7 ms, no memory traffic), so that the step's launches and
+    # events are all queued behind it before the first of them runs.
+    def block_gpu():
+        torch.cuda._sleep(4_000_000)
+
     traced_steps = 3 * nsets if nsets <= 8 else nsets
     B.gf_set_launch_observer(observer)
     try:
         for i in range(traced_steps):
             bs = sets[i % nsets]
             s = st()
+            block_gpu()
             cur["kind"], cur["li"] = "pool", -1
             B.gf_pool_activation_batch(pool_batches[i % nsets], s)
             for li in reversed(range(len(bs))):
@@ -559,6 +568,8 @@ def measure(args, c, dtype, r, exact_cache):
     pairs = []
     for rep in range(4):
         for k in range(nsets):
+            if k % 8 == 0:
+                block_gpu()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             enqueue_pool(sets[k][li_cal], st())
