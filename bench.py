@@ -833,8 +833,7 @@ def extras(args, cfg, dtype, r, sets, torch, B, T):
                 lb.x_q = torch.empty(s_["x_u"], dtype=torch.int8, device="cuda")
                 lb.gy_q = torch.empty(s_["gy_u"], dtype=torch.int8, device="cuda")
                 lb.w_q = torch.empty(s_["w"][:2], dtype=torch.int8, device="cuda")
-                lb.ws_q = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_WEIGHT_Q8),
-                                          B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_INPUT_Q8), 256),
+                lb.ws_q = torch.empty(max(B.gf_workspace_bytes(lb.d, B.GF_OP_BWD_FILTERED_Q8), 256),
                                       dtype=torch.uint8, device="cuda")
         # step sizes: max|.| / 127 of the reduced maps and of the kernel sum (the caller's choice; formed
         # once here from the floating-point maps of the first buffer set, outside the timed region)
@@ -847,18 +846,17 @@ def extras(args, cfg, dtype, r, sets, torch, B, T):
             dg = float(gy_u.float().abs().max()) / 127.0
             dw = float(lb.w.float().sum(dim=(2, 3)).abs().max()) / 127.0
             deltas.append((dx or 1.0, dg or 1.0, dw or 1.0))
+        pool_q = {id(bs): B.PoolBatchQ8([lb.d for lb in bs], [P(lb.x) for lb in bs], [1.0 / dl[0] for dl in deltas],
+                                        [P(lb.x_q) for lb in bs]) for bs in sets}
 
         def step_q8(bufset):
             s = st()
-            for li, lb in enumerate(bufset):
-                B.gf_pool_activation_q8(lb.d, P(lb.x), 1.0 / deltas[li][0], P(lb.x_q), s)
+            B.gf_pool_activation_batch_q8(pool_q[id(bufset)], s)
             for li in reversed(range(len(bufset))):
                 lb = bufset[li]
                 dx, dg, dw = deltas[li]
-                B.gf_filter_grad_q8(lb.d, P(lb.gy), 1.0 / dg, P(lb.gy_q), s)
-                B.gf_kernel_sum_q8(lb.d, P(lb.w), 1.0 / dw, P(lb.w_q), s)
-                B.gf_conv_bwd_weight_q8(lb.d, P(lb.x_q), P(lb.gy_q), dx * dg, P(lb.g_w), P(lb.ws_q), lb.ws_q.numel(), s)
-                B.gf_conv_bwd_input_q8(lb.d, P(lb.gy_q), P(lb.w_q), dg * dw, P(lb.g_x), False, P(lb.ws_q), lb.ws_q.numel(), s)
+                B.gf_conv_bwd_filtered_q8(lb.d, P(lb.gy), 1.0 / dg, P(lb.x_q), P(lb.w), 1.0 / dw, dx * dg, dg * dw, 0,
+                                          P(lb.g_w), P(lb.g_x), P(lb.ws_q), lb.ws_q.numel(), s)
 
         qms = run(step_q8)
         out["q8_block"] = {
@@ -866,8 +864,9 @@ def extras(args, cfg, dtype, r, sets, torch, B, T):
             "arithmetic": "int8 codes, int32 / int64 sums, one fp32 scaling",
             "stored_activation_bytes_per_step": int(sum(lb.x_q.numel() for lb in one)),
             "stored_activation_bytes_per_step_float_path": int(sum(lb.x_u.numel() * lb.x_u.element_size() for lb in one)),
-            "note": "plain launches; per layer gf_pool_activation_q8, then gf_filter_grad_q8, gf_kernel_sum_q8, "
-                    "gf_conv_bwd_weight_q8 and gf_conv_bwd_input_q8 (full-resolution g_x in the storage type)"}
+            "note": "plain launches; gf_pool_activation_batch_q8 over all layers, then per layer gf_conv_bwd_filtered_q8 "
+                    "(filter and kernel-sum codes in one launch, Eq. 5 and Eq. 3 on codes; full-resolution g_x in the "
+                    "storage type)"}
     return out
 
 

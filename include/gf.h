@@ -84,7 +84,8 @@ typedef enum gf_op {
   GF_OP_BWD_CHAINED = 4,
   GF_OP_FILTER_SNR = 5,
   GF_OP_BWD_WEIGHT_Q8 = 6,
-  GF_OP_BWD_INPUT_Q8 = 7
+  GF_OP_BWD_INPUT_Q8 = 7,
+  GF_OP_BWD_FILTERED_Q8 = 8
 } gf_op;
 
 /* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
@@ -247,6 +248,12 @@ gf_status gf_filter_grad_q8(const gf_conv_desc* desc, const void* g_y, float inv
 gf_status gf_pool_activation_q8(const gf_conv_desc* desc, const void* x, float inv_delta, int8_t* x_q,
                                 void* stream);
 
+/* gf_pool_activation_q8 for `count` layers (1 ... 4096) in one launch; host arrays as in
+ * gf_pool_activation_batch plus one step-size reciprocal per layer.  All layers must have the same
+ * dtype (else GF_ERR_UNSUPPORTED).  x_q[i] is bit-identical to gf_pool_activation_q8's. */
+gf_status gf_pool_activation_batch_q8(int32_t count, const gf_conv_desc* descs, const void* const* x,
+                                      const float* inv_delta, int8_t* const* x_q, void* stream);
+
 /* S2 with code output: w_q [C_out, C_in/groups] = codes of the spatial kernel sums (text after Eq. 3). */
 gf_status gf_kernel_sum_q8(const gf_conv_desc* desc, const void* w, float inv_delta, int8_t* w_q,
                            void* stream);
@@ -261,6 +268,19 @@ gf_status gf_conv_bwd_weight_q8(const gf_conv_desc* desc, const int8_t* x_q, con
  * reduced_out != 0, one value per patch is written ([N, C_in, H_p, W_p]).  ws: GF_OP_BWD_INPUT_Q8. */
 gf_status gf_conv_bwd_input_q8(const gf_conv_desc* desc, const int8_t* gy_q, const int8_t* w_q, float scale,
                                void* g_x, int reduced_out, void* ws, size_t ws_bytes, void* stream);
+
+/* The backward of a layer on codes in one call: gy_q = codes of the patch means of g_y (step size
+ * 1 / inv_delta_gy), w_q = codes of the kernel sums of w (1 / inv_delta_w), then Eq. 5 on x_q and gy_q
+ * (scale_w = step of x_q times step of gy_q) and Eq. 3 on gy_q and w_q (scale_x = step of gy_q times
+ * step of w_q) at full resolution -- the results of gf_filter_grad_q8, gf_kernel_sum_q8,
+ * gf_conv_bwd_weight_q8 and gf_conv_bwd_input_q8 called one after the other, bit for bit, in fewer
+ * launches (the kernel sums ride along with the filter launch).  x_q comes from gf_pool_activation_q8
+ * at forward time.  gy_q may be NULL (the codes then live in the workspace only).
+ * ws: gf_workspace_bytes(GF_OP_BWD_FILTERED_Q8). */
+gf_status gf_conv_bwd_filtered_q8(const gf_conv_desc* desc, const void* g_y, float inv_delta_gy,
+                                  const int8_t* x_q, const void* w, float inv_delta_w, float scale_w,
+                                  float scale_x, int8_t* gy_q, float* g_w, void* g_x, void* ws,
+                                  size_t ws_bytes, void* stream);
 
 /* Vanilla back-propagation of the layer (Sec. 3.1): g_w = g_y (F) x and
  * g_x = g_y (*) rot180(w), zero padding, with stride, dilation and groups.

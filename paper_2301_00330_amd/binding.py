@@ -18,7 +18,7 @@ GF_ERR_NULL, GF_ERR_BAD_DESC, GF_ERR_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE
 GF_F32, GF_BF16 = 0, 1
 GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BWD_CHAINED = 0, 1, 2, 3, 4
 GF_OP_FILTER_SNR = 5
-GF_OP_BWD_WEIGHT_Q8, GF_OP_BWD_INPUT_Q8 = 6, 7
+GF_OP_BWD_WEIGHT_Q8, GF_OP_BWD_INPUT_Q8, GF_OP_BWD_FILTERED_Q8 = 6, 7, 8
 
 EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_batch",
            "gf_pool_activation_mask", "gf_filter_grad",
@@ -27,7 +27,7 @@ EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_
            "gf_conv_bwd_chained",
            "gf_conv_bwd_exact",
            "gf_filter_grad_q8", "gf_pool_activation_q8", "gf_kernel_sum_q8", "gf_conv_bwd_weight_q8",
-           "gf_conv_bwd_input_q8",
+           "gf_conv_bwd_input_q8", "gf_conv_bwd_filtered_q8", "gf_pool_activation_batch_q8",
            "gf_cost_model",
            "gf_status_string", "gf_version", "gf_set_launch_observer")
 
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
         L.gf_workspace_bytes.argtypes = [dp, C.c_int, C.POINTER(C.c_size_t)]
         L.gf_pool_activation.argtypes = [dp, vp, vp, vp]
         L.gf_pool_activation_batch.argtypes = [C.c_int32, dp, C.POINTER(vp), C.POINTER(vp), vp]
+        L.gf_pool_activation_batch_q8.argtypes = [C.c_int32, dp, C.POINTER(vp), C.POINTER(C.c_float), C.POINTER(vp), vp]
         L.gf_filter_grad.argtypes = [dp, vp, vp, vp]
         L.gf_filter_grad_snr.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_weight.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -108,6 +109,8 @@ def lib() -> C.CDLL:
         L.gf_kernel_sum_q8.argtypes = [dp, vp, C.c_float, vp, vp]
         L.gf_conv_bwd_weight_q8.argtypes = [dp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_input_q8.argtypes = [dp, vp, vp, C.c_float, vp, C.c_int, vp, C.c_size_t, vp]
+        L.gf_conv_bwd_filtered_q8.argtypes = [dp, vp, C.c_float, vp, vp, C.c_float, C.c_float, C.c_float, vp, vp, vp,
+                                              vp, C.c_size_t, vp]
         L.gf_cost_model.argtypes = [dp, C.POINTER(_Cost)]
         L.gf_status_string.argtypes = [C.c_int]
         L.gf_status_string.restype = C.c_char_p
@@ -190,6 +193,21 @@ def gf_pool_activation_batch(batch: PoolBatch, stream: int = 0):
     _chk(lib().gf_pool_activation_batch(batch.n, batch.descs, batch.xs, batch.x_us, stream), "gf_pool_activation_batch")
 
 
+class PoolBatchQ8(PoolBatch):
+    """Marshalled arguments of gf_pool_activation_batch_q8: PoolBatch plus one step-size reciprocal per layer
+    (x_us then holds the int8 code tensors)."""
+
+    def __init__(self, descs, xs, inv_deltas, x_qs):
+        super().__init__(descs, xs, x_qs)
+        assert len(inv_deltas) == self.n
+        self.inv = (C.c_float * max(self.n, 1))(*inv_deltas)
+
+
+def gf_pool_activation_batch_q8(batch: PoolBatchQ8, stream: int = 0):
+    _chk(lib().gf_pool_activation_batch_q8(batch.n, batch.descs, batch.xs, batch.inv, batch.x_us, stream),
+         "gf_pool_activation_batch_q8")
+
+
 def gf_filter_grad(d: ConvDesc, g_y: int, gy_u: int, stream: int = 0):
     cd = d.c()
     _chk(lib().gf_filter_grad(C.byref(cd), g_y, gy_u, stream), "gf_filter_grad")
@@ -270,6 +288,14 @@ def gf_conv_bwd_weight_q8(d: ConvDesc, x_q: int, gy_q: int, scale: float, g_w: i
     cd = d.c()
     _chk(lib().gf_conv_bwd_weight_q8(C.byref(cd), x_q, gy_q, scale, g_w, ws, ws_bytes, stream),
          "gf_conv_bwd_weight_q8")
+
+
+def gf_conv_bwd_filtered_q8(d: ConvDesc, g_y: int, inv_delta_gy: float, x_q: int, w: int, inv_delta_w: float,
+                            scale_w: float, scale_x: float, gy_q: int, g_w: int, g_x: int, ws: int, ws_bytes: int,
+                            stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_conv_bwd_filtered_q8(C.byref(cd), g_y, inv_delta_gy, x_q, w, inv_delta_w, scale_w, scale_x, gy_q,
+                                       g_w, g_x, ws, ws_bytes, stream), "gf_conv_bwd_filtered_q8")
 
 
 def gf_conv_bwd_input_q8(d: ConvDesc, gy_q: int, w_q: int, scale: float, g_x: int, reduced_out: bool, ws: int,

@@ -124,6 +124,17 @@ static size_t ws_chained(const Geom& g, size_t* off_i) {
   return o + (a > b ? a : b);
 }
 
+// one-call backward on codes: [gy_q if the caller keeps none][w_q][weight-gradient slabs][input-gradient map]
+static size_t ws_filtered_q8(const Geom& g, bool own_gyq, size_t* off_wq, size_t* off_w, size_t* off_i) {
+  size_t o = own_gyq ? align256((size_t)g.N * g.Co * g.P) : 0;
+  if (off_wq) *off_wq = o;
+  o += align256((size_t)g.Co * g.Cg);
+  if (off_w) *off_w = o;
+  o += align256(ws_bwd_weight_q8(g));
+  if (off_i) *off_i = o;
+  return o + ws_bwd_input_q8(g, false);
+}
+
 static size_t ws_need(const Geom& g, int op, bool reduced_out) {
   switch (op) {
     case GF_OP_BWD_FILTERED:
@@ -136,6 +147,8 @@ static size_t ws_need(const Geom& g, int op, bool reduced_out) {
       return ws_bwd_weight_q8(g);
     case GF_OP_BWD_INPUT_Q8:
       return ws_bwd_input_q8(g, reduced_out);
+    case GF_OP_BWD_FILTERED_Q8:
+      return ws_filtered_q8(g, true, nullptr, nullptr, nullptr);
     case GF_OP_BWD_WEIGHT:
       return g.r == 1 ? ws_exact(g, true, false) : dense_ok(g) ? ws_dense(g, true, false) : ws_bwd_weight(g);
     case GF_OP_BWD_INPUT:
@@ -196,7 +209,7 @@ gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int
 gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
   if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT &&
       op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED && op != GF_OP_FILTER_SNR &&
-      op != GF_OP_BWD_WEIGHT_Q8 && op != GF_OP_BWD_INPUT_Q8)
+      op != GF_OP_BWD_WEIGHT_Q8 && op != GF_OP_BWD_INPUT_Q8 && op != GF_OP_BWD_FILTERED_Q8)
     return GF_ERR_BAD_DESC;
   if (!desc) return GF_ERR_NULL;
   gf_conv_desc d1;
@@ -250,7 +263,7 @@ gf_status gf_pool_activation_batch(int32_t count, const gf_conv_desc* descs, con
       if (rc) return rc;
       continue;
     }
-    jobs.push_back(PoolJob{x[i], x_u[i], planes, g.H, g.W, g.rx});
+    jobs.push_back(PoolJob{x[i], x_u[i], planes, g.H, g.W, g.rx, 0.f});
   }
   if (jobs.empty()) return GF_OK;
   return dev(launch_pool_batch(jobs.data(), (int)jobs.size(), gs[0].dtype, st));
@@ -298,6 +311,26 @@ gf_status gf_pool_activation_q8(const gf_conv_desc* desc, const void* x, float i
   if (!aligned16(x) || !aligned16(x_q)) return GF_ERR_UNSUPPORTED;
   return dev(launch_patch_reduce_q8(x, x_q, (long)g.N * g.Ci, g.H, g.W, g.rx, false, inv_delta, g.dtype,
                                     static_cast<hipStream_t>(stream)));
+}
+
+gf_status gf_pool_activation_batch_q8(int32_t count, const gf_conv_desc* descs, const void* const* x,
+                                      const float* inv_delta, int8_t* const* x_q, void* stream) {
+  if (count < 1 || count > 4096) return GF_ERR_BAD_DESC;
+  if (!descs || !x || !inv_delta || !x_q) return GF_ERR_NULL;
+  // every layer is validated before anything is enqueued
+  std::vector<PoolJob> jobs((size_t)count);
+  int dtype = GF_F32;
+  for (int i = 0; i < count; ++i) {
+    Geom g;
+    gf_status rc = q8_geom(&descs[i], inv_delta[i], &g);
+    if (rc) return rc;
+    if (!x[i] || !x_q[i]) return GF_ERR_NULL;
+    if (!aligned16(x[i]) || !aligned16(x_q[i])) return GF_ERR_UNSUPPORTED;
+    if (i == 0) dtype = g.dtype;
+    if (g.dtype != dtype) return GF_ERR_UNSUPPORTED;
+    jobs[(size_t)i] = PoolJob{x[i], x_q[i], (long)g.N * g.Ci, g.H, g.W, g.rx, inv_delta[i]};
+  }
+  return dev(launch_pool_batch(jobs.data(), count, dtype, static_cast<hipStream_t>(stream)));
 }
 
 gf_status gf_kernel_sum_q8(const gf_conv_desc* desc, const void* w, float inv_delta, int8_t* w_q,
@@ -559,6 +592,34 @@ static gf_status chained_body(const Geom& g, const void* gy_u, const void* x_u, 
   rc = dev(launch_gf_bwd_weight(g, x_u, gy_u, g_w, wsb, st));
   if (rc) return rc;
   return dev(launch_gf_bwd_input(g, gy_u, w, g_x, reduced_out != 0, wsb + off_i, st));
+}
+
+gf_status gf_conv_bwd_filtered_q8(const gf_conv_desc* desc, const void* g_y, float inv_delta_gy,
+                                  const int8_t* x_q, const void* w, float inv_delta_w, float scale_w,
+                                  float scale_x, int8_t* gy_q, float* g_w, void* g_x, void* ws,
+                                  size_t ws_bytes, void* stream) {
+  Geom g;
+  gf_status rc = q8_geom(desc, inv_delta_gy, &g);
+  if (rc) return rc;
+  for (float f : {inv_delta_w, scale_w, scale_x})
+    if (!(f > 0.f) || f > 3.0e38f) return GF_ERR_BAD_DESC;
+  if (!g_y || !x_q || !w || !g_w || !g_x) return GF_ERR_NULL;
+  if (!aligned16(g_y) || !aligned16(x_q) || !aligned16(w) || !aligned16(gy_q) || !aligned16(g_w) || !aligned16(g_x))
+    return GF_ERR_UNSUPPORTED;
+  size_t off_wq = 0, off_w = 0, off_i = 0;
+  rc = check_ws(ws_filtered_q8(g, gy_q == nullptr, &off_wq, &off_w, &off_i), ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* wsb = static_cast<char*>(ws);
+  int8_t* gq = gy_q ? gy_q : reinterpret_cast<int8_t*>(wsb);
+  int8_t* wq = reinterpret_cast<int8_t*>(wsb + off_wq);
+  // the codes of the kernel sums ride along with the filter launch
+  KsumJob ksum = {w, wq, g.Co * g.Cg, g.KK, inv_delta_w};
+  rc = dev(launch_patch_reduce_q8(g_y, gq, (long)g.N * g.Co, g.Hy, g.Wy, g.r, true, inv_delta_gy, g.dtype, st, &ksum));
+  if (rc) return rc;
+  rc = dev(launch_bwd_weight_q8(g, x_q, gq, scale_w, g_w, wsb + off_w, st));
+  if (rc) return rc;
+  return dev(launch_bwd_input_q8(g, gq, wq, scale_x, g_x, false, wsb + off_i, st));
 }
 
 gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void* w,

@@ -134,11 +134,12 @@ struct FastDiv {
 // ---- launchers; each returns the hipError_t of its launches ----------------
 
 // S2 as a side job of another launch: out[e] = spatial sum of kernel e (pairs of them, KK taps
-// each), rounded to the storage type.
+// each), rounded to the storage type -- or, with q_inv > 0, its signed 8-bit code (one byte per kernel).
 struct KsumJob {
   const void* w;
   void* out;
   int pairs, KK;
+  float q_inv;
 };
 
 // S0 / S1: out[plane, hp, wp] = sum or mean of in[plane] over q x q patches.  With `ksum` the
@@ -152,13 +153,15 @@ struct PoolJob {
   void* out;
   long planes;
   int H, W, q;
+  float q_inv;   // > 0 (in every job of a call, or in none): out holds signed 8-bit codes, step size 1 / q_inv
 };
 hipError_t launch_pool_batch(const PoolJob* jobs, int count, int dtype, hipStream_t st);
 
 // ---- 8-bit codes (gf_q8.hip; the reductions with code output live in gf_reduce.hip) ----
 // S0 / S1 with the result as signed 8-bit codes: round_half_even(value * inv_delta), clipped to +-127
+// (with `ksum`: the kernel sums ride along, as in launch_patch_reduce)
 hipError_t launch_patch_reduce_q8(const void* in, int8_t* out_q, long planes, int H, int W, int q, bool mean,
-                                  float inv_delta, int dtype, hipStream_t st);
+                                  float inv_delta, int dtype, hipStream_t st, const KsumJob* ksum = nullptr);
 bool q8_shape_ok(const Geom& g);
 hipError_t launch_kernel_sum_q8(const Geom& g, const void* w, float inv_delta, int8_t* w_q, hipStream_t st);
 size_t ws_bwd_weight_q8(const Geom& g);

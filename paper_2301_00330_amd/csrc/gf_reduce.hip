@@ -38,6 +38,7 @@ struct ReduceArgs {
   const void* ks_w;
   void* ks_out;
   int ks_pairs, ks_KK, ks_block0;
+  float ks_qinv;   // > 0: the kernel sums are written as signed 8-bit codes
   // noise figures of the filter (kStats kernels): per-block partial sums {sum v^2, sum (v - patch mean)^2}
   float2* stats_part;
   // kMask kernels: out2[patch] = fraction of the patch's in-bounds elements with 0 < v < mask_hi
@@ -69,8 +70,11 @@ template <class T>
 __device__ __forceinline__ bool ksum_side_job(const ReduceArgs& a) {
   if (a.ks_pairs == 0 || (int)blockIdx.x < a.ks_block0) return false;
   const int e = ((int)blockIdx.x - a.ks_block0) * kThreads + threadIdx.x;
-  if (e < a.ks_pairs)
-    static_cast<T*>(a.ks_out)[e] = from_f32<T>(kernel_sum_of(static_cast<const T*>(a.ks_w), e, a.ks_KK));
+  if (e < a.ks_pairs) {
+    const float v = kernel_sum_of(static_cast<const T*>(a.ks_w), e, a.ks_KK);
+    if (a.ks_qinv > 0.f) static_cast<int8_t*>(a.ks_out)[e] = q8_code(v, a.ks_qinv);
+    else static_cast<T*>(a.ks_out)[e] = from_f32<T>(v);
+  }
   return true;
 }
 
@@ -329,20 +333,20 @@ struct BatchArgs {
 };
 static_assert(sizeof(BatchArgs) <= 3584, "the job table travels as a kernel argument");
 
-template <class T>
+template <class T, int MODE = kPlain>
 __global__ __launch_bounds__(kThreads) void patch_reduce_batch_k(BatchArgs b) {
   int j = 0;
   while (j + 1 < b.njobs && (int)blockIdx.x >= b.first_block[j + 1]) ++j;
   const int blk = (int)blockIdx.x - b.first_block[j];
   const ReduceArgs& a = b.job[j];
   switch (b.variant[j]) {
-    case kVarRows2: rows_body<T, 2, 1, kPlain>(a, blk); break;
-    case kVarRows4: rows_body<T, 4, 1, kPlain>(a, blk); break;
-    case kVarRows8: rows_body<T, 8, 1, kPlain>(a, blk); break;
-    case kVarLds2: lds_body<T, 2, kPlain>(a, blk); break;
-    case kVarLds4: lds_body<T, 4, kPlain>(a, blk); break;
-    case kVarLds8: lds_body<T, 8, kPlain>(a, blk); break;
-    default: lds_body<T, 0, kPlain>(a, blk); break;
+    case kVarRows2: rows_body<T, 2, 1, MODE>(a, blk); break;
+    case kVarRows4: rows_body<T, 4, 1, MODE>(a, blk); break;
+    case kVarRows8: rows_body<T, 8, 1, MODE>(a, blk); break;
+    case kVarLds2: lds_body<T, 2, MODE>(a, blk); break;
+    case kVarLds4: lds_body<T, 4, MODE>(a, blk); break;
+    case kVarLds8: lds_body<T, MODE == kPlain ? 8 : 0, MODE>(a, blk); break;   // as the single-tensor launch picks
+    default: lds_body<T, 0, MODE>(a, blk); break;
   }
 }
 
@@ -558,9 +562,12 @@ hipError_t launch_pool_mask(const void* x, void* x_u, void* m_u, long planes, in
 }
 
 hipError_t launch_patch_reduce_q8(const void* in, int8_t* out_q, long planes, int H, int W, int q, bool mean,
-                                  float inv_delta, int dtype, hipStream_t st) {
+                                  float inv_delta, int dtype, hipStream_t st, const KsumJob* ksum) {
   ReduceArgs a = {};
   int blocks = 0;
+  if (ksum) {
+    a.ks_w = ksum->w; a.ks_out = ksum->out; a.ks_pairs = ksum->pairs; a.ks_KK = ksum->KK; a.ks_qinv = ksum->q_inv;
+  }
   a.in = in; a.out = out_q; a.q_inv = inv_delta; a.H = H; a.W = W; a.q = q;
   a.Hp = cdiv(H, q); a.Wp = cdiv(W, q);
   a.total_in = (int)(planes * H * W);
@@ -576,7 +583,7 @@ hipError_t launch_patch_reduce(const void* in, void* out, long planes, int H, in
   ReduceArgs a = {};
   int blocks = 0;
   if (ksum) {
-    a.ks_w = ksum->w; a.ks_out = ksum->out; a.ks_pairs = ksum->pairs; a.ks_KK = ksum->KK;
+    a.ks_w = ksum->w; a.ks_out = ksum->out; a.ks_pairs = ksum->pairs; a.ks_KK = ksum->KK; a.ks_qinv = ksum->q_inv;
   }
   a.in = in;
   a.out = out;
@@ -625,6 +632,7 @@ static bool plan_plain(ReduceArgs& a, int* variant, int* blocks, size_t* lds) {
 
 template <class T>
 static hipError_t batch_t(const PoolJob* jobs, int count, hipStream_t st) {
+  const bool codes = count > 0 && jobs[0].q_inv > 0.f;   // all jobs of a call write codes, or none does
   int i = 0;
   while (i < count) {
     BatchArgs b = {};
@@ -638,14 +646,17 @@ static hipError_t batch_t(const PoolJob* jobs, int count, hipStream_t st) {
       a.total_in = (int)(pj.planes * pj.H * pj.W);
       a.total_strips = (int)(pj.planes * a.Hp);
       a.mean = 0;
+      a.q_inv = pj.q_inv;
       a.d_hp = FastDiv((uint32_t)a.Hp);
       a.d_wp = FastDiv((uint32_t)a.Wp);
       int variant = 0, blocks = 0;
       size_t lds = 0;
       if (!plan_plain<T>(a, &variant, &blocks, &lds)) {   // a strip larger than LDS: a launch of its own
         if (b.njobs > 0) break;
-        hipError_t e = launch_patch_reduce(pj.in, pj.out, pj.planes, pj.H, pj.W, pj.q, false,
-                                           sizeof(T) == 2 ? GF_BF16 : GF_F32, st, nullptr);
+        const int dt = sizeof(T) == 2 ? GF_BF16 : GF_F32;
+        hipError_t e = codes ? launch_patch_reduce_q8(pj.in, static_cast<int8_t*>(pj.out), pj.planes, pj.H, pj.W, pj.q,
+                                                      false, pj.q_inv, dt, st, nullptr)
+                             : launch_patch_reduce(pj.in, pj.out, pj.planes, pj.H, pj.W, pj.q, false, dt, st, nullptr);
         if (e != hipSuccess) return e;
         ++i;
         continue;
@@ -660,7 +671,8 @@ static hipError_t batch_t(const PoolJob* jobs, int count, hipStream_t st) {
     }
     if (b.njobs == 0) continue;
     b.first_block[b.njobs] = blocks_total;
-    GF_LAUNCH(patch_reduce_batch_k<T>, dim3(blocks_total), dim3(kThreads), lds_max, st, b);
+    if (codes) GF_LAUNCH((patch_reduce_batch_k<T, kQ8>), dim3(blocks_total), dim3(kThreads), lds_max, st, b);
+    else GF_LAUNCH((patch_reduce_batch_k<T, kPlain>), dim3(blocks_total), dim3(kThreads), lds_max, st, b);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -98,6 +98,18 @@ def pool_activation_batch(descs, xs):
     return outs
 
 
+def pool_activation_batch_q8(descs, xs, inv_deltas):
+    """x_q of several layers from one launch (gf_pool_activation_batch_q8)."""
+    outs = []
+    for d, x in zip(descs, xs):
+        s = shapes(d)
+        _check(x, d, s["x"], "x")
+        outs.append(torch.empty(s["x_u"], dtype=torch.int8, device=x.device))
+    B.gf_pool_activation_batch_q8(B.PoolBatchQ8(descs, [B.ptr(x) for x in xs], list(inv_deltas), [B.ptr(o) for o in outs]),
+                                  _stream())
+    return outs
+
+
 def pool_activation_mask(d: B.ConvDesc, x: torch.Tensor, hi: float = float("inf")):
     """(x_u, m_u): patch sums of x and the share of each patch with 0 < x < hi (the gradient mask of the
     ReLU / clipped ReLU that produced x, averaged over the patch)."""
@@ -237,6 +249,23 @@ def conv_bwd_weight_q8(d: B.ConvDesc, x_q: torch.Tensor, gy_q: torch.Tensor, sca
     p, n = _ws(x_q, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_WEIGHT_Q8))
     B.gf_conv_bwd_weight_q8(d, B.ptr(x_q), B.ptr(gy_q), scale, B.ptr(g_w), p, n, _stream())
     return g_w
+
+
+def conv_bwd_filtered_q8(d: B.ConvDesc, g_y: torch.Tensor, inv_delta_gy: float, x_q: torch.Tensor, w: torch.Tensor,
+                         inv_delta_w: float, scale_w: float, scale_x: float, want_gyq: bool = False,
+                         ws: Workspace | None = None):
+    """Filter with code output + kernel-sum codes + Eq. 5 and Eq. 3 on codes in one call: (g_w, g_x[, gy_q])."""
+    s = shapes(d)
+    _check(g_y, d, s["g_y"], "g_y")
+    _check(x_q, d, s["x_u"], "x_q", torch.int8)
+    _check(w, d, s["w"], "w")
+    g_w = torch.empty(s["w"], dtype=torch.float32, device=g_y.device)
+    g_x = torch.empty(s["x"], dtype=_tdtype(d), device=g_y.device)
+    gy_q = torch.empty(s["gy_u"], dtype=torch.int8, device=g_y.device) if want_gyq else None
+    p, n = _ws(g_y, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED_Q8))
+    B.gf_conv_bwd_filtered_q8(d, B.ptr(g_y), inv_delta_gy, B.ptr(x_q), B.ptr(w), inv_delta_w, scale_w, scale_x,
+                              B.ptr(gy_q) if want_gyq else 0, B.ptr(g_w), B.ptr(g_x), p, n, _stream())
+    return (g_w, g_x, gy_q) if want_gyq else (g_w, g_x)
 
 
 def conv_bwd_input_q8(d: B.ConvDesc, gy_q: torch.Tensor, w_q: torch.Tensor, scale: float,

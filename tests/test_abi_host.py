@@ -246,6 +246,26 @@ def test_q8_entry_errors(lib):
             with pytest.raises(B.GfError) as ei:
                 call()
             assert ei.value.status == B.GF_ERR_BAD_DESC
+    # the one-call entry checks each of its four factors the same way, then pointers, then the workspace
+    for k in range(4):
+        for bad in (0.0, -1.0, float("nan"), float("inf")):
+            f = [1.0, 1.0, 1.0, 1.0]
+            f[k] = bad
+            with pytest.raises(B.GfError) as ei:
+                B.gf_conv_bwd_filtered_q8(d, FAKE, f[0], FAKE, FAKE, f[1], f[2], f[3], 0, FAKE, FAKE, FAKE, 1 << 30)
+            assert ei.value.status == B.GF_ERR_BAD_DESC
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_q8(d, FAKE, 1.0, 0, FAKE, 1.0, 1.0, 1.0, 0, FAKE, FAKE, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_NULL
+    need = B.gf_workspace_bytes(d, B.GF_OP_BWD_FILTERED_Q8)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    assert need >= d.N * d.C_out * Hp * Wp + d.C_out * (d.C_in // d.groups)   # codes of g_y and of the kernel sums
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_q8(d, FAKE, 1.0, FAKE, FAKE, 1.0, 1.0, 1.0, 0, FAKE, FAKE, FAKE, need - 1)
+    assert ei.value.status == B.GF_ERR_WORKSPACE
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_filtered_q8(d.with_(r=1), FAKE, 1.0, FAKE, FAKE, 1.0, 1.0, 1.0, 0, FAKE, FAKE, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
     # codes stand for reduced maps: r = 1 has none
     with pytest.raises(B.GfError) as ei:
         B.gf_filter_grad_q8(d.with_(r=1), FAKE, 1.0, FAKE)
@@ -302,3 +322,15 @@ def test_pool_batch_host_checks(lib):
     with pytest.raises(B.GfError) as ei:
         B.gf_pool_activation_batch(B.PoolBatch([d, d], [FAKE, FAKE + 4], [FAKE, FAKE]))
     assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    # the same on 8-bit codes, plus the step-size reciprocal of every layer
+    Q = B.PoolBatchQ8
+    for batch, want in ((Q([], [], [], []), B.GF_ERR_BAD_DESC),
+                        (Q([d, d], [FAKE, 0], [1.0, 1.0], [FAKE, FAKE]), B.GF_ERR_NULL),
+                        (Q([d, d], [FAKE, FAKE], [1.0, 0.0], [FAKE, FAKE]), B.GF_ERR_BAD_DESC),
+                        (Q([d, d], [FAKE, FAKE], [1.0, float("nan")], [FAKE, FAKE]), B.GF_ERR_BAD_DESC),
+                        (Q([d, d.with_(dtype=B.GF_BF16)], [FAKE, FAKE], [1.0, 1.0], [FAKE, FAKE]), B.GF_ERR_UNSUPPORTED),
+                        (Q([d, d.with_(r=1)], [FAKE, FAKE], [1.0, 1.0], [FAKE, FAKE]), B.GF_ERR_UNSUPPORTED),
+                        (Q([d, d], [FAKE, FAKE], [1.0, 1.0], [FAKE, FAKE + 4]), B.GF_ERR_UNSUPPORTED)):
+        with pytest.raises(B.GfError) as ei:
+            B.gf_pool_activation_batch_q8(batch)
+        assert ei.value.status == want

@@ -1028,6 +1028,70 @@ def test_q8_contractions_bit_exact(oracle, case, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_q8_pool_batch_is_bit_identical(oracle, dtype):
+    """gf_pool_activation_batch_q8: the codes of every layer equal gf_pool_activation_q8's bit for bit
+    (REDUCE_CASES: all kernel variants, ragged maps, strips larger than LDS), and agree with the oracle's."""
+    descs, xs, invs = [], [], []
+    for k, (N, C, H, W, r, s) in enumerate(REDUCE_CASES):
+        d = mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype)
+        x = randn((N, C, H, W), 200 + k, dtype, relu=True)
+        ref = oracle.pool_activation(odesc(oracle, d), to64(x))
+        descs.append(d); xs.append(x); invs.append(127.0 / float(np.abs(ref).max()))
+    xg = [x.cuda() for x in xs]
+    outs = T.pool_activation_batch_q8(descs, xg, invs)
+    singles = [T.pool_activation_q8(d, x, inv) for d, x, inv in zip(descs, xg, invs)]
+    torch.cuda.synchronize()
+    for d, x, inv, o, s1 in zip(descs, xs, invs, outs, singles):
+        assert torch.equal(o, s1)
+        check_codes(oracle, o, oracle.pool_activation(odesc(oracle, d), to64(x)), inv, "x_q")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", Q8_LAYERS)
+def test_q8_one_call_backward(oracle, case, dtype):
+    """gf_conv_bwd_filtered_q8 = filter with code output (the kernel-sum codes riding along) + Eq. 5 + Eq. 3
+    on codes.  Bit for bit the results of the four separate entry points; the codes against the oracle's;
+    and, where the library's codes equal the oracle's (always on integer-coded inputs with whole patches),
+    both gradients bit for bit against the oracle's contractions of ITS codes."""
+    N, Ci, Co, H, W, K, s, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, s=s, p=K // 2, g=g, r=r, dtype=dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    rs = np.random.default_rng(97)
+    x_q = torch.from_numpy(rs.integers(-127, 128, (N, Ci, Hp, Wp)).astype(np.int8)).cuda()
+    whole = Hy % r == 0 and Wy % r == 0
+    for integer in ([False, True] if whole else [False]):
+        if integer:   # patch means are exact multiples of 1/4, kernel sums small integers: the codes do not
+            # depend on the order of any sum (ties round to even on both sides)
+            gy = WL.integer_coded((N, Co, Hy, Wy), 61, lo=-8, hi=8, dtype=dtype)
+            w = WL.integer_coded((Co, Ci // g, K, K), 62, lo=-1, hi=1, dtype=dtype)
+            inv_g, inv_w = 1.0, 1.0
+        else:
+            gy = randn((N, Co, Hy, Wy), 63, dtype)
+            w = randn((Co, Ci // g, K, K), 64, dtype, scale=0.2)
+            inv_g = 127.0 / float(np.abs(oracle.filter_grad(od, to64(gy))).max())
+            inv_w = 127.0 / float(np.abs(oracle.kernel_sum(od, to64(w))).max())
+        sw, sx = 2.0e-5 / inv_g, 1.0 / (inv_g * inv_w)
+        g_w, g_x, gy_q = T.conv_bwd_filtered_q8(d, gy.cuda(), inv_g, x_q, w.cuda(), inv_w, sw, sx, want_gyq=True)
+        g_w0, g_x0 = T.conv_bwd_filtered_q8(d, gy.cuda(), inv_g, x_q, w.cuda(), inv_w, sw, sx)   # codes in the workspace
+        s_gyq, s_wq = T.filter_grad_q8(d, gy.cuda(), inv_g), T.kernel_sum_q8(d, w.cuda(), inv_w)
+        s_gw, s_gx = T.conv_bwd_weight_q8(d, x_q, s_gyq, sw), T.conv_bwd_input_q8(d, s_gyq, s_wq, sx)
+        torch.cuda.synchronize()
+        assert torch.equal(gy_q, s_gyq) and torch.equal(g_w, s_gw) and torch.equal(g_x, s_gx)
+        assert torch.equal(g_w0, s_gw) and torch.equal(g_x0, s_gx)
+        ref_gq = oracle.filter_grad_q8(od, to64(gy), inv_g)
+        ref_wq = oracle.quantize_q8(oracle.kernel_sum(od, to64(w)), inv_w)
+        check_codes(oracle, gy_q, oracle.filter_grad(od, to64(gy)), inv_g, "gy_q")
+        check_codes(oracle, s_wq, oracle.kernel_sum(od, to64(w)), inv_w, "w_q")
+        same = np.array_equal(gy_q.cpu().numpy(), ref_gq) and np.array_equal(s_wq.cpu().numpy(), ref_wq)
+        assert same or not integer
+        if same:
+            xq = x_q.cpu().numpy()
+            assert torch.equal(g_w.cpu(), torch.from_numpy(oracle.bwd_weight_q8(od, xq, ref_gq, sw)))
+            assert torch.equal(g_x.cpu(), rounded(oracle.bwd_input_q8(od, ref_gq, ref_wq, sx), dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_q8_layer_end_to_end(oracle, dtype):
     """Config 2's layers, N = 4.  The library's codes are checked against the oracle's; the two
     contractions run on the ORACLE's codes and must match the oracle's contractions bit for bit; the
