@@ -536,7 +536,9 @@ def measure(args, c, dtype, r, exact_cache):
     # only waits (torch's device sleep, ~1.7 ms, no memory traffic), so that the step's launches and
     # events are all queued behind it before the first of them runs.
     def block_gpu():
-        torch.cuda._sleep(4_000_000)
+        sleep = getattr(torch.cuda, "_sleep", None)
+        if sleep is not None:
+            sleep(4_000_000)
 
     traced_steps = 3 * nsets if nsets <= 8 else nsets
     B.gf_set_launch_observer(observer)
