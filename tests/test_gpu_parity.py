@@ -1430,6 +1430,40 @@ def test_launch_observer_lists_the_kernels_of_a_call():
     assert len(seen) == n
 
 
+@pytest.mark.parametrize("case", [
+    # N  Ci  Co   H   W  K  s  r  dtype   two-launch dense path?
+    (4, 32, 48, 14, 14, 1, 1, 2, "f32", True),     # 49 patches: one image per column tile
+    (4, 32, 48, 14, 14, 3, 1, 2, "f32", True),     # ... also with a 3 x 3 kernel
+    (4, 32, 48, 7, 7, 1, 1, 2, "f32", True),       # 16 patches, 1 x 1 kernel, r_x = 2
+    (4, 32, 48, 7, 7, 3, 1, 2, "f32", False),      # 16 patches, 3 x 3 kernel: general path
+    (4, 32, 48, 14, 14, 3, 2, 2, "f32", False),    # 16 patches, r_x = 4
+    (4, 32, 48, 7, 7, 1, 1, 4, "f32", False),      # 4 patches: 16 images per column tile
+    (4, 32, 48, 14, 14, 1, 1, 2, "bf16", False),   # bf16 storage
+    (4, 32, 48, 28, 28, 1, 1, 2, "f32", False),    # planes of more than 256 pixels
+])
+def test_which_layers_take_the_two_launch_path(oracle, case):
+    """The dense small-map path is taken exactly for the shapes it was measured faster on; whichever path
+    runs, the result is the oracle's."""
+    N, Ci, Co, H, W, K, s, r, dtype, dense = case
+    d = mk(N, Ci, Co, H, W, K=K, s=s, p=K // 2, r=r, dtype=dtype)
+    od = odesc(oracle, d)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    x = randn((N, Ci, H, W), 5, dtype, relu=True)
+    w = randn((Co, Ci, K, K), 6, dtype, scale=0.1)
+    gy = randn((N, Co, Hy, Wy), 7, dtype)
+    x_u = T.pool_activation(d, x.cuda())
+    seen = []
+    B.gf_set_launch_observer(lambda name, phase, stream: seen.append(name) if phase == 0 else None)
+    try:
+        g_w, g_x, _ = T.conv_bwd_filtered(d, gy.cuda(), x_u, w.cuda(), want_gyu=False)
+    finally:
+        B.gf_set_launch_observer(None)
+    torch.cuda.synchronize()
+    assert (seen == ["dense_prep_k", "dense_gemm_k"]) == dense, seen
+    ref_gw, ref_gx, _, _ = oracle.gf_backward(od, to64(x), to64(w), to64(gy))
+    assert rel_err(g_w, ref_gw) <= TOL[dtype] and rel_err(g_x, ref_gx) <= TOL[dtype]
+
+
 # ---------------------------------------------------------------------------
 # activation pooling of several layers in one launch
 # ---------------------------------------------------------------------------
