@@ -580,21 +580,38 @@ def measure(args, c, dtype, r, exact_cache):
     torch.cuda.synchronize()
     cal_pair_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
     pair_overhead_us = max(0.0, cal_pair_us - cal_replay_us)
+    # Every traced step issues the same launches in the same order: the duration of launch number p of a
+    # step is the MEDIAN over the traced steps (a single disturbed step -- the box is shared with a
+    # host that does other things -- must not move a mean over 77 samples by a factor), and a kernel's
+    # average is the mean of those medians over its launches of a step.
+    per_step = len(trace) // traced_steps
+    assert per_step * traced_steps == len(trace), "every traced step must issue the same launches"
+    dur = [e0.elapsed_time(e1) * 1e3 for _, _, _, e0, e1 in trace]
+    med = []
+    for pos in range(per_step):
+        v = sorted(dur[pos::per_step])
+        med.append(v[len(v) // 2])
+        assert all(trace[pos + k * per_step][2] == trace[pos][2] for k in range(traced_steps))
+        worst = v[-1]
+        if worst > 3.0 * med[-1] + 20.0:
+            log(f"    note: launch {pos} of the step ({trace[pos][2]}) took {worst:.0f} us in one traced step, "
+                f"median {med[-1]:.1f} us over {traced_steps} steps; the median is reported")
     kernels = {}
-    for kind, li, name, e0, e1 in trace:
+    for pos in range(per_step):
+        kind, li, name, _, _ = trace[pos]
         k = kernels.setdefault(name, {"us": 0.0, "launches": 0, "bytes": 0.0, "flops": 0.0, "mfma": False})
-        k["us"] += e0.elapsed_time(e1) * 1e3
-        k["launches"] += 1
+        k["us"] += med[pos] * traced_steps
+        k["launches"] += traced_steps
         for prefix, keys, mfma in KERNEL_RULES:
             if name.startswith(prefix):
                 for key in keys:
                     if key == "bytes_reduce" and kind == "pool":     # the batch launch pools every layer
-                        k["bytes"] += sum(q["bytes_pool"] for q in cost)
+                        k["bytes"] += traced_steps * sum(q["bytes_pool"] for q in cost)
                     else:
-                        k["bytes"] += cost[li]["bytes_filter" if key == "bytes_reduce" else key]
+                        k["bytes"] += traced_steps * cost[li]["bytes_filter" if key == "bytes_reduce" else key]
                 if mfma:
                     k["mfma"] = True
-                    k["flops"] += cost[li]["flops_backward"] if len(keys) == 2 else cost[li]["flops_bwd_weight"]
+                    k["flops"] += traced_steps * (cost[li]["flops_backward"] if len(keys) == 2 else cost[li]["flops_bwd_weight"])
                 break
     klist = []
     for name, k in kernels.items():
@@ -617,7 +634,8 @@ def measure(args, c, dtype, r, exact_cache):
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4)}
     roofline.update({"avg_launch_us": dom["avg_launch_us"], "launches_per_step": dom["launches_per_step"],
                      "bytes_per_launch": dom["bytes_per_launch"], "flops_per_launch": dom["flops_per_launch"],
-                     "method": "events around every launch of the step's kernels (launch observer), minus what an event "
+                     "method": "events around every launch of the step's kernels (launch observer; per launch of the step the "
+                               "median over the traced steps), minus what an event "
                                "pair adds to a launch (the same single-launch call timed as event pairs and as back-to-back "
                                "graph replays)", "event_pair_overhead_us": round(pair_overhead_us, 2),
                      "traffic": traffic_from_profile(cfg.cfg_id, dtype, r, dom["kernel"])})
