@@ -200,6 +200,32 @@ def bwd_exact(d: Desc, x, w, g_y, want_gw: bool = True, want_gx: bool = True):
     return g_w, g_x
 
 
+def bwd_unique(d: Desc, x_u, gy_u, w, reduced_out: bool = False):
+    """'Fewer unique elements' alone (Sec. 4.2, the middle cost line of Fig. 3): the gradient map is
+    replaced by its one value per patch, but the K x K kernel is kept.  The backward then runs on the
+    r^2 times smaller maps as it stands:
+        g_w[co, ci, u, v] = sum_{n, hp, wp} x_u[n, ci, hp + u d - p, wp + v d - p] gy_u[n, co, hp, wp]
+        g_xu[n, ci, hp, wp] = sum_{co, u, v} w[co, ci, u, v] gy_u[n, co, hp - u d + p, wp - v d + p]
+    i.e. vanilla BP (Sec. 3.1) of the same kernel on the patch grid, x_u being the patch sums and
+    gy_u the patch means; every pixel of an input patch then receives its patch's g_xu (or, with
+    reduced_out, g_xu itself is returned).  Stride-1 layers whose padding keeps the map size only;
+    r = 1 is vanilla BP.  Returns (g_w, g_x)."""
+    if d.r == 1:
+        return bwd_exact(d, x_u, w, gy_u)
+    if d.stride != 1:
+        raise OracleError("bwd_unique: stride-1 layers only")
+    Hy, Wy, Hp, Wp = out_shape(d)
+    ds = Desc(N=d.N, C_in=d.C_in, C_out=d.C_out, H_in=Hp, W_in=Wp, K_h=d.K_h, K_w=d.K_w, stride=1,
+              pad=d.pad, dilation=d.dilation, groups=d.groups, r=1)
+    if out_shape(ds)[:2] != (Hp, Wp):
+        raise OracleError("bwd_unique: the padding must keep the map size")
+    g_w, g_xu = bwd_exact(ds, x_u, w, gy_u)
+    if reduced_out:
+        return g_w, g_xu
+    g_x = np.repeat(np.repeat(g_xu, d.r, axis=2), d.r, axis=3)[:, :, :d.H_in, :d.W_in]
+    return g_w, np.ascontiguousarray(g_x)
+
+
 def conv_fwd(d: Desc, x, w) -> np.ndarray:
     e = Desc(**{**d.__dict__, "r": 1})
     Hy, Wy, _, _ = out_shape(e)

@@ -642,3 +642,80 @@ def test_q8_path_approaches_the_float_path(oracle):
     gw, gx = oracle.bwd_weight(d, x_u, gy_u), oracle.bwd_input(d, gy_u, w)
     assert np.abs(gw8 - gw).max() <= 0.02 * np.abs(gw).max()
     assert np.abs(gx8 - gx).max() <= 0.03 * np.abs(gx).max()
+
+
+# ---------------------------------------------------------------------------
+# 'fewer unique elements' alone (Sec. 4.2, middle cost line of Fig. 3)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("case", [
+    # N  Ci  Co  H   W  K  d  g  r
+    (2, 3, 4, 8, 8, 3, 1, 1, 2), (1, 4, 6, 9, 7, 3, 1, 2, 2), (2, 2, 3, 12, 12, 3, 2, 1, 4),
+    (1, 3, 3, 10, 14, 5, 1, 3, 2), (2, 2, 2, 7, 7, 1, 1, 1, 4),
+])
+def test_unique_elements_only_against_torch(oracle, case):
+    """bwd_unique against library routines: torch's fp64 convolution backward on the reduced maps,
+    and repeat_interleave for the replication to full resolution."""
+    N, Ci, Co, H, W, K, dl, g, r = case
+    p = dl * (K - 1) // 2
+    d = oracle.Desc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=K, K_w=K, stride=1, pad=p, dilation=dl, groups=g, r=r)
+    _, _, Hp, Wp = oracle.out_shape(d)
+    rr = np.random.default_rng(7)
+    x_u, gy_u = rr.standard_normal((N, Ci, Hp, Wp)), rr.standard_normal((N, Co, Hp, Wp))
+    w = rr.standard_normal((Co, Ci // g, K, K))
+    g_w, g_x = oracle.bwd_unique(d, x_u, gy_u, w)
+    _, g_xu = oracle.bwd_unique(d, x_u, gy_u, w, reduced_out=True)
+    xt = torch.from_numpy(x_u).requires_grad_(True)
+    wt = torch.from_numpy(w).requires_grad_(True)
+    y = torch.nn.functional.conv2d(xt, wt, None, 1, p, dl, g)
+    t_gx, t_gw = torch.autograd.grad(y, (xt, wt), torch.from_numpy(gy_u))
+    assert np.allclose(g_w, t_gw.numpy(), rtol=1e-12, atol=1e-12)
+    assert np.allclose(g_xu, t_gx.numpy(), rtol=1e-12, atol=1e-12)
+    up = t_gx.repeat_interleave(r, 2).repeat_interleave(r, 3)[:, :, :H, :W].numpy()
+    assert g_x.shape == (N, Ci, H, W) and np.allclose(g_x, up, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("r", [2, 3, 4])
+@pytest.mark.parametrize("g", [1, 2])
+def test_unique_elements_only_equals_filtering_for_1x1_kernels(oracle, r, g):
+    """With a 1 x 1 kernel there is nothing left to collapse: the reduced-map backward is Eq. 5 / Eq. 3
+    (ragged maps included), and with r = 1 it is vanilla BP."""
+    N, Ci, Co, H, W = 2, 4, 6, 9, 11
+    d = oracle.Desc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, groups=g, r=r)
+    rr = np.random.default_rng(8)
+    x, gy, w = rr.standard_normal((N, Ci, H, W)), rr.standard_normal((N, Co, H, W)), rr.standard_normal((Co, Ci // g, 1, 1))
+    x_u, gy_u = oracle.pool_activation(d, x), oracle.filter_grad(d, gy)
+    g_w, g_x = oracle.bwd_unique(d, x_u, gy_u, w)
+    assert np.allclose(g_w, oracle.bwd_weight(d, x_u, gy_u), rtol=1e-12, atol=1e-13)
+    assert np.allclose(g_x, oracle.bwd_input(d, gy_u, w), rtol=1e-12, atol=1e-13)
+    d1 = oracle.Desc(N=N, C_in=Ci, C_out=Co, H_in=H, W_in=W, K_h=3, K_w=3, pad=1, groups=g, r=1)
+    w3 = rr.standard_normal((Co, Ci // g, 3, 3))
+    e_w, e_x = oracle.bwd_exact(d1, x, w3, gy)
+    u_w, u_x = oracle.bwd_unique(d1, x, gy, w3)
+    assert np.array_equal(e_w, u_w) and np.array_equal(e_x, u_x)
+
+
+def test_unique_elements_only_by_hand(oracle):
+    """4 x 4 map, r = 2, one channel, 3 x 3 kernel, padding 1: the patch grid is 2 x 2, so every tap of
+    the kernel meets at most the four patch values; written out from the definition."""
+    d = oracle.Desc(N=1, C_in=1, C_out=1, H_in=4, W_in=4, K_h=3, K_w=3, pad=1, r=2)
+    x_u = np.array([[[[1., 2.], [3., 4.]]]])
+    gy_u = np.array([[[[0.5, -1.], [2., 0.25]]]])
+    w = np.arange(1., 10.).reshape(1, 1, 3, 3)
+    g_w, g_x = oracle.bwd_unique(d, x_u, gy_u, w)
+    xp = np.pad(x_u[0, 0], 1)
+    for u in range(3):
+        for v in range(3):
+            want = sum(xp[hp + u, wp + v] * gy_u[0, 0, hp, wp] for hp in range(2) for wp in range(2))
+            assert abs(g_w[0, 0, u, v] - want) < 1e-13
+    for hp in range(2):
+        for wp in range(2):
+            want = 0.0
+            for u in range(3):
+                for v in range(3):
+                    i, j = hp - u + 1, wp - v + 1
+                    if 0 <= i < 2 and 0 <= j < 2:
+                        want += w[0, 0, u, v] * gy_u[0, 0, i, j]
+            assert np.allclose(g_x[0, 0, 2 * hp:2 * hp + 2, 2 * wp:2 * wp + 2], want, atol=1e-13)
+    with pytest.raises(oracle.OracleError):
+        oracle.bwd_unique(oracle.Desc(N=1, C_in=1, C_out=1, H_in=4, W_in=4, K_h=3, K_w=3, stride=2, pad=1, r=2),
+                          np.zeros((1, 1, 1, 1)), np.zeros((1, 1, 1, 1)), w)
