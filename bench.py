@@ -132,7 +132,7 @@ def ceilings():
 def fig3(args):
     """Sec. 4.2 / Fig. 3 on this GPU: the layer of the figure's footnote (3x3, 192 -> 64 channels, 120 x 160
     map) under the three cost lines of the analysis -- vanilla BP; 'fewer unique elements' only, i.e. the
-    same K x K backward run on the r^2-smaller maps (gf_conv_bwd_exact on the reduced shape); and gradient
+    same K x K backward run on the r^2-smaller maps (gf_conv_bwd_unique, g_x at full resolution); and gradient
     filtering with the collapsed kernel (Eq. 3 / Eq. 5).  Times are per call, cold (rotating buffer sets),
     from HIP events around back-to-back launches; FLOPs are the closed forms of Eq. 1 and Eq. 12."""
     import torch
@@ -194,18 +194,16 @@ def fig3(args):
         for k in range(nsets):
             B.gf_pool_activation(d, P(xs[k]), P(xus[k]), 0)
         cost = B.gf_cost_model(d)
-        # fewer unique elements only: the exact K x K backward on the reduced maps
-        ds = d1.with_(H_in=sh["x_u"][2], W_in=sh["x_u"][3])
-        wss = ws_for(ds, B.GF_OP_BWD_EXACT)
-        gxr = [torch.empty(sh["x_u"], dtype=td, device="cuda") for _ in range(nsets)]
+        # fewer unique elements only: the K x K backward on the reduced maps, g_x replicated to full resolution
+        wss = ws_for(d, B.GF_OP_BWD_UNIQUE)
 
         def small_gx(k, s):
             B.gf_filter_grad(d, P(gs[k]), P(gus[k]), s)
-            B.gf_conv_bwd_exact(ds, 0, P(w), P(gus[k]), 0, P(gxr[k]), P(wss), wss.numel(), s)
+            B.gf_conv_bwd_unique(d, P(gus[k]), 0, P(w), 0, P(gxs[k]), False, P(wss), wss.numel(), s)
 
         def small_all(k, s):
             B.gf_filter_grad(d, P(gs[k]), P(gus[k]), s)
-            B.gf_conv_bwd_exact(ds, P(xus[k]), P(w), P(gus[k]), P(gws[k]), P(gxr[k]), P(wss), wss.numel(), s)
+            B.gf_conv_bwd_unique(d, P(gus[k]), P(xus[k]), P(w), P(gws[k]), P(gxs[k]), False, P(wss), wss.numel(), s)
 
         rows.append({"line": "fewer unique elements only", "r": r,
                      "flops_gx_per_image": cost1["flops_exact_gx"] / (r * r),
@@ -222,7 +220,7 @@ def fig3(args):
 
         rows.append({"line": "gradient filtering", "r": r, "flops_gx_per_image": cost["flops_gf_gx"],
                      "gx_us": round(timed(gf_gx), 1), "backward_us": round(timed(gf_all), 1)})
-        del xus, gus, gxr
+        del xus, gus
     log(f"Fig. 3 layer: 3x3, {Ci} -> {Co} channels, {H} x {W}, N={N}, {dtype}; times per call in us")
     log(f"{'line':30s} {'r':>2s} {'MFLOP g_x / image':>18s} {'g_x us':>9s} {'g_w + g_x us':>13s}")
     for q in rows:

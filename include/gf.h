@@ -85,7 +85,8 @@ typedef enum gf_op {
   GF_OP_FILTER_SNR = 5,
   GF_OP_BWD_WEIGHT_Q8 = 6,
   GF_OP_BWD_INPUT_Q8 = 7,
-  GF_OP_BWD_FILTERED_Q8 = 8
+  GF_OP_BWD_FILTERED_Q8 = 8,
+  GF_OP_BWD_UNIQUE = 9
 } gf_op;
 
 /* Plain-old-data layer descriptor in the paper's symbols (Table of symbols,
@@ -291,6 +292,22 @@ gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void*
                             void* stream);
 
 /* Closed forms of Sec. 3.2, 4.2, 4.3 plus the byte / FLOP model.  Host only. */
+/* "Fewer unique elements" alone (Sec. 4.2, the middle cost line of Fig. 3): the gradient map is
+ * replaced by its one value per patch, the K x K kernel is kept, and the backward runs on the r^2
+ * times smaller maps as it stands -- vanilla BP (Sec. 3.1) of the same kernel, padding and dilation on
+ * the patch grid, with x_u (patch sums, gf_pool_activation) for x and gy_u (patch means,
+ * gf_filter_grad) for g_y:
+ *   g_w[c_o, c_i, u, v] = sum over (n, patch) of x_u[n, c_i, patch + tap (u, v)] * gy_u[n, c_o, patch]
+ *   g_x[n, c_i, pixel]  = sum over (c_o, u, v) of w[c_o, c_i, u, v] * gy_u[n, c_o, patch(pixel) - tap (u, v)]
+ * every pixel of a patch receiving its patch's value, or, with reduced_out != 0, one value per patch
+ * ([N, C_in, H_p, W_p]).  For 1 x 1 kernels this is gf_conv_bwd_weight / gf_conv_bwd_input; with r == 1
+ * it is gf_conv_bwd_exact.  Stride-1 layers whose padding keeps the map size (2 pad = dilation (K - 1))
+ * only: GF_ERR_UNSUPPORTED for stride > 1, GF_ERR_SHAPE otherwise.  g_w or g_x may be NULL.
+ * ws: gf_workspace_bytes(GF_OP_BWD_UNIQUE). */
+gf_status gf_conv_bwd_unique(const gf_conv_desc* desc, const void* gy_u, const void* x_u, const void* w,
+                             float* g_w, void* g_x, int reduced_out, void* ws, size_t ws_bytes,
+                             void* stream);
+
 gf_status gf_cost_model(const gf_conv_desc* desc, gf_cost* out);
 
 const char* gf_status_string(int status);

@@ -19,6 +19,7 @@ GF_F32, GF_BF16 = 0, 1
 GF_OP_BWD_WEIGHT, GF_OP_BWD_INPUT, GF_OP_BWD_EXACT, GF_OP_BWD_FILTERED, GF_OP_BWD_CHAINED = 0, 1, 2, 3, 4
 GF_OP_FILTER_SNR = 5
 GF_OP_BWD_WEIGHT_Q8, GF_OP_BWD_INPUT_Q8, GF_OP_BWD_FILTERED_Q8 = 6, 7, 8
+GF_OP_BWD_UNIQUE = 9
 
 EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_activation_batch",
            "gf_pool_activation_mask", "gf_filter_grad",
@@ -27,7 +28,7 @@ EXPORTS = ("gf_out_shape", "gf_workspace_bytes", "gf_pool_activation", "gf_pool_
            "gf_conv_bwd_chained",
            "gf_conv_bwd_exact",
            "gf_filter_grad_q8", "gf_pool_activation_q8", "gf_kernel_sum_q8", "gf_conv_bwd_weight_q8",
-           "gf_conv_bwd_input_q8", "gf_conv_bwd_filtered_q8", "gf_pool_activation_batch_q8",
+           "gf_conv_bwd_input_q8", "gf_conv_bwd_filtered_q8", "gf_pool_activation_batch_q8", "gf_conv_bwd_unique",
            "gf_cost_model",
            "gf_status_string", "gf_version", "gf_set_launch_observer")
 
@@ -109,6 +110,7 @@ def lib() -> C.CDLL:
         L.gf_kernel_sum_q8.argtypes = [dp, vp, C.c_float, vp, vp]
         L.gf_conv_bwd_weight_q8.argtypes = [dp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         L.gf_conv_bwd_input_q8.argtypes = [dp, vp, vp, C.c_float, vp, C.c_int, vp, C.c_size_t, vp]
+        L.gf_conv_bwd_unique.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int, vp, C.c_size_t, vp]
         L.gf_conv_bwd_filtered_q8.argtypes = [dp, vp, C.c_float, vp, vp, C.c_float, C.c_float, C.c_float, vp, vp, vp,
                                               vp, C.c_size_t, vp]
         L.gf_cost_model.argtypes = [dp, C.POINTER(_Cost)]
@@ -288,6 +290,13 @@ def gf_conv_bwd_weight_q8(d: ConvDesc, x_q: int, gy_q: int, scale: float, g_w: i
     cd = d.c()
     _chk(lib().gf_conv_bwd_weight_q8(C.byref(cd), x_q, gy_q, scale, g_w, ws, ws_bytes, stream),
          "gf_conv_bwd_weight_q8")
+
+
+def gf_conv_bwd_unique(d: ConvDesc, gy_u: int, x_u: int, w: int, g_w: int, g_x: int, reduced_out: bool, ws: int,
+                       ws_bytes: int, stream: int = 0):
+    cd = d.c()
+    _chk(lib().gf_conv_bwd_unique(C.byref(cd), gy_u, x_u, w, g_w, g_x, int(bool(reduced_out)), ws, ws_bytes, stream),
+         "gf_conv_bwd_unique")
 
 
 def gf_conv_bwd_filtered_q8(d: ConvDesc, g_y: int, inv_delta_gy: float, x_q: int, w: int, inv_delta_w: float,

@@ -135,8 +135,34 @@ static size_t ws_filtered_q8(const Geom& g, bool own_gyq, size_t* off_wq, size_t
   return o + ws_bwd_input_q8(g, false);
 }
 
+// The layer of gf_conv_bwd_unique on its patch grid: the same kernel, padding, dilation and groups on
+// [N, C, H_p, W_p] maps, r = 1.  GF_ERR_SHAPE unless the padding keeps the map size.
+static gf_status unique_geom(const Geom& g, Geom* red) {
+  gf_conv_desc d;
+  d.struct_size = sizeof(gf_conv_desc);
+  d.N = g.N; d.C_in = g.Ci; d.C_out = g.Co; d.H_in = g.Hp; d.W_in = g.Wp;
+  d.K_h = g.Kh; d.K_w = g.Kw; d.stride = 1; d.pad = g.p; d.dilation = g.dl; d.groups = g.g; d.r = 1;
+  d.dtype = (gf_dtype)g.dtype;
+  gf_status rc = make_geom(&d, red);
+  if (rc) return rc;
+  return (red->Hy == g.Hp && red->Wy == g.Wp) ? GF_OK : GF_ERR_SHAPE;
+}
+
+// [vanilla BP on the patch grid][the reduced g_x when full resolution is asked for]
+static size_t ws_unique(const Geom& g, const Geom& red, bool want_gw, bool want_gx, bool reduced_out, size_t* off_red) {
+  size_t o = align256(ws_exact(red, want_gw, want_gx));
+  if (off_red) *off_red = o;
+  if (want_gx && !reduced_out) o += (size_t)g.N * g.Ci * g.P * g.b;
+  return o;
+}
+
 static size_t ws_need(const Geom& g, int op, bool reduced_out) {
   switch (op) {
+    case GF_OP_BWD_UNIQUE: {
+      Geom red;
+      if (g.r == 1 || g.s != 1 || unique_geom(g, &red) != GF_OK) return ws_exact(g, true, true);
+      return ws_unique(g, red, true, true, false, nullptr);
+    }
     case GF_OP_BWD_FILTERED:
       return ws_filtered(g, true, nullptr, nullptr);
     case GF_OP_BWD_CHAINED:
@@ -209,7 +235,8 @@ gf_status gf_out_shape(const gf_conv_desc* desc, int32_t* H_y, int32_t* W_y, int
 gf_status gf_workspace_bytes(const gf_conv_desc* desc, int op, size_t* bytes) {
   if (op != GF_OP_BWD_WEIGHT && op != GF_OP_BWD_INPUT && op != GF_OP_BWD_EXACT &&
       op != GF_OP_BWD_FILTERED && op != GF_OP_BWD_CHAINED && op != GF_OP_FILTER_SNR &&
-      op != GF_OP_BWD_WEIGHT_Q8 && op != GF_OP_BWD_INPUT_Q8 && op != GF_OP_BWD_FILTERED_Q8)
+      op != GF_OP_BWD_WEIGHT_Q8 && op != GF_OP_BWD_INPUT_Q8 && op != GF_OP_BWD_FILTERED_Q8 &&
+      op != GF_OP_BWD_UNIQUE)
     return GF_ERR_BAD_DESC;
   if (!desc) return GF_ERR_NULL;
   gf_conv_desc d1;
@@ -648,6 +675,39 @@ gf_status gf_conv_bwd_exact(const gf_conv_desc* desc, const void* x, const void*
   }
   if (g_x) rc = dev(launch_exact_dgrad(g, w, g_y, g_x, ws, st));
   return rc;
+}
+
+gf_status gf_conv_bwd_unique(const gf_conv_desc* desc, const void* gy_u, const void* x_u, const void* w,
+                             float* g_w, void* g_x, int reduced_out, void* ws, size_t ws_bytes,
+                             void* stream) {
+  Geom g;
+  gf_status rc = make_geom(desc, &g);
+  if (rc) return rc;
+  if (g.r == 1)   // no reduced maps: x_u is x, gy_u is g_y
+    return gf_conv_bwd_exact(desc, x_u, w, gy_u, g_w, g_x, ws, ws_bytes, stream);
+  if (g.s != 1) return GF_ERR_UNSUPPORTED;
+  Geom red;
+  rc = unique_geom(g, &red);
+  if (rc) return rc;
+  if (!gy_u || (!g_w && !g_x)) return GF_ERR_NULL;
+  if ((g_w && !x_u) || (g_x && !w)) return GF_ERR_NULL;
+  if (!aligned16(gy_u) || !aligned16(x_u) || !aligned16(w) || !aligned16(g_w) || !aligned16(g_x))
+    return GF_ERR_UNSUPPORTED;
+  size_t off_red = 0;
+  const bool full = g_x && !reduced_out;
+  rc = check_ws(ws_unique(g, red, g_w != nullptr, g_x != nullptr, reduced_out != 0, &off_red), ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* wsb = static_cast<char*>(ws);
+  void* gxu = full ? static_cast<void*>(wsb + off_red) : g_x;
+  if (implicit_ok(red)) {
+    rc = dev(launch_implicit(red, x_u, w, gy_u, g_w, gxu, ws, st));
+  } else {
+    if (g_w) rc = dev(launch_exact_wgrad(red, x_u, gy_u, g_w, ws, st));
+    if (!rc && g_x) rc = dev(launch_exact_dgrad(red, w, gy_u, gxu, ws, st));
+  }
+  if (rc || !full) return rc;
+  return dev(launch_replicate(g, gxu, g_x, st));
 }
 
 gf_status gf_cost_model(const gf_conv_desc* desc, gf_cost* out) {

@@ -43,7 +43,7 @@ constexpr int kPrepInBytes = 24 * 1024;
 
 template <class T> struct El;
 template <> struct El<float> { static constexpr int KB = 32, VE = 4; };    // elements per 128-byte chunk / 16-byte vector
-template <> struct El<bf16_t> { static constexpr int KB = 64, VE = 8; };
+template <> struct El<bf16_t> { [[maybe_unused]] static constexpr int KB = 64, VE = 8; };   // (no bf16 instance is built)
 
 // element (row, k) of a blocked matrix with `chunks` K chunks of KB elements
 template <int KB>
@@ -278,12 +278,12 @@ struct GemmArgs {
 
 template <class T> struct Acc;
 template <> struct Acc<float> { typedef f32x4 type; static constexpr int BASE = 16, NV = 4; };
-template <> struct Acc<bf16_t> { typedef f32x16 type; static constexpr int BASE = 32, NV = 16; };
+template <> struct Acc<bf16_t> { typedef f32x16 type; [[maybe_unused]] static constexpr int BASE = 32, NV = 16; };
 
 // row of the base MFMA tile that element v of lane `lane` holds (the column is lane % BASE)
 template <class T> __device__ __forceinline__ int acc_row(int lane, int v);
 template <> __device__ __forceinline__ int acc_row<float>(int lane, int v) { return 4 * (lane >> 4) + v; }
-template <> __device__ __forceinline__ int acc_row<bf16_t>(int lane, int v) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+template <> [[maybe_unused]] __device__ __forceinline__ int acc_row<bf16_t>(int lane, int v) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
 // Barrier between the waves of a block that orders LDS traffic only.  __syncthreads() also waits
 // for every global load in flight (its fence covers all address spaces), which would end the

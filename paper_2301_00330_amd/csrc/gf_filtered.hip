@@ -783,6 +783,16 @@ hipError_t launch_expand_f32(const Geom& g, const float* red, void* g_x, hipStre
                                      g.Wp, st);
 }
 
+// g_x[n, c, h, w] = red[n, c, h / r_x, w / r_x]: a reduced map in the storage type to full resolution
+hipError_t launch_replicate(const Geom& g, const void* red, void* g_x, hipStream_t st) {
+  const long planes = (long)g.N * g.Ci;
+  if (g.dtype == GF_BF16)
+    return launch_expand<bf16_t, bf16_t>(static_cast<const bf16_t*>(red), static_cast<bf16_t*>(g_x), nullptr, 1.f,
+                                         planes, g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
+  return launch_expand<float, float>(static_cast<const float*>(red), static_cast<float*>(g_x), nullptr, 1.f, planes,
+                                     g.Ci, g.H, g.W, g.rx, g.Hp, g.Wp, st);
+}
+
 hipError_t launch_gf_bwd_input(const Geom& g, const void* gy_u, const void* w, void* g_x,
                                bool reduced_out, void* ws, hipStream_t st) {
   if (g.dtype == GF_BF16)

@@ -172,6 +172,8 @@ hipError_t launch_bwd_input_q8(const Geom& g, const int8_t* gy_q, const int8_t* 
                                bool reduced_out, void* ws, hipStream_t st);
 // full-resolution g_x from an fp32 reduced map [N, C_in, H_p, W_p] (rounded once to the storage type)
 hipError_t launch_expand_f32(const Geom& g, const float* red, void* g_x, hipStream_t st);
+// the same from a reduced map in the storage type
+hipError_t launch_replicate(const Geom& g, const void* red, void* g_x, hipStream_t st);
 
 // S1 with the noise figures of the filter: gy_u as launch_patch_reduce(mean), plus
 // stats[0] = sum g_y^2 and stats[1] = sum (g_y - patch mean)^2 (doubles, device memory);

@@ -240,6 +240,20 @@ def kernel_sum_q8(d: B.ConvDesc, w: torch.Tensor, inv_delta: float) -> torch.Ten
     return out
 
 
+def conv_bwd_unique(d: B.ConvDesc, gy_u: torch.Tensor, x_u: torch.Tensor, w: torch.Tensor, reduced_out: bool = False,
+                    ws: Workspace | None = None):
+    """(g_w, g_x) of gf_conv_bwd_unique: vanilla BP of the layer's kernel on the patch grid."""
+    s = shapes(d)
+    _check(gy_u, d, s["gy_u"], "gy_u")
+    _check(x_u, d, s["x_u"], "x_u")
+    _check(w, d, s["w"], "w")
+    g_w = torch.empty(s["w"], dtype=torch.float32, device=gy_u.device)
+    g_x = torch.empty(s["g_x_u"] if (reduced_out and d.r > 1) else s["x"], dtype=_tdtype(d), device=gy_u.device)
+    p, n = _ws(gy_u, ws).get(B.gf_workspace_bytes(d, B.GF_OP_BWD_UNIQUE))
+    B.gf_conv_bwd_unique(d, B.ptr(gy_u), B.ptr(x_u), B.ptr(w), B.ptr(g_w), B.ptr(g_x), reduced_out, p, n, _stream())
+    return g_w, g_x
+
+
 def conv_bwd_weight_q8(d: B.ConvDesc, x_q: torch.Tensor, gy_q: torch.Tensor, scale: float,
                        ws: Workspace | None = None) -> torch.Tensor:
     s = shapes(d)

@@ -334,3 +334,27 @@ def test_pool_batch_host_checks(lib):
         with pytest.raises(B.GfError) as ei:
             B.gf_pool_activation_batch_q8(batch)
         assert ei.value.status == want
+
+
+def test_unique_elements_entry_host_checks(lib):
+    """gf_conv_bwd_unique: stride-1 layers whose padding keeps the map size; workspace = vanilla BP on
+    the patch grid plus the reduced g_x."""
+    d = B.ConvDesc(**OK)
+    need = B.gf_workspace_bytes(d, B.GF_OP_BWD_UNIQUE)
+    Hy, Wy, Hp, Wp = B.gf_out_shape(d)
+    assert need >= d.N * d.C_in * Hp * Wp * 4
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_unique(d.with_(stride=2, H_in=16, W_in=16), FAKE, FAKE, FAKE, FAKE, FAKE, False, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_UNSUPPORTED
+    with pytest.raises(B.GfError) as ei:   # 3 x 3 kernel without padding: the patch grid would shrink
+        B.gf_conv_bwd_unique(d.with_(pad=0, H_in=18, W_in=18), FAKE, FAKE, FAKE, FAKE, FAKE, False, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_SHAPE
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_unique(d, 0, FAKE, FAKE, FAKE, FAKE, False, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_unique(d, FAKE, FAKE, FAKE, 0, 0, False, FAKE, 1 << 30)
+    assert ei.value.status == B.GF_ERR_NULL
+    with pytest.raises(B.GfError) as ei:
+        B.gf_conv_bwd_unique(d, FAKE, FAKE, FAKE, FAKE, FAKE, False, FAKE, need - 1)
+    assert ei.value.status == B.GF_ERR_WORKSPACE

@@ -892,6 +892,47 @@ def test_fewer_unique_elements_only_variant(oracle, dtype):
     assert rel_err(g_w, ref_gw) <= TOL[dtype] and rel_err(g_x, ref_gx) <= TOL[dtype]
 
 
+UNIQUE_CASES = [
+    # N  Ci   Co   H   W  K  d   g  r
+    (2, 24, 16, 20, 28, 3, 1, 1, 2),
+    (2, 256, 256, 14, 14, 3, 1, 1, 2),     # ResNet-18 tail, 14 x 14 -> 7 x 7 patch grid
+    (2, 512, 512, 7, 7, 3, 1, 1, 2),       # 7 x 7 -> 4 x 4, ragged patches
+    (2, 512, 512, 7, 7, 3, 1, 1, 4),
+    (1, 256, 256, 64, 64, 3, 12, 1, 2),    # DeepLabV3 head: dilation 12 on the 32 x 32 patch grid
+    (1, 256, 256, 64, 64, 3, 12, 1, 4),    # ... on 16 x 16 (the taps reach past the map: padding only)
+    (1, 2048, 256, 64, 64, 1, 1, 1, 2),    # 1 x 1: the same as the collapsed kernel
+    (2, 32, 32, 15, 13, 3, 1, 32, 2),      # depthwise, ragged
+    (2, 12, 18, 9, 11, 5, 1, 3, 3),        # groups, 5 x 5, r = 3
+    (2, 16, 16, 12, 12, 3, 1, 1, 1),       # r = 1: vanilla BP
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", UNIQUE_CASES)
+def test_unique_elements_only_entry(oracle, case, dtype):
+    """gf_conv_bwd_unique (Sec. 4.2, middle cost line of Fig. 3) against the oracle's composition, full
+    resolution and reduced, from the oracle's own reduced maps rounded once to the storage type; g_x is
+    constant on patches and equal to the replicated reduced output."""
+    N, Ci, Co, H, W, K, dl, g, r = case
+    d = mk(N, Ci, Co, H, W, K=K, p=dl * (K - 1) // 2, dl=dl, g=g, r=r, dtype=dtype)
+    od = odesc(oracle, d)
+    x, gy = randn((N, Ci, H, W), 71, dtype, relu=True), randn((N, Co, H, W), 72, dtype)
+    w = randn((Co, Ci // g, K, K), 73, dtype, scale=(2.0 / (Ci // g * K * K)) ** 0.5)
+    x_u = rounded(oracle.pool_activation(od, to64(x)), dtype)
+    gy_u = rounded(oracle.filter_grad(od, to64(gy)), dtype)
+    ref_gw, ref_gx = oracle.bwd_unique(od, to64(x_u), to64(gy_u), to64(w))
+    _, ref_gxu = oracle.bwd_unique(od, to64(x_u), to64(gy_u), to64(w), reduced_out=True)
+    g_w, g_x = T.conv_bwd_unique(d, gy_u.cuda(), x_u.cuda(), w.cuda())
+    g_w2, g_xu = T.conv_bwd_unique(d, gy_u.cuda(), x_u.cuda(), w.cuda(), reduced_out=True)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_err(g_w, ref_gw) <= tol and rel_err(g_x, ref_gx) <= tol and rel_err(g_xu, ref_gxu) <= tol
+    assert torch.equal(g_w, g_w2)
+    if r > 1:
+        up = g_xu.repeat_interleave(r, 2).repeat_interleave(r, 3)[:, :, :H, :W]
+        assert torch.equal(g_x, up)
+
+
 # ---------------------------------------------------------------------------
 # Gradient filtering on 8-bit codes (reading of Supp. H)
 # ---------------------------------------------------------------------------
