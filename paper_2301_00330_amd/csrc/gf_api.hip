@@ -197,7 +197,7 @@ using namespace gf;
 
 extern "C" {
 
-int gf_version(void) { return 200; }
+int gf_version(void) { return 210; }
 
 void gf_set_launch_observer(gf_launch_observer_fn fn, void* user) {
   g_observer.store(nullptr, std::memory_order_relaxed);
