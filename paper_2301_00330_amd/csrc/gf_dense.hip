@@ -88,9 +88,23 @@ __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
   T* xut = static_cast<T*>(a.xut);
   T* wt = static_cast<T*>(a.wt);
   if (b < a.blk_w0) {   // x_u [n][ci][p] -> XUT [ci][n * P + p]
+    // a few hundred blocks that each walk their share (a block costs about the same whatever it moves);
+    // 16-byte pieces where the patches of a plane are a whole number of vectors
+    constexpr int VE = El<T>::VE;
     const T* xu = static_cast<const T*>(a.xu);
-    const int e = b * kT + tid;
-    if (e < a.nxu) {
+    const int step = a.blk_w0 * kT;
+    if (a.P % VE == 0) {
+      for (int v = b * kT + tid; v < a.nxu / VE; v += step) {
+        const int e = v * VE;
+        const int n = (int)a.d_cip.div((uint32_t)e);
+        const int rem = e - n * a.Ci * a.P;
+        const int ci = (int)a.d_p.div((uint32_t)rem);
+        const int p = rem - ci * a.P;
+        *reinterpret_cast<u32x4_t*>(xut + blk<KB>(ci, n * a.P + p, a.chj)) = *reinterpret_cast<const u32x4_t*>(xu + e);
+      }
+      return;
+    }
+    for (int e = b * kT + tid; e < a.nxu; e += step) {
       const int n = (int)a.d_cip.div((uint32_t)e);
       const int rem = e - n * a.Ci * a.P;
       const int ci = (int)a.d_p.div((uint32_t)rem);
@@ -701,7 +715,7 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
   a.Co = g.Co; a.KK = g.KK;
   a.tickets = reinterpret_cast<int*>(wsb + p.off_tick);
   a.ntickets = p.w_tm * p.w_tn + p.d_tm * p.d_tn;
-  a.blk_w0 = want_w ? cdiv(a.nxu, kT) : 0;
+  a.blk_w0 = want_w ? imin_host(cdiv(g.P % El<T>::VE == 0 ? a.nxu / El<T>::VE : a.nxu, kT), 512) : 0;
   a.blk_pad0 = a.blk_w0 + (want_d ? cdiv(g.Ci, 32) * cdiv(g.Co, 32) : 0);
   a.blk_red0 = a.blk_pad0 + 8;
   // filter blocks: at most eight per CU, each walks its share of the runs
