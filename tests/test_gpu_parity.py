@@ -1531,6 +1531,29 @@ def test_pool_activation_batch_is_bit_identical(oracle, dtype):
         assert rel_err(got, oracle.pool_activation(odesc(oracle, d), to64(x))) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pool_activation_batch_walks_large_jobs(oracle, dtype):
+    """A register-variant job with more blocks of work than the launch gives it (1024 planes of 111x112,
+    ragged in height: 3136 blocks of work in bf16, 6272 in fp32, 2048 launched), beside a small job and an
+    LDS job; floats against the oracle, codes bit for bit against the single-tensor entry."""
+    cases = [(2, 3, 16, 16, 2, 1), (16, 64, 111, 112, 2, 1), (3, 5, 7, 7, 2, 1), (4, 32, 56, 56, 4, 1)]
+    descs, xs, invs = [], [], []
+    for k, (N, C, H, W, r, s) in enumerate(cases):
+        descs.append(mk(N, C, C, H, W, K=3, s=s, p=1, r=r, dtype=dtype))
+        xs.append(randn((N, C, H, W), 300 + k, dtype, relu=True))
+    xg = [x.cuda() for x in xs]
+    outs = T.pool_activation_batch(descs, xg)
+    refs = [oracle.pool_activation(odesc(oracle, d), to64(x)) for d, x in zip(descs, xs)]
+    invs = [127.0 / float(np.abs(ref).max()) for ref in refs]
+    codes = T.pool_activation_batch_q8(descs, xg, invs)
+    singles = [T.pool_activation_q8(d, x, inv) for d, x, inv in zip(descs, xg, invs)]
+    torch.cuda.synchronize()
+    for got, ref, c, s1 in zip(outs, refs, codes, singles):
+        assert tuple(got.shape) == ref.shape
+        assert rel_err(got, ref) <= TOL[dtype]
+        assert torch.equal(c, s1)
+
+
 def test_pool_activation_batch_full_config5(oracle):
     """The call bench.py times: all ten layers of configuration 5 at N = 128, fp32, in one launch."""
     cfg = WL.CONFIGS[5]
