@@ -16,8 +16,13 @@
 //      so neither the patch count of a plane (49, 16, 4 ...) nor image boundaries show up in the
 //      operand loaders any more.
 //   2. dense_gemm_k: one grid whose blocks are (tile, K slab) pairs of the two products.  Operands
-//      go global -> registers (one chunk ahead) -> LDS rows of 128 + 16 bytes -> 16-byte fragment
-//      reads -> MFMA (v_mfma_f32_32x32x16_bf16, v_mfma_f32_16x16x4_f32).  A slab's partial tile goes
+//      go global -> registers (three chunks ahead) -> LDS -> 16-byte fragment reads ->
+//      v_mfma_f32_32x32x16_bf16.  fp32 operands are split on their way into LDS into three bf16
+//      terms each (x = t0 + t1 + t2 exactly) and a product is accumulated from the six term products
+//      of order <= 2 in fp32: six bf16 matrix instructions cost 6/16 of the fp32 ones they replace,
+//      and the result is as close to the fp64 reference as that of v_mfma_f32_16x16x4_f32 (measured
+//      rms error 2 - 3.5e-7 of the rms gradient either way; 244 -> 222 us for the seven layers of the
+//      MobileNetV2 tail).  A slab's partial tile goes
 //      to the workspace; the block that takes the last ticket of a tile adds the slabs in slab
 //      order (so the result does not depend on which block that is) and runs the epilogue:
 //      scale and replicate to the K_h x K_w taps, or round once and write whole planes of g_x
@@ -290,14 +295,35 @@ struct GemmArgs {
   FastDiv d_p, d_wp, d_kk;
 };
 
-template <class T> struct Acc;
-template <> struct Acc<float> { typedef f32x4 type; static constexpr int BASE = 16, NV = 4; };
-template <> struct Acc<bf16_t> { typedef f32x16 type; [[maybe_unused]] static constexpr int BASE = 32, NV = 16; };
+// Accumulators of a wave: one 32 x 32 tile of v_mfma_f32_32x32x16_bf16 (fp32 operands enter it as three
+// bf16 terms each, see below); row of the tile that element v of lane `lane` holds (the column is lane % 32)
+typedef f32x16 acc_t;
+constexpr int kBase = 32, kNV = 16;
+__device__ __forceinline__ int acc_row(int lane, int v) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
-// row of the base MFMA tile that element v of lane `lane` holds (the column is lane % BASE)
-template <class T> __device__ __forceinline__ int acc_row(int lane, int v);
-template <> __device__ __forceinline__ int acc_row<float>(int lane, int v) { return 4 * (lane >> 4) + v; }
-template <> [[maybe_unused]] __device__ __forceinline__ int acc_row<bf16_t>(int lane, int v) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+// Four fp32 values as three bf16 terms, x = t0 + t1 + t2 exactly: every term is the nearest bf16 of what the
+// earlier ones leave (|t1| <= 2^-9 |x|, |t2| <= 2^-18 |x|), both remainders are exact in fp32, and the second
+// has at most 8 significant bits.  A product x y is taken as the six term products of order <= 2; the three
+// that are dropped are below 2^-26 |x y|, less than one rounding of the fp32 accumulation.  One packed
+// conversion per pair of values and term, two shifts / masks and two subtractions per pair and remainder.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split3(const u32x4_t& v, uint2 (&t)[3]) {
+  f32x2_t a = {__uint_as_float(v.x), __uint_as_float(v.y)}, b = {__uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    // one packed conversion per pair (round to nearest even)
+    const uint32_t pa = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2_t));
+    const uint32_t pb = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2_t));
+    t[k] = make_uint2(pa, pb);
+    if (k < 2) {
+      a.x -= bf_lo(pa); a.y -= bf_hi(pa);
+      b.x -= bf_lo(pb); b.y -= bf_hi(pb);
+    }
+  }
+}
+constexpr int kPitchS = 64 + 16;             // bytes of one staged row of one term (32 k as bf16)
+constexpr int kTermBytes = kTile * kPitchS;  // one term of an operand tile
 
 // Barrier between the waves of a block that orders LDS traffic only.  __syncthreads() also waits
 // for every global load in flight (its fence covers all address spaces), which would end the
@@ -309,14 +335,15 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 // acc += A[rows of tile ta][chunks kc0 .. kc1) * B[rows of tile tb][same chunks]^T for blocked operands with
-// `chunks` chunks per row.  WT: base MFMA tiles per wave and direction.
-template <class T, int WT>
+// `chunks` chunks per row; every wave owns one 32 x 32 quadrant of the 64 x 64 tile.
+template <class T>
 __device__ __forceinline__ void mainloop(const T* A, int ta, const T* B, int tb, int chunks, int kc0, int kc1,
                                          unsigned char* As, unsigned char* Bs,
-                                         typename Acc<T>::type (&acc)[WT][WT]) {
-  constexpr int KB = El<T>::KB, VE = El<T>::VE, BASE = Acc<T>::BASE;
+                                         acc_t& acc) {
+  constexpr int KB = El<T>::KB, VE = El<T>::VE;
+  constexpr bool SPLIT = sizeof(T) == 4;   // fp32 operands: three bf16 terms each, six products
   constexpr int LV = kTile * 8 / kT;   // 16-byte vectors per lane, operand and chunk
-  static_assert(2 * WT * BASE == kTile, "tile shape");
+  static_assert(2 * kBase == kTile, "tile shape");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   // the tile of one chunk is 8 KB of consecutive memory in the order of the LDS tile
@@ -338,52 +365,54 @@ __device__ __forceinline__ void mainloop(const T* A, int ta, const T* B, int tb,
   // chunk kc: registers (ca, cb) -> LDS, the load of chunk kc + 3 into (na, nb), then the MFMAs
   auto step = [&](u32x4_t (&ca)[LV], u32x4_t (&cb)[LV], u32x4_t (&na)[LV], u32x4_t (&nb)[LV], int kc, bool more)
                   __attribute__((always_inline)) {
+    if constexpr (SPLIT) {   // a vector of four k becomes 8 bytes in each of the three term tiles
 #pragma unroll
-    for (int i = 0; i < LV; ++i) {
-      const int s = tid + i * kT;
-      *reinterpret_cast<u32x4_t*>(As + (s >> 3) * kPitch + (s & 7) * 16) = ca[i];
-      *reinterpret_cast<u32x4_t*>(Bs + (s >> 3) * kPitch + (s & 7) * 16) = cb[i];
+      for (int i = 0; i < LV; ++i) {
+        const int s = tid + i * kT;
+        uint2 sa[3], sb[3];
+        split3(ca[i], sa);
+        split3(cb[i], sb);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+          *reinterpret_cast<uint2*>(As + t * kTermBytes + (s >> 3) * kPitchS + (s & 7) * 8) = sa[t];
+          *reinterpret_cast<uint2*>(Bs + t * kTermBytes + (s >> 3) * kPitchS + (s & 7) * 8) = sb[t];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < LV; ++i) {
+        const int s = tid + i * kT;
+        *reinterpret_cast<u32x4_t*>(As + (s >> 3) * kPitch + (s & 7) * 16) = ca[i];
+        *reinterpret_cast<u32x4_t*>(Bs + (s >> 3) * kPitch + (s & 7) * 16) = cb[i];
+      }
     }
     lds_barrier();
     if (more) fetch(na, nb, kc + 3);
-    if constexpr (sizeof(T) == 2) {
+    if constexpr (SPLIT) {
+      const int r = lane & 31, kg = lane >> 5;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {   // 16 k per MFMA, 32 per chunk
+        uint4 fa[3], fb[3];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+          fa[t] = *reinterpret_cast<const uint4*>(As + t * kTermBytes + (wm * 32 + r) * kPitchS + ks * 32 + kg * 16);
+          fb[t] = *reinterpret_cast<const uint4*>(Bs + t * kTermBytes + (wn * 32 + r) * kPitchS + ks * 32 + kg * 16);
+        }
+        // smallest products first
+        acc = mma32(fa[2], fb[0], acc);
+        acc = mma32(fa[0], fb[2], acc);
+        acc = mma32(fa[1], fb[1], acc);
+        acc = mma32(fa[1], fb[0], acc);
+        acc = mma32(fa[0], fb[1], acc);
+        acc = mma32(fa[0], fb[0], acc);
+      }
+    } else {
       const int r = lane & 31, kg = lane >> 5;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {   // 16 k per MFMA, 64 per chunk
-        uint4 fa[WT], fb[WT];
-#pragma unroll
-        for (int i = 0; i < WT; ++i)
-          fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * WT + i) * 32 + r) * kPitch + ks * 32 + kg * 16);
-#pragma unroll
-        for (int j = 0; j < WT; ++j)
-          fb[j] = *reinterpret_cast<const uint4*>(Bs + ((wn * WT + j) * 32 + r) * kPitch + ks * 32 + kg * 16);
-#pragma unroll
-        for (int i = 0; i < WT; ++i)
-#pragma unroll
-          for (int j = 0; j < WT; ++j) acc[i][j] = mma32(fa[i], fb[j], acc[i][j]);
-      }
-    } else {
-      // one 16-byte read per operand row and 16 k; MFMA number e of the four that follow takes
-      // element e of every lane's vector (k = 16 ks + 4 (lane / 16) + e on both sides)
-      const int r = lane & 15, kg = lane >> 4;
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        uint4 fa[WT], fb[WT];
-#pragma unroll
-        for (int i = 0; i < WT; ++i)
-          fa[i] = *reinterpret_cast<const uint4*>(As + ((wm * WT + i) * 16 + r) * kPitch + ks * 64 + kg * 16);
-#pragma unroll
-        for (int j = 0; j < WT; ++j)
-          fb[j] = *reinterpret_cast<const uint4*>(Bs + ((wn * WT + j) * 16 + r) * kPitch + ks * 64 + kg * 16);
-#pragma unroll
-        for (int i = 0; i < WT; ++i)
-#pragma unroll
-          for (int j = 0; j < WT; ++j) {
-            acc[i][j] = mma16(__uint_as_float(fa[i].x), __uint_as_float(fb[j].x), acc[i][j]);
-            acc[i][j] = mma16(__uint_as_float(fa[i].y), __uint_as_float(fb[j].y), acc[i][j]);
-            acc[i][j] = mma16(__uint_as_float(fa[i].z), __uint_as_float(fb[j].z), acc[i][j]);
-            acc[i][j] = mma16(__uint_as_float(fa[i].w), __uint_as_float(fb[j].w), acc[i][j]);
-          }
+        const uint4 fa = *reinterpret_cast<const uint4*>(As + (wm * 32 + r) * kPitch + ks * 32 + kg * 16);
+        const uint4 fb = *reinterpret_cast<const uint4*>(Bs + (wn * 32 + r) * kPitch + ks * 32 + kg * 16);
+        acc = mma32(fa, fb, acc);
       }
     }
     lds_barrier();
@@ -423,18 +452,12 @@ __device__ __forceinline__ float slab_load(const float* p) {
 // (element e of lane t at slab[e * 256 + t]: every store and load is one contiguous 1 KB run per
 // wave), then the ticket.  The block that arrives last -- all slabs of the tile are complete by
 // then -- returns true with acc = slab 0 + slab 1 + ... in slab order, whichever block it is.
-template <class T, int WT>
-__device__ __forceinline__ bool reduce_slabs(typename Acc<T>::type (&acc)[WT][WT], float* slabs, int z, int* ticket,
-                                             int nz, int* s_flag) {
-  constexpr int NV = Acc<T>::NV, NE = WT * WT * NV;   // 16 floats per lane
+__device__ __forceinline__ bool reduce_slabs(acc_t& acc, float* slabs, int z, int* ticket, int nz, int* s_flag) {
+  constexpr int NE = kNV;   // 16 floats per lane
   const int tid = threadIdx.x;
   float* mine = slabs + (long)z * kTile * kTile + tid;
 #pragma unroll
-  for (int i = 0; i < WT; ++i)
-#pragma unroll
-    for (int j = 0; j < WT; ++j)
-#pragma unroll
-      for (int v = 0; v < NV; ++v) slab_store(mine + ((i * WT + j) * NV + v) * kT, acc[i][j][v]);
+  for (int v = 0; v < NE; ++v) slab_store(mine + v * kT, acc[v]);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores have completed ...
   __syncthreads();                                          // ... and so have the other waves'
   if (tid == 0) *s_flag = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nz - 1;
@@ -460,50 +483,37 @@ __device__ __forceinline__ bool reduce_slabs(typename Acc<T>::type (&acc)[WT][WT
         if (z0 + zz < nz) s[e] += t[zz][e];
   }
 #pragma unroll
-  for (int i = 0; i < WT; ++i)
-#pragma unroll
-    for (int j = 0; j < WT; ++j)
-#pragma unroll
-      for (int v = 0; v < NV; ++v) acc[i][j][v] = s[(i * WT + j) * NV + v];
+  for (int v = 0; v < NE; ++v) acc[v] = s[v];
   return true;
 }
 
 // rows r0 .. r0+epr of the finished tile from the registers into Cs[epr][kTile + 1]
-template <class T, int WT>
-__device__ __forceinline__ void gather_rows(typename Acc<T>::type (&acc)[WT][WT], int r0, int epr, float* Cs) {
-  constexpr int BASE = Acc<T>::BASE, NV = Acc<T>::NV, SC = kTile + 1;
+__device__ __forceinline__ void gather_rows(const acc_t& acc, int r0, int epr, float* Cs) {
+  constexpr int SC = kTile + 1;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 #pragma unroll
-  for (int i = 0; i < WT; ++i)
-#pragma unroll
-    for (int j = 0; j < WT; ++j)
-#pragma unroll
-      for (int v = 0; v < NV; ++v) {
-        const int row = (wm * WT + i) * BASE + acc_row<T>(lane, v) - r0;
-        const int col = (wn * WT + j) * BASE + (lane & (BASE - 1));
-        if (row >= 0 && row < epr) Cs[row * SC + col] = acc[i][j][v];
-      }
+  for (int v = 0; v < kNV; ++v) {
+    const int row = wm * kBase + acc_row(lane, v) - r0;
+    const int col = wn * kBase + (lane & (kBase - 1));
+    if (row >= 0 && row < epr) Cs[row * SC + col] = acc[v];
+  }
 }
 
-template <class T, int WT>
+template <class T>
 __device__ __forceinline__ void wgrad_block(const GemmArgs& a, int L, unsigned char* smem, int* s_flag) {
-  typename Acc<T>::type acc[WT][WT];
+  acc_t acc;
 #pragma unroll
-  for (int i = 0; i < WT; ++i)
-#pragma unroll
-    for (int j = 0; j < WT; ++j)
-#pragma unroll
-      for (int v = 0; v < Acc<T>::NV; ++v) acc[i][j][v] = 0.f;
+  for (int v = 0; v < kNV; ++v) acc[v] = 0.f;
   const int tiles = a.w_tm * a.w_tn;
   const int z = L / tiles, t = L - z * tiles;
   const int tmi = t / a.w_tn, tni = t - tmi * a.w_tn;
   const int m0 = tmi * kTile, n0 = tni * kTile;
   const int kc0 = z * a.w_cpz, kc1 = min(kc0 + a.w_cpz, a.w_chunks);
-  mainloop<T, WT>(static_cast<const T*>(a.gyt), tmi, static_cast<const T*>(a.xut), tni, a.w_chunks, kc0, kc1,
-                  smem, smem + kTile * kPitch, acc);
+  mainloop<T>(static_cast<const T*>(a.gyt), tmi, static_cast<const T*>(a.xut), tni, a.w_chunks, kc0, kc1,
+                         smem, smem + (sizeof(T) == 4 ? 3 * kTermBytes : kTile * kPitch), acc);
   if (a.w_nz > 1 &&
-      !reduce_slabs<T, WT>(acc, a.partW + (long)t * a.w_nz * kTile * kTile, z, a.tickW + t, a.w_nz, s_flag))
+      !reduce_slabs(acc, a.partW + (long)t * a.w_nz * kTile * kTile, z, a.tickW + t, a.w_nz, s_flag))
     return;
   constexpr int SC = kTile + 1, EPR = 32;
   float* Cs = reinterpret_cast<float*>(smem);
@@ -512,7 +522,7 @@ __device__ __forceinline__ void wgrad_block(const GemmArgs& a, int L, unsigned c
   const int run = ncol * a.KK;   // one c_o row of the tile is one contiguous run of g_w
   for (int r0 = 0; r0 < kTile && m0 + r0 < a.Co; r0 += EPR) {
     __syncthreads();
-    gather_rows<T, WT>(acc, r0, EPR, Cs);
+    gather_rows(acc, r0, EPR, Cs);
     __syncthreads();
     const int nr = min(EPR, a.Co - m0 - r0);
     for (int row = 0; row < nr; ++row) {
@@ -522,15 +532,11 @@ __device__ __forceinline__ void wgrad_block(const GemmArgs& a, int L, unsigned c
   }
 }
 
-template <class T, int WT>
+template <class T>
 __device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned char* smem, int* s_flag) {
-  typename Acc<T>::type acc[WT][WT];
+  acc_t acc;
 #pragma unroll
-  for (int i = 0; i < WT; ++i)
-#pragma unroll
-    for (int j = 0; j < WT; ++j)
-#pragma unroll
-      for (int v = 0; v < Acc<T>::NV; ++v) acc[i][j][v] = 0.f;
+  for (int v = 0; v < kNV; ++v) acc[v] = 0.f;
   // image group slowest: the blocks one XCD receives share their rows of GYN
   const int per_group = a.d_tm * a.d_nz;
   const int tni = L / per_group, rem = L - tni * per_group;
@@ -539,10 +545,10 @@ __device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned c
   const int m0 = tmi * kTile;                 // first c_i
   const int img0 = tni * a.ipt;               // first image
   const int kc0 = z * a.d_cpz, kc1 = min(kc0 + a.d_cpz, a.d_chunks);
-  mainloop<T, WT>(static_cast<const T*>(a.wt), tmi, static_cast<const T*>(a.gyn), tni, a.d_chunks, kc0, kc1,
-                  smem, smem + kTile * kPitch, acc);
+  mainloop<T>(static_cast<const T*>(a.wt), tmi, static_cast<const T*>(a.gyn), tni, a.d_chunks, kc0, kc1,
+                         smem, smem + (sizeof(T) == 4 ? 3 * kTermBytes : kTile * kPitch), acc);
   if (a.d_nz > 1 &&
-      !reduce_slabs<T, WT>(acc, a.partD + (long)t * a.d_nz * kTile * kTile, z, a.tickD + t, a.d_nz, s_flag))
+      !reduce_slabs(acc, a.partD + (long)t * a.d_nz * kTile * kTile, z, a.tickD + t, a.d_nz, s_flag))
     return;
   constexpr int SC = kTile + 1;
   float* Cs = reinterpret_cast<float*>(smem);
@@ -554,7 +560,7 @@ __device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned c
   constexpr int VE = El<T>::VE;
   for (int r0 = 0; r0 < kTile && m0 + r0 < a.Ci; r0 += a.epr) {
     __syncthreads();
-    gather_rows<T, WT>(acc, r0, a.epr, Cs);
+    gather_rows(acc, r0, a.epr, Cs);
     __syncthreads();
     const int nr = min(a.epr, a.Ci - m0 - r0);
     if (a.reduced) {   // one value per patch: rows of an image are one contiguous run of nr * P
@@ -593,25 +599,26 @@ __device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned c
   }
 }
 
-constexpr int kOperandBytes = 2 * kTile * kPitch;
 constexpr int kEpilogueBytes = 32 * (kTile + 1) * 4 + kEsBytes;
-constexpr int kGemmSmemBytes = kOperandBytes > kEpilogueBytes ? kOperandBytes : kEpilogueBytes;
+constexpr int gemm_smem_bytes(int elem_bytes) {
+  const int operands = elem_bytes == 4 ? 2 * 3 * kTermBytes : 2 * kTile * kPitch;
+  return operands > kEpilogueBytes ? operands : kEpilogueBytes;
+}
 
 template <class T>
 __global__ __launch_bounds__(kT) void dense_gemm_k(GemmArgs a) {
-  constexpr int WT = kTile / 2 / Acc<T>::BASE;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[kGemmSmemBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[gemm_smem_bytes(sizeof(T))];
   __shared__ int s_flag;
   // blocks b, b + 8, b + 16 ... run on one XCD: give them consecutive work items of one product
   int b = blockIdx.x;
   if (b < a.nW8) {
     const int L = (b & 7) * (a.nW8 >> 3) + (b >> 3);
-    if (L < a.nW) wgrad_block<T, WT>(a, L, smem, &s_flag);
+    if (L < a.nW) wgrad_block<T>(a, L, smem, &s_flag);
     return;
   }
   b -= a.nW8;
   const int L = (b & 7) * (a.nD8 >> 3) + (b >> 3);
-  if (L < a.nD) dgrad_block<T, WT>(a, L, smem, &s_flag);
+  if (L < a.nD) dgrad_block<T>(a, L, smem, &s_flag);
 }
 
 long round_up(long v, long m) { return (v + m - 1) / m * m; }

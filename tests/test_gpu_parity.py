@@ -1505,6 +1505,47 @@ def test_which_layers_take_the_two_launch_path(oracle, case):
     assert rel_err(g_w, ref_gw) <= TOL[dtype] and rel_err(g_x, ref_gx) <= TOL[dtype]
 
 
+def test_dense_fp32_products_are_fp32_products(oracle):
+    """The dense small-map path multiplies fp32 operands as three bf16 terms each, six term products per
+    product.  Operands on the grid (1 + a 2^-9 + b 2^-18) 2^e need all three terms, and a one-hot gy_u (one
+    patch per output channel, each on a patch of its own) makes every output a single product, so a term
+    product that is missing or misplaced shows as an error of 2^-9 ... 2^-19 of the value; what is allowed is
+    the fp32 rounding of the product plus the three dropped products: 2^-22 of the value.  Zeros stay zeros."""
+    N, Ci, Co, H = 8, 64, 64, 7
+    d = mk(N, Ci, Co, H, H, K=1, r=2, dtype="f32")
+    od = odesc(oracle, d)
+    P = 16
+    rng = np.random.default_rng(77)
+    def grid(shape):
+        a, b = rng.integers(0, 256, shape), rng.integers(0, 256, shape)
+        e = rng.integers(-6, 7, shape)
+        sign = rng.choice([-1.0, 1.0], shape)
+        return sign * (1.0 + a * 2.0 ** -9 + b * 2.0 ** -18) * 2.0 ** e
+    x_u = grid((N, Ci, 4, 4))
+    w = grid((Co, Ci, 1, 1))
+    gy_u = np.zeros((N, Co, 4, 4))
+    slots = rng.permutation(N * P)[:Co]   # (image, patch) of the only non-zero of channel c_o
+    gy_u.reshape(N, Co, P)[slots // P, np.arange(Co), slots % P] = grid((Co,))
+    for arr in (x_u, w, gy_u):
+        assert np.array_equal(arr.astype(np.float32).astype(np.float64), arr)   # exactly fp32
+    tg = lambda a: torch.from_numpy(a.astype(np.float32)).cuda()
+    seen = []
+    B.gf_set_launch_observer(lambda name, phase, stream: seen.append(name) if phase == 0 else None)
+    try:
+        g_w = T.conv_bwd_weight(d, tg(x_u), tg(gy_u))
+        g_x = T.conv_bwd_input(d, tg(gy_u), tg(w), reduced_out=True)
+    finally:
+        B.gf_set_launch_observer(None)
+    torch.cuda.synchronize()
+    assert seen == ["dense_prep_k", "dense_gemm_k"] * 2, seen
+    for got, ref in ((g_w, oracle.bwd_weight(od, x_u, gy_u)), (g_x, oracle.bwd_input(od, gy_u, w, reduced_out=True))):
+        got = to64(got)
+        assert np.array_equal(got == 0, ref == 0)
+        nz = ref != 0
+        assert nz.sum() >= Co * Ci
+        assert (np.abs(got[nz] - ref[nz]) / np.abs(ref[nz])).max() <= 2.0 ** -22
+
+
 # ---------------------------------------------------------------------------
 # activation pooling of several layers in one launch
 # ---------------------------------------------------------------------------
