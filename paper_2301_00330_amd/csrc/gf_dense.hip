@@ -43,7 +43,7 @@ namespace {
 constexpr int kT = 256;
 constexpr int kPitch = 128 + 16;       // bytes of one staged operand row
 constexpr int kTile = 64;              // block tile (rows and columns)
-constexpr int kEsBytes = 16 * 1024;    // LDS image of the planes one epilogue pass stores
+constexpr int kEsBytes = 32 * 14 * 14 * 4;   // LDS image of the planes one epilogue pass stores (32 fp32 planes of 14 x 14)
 constexpr int kPrepInBytes = 24 * 1024;
 
 template <class T> struct El;
@@ -575,8 +575,11 @@ __device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned c
       }
       continue;
     }
+    // every patch value, rounded once, to its r_x x r_x pixels of the LDS image of the runs: the nr planes of
+    // one image after the other (a run of nr planes is a multiple of 16 bytes: nr is a multiple of 8)
+    const int nel = nr * a.HW, nvec = nel / VE;
     for (int il = 0; il < nimg; ++il) {
-      // every patch value, rounded once, to its r_x x r_x pixels of the LDS image of the run
+      T* Ei = Es + il * nel;
       for (int e = tid; e < nr * a.P; e += kT) {
         const int row = (int)a.d_p.div((uint32_t)e);
         const int pp = e - row * a.P;
@@ -585,16 +588,17 @@ __device__ __forceinline__ void dgrad_block(const GemmArgs& a, int L, unsigned c
         const T val = from_f32<T>(Cs[row * SC + il * a.P + pp] * a.dscale);
         const int h1 = min(a.H, (hp + 1) * a.rx), w1 = min(a.W, (wp + 1) * a.rx);
         for (int h = hp * a.rx; h < h1; ++h)
-          for (int ww = wp * a.rx; ww < w1; ++ww) Es[row * a.HW + h * a.W + ww] = val;
+          for (int ww = wp * a.rx; ww < w1; ++ww) Ei[row * a.HW + h * a.W + ww] = val;
       }
-      __syncthreads();
+    }
+    __syncthreads();
+    for (int il = 0; il < nimg; ++il) {
       // planes (n, m0 + r0 ...) are consecutive in memory and start on a 16-byte boundary
       T* d = out + ((long)(img0 + il) * a.Ci + m0 + r0) * a.HW;
-      const int nel = nr * a.HW, nvec = nel / VE;
+      const T* Ei = Es + il * nel;
       for (int v = tid; v < nvec; v += kT)
-        store_stream16(reinterpret_cast<uint4*>(d) + v, reinterpret_cast<const uint4*>(Es)[v]);
-      for (int e = nvec * VE + tid; e < nel; e += kT) d[e] = Es[e];
-      __syncthreads();
+        store_stream16(reinterpret_cast<uint4*>(d) + v, reinterpret_cast<const uint4*>(Ei)[v]);
+      for (int e = nvec * VE + tid; e < nel; e += kT) d[e] = Ei[e];
     }
   }
 }
@@ -660,8 +664,8 @@ Plan make_plan(const Geom& g, bool want_w, bool want_d) {
   p.d_nz = slabs_for(p.d_tm * p.d_tn, p.d_chunks, want_d_blocks);
   p.d_cpz = cdiv(p.d_chunks, p.d_nz);
   p.d_nz = cdiv(p.d_chunks, p.d_cpz);
-  const int plane_bytes = g.H * g.W * g.b;
-  p.epr = 32 * plane_bytes <= kEsBytes ? 32 : 16 * plane_bytes <= kEsBytes ? 16 : 8;
+  const int tile_plane_bytes = p.ipt * g.H * g.W * g.b;   // one c_x row of a tile: its plane in every image of the tile
+  p.epr = 32 * tile_plane_bytes <= kEsBytes ? 32 : 16 * tile_plane_bytes <= kEsBytes ? 16 : 8;
   auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
   size_t o = 0;
   p.off_tick = o; o += al(((size_t)p.w_tm * p.w_tn + (size_t)p.d_tm * p.d_tn) * sizeof(int));
