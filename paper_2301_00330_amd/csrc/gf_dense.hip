@@ -760,18 +760,16 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 }  // namespace
 
 // Layers this path takes: dense, filtered, fp32, at most 64 patches per plane (a column tile of the
-// input gradient is whole images), planes of at most 256 pixels, C_x a multiple of 8 (every run of
-// planes the epilogue stores then starts on a 16-byte boundary) -- and of those the shapes on which
-// it measured faster than filter -> merged launch -> finalize (gf_mfma.hip).  Measured on MI355X,
-// whole backward of a layer, this path against the general one:
-//   one image per column tile (P > 32: 14 x 14 and 16 x 16 maps at r = 2), 1 x 1 and 3 x 3 kernels:
-//     61 / 85, 62 / 80, 46 / 54, 56 / 76, 35 / 46 us -- taken;
-//   four images per tile (P = 16), 1 x 1 kernel, r_x = 2 (7 x 7 maps at r = 2): 67 / 72, 49 / 63,
-//     44 / 47, 39 / 41, 30 / 29 us -- taken;
-//   the same with a 3 x 3 kernel (48 / 44 us) or r_x = 4 (41 / 33, 41 / 36 us): not taken -- the K^2
-//     replication of g_w and the wider pixel blocks are work of the few finishing blocks;
-//   16 or 64 images per tile (P = 4, P = 1): 44 - 54 / 26 - 41 us and 280 - 295 / 32 - 106 us: not
-//     taken -- the epilogue walks the images of a tile one after the other;
+// input gradient is whole images) and at least 16 (at most four images per tile), planes of at most 256
+// pixels, C_x a multiple of 8 (every run of planes the epilogue stores then starts on a 16-byte
+// boundary) -- the shapes on which it measured faster than filter -> merged launch -> finalize
+// (gf_mfma.hip).  Measured on MI355X, whole backward of a layer, this path against the general one:
+//   one image per column tile (P > 32: 14 x 14 and 16 x 16 maps at r = 2), 1 x 1 and 3 x 3 kernels,
+//     N = 32 ... 128: 47 / 76, 34 / 46 us (512 and 256 channels 3 x 3), 55 / 85, 46 / 80 us (96 <-> 576);
+//   four images per tile (P = 16: 7 x 7 maps at r = 2, 14 x 14 at r = 4): 1 x 1 kernels 54 / 72, 38 / 63,
+//     36 / 47, 30 / 41, 27 / 29 us; 3 x 3 kernels at r_x = 4 33 / 35, 28 / 29 us;
+//   16 or 64 images per tile (P = 4, P = 1), measured with the earlier epilogue: 44 - 54 / 26 - 41 us and
+//     280 - 295 / 32 - 106 us: not taken;
 //   with bf16 storage the contractions cost a sixteenth and every layer is a chain of fixed costs
 //     either way: 113 / 88 us per step (ResNet-18 tail), 375 / 350 us (MobileNetV2 tail): not taken.
 bool dense_ok(const Geom& g) {
@@ -779,7 +777,7 @@ bool dense_ok(const Geom& g) {
   if (g.dtype != GF_F32) return false;
   if (g.P > kTile || (long)g.H * g.W > 256 || (long)g.Hy * g.Wy > 256) return false;
   const int ipt = kTile / g.P;   // images per column tile of the input gradient
-  if (!(ipt == 1 || (ipt <= 4 && g.KK == 1 && g.rx == 2))) return false;
+  if (ipt > 4) return false;
   if (g.Ci % 8 != 0) return false;
   // 32-bit indices into the blocked matrices
   const long KB = g.b == 2 ? 64 : 32;
