@@ -47,7 +47,7 @@ constexpr int kPrepInBytes = 24 * 1024;
 
 template <class T> struct El;
 template <> struct El<float> { static constexpr int KB = 32, VE = 4; };    // elements per 128-byte chunk / 16-byte vector
-template <> struct El<bf16_t> { [[maybe_unused]] static constexpr int KB = 64, VE = 8; };   // (no bf16 instance is built)
+template <> struct El<bf16_t> { static constexpr int KB = 64, VE = 8; };
 
 // element (row, k) of a blocked matrix with `chunks` K chunks of KB elements
 template <int KB>
@@ -810,7 +810,7 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 
 }  // namespace
 
-// Layers this path takes: dense, filtered, fp32, at most 64 patches per plane (a column tile of the
+// Layers this path takes: dense, filtered, fp32 (bf16: 1 x 1 kernels only), at most 64 patches per plane (a column tile of the
 // input gradient is whole images) and at least 16 (at most four images per tile), planes of at most 256
 // pixels, C_x a multiple of 8 (every run of planes the epilogue stores then starts on a 16-byte
 // boundary) -- the shapes on which it measured faster than filter -> merged launch -> finalize
@@ -821,11 +821,12 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 //     36 / 47, 30 / 41, 27 / 29 us; 3 x 3 kernels at r_x = 4 33 / 35, 28 / 29 us;
 //   16 or 64 images per tile (P = 4, P = 1), measured with the earlier epilogue: 44 - 54 / 26 - 41 us and
 //     280 - 295 / 32 - 106 us: not taken;
-//   with bf16 storage the contractions cost a sixteenth and every layer is a chain of fixed costs
-//     either way: 113 / 88 us per step (ResNet-18 tail), 375 / 350 us (MobileNetV2 tail): not taken.
+//   with bf16 storage the contractions cost a sixteenth and a layer is a chain of fixed costs either way:
+//     1 x 1 kernels (MobileNetV2 tail, seven layers) 218 / 234 us, taken; 3 x 3 kernels (ResNet-18 tail,
+//     three layers) 91 / 73 us at r = 2, 85 / 79 us at r = 4: not taken.
 bool dense_ok(const Geom& g) {
   if (g.g != 1 || g.r == 1) return false;
-  if (g.dtype != GF_F32) return false;
+  if (g.dtype != GF_F32 && g.KK != 1) return false;
   if (g.P > kTile || (long)g.H * g.W > 256 || (long)g.Hy * g.Wy > 256) return false;
   const int ipt = kTile / g.P;   // images per column tile of the input gradient
   if (ipt > 4) return false;
@@ -844,9 +845,7 @@ size_t ws_dense(const Geom& g, bool want_w, bool want_d) { return make_plan(g, w
 hipError_t launch_dense(const Geom& g, const void* src, bool src_is_gy, const void* x_u, const void* w,
                         void* gy_u_out, float* g_w, void* g_x, bool reduced, const void* mask_u, void* ws,
                         hipStream_t st) {
-  // dense_ok() admits fp32 layers only (the kernels are written for both storage types, but with bf16
-  // the general path measured faster, so no bf16 instance is built)
-  if (g.dtype != GF_F32) return hipErrorInvalidValue;
+  if (g.dtype != GF_F32) return launch_t<bf16_t>(g, src, src_is_gy, x_u, w, gy_u_out, g_w, g_x, reduced, mask_u, ws, st);
   return launch_t<float>(g, src, src_is_gy, x_u, w, gy_u_out, g_w, g_x, reduced, mask_u, ws, st);
 }
 
