@@ -298,8 +298,7 @@ __global__ __launch_bounds__(kT) void dense_prep_k(PrepArgs a) {
     __syncthreads();
     if (a.gyn) {   // row = (n, p), consecutive lanes = consecutive channels (32 plane slots x 8 patches per pass)
       T* d = static_cast<T*>(a.gyn);
-      const int pl = tid & 31;
-      if (pl < npl) {
+      for (int pl = tid & 31; pl < npl; pl += 32) {
         int n = n0, c = c0 + pl;
         while (c >= a.C) { c -= a.C; ++n; }
         const int tn = (int)a.d_ipt.div((uint32_t)n);
@@ -728,7 +727,8 @@ Plan make_plan(const Geom& g, bool want_w, bool want_d) {
 
 int prep_planes_per_block(const Geom& g, int H, int W) {
   int R = kPrepInBytes / (H * W * g.b) / 8 * 8;
-  if (R > 32) R = 32;
+  const int most = 128 / g.b;   // runs of about 6 KB on 7 x 7 maps: 32 fp32 planes, 64 bf16 planes
+  if (R > most) R = most;
   if (R < 8) R = 8;
   return R;
 }
