@@ -423,7 +423,7 @@ int lds_planes_per_block(const Geom& g) {
   const long per_plane = (long)g.H * g.W * sizeof(T) + (long)g.P * 4 + 4;
   long ppb = (kLdsBudget - 64) / per_plane;
   const long planes = (long)g.N * g.Ci;
-  if (ppb > planes / 1024) ppb = planes / 1024;  // keep ~4 blocks per CU when the tensor allows
+  if (ppb > planes / 3072) ppb = planes / 3072;  // ~12 blocks per CU when the tensor allows: rounds of blocks overlap loads and stores
   if (ppb > kThreads) ppb = kThreads;
   const long fit = (64 * 1024 - 64) / per_plane;
   if (ppb < 1) ppb = fit >= 1 ? 1 : 0;
@@ -435,7 +435,7 @@ int strided_planes_per_block(const Geom& g) {
   const long per_plane = ((long)g.H * g.W + (long)g.Hy * g.Wy) * sizeof(T) + (long)g.P * 4 + 4;
   long ppb = (kLdsBudget - 128) / per_plane;
   const long planes = (long)g.N * g.Ci;
-  if (ppb > planes / 1024) ppb = planes / 1024;  // keep ~4 blocks per CU when the tensor allows
+  if (ppb > planes / 3072) ppb = planes / 3072;  // ~12 blocks per CU when the tensor allows: rounds of blocks overlap loads and stores
   if (ppb > kThreads) ppb = kThreads;
   const long fit = (64 * 1024 - 128) / per_plane;
   if (ppb < 1) ppb = fit >= 1 ? 1 : 0;
