@@ -33,6 +33,7 @@
 // a K slab of the weight gradient, a group of images of the input gradient.
 #include "gf_internal.h"
 #include "gf_mma.h"
+#include <algorithm>
 
 namespace gf {
 
@@ -77,6 +78,8 @@ struct PrepArgs {
   void* xut;
   int Ci, nxu;         // nxu = N * Ci * P
   FastDiv d_cip;       // / (Ci * P)
+  int relay_t, N;      // relay_t: x_u goes through LDS in pieces of 8 images x 8 channels (16-byte loads and stores)
+  FastDiv d_nvi;       // / (8 * P / VE), the vectors of one image's piece
   const void* w;       // nullable [Co][Ci][KK] -> wt, blocked [Ci][kpc], kernel sums rounded to the storage type
   void* wt;
   int Co, KK;
@@ -86,7 +89,7 @@ struct PrepArgs {
 };
 
 template <class T>
-__device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
+__device__ __forceinline__ void prep_side_jobs(const PrepArgs& a, unsigned char* smem) {
   constexpr int KB = El<T>::KB;
   const int b = blockIdx.x, tid = threadIdx.x;
   T* xut = static_cast<T*>(a.xut);
@@ -96,6 +99,49 @@ __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
     // 16-byte pieces where the patches of a plane are a whole number of vectors
     constexpr int VE = El<T>::VE;
     const T* xu = static_cast<const T*>(a.xu);
+    if (a.relay_t) {
+      // The patches of a plane are no whole number of vectors (7 x 7 patches): a piece of 8 images x 8 channels
+      // is read with 16-byte loads (the 8 planes of an image are one aligned run), laid out in LDS as 8 rows
+      // [c][n * P + p], and every row leaves as 16-byte stores -- it is a run of 8 P columns of XUT that starts
+      // on a vector boundary.  (Element by element this relay took 18 us for 14.5 MB.)
+      T* rows = reinterpret_cast<T*>(smem);
+      const int pitch = 8 * a.P + VE;
+      const int nvi = 8 * a.P / VE, nv = 8 * nvi;
+      const int cgroups = a.Ci >> 3, items = (a.N >> 3) * cgroups;
+      for (int item = b; item < items; item += a.blk_w0) {
+        const int ng = item / cgroups, n0 = ng * 8, ci0 = (item - ng * cgroups) * 8;
+        __syncthreads();   // the rows of the previous piece have been stored
+        for (int v0 = tid; v0 < nv; v0 += 4 * kT) {
+          u32x4_t r[4];
+          int n[4], kk[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int idx = min(v0 + k * kT, nv - 1);
+            n[k] = (int)a.d_nvi.div((uint32_t)idx);
+            kk[k] = idx - n[k] * nvi;
+            r[k] = *reinterpret_cast<const u32x4_t*>(xu + ((long)(n0 + n[k]) * a.Ci + ci0) * a.P + kk[k] * VE);
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (v0 + k * kT >= nv) continue;
+            const T* el = reinterpret_cast<const T*>(&r[k]);
+#pragma unroll
+            for (int j = 0; j < VE; ++j) {
+              const int e = kk[k] * VE + j;
+              const int cl = (int)a.d_p.div((uint32_t)e);
+              rows[cl * pitch + n[k] * a.P + e - cl * a.P] = el[j];
+            }
+          }
+        }
+        __syncthreads();
+        for (int v = tid; v < nv; v += kT) {
+          const int cl = (int)a.d_nvi.div((uint32_t)v), kk = v - cl * nvi;
+          *reinterpret_cast<u32x4_t*>(xut + blk<KB>(ci0 + cl, n0 * a.P + kk * VE, a.chj)) =
+              *reinterpret_cast<const u32x4_t*>(rows + cl * pitch + kk * VE);
+        }
+      }
+      return;
+    }
     const int step = a.blk_w0 * kT;
     // eight loads of a lane are in flight together (one at a time, the walk paid a memory latency per step:
     // 18 us for the 14.5 MB of the 576-channel 14 x 14 layer)
@@ -176,10 +222,10 @@ __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
 template <class T>
 __global__ __launch_bounds__(kT) void dense_prep_k(PrepArgs a) {
   // side jobs first: their blocks start first and overlap with the filter blocks
-  if ((int)blockIdx.x < a.blk_red0) { prep_side_jobs<T>(a); return; }
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  if ((int)blockIdx.x < a.blk_red0) { prep_side_jobs<T>(a, smem); return; }
   constexpr int VE = El<T>::VE;
   constexpr int MAXV = kPrepInBytes / 16 / kT;   // 16-byte vectors of a run per lane
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int HW = a.H * a.W;
   T* lin = reinterpret_cast<T*>(smem);
@@ -771,14 +817,19 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
   a.Co = g.Co; a.KK = g.KK;
   a.tickets = reinterpret_cast<int*>(wsb + p.off_tick);
   a.ntickets = p.w_tm * p.w_tn + p.d_tm * p.d_tn;
-  a.blk_w0 = want_w ? imin_host(cdiv(g.P % El<T>::VE == 0 ? a.nxu / El<T>::VE : a.nxu, kT), 512) : 0;
+  a.N = g.N;
+  a.relay_t = (g.P % El<T>::VE != 0 && g.N % 8 == 0) ? 1 : 0;
+  a.d_nvi = FastDiv((uint32_t)(8 * g.P / El<T>::VE));
+  a.blk_w0 = !want_w ? 0 : a.relay_t ? imin_host((g.N / 8) * (g.Ci / 8), 512)
+                                     : imin_host(cdiv(g.P % El<T>::VE == 0 ? a.nxu / El<T>::VE : a.nxu, kT), 512);
   a.blk_pad0 = a.blk_w0 + (want_d ? cdiv(g.Ci, 32) * cdiv(g.Co, 32) : 0);
   a.blk_red0 = a.blk_pad0 + 8;
   // filter blocks: at most eight per CU, each walks its share of the runs
   const int nruns = cdiv(a.planes, a.R);
   const int nred = nruns < 2048 ? nruns : 2048;
   const int VE = El<T>::VE;
-  const size_t lds = (size_t)((a.R * a.H * a.W + VE - 1) / VE * VE + a.R * (g.P + 1)) * sizeof(T) + 16;
+  size_t lds = (size_t)((a.R * a.H * a.W + VE - 1) / VE * VE + a.R * (g.P + 1)) * sizeof(T) + 16;
+  if (a.relay_t && want_w) lds = std::max(lds, (size_t)8 * (8 * g.P + VE) * sizeof(T));
   GF_LAUNCH(dense_prep_k<T>, dim3(a.blk_red0 + nred), dim3(kT), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
