@@ -26,7 +26,7 @@
 //      to the workspace; the block that takes the last ticket of a tile adds the slabs in slab
 //      order (so the result does not depend on which block that is) and runs the epilogue:
 //      scale and replicate to the K_h x K_w taps, or round once and write whole planes of g_x
-//      (every patch value to its r_x x r_x pixels, built in LDS, stored as one contiguous run).
+//      (a lane forms 16 bytes of the run at a time, every pixel taking its patch's value).
 //      No separate slab-sum launch, no float atomics.
 //
 // Blocks are numbered so that the blocks one XCD receives (block index mod 8) share operands:
