@@ -616,9 +616,11 @@ __device__ __forceinline__ void wgrad_block(const GemmArgs& a, int L, unsigned c
   gather_tile(acc, Cs);
   __syncthreads();
   const int nr = min(kTile, a.Co - m0);
-  for (int row = 0; row < nr; ++row) {
-    float* d = a.g_w + ((long)(m0 + row) * a.Ci + n0) * a.KK;
-    for (int rem = tid; rem < run; rem += kT) d[rem] = Cs[row * SC + (int)a.d_kk.div((uint32_t)rem)] * a.wscale;
+  // all rows in one flat loop (row by row, a 1 x 1 layer kept 64 of 256 lanes busy for 64 passes: 6 - 7 us per tile,
+  // 12.6 us with 3 x 3 taps, on the critical path of the launch)
+  for (int e = tid; e < nr * run; e += kT) {
+    const int row = e / run, rem = e - row * run;
+    a.g_w[((long)(m0 + row) * a.Ci + n0) * a.KK + rem] = Cs[row * SC + (int)a.d_kk.div((uint32_t)rem)] * a.wscale;
   }
 }
 
