@@ -882,7 +882,7 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 
 }  // namespace
 
-// Layers this path takes: dense, filtered, fp32 (bf16: 1 x 1 kernels only), at most 64 patches per plane (a column tile of the
+// Layers this path takes: dense, filtered, at most 64 patches per plane (a column tile of the
 // input gradient is whole images) and at least 16 (at most four images per tile), planes of at most 256
 // pixels, C_x a multiple of 8 (every run of planes the epilogue stores then starts on a 16-byte
 // boundary) -- the shapes on which it measured faster than filter -> merged launch -> finalize
@@ -894,11 +894,10 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 //   16 or 64 images per tile (P = 4, P = 1), measured with the earlier epilogue: 44 - 54 / 26 - 41 us and
 //     280 - 295 / 32 - 106 us: not taken;
 //   with bf16 storage the contractions cost a sixteenth and a layer is a chain of fixed costs either way:
-//     1 x 1 kernels (MobileNetV2 tail, seven layers) 218 / 234 us, taken; 3 x 3 kernels (ResNet-18 tail,
-//     three layers) 91 / 73 us at r = 2, 85 / 79 us at r = 4: not taken.
+//     1 x 1 kernels (MobileNetV2 tail, seven layers) 218 / 234 us; 3 x 3 kernels (ResNet-18 tail) 24 / 25,
+//     23 / 21 (stride 2), 23 / 27 us at r = 2 and 22 / 21 us at r = 4: taken as well.
 bool dense_ok(const Geom& g) {
   if (g.g != 1 || g.r == 1) return false;
-  if (g.dtype != GF_F32 && g.KK != 1) return false;
   if (g.P > kTile || (long)g.H * g.W > 256 || (long)g.Hy * g.Wy > 256) return false;
   const int ipt = kTile / g.P;   // images per column tile of the input gradient
   if (ipt > 4) return false;

@@ -1480,9 +1480,9 @@ def test_launch_observer_lists_the_kernels_of_a_call():
     (4, 32, 48, 14, 14, 3, 2, 2, "f32", True),     # 16 patches, r_x = 4 (stride 2)
     (4, 32, 48, 14, 14, 3, 1, 4, "f32", True),     # 16 patches, r_x = 4 (r = 4)
     (4, 32, 48, 7, 7, 1, 1, 4, "f32", False),      # 4 patches: 16 images per column tile
-    (4, 32, 48, 14, 14, 1, 1, 2, "bf16", True),    # bf16 storage: 1 x 1 kernels
+    (4, 32, 48, 14, 14, 1, 1, 2, "bf16", True),    # bf16 storage
     (4, 32, 48, 7, 7, 1, 1, 2, "bf16", True),
-    (4, 32, 48, 14, 14, 3, 1, 2, "bf16", False),   # ... but not 3 x 3
+    (4, 32, 48, 14, 14, 3, 1, 2, "bf16", True),
     (4, 32, 48, 28, 28, 1, 1, 2, "f32", False),    # planes of more than 256 pixels
 ])
 def test_which_layers_take_the_two_launch_path(oracle, case):
