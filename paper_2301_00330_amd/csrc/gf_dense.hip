@@ -883,7 +883,7 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 }  // namespace
 
 // Layers this path takes: dense, filtered, at most 64 patches per plane (a column tile of the
-// input gradient is whole images) and at least 16 (at most four images per tile), planes of at most 256
+// input gradient is whole images) and at least 4 (at most sixteen images per tile), planes of at most 256
 // pixels, C_x a multiple of 8 (every run of planes the epilogue stores then starts on a 16-byte
 // boundary) -- the shapes on which it measured faster than filter -> merged launch -> finalize
 // (gf_mfma.hip).  Measured on MI355X, whole backward of a layer, this path against the general one:
@@ -891,8 +891,9 @@ hipError_t launch_t(const Geom& g, const void* src, bool src_is_gy, const void* 
 //     N = 32 ... 128: 47 / 76, 34 / 46 us (512 and 256 channels 3 x 3), 55 / 85, 46 / 80 us (96 <-> 576);
 //   four images per tile (P = 16: 7 x 7 maps at r = 2, 14 x 14 at r = 4): 1 x 1 kernels 54 / 72, 38 / 63,
 //     36 / 47, 30 / 41, 27 / 29 us; 3 x 3 kernels at r_x = 4 33 / 35, 28 / 29 us;
-//   16 or 64 images per tile (P = 4, P = 1), measured with the earlier epilogue: 44 - 54 / 26 - 41 us and
-//     280 - 295 / 32 - 106 us: not taken;
+//   16 images per tile (P = 4: 7 x 7 maps at r = 4): 512 channels 3 x 3, bf16, 23 / 31 us -- taken while a
+//     tile's share of g_x stays below 256 KB (256 -> 512 channels, stride 2, 14 x 14 planes: 16 tiles of 401 KB,
+//     44 / 27 us); 64 images per tile (P = 1), measured with an earlier epilogue: 280 - 295 / 32 - 106 us: not taken;
 //   with bf16 storage the contractions cost a sixteenth and a layer is a chain of fixed costs either way:
 //     1 x 1 kernels (MobileNetV2 tail, seven layers) 218 / 234 us; 3 x 3 kernels (ResNet-18 tail) 24 / 25,
 //     23 / 21 (stride 2), 23 / 27 us at r = 2 and 22 / 21 us at r = 4: taken as well.
@@ -900,7 +901,8 @@ bool dense_ok(const Geom& g) {
   if (g.g != 1 || g.r == 1) return false;
   if (g.P > kTile || (long)g.H * g.W > 256 || (long)g.Hy * g.Wy > 256) return false;
   const int ipt = kTile / g.P;   // images per column tile of the input gradient
-  if (ipt > 4) return false;
+  // a finishing block of the input gradient stores the planes of all images of its tile: 64 rows x ipt planes
+  if (ipt > 16 || (long)kTile * ipt * g.H * g.W * g.b > 256 * 1024) return false;
   if (g.Ci % 8 != 0) return false;
   // 32-bit indices into the blocked matrices
   const long KB = g.b == 2 ? 64 : 32;

@@ -1479,7 +1479,9 @@ def test_launch_observer_lists_the_kernels_of_a_call():
     (4, 32, 48, 7, 7, 3, 1, 2, "f32", True),       # ... with a 3 x 3 kernel
     (4, 32, 48, 14, 14, 3, 2, 2, "f32", True),     # 16 patches, r_x = 4 (stride 2)
     (4, 32, 48, 14, 14, 3, 1, 4, "f32", True),     # 16 patches, r_x = 4 (r = 4)
-    (4, 32, 48, 7, 7, 1, 1, 4, "f32", False),      # 4 patches: 16 images per column tile
+    (4, 32, 48, 7, 7, 1, 1, 4, "f32", True),       # 4 patches: 16 images per column tile
+    (4, 32, 48, 7, 7, 1, 1, 7, "f32", False),      # 1 patch: 64 images per column tile
+    (40, 256, 64, 14, 14, 3, 2, 4, "bf16", False), # 16 images per tile whose planes come to more than 256 KB
     (4, 32, 48, 14, 14, 1, 1, 2, "bf16", True),    # bf16 storage
     (4, 32, 48, 7, 7, 1, 1, 2, "bf16", True),
     (4, 32, 48, 14, 14, 3, 1, 2, "bf16", True),
