@@ -397,9 +397,10 @@ constexpr int kBase = 32, kNV = 16;
 __device__ __forceinline__ int acc_row(int lane, int v) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
 // Four fp32 values as three bf16 terms, x = t0 + t1 + t2 exactly: every term is the nearest bf16 of what the
-// earlier ones leave (|t1| <= 2^-9 |x|, |t2| <= 2^-18 |x|), both remainders are exact in fp32, and the second
+// earlier ones leave (|t1| <= 2^-8 |x|, |t2| <= 2^-16 |x|), both remainders are exact in fp32, and the second
 // has at most 8 significant bits.  A product x y is taken as the six term products of order <= 2; the three
-// that are dropped are below 2^-26 |x y|, less than one rounding of the fp32 accumulation.  One packed
+// that are dropped stay below 2^-23 |x y| (2^-24 at most and 2^-27 rms over random operands): the size of one
+// rounding of the fp32 accumulation.  One packed
 // conversion per pair of values and term, two shifts / masks and two subtractions per pair and remainder.
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));

@@ -1,5 +1,6 @@
 """Host-side checks of the C ABI that need no GPU: the library loads, exports
 every symbol include/gf.h declares, and rejects bad calls before any launch."""
+import numpy as np
 import ctypes as C
 import os
 import re
@@ -358,3 +359,39 @@ def test_unique_elements_entry_host_checks(lib):
     with pytest.raises(B.GfError) as ei:
         B.gf_conv_bwd_unique(d, FAKE, FAKE, FAKE, FAKE, FAKE, False, FAKE, need - 1)
     assert ei.value.status == B.GF_ERR_WORKSPACE
+
+
+# ---------------------------------------------------------------------------
+# arithmetic of the fp32 contraction on the bf16 matrix pipe (dense small-map path), checked on the host
+# ---------------------------------------------------------------------------
+def _bf16_rne(x):
+    """float32 array -> nearest bfloat16 (ties to even), returned as float32."""
+    u = np.asarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+def test_three_term_bf16_split_is_exact_and_six_products_suffice():
+    """The dense small-map kernels split every fp32 operand as t0 = bf16(x), t1 = bf16(x - t0), t2 = x - t0 - t1 and
+    form x*y from the six term products of order <= 2.  Emulated here with numpy: both remainders are exact fp32
+    values, t2 is a bf16 value, the three terms add up to x exactly, and the three dropped products (at most
+    2^-23 |x y| in theory: |t1| <= 2^-8 |x|, |t2| <= 2^-16 |x|) stay below 2^-24 |x y| on these operands."""
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(200000).astype(np.float32) * np.float32(10.0) ** rng.integers(-6, 7, 200000).astype(np.float32),
+                        np.float32([1.0, -1.0, 1.0 + 2.0 ** -23, 1.0 - 2.0 ** -24, 255.0 / 256.0, 3.0e38, 1.2e-30, 0.0])])
+    y = np.roll(x, 7)
+    def split(v):
+        t0 = _bf16_rne(v)
+        r1 = v - t0                                   # float32 arithmetic
+        assert np.array_equal(r1.astype(np.float64), v.astype(np.float64) - t0.astype(np.float64))
+        t1 = _bf16_rne(r1)
+        r2 = r1 - t1
+        assert np.array_equal(r2.astype(np.float64), r1.astype(np.float64) - t1.astype(np.float64))
+        assert np.array_equal(_bf16_rne(r2), r2)      # the second remainder is a bf16 value
+        return t0.astype(np.float64), t1.astype(np.float64), r2.astype(np.float64)
+    a, b = split(x), split(y)
+    assert np.array_equal(a[0] + a[1] + a[2], x.astype(np.float64))
+    kept = a[0] * b[0] + a[0] * b[1] + a[1] * b[0] + a[1] * b[1] + a[0] * b[2] + a[2] * b[0]
+    exact = x.astype(np.float64) * y.astype(np.float64)
+    nz = exact != 0
+    assert (np.abs(kept - exact)[nz] / np.abs(exact)[nz]).max() <= 2.0 ** -24
